@@ -1,0 +1,133 @@
+/*
+ * libmuse — Multipole Semantic Attention (MuSe), causal, training-time, on one
+ * AMD MI355X (gfx950).  C ABI; no C++ or framework types cross this boundary.
+ *
+ * Problem statement (Alg. 1 header): queries Q, keys K, values V of length N per
+ * head, a spatial block size, cluster counts, retrieval counts k1 (= r) and k2;
+ * output O of length N.  The method is Sec. 3 (Eq. 1-7) with the clustering of
+ * App. C; the backward pass freezes the discrete choices and treats the query
+ * centroids as constants (App. C "Centroid Gradient Flow").
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers on the current HIP device, owned by
+ *     the caller; the library never allocates, frees or keeps them.  `ws` is a
+ *     caller-owned device scratch buffer of `ws_bytes` bytes, 256-byte aligned;
+ *     its required size comes from muse_workspace_bytes().  Its contents are
+ *     undefined before and after a call.
+ *   - `p` is a HOST pointer.  `stream` is a hipStream_t passed as void* (NULL =
+ *     default stream).  Work is enqueued on that stream; calls return without
+ *     synchronising.  No global state; calls on different streams with different
+ *     workspaces do not interfere.
+ *   - Layout: Q, O, dO, dQ are [B, Hq, N, D]; K, V, dK, dV are [B, Hkv, N, D];
+ *     row-major, contiguous, element type given by p->dtype (fp32 or bf16).
+ *     Hq % Hkv == 0; query head h uses kv head h / (Hq / Hkv) (GQA, Sec. 6).
+ *   - Return value: MUSE_OK (0) or a negative MUSE_ERR_* code.  Arguments are
+ *     validated on the host before anything is launched; a failed call has
+ *     launched nothing.
+ */
+#ifndef MUSE_H_
+#define MUSE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  MUSE_OK = 0,
+  MUSE_ERR_INVALID_ARG = -1,        /* NULL pointer, non-positive size, N % block != 0, ... */
+  MUSE_ERR_UNSUPPORTED = -2,        /* non-causal, D not in {64,128}, sizes beyond the kernels' limits */
+  MUSE_ERR_WORKSPACE_TOO_SMALL = -3,
+  MUSE_ERR_HIP = -4                 /* a HIP call or launch failed */
+};
+
+enum { MUSE_DTYPE_FP32 = 0, MUSE_DTYPE_BF16 = 1 };
+enum { MUSE_WS_CLUSTER = 0, MUSE_WS_FWD = 1, MUSE_WS_BWD = 2, MUSE_WS_EXACT_FWD = 3, MUSE_WS_EXACT_BWD = 4 };
+
+typedef struct {
+  int32_t B, Hq, Hkv;   /* batch, query heads, key/value heads */
+  int32_t N, D;         /* sequence length, head dimension (64 or 128) */
+  int32_t Cq, Ck;       /* number of query / key clusters (Sec. 3 "Clustering"), 1 <= C <= 2048 */
+  int32_t r;            /* k1: key clusters retrieved per query (Sec. 3.2), 0 <= r <= min(Ck, 32) */
+  int32_t k2;           /* spatial blocks retrieved per retrieved cluster (Sec. 3.2);
+                           0 = every preceding block of a retrieved cluster */
+  int32_t block;        /* spatial block size (Sec. 3 "Spatial blocks"); 0 -> N/8.  N % block == 0,
+                           N/block <= 16 */
+  int32_t kmeans_iters; /* T: Lloyd iterations (assign + mean update) before the final assignment */
+  int32_t dtype;        /* MUSE_DTYPE_*: element type of Q,K,V,O,dO */
+  int32_t grad_dtype;   /* element type of dQ,dK,dV: MUSE_DTYPE_FP32 or the same as dtype */
+  int32_t causal;       /* must be 1 (the paper defines the causal form only) */
+  uint32_t flags;       /* reserved, must be 0 */
+  float scale;          /* logit scale applied to q (Eq. 1 has none written); 0 -> 1/sqrt(D) */
+} muse_params;
+
+/* Bytes of device scratch that entry point `which` (MUSE_WS_*) needs for `p`.  The far-field
+ * stages keep the summaries tensor of Sec. 3 ([Cq, Ck, N/block] cells of 2D+1 floats) in the
+ * workspace for as many heads at a time as fit: any size >= the returned minimum works, and
+ * *preferred (may be NULL) is the size at which all heads are processed in one pass. */
+int muse_workspace_bytes(const muse_params* p, int which, size_t* min_bytes, size_t* preferred);
+
+/* Clustering (Sec. 3 "Clustering", App. C): per head, K-means of the query rows into Cq clusters and
+ * of the key rows into Ck clusters (keys once per kv head).  Initial centroid j = row init_idx[j]
+ * (App. C initialisation: the caller draws a seeded shuffle and takes every floor(N/C)-th index);
+ * if an init_idx pointer is NULL the initial centroids are read from the centroid buffer instead.
+ * Then T = kmeans_iters times { nearest-centroid assignment; centroid <- mean of its points (an empty
+ * cluster keeps its centroid) } and one final assignment.  Nearest means smallest
+ * ||c||^2 - 2<x,c> (App. C, the ||x||^2 term dropped), lowest index on ties; for bf16 inputs the
+ * centroids are rounded to bf16 for this score, products are exact and sums are fp32.
+ *   q_init_idx [B,Hq,Cq] / k_init_idx [B,Hkv,Ck]  int32 row indices in [0,N)       (in, may be NULL)
+ *   q_centroids [B,Hq,Cq,D] / k_centroids [B,Hkv,Ck,D]  fp32, centroids of the raw rows   (in/out)
+ *   q_assign [B,Hq,N] / k_assign [B,Hkv,N]  int32 cluster of every row                       (out)
+ * Q or K may be NULL to skip that side (its other pointers are then ignored). */
+int muse_cluster(const muse_params* p, const void* Q, const void* K,
+                 const int32_t* q_init_idx, const int32_t* k_init_idx,
+                 float* q_centroids, int32_t* q_assign,
+                 float* k_centroids, int32_t* k_assign,
+                 void* ws, size_t ws_bytes, void* stream);
+
+/* Forward (Sec. 3.1-3.3, Alg. 1): per-block tilted summaries (Eq. 4-6), exclusive causal
+ * accumulation, cluster selection by Eq. 7, spatial block selection, exact attention on the
+ * retrieved (cluster, block) pairs with the full query, exact causal attention inside the
+ * query's own block, all merged in one softmax.
+ *   q_centroids, q_assign, k_assign: as produced by muse_cluster (any partition is valid)   (in)
+ *   O [B,Hq,N,D] dtype; LSE [B,Hq,N] fp32 log of the merged softmax normaliser             (out)
+ *   sel_clusters [B,Hq,N,r] int32: retrieved key clusters in descending score order, -1 padded;
+ *   sel_blocks [B,Hq,N,r,k2e] int32, k2e = k2 or N/block-1 when k2 == 0: retrieved blocks of each,
+ *   descending score, -1 padded.  Required when r > 0 (muse_bwd reads them)                 (out) */
+int muse_fwd(const muse_params* p, const void* Q, const void* K, const void* V,
+             const float* q_centroids, const int32_t* q_assign, const int32_t* k_assign,
+             void* O, float* LSE, int32_t* sel_clusters, int32_t* sel_blocks,
+             void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of muse_fwd: gradient of (Q,K,V) -> O contracted with dO, with the assignments, the
+ * selections and the query centroids held fixed (App. C "Centroid Gradient Flow"); gradient does flow
+ * into K and V through the tilted aggregation weights (the default of App. C "Aggregation Weight
+ * Gradient Flow").  O, LSE, sel_* are the outputs of muse_fwd for the same inputs.
+ *   dQ [B,Hq,N,D], dK, dV [B,Hkv,N,D] of grad_dtype (summed over the query heads of a group)   (out)
+ * Sums over many queries into one key use fp32 atomics in the retrieval stage, so the last bits of
+ * dK, dV may differ between runs. */
+int muse_bwd(const muse_params* p, const void* Q, const void* K, const void* V,
+             const void* O, const float* LSE, const void* dO,
+             const float* q_centroids, const int32_t* q_assign, const int32_t* k_assign,
+             const int32_t* sel_clusters, const int32_t* sel_blocks,
+             void* dQ, void* dK, void* dV,
+             void* ws, size_t ws_bytes, void* stream);
+
+/* Exact causal softmax attention (Sec. 3, Eq. 1-2) with the same scale, and its gradient: the
+ * in-house baseline the MuSe timings are compared with.  Uses N, D, B, Hq, Hkv, dtype, grad_dtype,
+ * scale of p; the other fields are ignored. */
+int exact_attn_fwd(const muse_params* p, const void* Q, const void* K, const void* V,
+                   void* O, float* LSE, void* ws, size_t ws_bytes, void* stream);
+int exact_attn_bwd(const muse_params* p, const void* Q, const void* K, const void* V,
+                   const void* O, const float* LSE, const void* dO,
+                   void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
+
+/* Static, NUL-terminated description of a return code. */
+const char* muse_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MUSE_H_ */

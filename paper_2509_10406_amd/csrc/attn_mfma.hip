@@ -1,0 +1,410 @@
+// bf16 causal attention on MFMA (Sec. 3, Eq. 1-2; Sec. 3.3 "Local attention"): keys restricted to
+// the query's own spatial block of size Bs (Bs = N gives exact attention).  Forward plus the two
+// backward kernels (dQ per query tile, dK/dV per key tile; no atomics).
+//
+// Tiling for 64-wide waves and v_mfma_f32_32x32x16_bf16:
+//   - a wave owns 32 queries (fwd, dQ) or 32 keys (dK/dV) as the N-columns of the MFMA, so every
+//     per-row softmax quantity lives in one lane (two lanes: the two halves hold different K-rows);
+//   - scores are produced transposed (S^T = K Q^T in fwd/dQ, S = Q K^T in dK/dV) so that their
+//     accumulator layout IS the B-operand layout of the following contraction: probabilities go
+//     from registers straight back into the matrix cores, never through LDS;
+//   - accumulator element e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32; an operand
+//     lane holds 8 consecutive k for k-slot-half l/32.  For the second contraction the 8 k-slots of
+//     half h over 16 keys are keys {4h..4h+3} and {8+4h..8+4h+3}: a permutation applied to both
+//     operands, which a contraction does not see.
+#include "common.h"
+
+namespace {
+
+constexpr int BN = 64;  // rows staged in LDS per step
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ bf16x8_t pack8(const f32x16_t& s, int g0, int g1) {
+  bf16x8_t r;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    r[t] = (__bf16)s[4 * g0 + t];
+    r[4 + t] = (__bf16)s[4 * g1 + t];
+  }
+  return r;
+}
+
+// A operand for the second contraction from a transposed LDS tile `row` ([..][BN+8]): the 8 k-slots
+// of lane half `half` over the 16 rows starting at r0
+__device__ __forceinline__ bf16x8_t ld_tr8(const bf16_t* row, int r0, int half) {
+  uint2 a = *reinterpret_cast<const uint2*>(row + r0 + 4 * half);
+  uint2 b = *reinterpret_cast<const uint2*>(row + r0 + 8 + 4 * half);
+  uint4 v = make_uint4(a.x, a.y, b.x, b.y);
+  return *reinterpret_cast<bf16x8_t*>(&v);
+}
+
+// cooperative load of `rows` x D bf16 into a row-major tile (pad 8) and optionally a transposed one
+template <int D, int ROWS, bool ROWM, bool TRANS>
+__device__ __forceinline__ void load_tile(const bf16_t* __restrict__ src, int r0, int N,
+                                          bf16_t (*rm)[D + 8], bf16_t (*tr)[ROWS + 8]) {
+  constexpr int CPR = D / 8;
+  for (int c = threadIdx.x; c < ROWS * CPR; c += 256) {
+    int row = c / CPR, cc = c % CPR;
+    int gr = r0 + row;
+    gr = gr < N ? gr : N - 1;
+    uint4 v = *reinterpret_cast<const uint4*>(src + (size_t)gr * D + cc * 8);
+    if (ROWM) *reinterpret_cast<uint4*>(&rm[row][cc * 8]) = v;
+    if (TRANS) {
+      const bf16_t* pv = reinterpret_cast<const bf16_t*>(&v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) tr[cc * 8 + e][row] = pv[e];
+    }
+  }
+}
+
+template <int D>
+__global__ void __launch_bounds__(256) k_flash_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                    const bf16_t* __restrict__ V, const float* __restrict__ ff,
+                                                    bf16_t* __restrict__ O, float* __restrict__ LSE, int N, int Bs,
+                                                    int Hq, int Hkv, float scale_log2e) {
+  constexpr int KS = D / 16, DT = D / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t ks[BN][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t vt[D][BN + 8];
+  const int hq = blockIdx.y, b = blockIdx.z, hk = hq / (Hq / Hkv);
+  const size_t qh = ((size_t)b * Hq + hq) * N, kh = ((size_t)b * Hkv + hk) * N;
+  const int q0 = (gridDim.x - 1 - blockIdx.x) * 128;  // long rows first
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  const int nq = q0 + 32 * wave + col;
+  const int nqc = nq < N ? nq : N - 1;
+  const int myb = (nqc / Bs) * Bs;
+  const bool unaligned = (Bs % 128) != 0;
+
+  bf16x8_t qf[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s)
+    qf[s] = *reinterpret_cast<const bf16x8_t*>(Q + (qh + nqc) * D + 16 * s + 8 * half);
+  f32x16_t o[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
+  float m = MUSE_NEG_INF, l = 0.f;
+
+  const int kbeg = (q0 / Bs) * Bs, kend = min(q0 + 128, N);
+  for (int k0 = kbeg; k0 < kend; k0 += BN) {
+    __syncthreads();
+    load_tile<D, BN, true, false>(K + kh * D, k0, N, ks, nullptr);
+    load_tile<D, BN, false, true>(V + kh * D, k0, N, nullptr, vt);
+    __syncthreads();
+    if (k0 > q0 + 32 * wave + 31) continue;  // every key of the tile is in this wave's future
+    f32x16_t s[2];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[kt][e] = 0.f;
+#pragma unroll
+      for (int x = 0; x < KS; ++x) {
+        bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&ks[32 * kt + col][16 * x + 8 * half]);
+        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[x], s[kt], 0, 0, 0);
+      }
+    }
+    if (unaligned || k0 + BN - 1 > q0 + 32 * wave || k0 + BN > N) {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          int kg = k0 + 32 * kt + 8 * (e / 4) + 4 * half + (e % 4);
+          if (kg > nq || kg < myb) s[kt][e] = MUSE_NEG_INF;
+        }
+    }
+    float tmax = MUSE_NEG_INF;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[kt][e]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    float mn = fmaxf(m, tmax * scale_log2e);
+    float mref = mn == MUSE_NEG_INF ? 0.f : mn;
+    float alpha = fast_exp2(m - mref);
+    float psum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        float p = fast_exp2(fmaf(s[kt][e], scale_log2e, -mref));
+        s[kt][e] = p;
+        psum += p;
+      }
+    l = l * alpha + psum;
+    m = mn;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int G = 0; G < 2; ++G) {
+        bf16x8_t pf = pack8(s[kt], 2 * G, 2 * G + 1);
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+          bf16x8_t a = ld_tr8(&vt[32 * t + col][0], 32 * kt + 16 * G, half);
+          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, o[t], 0, 0, 0);
+        }
+      }
+  }
+  l += __shfl_xor(l, 32, 64);
+  if (nq >= N) return;
+  float mnat = m * 0.6931471805599453f;  // natural-log units
+  float cl = 1.f;                        // weight of the local part after the merge
+  float cf = 0.f, lf = 0.f;
+  const float* fa = nullptr;
+  if (ff) {
+    const float* fm = ff + (size_t)gridDim.z * Hq * N * D + (qh + nq) * 2;  // [acc | (max,sum)] planes
+    float mf = fm[0];
+    lf = fm[1];
+    if (lf > 0.f) {
+      float mx = fmaxf(mnat, mf);
+      cl = __expf(mnat - mx);
+      cf = __expf(mf - mx);
+      mnat = mx;
+      fa = ff + (qh + nq) * D;
+    }
+  }
+  float lt = l * cl + lf * cf;
+  float inv = 1.f / lt;
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      int d = 32 * t + 8 * g + 4 * half;
+      float v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = o[t][4 * g + u] * cl;
+      if (fa) {
+        float4 f = *reinterpret_cast<const float4*>(fa + d);
+        v[0] += cf * f.x; v[1] += cf * f.y; v[2] += cf * f.z; v[3] += cf * f.w;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] *= inv;
+      st4(O, (qh + nq) * D + d, v);
+    }
+  if (half == 0) LSE[qh + nq] = mnat + __logf(lt);
+}
+
+template <int D>
+__global__ void __launch_bounds__(256) k_flash_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                       const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO,
+                                                       const float* __restrict__ LSE, const float* __restrict__ delta,
+                                                       float* __restrict__ dQ, int N, int Bs, int Hq, int Hkv,
+                                                       float scale, float scale_log2e) {
+  constexpr int KS = D / 16, DT = D / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t ks[BN][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t vs[BN][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t kt_[D][BN + 8];
+  const int hq = blockIdx.y, b = blockIdx.z, hk = hq / (Hq / Hkv);
+  const size_t qh = ((size_t)b * Hq + hq) * N, kh = ((size_t)b * Hkv + hk) * N;
+  const int q0 = (gridDim.x - 1 - blockIdx.x) * 128;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  const int nq = q0 + 32 * wave + col;
+  const int nqc = nq < N ? nq : N - 1;
+  const int myb = (nqc / Bs) * Bs;
+
+  bf16x8_t qf[KS], gf[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    qf[s] = *reinterpret_cast<const bf16x8_t*>(Q + (qh + nqc) * D + 16 * s + 8 * half);
+    gf[s] = *reinterpret_cast<const bf16x8_t*>(dO + (qh + nqc) * D + 16 * s + 8 * half);
+  }
+  const float lse2 = LSE[qh + nqc] * 1.4426950408889634f, dl = delta[qh + nqc];
+  f32x16_t dq[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dq[t][e] = 0.f;
+
+  const int kbeg = (q0 / Bs) * Bs, kend = min(q0 + 128, N);
+  for (int k0 = kbeg; k0 < kend; k0 += BN) {
+    __syncthreads();
+    load_tile<D, BN, true, true>(K + kh * D, k0, N, ks, kt_);
+    load_tile<D, BN, true, false>(V + kh * D, k0, N, vs, nullptr);
+    __syncthreads();
+    if (k0 > q0 + 32 * wave + 31) continue;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      f32x16_t s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+      for (int x = 0; x < KS; ++x) {
+        bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&ks[32 * kt + col][16 * x + 8 * half]);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[x], s, 0, 0, 0);
+        bf16x8_t av = *reinterpret_cast<const bf16x8_t*>(&vs[32 * kt + col][16 * x + 8 * half]);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, gf[x], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        int kg = k0 + 32 * kt + 8 * (e / 4) + 4 * half + (e % 4);
+        float p = fast_exp2(fmaf(s[e], scale_log2e, -lse2));
+        p = (kg > nq || kg < myb) ? 0.f : p;
+        s[e] = p * (dp[e] - dl);
+      }
+#pragma unroll
+      for (int G = 0; G < 2; ++G) {
+        bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+          bf16x8_t a = ld_tr8(&kt_[32 * t + col][0], 32 * kt + 16 * G, half);
+          dq[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, df, dq[t], 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (nq >= N) return;
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      float* p = dQ + (qh + nq) * D + 32 * t + 8 * g + 4 * half;
+      float4 old = *reinterpret_cast<float4*>(p);
+      old.x += scale * dq[t][4 * g + 0]; old.y += scale * dq[t][4 * g + 1];
+      old.z += scale * dq[t][4 * g + 2]; old.w += scale * dq[t][4 * g + 3];
+      *reinterpret_cast<float4*>(p) = old;
+    }
+}
+
+template <int D>
+__global__ void __launch_bounds__(256) k_flash_bwd_dkv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                        const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO,
+                                                        const float* __restrict__ LSE, const float* __restrict__ delta,
+                                                        float* __restrict__ dK, float* __restrict__ dV, int N, int Bs,
+                                                        int Hq, int Hkv, float scale, float scale_log2e) {
+  constexpr int KS = D / 16, DT = D / 32;
+  constexpr int BQ = D == 64 ? 64 : 32;  // queries staged per step (LDS budget)
+  __shared__ __attribute__((aligned(16))) bf16_t qs[BQ][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gs[BQ][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][BQ + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][BQ + 8];
+  __shared__ __attribute__((aligned(16))) float lse_s[BQ];
+  __shared__ __attribute__((aligned(16))) float dl_s[BQ];
+  const int hk = blockIdx.y, b = blockIdx.z, G_ = Hq / Hkv;
+  const size_t kh = ((size_t)b * Hkv + hk) * N;
+  const int k0 = blockIdx.x * 128;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  const int mk = k0 + 32 * wave + col;
+  const int mkc = mk < N ? mk : N - 1;
+  const int myend = min((mkc / Bs + 1) * Bs, N);
+  const int qend = min((min(k0 + 127, N - 1) / Bs + 1) * Bs, N);
+
+  bf16x8_t kf[KS], vf[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    kf[s] = *reinterpret_cast<const bf16x8_t*>(K + (kh + mkc) * D + 16 * s + 8 * half);
+    vf[s] = *reinterpret_cast<const bf16x8_t*>(V + (kh + mkc) * D + 16 * s + 8 * half);
+  }
+  f32x16_t dk[DT], dv[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { dk[t][e] = 0.f; dv[t][e] = 0.f; }
+
+  for (int g = 0; g < G_; ++g) {
+    const size_t qh = ((size_t)b * Hq + (size_t)hk * G_ + g) * N;
+    for (int q0 = k0; q0 < qend; q0 += BQ) {
+      __syncthreads();
+      load_tile<D, BQ, true, true>(Q + qh * D, q0, N, qs, qt_);
+      load_tile<D, BQ, true, true>(dO + qh * D, q0, N, gs, gt_);
+      if (threadIdx.x < BQ) {
+        int n = q0 + threadIdx.x;
+        n = n < N ? n : N - 1;
+        lse_s[threadIdx.x] = LSE[qh + n] * 1.4426950408889634f;
+        dl_s[threadIdx.x] = delta[qh + n];
+      }
+      __syncthreads();
+      if (q0 + BQ - 1 < k0 + 32 * wave) continue;  // every query of the tile precedes this wave's keys
+#pragma unroll
+      for (int qt = 0; qt < BQ / 32; ++qt) {
+        f32x16_t s, dp;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+        for (int x = 0; x < KS; ++x) {
+          bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&qs[32 * qt + col][16 * x + 8 * half]);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[x], s, 0, 0, 0);
+          bf16x8_t ag = *reinterpret_cast<const bf16x8_t*>(&gs[32 * qt + col][16 * x + 8 * half]);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, vf[x], dp, 0, 0, 0);
+        }
+        f32x16_t pr;
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          float4 l4 = *reinterpret_cast<const float4*>(&lse_s[32 * qt + 8 * gq + 4 * half]);
+          float4 d4 = *reinterpret_cast<const float4*>(&dl_s[32 * qt + 8 * gq + 4 * half]);
+          float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            int e = 4 * gq + u;
+            int n = q0 + 32 * qt + 8 * gq + 4 * half + u;
+            float p = fast_exp2(fmaf(s[e], scale_log2e, -lv[u]));
+            p = (n < mk || n >= myend) ? 0.f : p;
+            pr[e] = p;
+            s[e] = p * (dp[e] - dv4[u]);
+          }
+        }
+#pragma unroll
+        for (int G = 0; G < 2; ++G) {
+          bf16x8_t pf = pack8(pr, 2 * G, 2 * G + 1);
+          bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
+#pragma unroll
+          for (int t = 0; t < DT; ++t) {
+            bf16x8_t ag = ld_tr8(&gt_[32 * t + col][0], 32 * qt + 16 * G, half);
+            dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, pf, dv[t], 0, 0, 0);
+            bf16x8_t aq = ld_tr8(&qt_[32 * t + col][0], 32 * qt + 16 * G, half);
+            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, df, dk[t], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+  if (mk >= N) return;
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      size_t o = (kh + mk) * D + 32 * t + 8 * g + 4 * half;
+      float4 a = *reinterpret_cast<float4*>(dK + o), c = *reinterpret_cast<float4*>(dV + o);
+      a.x += scale * dk[t][4 * g + 0]; a.y += scale * dk[t][4 * g + 1];
+      a.z += scale * dk[t][4 * g + 2]; a.w += scale * dk[t][4 * g + 3];
+      c.x += dv[t][4 * g + 0]; c.y += dv[t][4 * g + 1]; c.z += dv[t][4 * g + 2]; c.w += dv[t][4 * g + 3];
+      *reinterpret_cast<float4*>(dK + o) = a;
+      *reinterpret_cast<float4*>(dV + o) = c;
+    }
+}
+
+}  // namespace
+
+int muse_launch_attn_fwd_mfma(const MuseDims& d, int Bs, const void* Q, const void* K, const void* V,
+                              const float* ff, void* O, float* LSE, hipStream_t st) {
+  dim3 g((d.N + 127) / 128, d.Hq, d.B);
+  float sl = d.scale * 1.4426950408889634f;
+  if (d.D == 64)
+    hipLaunchKernelGGL(k_flash_fwd<64>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, ff,
+                       (bf16_t*)O, LSE, d.N, Bs, d.Hq, d.Hkv, sl);
+  else
+    hipLaunchKernelGGL(k_flash_fwd<128>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, ff,
+                       (bf16_t*)O, LSE, d.N, Bs, d.Hq, d.Hkv, sl);
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
+
+int muse_launch_attn_bwd_mfma(const MuseDims& d, int Bs, const void* Q, const void* K, const void* V,
+                              const void* dO, const float* LSE, const float* delta, float* dQacc,
+                              float* dKacc, float* dVacc, hipStream_t st) {
+  dim3 gq((d.N + 127) / 128, d.Hq, d.B), gk((d.N + 127) / 128, d.Hkv, d.B);
+  float sl = d.scale * 1.4426950408889634f;
+  const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V, *g = (const bf16_t*)dO;
+  if (d.D == 64) {
+    hipLaunchKernelGGL(k_flash_bwd_dq<64>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl);
+    hipLaunchKernelGGL(k_flash_bwd_dkv<64>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl);
+  } else {
+    hipLaunchKernelGGL(k_flash_bwd_dq<128>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl);
+    hipLaunchKernelGGL(k_flash_bwd_dkv<128>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl);
+  }
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}

@@ -1,0 +1,118 @@
+// Shared device helpers for the MuSe kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/muse.h"
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+#define MUSE_WAVE 64
+#define MUSE_NEG_INF (-__builtin_huge_valf())
+
+__device__ __forceinline__ float bf16_bits_to_f32(bf16_t h) {
+  return __uint_as_float(((uint32_t)h) << 16);
+}
+
+// round-to-nearest-even; inf/nan pass through (nan stays nan because the top mantissa bit survives)
+__device__ __forceinline__ bf16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7f800000u) == 0x7f800000u) return (bf16_t)(u >> 16);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+}
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+  static constexpr int kBytes = 4;
+  __device__ static __forceinline__ float ld(const float* p, size_t i) { return p[i]; }
+  __device__ static __forceinline__ void st(float* p, size_t i, float v) { p[i] = v; }
+};
+template <>
+struct Elem<bf16_t> {
+  static constexpr int kBytes = 2;
+  __device__ static __forceinline__ float ld(const bf16_t* p, size_t i) { return bf16_bits_to_f32(p[i]); }
+  __device__ static __forceinline__ void st(bf16_t* p, size_t i, float v) { p[i] = f32_to_bf16_bits(v); }
+};
+
+// loads 4 consecutive elements (address must be aligned to 4 elements)
+__device__ __forceinline__ void ld4(const float* p, size_t i, float out[4]) {
+  float4 v = *reinterpret_cast<const float4*>(p + i);
+  out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+__device__ __forceinline__ void ld4(const bf16_t* p, size_t i, float out[4]) {
+  uint2 v = *reinterpret_cast<const uint2*>(p + i);
+  out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xffff0000u);
+  out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xffff0000u);
+}
+__device__ __forceinline__ void st4(float* p, size_t i, const float v[4]) {
+  *reinterpret_cast<float4*>(p + i) = make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void st4(bf16_t* p, size_t i, const float v[4]) {
+  *reinterpret_cast<uint2*>(p + i) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// host-side launch parameters shared by the translation units
+struct MuseDims {
+  int B, Hq, Hkv, N, D, Cq, Ck, r, k2, k2e, Bs, nb, T;
+  int dtype, grad_dtype;
+  float scale;
+};
+
+#define MUSE_HIP_CHECK(expr)                      \
+  do {                                            \
+    hipError_t e__ = (expr);                      \
+    if (e__ != hipSuccess) return MUSE_ERR_HIP;   \
+  } while (0)
+
+#define MUSE_LAUNCH_CHECK()                                   \
+  do {                                                        \
+    if (hipGetLastError() != hipSuccess) return MUSE_ERR_HIP; \
+  } while (0)
+
+// ---- stage launchers (one per translation unit) ------------------------------------------
+// kmeans.hip
+size_t muse_cluster_ws_bytes(const MuseDims& d);
+int muse_launch_cluster(const MuseDims& d, const void* X, int H, int C, const int32_t* init_idx,
+                        float* cent, int32_t* assign, void* ws, hipStream_t st);
+// Stable bucketing of the N positions of every head by (spatial block, cluster):
+// perm [heads, N] position lists, off [heads, nb*C + 1] segment offsets.
+int muse_launch_bucket(const int32_t* assign, int heads, int N, int Bs, int C, int32_t* perm,
+                       int32_t* off, hipStream_t st);
+
+// attn_simple.hip / attn_mfma.hip: causal attention restricted to keys m with
+// floor(n/Bs)*Bs <= m <= n  (Bs = N gives exact attention).  ff (may be NULL): per query
+// (max, sum, acc[D]) fp32 partial softmax state in natural-log units merged into the result.
+int muse_launch_attn_fwd(const MuseDims& d, int Bs, const void* Q, const void* K, const void* V,
+                         const float* ff, void* O, float* LSE, hipStream_t st);
+// delta [B,Hq,N] = dO . O
+int muse_launch_delta(const MuseDims& d, const void* O, const void* dO, float* delta, hipStream_t st);
+// dQacc [B,Hq,N,D], dKacc, dVacc [B,Hkv,N,D] fp32: += contribution (buffers hold the far-field part
+// or zeros on entry).
+int muse_launch_attn_bwd(const MuseDims& d, int Bs, const void* Q, const void* K, const void* V,
+                         const void* dO, const float* LSE, const float* delta, float* dQacc,
+                         float* dKacc, float* dVacc, hipStream_t st);
+// fp32 accumulators -> gradient tensors of grad dtype, multiplied by `mul`
+int muse_launch_cast(const float* src, void* dst, size_t n, int dst_dtype, float mul, hipStream_t st);
+int muse_launch_fill(float* dst, size_t n, float v, hipStream_t st);

@@ -1,0 +1,367 @@
+// Clustering stage (Sec. 3 "Clustering", App. C): Lloyd K-means per head at a fixed iteration
+// count, nearest centroid by ||c||^2 - 2<x,c> (App. C, "Balanced Assignment": the ||x||^2 term
+// cancels), and the stable bucketing by (spatial block, cluster) that both the centroid update
+// and the attention stages use.
+//
+//   assign (bf16): the N x C x D similarity is a dense contraction -> MFMA 32x32x16 bf16 with the
+//                  argmin kept in the accumulator layout (one query point per lane column).
+//   assign (fp32): plain FMA kernel, used for fp32 inputs only.
+//   bucket:        one workgroup per (head, spatial block), LDS histograms per wave, ballot-based
+//                  stable ranks -> no global atomics, order inside a segment = ascending position.
+//   update:        one wave per (head, cluster): fixed-order sum over its segments.
+#include "common.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// centroid gather / preparation
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void k_init_centroids(const T* __restrict__ X, const int32_t* __restrict__ init_idx,
+                                 float* __restrict__ cent, int N, int D, int C) {
+  int h = blockIdx.y, j = blockIdx.x;
+  int row = init_idx[(size_t)h * C + j];
+  for (int d = threadIdx.x; d < D; d += blockDim.x)
+    cent[((size_t)h * C + j) * D + d] = Elem<T>::ld(X, ((size_t)h * N + row) * D + d);
+}
+
+// chat [H,C,D]: centroid in the scoring type; nhc2 [H,C] = -0.5 * ||chat||^2 (fp32 of the rounded values)
+template <typename T>
+__global__ void k_prep_centroids(const float* __restrict__ cent, T* __restrict__ chat,
+                                 float* __restrict__ nhc2, int D, int total) {
+  int row = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64;
+  int lane = threadIdx.x % 64;
+  if (row >= total) return;
+  float s = 0.f;
+  for (int d = lane; d < D; d += 64) {
+    float c = cent[(size_t)row * D + d];
+    Elem<T>::st(chat, (size_t)row * D + d, c);
+    float cr = Elem<T>::ld(chat, (size_t)row * D + d);
+    s += cr * cr;
+  }
+  s = wave_sum(s);
+  if (lane == 0) nhc2[row] = -0.5f * s;
+}
+
+// ------------------------------------------------------------------------------------------
+// assignment, fp32 inputs: one thread per point, centroid tiles in LDS
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256) k_assign_f32(const float* __restrict__ X,
+                                                     const float* __restrict__ chat,
+                                                     const float* __restrict__ nhc2,
+                                                     int32_t* __restrict__ assign, int N, int C) {
+  constexpr int CT = 32;
+  __shared__ float cs[CT][D + 1];
+  __shared__ float c2s[CT];
+  int h = blockIdx.y;
+  int n = blockIdx.x * 256 + threadIdx.x;
+  float x[D];
+  if (n < N) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) x[d] = X[((size_t)h * N + n) * D + d];
+  }
+  float best = MUSE_NEG_INF;
+  int bj = 0;
+  for (int j0 = 0; j0 < C; j0 += CT) {
+    __syncthreads();
+    for (int t = threadIdx.x; t < CT * D; t += 256) {
+      int jj = t / D, d = t % D;
+      cs[jj][d] = (j0 + jj < C) ? chat[((size_t)h * C + j0 + jj) * D + d] : 0.f;
+    }
+    if (threadIdx.x < CT) c2s[threadIdx.x] = (j0 + threadIdx.x < C) ? nhc2[(size_t)h * C + j0 + threadIdx.x] : MUSE_NEG_INF;
+    __syncthreads();
+    if (n < N) {
+      for (int jj = 0; jj < CT && j0 + jj < C; ++jj) {
+        float acc = c2s[jj];
+#pragma unroll
+        for (int d = 0; d < D; ++d) acc = fmaf(x[d], cs[jj][d], acc);
+        if (acc > best) { best = acc; bj = j0 + jj; }
+      }
+    }
+  }
+  if (n < N) assign[(size_t)h * N + n] = bj;
+}
+
+// ------------------------------------------------------------------------------------------
+// assignment, bf16 inputs: S^T = Chat X^T on MFMA, accumulator preloaded with -||c||^2/2, so the
+// nearest centroid is the row-argmax.  Each wave owns PT tiles of 32 points (one point per lane
+// column, two lane halves hold different centroid rows).
+// ------------------------------------------------------------------------------------------
+template <int D, int PT>
+__global__ void __launch_bounds__(256) k_assign_bf16(const bf16_t* __restrict__ X,
+                                                      const bf16_t* __restrict__ chat,
+                                                      const float* __restrict__ nhc2,
+                                                      int32_t* __restrict__ assign, int N, int C) {
+  constexpr int KS = D / 16;
+  const int h = blockIdx.y;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int col = lane % 32, half = lane / 32;
+  const int p0 = (blockIdx.x * 4 + wave) * (32 * PT);
+  const bf16_t* Xh = X + (size_t)h * N * D;
+  const bf16_t* Ch = chat + (size_t)h * C * D;
+  const float* c2h = nhc2 + (size_t)h * C;
+
+  bf16x8_t xb[PT][KS];
+#pragma unroll
+  for (int t = 0; t < PT; ++t) {
+    int n = p0 + 32 * t + col;
+    n = n < N ? n : N - 1;
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+      xb[t][s] = *reinterpret_cast<const bf16x8_t*>(Xh + (size_t)n * D + 16 * s + 8 * half);
+  }
+  float best[PT][16];
+  int btile[PT][16];
+#pragma unroll
+  for (int t = 0; t < PT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { best[t][e] = MUSE_NEG_INF; btile[t][e] = 0; }
+
+  const int ntile = (C + 31) / 32;
+  for (int ct = 0; ct < ntile; ++ct) {
+    int j = ct * 32 + col;
+    int jc = j < C ? j : C - 1;
+    bf16x8_t ca[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+      ca[s] = *reinterpret_cast<const bf16x8_t*>(Ch + (size_t)jc * D + 16 * s + 8 * half);
+    f32x16_t init;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        int jr = ct * 32 + 8 * g + 4 * half + u;
+        init[4 * g + u] = jr < C ? c2h[jr] : MUSE_NEG_INF;
+      }
+#pragma unroll
+    for (int t = 0; t < PT; ++t) {
+      f32x16_t acc = init;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[s], xb[t][s], acc, 0, 0, 0);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        bool gt = acc[e] > best[t][e];
+        best[t][e] = gt ? acc[e] : best[t][e];
+        btile[t][e] = gt ? ct : btile[t][e];
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < PT; ++t) {
+    float bv = MUSE_NEG_INF;
+    int bj = 0x7fffffff;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int j = btile[t][e] * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+      bool take = best[t][e] > bv || (best[t][e] == bv && j < bj);
+      bv = take ? best[t][e] : bv;
+      bj = take ? j : bj;
+    }
+    float ov = __shfl_xor(bv, 32, 64);
+    int oj = __shfl_xor(bj, 32, 64);
+    if (ov > bv || (ov == bv && oj < bj)) { bv = ov; bj = oj; }
+    int n = p0 + 32 * t + col;
+    if (half == 0 && n < N) assign[(size_t)h * N + n] = bj;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// stable bucketing by (block, cluster): grid (nb, heads), 1024 threads = 16 waves
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024) k_bucket(const int32_t* __restrict__ assign,
+                                                  int32_t* __restrict__ perm,
+                                                  int32_t* __restrict__ off, int N, int Bs, int C) {
+  extern __shared__ uint32_t smem[];
+  uint32_t* hist = smem;               // [16][C]
+  uint32_t* tot = smem + 16 * C;       // [C]
+  __shared__ uint32_t wsum[16];
+  const int b = blockIdx.x, h = blockIdx.y, nb = gridDim.x;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int32_t* a = assign + (size_t)h * N + (size_t)b * Bs;
+  const int sub = (Bs + 15) / 16;
+  const int lo = wave * sub, hi = min(lo + sub, Bs);
+
+  for (int t = threadIdx.x; t < 17 * C; t += 1024) smem[t] = 0;
+  __syncthreads();
+  for (int i = lo + lane; i < hi; i += 64) atomicAdd(&hist[wave * C + a[i]], 1u);
+  __syncthreads();
+  // per cluster: exclusive prefix over the waves, total per cluster
+  for (int c = threadIdx.x; c < C; c += 1024) {
+    uint32_t run = 0;
+    for (int w = 0; w < 16; ++w) {
+      uint32_t v = hist[w * C + c];
+      hist[w * C + c] = run;
+      run += v;
+    }
+    tot[c] = run;
+  }
+  __syncthreads();
+  // exclusive scan of tot over clusters; every thread owns a contiguous run of clusters
+  const int per = (C + 1023) / 1024;
+  uint32_t mine = 0;
+  for (int u = 0; u < per; ++u) {
+    int c = threadIdx.x * per + u;
+    if (c < C) mine += tot[c];
+  }
+  uint32_t incl = mine;
+  for (int o = 1; o < 64; o <<= 1) {
+    uint32_t v = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += v;
+  }
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int w = 0; w < wave; ++w) base += wsum[w];
+  uint32_t run = base + incl - mine;
+  for (int u = 0; u < per; ++u) {
+    int c = threadIdx.x * per + u;
+    if (c < C) {
+      uint32_t v = tot[c];
+      tot[c] = run;
+      off[(size_t)h * ((size_t)nb * C + 1) + (size_t)b * C + c] = b * Bs + (int)run;
+      run += v;
+    }
+  }
+  if (b == nb - 1 && threadIdx.x == 0) off[(size_t)h * ((size_t)nb * C + 1) + (size_t)nb * C] = N;
+  __syncthreads();
+  // placement: each wave walks its sub-chunk in order; equal keys inside a group of 64 are ranked
+  // by lane with ballots over the key bits
+  for (int i0 = lo; i0 < hi; i0 += 64) {
+    int i = i0 + lane;
+    bool act = i < hi;
+    int key = act ? a[i] : 0;
+    unsigned long long m = __ballot(act);
+#pragma unroll
+    for (int bit = 0; bit < 12; ++bit) {
+      unsigned long long bb = __ballot((key >> bit) & 1);
+      m &= ((key >> bit) & 1) ? bb : ~bb;
+    }
+    unsigned long long below = m & ((1ull << lane) - 1ull);
+    int rank = __popcll(below), cnt = __popcll(m);
+    if (act) {
+      uint32_t start = hist[wave * C + key];
+      perm[(size_t)h * N + (size_t)b * Bs + tot[key] + start + rank] = b * Bs + i;
+      if (rank == cnt - 1) hist[wave * C + key] = start + cnt;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// centroid update: one wave per (head, cluster); RL lanes cover one row with 16-byte loads, the
+// 64/RL row slots run over the members in order, slots are combined in a fixed tree.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) k_update(const T* __restrict__ X, const int32_t* __restrict__ perm,
+                                                 const int32_t* __restrict__ off, float* __restrict__ cent,
+                                                 int N, int D, int C, int nb, int total) {
+  constexpr int EPL = 16 / Elem<T>::kBytes;  // elements per lane
+  int wid = blockIdx.x * 4 + threadIdx.x / 64;
+  if (wid >= total) return;
+  const int lane = threadIdx.x % 64;
+  const int h = wid / C, j = wid % C;
+  const int RL = D / EPL, slots = 64 / RL;
+  const int slot = lane / RL, chunk = lane % RL;
+  const T* Xh = X + (size_t)h * N * D;
+  const int32_t* ph = perm + (size_t)h * N;
+  const int32_t* oh = off + (size_t)h * ((size_t)nb * C + 1);
+  float acc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+  int count = 0;
+  for (int b = 0; b < nb; ++b) {
+    int lo = oh[b * C + j], hi = oh[b * C + j + 1];
+    count += hi - lo;
+    for (int p = lo + slot; p < hi; p += slots) {
+      int row = ph[p];
+      if constexpr (EPL == 8) {
+        uint4 v = *reinterpret_cast<const uint4*>(Xh + (size_t)row * D + chunk * 8);
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[2 * e] += __uint_as_float(w[e] << 16);
+          acc[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+        }
+      } else {
+        float4 v = *reinterpret_cast<const float4*>(Xh + (size_t)row * D + chunk * 4);
+        acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+      }
+    }
+  }
+  for (int o = RL; o < 64; o <<= 1)
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
+  if (slot == 0 && count > 0) {
+    float inv = (float)count;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) cent[((size_t)h * C + j) * D + chunk * EPL + e] = acc[e] / inv;
+  }
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+template <typename T>
+int cluster_impl(const MuseDims& d, const T* X, int H, int C, const int32_t* init_idx, float* cent,
+                 int32_t* assign, void* ws, hipStream_t st) {
+  const int N = d.N, D = d.D, heads = d.B * H;
+  char* w = (char*)ws;
+  T* chat = (T*)w;                w += align256((size_t)heads * C * D * sizeof(T));
+  float* nhc2 = (float*)w;        w += align256((size_t)heads * C * sizeof(float));
+  int32_t* perm = (int32_t*)w;    w += align256((size_t)heads * N * sizeof(int32_t));
+  int32_t* off = (int32_t*)w;
+  if (init_idx) {
+    hipLaunchKernelGGL(k_init_centroids<T>, dim3(C, heads), dim3(64), 0, st, X, init_idx, cent, N, D, C);
+    MUSE_LAUNCH_CHECK();
+  }
+  for (int it = 0; it <= d.T; ++it) {
+    int rows = heads * C;
+    hipLaunchKernelGGL(k_prep_centroids<T>, dim3((rows + 3) / 4), dim3(256), 0, st, cent, chat, nhc2, D, rows);
+    MUSE_LAUNCH_CHECK();
+    if constexpr (sizeof(T) == 4) {
+      dim3 g((N + 255) / 256, heads);
+      if (D == 64) hipLaunchKernelGGL(k_assign_f32<64>, g, dim3(256), 0, st, (const float*)X, (const float*)chat, nhc2, assign, N, C);
+      else hipLaunchKernelGGL(k_assign_f32<128>, g, dim3(256), 0, st, (const float*)X, (const float*)chat, nhc2, assign, N, C);
+    } else {
+      constexpr int PT = 2;
+      dim3 g((N + 4 * 32 * PT - 1) / (4 * 32 * PT), heads);
+      if (D == 64) hipLaunchKernelGGL((k_assign_bf16<64, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C);
+      else hipLaunchKernelGGL((k_assign_bf16<128, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C);
+    }
+    MUSE_LAUNCH_CHECK();
+    if (it == d.T) break;
+    int rc = muse_launch_bucket(assign, heads, N, d.Bs, C, perm, off, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_update<T>, dim3((rows + 3) / 4), dim3(256), 0, st, X, perm, off, cent, N, D, C, d.nb, rows);
+    MUSE_LAUNCH_CHECK();
+  }
+  return MUSE_OK;
+}
+
+}  // namespace
+
+size_t muse_cluster_ws_bytes(const MuseDims& d) {
+  size_t heads = (size_t)d.B * (d.Hq > d.Hkv ? d.Hq : d.Hkv);
+  size_t C = d.Cq > d.Ck ? d.Cq : d.Ck;
+  return align256(heads * C * d.D * 4) + align256(heads * C * 4) + align256(heads * d.N * 4) +
+         align256(heads * ((size_t)d.nb * C + 1) * 4);
+}
+
+int muse_launch_bucket(const int32_t* assign, int heads, int N, int Bs, int C, int32_t* perm,
+                       int32_t* off, hipStream_t st) {
+  size_t lds = (size_t)17 * C * sizeof(uint32_t);
+  if (lds > 150 * 1024) return MUSE_ERR_UNSUPPORTED;
+  static bool attr_set = false;
+  if (!attr_set) {
+    MUSE_HIP_CHECK(hipFuncSetAttribute((const void*)k_bucket, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(k_bucket, dim3(N / Bs, heads), dim3(1024), lds, st, assign, perm, off, N, Bs, C);
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
+
+int muse_launch_cluster(const MuseDims& d, const void* X, int H, int C, const int32_t* init_idx,
+                        float* cent, int32_t* assign, void* ws, hipStream_t st) {
+  if (d.dtype == MUSE_DTYPE_FP32) return cluster_impl<float>(d, (const float*)X, H, C, init_idx, cent, assign, ws, st);
+  return cluster_impl<bf16_t>(d, (const bf16_t*)X, H, C, init_idx, cent, assign, ws, st);
+}

@@ -1,0 +1,192 @@
+// C-ABI entry points of libmuse: argument validation on the host, workspace carving, stage order.
+#include <math.h>
+
+#include "common.h"
+
+// farfield.hip
+size_t muse_farfield_ws_bytes(const MuseDims& d, bool bwd, int heads_at_once);
+size_t muse_farfield_fixed_bytes(const MuseDims& d, bool bwd);
+int muse_run_fwd(const MuseDims& d, const void* Q, const void* K, const void* V, const float* qc,
+                 const int32_t* aq, const int32_t* ak, void* O, float* LSE, int32_t* selc, int32_t* selb,
+                 void* ws, size_t ws_bytes, hipStream_t st);
+int muse_run_bwd(const MuseDims& d, const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                 const void* dO, const float* qc, const int32_t* aq, const int32_t* ak, const int32_t* selc,
+                 const int32_t* selb, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, hipStream_t st);
+
+namespace {
+
+size_t al(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// validates and derives; `full` = the clustering / MuSe fields matter too
+int make_dims(const muse_params* p, bool full, MuseDims* d) {
+  if (!p) return MUSE_ERR_INVALID_ARG;
+  if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->N < 1 || p->Hq % p->Hkv) return MUSE_ERR_INVALID_ARG;
+  if (p->dtype != MUSE_DTYPE_FP32 && p->dtype != MUSE_DTYPE_BF16) return MUSE_ERR_INVALID_ARG;
+  if (p->grad_dtype != MUSE_DTYPE_FP32 && p->grad_dtype != p->dtype) return MUSE_ERR_INVALID_ARG;
+  if (p->flags != 0) return MUSE_ERR_INVALID_ARG;
+  if (!(p->scale >= 0.f) || isinf(p->scale)) return MUSE_ERR_INVALID_ARG;
+  if (p->causal != 1) return MUSE_ERR_UNSUPPORTED;
+  if (p->D != 64 && p->D != 128) return MUSE_ERR_UNSUPPORTED;
+  d->B = p->B; d->Hq = p->Hq; d->Hkv = p->Hkv; d->N = p->N; d->D = p->D;
+  d->dtype = p->dtype; d->grad_dtype = p->grad_dtype;
+  d->scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->D);
+  d->Cq = d->Ck = 1; d->r = 0; d->k2 = 1; d->k2e = 1; d->Bs = p->N; d->nb = 1; d->T = 0;
+  if (!full) return MUSE_OK;
+  int Bs = p->block > 0 ? p->block : p->N / 8;
+  if (p->block < 0 || Bs < 1 || p->N % Bs) return MUSE_ERR_INVALID_ARG;
+  if (p->Cq < 1 || p->Ck < 1 || p->Cq > p->N || p->Ck > p->N) return MUSE_ERR_INVALID_ARG;
+  if (p->r < 0 || p->r > p->Ck || p->k2 < 0 || p->kmeans_iters < 0) return MUSE_ERR_INVALID_ARG;
+  if (p->Cq > 2048 || p->Ck > 2048 || p->r > 32 || p->N / Bs > 16 || Bs > 16384) return MUSE_ERR_UNSUPPORTED;
+  d->Bs = Bs; d->nb = p->N / Bs; d->Cq = p->Cq; d->Ck = p->Ck;
+  d->r = p->r;
+  d->k2 = p->k2; d->T = p->kmeans_iters;
+  d->k2e = p->k2 > 0 ? p->k2 : (d->nb > 1 ? d->nb - 1 : 1);
+  if (d->k2e > 16) return MUSE_ERR_UNSUPPORTED;
+  return MUSE_OK;
+}
+
+size_t exact_bwd_bytes(const MuseDims& d) {
+  size_t q = (size_t)d.B * d.Hq * d.N, k = (size_t)d.B * d.Hkv * d.N;
+  size_t b = al(q * 4);  // delta
+  if (d.grad_dtype != MUSE_DTYPE_FP32) b += al(q * d.D * 4) + 2 * al(k * d.D * 4);
+  return b;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* muse_strerror(int code) {
+  switch (code) {
+    case MUSE_OK: return "ok";
+    case MUSE_ERR_INVALID_ARG: return "invalid argument";
+    case MUSE_ERR_UNSUPPORTED: return "unsupported configuration";
+    case MUSE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MUSE_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error code";
+  }
+}
+
+int muse_workspace_bytes(const muse_params* p, int which, size_t* min_bytes, size_t* preferred) {
+  if (!min_bytes) return MUSE_ERR_INVALID_ARG;
+  MuseDims d;
+  bool full = which == MUSE_WS_CLUSTER || which == MUSE_WS_FWD || which == MUSE_WS_BWD;
+  int rc = make_dims(p, full, &d);
+  if (rc) return rc;
+  size_t mn = 0, pref = 0;
+  switch (which) {
+    case MUSE_WS_CLUSTER: mn = pref = muse_cluster_ws_bytes(d); break;
+    case MUSE_WS_EXACT_FWD: mn = pref = 256; break;
+    case MUSE_WS_EXACT_BWD: mn = pref = exact_bwd_bytes(d); break;
+    case MUSE_WS_FWD:
+    case MUSE_WS_BWD: {
+      bool bwd = which == MUSE_WS_BWD;
+      mn = muse_farfield_fixed_bytes(d, bwd) + muse_farfield_ws_bytes(d, bwd, 1);
+      pref = muse_farfield_fixed_bytes(d, bwd) + muse_farfield_ws_bytes(d, bwd, d.B * d.Hq);
+      break;
+    }
+    default: return MUSE_ERR_INVALID_ARG;
+  }
+  *min_bytes = mn;
+  if (preferred) *preferred = pref;
+  return MUSE_OK;
+}
+
+int muse_cluster(const muse_params* p, const void* Q, const void* K, const int32_t* q_init_idx,
+                 const int32_t* k_init_idx, float* q_centroids, int32_t* q_assign, float* k_centroids,
+                 int32_t* k_assign, void* ws, size_t ws_bytes, void* stream) {
+  MuseDims d;
+  int rc = make_dims(p, true, &d);
+  if (rc) return rc;
+  if (!Q && !K) return MUSE_ERR_INVALID_ARG;
+  if (Q && (!q_centroids || !q_assign)) return MUSE_ERR_INVALID_ARG;
+  if (K && (!k_centroids || !k_assign)) return MUSE_ERR_INVALID_ARG;
+  if (!ws) return MUSE_ERR_INVALID_ARG;
+  if (ws_bytes < muse_cluster_ws_bytes(d)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)stream;
+  if (Q) {
+    rc = muse_launch_cluster(d, Q, d.Hq, d.Cq, q_init_idx, q_centroids, q_assign, ws, st);
+    if (rc) return rc;
+  }
+  if (K) {
+    rc = muse_launch_cluster(d, K, d.Hkv, d.Ck, k_init_idx, k_centroids, k_assign, ws, st);
+    if (rc) return rc;
+  }
+  return MUSE_OK;
+}
+
+int muse_fwd(const muse_params* p, const void* Q, const void* K, const void* V, const float* q_centroids,
+             const int32_t* q_assign, const int32_t* k_assign, void* O, float* LSE, int32_t* sel_clusters,
+             int32_t* sel_blocks, void* ws, size_t ws_bytes, void* stream) {
+  MuseDims d;
+  int rc = make_dims(p, true, &d);
+  if (rc) return rc;
+  if (!Q || !K || !V || !q_centroids || !q_assign || !k_assign || !O || !LSE || !ws) return MUSE_ERR_INVALID_ARG;
+  if (d.r > 0 && (!sel_clusters || !sel_blocks)) return MUSE_ERR_INVALID_ARG;
+  size_t need = muse_farfield_fixed_bytes(d, false) + muse_farfield_ws_bytes(d, false, 1);
+  if (ws_bytes < need) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  return muse_run_fwd(d, Q, K, V, q_centroids, q_assign, k_assign, O, LSE, sel_clusters, sel_blocks, ws, ws_bytes,
+                      (hipStream_t)stream);
+}
+
+int muse_bwd(const muse_params* p, const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+             const void* dO, const float* q_centroids, const int32_t* q_assign, const int32_t* k_assign,
+             const int32_t* sel_clusters, const int32_t* sel_blocks, void* dQ, void* dK, void* dV, void* ws,
+             size_t ws_bytes, void* stream) {
+  MuseDims d;
+  int rc = make_dims(p, true, &d);
+  if (rc) return rc;
+  if (!Q || !K || !V || !O || !LSE || !dO || !q_centroids || !q_assign || !k_assign || !dQ || !dK || !dV || !ws)
+    return MUSE_ERR_INVALID_ARG;
+  if (d.r > 0 && (!sel_clusters || !sel_blocks)) return MUSE_ERR_INVALID_ARG;
+  size_t need = muse_farfield_fixed_bytes(d, true) + muse_farfield_ws_bytes(d, true, 1);
+  if (ws_bytes < need) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  return muse_run_bwd(d, Q, K, V, O, LSE, dO, q_centroids, q_assign, k_assign, sel_clusters, sel_blocks, dQ, dK, dV,
+                      ws, ws_bytes, (hipStream_t)stream);
+}
+
+int exact_attn_fwd(const muse_params* p, const void* Q, const void* K, const void* V, void* O, float* LSE,
+                   void* ws, size_t ws_bytes, void* stream) {
+  (void)ws; (void)ws_bytes;
+  MuseDims d;
+  int rc = make_dims(p, false, &d);
+  if (rc) return rc;
+  if (!Q || !K || !V || !O || !LSE) return MUSE_ERR_INVALID_ARG;
+  return muse_launch_attn_fwd(d, d.N, Q, K, V, nullptr, O, LSE, (hipStream_t)stream);
+}
+
+int exact_attn_bwd(const muse_params* p, const void* Q, const void* K, const void* V, const void* O,
+                   const float* LSE, const void* dO, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes,
+                   void* stream) {
+  MuseDims d;
+  int rc = make_dims(p, false, &d);
+  if (rc) return rc;
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !ws) return MUSE_ERR_INVALID_ARG;
+  if (ws_bytes < exact_bwd_bytes(d)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)stream;
+  size_t q = (size_t)d.B * d.Hq * d.N, k = (size_t)d.B * d.Hkv * d.N;
+  char* w = (char*)ws;
+  float* delta = (float*)w; w += al(q * 4);
+  float *aq, *ak, *av;
+  bool direct = d.grad_dtype == MUSE_DTYPE_FP32;
+  if (direct) {
+    aq = (float*)dQ; ak = (float*)dK; av = (float*)dV;
+  } else {
+    aq = (float*)w; w += al(q * d.D * 4);
+    ak = (float*)w; w += al(k * d.D * 4);
+    av = (float*)w;
+  }
+  if ((rc = muse_launch_fill(aq, q * d.D, 0.f, st))) return rc;
+  if ((rc = muse_launch_fill(ak, k * d.D, 0.f, st))) return rc;
+  if ((rc = muse_launch_fill(av, k * d.D, 0.f, st))) return rc;
+  if ((rc = muse_launch_delta(d, O, dO, delta, st))) return rc;
+  if ((rc = muse_launch_attn_bwd(d, d.N, Q, K, V, dO, LSE, delta, aq, ak, av, st))) return rc;
+  if (!direct) {
+    if ((rc = muse_launch_cast(aq, dQ, q * d.D, d.grad_dtype, 1.f, st))) return rc;
+    if ((rc = muse_launch_cast(ak, dK, k * d.D, d.grad_dtype, 1.f, st))) return rc;
+    if ((rc = muse_launch_cast(av, dV, k * d.D, d.grad_dtype, 1.f, st))) return rc;
+  }
+  return MUSE_OK;
+}
+
+}  // extern "C"
