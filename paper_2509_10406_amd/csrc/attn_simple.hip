@@ -228,6 +228,12 @@ __global__ void k_cast(const float* __restrict__ src, T* __restrict__ dst, size_
   for (; i < n; i += stride) Elem<T>::st(dst, i, src[i] * mul);
 }
 
+__global__ void k_fill_i32(int32_t* __restrict__ dst, size_t n, int32_t v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = v;
+}
+
 __global__ void k_fill(float* __restrict__ dst, size_t n, float v) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -302,6 +308,14 @@ int muse_launch_fill(float* dst, size_t n, float v, hipStream_t st) {
   unsigned blocks = (unsigned)((n + 1023) / 1024 > 65535 * 16 ? 65535 * 16 : (n + 1023) / 1024);
   if (blocks == 0) return MUSE_OK;
   hipLaunchKernelGGL(k_fill, dim3(blocks), dim3(256), 0, st, dst, n, v);
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
+
+int muse_launch_fill_i32(int32_t* dst, size_t n, int32_t v, hipStream_t st) {
+  unsigned blocks = (unsigned)((n + 1023) / 1024 > 65535 * 16 ? 65535 * 16 : (n + 1023) / 1024);
+  if (blocks == 0) return MUSE_OK;
+  hipLaunchKernelGGL(k_fill_i32, dim3(blocks), dim3(256), 0, st, dst, n, v);
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }

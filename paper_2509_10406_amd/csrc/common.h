@@ -116,3 +116,4 @@ int muse_launch_attn_bwd(const MuseDims& d, int Bs, const void* Q, const void* K
 // fp32 accumulators -> gradient tensors of grad dtype, multiplied by `mul`
 int muse_launch_cast(const float* src, void* dst, size_t n, int dst_dtype, float mul, hipStream_t st);
 int muse_launch_fill(float* dst, size_t n, float v, hipStream_t st);
+int muse_launch_fill_i32(int32_t* dst, size_t n, int32_t v, hipStream_t st);

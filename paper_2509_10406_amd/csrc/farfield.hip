@@ -1,9 +1,653 @@
-// placeholder until the far-field stages land
-#include "common.h"
-size_t muse_farfield_ws_bytes(const MuseDims&, bool, int) { return 256; }
-size_t muse_farfield_fixed_bytes(const MuseDims&, bool) { return 256; }
-int muse_run_fwd(const MuseDims&, const void*, const void*, const void*, const float*, const int32_t*, const int32_t*,
-                 void*, float*, int32_t*, int32_t*, void*, size_t, hipStream_t) { return MUSE_ERR_UNSUPPORTED; }
-int muse_run_bwd(const MuseDims&, const void*, const void*, const void*, const void*, const float*, const void*,
-                 const float*, const int32_t*, const int32_t*, const int32_t*, const int32_t*, void*, void*, void*,
-                 void*, size_t, hipStream_t) { return MUSE_ERR_UNSUPPORTED; }
+// Far-field forward (Sec. 3.1-3.3, Alg. 1): tilt logits q-bar.k, per-block tilted summaries
+// (Eq. 4-6) fused with the exclusive causal accumulation, and per query tile: cluster scores
+// (Eq. 7) with top-r selection, monopole attention over the non-retrieved clusters, spatial block
+// selection, approximate attention over non-retrieved blocks, exact attention over the retrieved
+// (cluster, block) pairs.  The result is a partial softmax state (max, sum, acc) per query that the
+// block-diagonal attention kernel merges with the local part (Sec. 3.3 "Output merging").
+//
+// All summary arithmetic and every score that decides a selection is fp32 (fp32 MFMA for the
+// contractions), so the discrete choices agree with an fp64 evaluation up to fp32 rounding.
+#include "ff_common.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// bucketed copies of K and V: Xs[p] = X[perm[p]]
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) k_gather_rows(const T* __restrict__ X, const int32_t* __restrict__ perm,
+                                                      T* __restrict__ Xs, int N, int D) {
+  const int CPR = D * (int)sizeof(T) / 16;
+  size_t h = blockIdx.y;
+  size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= (size_t)N * CPR) return;
+  int p = (int)(c / CPR), cc = (int)(c % CPR);
+  int src = perm[h * N + p];
+  const uint4* s = reinterpret_cast<const uint4*>(X + (h * N + src) * D) + cc;
+  uint4* dst = reinterpret_cast<uint4*>(Xs + (h * N + p) * D) + cc;
+  *dst = *s;
+}
+
+// ------------------------------------------------------------------------------------------
+// tile schedule: tile_off[hq][b][i] = number of 32-query tiles of clusters < i in block b
+// ------------------------------------------------------------------------------------------
+__global__ void k_tile_schedule(const int32_t* __restrict__ off_q, int32_t* __restrict__ tile_off, int HQ, int nb,
+                                int Cq) {
+  int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= HQ * nb) return;
+  int hq = t / nb, b = t % nb;
+  const int32_t* o = off_q + (size_t)hq * ((size_t)nb * Cq + 1) + (size_t)b * Cq;
+  int32_t* to = tile_off + (size_t)t * (Cq + 1);
+  int run = 0;
+  for (int i = 0; i < Cq; ++i) {
+    to[i] = run;
+    run += (o[i + 1] - o[i] + 31) / 32;
+  }
+  to[Cq] = run;
+}
+
+// ------------------------------------------------------------------------------------------
+// tilt logits L[hl][i][p] = (scale * qc_i) . Ks[p]   (keys in bucketed order)
+// ------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ void __launch_bounds__(256) k_tilt_logits(const T* __restrict__ Ks, const float* __restrict__ qc,
+                                                      float* __restrict__ L, int h0, int N, int Cq, int Hq, int Hkv,
+                                                      float scale) {
+  __shared__ float qs[32][D];
+  const int hl = blockIdx.y, hq = h0 + hl;
+  const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
+  const int p = blockIdx.x * 256 + threadIdx.x;
+  const bool live = p < N;
+  float k[D];
+  {
+    const T* row = Ks + ((size_t)hk * N + (live ? p : 0)) * D;
+#pragma unroll
+    for (int d = 0; d < D; d += 4) ld4(row, d, &k[d]);
+  }
+  for (int i0 = 0; i0 < Cq; i0 += 32) {
+    __syncthreads();
+    for (int t = threadIdx.x; t < 32 * D; t += 256) {
+      int ii = t / D, d = t % D;
+      qs[ii][d] = (i0 + ii < Cq) ? scale * qc[((size_t)hq * Cq + i0 + ii) * D + d] : 0.f;
+    }
+    __syncthreads();
+    for (int ii = 0; ii < 32 && i0 + ii < Cq; ++ii) {
+      float s = 0.f;
+#pragma unroll
+      for (int d = 0; d < D; ++d) s = fmaf(qs[ii][d], k[d], s);
+      if (live) L[((size_t)hl * Cq + i0 + ii) * N + p] = s;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// per-block summaries (Eq. 4-6) + exclusive accumulation.  grid (Ck, ceil(Cq/32), hc); 4 waves share
+// the key cluster j (its keys staged in LDS), each wave owns 8 query clusters; lanes = head dim.
+// s_*[b] is the summary of key block b, A_*[b] the accumulation of blocks 0..b (what query block
+// b+1 sees), b = 0..nb-2.
+// ------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ void __launch_bounds__(256) k_summaries(const T* __restrict__ Ks, const T* __restrict__ Vs,
+                                                    const float* __restrict__ L, const int32_t* __restrict__ off_k,
+                                                    float* __restrict__ s_mu, float* __restrict__ s_k,
+                                                    float* __restrict__ s_v, float* __restrict__ A_mu,
+                                                    float* __restrict__ A_k, float* __restrict__ A_v, int h0, int N,
+                                                    int nb, int Cq, int Ck, int Hq, int Hkv) {
+  constexpr int IPW = 8, DL = D / 64;
+  constexpr int KC = 4096 / D;  // keys staged per step (LDS budget)
+  __shared__ float ks[KC][D];
+  __shared__ float vs[KC][D];
+  __shared__ float eb[4][64];
+  const int j = blockIdx.x, hl = blockIdx.z, hq = h0 + hl;
+  const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int i0 = (blockIdx.y * 4 + wave) * IPW;
+  const int NBm = nb - 1;
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+
+  float Amx[IPW], AS[IPW], Aak[IPW][DL], Aav[IPW][DL];
+#pragma unroll
+  for (int q = 0; q < IPW; ++q) {
+    Amx[q] = MUSE_NEG_INF; AS[q] = 0.f;
+#pragma unroll
+    for (int x = 0; x < DL; ++x) { Aak[q][x] = 0.f; Aav[q][x] = 0.f; }
+  }
+  for (int b = 0; b < NBm; ++b) {
+    const int lo = ok[b * Ck + j], hi = ok[b * Ck + j + 1];
+    float mx[IPW], S[IPW], ak[IPW][DL], av[IPW][DL];
+#pragma unroll
+    for (int q = 0; q < IPW; ++q) {
+      mx[q] = MUSE_NEG_INF; S[q] = 0.f;
+#pragma unroll
+      for (int x = 0; x < DL; ++x) { ak[q][x] = 0.f; av[q][x] = 0.f; }
+    }
+    for (int c0 = lo; c0 < hi; c0 += KC) {
+      const int cn = min(KC, hi - c0);
+      __syncthreads();
+      for (int t = threadIdx.x; t < cn * (D / 4); t += 256) {
+        int kk = t / (D / 4), d4 = (t % (D / 4)) * 4;
+        ld4(Ks, ((size_t)hk * N + c0 + kk) * D + d4, &ks[kk][d4]);
+        ld4(Vs, ((size_t)hk * N + c0 + kk) * D + d4, &vs[kk][d4]);
+      }
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < IPW; ++q) {
+        const int i = i0 + q;
+        if (i >= Cq) continue;
+        float lg = lane < cn ? L[((size_t)hl * Cq + i) * N + c0 + lane] : MUSE_NEG_INF;
+        float nm = fmaxf(mx[q], wave_max(lg));
+        float resc = __expf(mx[q] - nm);
+        float e = __expf(lg - nm);
+        S[q] = S[q] * resc + wave_sum(e);
+        mx[q] = nm;
+        eb[wave][lane] = e;
+#pragma unroll
+        for (int x = 0; x < DL; ++x) { ak[q][x] *= resc; av[q][x] *= resc; }
+        for (int kk = 0; kk < cn; ++kk) {
+          float ee = eb[wave][kk];
+#pragma unroll
+          for (int x = 0; x < DL; ++x) {
+            ak[q][x] = fmaf(ee, ks[kk][lane + 64 * x], ak[q][x]);
+            av[q][x] = fmaf(ee, vs[kk][lane + 64 * x], av[q][x]);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < IPW; ++q) {
+      const int i = i0 + q;
+      if (i >= Cq) continue;
+      const size_t cell = (((size_t)hl * NBm + b) * Cq + i) * Ck + j;
+      const bool empty = hi == lo;
+      float inv = empty ? 0.f : 1.f / S[q];
+      if (lane == 0) s_mu[cell] = empty ? MUSE_NEG_INF : mx[q] + __logf(S[q]);
+#pragma unroll
+      for (int x = 0; x < DL; ++x) {
+        s_k[cell * D + lane + 64 * x] = ak[q][x] * inv;
+        s_v[cell * D + lane + 64 * x] = av[q][x] * inv;
+      }
+      if (!empty) {  // running sums relative to the running max
+        float nm = fmaxf(Amx[q], mx[q]);
+        float ra = __expf(Amx[q] - nm), rb = __expf(mx[q] - nm);
+        AS[q] = AS[q] * ra + S[q] * rb;
+#pragma unroll
+        for (int x = 0; x < DL; ++x) {
+          Aak[q][x] = Aak[q][x] * ra + ak[q][x] * rb;
+          Aav[q][x] = Aav[q][x] * ra + av[q][x] * rb;
+        }
+        Amx[q] = nm;
+      }
+      const bool aempty = AS[q] == 0.f;
+      float ainv = aempty ? 0.f : 1.f / AS[q];
+      if (lane == 0) A_mu[cell] = aempty ? MUSE_NEG_INF : Amx[q] + __logf(AS[q]);
+#pragma unroll
+      for (int x = 0; x < DL; ++x) {
+        A_k[cell * D + lane + 64 * x] = Aak[q][x] * ainv;
+        A_v[cell * D + lane + 64 * x] = Aav[q][x] * ainv;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// the per-query-tile far-field kernel: one wave per tile of up to 32 queries of one
+// (spatial block b >= 1, query cluster i)
+// ------------------------------------------------------------------------------------------
+template <int D>
+__device__ __forceinline__ f32x16_t score_tile(const float* __restrict__ Amu, const float* __restrict__ Ak, int j0,
+                                               int Ck, const float (&qt)[D / 8][4], int col, int half) {
+  f32x16_t acc;
+#pragma unroll
+  for (int g = 0; g < 4; ++g)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      int jr = j0 + 8 * g + 4 * half + t;
+      acc[4 * g + t] = jr < Ck ? Amu[jr] : MUSE_NEG_INF;
+    }
+  int c = j0 + col;
+  c = c < Ck ? c : Ck - 1;
+  const float* row = Ak + (size_t)c * D + 4 * half;
+#pragma unroll
+  for (int u = 0; u < D / 8; ++u) {
+    float4 a = *reinterpret_cast<const float4*>(row + 8 * u);
+    acc = mfma32(a.x, qt[u][0], acc);
+    acc = mfma32(a.y, qt[u][1], acc);
+    acc = mfma32(a.z, qt[u][2], acc);
+    acc = mfma32(a.w, qt[u][3], acc);
+  }
+  return acc;
+}
+
+template <typename T, int D, int RCAP>
+__global__ void __launch_bounds__(64) k_farfield_fwd(
+    const T* __restrict__ Q, const float* __restrict__ qc, const T* __restrict__ Ks, const T* __restrict__ Vs,
+    const float* __restrict__ L, const float* __restrict__ s_mu, const float* __restrict__ s_k,
+    const float* __restrict__ s_v, const float* __restrict__ A_mu, const float* __restrict__ A_k,
+    const float* __restrict__ A_v, const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q,
+    const int32_t* __restrict__ off_k, const int32_t* __restrict__ tile_off, float* __restrict__ ff_acc,
+    float* __restrict__ ff_ml, int32_t* __restrict__ selc, int32_t* __restrict__ selb, int h0, int N, int nb, int Cq,
+    int Ck, int r, int k2e, int Hq, int Hkv, float scale) {
+  constexpr int U = D / 8, DT = D / 32;
+  __shared__ float cs[64][RCAP];
+  __shared__ int ci[64][RCAP];
+  __shared__ int sel_s[32][RCAP];
+  const int hl = blockIdx.z, hq = h0 + hl;
+  const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
+  const int b = blockIdx.y + 1, NBm = nb - 1;
+  const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
+
+  const int32_t* to = tile_off + ((size_t)hq * nb + b) * (Cq + 1);
+  const int tile = blockIdx.x;
+  if (tile >= to[Cq]) return;
+  int lo_ = 0, hi_ = Cq;
+  while (hi_ - lo_ > 1) {
+    int mid = (lo_ + hi_) >> 1;
+    if (to[mid] <= tile) lo_ = mid; else hi_ = mid;
+  }
+  const int i = lo_, tt = tile - to[lo_];
+  const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
+  int pos = qlo + 32 * tt + col;
+  const bool valid = pos < qhi;
+  pos = valid ? pos : qlo + 32 * tt;
+  const int n = perm_q[(size_t)hq * N + pos];
+
+  float qt[U][4];
+  {
+    const T* qrow = Q + ((size_t)hq * N + n) * D;
+    const float* qci = qc + ((size_t)hq * Cq + i) * D;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float x[4];
+      ld4(qrow, 8 * u + 4 * half, x);
+      float4 c = *reinterpret_cast<const float4*>(qci + 8 * u + 4 * half);
+      qt[u][0] = scale * (x[0] - c.x); qt[u][1] = scale * (x[1] - c.y);
+      qt[u][2] = scale * (x[2] - c.z); qt[u][3] = scale * (x[3] - c.w);
+    }
+  }
+  const size_t acell = (((size_t)hl * NBm + (b - 1)) * Cq + i) * Ck;
+  const float* Amu = A_mu + acell;
+  const float* Ak = A_k + acell * D;
+  const float* Av = A_v + acell * D;
+  const int ntile = (Ck + 31) / 32;
+
+  // ---- pass 1: the r largest scores seen by this lane half (values only) ----
+  float list[RCAP];
+#pragma unroll
+  for (int k = 0; k < RCAP; ++k) list[k] = MUSE_NEG_INF;
+  for (int jt = 0; jt < ntile; ++jt) {
+    f32x16_t acc = score_tile<D>(Amu, Ak, jt * 32, Ck, qt, col, half);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float x = acc[e];
+#pragma unroll
+      for (int k = 0; k < RCAP; ++k) {
+        float hi = fmaxf(list[k], x);
+        x = fminf(list[k], x);
+        list[k] = hi;
+      }
+    }
+  }
+  // ---- split the quota of r between the two halves of the query (ties: lower half first) ----
+  int quota = 0;
+  {
+    float other[RCAP];
+#pragma unroll
+    for (int k = 0; k < RCAP; ++k) other[k] = __shfl_xor(list[k], 32, 64);
+#pragma unroll
+    for (int k = 0; k < RCAP; ++k) {
+      int ahead = 0;
+#pragma unroll
+      for (int y = 0; y < RCAP; ++y) ahead += half == 0 ? (other[y] > list[k]) : (other[y] >= list[k]);
+      quota += (k + ahead < r) && (list[k] > MUSE_NEG_INF);
+    }
+  }
+  float thr = __builtin_huge_valf();
+#pragma unroll
+  for (int k = 0; k < RCAP; ++k)
+    if (k == quota - 1) thr = list[k];
+  int cgt = 0;
+#pragma unroll
+  for (int k = 0; k < RCAP; ++k) cgt += (k < quota) && (list[k] > thr);
+  const int eqquota = quota - cgt;
+
+  // ---- pass 2: same scores again; selected ones are recorded and masked, the rest is the
+  //      monopole attention over accumulated value summaries (component 1) ----
+  float m = MUSE_NEG_INF, l = 0.f;
+  f32x16_t o[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t) o[t] = zero16();
+  int eqc = 0, ncand = 0;
+  for (int jt = 0; jt < ntile; ++jt) {
+    const int j0 = jt * 32;
+    f32x16_t acc = score_tile<D>(Amu, Ak, j0, Ck, qt, col, half);
+    float tmax = MUSE_NEG_INF;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float s = acc[e];
+      bool eq = (s == thr) && (eqc < eqquota);
+      bool take = (s > thr) || eq;
+      eqc += eq;
+      if (take) {
+        cs[lane][ncand] = s;
+        ci[lane][ncand] = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+        ++ncand;
+        acc[e] = MUSE_NEG_INF;
+      }
+      tmax = fmaxf(tmax, acc[e]);
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    float mn = fmaxf(m, tmax);
+    float mref = mn == MUSE_NEG_INF ? 0.f : mn;
+    float alpha = __expf(m - mref);
+    float psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float p = __expf(acc[e] - mref);
+      acc[e] = p;
+      psum += p;
+    }
+    l = l * alpha + psum;
+    m = mn;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        int jr = j0 + 8 * g + 4 * half + t;
+        jr = jr < Ck ? jr : Ck - 1;
+        const float* vrow = Av + (size_t)jr * D + col;
+#pragma unroll
+        for (int x = 0; x < DT; ++x) o[x] = mfma32(vrow[32 * x], acc[4 * g + t], o[x]);
+      }
+  }
+  // ---- order the selected clusters of each query by (score desc, index asc) ----
+  for (int k = lane; k < 32 * RCAP; k += 64) (&sel_s[0][0])[k] = -1;
+  __syncthreads();
+  {
+    const int nother = __shfl_xor(ncand, 32, 64);
+    const int total = ncand + nother;
+    for (int k = 0; k < ncand; ++k) {
+      float sv = cs[lane][k];
+      int iv = ci[lane][k];
+      int rank = 0;
+      for (int y = 0; y < ncand; ++y) rank += (cs[lane][y] > sv) || (cs[lane][y] == sv && ci[lane][y] < iv);
+      for (int y = 0; y < nother; ++y)
+        rank += (cs[lane ^ 32][y] > sv) || (cs[lane ^ 32][y] == sv && ci[lane ^ 32][y] < iv);
+      sel_s[col][rank] = iv;
+    }
+    __syncthreads();
+    if (valid && half == 0) {
+      int32_t* out = selc + ((size_t)hq * N + n) * r;
+      for (int k = 0; k < r; ++k) out[k] = k < total ? sel_s[col][k] : -1;
+    }
+  }
+  // ---- per selected cluster: block selection on the per-block summaries, components 2 and 3 ----
+  for (int t = 0; t < r; ++t) {
+    const int j = sel_s[col][t];
+    if (j < 0) continue;
+    float sc2[15];
+#pragma unroll
+    for (int bp = 0; bp < 15; ++bp) {
+      sc2[bp] = MUSE_NEG_INF;
+      if (bp < b) {
+        const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
+        const float mu = s_mu[cell];
+        if (mu > MUSE_NEG_INF) {
+          const float* kr = s_k + cell * D + 4 * half;
+          float part = 0.f;
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            float4 k4 = *reinterpret_cast<const float4*>(kr + 8 * u);
+            part = fmaf(qt[u][0], k4.x, part); part = fmaf(qt[u][1], k4.y, part);
+            part = fmaf(qt[u][2], k4.z, part); part = fmaf(qt[u][3], k4.w, part);
+          }
+          part += __shfl_xor(part, 32, 64);
+          sc2[bp] = part + mu;
+        }
+      }
+    }
+    unsigned selbits = 0;
+    for (int u = 0; u < k2e; ++u) {
+      float best = MUSE_NEG_INF;
+      int bi = -1;
+#pragma unroll
+      for (int bp = 0; bp < 15; ++bp)
+        if (!((selbits >> bp) & 1u) && sc2[bp] > best) { best = sc2[bp]; bi = bp; }
+      if (bi >= 0) selbits |= 1u << bi;
+      if (valid && half == 0) selb[(((size_t)hq * N + n) * r + t) * k2e + u] = bi;
+    }
+#pragma unroll
+    for (int bp = 0; bp < 15; ++bp) {
+      if (!(sc2[bp] > MUSE_NEG_INF)) continue;
+      if (!((selbits >> bp) & 1u)) {  // component 2: summary of a non-retrieved block
+        const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
+        const float* vr = s_v + cell * D + 4 * half;
+        float mn = fmaxf(m, sc2[bp]);
+        float a = __expf(m - mn), p = __expf(sc2[bp] - mn);
+        l = l * a + (half == 0 ? p : 0.f);
+        m = mn;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          float4 v4 = *reinterpret_cast<const float4*>(vr + 8 * u);
+          o[u / 4][4 * (u % 4) + 0] = o[u / 4][4 * (u % 4) + 0] * a + p * v4.x;
+          o[u / 4][4 * (u % 4) + 1] = o[u / 4][4 * (u % 4) + 1] * a + p * v4.y;
+          o[u / 4][4 * (u % 4) + 2] = o[u / 4][4 * (u % 4) + 2] * a + p * v4.z;
+          o[u / 4][4 * (u % 4) + 3] = o[u / 4][4 * (u % 4) + 3] * a + p * v4.w;
+        }
+      } else {  // component 3: exact attention over the keys of the retrieved (cluster, block)
+        const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
+        for (int p_ = klo; p_ < khi; ++p_) {
+          const size_t krow = ((size_t)hk * N + p_) * D + 4 * half;
+          float part = 0.f;
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            float k4[4];
+            ld4(Ks, krow + 8 * u, k4);
+            part = fmaf(qt[u][0], k4[0], part); part = fmaf(qt[u][1], k4[1], part);
+            part = fmaf(qt[u][2], k4[2], part); part = fmaf(qt[u][3], k4[3], part);
+          }
+          part += __shfl_xor(part, 32, 64);
+          const float lg = part + L[((size_t)hl * Cq + i) * N + p_];  // q.k = q~.k + q-bar.k
+          float mn = fmaxf(m, lg);
+          float a = __expf(m - mn), p = __expf(lg - mn);
+          l = l * a + (half == 0 ? p : 0.f);
+          m = mn;
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            float v4[4];
+            ld4(Vs, krow + 8 * u, v4);
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+              o[u / 4][4 * (u % 4) + x] = o[u / 4][4 * (u % 4) + x] * a + p * v4[x];
+          }
+        }
+      }
+    }
+  }
+  l += __shfl_xor(l, 32, 64);
+  if (!valid) return;
+  float* fa = ff_acc + ((size_t)hq * N + n) * D + 4 * half;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    *reinterpret_cast<float4*>(fa + 8 * u) = make_float4(o[u / 4][4 * (u % 4)], o[u / 4][4 * (u % 4) + 1],
+                                                         o[u / 4][4 * (u % 4) + 2], o[u / 4][4 * (u % 4) + 3]);
+  }
+  if (half == 0) {
+    ff_ml[((size_t)hq * N + n) * 2] = m;
+    ff_ml[((size_t)hq * N + n) * 2 + 1] = l;
+  }
+}
+
+template <typename T>
+int run_fwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const float* qc, const int32_t* aq,
+                  const int32_t* ak, void* O, float* LSE, int32_t* selc, int32_t* selb, FFWorkspace& w,
+                  hipStream_t st);
+
+}  // namespace
+
+// carve the workspace; returns the number of heads per chunk (0 if too small)
+int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWorkspace* w, void* dQ, void* dK,
+                  void* dV) {
+  size_t HQ = (size_t)d.B * d.Hq, HK = (size_t)d.B * d.Hkv, N = d.N, D = d.D;
+  size_t es = d.dtype == MUSE_DTYPE_BF16 ? 2 : 4;
+  size_t fixed = ff_fixed_bytes(d, bwd), per = ff_head_bytes(d, bwd);
+  int G = d.Hq / d.Hkv;
+  if (ws_bytes < fixed + per * G) return 0;
+  size_t hc = (ws_bytes - fixed) / per;
+  hc = hc > HQ ? HQ : hc;
+  hc -= hc % G;
+  char* p = (char*)ws;
+  auto take = [&](size_t bytes) { char* r = p; p += ff_al(bytes); return r; };
+  w->perm_k = (int32_t*)take(HK * N * 4);
+  w->off_k = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
+  w->perm_q = (int32_t*)take(HQ * N * 4);
+  w->off_q = (int32_t*)take(HQ * ((size_t)d.nb * d.Cq + 1) * 4);
+  w->tile_off = (int32_t*)take(HQ * d.nb * ((size_t)d.Cq + 1) * 4);
+  w->Ks = take(HK * N * D * es);
+  w->Vs = take(HK * N * D * es);
+  w->ff_acc = (float*)take(HQ * N * (D + 2) * 4);
+  w->ff_ml = w->ff_acc + HQ * N * D;
+  if (bwd) {
+    size_t W = (d.Ck + 31) / 32;
+    w->delta = (float*)take(HQ * N * 4);
+    w->selmask = (uint32_t*)take(HQ * N * W * 4);
+    w->dKs = (float*)take(HK * N * D * 4);
+    w->dVs = (float*)take(HK * N * D * 4);
+    if (d.grad_dtype != MUSE_DTYPE_FP32) {
+      w->dQacc = (float*)take(HQ * N * D * 4);
+      w->dKacc = (float*)take(HK * N * D * 4);
+      w->dVacc = (float*)take(HK * N * D * 4);
+    } else {
+      w->dQacc = (float*)dQ; w->dKacc = (float*)dK; w->dVacc = (float*)dV;
+    }
+  }
+  size_t cells = (size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * d.Ck;
+  w->L = (float*)take(hc * d.Cq * N * 4);
+  w->s_mu = (float*)take(hc * cells * 4);
+  w->A_mu = (float*)take(hc * cells * 4);
+  w->s_k = (float*)take(hc * cells * D * 4);
+  w->s_v = (float*)take(hc * cells * D * 4);
+  w->A_k = (float*)take(hc * cells * D * 4);
+  w->A_v = (float*)take(hc * cells * D * 4);
+  if (bwd) {
+    w->g_s_c = (float*)take(hc * cells * 4);
+    w->g_A_c = (float*)take(hc * cells * 4);
+    w->g_s_k = (float*)take(hc * cells * D * 4);
+    w->g_s_v = (float*)take(hc * cells * D * 4);
+    w->g_A_k = (float*)take(hc * cells * D * 4);
+    w->g_A_v = (float*)take(hc * cells * D * 4);
+  }
+  w->hc = (int)hc;
+  return (int)hc;
+}
+
+// stages shared by forward and backward: bucketing, bucketed copies, tile schedule
+template <typename T>
+int muse_ff_prepare(const MuseDims& d, const T* K, const T* V, const int32_t* aq, const int32_t* ak, FFWorkspace& w,
+                    hipStream_t st) {
+  const int HQ = d.B * d.Hq, HK = d.B * d.Hkv, N = d.N, D = d.D;
+  int rc;
+  if ((rc = muse_launch_bucket(ak, HK, N, d.Bs, d.Ck, w.perm_k, w.off_k, st))) return rc;
+  if ((rc = muse_launch_bucket(aq, HQ, N, d.Bs, d.Cq, w.perm_q, w.off_q, st))) return rc;
+  const int CPR = D * (int)sizeof(T) / 16;
+  dim3 g((unsigned)(((size_t)N * CPR + 255) / 256), HK);
+  hipLaunchKernelGGL(k_gather_rows<T>, g, dim3(256), 0, st, K, w.perm_k, (T*)w.Ks, N, D);
+  hipLaunchKernelGGL(k_gather_rows<T>, g, dim3(256), 0, st, V, w.perm_k, (T*)w.Vs, N, D);
+  hipLaunchKernelGGL(k_tile_schedule, dim3((HQ * d.nb + 63) / 64), dim3(64), 0, st, w.off_q, w.tile_off, HQ, d.nb, d.Cq);
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
+
+// summaries of the query heads [h0, h0+hn)
+template <typename T>
+int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0, int hn, hipStream_t st) {
+  const int N = d.N;
+  dim3 gl((N + 255) / 256, hn);
+  dim3 gs(d.Ck, (d.Cq + 31) / 32, hn);
+  if (d.D == 64) {
+    hipLaunchKernelGGL((k_tilt_logits<T, 64>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale);
+    hipLaunchKernelGGL((k_summaries<T, 64>), gs, dim3(256), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
+                       w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv);
+  } else {
+    hipLaunchKernelGGL((k_tilt_logits<T, 128>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale);
+    hipLaunchKernelGGL((k_summaries<T, 128>), gs, dim3(256), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
+                       w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv);
+  }
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
+
+template int muse_ff_prepare<float>(const MuseDims&, const float*, const float*, const int32_t*, const int32_t*, FFWorkspace&, hipStream_t);
+template int muse_ff_prepare<bf16_t>(const MuseDims&, const bf16_t*, const bf16_t*, const int32_t*, const int32_t*, FFWorkspace&, hipStream_t);
+template int muse_ff_summaries<float>(const MuseDims&, const float*, FFWorkspace&, int, int, hipStream_t);
+template int muse_ff_summaries<bf16_t>(const MuseDims&, const float*, FFWorkspace&, int, int, hipStream_t);
+
+namespace {
+
+template <typename T, int D, int RCAP>
+void launch_ff_fwd(const MuseDims& d, const T* Q, const float* qc, FFWorkspace& w, int32_t* selc, int32_t* selb, int h0,
+                   int hn, hipStream_t st) {
+  dim3 g(d.Bs / 32 + d.Cq + 1, d.nb - 1, hn);
+  hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, (const T*)w.Ks, (const T*)w.Vs, w.L,
+                     w.s_mu, w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q, w.off_k, w.tile_off, w.ff_acc,
+                     w.ff_ml, selc, selb, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale);
+}
+
+template <typename T, int D>
+void launch_ff_fwd_r(const MuseDims& d, const T* Q, const float* qc, FFWorkspace& w, int32_t* selc, int32_t* selb,
+                     int h0, int hn, hipStream_t st) {
+  if (d.r <= 8) launch_ff_fwd<T, D, 8>(d, Q, qc, w, selc, selb, h0, hn, st);
+  else if (d.r <= 16) launch_ff_fwd<T, D, 16>(d, Q, qc, w, selc, selb, h0, hn, st);
+  else launch_ff_fwd<T, D, 32>(d, Q, qc, w, selc, selb, h0, hn, st);
+}
+
+template <typename T>
+int run_fwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const float* qc, const int32_t* aq,
+                  const int32_t* ak, void* O, float* LSE, int32_t* selc, int32_t* selb, FFWorkspace& w,
+                  hipStream_t st) {
+  const int HQ = d.B * d.Hq;
+  int rc;
+  if ((rc = muse_ff_prepare<T>(d, K, V, aq, ak, w, st))) return rc;
+  if ((rc = muse_launch_fill(w.ff_ml, (size_t)HQ * d.N * 2, 0.f, st))) return rc;
+  if (d.nb > 1) {
+    for (int h0 = 0; h0 < HQ; h0 += w.hc) {
+      int hn = HQ - h0 < w.hc ? HQ - h0 : w.hc;
+      if ((rc = muse_ff_summaries<T>(d, qc, w, h0, hn, st))) return rc;
+      if (d.D == 64) launch_ff_fwd_r<T, 64>(d, Q, qc, w, selc, selb, h0, hn, st);
+      else launch_ff_fwd_r<T, 128>(d, Q, qc, w, selc, selb, h0, hn, st);
+      MUSE_LAUNCH_CHECK();
+    }
+  }
+  return muse_launch_attn_fwd(d, d.Bs, Q, K, V, w.ff_acc, O, LSE, st);
+}
+
+}  // namespace
+
+size_t muse_farfield_fixed_bytes(const MuseDims& d, bool bwd) { return ff_fixed_bytes(d, bwd); }
+size_t muse_farfield_ws_bytes(const MuseDims& d, bool bwd, int heads) {
+  int G = d.Hq / d.Hkv;
+  int h = heads < G ? G : heads;
+  return ff_head_bytes(d, bwd) * (size_t)h;
+}
+
+int muse_run_fwd(const MuseDims& d, const void* Q, const void* K, const void* V, const float* qc, const int32_t* aq,
+                 const int32_t* ak, void* O, float* LSE, int32_t* selc, int32_t* selb, void* ws, size_t ws_bytes,
+                 hipStream_t st) {
+  FFWorkspace w;
+  if (!muse_ff_carve(d, false, ws, ws_bytes, &w, nullptr, nullptr, nullptr)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  // block-0 queries and r = 0 leave the selection outputs untouched by the tile kernel: pad them
+  if (d.r > 0) {
+    size_t nq = (size_t)d.B * d.Hq * d.N;
+    int rc;
+    if ((rc = muse_launch_fill_i32(selc, nq * d.r, -1, st))) return rc;
+    if ((rc = muse_launch_fill_i32(selb, nq * d.r * d.k2e, -1, st))) return rc;
+  }
+  if (d.dtype == MUSE_DTYPE_FP32)
+    return run_fwd_typed<float>(d, (const float*)Q, (const float*)K, (const float*)V, qc, aq, ak, O, LSE, selc, selb, w, st);
+  return run_fwd_typed<bf16_t>(d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, qc, aq, ak, O, LSE, selc, selb, w, st);
+}

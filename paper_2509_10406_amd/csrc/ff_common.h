@@ -1,0 +1,65 @@
+// Far-field stages (Sec. 3.1-3.3): workspace layout and fp32-MFMA helpers shared by the forward and
+// backward translation units.
+//
+// fp32 MFMA (v_mfma_f32_32x32x2_f32) conventions used throughout:
+//   - accumulator element e = 4g+t of lane l is row 8g + 4(l/32) + t, column l%32;
+//   - an operand lane supplies one value per instruction: its k-slot is l/32.
+//   "Row pattern": operand X[row = l%32][c], contraction over the contiguous index c.  A lane loads
+//   float4 groups X[row][8u + 4(l/32) .. +3]; instruction (u,t) uses element t, i.e. half h
+//   contributes c = 8u + 4h + t.  Two row-pattern operands pair up consistently.
+//   "Column pattern": A[m][k] = X[k][m] read as X[k0 + 8g + 4(l/32) + t][m0 + l%32] (coalesced over
+//   lanes), pairing with a B operand taken straight from an accumulator (its rows are 8g+4h+t).
+#pragma once
+#include "common.h"
+
+__device__ __forceinline__ f32x16_t mfma32(float a, float b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x16_t zero16() {
+  f32x16_t z;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) z[e] = 0.f;
+  return z;
+}
+
+struct FFWorkspace {
+  // all heads
+  int32_t *perm_k, *off_k, *perm_q, *off_q, *tile_off;
+  void *Ks, *Vs;      // keys / values in bucketed order, input dtype
+  float *ff_acc, *ff_ml;  // contiguous: [HQ,N,D] then [HQ,N,2]
+  // backward only, all heads
+  float* delta;
+  uint32_t* selmask;
+  float *dKs, *dVs;            // fp32 gradients in bucketed key order
+  float *dQacc, *dKacc, *dVacc;  // fp32 gradients in sequence order (alias the outputs when they are fp32)
+  // per chunk of `hc` query heads
+  float* L;
+  float *s_mu, *s_k, *s_v, *A_mu, *A_k, *A_v;
+  float *g_s_c, *g_s_k, *g_s_v, *g_A_c, *g_A_k, *g_A_v;
+  int hc;
+};
+
+static inline size_t ff_al(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// bytes of the all-heads part / of one query head of the chunked part
+static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
+  size_t HQ = (size_t)d.B * d.Hq, HK = (size_t)d.B * d.Hkv, N = d.N, D = d.D;
+  size_t es = d.dtype == MUSE_DTYPE_BF16 ? 2 : 4;
+  size_t b = ff_al(HK * N * 4) + ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) + ff_al(HQ * N * 4) +
+             ff_al(HQ * ((size_t)d.nb * d.Cq + 1) * 4) + ff_al(HQ * d.nb * ((size_t)d.Cq + 1) * 4) +
+             2 * ff_al(HK * N * D * es) + ff_al(HQ * N * (D + 2) * 4);
+  if (bwd) {
+    size_t W = (d.Ck + 31) / 32;
+    b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + 2 * ff_al(HK * N * D * 4);
+    if (d.grad_dtype != MUSE_DTYPE_FP32) b += ff_al(HQ * N * D * 4) + 2 * ff_al(HK * N * D * 4);
+  }
+  return b;
+}
+
+static inline size_t ff_head_bytes(const MuseDims& d, bool bwd) {
+  size_t cells = (size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * d.Ck, D = d.D;
+  size_t b = ff_al((size_t)d.Cq * d.N * 4) + 2 * ff_al(cells * 4) + 4 * ff_al(cells * D * 4);
+  if (bwd) b += 2 * ff_al(cells * 4) + 4 * ff_al(cells * D * 4);
+  return b;
+}

@@ -1,0 +1,151 @@
+"""GPU parity of muse_fwd / muse_bwd against the CPU oracle, through the C ABI.
+
+The clustering handed to both sides is the oracle's (teacher forcing: one near-tie flip upstream
+must not invalidate every downstream comparison).  Selections are compared as sets wherever the
+oracle's relative score margin exceeds 1e-5; outputs and gradients are then compared against the
+oracle evaluated at the GPU's own selections (identical to the oracle's except at sub-margin ties).
+"""
+import dataclasses
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from paper_2509_10406_amd import binding as mb
+from paper_2509_10406_amd.inputs import generate, small
+from tests.util import assert_close, dev, f64
+
+pytestmark = pytest.mark.gpu
+MARGIN = 1e-5
+
+CASES = {
+    "cfg1_full": ("cfg1", {}),
+    "cfg1_k2all": ("cfg1", dict(N=1024, k2=0, block=128, kmeans_iters=3)),
+    "cfg1_r0": ("cfg1", dict(N=512, r=0, block=64, kmeans_iters=2)),
+    "cfg1_k2_2_ragged": ("cfg1", dict(N=768, Cq=5, Ck=19, r=3, k2=2, block=96, kmeans_iters=2)),
+    "cfg2_small": ("cfg2", dict(N=2048, Hq=2, Hkv=2, Cq=16, Ck=64, r=4, block=256, kmeans_iters=3)),
+    "cfg4_gqa": ("cfg4", dict(N=1024, Hq=4, Hkv=2, Cq=8, Ck=40, r=3, block=128, kmeans_iters=2)),
+    "cfg5_d128": ("cfg5", dict(N=1024, Hq=2, Hkv=1, Cq=8, Ck=33, r=9, block=128, kmeans_iters=2)),
+    "bf16_one_block": ("cfg2", dict(N=512, Hq=1, Hkv=1, Cq=4, Ck=8, r=2, block=512, kmeans_iters=1)),
+    "bf16_r17": ("cfg2", dict(N=1024, Hq=1, Hkv=1, Cq=4, Ck=70, r=17, block=128, kmeans_iters=1)),
+}
+
+
+def oracle_clustering(w, d, p):
+    rm = 1 if w.dtype == "bf16" else 0
+    G = w.Hq // w.Hkv
+    qc = np.zeros((w.B, w.Hq, w.Cq, w.D), np.float32)
+    aq = np.zeros((w.B, w.Hq, w.N), np.int32)
+    ak = np.zeros((w.B, w.Hkv, w.N), np.int32)
+    for h in range(w.Hq):
+        o = orc.kmeans(d["Q"][0, h].double().numpy(), w.Cq, w.kmeans_iters, init_idx=d["q_init_idx"][0, h].numpy(), round_mode=rm)
+        qc[0, h], aq[0, h] = o["cent"], o["assign"]
+    for h in range(w.Hkv):
+        o = orc.kmeans(d["K"][0, h].double().numpy(), w.Ck, w.kmeans_iters, init_idx=d["k_init_idx"][0, h].numpy(), round_mode=rm)
+        ak[0, h] = o["assign"]
+    return qc, aq, ak
+
+
+def as_sets(sel):
+    s = np.sort(sel.reshape(sel.shape[0], -1), axis=1)
+    return s
+
+
+def run_case(name, with_bwd):
+    base, kw = CASES[name]
+    w = small(base, **kw)
+    d = generate(w, need_dO=True)
+    p = mb.params_for(w)
+    qc, aq, ak = oracle_clustering(w, d, p)
+    Q, K, V, dO = (dev(d[x], p) for x in ("Q", "K", "V", "dO"))
+    qc_d, aq_d, ak_d = torch.tensor(qc).cuda(), torch.tensor(aq).cuda(), torch.tensor(ak).cuda()
+    O, LSE, selc, selb = mb.muse_fwd(p, Q, K, V, qc_d, aq_d, ak_d)
+    if with_bwd:
+        dQ, dK, dV = mb.muse_bwd(p, Q, K, V, O, LSE, dO, qc_d, aq_d, ak_d, selc, selb)
+    torch.cuda.synchronize()
+    op = orc.MuseParams(w.N, w.D, w.Bs, w.Cq, w.Ck, w.r, w.k2, p.eff_scale)
+    G = w.Hq // w.Hkv
+    selc_h, selb_h = selc.cpu().numpy()[0], selb.cpu().numpy()[0]
+
+    def head(h):
+        q, k, v, g = (f64(x) for x in (Q[0, h], K[0, h // G], V[0, h // G], dO[0, h]))
+        free = orc.muse_fwd(op, q, k, v, qc[0, h], aq[0, h], ak[0, h // G])
+        sc = selc_h[h][:, : w.r]
+        sb = selb_h[h][:, : w.r].reshape(w.N, w.r, op.k2e) if w.r else selb_h[h][:, :0].reshape(w.N, 0, op.k2e)
+        forced = orc.muse_fwd(op, q, k, v, qc[0, h], aq[0, h], ak[0, h // G], sel=(sc, sb))
+        grads = None
+        if with_bwd:
+            grads = orc.muse_bwd(op, q, k, v, qc[0, h], aq[0, h], ak[0, h // G], forced["O"], forced["LSE"], g, sc, sb)
+        return free, forced, grads
+
+    with ThreadPoolExecutor(8) as ex:
+        res = list(ex.map(head, range(w.Hq)))
+    wantK = np.zeros((w.Hkv, w.N, w.D)); wantV = np.zeros((w.Hkv, w.N, w.D))
+    for h, (free, forced, grads) in enumerate(res):
+        if w.r:
+            safe_c = free["margin_c"] > MARGIN
+            assert safe_c.mean() > 0.98, safe_c.mean()
+            got_c = as_sets(selc_h[h][:, : w.r]); want_c = as_sets(free["selc"])
+            np.testing.assert_array_equal(got_c[safe_c], want_c[safe_c], err_msg=f"{name} head {h}: retrieved clusters")
+            # descending-score export order, and the blocks of every slot, where both margins are safe
+            safe = safe_c & (free["margin_b"] > MARGIN)
+            same_order = (selc_h[h][:, : w.r] == free["selc"]).all(1)
+            chk = safe & same_order
+            got_b = selb_h[h][:, : w.r].reshape(w.N, w.r, op.k2e)
+            np.testing.assert_array_equal(np.sort(got_b[chk], -1), np.sort(free["selb"][chk], -1),
+                                          err_msg=f"{name} head {h}: retrieved blocks")
+        assert_close(f64(O[0, h]), forced["O"], p, f"{name} O head {h}")
+        lse_tol = 1e-4 if w.dtype == "fp32" else 2e-2
+        np.testing.assert_allclose(LSE[0, h].cpu().numpy(), forced["LSE"], rtol=0, atol=lse_tol * max(1, np.abs(forced["LSE"]).max()))
+        if with_bwd:
+            assert_close(f64(dQ[0, h]), grads[0], p, f"{name} dQ head {h}", grad=True)
+            wantK[h // G] += grads[1]; wantV[h // G] += grads[2]
+    if with_bwd:
+        for hk in range(w.Hkv):
+            assert_close(f64(dK[0, hk]), wantK[hk], p, f"{name} dK head {hk}", grad=True)
+            assert_close(f64(dV[0, hk]), wantV[hk], p, f"{name} dV head {hk}", grad=True)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_muse_forward(name):
+    run_case(name, with_bwd=False)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_muse_backward(name):
+    run_case(name, with_bwd=True)
+
+
+def test_forward_with_small_workspace_chunks_heads():
+    """The minimum workspace processes one KV group at a time; results must not change."""
+    base, kw = CASES["cfg4_gqa"]
+    w = small(base, **kw)
+    d = generate(w)
+    p = mb.params_for(w)
+    qc, aq, ak = oracle_clustering(w, d, p)
+    Q, K, V = (dev(d[x], p) for x in ("Q", "K", "V"))
+    args = (p, Q, K, V, torch.tensor(qc).cuda(), torch.tensor(aq).cuda(), torch.tensor(ak).cuda())
+    mn, pref = mb.muse_workspace_bytes(p, mb.WS_FWD)
+    assert mn < pref
+    a = mb.muse_fwd(*args, ws=torch.empty(pref, dtype=torch.uint8, device="cuda"))
+    b = mb.muse_fwd(*args, ws=torch.empty(mn, dtype=torch.uint8, device="cuda"))
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    with pytest.raises(mb.MuseError, match="workspace"):
+        mb.muse_fwd(*args, ws=torch.empty(mn - 256, dtype=torch.uint8, device="cuda"))
+
+
+def test_gpu_own_clustering_reports_rse(oracle):
+    """End to end on the GPU's own clustering (cfg1): approximation error against exact attention."""
+    w = small("cfg1")
+    d = generate(w)
+    p = mb.params_for(w)
+    Q, K, V = (dev(d[x], p) for x in ("Q", "K", "V"))
+    qc, aq, kc, ka = mb.muse_cluster(p, Q, K, d["q_init_idx"].cuda(), d["k_init_idx"].cuda())
+    O, LSE, _, _ = mb.muse_fwd(p, Q, K, V, qc, aq, ka)
+    Oe, _ = mb.exact_attn_fwd(p, Q, K, V)
+    rse = (((O - Oe) ** 2).sum(-1) / (Oe ** 2).sum(-1)).mean().item()
+    print(f"cfg1 RSE vs exact = {rse:.3e}")
+    assert rse < 0.05
