@@ -193,31 +193,6 @@ __global__ void __launch_bounds__(256) k_summaries(const T* __restrict__ Ks, con
 // the per-query-tile far-field kernel: one wave per tile of up to 32 queries of one
 // (spatial block b >= 1, query cluster i)
 // ------------------------------------------------------------------------------------------
-template <int D>
-__device__ __forceinline__ f32x16_t score_tile(const float* __restrict__ Amu, const float* __restrict__ Ak, int j0,
-                                               int Ck, const float (&qt)[D / 8][4], int col, int half) {
-  f32x16_t acc;
-#pragma unroll
-  for (int g = 0; g < 4; ++g)
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      int jr = j0 + 8 * g + 4 * half + t;
-      acc[4 * g + t] = jr < Ck ? Amu[jr] : MUSE_NEG_INF;
-    }
-  int c = j0 + col;
-  c = c < Ck ? c : Ck - 1;
-  const float* row = Ak + (size_t)c * D + 4 * half;
-#pragma unroll
-  for (int u = 0; u < D / 8; ++u) {
-    float4 a = *reinterpret_cast<const float4*>(row + 8 * u);
-    acc = mfma32(a.x, qt[u][0], acc);
-    acc = mfma32(a.y, qt[u][1], acc);
-    acc = mfma32(a.z, qt[u][2], acc);
-    acc = mfma32(a.w, qt[u][3], acc);
-  }
-  return acc;
-}
-
 template <typename T, int D, int RCAP>
 __global__ void __launch_bounds__(64) k_farfield_fwd(
     const T* __restrict__ Q, const float* __restrict__ qc, const T* __restrict__ Ks, const T* __restrict__ Vs,

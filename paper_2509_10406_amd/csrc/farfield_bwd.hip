@@ -1,5 +1,816 @@
-// placeholder until the far-field backward lands
+// Far-field backward: gradient of the forward of Sec. 3.1-3.3 with the assignments, the selections
+// and the query centroids held fixed (App. C "Centroid Gradient Flow"); gradient flows into K and
+// V through the tilted aggregation weights (App. C "Aggregation Weight Gradient Flow", default).
+//
+// With p_u = exp(logit_u - LSE), delta = dO.O, dl_u = p_u (dO.value_u - delta) per virtual key:
+//   summary keys (component 1 on accumulated cells, component 2 on per-block cells):
+//     dq~ += dl kappa,  g_k[cell] += dl q~,  g_v[cell] += p dO,  g_mu[cell] += dl
+//   a cell in unnormalised form (S = e^mu, Ksum = S kappa, Vsum = S vbar) receives
+//     dKsum = g_k/S, dVsum = g_v/S, dS = c/S with c = g_mu - g_k.kappa - g_v.vbar,
+//   accumulated cells are plain sums of per-block (S, Ksum, Vsum), and for a key m of a per-block
+//   cell with w = exp(qbar.k_m - mu):  dv_m += w G_v,  dk_m += w G_k + w (G_c + G_k.k_m + G_v.v_m) qbar,
+//   where G = own gradient + sum over later accumulated cells a of exp(mu - Amu[a]) gA[a].
+// Every reduction has one owner (no float atomics): cells by (query cluster, key-cluster tile),
+// keys by (key block, key-cluster tile).
 #include "ff_common.h"
-int muse_run_bwd(const MuseDims&, const void*, const void*, const void*, const void*, const float*, const void*,
-                 const float*, const int32_t*, const int32_t*, const int32_t*, const int32_t*, void*, void*, void*,
-                 void*, size_t, hipStream_t) { return MUSE_ERR_UNSUPPORTED; }
+
+namespace {
+
+// bit j of selmask[q][j/32]: query q retrieved key cluster j
+__global__ void __launch_bounds__(256) k_selmask(const int32_t* __restrict__ selc, uint32_t* __restrict__ mask,
+                                                  size_t nq, int r, int W) {
+  size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= nq * W) return;
+  size_t q = t / W;
+  int w = (int)(t % W);
+  uint32_t m = 0;
+  for (int k = 0; k < r; ++k) {
+    int j = selc[q * r + k];
+    if (j >= 0 && (j >> 5) == w) m |= 1u << (j & 31);
+  }
+  mask[t] = m;
+}
+
+// ------------------------------------------------------------------------------------------
+// dQ of the far field, one wave per query tile (same tiling as the forward kernel)
+// ------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ void __launch_bounds__(64) k_ff_bwd_dq(
+    const T* __restrict__ Q, const T* __restrict__ dO, const float* __restrict__ qc, const T* __restrict__ Ks,
+    const T* __restrict__ Vs, const float* __restrict__ L, const float* __restrict__ s_mu,
+    const float* __restrict__ s_k, const float* __restrict__ s_v, const float* __restrict__ A_mu,
+    const float* __restrict__ A_k, const float* __restrict__ A_v, const int32_t* __restrict__ perm_q,
+    const int32_t* __restrict__ off_q, const int32_t* __restrict__ off_k, const int32_t* __restrict__ tile_off,
+    const float* __restrict__ LSE, const float* __restrict__ delta, const uint32_t* __restrict__ selmask,
+    const int32_t* __restrict__ selc, const int32_t* __restrict__ selb, float* __restrict__ dQ, int h0, int N, int nb,
+    int Cq, int Ck, int r, int k2e, int Hq, int Hkv, float scale) {
+  constexpr int U = D / 8, DT = D / 32;
+  const int hl = blockIdx.z, hq = h0 + hl;
+  const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
+  const int b = blockIdx.y + 1, NBm = nb - 1;
+  const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
+  const int W = (Ck + 31) / 32;
+
+  const int32_t* to = tile_off + ((size_t)hq * nb + b) * (Cq + 1);
+  const int tile = blockIdx.x;
+  if (tile >= to[Cq]) return;
+  int lo_ = 0, hi_ = Cq;
+  while (hi_ - lo_ > 1) {
+    int mid = (lo_ + hi_) >> 1;
+    if (to[mid] <= tile) lo_ = mid; else hi_ = mid;
+  }
+  const int i = lo_, tt = tile - to[lo_];
+  const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
+  int pos = qlo + 32 * tt + col;
+  const bool valid = pos < qhi;
+  pos = valid ? pos : qlo + 32 * tt;
+  const int n = perm_q[(size_t)hq * N + pos];
+  const size_t qn = (size_t)hq * N + n;
+
+  float qt[U][4], gt[U][4];
+  {
+    const float* qci = qc + ((size_t)hq * Cq + i) * D;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float x[4];
+      ld4(Q, qn * D + 8 * u + 4 * half, x);
+      float4 c = *reinterpret_cast<const float4*>(qci + 8 * u + 4 * half);
+      qt[u][0] = scale * (x[0] - c.x); qt[u][1] = scale * (x[1] - c.y);
+      qt[u][2] = scale * (x[2] - c.z); qt[u][3] = scale * (x[3] - c.w);
+      ld4(dO, qn * D + 8 * u + 4 * half, gt[u]);
+    }
+  }
+  const float lse = LSE[qn], dl = delta[qn];
+  const size_t acell = (((size_t)hl * NBm + (b - 1)) * Cq + i) * Ck;
+  const float* Amu = A_mu + acell;
+  const float* Ak = A_k + acell * D;
+  const float* Av = A_v + acell * D;
+  const int ntile = (Ck + 31) / 32;
+
+  f32x16_t dq[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t) dq[t] = zero16();
+  // component 1
+  for (int jt = 0; jt < ntile; ++jt) {
+    const int j0 = jt * 32;
+    f32x16_t s = score_tile<D>(Amu, Ak, j0, Ck, qt, col, half);
+    int c = j0 + col;
+    c = c < Ck ? c : Ck - 1;
+    f32x16_t dp = mfma_rows<D>(zero16(), Av + (size_t)c * D + 4 * half, gt);
+    const uint32_t mw = selmask[qn * W + jt];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int row = 8 * (e / 4) + 4 * half + (e % 4);
+      float p = ((mw >> row) & 1u) ? 0.f : __expf(s[e] - lse);
+      s[e] = p * (dp[e] - dl);
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        int jr = j0 + 8 * g + 4 * half + t;
+        jr = jr < Ck ? jr : Ck - 1;
+        const float* krow = Ak + (size_t)jr * D + col;
+#pragma unroll
+        for (int x = 0; x < DT; ++x) dq[x] = mfma32(krow[32 * x], s[4 * g + t], dq[x]);
+      }
+  }
+  // components 2 and 3
+  for (int t = 0; t < r; ++t) {
+    const int j = selc[qn * r + t];
+    if (j < 0) continue;
+    unsigned selbits = 0;
+    for (int u = 0; u < k2e; ++u) {
+      int bb = selb[(qn * r + t) * k2e + u];
+      if (bb >= 0) selbits |= 1u << bb;
+    }
+    for (int bp = 0; bp < b; ++bp) {
+      const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
+      const float mu = s_mu[cell];
+      if (!(mu > MUSE_NEG_INF)) continue;
+      if (!((selbits >> bp) & 1u)) {
+        const float* kr = s_k + cell * D + 4 * half;
+        const float* vr = s_v + cell * D + 4 * half;
+        float part = 0.f, dpp = 0.f;
+        float4 k4[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          k4[u] = *reinterpret_cast<const float4*>(kr + 8 * u);
+          float4 v4 = *reinterpret_cast<const float4*>(vr + 8 * u);
+          part = fmaf(qt[u][0], k4[u].x, part); part = fmaf(qt[u][1], k4[u].y, part);
+          part = fmaf(qt[u][2], k4[u].z, part); part = fmaf(qt[u][3], k4[u].w, part);
+          dpp = fmaf(gt[u][0], v4.x, dpp); dpp = fmaf(gt[u][1], v4.y, dpp);
+          dpp = fmaf(gt[u][2], v4.z, dpp); dpp = fmaf(gt[u][3], v4.w, dpp);
+        }
+        part += __shfl_xor(part, 32, 64);
+        dpp += __shfl_xor(dpp, 32, 64);
+        float p = __expf(part + mu - lse);
+        float dlg = p * (dpp - dl);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          dq[u / 4][4 * (u % 4) + 0] += dlg * k4[u].x; dq[u / 4][4 * (u % 4) + 1] += dlg * k4[u].y;
+          dq[u / 4][4 * (u % 4) + 2] += dlg * k4[u].z; dq[u / 4][4 * (u % 4) + 3] += dlg * k4[u].w;
+        }
+      } else {
+        const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
+        for (int p_ = klo; p_ < khi; ++p_) {
+          const size_t krow = ((size_t)hk * N + p_) * D + 4 * half;
+          float part = 0.f, dpp = 0.f;
+          float k4[U][4];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            float v4[4];
+            ld4(Ks, krow + 8 * u, k4[u]);
+            ld4(Vs, krow + 8 * u, v4);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+              part = fmaf(qt[u][x], k4[u][x], part);
+              dpp = fmaf(gt[u][x], v4[x], dpp);
+            }
+          }
+          part += __shfl_xor(part, 32, 64);
+          dpp += __shfl_xor(dpp, 32, 64);
+          float p = __expf(part + L[((size_t)hl * Cq + i) * N + p_] - lse);
+          float dlg = p * (dpp - dl);
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) dq[u / 4][4 * (u % 4) + x] += dlg * k4[u][x];
+        }
+      }
+    }
+  }
+  if (!valid) return;
+  float* out = dQ + qn * D + 4 * half;
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    *reinterpret_cast<float4*>(out + 8 * u) =
+        make_float4(scale * dq[u / 4][4 * (u % 4)], scale * dq[u / 4][4 * (u % 4) + 1],
+                    scale * dq[u / 4][4 * (u % 4) + 2], scale * dq[u / 4][4 * (u % 4) + 3]);
+}
+
+// ------------------------------------------------------------------------------------------
+// gradients of the accumulated cells (component 1): one wave per (query block b, query cluster i,
+// tile of 32 key clusters); loops over the queries of the group.  Writes every cell it owns:
+//   g_A_k = sum dl q~,  g_A_v = sum p dO,  g_A_c = sum [dl (1 - q~.kappa) - p dO.vbar]
+// ------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ void __launch_bounds__(64) k_ff_bwd_cells(
+    const T* __restrict__ Q, const T* __restrict__ dO, const float* __restrict__ qc, const float* __restrict__ A_mu,
+    const float* __restrict__ A_k, const float* __restrict__ A_v, const int32_t* __restrict__ perm_q,
+    const int32_t* __restrict__ off_q, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const uint32_t* __restrict__ selmask, float* __restrict__ g_A_c, float* __restrict__ g_A_k,
+    float* __restrict__ g_A_v, int h0, int N, int nb, int Cq, int Ck, float scale) {
+  constexpr int U = D / 8, DT = D / 32;
+  __shared__ int ns[32];
+  __shared__ float ls[32], ds[32];
+  __shared__ uint32_t mws[32];
+  const int hl = blockIdx.z, hq = h0 + hl;
+  const int NBm = nb - 1;
+  const int b = blockIdx.y / Cq + 1, i = blockIdx.y % Cq;
+  const int jt = blockIdx.x, j0 = jt * 32;
+  const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
+  const int W = (Ck + 31) / 32;
+  const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
+  const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
+  const size_t acell = (((size_t)hl * NBm + (b - 1)) * Cq + i) * Ck;
+  const int jc = j0 + col;
+  const bool jvalid = jc < Ck;
+  const int jcc = jvalid ? jc : Ck - 1;
+  // B operands: this lane's key cluster
+  float kt[U][4], vt[U][4];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    float4 a = *reinterpret_cast<const float4*>(A_k + (acell + jcc) * D + 8 * u + 4 * half);
+    float4 c = *reinterpret_cast<const float4*>(A_v + (acell + jcc) * D + 8 * u + 4 * half);
+    kt[u][0] = a.x; kt[u][1] = a.y; kt[u][2] = a.z; kt[u][3] = a.w;
+    vt[u][0] = c.x; vt[u][1] = c.y; vt[u][2] = c.z; vt[u][3] = c.w;
+  }
+  const float amu = jvalid ? A_mu[acell + jcc] : MUSE_NEG_INF;
+  const float* qci = qc + ((size_t)hq * Cq + i) * D;
+  f32x16_t gk[DT], gv[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t) { gk[t] = zero16(); gv[t] = zero16(); }
+  float csum = 0.f;
+  for (int q0 = qlo; q0 < qhi; q0 += 32) {
+    __syncthreads();
+    if (half == 0) {
+      int pos = q0 + col;
+      bool ok_ = pos < qhi;
+      int n = perm_q[(size_t)hq * N + (ok_ ? pos : q0)];
+      ns[col] = n;
+      ls[col] = ok_ ? LSE[(size_t)hq * N + n] : __builtin_huge_valf();  // +inf -> p = 0 for padding rows
+      ds[col] = delta[(size_t)hq * N + n];
+      mws[col] = selmask[((size_t)hq * N + n) * W + jt];
+    }
+    __syncthreads();
+    // A operands (row pattern): this lane's query row
+    const size_t qn = (size_t)hq * N + ns[col];
+    f32x16_t s = zero16(), dp = zero16();
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float x[4], g[4];
+      ld4(Q, qn * D + 8 * u + 4 * half, x);
+      ld4(dO, qn * D + 8 * u + 4 * half, g);
+      float4 c = *reinterpret_cast<const float4*>(qci + 8 * u + 4 * half);
+      s = mfma32(scale * (x[0] - c.x), kt[u][0], s); s = mfma32(scale * (x[1] - c.y), kt[u][1], s);
+      s = mfma32(scale * (x[2] - c.z), kt[u][2], s); s = mfma32(scale * (x[3] - c.w), kt[u][3], s);
+      dp = mfma32(g[0], vt[u][0], dp); dp = mfma32(g[1], vt[u][1], dp);
+      dp = mfma32(g[2], vt[u][2], dp); dp = mfma32(g[3], vt[u][3], dp);
+    }
+    f32x16_t pr;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int row = 8 * (e / 4) + 4 * half + (e % 4);
+      float p = __expf(s[e] + amu - ls[row]);   // amu = -inf or lse = +inf -> 0
+      p = ((mws[row] >> col) & 1u) ? 0.f : p;
+      float dlg = p * (dp[e] - ds[row]);
+      csum += p > 0.f ? dlg * (1.f - s[e]) - p * dp[e] : 0.f;
+      pr[e] = p;
+      s[e] = dlg;
+    }
+    // g_k^T [D x clusters] += q~^T dl,  g_v^T += dO^T p  (column pattern over the query rows)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const size_t rn = (size_t)hq * N + ns[8 * g + 4 * half + t];
+#pragma unroll
+        for (int x = 0; x < DT; ++x) {
+          float qv = scale * (Elem<T>::ld(Q, rn * D + 32 * x + col) - qci[32 * x + col]);
+          float gvv = Elem<T>::ld(dO, rn * D + 32 * x + col);
+          gk[x] = mfma32(qv, s[4 * g + t], gk[x]);
+          gv[x] = mfma32(gvv, pr[4 * g + t], gv[x]);
+        }
+      }
+  }
+  csum += __shfl_xor(csum, 32, 64);
+  if (!jvalid) return;
+  float* ok_ = g_A_k + (acell + jc) * D;
+  float* ov_ = g_A_v + (acell + jc) * D;
+#pragma unroll
+  for (int x = 0; x < DT; ++x)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      int d = 32 * x + 8 * g + 4 * half;
+      *reinterpret_cast<float4*>(ok_ + d) = make_float4(gk[x][4 * g], gk[x][4 * g + 1], gk[x][4 * g + 2], gk[x][4 * g + 3]);
+      *reinterpret_cast<float4*>(ov_ + d) = make_float4(gv[x][4 * g], gv[x][4 * g + 1], gv[x][4 * g + 2], gv[x][4 * g + 3]);
+    }
+  if (half == 0) g_A_c[acell + jc] = csum;
+}
+
+// ------------------------------------------------------------------------------------------
+// gradients of the per-block cells (component 2): one wave per (query cluster i, tile of 32 key
+// clusters) owns the cells (i, tile, all blocks); it walks the queries of cluster i, and for every
+// query that retrieved a cluster of the tile adds its non-retrieved-block terms.  Lanes = head dim.
+// The cells must be zero on entry.
+// ------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ void __launch_bounds__(64) k_c2_cells(
+    const T* __restrict__ Q, const T* __restrict__ dO, const float* __restrict__ qc, const float* __restrict__ s_mu,
+    const float* __restrict__ s_k, const float* __restrict__ s_v, const int32_t* __restrict__ perm_q,
+    const int32_t* __restrict__ off_q, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const uint32_t* __restrict__ selmask, const int32_t* __restrict__ selc, const int32_t* __restrict__ selb,
+    float* __restrict__ g_s_c, float* __restrict__ g_s_k, float* __restrict__ g_s_v, int h0, int N, int nb, int Cq,
+    int Ck, int r, int k2e, float scale) {
+  constexpr int DL = D / 64;
+  const int hl = blockIdx.z, hq = h0 + hl;
+  const int i = blockIdx.y, jt = blockIdx.x;
+  const int lane = threadIdx.x, NBm = nb - 1;
+  const int W = (Ck + 31) / 32;
+  const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
+  float qcv[DL];
+#pragma unroll
+  for (int x = 0; x < DL; ++x) qcv[x] = qc[((size_t)hq * Cq + i) * D + lane + 64 * x];
+  for (int b = 1; b < nb; ++b) {
+    const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
+    for (int q0 = qlo; q0 < qhi; q0 += 64) {
+      const int pos = q0 + lane;
+      int n = 0;
+      uint32_t mw = 0;
+      if (pos < qhi) {
+        n = perm_q[(size_t)hq * N + pos];
+        mw = selmask[((size_t)hq * N + n) * W + jt];
+      }
+      unsigned long long live = __ballot(mw != 0);
+      while (live) {
+        const int src = __ffsll((long long)live) - 1;
+        live &= live - 1;
+        const int nn = __shfl(n, src, 64);
+        uint32_t bits = (uint32_t)__shfl((int)mw, src, 64);
+        const size_t qn = (size_t)hq * N + nn;
+        float qv[DL], gv[DL];
+#pragma unroll
+        for (int x = 0; x < DL; ++x) {
+          qv[x] = scale * (Elem<T>::ld(Q, qn * D + lane + 64 * x) - qcv[x]);
+          gv[x] = Elem<T>::ld(dO, qn * D + lane + 64 * x);
+        }
+        const float lse = LSE[qn], dl = delta[qn];
+        while (bits) {
+          const int jl = __ffs((int)bits) - 1;
+          bits &= bits - 1;
+          const int j = jt * 32 + jl;
+          int slot = -1;
+          for (int t = 0; t < r; ++t)
+            if (selc[qn * r + t] == j) slot = t;
+          if (slot < 0) continue;
+          unsigned selbits = 0;
+          for (int u = 0; u < k2e; ++u) {
+            int bb = selb[(qn * r + slot) * k2e + u];
+            if (bb >= 0) selbits |= 1u << bb;
+          }
+          for (int bp = 0; bp < b; ++bp) {
+            if ((selbits >> bp) & 1u) continue;
+            const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
+            const float mu = s_mu[cell];
+            if (!(mu > MUSE_NEG_INF)) continue;
+            float kv[DL], vv[DL], part = 0.f, dpp = 0.f;
+#pragma unroll
+            for (int x = 0; x < DL; ++x) {
+              kv[x] = s_k[cell * D + lane + 64 * x];
+              vv[x] = s_v[cell * D + lane + 64 * x];
+              part = fmaf(qv[x], kv[x], part);
+              dpp = fmaf(gv[x], vv[x], dpp);
+            }
+            part = wave_sum(part);
+            dpp = wave_sum(dpp);
+            const float p = __expf(part + mu - lse);
+            const float dlg = p * (dpp - dl);
+#pragma unroll
+            for (int x = 0; x < DL; ++x) {
+              g_s_k[cell * D + lane + 64 * x] += dlg * qv[x];
+              g_s_v[cell * D + lane + 64 * x] += p * gv[x];
+            }
+            if (lane == 0) g_s_c[cell] += dlg * (1.f - part) - p * dpp;
+          }
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// reverse accumulation: G[b'] = g_s[b'] + exp(mu[b'] - Amu[b']) R[b'],
+// R[a] = g_A[a] + exp(Amu[a] - Amu[a+1]) R[a+1]   (all factors <= 1).  In place into g_s_*.
+// One thread per (cell chain, group of 4 dims); the scalar c-terms ride on the first group.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_cell_scan_bwd(const float* __restrict__ s_mu, const float* __restrict__ A_mu,
+                                                        const float* __restrict__ g_A_c, const float* __restrict__ g_A_k,
+                                                        const float* __restrict__ g_A_v, float* __restrict__ g_s_c,
+                                                        float* __restrict__ g_s_k, float* __restrict__ g_s_v, int hn,
+                                                        int NBm, size_t chains, int D) {
+  const int D4 = D / 4;
+  size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (size_t)hn * chains * D4) return;
+  const int d4 = (int)(t % D4);
+  const size_t ch = (t / D4) % chains;
+  const size_t hl = t / D4 / chains;
+  float4 Rk = make_float4(0, 0, 0, 0), Rv = make_float4(0, 0, 0, 0);
+  float Rc = 0.f, Anext = 0.f;
+  for (int a = NBm - 1; a >= 0; --a) {
+    const size_t cell = (hl * NBm + a) * chains + ch;
+    const float Am = A_mu[cell];
+    float f = 0.f;
+    if (a < NBm - 1 && Am > MUSE_NEG_INF) f = __expf(Am - Anext);
+    Anext = Am;
+    float4 gk = *reinterpret_cast<const float4*>(g_A_k + cell * D + 4 * d4);
+    float4 gv = *reinterpret_cast<const float4*>(g_A_v + cell * D + 4 * d4);
+    Rk.x = gk.x + f * Rk.x; Rk.y = gk.y + f * Rk.y; Rk.z = gk.z + f * Rk.z; Rk.w = gk.w + f * Rk.w;
+    Rv.x = gv.x + f * Rv.x; Rv.y = gv.y + f * Rv.y; Rv.z = gv.z + f * Rv.z; Rv.w = gv.w + f * Rv.w;
+    Rc = g_A_c[cell] + f * Rc;
+    const float mu = s_mu[cell];
+    if (mu > MUSE_NEG_INF) {
+      const float w = __expf(mu - Am);
+      float4 sk = *reinterpret_cast<float4*>(g_s_k + cell * D + 4 * d4);
+      float4 sv = *reinterpret_cast<float4*>(g_s_v + cell * D + 4 * d4);
+      sk.x += w * Rk.x; sk.y += w * Rk.y; sk.z += w * Rk.z; sk.w += w * Rk.w;
+      sv.x += w * Rv.x; sv.y += w * Rv.y; sv.z += w * Rv.z; sv.w += w * Rv.w;
+      *reinterpret_cast<float4*>(g_s_k + cell * D + 4 * d4) = sk;
+      *reinterpret_cast<float4*>(g_s_v + cell * D + 4 * d4) = sv;
+      if (d4 == 0) g_s_c[cell] += w * Rc;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// summary gradients -> keys and values: one wave per (kv head, key block b', key cluster j); loops
+// over the query heads of the group and over tiles of 32 query clusters.
+//   W[i,m] = exp(L[i,m] - mu[i]),  T[i,m] = G_c[i] + G_k[i].k_m + G_v[i].v_m
+//   dv_m += sum_i W G_v[i],  dk_m += sum_i W G_k[i] + (W T) qbar_i
+// ------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ void __launch_bounds__(64) k_cells_to_keys(const T* __restrict__ Ks, const T* __restrict__ Vs,
+                                                       const float* __restrict__ qc, const float* __restrict__ L,
+                                                       const float* __restrict__ s_mu, const float* __restrict__ G_c,
+                                                       const float* __restrict__ G_k, const float* __restrict__ G_v,
+                                                       const int32_t* __restrict__ off_k, float* __restrict__ dKs,
+                                                       float* __restrict__ dVs, int h0, int N, int nb, int Cq, int Ck,
+                                                       int Hq, int Hkv, float scale) {
+  constexpr int U = D / 8, DT = D / 32;
+  const int G_ = Hq / Hkv;
+  const int hkl = blockIdx.z;                 // kv head inside the chunk
+  const int hq0 = h0 + hkl * G_;              // first query head of the group (global flat index)
+  const int hk = (hq0 / Hq) * Hkv + (hq0 % Hq) / G_;
+  const int bp = blockIdx.y, j = blockIdx.x, NBm = nb - 1;
+  const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
+  for (int m0 = klo; m0 < khi; m0 += 32) {
+    const int pm = m0 + col;
+    const bool mvalid = pm < khi;
+    const int pmc = mvalid ? pm : m0;
+    // B operands (row pattern): this lane's key
+    float kb[U][4], vb[U][4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      ld4(Ks, ((size_t)hk * N + pmc) * D + 8 * u + 4 * half, kb[u]);
+      ld4(Vs, ((size_t)hk * N + pmc) * D + 8 * u + 4 * half, vb[u]);
+    }
+    f32x16_t dk[DT], dv[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t) { dk[t] = zero16(); dv[t] = zero16(); }
+    for (int g = 0; g < G_; ++g) {
+      const int hl = hkl * G_ + g, hq = h0 + hl;
+      for (int i0 = 0; i0 < Cq; i0 += 32) {
+        const int ic = i0 + col < Cq ? i0 + col : Cq - 1;  // A-operand row of this lane
+        const size_t cellA = (((size_t)hl * NBm + bp) * Cq + ic) * Ck + j;
+        f32x16_t tacc, wv;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          int ir = i0 + 8 * (e / 4) + 4 * half + (e % 4);
+          bool iv = ir < Cq;
+          int irc = iv ? ir : Cq - 1;
+          const size_t cell = (((size_t)hl * NBm + bp) * Cq + irc) * Ck + j;
+          tacc[e] = G_c[cell];
+          float w = __expf(L[((size_t)hl * Cq + irc) * N + pmc] - s_mu[cell]);
+          wv[e] = (iv && mvalid) ? w : 0.f;
+        }
+        tacc = mfma_rows<D>(tacc, G_k + cellA * D + 4 * half, kb);
+        tacc = mfma_rows<D>(tacc, G_v + cellA * D + 4 * half, vb);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tacc[e] = wv[e] > 0.f ? wv[e] * tacc[e] : 0.f;
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg)
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            int ir = i0 + 8 * gg + 4 * half + t;
+            ir = ir < Cq ? ir : Cq - 1;
+            const size_t cell = (((size_t)hl * NBm + bp) * Cq + ir) * Ck + j;
+#pragma unroll
+            for (int x = 0; x < DT; ++x) {
+              float gkv = G_k[cell * D + 32 * x + col];
+              float gvv = G_v[cell * D + 32 * x + col];
+              float qb = scale * qc[((size_t)hq * Cq + ir) * D + 32 * x + col];
+              dv[x] = mfma32(gvv, wv[4 * gg + t], dv[x]);
+              dk[x] = mfma32(gkv, wv[4 * gg + t], dk[x]);
+              dk[x] = mfma32(qb, tacc[4 * gg + t], dk[x]);
+            }
+          }
+      }
+    }
+    if (mvalid) {
+      float* ok_ = dKs + ((size_t)hk * N + pm) * D;
+      float* ov_ = dVs + ((size_t)hk * N + pm) * D;
+#pragma unroll
+      for (int x = 0; x < DT; ++x)
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {
+          int d = 32 * x + 8 * gg + 4 * half;
+          float4 a = *reinterpret_cast<float4*>(ok_ + d), c = *reinterpret_cast<float4*>(ov_ + d);
+          a.x += dk[x][4 * gg]; a.y += dk[x][4 * gg + 1]; a.z += dk[x][4 * gg + 2]; a.w += dk[x][4 * gg + 3];
+          c.x += dv[x][4 * gg]; c.y += dv[x][4 * gg + 1]; c.z += dv[x][4 * gg + 2]; c.w += dv[x][4 * gg + 3];
+          *reinterpret_cast<float4*>(ok_ + d) = a;
+          *reinterpret_cast<float4*>(ov_ + d) = c;
+        }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// retrieval (component 3) -> keys and values: one wave per (kv head, key block b', tile of 32 key
+// clusters) owns those keys.  Phase 1 scans the queries of later blocks (all heads of the group),
+// collecting (query, cluster) hits into LDS; phase 2 accumulates per cluster in registers and adds
+// the result to the bucketed gradient rows.  When the list fills, phase 2 runs and scanning resumes.
+// ------------------------------------------------------------------------------------------
+constexpr int kHitCap = 2048;
+
+// stable counting sort of the hits by their 5-bit cluster id (single wave): sorted[], start[33]
+__device__ __forceinline__ void c3_sort_hits(const uint32_t* hits, int nh, uint32_t* sorted, int* start, int* cursor) {
+  const int lane = threadIdx.x;
+  if (lane < 33) start[lane] = 0;
+  __syncthreads();
+  for (int i = lane; i < nh; i += 64) atomicAdd(&start[(hits[i] & 31u) + 1], 1);
+  __syncthreads();
+  if (lane == 0)
+    for (int k = 0; k < 32; ++k) start[k + 1] += start[k];
+  __syncthreads();
+  if (lane < 32) cursor[lane] = start[lane];
+  __syncthreads();
+  for (int i0 = 0; i0 < nh; i0 += 64) {
+    const int i = i0 + lane;
+    const bool act = i < nh;
+    const uint32_t h = act ? hits[i] : 0u;
+    const int key = h & 31u;
+    unsigned long long m = __ballot(act);
+#pragma unroll
+    for (int bit = 0; bit < 5; ++bit) {
+      unsigned long long bb = __ballot((key >> bit) & 1);
+      m &= ((key >> bit) & 1) ? bb : ~bb;
+    }
+    const int rank = __popcll(m & ((1ull << lane) - 1ull)), cnt = __popcll(m);
+    if (act) {
+      const int base = cursor[key];
+      sorted[base + rank] = h;
+      if (rank == cnt - 1) cursor[key] = base + cnt;
+    }
+  }
+  __syncthreads();
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void c3_flush(const uint32_t* hits, const int* start, const T* __restrict__ Q,
+                                         const T* __restrict__ dO, const T* __restrict__ Ks, const T* __restrict__ Vs,
+                                         const float* __restrict__ LSE, const float* __restrict__ delta,
+                                         const int32_t* __restrict__ ok, float* __restrict__ dKs,
+                                         float* __restrict__ dVs, int hk, int hqbase, int N, int Ck, int bp, int jt,
+                                         float scale) {
+  constexpr int CH = D / 8, KSL = 64 / CH;  // lanes per key, keys per step
+  const int lane = threadIdx.x, slot = lane / CH, chunk = lane % CH;
+  for (int jl = 0; jl < 32; ++jl) {
+    const int j = jt * 32 + jl;
+    if (j >= Ck) break;
+    const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
+    for (int kb = klo; kb < khi; kb += KSL) {
+      const int pk = kb + slot;
+      const bool kvalid = pk < khi;
+      const size_t krow = ((size_t)hk * N + (kvalid ? pk : klo)) * D + 8 * chunk;
+      float k8[8], v8[8], ak[8], av[8];
+      ld4(Ks, krow, k8); ld4(Ks, krow + 4, k8 + 4);
+      ld4(Vs, krow, v8); ld4(Vs, krow + 4, v8 + 4);
+#pragma unroll
+      for (int x = 0; x < 8; ++x) { ak[x] = 0.f; av[x] = 0.f; }
+      for (int hI = start[jl]; hI < start[jl + 1]; ++hI) {
+        const uint32_t hit = hits[hI];
+        const int g = (hit >> 5) & 7, n = hit >> 8;
+        const size_t qn = ((size_t)hqbase + g) * N + n;
+        float q8[8], g8[8];
+        ld4(Q, qn * D + 8 * chunk, q8); ld4(Q, qn * D + 8 * chunk + 4, q8 + 4);
+        ld4(dO, qn * D + 8 * chunk, g8); ld4(dO, qn * D + 8 * chunk + 4, g8 + 4);
+        float part = 0.f, dpp = 0.f;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          q8[x] *= scale;
+          part = fmaf(q8[x], k8[x], part);
+          dpp = fmaf(g8[x], v8[x], dpp);
+        }
+#pragma unroll
+        for (int o = 1; o < CH; o <<= 1) {
+          part += __shfl_xor(part, o, 64);
+          dpp += __shfl_xor(dpp, o, 64);
+        }
+        const float p = kvalid ? __expf(part - LSE[qn]) : 0.f;
+        const float dlg = p * (dpp - delta[qn]);
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          ak[x] = fmaf(dlg, q8[x], ak[x]);
+          av[x] = fmaf(p, g8[x], av[x]);
+        }
+      }
+      if (kvalid) {
+        float* ok_ = dKs + krow;
+        float* ov_ = dVs + krow;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) { ok_[x] += ak[x]; ov_[x] += av[x]; }
+      }
+    }
+  }
+}
+
+template <typename T, int D>
+__global__ void __launch_bounds__(64) k_c3_keys(const T* __restrict__ Q, const T* __restrict__ dO,
+                                                 const T* __restrict__ Ks, const T* __restrict__ Vs,
+                                                 const float* __restrict__ LSE, const float* __restrict__ delta,
+                                                 const uint32_t* __restrict__ selmask, const int32_t* __restrict__ selc,
+                                                 const int32_t* __restrict__ selb, const int32_t* __restrict__ off_k,
+                                                 float* __restrict__ dKs, float* __restrict__ dVs, int N, int Bs, int nb,
+                                                 int Ck, int r, int k2e, int Hq, int Hkv, float scale) {
+  __shared__ uint32_t hits[kHitCap];
+  __shared__ uint32_t sorted[kHitCap];
+  __shared__ int start[33], cursor[32];
+  const int hk = blockIdx.z, bp = blockIdx.y, jt = blockIdx.x;
+  const int G_ = Hq / Hkv;
+  const int hqbase = (hk / Hkv) * Hq + (hk % Hkv) * G_;
+  const int lane = threadIdx.x;
+  const int W = (Ck + 31) / 32;
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  // nothing to do when the tile has no keys in this block
+  {
+    int jhi = min(jt * 32 + 32, Ck);
+    if (ok[bp * Ck + jt * 32] == ok[bp * Ck + jhi]) return;
+  }
+  int nh = 0;
+  for (int g = 0; g < G_; ++g) {
+    const size_t hq = (size_t)hqbase + g;
+    for (int n0 = (bp + 1) * Bs; n0 < N; n0 += 64) {
+      const int n = n0 + lane;
+      uint32_t mw = n < N ? selmask[(hq * N + n) * W + jt] : 0u;
+      // keep only the clusters whose retrieved blocks include bp
+      uint32_t keep = 0;
+      while (mw) {
+        const int jl = __ffs((int)mw) - 1;
+        mw &= mw - 1;
+        const int j = jt * 32 + jl;
+        for (int t = 0; t < r; ++t)
+          if (selc[(hq * N + n) * r + t] == j)
+            for (int u = 0; u < k2e; ++u)
+              if (selb[((hq * N + n) * r + t) * k2e + u] == bp) keep |= 1u << jl;
+      }
+      // append (n, g, jl) for every kept bit, in lane order
+      int cnt = __popc(keep);
+      unsigned long long any = __ballot(cnt > 0);
+      if (!any) continue;
+      int incl = cnt;
+      for (int o = 1; o < 64; o <<= 1) {
+        int v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+      }
+      const int total = __shfl(incl, 63, 64);
+      if (nh + total > kHitCap) {
+        __syncthreads();
+        c3_sort_hits(hits, nh, sorted, start, cursor);
+        c3_flush<T, D>(sorted, start, Q, dO, Ks, Vs, LSE, delta, ok, dKs, dVs, hk, hqbase, N, Ck, bp, jt, scale);
+        __syncthreads();
+        nh = 0;
+      }
+      int at = nh + incl - cnt;
+      while (keep) {
+        const int jl = __ffs((int)keep) - 1;
+        keep &= keep - 1;
+        hits[at++] = ((uint32_t)n << 8) | ((uint32_t)g << 5) | (uint32_t)jl;
+      }
+      nh += total;
+    }
+  }
+  __syncthreads();
+  c3_sort_hits(hits, nh, sorted, start, cursor);
+  c3_flush<T, D>(sorted, start, Q, dO, Ks, Vs, LSE, delta, ok, dKs, dVs, hk, hqbase, N, Ck, bp, jt, scale);
+}
+
+// rows back to sequence order: dst[perm[p]] = src[p]
+__global__ void __launch_bounds__(256) k_scatter_rows(const float* __restrict__ src, const int32_t* __restrict__ perm,
+                                                       float* __restrict__ dst, int N, int D) {
+  const int CPR = D / 4;
+  size_t h = blockIdx.y;
+  size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= (size_t)N * CPR) return;
+  int p = (int)(c / CPR), cc = (int)(c % CPR);
+  int to = perm[h * N + p];
+  reinterpret_cast<float4*>(dst + (h * N + to) * D)[cc] = reinterpret_cast<const float4*>(src + (h * N + p) * D)[cc];
+}
+
+template <typename T, int D>
+int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, const float* LSE, const int32_t* selc,
+                  const int32_t* selb, FFWorkspace& w, int h0, int hn, hipStream_t st) {
+  const int NBm = d.nb - 1;
+  const size_t cells = (size_t)NBm * d.Cq * d.Ck;
+  const int W = (d.Ck + 31) / 32;
+  int rc;
+  // component-2 cells are accumulated into: start from zero
+  if ((rc = muse_launch_fill(w.g_s_c, (size_t)hn * cells, 0.f, st))) return rc;
+  if ((rc = muse_launch_fill(w.g_s_k, (size_t)hn * cells * D, 0.f, st))) return rc;
+  if ((rc = muse_launch_fill(w.g_s_v, (size_t)hn * cells * D, 0.f, st))) return rc;
+  dim3 gt(d.Bs / 32 + d.Cq + 1, NBm, hn);
+  hipLaunchKernelGGL((k_ff_bwd_dq<T, D>), gt, dim3(64), 0, st, Q, dO, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu,
+                     w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q, w.off_k, w.tile_off, LSE, w.delta,
+                     w.selmask, selc, selb, w.dQacc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale);
+  hipLaunchKernelGGL((k_ff_bwd_cells<T, D>), dim3(W, NBm * d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.A_mu, w.A_k, w.A_v,
+                     w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.g_A_c, w.g_A_k, w.g_A_v, h0, d.N, d.nb, d.Cq, d.Ck,
+                     d.scale);
+  if (d.r > 0)
+    hipLaunchKernelGGL((k_c2_cells<T, D>), dim3(W, d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.s_mu, w.s_k, w.s_v, w.perm_q,
+                       w.off_q, LSE, w.delta, w.selmask, selc, selb, w.g_s_c, w.g_s_k, w.g_s_v, h0, d.N, d.nb, d.Cq,
+                       d.Ck, d.r, d.k2e, d.scale);
+  {
+    size_t chains = (size_t)d.Cq * d.Ck;
+    size_t total = (size_t)hn * chains * (D / 4);
+    hipLaunchKernelGGL(k_cell_scan_bwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w.s_mu, w.A_mu, w.g_A_c,
+                       w.g_A_k, w.g_A_v, w.g_s_c, w.g_s_k, w.g_s_v, hn, NBm, chains, D);
+  }
+  const int G_ = d.Hq / d.Hkv;
+  hipLaunchKernelGGL((k_cells_to_keys<T, D>), dim3(d.Ck, NBm, hn / G_), dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs,
+                     qc, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq,
+                     d.Hkv, d.scale);
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
+
+template <typename T>
+int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T* O, const float* LSE, const T* dO,
+                  const float* qc, const int32_t* aq, const int32_t* ak, const int32_t* selc, const int32_t* selb,
+                  void* dQ, void* dK, void* dV, FFWorkspace& w, hipStream_t st) {
+  const int HQ = d.B * d.Hq, HK = d.B * d.Hkv, N = d.N, D = d.D;
+  const size_t nq = (size_t)HQ * N, nk = (size_t)HK * N;
+  int rc;
+  if ((rc = muse_ff_prepare<T>(d, K, V, aq, ak, w, st))) return rc;
+  if ((rc = muse_launch_delta(d, O, dO, w.delta, st))) return rc;
+  if ((rc = muse_launch_fill(w.dQacc, nq * D, 0.f, st))) return rc;
+  if ((rc = muse_launch_fill(w.dKs, nk * D, 0.f, st))) return rc;
+  if ((rc = muse_launch_fill(w.dVs, nk * D, 0.f, st))) return rc;
+  if (d.nb > 1) {
+    const int W = (d.Ck + 31) / 32;
+    if (d.r > 0) {
+      hipLaunchKernelGGL(k_selmask, dim3((unsigned)((nq * W + 255) / 256)), dim3(256), 0, st, selc, w.selmask, nq, d.r, W);
+    } else {
+      if ((rc = muse_launch_fill_i32((int32_t*)w.selmask, nq * W, 0, st))) return rc;
+    }
+    MUSE_LAUNCH_CHECK();
+    for (int h0 = 0; h0 < HQ; h0 += w.hc) {
+      int hn = HQ - h0 < w.hc ? HQ - h0 : w.hc;
+      if ((rc = muse_ff_summaries<T>(d, qc, w, h0, hn, st))) return rc;
+      if (D == 64) rc = run_bwd_chunk<T, 64>(d, Q, dO, qc, LSE, selc, selb, w, h0, hn, st);
+      else rc = run_bwd_chunk<T, 128>(d, Q, dO, qc, LSE, selc, selb, w, h0, hn, st);
+      if (rc) return rc;
+    }
+    if (d.r > 0) {
+      dim3 g((d.Ck + 31) / 32, d.nb - 1, HK);
+      if (D == 64)
+        hipLaunchKernelGGL((k_c3_keys<T, 64>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
+                           w.selmask, selc, selb, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.r, d.k2e, d.Hq, d.Hkv,
+                           d.scale);
+      else
+        hipLaunchKernelGGL((k_c3_keys<T, 128>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
+                           w.selmask, selc, selb, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.r, d.k2e, d.Hq, d.Hkv,
+                           d.scale);
+      MUSE_LAUNCH_CHECK();
+    }
+  }
+  {
+    dim3 g((unsigned)(((size_t)N * (D / 4) + 255) / 256), HK);
+    hipLaunchKernelGGL(k_scatter_rows, g, dim3(256), 0, st, w.dKs, w.perm_k, w.dKacc, N, D);
+    hipLaunchKernelGGL(k_scatter_rows, g, dim3(256), 0, st, w.dVs, w.perm_k, w.dVacc, N, D);
+    MUSE_LAUNCH_CHECK();
+  }
+  if ((rc = muse_launch_attn_bwd(d, d.Bs, Q, K, V, dO, LSE, w.delta, w.dQacc, w.dKacc, w.dVacc, st))) return rc;
+  if (d.grad_dtype != MUSE_DTYPE_FP32) {
+    if ((rc = muse_launch_cast(w.dQacc, dQ, nq * D, d.grad_dtype, 1.f, st))) return rc;
+    if ((rc = muse_launch_cast(w.dKacc, dK, nk * D, d.grad_dtype, 1.f, st))) return rc;
+    if ((rc = muse_launch_cast(w.dVacc, dV, nk * D, d.grad_dtype, 1.f, st))) return rc;
+  }
+  return MUSE_OK;
+}
+
+}  // namespace
+
+int muse_run_bwd(const MuseDims& d, const void* Q, const void* K, const void* V, const void* O, const float* LSE,
+                 const void* dO, const float* qc, const int32_t* aq, const int32_t* ak, const int32_t* selc,
+                 const int32_t* selb, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, hipStream_t st) {
+  FFWorkspace w;
+  if (!muse_ff_carve(d, true, ws, ws_bytes, &w, dQ, dK, dV)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  if (d.dtype == MUSE_DTYPE_FP32)
+    return run_bwd_typed<float>(d, (const float*)Q, (const float*)K, (const float*)V, (const float*)O, LSE,
+                                (const float*)dO, qc, aq, ak, selc, selb, dQ, dK, dV, w, st);
+  return run_bwd_typed<bf16_t>(d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)O, LSE,
+                               (const bf16_t*)dO, qc, aq, ak, selc, selb, dQ, dK, dV, w, st);
+}

@@ -23,6 +23,38 @@ __device__ __forceinline__ f32x16_t zero16() {
   return z;
 }
 
+// acc += X[row][.] (row pattern, `row` already offset by 4*(l/32)) times the row-pattern operand b
+template <int D>
+__device__ __forceinline__ f32x16_t mfma_rows(f32x16_t acc, const float* __restrict__ row, const float (&b)[D / 8][4]) {
+#pragma unroll
+  for (int u = 0; u < D / 8; ++u) {
+    float4 a = *reinterpret_cast<const float4*>(row + 8 * u);
+    acc = mfma32(a.x, b[u][0], acc);
+    acc = mfma32(a.y, b[u][1], acc);
+    acc = mfma32(a.z, b[u][2], acc);
+    acc = mfma32(a.w, b[u][3], acc);
+  }
+  return acc;
+}
+
+// scores^T of 32 key clusters (rows) x 32 queries (columns) against accumulated summaries, Eq. 7:
+// accumulator preloaded with mu-bar, then += k-bar . q~
+template <int D>
+__device__ __forceinline__ f32x16_t score_tile(const float* __restrict__ Amu, const float* __restrict__ Ak, int j0,
+                                               int Ck, const float (&qt)[D / 8][4], int col, int half) {
+  f32x16_t acc;
+#pragma unroll
+  for (int g = 0; g < 4; ++g)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      int jr = j0 + 8 * g + 4 * half + t;
+      acc[4 * g + t] = jr < Ck ? Amu[jr] : MUSE_NEG_INF;
+    }
+  int c = j0 + col;
+  c = c < Ck ? c : Ck - 1;
+  return mfma_rows<D>(acc, Ak + (size_t)c * D + 4 * half, qt);
+}
+
 struct FFWorkspace {
   // all heads
   int32_t *perm_k, *off_k, *perm_q, *off_q, *tile_off;
@@ -63,3 +95,11 @@ static inline size_t ff_head_bytes(const MuseDims& d, bool bwd) {
   if (bwd) b += 2 * ff_al(cells * 4) + 4 * ff_al(cells * D * 4);
   return b;
 }
+
+// farfield.hip
+int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWorkspace* w, void* dQ, void* dK, void* dV);
+template <typename T>
+int muse_ff_prepare(const MuseDims& d, const T* K, const T* V, const int32_t* aq, const int32_t* ak, FFWorkspace& w,
+                    hipStream_t st);
+template <typename T>
+int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0, int hn, hipStream_t st);

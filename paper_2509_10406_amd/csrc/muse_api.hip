@@ -27,6 +27,7 @@ int make_dims(const muse_params* p, bool full, MuseDims* d) {
   if (!(p->scale >= 0.f) || isinf(p->scale)) return MUSE_ERR_INVALID_ARG;
   if (p->causal != 1) return MUSE_ERR_UNSUPPORTED;
   if (p->D != 64 && p->D != 128) return MUSE_ERR_UNSUPPORTED;
+  if (p->Hq / p->Hkv > 8 || p->N > (1 << 22)) return MUSE_ERR_UNSUPPORTED;
   d->B = p->B; d->Hq = p->Hq; d->Hkv = p->Hkv; d->N = p->N; d->D = p->D;
   d->dtype = p->dtype; d->grad_dtype = p->grad_dtype;
   d->scale = p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->D);

@@ -84,6 +84,10 @@ def run_case(name, with_bwd):
         res = list(ex.map(head, range(w.Hq)))
     wantK = np.zeros((w.Hkv, w.N, w.D)); wantV = np.zeros((w.Hkv, w.N, w.D))
     for h, (free, forced, grads) in enumerate(res):
+        if name in ("cfg1_full", "cfg2_small"):
+            # the far field must matter in these cases, or the parity below would say little about it
+            far = free["mass"][w.Bs:, :3].sum(1)
+            assert far.mean() > 0.2 and (free["mass"][w.Bs:, :3].mean(0) > 1e-3).all(), free["mass"][w.Bs:].mean(0)
         if w.r:
             safe_c = free["margin_c"] > MARGIN
             assert safe_c.mean() > 0.98, safe_c.mean()
