@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the MuSe hot path on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic input: muse_cluster (Lloyd,
+T iterations, queries and keys) + muse_fwd + muse_bwd, inputs resident in HBM.  The workload is
+BASELINE.json's configs[2] ("1B-scale pretraining layer": H=16, N=65536, D=64, bf16, Cq=256,
+Ck=1024, r=8), the configuration the metric "MuSe fwd+bwd ms/layer at N=64k" is quoted on.
+
+Prints ONE JSON line; see the design doc for how every figure is derived.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"mfma_bf16": 2.5e15, "mfma_fp32": 157.3e12, "hbm": 8.0e12}
+
+
+def kernel_models(w, p):
+    """Algorithmic work per LAUNCH of each kernel at workload w (all heads of one launch).
+    Masked (causal) tiles count at half.  Returns {kernel: (bound, peak, amount, unit)}."""
+    H, Hk, N, D, Bs, Cq, Ck = w.B * w.Hq, w.B * w.Hkv, w.N, w.D, w.Bs, w.Cq, w.Ck
+    nb = N // Bs
+    Nff = N * (nb - 1) // nb           # queries that have a far field / keys that are summarised
+    cells = (nb - 1) * Cq * Ck
+    cellb = cells * (2 * D + 1) * 4    # bytes of one copy of the summaries tensor, one head
+    es = 2 if w.dtype == "bf16" else 4
+    m = {}
+    m["k_flash_fwd"] = ("mfma", PEAK["mfma_bf16"], 2 * N * Bs * D * H, "flop")          # QK^T + PV
+    m["k_flash_bwd_dq"] = ("mfma", PEAK["mfma_bf16"], 3 * N * Bs * D * H, "flop")        # S, dP, dQ
+    m["k_flash_bwd_dkv"] = ("mfma", PEAK["mfma_bf16"], 4 * N * Bs * D * H, "flop")       # S, dP, dV, dK
+    # k-means assignment: one launch per tensor per pass; report the key launch (larger C)
+    m["k_assign_bf16"] = ("mfma", PEAK["mfma_bf16"], 2 * N * Ck * D * Hk, "flop")
+    m["k_farfield_fwd"] = ("mfma", PEAK["mfma_fp32"], 2 * 2 * Nff * Ck * D * H, "flop")  # scores + PV
+    m["k_ff_bwd_dq"] = ("mfma", PEAK["mfma_fp32"], 3 * 2 * Nff * Ck * D * H, "flop")
+    m["k_ff_bwd_cells"] = ("mfma", PEAK["mfma_fp32"], 4 * 2 * Nff * Ck * D * H, "flop")
+    m["k_cells_to_keys"] = ("mfma", PEAK["mfma_fp32"], 5 * 2 * Cq * Nff * D * H, "flop")
+    m["k_summaries"] = ("hbm", PEAK["hbm"], (2 * cellb + Cq * Nff * 4 + 2 * Nff * D * es) * H, "byte")
+    m["k_cell_scan_bwd"] = ("hbm", PEAK["hbm"], 3 * cellb * H, "byte")                   # read gA, gs; write G
+    m["k_tilt_logits"] = ("hbm", PEAK["hbm"], (Cq * N * 4 + N * D * es) * H, "byte")
+    m["k_fill"] = ("hbm", PEAK["hbm"], None, "byte")
+    return m
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ws-gib", type=float, default=0.0, help="cap of the backward workspace (0 = all heads at once)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (every stage is independent per head; see DESIGN.md for how it "
+              "would shard); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2509_10406_amd import binding as mb
+    from paper_2509_10406_amd.inputs import CONFIGS, generate
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    mb.load()
+    w = CONFIGS[a.workload]
+    d = generate(w, need_dO=True)
+    p = mb.params_for(w)
+    Q, K, V, dO = (d[x].to(p.torch_dtype).cuda().contiguous() for x in ("Q", "K", "V", "dO"))
+    qi, ki = d["q_init_idx"].cuda(), d["k_init_idx"].cuda()
+    lim = int(a.ws_gib * 2 ** 30) if a.ws_gib > 0 else None
+    ws_c = mb.workspace(p, mb.WS_CLUSTER)
+    ws_b = mb.workspace(p, mb.WS_BWD, limit_bytes=lim)   # forward reuses the (larger) backward buffer
+    ws_e = mb.workspace(p, mb.WS_EXACT_BWD)
+    dev = Q.device
+    qc = torch.empty(p.B, p.Hq, p.Cq, p.D, dtype=torch.float32, device=dev)
+    kc = torch.empty(p.B, p.Hkv, p.Ck, p.D, dtype=torch.float32, device=dev)
+    fo = (torch.empty_like(Q), torch.empty(p.B, p.Hq, p.N, dtype=torch.float32, device=dev),
+          torch.empty(p.B, p.Hq, p.N, max(p.r, 1), dtype=torch.int32, device=dev),
+          torch.empty(p.B, p.Hq, p.N, max(p.r, 1), p.k2e, dtype=torch.int32, device=dev))
+    go = (torch.empty(p.B, p.Hq, p.N, p.D, dtype=torch.float32, device=dev),
+          torch.empty(p.B, p.Hkv, p.N, p.D, dtype=torch.float32, device=dev),
+          torch.empty(p.B, p.Hkv, p.N, p.D, dtype=torch.float32, device=dev))
+
+    def step():
+        _, qa, _, ka = mb.muse_cluster(p, Q, K, qi, ki, q_centroids=qc, k_centroids=kc, ws=ws_c)
+        O, LSE, selc, selb = mb.muse_fwd(p, Q, K, V, qc, qa, ka, ws=ws_b, out=fo)
+        mb.muse_bwd(p, Q, K, V, O, LSE, dO, qc, qa, ka, selc, selb, ws=ws_b, out=go)
+        return qa, ka
+
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    for _ in range(a.warmup):
+        step()
+    ms_step = timed(step, a.steps)
+
+    # stage split (separately timed, not part of the headline)
+    _, qa, _, ka = mb.muse_cluster(p, Q, K, qi, ki, q_centroids=qc, k_centroids=kc, ws=ws_c)
+    ms_cluster = timed(lambda: mb.muse_cluster(p, Q, K, qi, ki, q_centroids=qc, k_centroids=kc, ws=ws_c), 2)
+    ms_fwd = timed(lambda: mb.muse_fwd(p, Q, K, V, qc, qa, ka, ws=ws_b, out=fo), 2)
+    O, LSE, selc, selb = fo
+    ms_bwd = timed(lambda: mb.muse_bwd(p, Q, K, V, O, LSE, dO, qc, qa, ka, selc, selb, ws=ws_b, out=go), 2)
+
+    # in-house exact attention at the same shape
+    eo = (torch.empty_like(Q), torch.empty_like(LSE))
+
+    def exact():
+        Oe, Le = mb.exact_attn_fwd(p, Q, K, V, out=eo)
+        mb.exact_attn_bwd(p, Q, K, V, Oe, Le, dO, ws=ws_e, out=go)
+
+    exact()
+    ms_exact = timed(exact, 2)
+    Oe = eo[0].float()
+    rse = (((O.float() - Oe) ** 2).sum(-1) / (Oe ** 2).sum(-1).clamp_min(1e-30)).mean().item()
+    # MuSe at the same selections must not have been disturbed by the exact run (go was reused): fine.
+
+    # per-kernel durations (HIP events on the launch stream), two steps
+    mb.muse_profile_enable(True)
+    nprof = 2
+    for _ in range(nprof):
+        step()
+    prof = mb.muse_profile_report()
+    mb.muse_profile_enable(False)
+    models = kernel_models(w, p)
+    tot = sum(v[1] for v in prof.values())
+    dom = max((k for k in prof if k in models and models[k][2]), key=lambda k: prof[k][1])
+    cnt, tms = prof[dom]
+    bound, peak, amount, unit = models[dom]
+    if dom == "k_assign_bf16":   # launched for queries (Cq) and keys (Ck): per-launch work is the mean of the two
+        amount = amount * (w.Cq * w.Hq + w.Ck * w.Hkv) / (2 * w.Ck * w.Hkv)
+    avg_s = tms / cnt * 1e-3
+    ach = amount / avg_s
+    roofline = {"kernel": dom, "bound": bound, "achieved": ach / (1e12 if unit == "flop" else 1e9),
+                "peak": peak / (1e12 if unit == "flop" else 1e9), "unit": "TFLOP/s" if unit == "flop" else "GB/s",
+                "frac": ach / peak, "traffic": None, "avg_launch_ms": tms / cnt, "launches_per_step": cnt / nprof,
+                "share_of_step": tms / tot}
+    breakdown = {k: round(v[1] / nprof, 3) for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])}
+    fracs = {}
+    for k, (c, t) in prof.items():
+        if k in models and models[k][2]:
+            amt = models[k][2]
+            if k == "k_assign_bf16":
+                amt = amt * (w.Cq * w.Hq + w.Ck * w.Hkv) / (2 * w.Ck * w.Hkv)
+            fracs[k] = round(amt / (t / c * 1e-3) / models[k][1], 4)
+
+    eff_flops = 7.0 * w.N * w.N * w.D * w.B * w.Hq
+    out = {
+        "metric": "MuSe fwd+bwd ms/layer at N=64k", "value": ms_step, "unit": "ms", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} N={w.N} D={w.D} Cq={w.Cq} Ck={w.Ck} r={w.r} "
+                               f"k2={w.k2} block={w.Bs} kmeans_iters={w.kmeans_iters} (BASELINE.json configs[2])",
+                   "step": "muse_cluster + muse_fwd + muse_bwd"},
+        "ms": {"cluster": ms_cluster, "fwd": ms_fwd, "bwd": ms_bwd, "exact_attn_fwd_bwd": ms_exact},
+        "effective_attention_tflops": eff_flops / (ms_step * 1e-3) / 1e12,
+        "frac_of_bf16_mfma_peak_effective": eff_flops / (ms_step * 1e-3) / PEAK["mfma_bf16"],
+        "speedup_vs_own_exact": ms_exact / ms_step,
+        "exact_attention_tflops": eff_flops / (ms_exact * 1e-3) / 1e12,
+        "rse_vs_exact": rse,
+        "roofline": roofline,
+        "kernel_ms_per_step": breakdown,
+        "kernel_frac_of_peak": fracs,
+        "paper_context": "paper: MuSe 114.1 ms vs cuDNN flash 225.6 ms (1.98x) for 16 head-sequences per A100 80GB at "
+                         "Q128 K128 R8, another workload and machine",
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, d, p)
+    print(json.dumps(out))
+
+
+def cpu_baseline(w, d, p):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import numpy as np
+
+    import oracle as orc
+
+    orc.build()
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), w.Hq)
+    heads = list(range(cores))                    # one head per thread
+    op = orc.MuseParams(w.N, w.D, w.Bs, w.Cq, w.Ck, w.r, w.k2, 1.0 / math.sqrt(w.D))
+    rm = 1 if w.dtype == "bf16" else 0
+    G = w.Hq // w.Hkv
+    ncl = 8                                       # query clusters whose queries are evaluated
+
+    def one(h):
+        q, k, v, g = (d[x][0, hh].double().numpy() for x, hh in (("Q", h), ("K", h // G), ("V", h // G), ("dO", h)))
+        t0 = time.perf_counter()
+        cq = orc.kmeans(q, w.Cq, 0, init_idx=d["q_init_idx"][0, h].numpy(), round_mode=rm)
+        ck = orc.kmeans(k, w.Ck, 0, init_idx=d["k_init_idx"][0, h // G].numpy(), round_mode=rm)
+        t_cl = time.perf_counter() - t0
+        rows = np.nonzero(cq["assign"] < ncl)[0].astype(np.int32)
+        t0 = time.perf_counter()
+        f = orc.muse_fwd(op, q, k, v, cq["cent"], cq["assign"], ck["assign"], rows=rows)
+        orc.muse_bwd(op, q, k, v, cq["cent"], cq["assign"], ck["assign"], f["O"], f["LSE"], g, f["selc"], f["selb"],
+                     rows=rows)
+        t_fb = time.perf_counter() - t0
+        # one assignment pass measured; Lloyd needs T + 1 of them (the mean updates are a small extra)
+        return t_cl * (w.kmeans_iters + 1) + t_fb * w.N / max(len(rows), 1), len(rows)
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        res = list(ex.map(one, heads))
+    wall = time.perf_counter() - t0
+    per_head = float(np.mean([r[0] for r in res]))
+    nrows = int(np.mean([r[1] for r in res]))
+    # `cores` heads run concurrently, one per thread: a layer of B*Hq heads takes ceil(B*Hq/cores) rounds
+    layer_ms = per_head * math.ceil(w.B * w.Hq / cores) * 1e3
+    return {"value": layer_ms, "unit": "ms", "cores": cores, "kind": "oracle",
+            "sample": f"{cores} heads in parallel (one thread each); per head one nearest-centroid pass for Q and K "
+                      f"(scaled by the {w.kmeans_iters + 1} passes of Lloyd) and forward+backward of the queries of "
+                      f"{ncl} of {w.Cq} query clusters (~{nrows} of {w.N} rows, scaled by rows); extrapolated to "
+                      f"{w.B * w.Hq} heads; measured wall {wall:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()

@@ -124,6 +124,14 @@ int exact_attn_bwd(const muse_params* p, const void* Q, const void* K, const voi
                    const void* O, const float* LSE, const void* dO,
                    void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
 
+/* Diagnostics for benchmarks (not part of the method; process-wide, not thread-safe, allocates HIP
+ * events): after muse_profile_enable(1) every kernel the library launches is bracketed by HIP events on
+ * its stream; muse_profile_report synchronises those events and writes one line per kernel name,
+ * "<name> <launches> <total milliseconds>", into the HOST buffer buf of cap bytes (INVALID_ARG if it
+ * does not fit).  muse_profile_enable(0 or 1) also discards what was recorded so far. */
+int muse_profile_enable(int on);
+int muse_profile_report(char* buf, size_t cap);
+
 /* Static, NUL-terminated description of a return code. */
 const char* muse_strerror(int code);
 

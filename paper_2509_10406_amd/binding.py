@@ -20,7 +20,7 @@ _lib = None
 FP32, BF16 = 0, 1
 WS_CLUSTER, WS_FWD, WS_BWD, WS_EXACT_FWD, WS_EXACT_BWD = range(5)
 SYMBOLS = ["muse_workspace_bytes", "muse_cluster", "muse_fwd", "muse_bwd", "exact_attn_fwd", "exact_attn_bwd",
-           "muse_strerror"]
+           "muse_profile_enable", "muse_profile_report", "muse_strerror"]
 
 
 class MuseError(RuntimeError):
@@ -228,6 +228,21 @@ def exact_attn_bwd(p: Params, Q, K, V, O, LSE, dO, ws=None, out=None):
     _check(load().exact_attn_bwd(C.byref(pc), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO), _ptr(dQ),
                                  _ptr(dK), _ptr(dV), _ptr(ws), C.c_size_t(ws.numel()), _stream()), "exact_attn_bwd")
     return dQ, dK, dV
+
+
+def muse_profile_enable(on: bool):
+    _check(load().muse_profile_enable(C.c_int(1 if on else 0)), "muse_profile_enable")
+
+
+def muse_profile_report() -> dict:
+    """{kernel name: (launches, total ms)} of everything launched since muse_profile_enable(True)."""
+    buf = C.create_string_buffer(1 << 16)
+    _check(load().muse_profile_report(buf, C.c_size_t(len(buf))), "muse_profile_report")
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, cnt, ms = line.split()
+        out[name] = (int(cnt), float(ms))
+    return out
 
 
 def params_for(w, **kw) -> Params:

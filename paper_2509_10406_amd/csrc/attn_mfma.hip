@@ -383,11 +383,11 @@ int muse_launch_attn_fwd_mfma(const MuseDims& d, int Bs, const void* Q, const vo
   dim3 g((d.N + 127) / 128, d.Hq, d.B);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64)
-    hipLaunchKernelGGL(k_flash_fwd<64>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, ff,
-                       (bf16_t*)O, LSE, d.N, Bs, d.Hq, d.Hkv, sl);
+    { MuseProf prof_("k_flash_fwd", st); hipLaunchKernelGGL(k_flash_fwd<64>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, ff,
+                       (bf16_t*)O, LSE, d.N, Bs, d.Hq, d.Hkv, sl); }
   else
-    hipLaunchKernelGGL(k_flash_fwd<128>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, ff,
-                       (bf16_t*)O, LSE, d.N, Bs, d.Hq, d.Hkv, sl);
+    { MuseProf prof_("k_flash_fwd", st); hipLaunchKernelGGL(k_flash_fwd<128>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, ff,
+                       (bf16_t*)O, LSE, d.N, Bs, d.Hq, d.Hkv, sl); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
@@ -399,11 +399,11 @@ int muse_launch_attn_bwd_mfma(const MuseDims& d, int Bs, const void* Q, const vo
   float sl = d.scale * 1.4426950408889634f;
   const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V, *g = (const bf16_t*)dO;
   if (d.D == 64) {
-    hipLaunchKernelGGL(k_flash_bwd_dq<64>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl);
-    hipLaunchKernelGGL(k_flash_bwd_dkv<64>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl);
+    { MuseProf prof_("k_flash_bwd_dq", st); hipLaunchKernelGGL(k_flash_bwd_dq<64>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl); }
+    { MuseProf prof_("k_flash_bwd_dkv", st); hipLaunchKernelGGL(k_flash_bwd_dkv<64>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl); }
   } else {
-    hipLaunchKernelGGL(k_flash_bwd_dq<128>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl);
-    hipLaunchKernelGGL(k_flash_bwd_dkv<128>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl);
+    { MuseProf prof_("k_flash_bwd_dq", st); hipLaunchKernelGGL(k_flash_bwd_dq<128>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl); }
+    { MuseProf prof_("k_flash_bwd_dkv", st); hipLaunchKernelGGL(k_flash_bwd_dkv<128>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl); }
   }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;

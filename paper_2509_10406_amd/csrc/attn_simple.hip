@@ -254,11 +254,11 @@ int muse_launch_attn_fwd(const MuseDims& d, int Bs, const void* Q, const void* K
   if (d.dtype == MUSE_DTYPE_BF16) return muse_launch_attn_fwd_mfma(d, Bs, Q, K, V, ff, O, LSE, st);
   dim3 g((d.N + 63) / 64, d.Hq, d.B);
   if (d.D == 64)
-    hipLaunchKernelGGL((k_attn_fwd_simple<float, 64>), g, dim3(256), 0, st, (const float*)Q, (const float*)K,
-                       (const float*)V, ff, (float*)O, LSE, d.N, Bs, d.Hq, d.Hkv, d.scale);
+    { MuseProf prof_("k_attn_fwd_simple", st); hipLaunchKernelGGL((k_attn_fwd_simple<float, 64>), g, dim3(256), 0, st, (const float*)Q, (const float*)K,
+                       (const float*)V, ff, (float*)O, LSE, d.N, Bs, d.Hq, d.Hkv, d.scale); }
   else
-    hipLaunchKernelGGL((k_attn_fwd_simple<float, 128>), g, dim3(256), 0, st, (const float*)Q, (const float*)K,
-                       (const float*)V, ff, (float*)O, LSE, d.N, Bs, d.Hq, d.Hkv, d.scale);
+    { MuseProf prof_("k_attn_fwd_simple", st); hipLaunchKernelGGL((k_attn_fwd_simple<float, 128>), g, dim3(256), 0, st, (const float*)Q, (const float*)K,
+                       (const float*)V, ff, (float*)O, LSE, d.N, Bs, d.Hq, d.Hkv, d.scale); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
@@ -267,11 +267,11 @@ int muse_launch_delta(const MuseDims& d, const void* O, const void* dO, float* d
   size_t rows = (size_t)d.B * d.Hq * d.N;
   dim3 g((unsigned)((rows + 3) / 4));
   if (d.dtype == MUSE_DTYPE_BF16) {
-    if (d.D == 64) hipLaunchKernelGGL((k_delta<bf16_t, 64>), g, dim3(256), 0, st, (const bf16_t*)O, (const bf16_t*)dO, delta, rows);
-    else hipLaunchKernelGGL((k_delta<bf16_t, 128>), g, dim3(256), 0, st, (const bf16_t*)O, (const bf16_t*)dO, delta, rows);
+    if (d.D == 64) { MuseProf prof_("k_delta", st); hipLaunchKernelGGL((k_delta<bf16_t, 64>), g, dim3(256), 0, st, (const bf16_t*)O, (const bf16_t*)dO, delta, rows); }
+    else { MuseProf prof_("k_delta", st); hipLaunchKernelGGL((k_delta<bf16_t, 128>), g, dim3(256), 0, st, (const bf16_t*)O, (const bf16_t*)dO, delta, rows); }
   } else {
-    if (d.D == 64) hipLaunchKernelGGL((k_delta<float, 64>), g, dim3(256), 0, st, (const float*)O, (const float*)dO, delta, rows);
-    else hipLaunchKernelGGL((k_delta<float, 128>), g, dim3(256), 0, st, (const float*)O, (const float*)dO, delta, rows);
+    if (d.D == 64) { MuseProf prof_("k_delta", st); hipLaunchKernelGGL((k_delta<float, 64>), g, dim3(256), 0, st, (const float*)O, (const float*)dO, delta, rows); }
+    else { MuseProf prof_("k_delta", st); hipLaunchKernelGGL((k_delta<float, 128>), g, dim3(256), 0, st, (const float*)O, (const float*)dO, delta, rows); }
   }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
@@ -285,11 +285,11 @@ int muse_launch_attn_bwd(const MuseDims& d, int Bs, const void* Q, const void* K
   dim3 gq((d.N + 63) / 64, d.Hq, d.B), gk((d.N + 63) / 64, d.Hkv, d.B);
   const float *q = (const float*)Q, *k = (const float*)K, *v = (const float*)V, *g = (const float*)dO;
   if (d.D == 64) {
-    hipLaunchKernelGGL((k_attn_bwd_dq_simple<float, 64>), gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale);
-    hipLaunchKernelGGL((k_attn_bwd_dkv_simple<float, 64>), gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale);
+    { MuseProf prof_("k_attn_bwd_dq_simple", st); hipLaunchKernelGGL((k_attn_bwd_dq_simple<float, 64>), gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale); }
+    { MuseProf prof_("k_attn_bwd_dkv_simple", st); hipLaunchKernelGGL((k_attn_bwd_dkv_simple<float, 64>), gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale); }
   } else {
-    hipLaunchKernelGGL((k_attn_bwd_dq_simple<float, 128>), gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale);
-    hipLaunchKernelGGL((k_attn_bwd_dkv_simple<float, 128>), gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale);
+    { MuseProf prof_("k_attn_bwd_dq_simple", st); hipLaunchKernelGGL((k_attn_bwd_dq_simple<float, 128>), gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale); }
+    { MuseProf prof_("k_attn_bwd_dkv_simple", st); hipLaunchKernelGGL((k_attn_bwd_dkv_simple<float, 128>), gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale); }
   }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
@@ -298,8 +298,8 @@ int muse_launch_attn_bwd(const MuseDims& d, int Bs, const void* Q, const void* K
 int muse_launch_cast(const float* src, void* dst, size_t n, int dst_dtype, float mul, hipStream_t st) {
   unsigned blocks = (unsigned)((n + 1023) / 1024 > 65535 * 16 ? 65535 * 16 : (n + 1023) / 1024);
   if (blocks == 0) return MUSE_OK;
-  if (dst_dtype == MUSE_DTYPE_BF16) hipLaunchKernelGGL(k_cast<bf16_t>, dim3(blocks), dim3(256), 0, st, src, (bf16_t*)dst, n, mul);
-  else hipLaunchKernelGGL(k_cast<float>, dim3(blocks), dim3(256), 0, st, src, (float*)dst, n, mul);
+  if (dst_dtype == MUSE_DTYPE_BF16) { MuseProf prof_("k_cast", st); hipLaunchKernelGGL(k_cast<bf16_t>, dim3(blocks), dim3(256), 0, st, src, (bf16_t*)dst, n, mul); }
+  else { MuseProf prof_("k_cast", st); hipLaunchKernelGGL(k_cast<float>, dim3(blocks), dim3(256), 0, st, src, (float*)dst, n, mul); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
@@ -307,7 +307,7 @@ int muse_launch_cast(const float* src, void* dst, size_t n, int dst_dtype, float
 int muse_launch_fill(float* dst, size_t n, float v, hipStream_t st) {
   unsigned blocks = (unsigned)((n + 1023) / 1024 > 65535 * 16 ? 65535 * 16 : (n + 1023) / 1024);
   if (blocks == 0) return MUSE_OK;
-  hipLaunchKernelGGL(k_fill, dim3(blocks), dim3(256), 0, st, dst, n, v);
+  { MuseProf prof_("k_fill", st); hipLaunchKernelGGL(k_fill, dim3(blocks), dim3(256), 0, st, dst, n, v); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
@@ -315,7 +315,7 @@ int muse_launch_fill(float* dst, size_t n, float v, hipStream_t st) {
 int muse_launch_fill_i32(int32_t* dst, size_t n, int32_t v, hipStream_t st) {
   unsigned blocks = (unsigned)((n + 1023) / 1024 > 65535 * 16 ? 65535 * 16 : (n + 1023) / 1024);
   if (blocks == 0) return MUSE_OK;
-  hipLaunchKernelGGL(k_fill_i32, dim3(blocks), dim3(256), 0, st, dst, n, v);
+  { MuseProf prof_("k_fill_i32", st); hipLaunchKernelGGL(k_fill_i32, dim3(blocks), dim3(256), 0, st, dst, n, v); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }

@@ -91,6 +91,16 @@ struct MuseDims {
     if (hipGetLastError() != hipSuccess) return MUSE_ERR_HIP; \
   } while (0)
 
+// Optional per-kernel timing (diagnostics for the benchmark): when enabled through
+// muse_profile_enable, every launch is bracketed by HIP events on its stream.
+struct MuseProf {
+  MuseProf(const char* name, hipStream_t st);
+  ~MuseProf();
+  const char* name_;
+  hipStream_t st_;
+  int slot_;
+};
+
 // ---- stage launchers (one per translation unit) ------------------------------------------
 // kmeans.hip
 size_t muse_cluster_ws_bytes(const MuseDims& d);

@@ -531,9 +531,9 @@ int muse_ff_prepare(const MuseDims& d, const T* K, const T* V, const int32_t* aq
   if ((rc = muse_launch_bucket(aq, HQ, N, d.Bs, d.Cq, w.perm_q, w.off_q, st))) return rc;
   const int CPR = D * (int)sizeof(T) / 16;
   dim3 g((unsigned)(((size_t)N * CPR + 255) / 256), HK);
-  hipLaunchKernelGGL(k_gather_rows<T>, g, dim3(256), 0, st, K, w.perm_k, (T*)w.Ks, N, D);
-  hipLaunchKernelGGL(k_gather_rows<T>, g, dim3(256), 0, st, V, w.perm_k, (T*)w.Vs, N, D);
-  hipLaunchKernelGGL(k_tile_schedule, dim3((HQ * d.nb + 63) / 64), dim3(64), 0, st, w.off_q, w.tile_off, HQ, d.nb, d.Cq);
+  { MuseProf prof_("k_gather_rows", st); hipLaunchKernelGGL(k_gather_rows<T>, g, dim3(256), 0, st, K, w.perm_k, (T*)w.Ks, N, D); }
+  { MuseProf prof_("k_gather_rows", st); hipLaunchKernelGGL(k_gather_rows<T>, g, dim3(256), 0, st, V, w.perm_k, (T*)w.Vs, N, D); }
+  { MuseProf prof_("k_tile_schedule", st); hipLaunchKernelGGL(k_tile_schedule, dim3((HQ * d.nb + 63) / 64), dim3(64), 0, st, w.off_q, w.tile_off, HQ, d.nb, d.Cq); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
@@ -545,13 +545,13 @@ int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0
   dim3 gl((N + 255) / 256, hn);
   dim3 gs(d.Ck, (d.Cq + 31) / 32, hn);
   if (d.D == 64) {
-    hipLaunchKernelGGL((k_tilt_logits<T, 64>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale);
-    hipLaunchKernelGGL((k_summaries<T, 64>), gs, dim3(256), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
-                       w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv);
+    { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 64>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
+    { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 64>), gs, dim3(256), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
+                       w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   } else {
-    hipLaunchKernelGGL((k_tilt_logits<T, 128>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale);
-    hipLaunchKernelGGL((k_summaries<T, 128>), gs, dim3(256), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
-                       w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv);
+    { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 128>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
+    { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 128>), gs, dim3(256), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
+                       w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
@@ -568,9 +568,9 @@ template <typename T, int D, int RCAP>
 void launch_ff_fwd(const MuseDims& d, const T* Q, const float* qc, FFWorkspace& w, int32_t* selc, int32_t* selb, int h0,
                    int hn, hipStream_t st) {
   dim3 g(d.Bs / 32 + d.Cq + 1, d.nb - 1, hn);
-  hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, (const T*)w.Ks, (const T*)w.Vs, w.L,
+  { MuseProf prof_("k_farfield_fwd", st); hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, (const T*)w.Ks, (const T*)w.Vs, w.L,
                      w.s_mu, w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q, w.off_k, w.tile_off, w.ff_acc,
-                     w.ff_ml, selc, selb, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale);
+                     w.ff_ml, selc, selb, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
 }
 
 template <typename T, int D>

@@ -722,26 +722,26 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
   if ((rc = muse_launch_fill(w.g_s_k, (size_t)hn * cells * D, 0.f, st))) return rc;
   if ((rc = muse_launch_fill(w.g_s_v, (size_t)hn * cells * D, 0.f, st))) return rc;
   dim3 gt(d.Bs / 32 + d.Cq + 1, NBm, hn);
-  hipLaunchKernelGGL((k_ff_bwd_dq<T, D>), gt, dim3(64), 0, st, Q, dO, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu,
+  { MuseProf prof_("k_ff_bwd_dq", st); hipLaunchKernelGGL((k_ff_bwd_dq<T, D>), gt, dim3(64), 0, st, Q, dO, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu,
                      w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q, w.off_k, w.tile_off, LSE, w.delta,
-                     w.selmask, selc, selb, w.dQacc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale);
-  hipLaunchKernelGGL((k_ff_bwd_cells<T, D>), dim3(W, NBm * d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.A_mu, w.A_k, w.A_v,
+                     w.selmask, selc, selb, w.dQacc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
+  { MuseProf prof_("k_ff_bwd_cells", st); hipLaunchKernelGGL((k_ff_bwd_cells<T, D>), dim3(W, NBm * d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.A_mu, w.A_k, w.A_v,
                      w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.g_A_c, w.g_A_k, w.g_A_v, h0, d.N, d.nb, d.Cq, d.Ck,
-                     d.scale);
+                     d.scale); }
   if (d.r > 0)
-    hipLaunchKernelGGL((k_c2_cells<T, D>), dim3(W, d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.s_mu, w.s_k, w.s_v, w.perm_q,
+    { MuseProf prof_("k_c2_cells", st); hipLaunchKernelGGL((k_c2_cells<T, D>), dim3(W, d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.s_mu, w.s_k, w.s_v, w.perm_q,
                        w.off_q, LSE, w.delta, w.selmask, selc, selb, w.g_s_c, w.g_s_k, w.g_s_v, h0, d.N, d.nb, d.Cq,
-                       d.Ck, d.r, d.k2e, d.scale);
+                       d.Ck, d.r, d.k2e, d.scale); }
   {
     size_t chains = (size_t)d.Cq * d.Ck;
     size_t total = (size_t)hn * chains * (D / 4);
-    hipLaunchKernelGGL(k_cell_scan_bwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w.s_mu, w.A_mu, w.g_A_c,
-                       w.g_A_k, w.g_A_v, w.g_s_c, w.g_s_k, w.g_s_v, hn, NBm, chains, D);
+    { MuseProf prof_("k_cell_scan_bwd", st); hipLaunchKernelGGL(k_cell_scan_bwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w.s_mu, w.A_mu, w.g_A_c,
+                       w.g_A_k, w.g_A_v, w.g_s_c, w.g_s_k, w.g_s_v, hn, NBm, chains, D); }
   }
   const int G_ = d.Hq / d.Hkv;
-  hipLaunchKernelGGL((k_cells_to_keys<T, D>), dim3(d.Ck, NBm, hn / G_), dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs,
+  { MuseProf prof_("k_cells_to_keys", st); hipLaunchKernelGGL((k_cells_to_keys<T, D>), dim3(d.Ck, NBm, hn / G_), dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs,
                      qc, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq,
-                     d.Hkv, d.scale);
+                     d.Hkv, d.scale); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
@@ -761,7 +761,7 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
   if (d.nb > 1) {
     const int W = (d.Ck + 31) / 32;
     if (d.r > 0) {
-      hipLaunchKernelGGL(k_selmask, dim3((unsigned)((nq * W + 255) / 256)), dim3(256), 0, st, selc, w.selmask, nq, d.r, W);
+      { MuseProf prof_("k_selmask", st); hipLaunchKernelGGL(k_selmask, dim3((unsigned)((nq * W + 255) / 256)), dim3(256), 0, st, selc, w.selmask, nq, d.r, W); }
     } else {
       if ((rc = muse_launch_fill_i32((int32_t*)w.selmask, nq * W, 0, st))) return rc;
     }
@@ -776,20 +776,20 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
     if (d.r > 0) {
       dim3 g((d.Ck + 31) / 32, d.nb - 1, HK);
       if (D == 64)
-        hipLaunchKernelGGL((k_c3_keys<T, 64>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
+        { MuseProf prof_("k_c3_keys", st); hipLaunchKernelGGL((k_c3_keys<T, 64>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
                            w.selmask, selc, selb, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.r, d.k2e, d.Hq, d.Hkv,
-                           d.scale);
+                           d.scale); }
       else
-        hipLaunchKernelGGL((k_c3_keys<T, 128>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
+        { MuseProf prof_("k_c3_keys", st); hipLaunchKernelGGL((k_c3_keys<T, 128>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
                            w.selmask, selc, selb, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.r, d.k2e, d.Hq, d.Hkv,
-                           d.scale);
+                           d.scale); }
       MUSE_LAUNCH_CHECK();
     }
   }
   {
     dim3 g((unsigned)(((size_t)N * (D / 4) + 255) / 256), HK);
-    hipLaunchKernelGGL(k_scatter_rows, g, dim3(256), 0, st, w.dKs, w.perm_k, w.dKacc, N, D);
-    hipLaunchKernelGGL(k_scatter_rows, g, dim3(256), 0, st, w.dVs, w.perm_k, w.dVacc, N, D);
+    { MuseProf prof_("k_scatter_rows", st); hipLaunchKernelGGL(k_scatter_rows, g, dim3(256), 0, st, w.dKs, w.perm_k, w.dKacc, N, D); }
+    { MuseProf prof_("k_scatter_rows", st); hipLaunchKernelGGL(k_scatter_rows, g, dim3(256), 0, st, w.dVs, w.perm_k, w.dVacc, N, D); }
     MUSE_LAUNCH_CHECK();
   }
   if ((rc = muse_launch_attn_bwd(d, d.Bs, Q, K, V, dO, LSE, w.delta, w.dQacc, w.dKacc, w.dVacc, st))) return rc;

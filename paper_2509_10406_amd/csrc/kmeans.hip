@@ -310,28 +310,28 @@ int cluster_impl(const MuseDims& d, const T* X, int H, int C, const int32_t* ini
   int32_t* perm = (int32_t*)w;    w += align256((size_t)heads * N * sizeof(int32_t));
   int32_t* off = (int32_t*)w;
   if (init_idx) {
-    hipLaunchKernelGGL(k_init_centroids<T>, dim3(C, heads), dim3(64), 0, st, X, init_idx, cent, N, D, C);
+    { MuseProf prof_("k_init_centroids", st); hipLaunchKernelGGL(k_init_centroids<T>, dim3(C, heads), dim3(64), 0, st, X, init_idx, cent, N, D, C); }
     MUSE_LAUNCH_CHECK();
   }
   for (int it = 0; it <= d.T; ++it) {
     int rows = heads * C;
-    hipLaunchKernelGGL(k_prep_centroids<T>, dim3((rows + 3) / 4), dim3(256), 0, st, cent, chat, nhc2, D, rows);
+    { MuseProf prof_("k_prep_centroids", st); hipLaunchKernelGGL(k_prep_centroids<T>, dim3((rows + 3) / 4), dim3(256), 0, st, cent, chat, nhc2, D, rows); }
     MUSE_LAUNCH_CHECK();
     if constexpr (sizeof(T) == 4) {
       dim3 g((N + 255) / 256, heads);
-      if (D == 64) hipLaunchKernelGGL(k_assign_f32<64>, g, dim3(256), 0, st, (const float*)X, (const float*)chat, nhc2, assign, N, C);
-      else hipLaunchKernelGGL(k_assign_f32<128>, g, dim3(256), 0, st, (const float*)X, (const float*)chat, nhc2, assign, N, C);
+      if (D == 64) { MuseProf prof_("k_assign_f32", st); hipLaunchKernelGGL(k_assign_f32<64>, g, dim3(256), 0, st, (const float*)X, (const float*)chat, nhc2, assign, N, C); }
+      else { MuseProf prof_("k_assign_f32", st); hipLaunchKernelGGL(k_assign_f32<128>, g, dim3(256), 0, st, (const float*)X, (const float*)chat, nhc2, assign, N, C); }
     } else {
       constexpr int PT = 2;
       dim3 g((N + 4 * 32 * PT - 1) / (4 * 32 * PT), heads);
-      if (D == 64) hipLaunchKernelGGL((k_assign_bf16<64, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C);
-      else hipLaunchKernelGGL((k_assign_bf16<128, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C);
+      if (D == 64) { MuseProf prof_("k_assign_bf16", st); hipLaunchKernelGGL((k_assign_bf16<64, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C); }
+      else { MuseProf prof_("k_assign_bf16", st); hipLaunchKernelGGL((k_assign_bf16<128, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C); }
     }
     MUSE_LAUNCH_CHECK();
     if (it == d.T) break;
     int rc = muse_launch_bucket(assign, heads, N, d.Bs, C, perm, off, st);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_update<T>, dim3((rows + 3) / 4), dim3(256), 0, st, X, perm, off, cent, N, D, C, d.nb, rows);
+    { MuseProf prof_("k_update", st); hipLaunchKernelGGL(k_update<T>, dim3((rows + 3) / 4), dim3(256), 0, st, X, perm, off, cent, N, D, C, d.nb, rows); }
     MUSE_LAUNCH_CHECK();
   }
   return MUSE_OK;
@@ -355,7 +355,7 @@ int muse_launch_bucket(const int32_t* assign, int heads, int N, int Bs, int C, i
     MUSE_HIP_CHECK(hipFuncSetAttribute((const void*)k_bucket, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
     attr_set = true;
   }
-  hipLaunchKernelGGL(k_bucket, dim3(N / Bs, heads), dim3(1024), lds, st, assign, perm, off, N, Bs, C);
+  { MuseProf prof_("k_bucket", st); hipLaunchKernelGGL(k_bucket, dim3(N / Bs, heads), dim3(1024), lds, st, assign, perm, off, N, Bs, C); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }

@@ -1,6 +1,13 @@
 // C-ABI entry points of libmuse: argument validation on the host, workspace carving, stage order.
 #include <math.h>
 
+#include <stdio.h>
+#include <string.h>
+
+#include <map>
+#include <string>
+#include <vector>
+
 #include "common.h"
 
 // farfield.hip
@@ -12,6 +19,25 @@ int muse_run_fwd(const MuseDims& d, const void* Q, const void* K, const void* V,
 int muse_run_bwd(const MuseDims& d, const void* Q, const void* K, const void* V, const void* O, const float* LSE,
                  const void* dO, const float* qc, const int32_t* aq, const int32_t* ak, const int32_t* selc,
                  const int32_t* selb, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, hipStream_t st);
+
+// ---- per-kernel timing (diagnostics) ---------------------------------------------------------
+namespace {
+struct ProfRec { const char* name; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+}  // namespace
+
+MuseProf::MuseProf(const char* name, hipStream_t st) : name_(name), st_(st), slot_(-1) {
+  if (!g_prof_on) return;
+  ProfRec r{name, nullptr, nullptr};
+  if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+  (void)hipEventRecord(r.a, st);
+  g_prof.push_back(r);
+  slot_ = (int)g_prof.size() - 1;
+}
+MuseProf::~MuseProf() {
+  if (slot_ >= 0) (void)hipEventRecord(g_prof[slot_].b, st_);
+}
 
 namespace {
 
@@ -186,6 +212,34 @@ int exact_attn_bwd(const muse_params* p, const void* Q, const void* K, const voi
     if ((rc = muse_launch_cast(aq, dQ, q * d.D, d.grad_dtype, 1.f, st))) return rc;
     if ((rc = muse_launch_cast(ak, dK, k * d.D, d.grad_dtype, 1.f, st))) return rc;
     if ((rc = muse_launch_cast(av, dV, k * d.D, d.grad_dtype, 1.f, st))) return rc;
+  }
+  return MUSE_OK;
+}
+
+int muse_profile_enable(int on) {
+  for (auto& r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  g_prof.clear();
+  g_prof_on = on != 0;
+  return MUSE_OK;
+}
+
+int muse_profile_report(char* buf, size_t cap) {
+  if (!buf || cap == 0) return MUSE_ERR_INVALID_ARG;
+  std::map<std::string, std::pair<int, double>> agg;
+  for (auto& r : g_prof) {
+    if (hipEventSynchronize(r.b) != hipSuccess) return MUSE_ERR_HIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return MUSE_ERR_HIP;
+    auto& e = agg[r.name];
+    e.first += 1;
+    e.second += ms;
+  }
+  size_t used = 0;
+  buf[0] = 0;
+  for (auto& kv : agg) {
+    int n = snprintf(buf + used, cap - used, "%s %d %.6f\n", kv.first.c_str(), kv.second.first, kv.second.second);
+    if (n < 0 || (size_t)n >= cap - used) return MUSE_ERR_INVALID_ARG;
+    used += (size_t)n;
   }
   return MUSE_OK;
 }
