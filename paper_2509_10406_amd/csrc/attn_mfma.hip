@@ -376,7 +376,147 @@ __global__ void __launch_bounds__(256) k_flash_bwd_dkv(const bf16_t* __restrict_
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Retrieval backward (Sec. 3.3 "Exact retrieval", gradient w.r.t. keys and values): one wave per
+// retrieved (key cluster, key block) pair.  `hits` lists the queries that retrieved the pair (the
+// inverse index: pair -> queries); they are gathered 32 at a time into LDS and the pair is treated as a
+// dense attention-backward block on the matrix cores, the keys of the pair being the MFMA columns.
+//   hit = n | g << 22  (query position, query head inside the KV group)
+// Results are added to the bucketed-order gradient rows this wave owns.
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
+                                                  const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
+                                                  const float* __restrict__ LSE, const float* __restrict__ delta,
+                                                  const int32_t* __restrict__ off_k, const int32_t* __restrict__ pair_off,
+                                                  const uint32_t* __restrict__ hits, float* __restrict__ dKs,
+                                                  float* __restrict__ dVs, size_t hit_cap, int N, int nb, int Ck,
+                                                  int Hq, int Hkv, float scale, float scale_log2e) {
+  constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
+  __shared__ __attribute__((aligned(16))) bf16_t qs[32][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gs[32][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][32 + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][32 + 8];
+  __shared__ __attribute__((aligned(16))) float lse_s[32];
+  __shared__ __attribute__((aligned(16))) float dl_s[32];
+  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
+  const int G_ = Hq / Hkv;
+  const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
+  const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
+  const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
+  const int hlo = po[0], hhi = po[1];
+  if (klo == khi || hlo == hhi) return;
+  const uint32_t* hh = hits + (size_t)hk * hit_cap;
+  for (int k0 = klo; k0 < khi; k0 += 32) {
+    const int mk = k0 + col;
+    const bool kvalid = mk < khi;
+    const size_t krow = ((size_t)hk * N + (kvalid ? mk : klo)) * D;
+    bf16x8_t kf[KS], vf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      kf[s] = *reinterpret_cast<const bf16x8_t*>(Ks + krow + 16 * s + 8 * half);
+      vf[s] = *reinterpret_cast<const bf16x8_t*>(Vs + krow + 16 * s + 8 * half);
+    }
+    f32x16_t dk[DT], dv[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { dk[t][e] = 0.f; dv[t][e] = 0.f; }
+    for (int h0 = hlo; h0 < hhi; h0 += 32) {
+      __syncthreads();
+      for (int c = lane; c < 32 * CPR; c += 64) {
+        const int row = c / CPR, cc = c % CPR;
+        const int hi_ = h0 + row < hhi ? h0 + row : hhi - 1;
+        const uint32_t hit = hh[hi_];
+        const size_t qn = (hqbase + (hit >> 22)) * N + (hit & 0x3fffffu);
+        uint4 qv = *reinterpret_cast<const uint4*>(Q + qn * D + cc * 8);
+        uint4 gv = *reinterpret_cast<const uint4*>(dO + qn * D + cc * 8);
+        *reinterpret_cast<uint4*>(&qs[row][cc * 8]) = qv;
+        *reinterpret_cast<uint4*>(&gs[row][cc * 8]) = gv;
+        const bf16_t* pq = reinterpret_cast<const bf16_t*>(&qv);
+        const bf16_t* pg = reinterpret_cast<const bf16_t*>(&gv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { qt_[cc * 8 + e][row] = pq[e]; gt_[cc * 8 + e][row] = pg[e]; }
+        if (cc == 0) {
+          const bool ok2 = h0 + row < hhi;
+          lse_s[row] = ok2 ? LSE[qn] * 1.4426950408889634f : __builtin_huge_valf();  // +inf -> p = 0
+          dl_s[row] = delta[qn];
+        }
+      }
+      __syncthreads();
+      f32x16_t s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+      for (int x = 0; x < KS; ++x) {
+        bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&qs[col][16 * x + 8 * half]);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[x], s, 0, 0, 0);
+        bf16x8_t ag = *reinterpret_cast<const bf16x8_t*>(&gs[col][16 * x + 8 * half]);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, vf[x], dp, 0, 0, 0);
+      }
+      f32x16_t pr;
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        float4 l4 = *reinterpret_cast<const float4*>(&lse_s[8 * gq + 4 * half]);
+        float4 d4 = *reinterpret_cast<const float4*>(&dl_s[8 * gq + 4 * half]);
+        float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int e = 4 * gq + u;
+          float p = fast_exp2(fmaf(s[e], scale_log2e, -lv[u]));
+          p = kvalid ? p : 0.f;
+          pr[e] = p;
+          s[e] = p * (dp[e] - dv4[u]);
+        }
+      }
+#pragma unroll
+      for (int G = 0; G < 2; ++G) {
+        bf16x8_t pf = pack8(pr, 2 * G, 2 * G + 1);
+        bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+          bf16x8_t ag = ld_tr8(&gt_[32 * t + col][0], 16 * G, half);
+          dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, pf, dv[t], 0, 0, 0);
+          bf16x8_t aq = ld_tr8(&qt_[32 * t + col][0], 16 * G, half);
+          dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, df, dk[t], 0, 0, 0);
+        }
+      }
+    }
+    if (kvalid) {
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const size_t o = ((size_t)hk * N + mk) * D + 32 * t + 8 * g + 4 * half;
+          float4 a = *reinterpret_cast<float4*>(dKs + o), c = *reinterpret_cast<float4*>(dVs + o);
+          a.x += scale * dk[t][4 * g + 0]; a.y += scale * dk[t][4 * g + 1];
+          a.z += scale * dk[t][4 * g + 2]; a.w += scale * dk[t][4 * g + 3];
+          c.x += dv[t][4 * g + 0]; c.y += dv[t][4 * g + 1]; c.z += dv[t][4 * g + 2]; c.w += dv[t][4 * g + 3];
+          *reinterpret_cast<float4*>(dKs + o) = a;
+          *reinterpret_cast<float4*>(dVs + o) = c;
+        }
+    }
+  }
+}
+
 }  // namespace
+
+int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
+                         const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
+                         const uint32_t* hits, size_t hit_cap, float* dKs, float* dVs, hipStream_t st) {
+  dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv);
+  float sl = d.scale * 1.4426950408889634f;
+  if (d.D == 64)
+    { MuseProf prof_("k_c3_pairs", st); hipLaunchKernelGGL(k_c3_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks,
+                       (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dKs, dVs, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.scale, sl); }
+  else
+    { MuseProf prof_("k_c3_pairs", st); hipLaunchKernelGGL(k_c3_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks,
+                       (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dKs, dVs, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.scale, sl); }
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
 
 int muse_launch_attn_fwd_mfma(const MuseDims& d, int Bs, const void* Q, const void* K, const void* V,
                               const float* ff, void* O, float* LSE, hipStream_t st) {

@@ -81,111 +81,112 @@ __global__ void __launch_bounds__(256) k_tilt_logits(const T* __restrict__ Ks, c
 }
 
 // ------------------------------------------------------------------------------------------
-// per-block summaries (Eq. 4-6) + exclusive accumulation.  grid (Ck, ceil(Cq/32), hc); 4 waves share
-// the key cluster j (its keys staged in LDS), each wave owns 8 query clusters; lanes = head dim.
-// s_*[b] is the summary of key block b, A_*[b] the accumulation of blocks 0..b (what query block
-// b+1 sees), b = 0..nb-2.
+// per-block summaries (Eq. 4-6) + exclusive accumulation on fp32 MFMA.  One wave per (key cluster j,
+// tile of 32 query clusters, 64-wide slice of the head dim); it walks the key blocks in order and
+// keeps the running accumulation in registers.  For a segment (j, b):
+//   E^T[key, i] = exp(L[i, key] - max_i)         (B operand, row pattern over the keys)
+//   Ksum^T[d, i] += K^T[d, key] E^T[key, i]      (A operand = bucketed K rows, column pattern)
+// s_*[b] is the summary of key block b, A_*[b] the accumulation of blocks 0..b (what query block b+1
+// sees), b = 0..nb-2.
 // ------------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ void __launch_bounds__(256) k_summaries(const T* __restrict__ Ks, const T* __restrict__ Vs,
-                                                    const float* __restrict__ L, const int32_t* __restrict__ off_k,
-                                                    float* __restrict__ s_mu, float* __restrict__ s_k,
-                                                    float* __restrict__ s_v, float* __restrict__ A_mu,
-                                                    float* __restrict__ A_k, float* __restrict__ A_v, int h0, int N,
-                                                    int nb, int Cq, int Ck, int Hq, int Hkv) {
-  constexpr int IPW = 8, DL = D / 64;
-  constexpr int KC = 4096 / D;  // keys staged per step (LDS budget)
-  __shared__ float ks[KC][D];
-  __shared__ float vs[KC][D];
-  __shared__ float eb[4][64];
+__global__ void __launch_bounds__(64) k_summaries(const T* __restrict__ Ks, const T* __restrict__ Vs,
+                                                   const float* __restrict__ L, const int32_t* __restrict__ off_k,
+                                                   float* __restrict__ s_mu, float* __restrict__ s_k,
+                                                   float* __restrict__ s_v, float* __restrict__ A_mu,
+                                                   float* __restrict__ A_k, float* __restrict__ A_v, int h0, int N,
+                                                   int nb, int Cq, int Ck, int Hq, int Hkv) {
+  constexpr int DS = D / 64;  // slices of the head dim
   const int j = blockIdx.x, hl = blockIdx.z, hq = h0 + hl;
   const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
-  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-  const int i0 = (blockIdx.y * 4 + wave) * IPW;
+  const int it = blockIdx.y / DS, d0 = (blockIdx.y % DS) * 64;
+  const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
+  const int i = it * 32 + col;
+  const bool iv = i < Cq;
+  const int ic = iv ? i : Cq - 1;
   const int NBm = nb - 1;
   const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  const float* Li = L + ((size_t)hl * Cq + ic) * N;
+  const T* Kh = Ks + (size_t)hk * N * D + d0 + col;
+  const T* Vh = Vs + (size_t)hk * N * D + d0 + col;
 
-  float Amx[IPW], AS[IPW], Aak[IPW][DL], Aav[IPW][DL];
-#pragma unroll
-  for (int q = 0; q < IPW; ++q) {
-    Amx[q] = MUSE_NEG_INF; AS[q] = 0.f;
-#pragma unroll
-    for (int x = 0; x < DL; ++x) { Aak[q][x] = 0.f; Aav[q][x] = 0.f; }
-  }
+  float Amx = MUSE_NEG_INF, AS = 0.f;
+  f32x16_t Aak[2], Aav[2];
+  Aak[0] = zero16(); Aak[1] = zero16(); Aav[0] = zero16(); Aav[1] = zero16();
   for (int b = 0; b < NBm; ++b) {
     const int lo = ok[b * Ck + j], hi = ok[b * Ck + j + 1];
-    float mx[IPW], S[IPW], ak[IPW][DL], av[IPW][DL];
+    float mx = MUSE_NEG_INF, S = 0.f;
+    f32x16_t ak[2], av[2];
+    ak[0] = zero16(); ak[1] = zero16(); av[0] = zero16(); av[1] = zero16();
+    for (int c0 = lo; c0 < hi; c0 += 16) {
+      float lg[2][4];
+      float cm = MUSE_NEG_INF;
 #pragma unroll
-    for (int q = 0; q < IPW; ++q) {
-      mx[q] = MUSE_NEG_INF; S[q] = 0.f;
+      for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int x = 0; x < DL; ++x) { ak[q][x] = 0.f; av[q][x] = 0.f; }
-    }
-    for (int c0 = lo; c0 < hi; c0 += KC) {
-      const int cn = min(KC, hi - c0);
-      __syncthreads();
-      for (int t = threadIdx.x; t < cn * (D / 4); t += 256) {
-        int kk = t / (D / 4), d4 = (t % (D / 4)) * 4;
-        ld4(Ks, ((size_t)hk * N + c0 + kk) * D + d4, &ks[kk][d4]);
-        ld4(Vs, ((size_t)hk * N + c0 + kk) * D + d4, &vs[kk][d4]);
-      }
-      __syncthreads();
+        for (int t = 0; t < 4; ++t) {
+          int p = c0 + 8 * u + 4 * half + t;
+          lg[u][t] = p < hi ? Li[p] : MUSE_NEG_INF;
+          cm = fmaxf(cm, lg[u][t]);
+        }
+      cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
+      const float nm = fmaxf(mx, cm);
+      const float resc = __expf(mx - nm);
+      mx = nm;
+      S *= resc;
 #pragma unroll
-      for (int q = 0; q < IPW; ++q) {
-        const int i = i0 + q;
-        if (i >= Cq) continue;
-        float lg = lane < cn ? L[((size_t)hl * Cq + i) * N + c0 + lane] : MUSE_NEG_INF;
-        float nm = fmaxf(mx[q], wave_max(lg));
-        float resc = __expf(mx[q] - nm);
-        float e = __expf(lg - nm);
-        S[q] = S[q] * resc + wave_sum(e);
-        mx[q] = nm;
-        eb[wave][lane] = e;
+      for (int x = 0; x < 2; ++x)
 #pragma unroll
-        for (int x = 0; x < DL; ++x) { ak[q][x] *= resc; av[q][x] *= resc; }
-        for (int kk = 0; kk < cn; ++kk) {
-          float ee = eb[wave][kk];
+        for (int e = 0; e < 16; ++e) { ak[x][e] *= resc; av[x][e] *= resc; }
 #pragma unroll
-          for (int x = 0; x < DL; ++x) {
-            ak[q][x] = fmaf(ee, ks[kk][lane + 64 * x], ak[q][x]);
-            av[q][x] = fmaf(ee, vs[kk][lane + 64 * x], av[q][x]);
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const float e = __expf(lg[u][t] - nm);
+          S += e;
+          int p = c0 + 8 * u + 4 * half + t;
+          p = p < hi ? p : hi - 1;
+#pragma unroll
+          for (int x = 0; x < 2; ++x) {
+            ak[x] = mfma32(Elem<T>::ld(Kh, (size_t)p * D + 32 * x), e, ak[x]);
+            av[x] = mfma32(Elem<T>::ld(Vh, (size_t)p * D + 32 * x), e, av[x]);
           }
         }
-      }
     }
+    S += __shfl_xor(S, 32, 64);
+    const bool empty = hi == lo;
+    if (!empty) {  // running sums relative to the running max
+      const float nm = fmaxf(Amx, mx);
+      const float ra = __expf(Amx - nm), rb = __expf(mx - nm);
+      AS = AS * ra + S * rb;
 #pragma unroll
-    for (int q = 0; q < IPW; ++q) {
-      const int i = i0 + q;
-      if (i >= Cq) continue;
-      const size_t cell = (((size_t)hl * NBm + b) * Cq + i) * Ck + j;
-      const bool empty = hi == lo;
-      float inv = empty ? 0.f : 1.f / S[q];
-      if (lane == 0) s_mu[cell] = empty ? MUSE_NEG_INF : mx[q] + __logf(S[q]);
+      for (int x = 0; x < 2; ++x)
 #pragma unroll
-      for (int x = 0; x < DL; ++x) {
-        s_k[cell * D + lane + 64 * x] = ak[q][x] * inv;
-        s_v[cell * D + lane + 64 * x] = av[q][x] * inv;
-      }
-      if (!empty) {  // running sums relative to the running max
-        float nm = fmaxf(Amx[q], mx[q]);
-        float ra = __expf(Amx[q] - nm), rb = __expf(mx[q] - nm);
-        AS[q] = AS[q] * ra + S[q] * rb;
-#pragma unroll
-        for (int x = 0; x < DL; ++x) {
-          Aak[q][x] = Aak[q][x] * ra + ak[q][x] * rb;
-          Aav[q][x] = Aav[q][x] * ra + av[q][x] * rb;
+        for (int e = 0; e < 16; ++e) {
+          Aak[x][e] = Aak[x][e] * ra + ak[x][e] * rb;
+          Aav[x][e] = Aav[x][e] * ra + av[x][e] * rb;
         }
-        Amx[q] = nm;
-      }
-      const bool aempty = AS[q] == 0.f;
-      float ainv = aempty ? 0.f : 1.f / AS[q];
-      if (lane == 0) A_mu[cell] = aempty ? MUSE_NEG_INF : Amx[q] + __logf(AS[q]);
-#pragma unroll
-      for (int x = 0; x < DL; ++x) {
-        A_k[cell * D + lane + 64 * x] = Aak[q][x] * ainv;
-        A_v[cell * D + lane + 64 * x] = Aav[q][x] * ainv;
-      }
+      Amx = nm;
     }
+    if (!iv) continue;
+    const size_t cell = (((size_t)hl * NBm + b) * Cq + i) * Ck + j;
+    const float inv = empty ? 0.f : 1.f / S;
+    const bool aempty = AS == 0.f;
+    const float ainv = aempty ? 0.f : 1.f / AS;
+    if (half == 0 && d0 == 0) {
+      s_mu[cell] = empty ? MUSE_NEG_INF : mx + __logf(S);
+      A_mu[cell] = aempty ? MUSE_NEG_INF : Amx + __logf(AS);
+    }
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const size_t o = cell * D + d0 + 32 * x + 8 * g + 4 * half;
+        *reinterpret_cast<float4*>(s_k + o) = make_float4(ak[x][4 * g] * inv, ak[x][4 * g + 1] * inv, ak[x][4 * g + 2] * inv, ak[x][4 * g + 3] * inv);
+        *reinterpret_cast<float4*>(s_v + o) = make_float4(av[x][4 * g] * inv, av[x][4 * g + 1] * inv, av[x][4 * g + 2] * inv, av[x][4 * g + 3] * inv);
+        *reinterpret_cast<float4*>(A_k + o) = make_float4(Aak[x][4 * g] * ainv, Aak[x][4 * g + 1] * ainv, Aak[x][4 * g + 2] * ainv, Aak[x][4 * g + 3] * ainv);
+        *reinterpret_cast<float4*>(A_v + o) = make_float4(Aav[x][4 * g] * ainv, Aav[x][4 * g + 1] * ainv, Aav[x][4 * g + 2] * ainv, Aav[x][4 * g + 3] * ainv);
+      }
   }
 }
 
@@ -491,6 +492,11 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
     size_t W = (d.Ck + 31) / 32;
     w->delta = (float*)take(HQ * N * 4);
     w->selmask = (uint32_t*)take(HQ * N * W * 4);
+    w->pairmask = (uint32_t*)take(HQ * N * W * 4 * (size_t)(d.nb > 1 ? d.nb - 1 : 1));
+    w->pair_cnt = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
+    w->pair_off = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
+    w->hit_cap = (size_t)(d.Hq / d.Hkv) * N * (size_t)(d.r > 0 ? d.r : 1) * d.k2e;
+    w->hits = (uint32_t*)take(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * d.k2e * 4);
     w->dKs = (float*)take(HK * N * D * 4);
     w->dVs = (float*)take(HK * N * D * 4);
     if (d.grad_dtype != MUSE_DTYPE_FP32) {
@@ -543,14 +549,14 @@ template <typename T>
 int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0, int hn, hipStream_t st) {
   const int N = d.N;
   dim3 gl((N + 255) / 256, hn);
-  dim3 gs(d.Ck, (d.Cq + 31) / 32, hn);
+  dim3 gs(d.Ck, ((d.Cq + 31) / 32) * (d.D / 64), hn);
   if (d.D == 64) {
     { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 64>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
-    { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 64>), gs, dim3(256), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
+    { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 64>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
                        w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   } else {
     { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 128>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
-    { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 128>), gs, dim3(256), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
+    { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 128>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
                        w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   }
   MUSE_LAUNCH_CHECK();

@@ -31,6 +31,24 @@ __global__ void __launch_bounds__(256) k_selmask(const int32_t* __restrict__ sel
   mask[t] = m;
 }
 
+// bit j of pairmask[hq][b'][j/32][n]: query n of head hq retrieved the pair (key cluster j, key block b').
+// Word-major so that the owner of (b', tile of 32 clusters) reads consecutive queries.  Zero on entry.
+__global__ void __launch_bounds__(256) k_pairmask(const int32_t* __restrict__ selc, const int32_t* __restrict__ selb,
+                                                   uint32_t* __restrict__ pmask, int HQ, int N, int r, int k2e, int NBm,
+                                                   int W) {
+  size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (size_t)HQ * N * r) return;
+  const int slot = (int)(t % r);
+  const size_t q = t / r;
+  const size_t hq = q / N, n = q % N;
+  const int j = selc[q * r + slot];
+  if (j < 0) return;
+  for (int u = 0; u < k2e; ++u) {
+    const int bp = selb[(q * r + slot) * k2e + u];
+    if (bp >= 0) atomicOr(&pmask[((hq * NBm + bp) * W + (j >> 5)) * N + n], 1u << (j & 31));
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // dQ of the far field, one wave per query tile (same tiling as the forward kernel)
 // ------------------------------------------------------------------------------------------
@@ -632,10 +650,9 @@ template <typename T, int D>
 __global__ void __launch_bounds__(64) k_c3_keys(const T* __restrict__ Q, const T* __restrict__ dO,
                                                  const T* __restrict__ Ks, const T* __restrict__ Vs,
                                                  const float* __restrict__ LSE, const float* __restrict__ delta,
-                                                 const uint32_t* __restrict__ selmask, const int32_t* __restrict__ selc,
-                                                 const int32_t* __restrict__ selb, const int32_t* __restrict__ off_k,
+                                                 const uint32_t* __restrict__ pmask, const int32_t* __restrict__ off_k,
                                                  float* __restrict__ dKs, float* __restrict__ dVs, int N, int Bs, int nb,
-                                                 int Ck, int r, int k2e, int Hq, int Hkv, float scale) {
+                                                 int Ck, int Hq, int Hkv, float scale) {
   __shared__ uint32_t hits[kHitCap];
   __shared__ uint32_t sorted[kHitCap];
   __shared__ int start[33], cursor[32];
@@ -655,18 +672,7 @@ __global__ void __launch_bounds__(64) k_c3_keys(const T* __restrict__ Q, const T
     const size_t hq = (size_t)hqbase + g;
     for (int n0 = (bp + 1) * Bs; n0 < N; n0 += 64) {
       const int n = n0 + lane;
-      uint32_t mw = n < N ? selmask[(hq * N + n) * W + jt] : 0u;
-      // keep only the clusters whose retrieved blocks include bp
-      uint32_t keep = 0;
-      while (mw) {
-        const int jl = __ffs((int)mw) - 1;
-        mw &= mw - 1;
-        const int j = jt * 32 + jl;
-        for (int t = 0; t < r; ++t)
-          if (selc[(hq * N + n) * r + t] == j)
-            for (int u = 0; u < k2e; ++u)
-              if (selb[((hq * N + n) * r + t) * k2e + u] == bp) keep |= 1u << jl;
-      }
+      uint32_t keep = n < N ? pmask[((hq * (nb - 1) + bp) * W + jt) * N + n] : 0u;
       // append (n, g, jl) for every kept bit, in lane order
       int cnt = __popc(keep);
       unsigned long long any = __ballot(cnt > 0);
@@ -696,6 +702,78 @@ __global__ void __launch_bounds__(64) k_c3_keys(const T* __restrict__ Q, const T
   __syncthreads();
   c3_sort_hits(hits, nh, sorted, start, cursor);
   c3_flush<T, D>(sorted, start, Q, dO, Ks, Vs, LSE, delta, ok, dKs, dVs, hk, hqbase, N, Ck, bp, jt, scale);
+}
+
+// ------------------------------------------------------------------------------------------
+// inverse index of the retrieval: for every (kv head, key block b', key cluster j) the list of
+// queries (of all heads of the group, ascending) that retrieved the pair.  Pass 1 (FILL = false)
+// counts, k_pair_scan turns counts into offsets, pass 2 (FILL = true) writes the lists in order.
+// One wave per (b', tile of 32 clusters); hit = n | g << 22.
+// ------------------------------------------------------------------------------------------
+template <bool FILL>
+__global__ void __launch_bounds__(64) k_pair_hits(const uint32_t* __restrict__ pmask, int32_t* __restrict__ pair_cnt,
+                                                   const int32_t* __restrict__ pair_off, uint32_t* __restrict__ hits,
+                                                   size_t hit_cap, int N, int Bs, int nb, int Ck, int Hq, int Hkv) {
+  __shared__ int cur[32];
+  const int jt = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
+  const int G_ = Hq / Hkv, W = (Ck + 31) / 32;
+  const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
+  const int lane = threadIdx.x;
+  const size_t pbase = (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + jt * 32;
+  if (lane < 32) cur[lane] = (FILL && jt * 32 + lane < Ck) ? pair_off[pbase + lane] : 0;
+  __syncthreads();
+  for (int g = 0; g < G_; ++g) {
+    const size_t hq = hqbase + g;
+    const uint32_t* colw = pmask + ((hq * NBm + bp) * W + jt) * N;
+    for (int n0 = (bp + 1) * Bs; n0 < N; n0 += 64) {
+      const int n = n0 + lane;
+      const uint32_t word = n < N ? colw[n] : 0u;
+      if (!__ballot(word != 0u)) continue;
+      for (int jl = 0; jl < 32; ++jl) {
+        const bool has = (word >> jl) & 1u;
+        const unsigned long long bal = __ballot(has);
+        if (!bal) continue;
+        const int base = cur[jl];
+        if (FILL && has) {
+          const int rank = __popcll(bal & ((1ull << lane) - 1ull));
+          hits[(size_t)hk * hit_cap + base + rank] = (uint32_t)n | ((uint32_t)g << 22);
+        }
+        __syncthreads();
+        if (lane == 0) cur[jl] = base + __popcll(bal);
+        __syncthreads();
+      }
+    }
+  }
+  if (!FILL && lane < 32 && jt * 32 + lane < Ck) pair_cnt[pbase + lane] = cur[lane];
+}
+
+// exclusive prefix of n counts per kv head, off[n] = total
+__global__ void __launch_bounds__(1024) k_pair_scan(const int32_t* __restrict__ cnt, int32_t* __restrict__ off, int n) {
+  __shared__ int wsum[16];
+  const int hk = blockIdx.x, lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+  const int32_t* c = cnt + (size_t)hk * (n + 1);
+  int32_t* o = off + (size_t)hk * (n + 1);
+  const int per = (n + 1023) / 1024;
+  int mine = 0;
+  for (int u = 0; u < per; ++u) {
+    int i = threadIdx.x * per + u;
+    if (i < n) mine += c[i];
+  }
+  int incl = mine;
+  for (int d = 1; d < 64; d <<= 1) {
+    int v = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += v;
+  }
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  int base = 0;
+  for (int w = 0; w < wave; ++w) base += wsum[w];
+  int run = base + incl - mine;
+  for (int u = 0; u < per; ++u) {
+    int i = threadIdx.x * per + u;
+    if (i < n) { o[i] = run; run += c[i]; }
+  }
+  if (threadIdx.x == 1023) o[n] = run;
 }
 
 // rows back to sequence order: dst[perm[p]] = src[p]
@@ -774,15 +852,26 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
       if (rc) return rc;
     }
     if (d.r > 0) {
+      const size_t pm = (size_t)HQ * (d.nb - 1) * W * N;
+      if ((rc = muse_launch_fill_i32((int32_t*)w.pairmask, pm, 0, st))) return rc;
+      { MuseProf prof_("k_pairmask", st); hipLaunchKernelGGL(k_pairmask, dim3((unsigned)((nq * d.r + 255) / 256)), dim3(256), 0, st, selc, selb, w.pairmask, HQ, N, d.r, d.k2e, d.nb - 1, W); }
+      MUSE_LAUNCH_CHECK();
       dim3 g((d.Ck + 31) / 32, d.nb - 1, HK);
-      if (D == 64)
+      if (sizeof(T) == 2) {
+        const int npair = (d.nb - 1) * d.Ck;
+        { MuseProf prof_("k_pair_hits", st); hipLaunchKernelGGL(k_pair_hits<false>, g, dim3(64), 0, st, w.pairmask, w.pair_cnt, w.pair_off, w.hits, w.hit_cap, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv); }
+        { MuseProf prof_("k_pair_scan", st); hipLaunchKernelGGL(k_pair_scan, dim3(HK), dim3(1024), 0, st, w.pair_cnt, w.pair_off, npair); }
+        { MuseProf prof_("k_pair_hits", st); hipLaunchKernelGGL(k_pair_hits<true>, g, dim3(64), 0, st, w.pairmask, w.pair_cnt, w.pair_off, w.hits, w.hit_cap, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv); }
+        MUSE_LAUNCH_CHECK();
+        if ((rc = muse_launch_c3_pairs(d, Q, dO, w.Ks, w.Vs, LSE, w.delta, w.off_k, w.pair_off, w.hits, w.hit_cap, w.dKs,
+                                       w.dVs, st)))
+          return rc;
+      } else if (D == 64)
         { MuseProf prof_("k_c3_keys", st); hipLaunchKernelGGL((k_c3_keys<T, 64>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
-                           w.selmask, selc, selb, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.r, d.k2e, d.Hq, d.Hkv,
-                           d.scale); }
+                           w.pairmask, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv, d.scale); }
       else
         { MuseProf prof_("k_c3_keys", st); hipLaunchKernelGGL((k_c3_keys<T, 128>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
-                           w.selmask, selc, selb, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.r, d.k2e, d.Hq, d.Hkv,
-                           d.scale); }
+                           w.pairmask, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv, d.scale); }
       MUSE_LAUNCH_CHECK();
     }
   }

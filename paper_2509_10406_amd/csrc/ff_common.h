@@ -63,6 +63,10 @@ struct FFWorkspace {
   // backward only, all heads
   float* delta;
   uint32_t* selmask;
+  uint32_t* pairmask;  // [HQ][nb-1][W][N]
+  int32_t *pair_cnt, *pair_off;  // inverse index of the retrieval: (kv head, key block, key cluster) -> hits
+  uint32_t* hits;
+  size_t hit_cap;                // hits per kv head
   float *dKs, *dVs;            // fp32 gradients in bucketed key order
   float *dQacc, *dKacc, *dVacc;  // fp32 gradients in sequence order (alias the outputs when they are fp32)
   // per chunk of `hc` query heads
@@ -83,7 +87,9 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
              2 * ff_al(HK * N * D * es) + ff_al(HQ * N * (D + 2) * 4);
   if (bwd) {
     size_t W = (d.Ck + 31) / 32;
-    b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + 2 * ff_al(HK * N * D * 4);
+    b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + ff_al(HQ * N * W * 4 * (size_t)(d.nb > 1 ? d.nb - 1 : 1)) +
+         2 * ff_al(HK * N * D * 4) + 2 * ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) +
+         ff_al(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * d.k2e * 4);
     if (d.grad_dtype != MUSE_DTYPE_FP32) b += ff_al(HQ * N * D * 4) + 2 * ff_al(HK * N * D * 4);
   }
   return b;
@@ -103,3 +109,8 @@ int muse_ff_prepare(const MuseDims& d, const T* K, const T* V, const int32_t* aq
                     hipStream_t st);
 template <typename T>
 int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0, int hn, hipStream_t st);
+
+// attn_mfma.hip
+int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
+                         const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
+                         const uint32_t* hits, size_t hit_cap, float* dKs, float* dVs, hipStream_t st);
