@@ -44,6 +44,12 @@ enum {
 };
 
 enum { MUSE_DTYPE_FP32 = 0, MUSE_DTYPE_BF16 = 1 };
+/* MUSE_FLAG_KEEP_FWD_STATE: muse_fwd lays its workspace out as muse_bwd does and leaves the bucketing and
+ * the summaries there; muse_bwd called with the same flag, the same params and the SAME, untouched
+ * workspace reuses them instead of recomputing (the usual save-for-backward of a training step).  Needs a
+ * workspace that holds all heads at once (the `preferred` size of MUSE_WS_BWD), else
+ * MUSE_ERR_WORKSPACE_TOO_SMALL. */
+enum { MUSE_FLAG_KEEP_FWD_STATE = 1 };
 enum { MUSE_WS_CLUSTER = 0, MUSE_WS_FWD = 1, MUSE_WS_BWD = 2, MUSE_WS_EXACT_FWD = 3, MUSE_WS_EXACT_BWD = 4 };
 
 typedef struct {
@@ -59,7 +65,7 @@ typedef struct {
   int32_t dtype;        /* MUSE_DTYPE_*: element type of Q,K,V,O,dO */
   int32_t grad_dtype;   /* element type of dQ,dK,dV: MUSE_DTYPE_FP32 or the same as dtype */
   int32_t causal;       /* must be 1 (the paper defines the causal form only) */
-  uint32_t flags;       /* reserved, must be 0 */
+  uint32_t flags;       /* MUSE_FLAG_* bits, others must be 0 */
   float scale;          /* logit scale applied to q (Eq. 1 has none written); 0 -> 1/sqrt(D) */
 } muse_params;
 

@@ -12,7 +12,7 @@
 //     lane holds 8 consecutive k for k-slot-half l/32.  For the second contraction the 8 k-slots of
 //     half h over 16 keys are keys {4h..4h+3} and {8+4h..8+4h+3}: a permutation applied to both
 //     operands, which a contraction does not see.
-#include "common.h"
+#include "ff_common.h"
 
 namespace {
 
@@ -389,7 +389,7 @@ __global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, c
                                                   const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
                                                   const float* __restrict__ LSE, const float* __restrict__ delta,
                                                   const int32_t* __restrict__ off_k, const int32_t* __restrict__ pair_off,
-                                                  const uint32_t* __restrict__ hits, float* __restrict__ dKs,
+                                                  const uint2* __restrict__ hits, float* __restrict__ dKs,
                                                   float* __restrict__ dVs, size_t hit_cap, int N, int nb, int Ck,
                                                   int Hq, int Hkv, float scale, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
@@ -408,7 +408,7 @@ __global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, c
   const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
   const int hlo = po[0], hhi = po[1];
   if (klo == khi || hlo == hhi) return;
-  const uint32_t* hh = hits + (size_t)hk * hit_cap;
+  const uint2* hh = hits + (size_t)hk * hit_cap;
   for (int k0 = klo; k0 < khi; k0 += 32) {
     const int mk = k0 + col;
     const bool kvalid = mk < khi;
@@ -429,7 +429,7 @@ __global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, c
       for (int c = lane; c < 32 * CPR; c += 64) {
         const int row = c / CPR, cc = c % CPR;
         const int hi_ = h0 + row < hhi ? h0 + row : hhi - 1;
-        const uint32_t hit = hh[hi_];
+        const uint32_t hit = hh[hi_].x;
         const size_t qn = (hqbase + (hit >> 22)) * N + (hit & 0x3fffffu);
         uint4 qv = *reinterpret_cast<const uint4*>(Q + qn * D + cc * 8);
         uint4 gv = *reinterpret_cast<const uint4*>(dO + qn * D + cc * 8);
@@ -501,11 +501,232 @@ __global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, c
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Retrieval forward (Sec. 3.3 "Exact retrieval"): one wave per retrieved pair; the queries that
+// retrieved it are the MFMA columns (32 at a time, rows read straight from Q), its keys the rows.
+// Writes, per (query, slot), the partial softmax state over the keys of the pair:
+//   part[(qn*R2 + su)][0..D) = sum_m exp(l_m - max) v_m,  [D] = max (natural log units),  [D+1] = sum.
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(64) k_ret_fwd_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Ks,
+                                                       const bf16_t* __restrict__ Vs, const int32_t* __restrict__ off_k,
+                                                       const int32_t* __restrict__ pair_off, const uint2* __restrict__ hits,
+                                                       float* __restrict__ part, size_t hit_cap, int N, int nb, int Ck,
+                                                       int Hq, int Hkv, int R2, float scale_log2e) {
+  constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
+  __shared__ __attribute__((aligned(16))) bf16_t vt[D][32 + 8];
+  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
+  const int G_ = Hq / Hkv;
+  const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
+  const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
+  const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
+  const int hlo = po[0], hhi = po[1];
+  if (klo == khi || hlo == hhi) return;
+  const uint2* hh = hits + (size_t)hk * hit_cap;
+  for (int h0 = hlo; h0 < hhi; h0 += 32) {
+    const bool hvalid = h0 + col < hhi;
+    const uint2 hit = hh[hvalid ? h0 + col : hhi - 1];
+    const size_t qn = (hqbase + (hit.x >> 22)) * N + (hit.x & 0x3fffffu);
+    bf16x8_t qf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qf[s] = *reinterpret_cast<const bf16x8_t*>(Q + qn * D + 16 * s + 8 * half);
+    f32x16_t o[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
+    float m = MUSE_NEG_INF, l = 0.f;
+    for (int k0 = klo; k0 < khi; k0 += 32) {
+      __syncthreads();
+      for (int c = lane; c < 32 * CPR; c += 64) {
+        const int row = c / CPR, cc = c % CPR;
+        const int kr = k0 + row < khi ? k0 + row : khi - 1;
+        uint4 v = *reinterpret_cast<const uint4*>(Vs + ((size_t)hk * N + kr) * D + cc * 8);
+        const bf16_t* pv = reinterpret_cast<const bf16_t*>(&v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vt[cc * 8 + e][row] = pv[e];
+      }
+      __syncthreads();
+      const int kr = k0 + col < khi ? k0 + col : khi - 1;
+      f32x16_t s;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
+      for (int x = 0; x < KS; ++x) {
+        bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(Ks + ((size_t)hk * N + kr) * D + 16 * x + 8 * half);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[x], s, 0, 0, 0);
+      }
+      float tmax = MUSE_NEG_INF;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int kg = k0 + 8 * (e / 4) + 4 * half + (e % 4);
+        if (kg >= khi) s[e] = MUSE_NEG_INF;
+        tmax = fmaxf(tmax, s[e]);
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float mn = fmaxf(m, tmax * scale_log2e);
+      const float alpha = fast_exp2(m - mn);  // every tile holds at least one key, so mn is finite
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float p = fast_exp2(fmaf(s[e], scale_log2e, -mn));
+        s[e] = p;
+        psum += p;
+      }
+      l = l * alpha + psum;
+      m = mn;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+#pragma unroll
+      for (int G = 0; G < 2; ++G) {
+        bf16x8_t pf = pack8(s, 2 * G, 2 * G + 1);
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+          bf16x8_t a = ld_tr8(&vt[32 * t + col][0], 16 * G, half);
+          o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, o[t], 0, 0, 0);
+        }
+      }
+    }
+    l += __shfl_xor(l, 32, 64);
+    if (hvalid) {
+      float* pr = part + (qn * R2 + hit.y) * (size_t)(D + 4);
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(pr + 32 * t + 8 * g + 4 * half) =
+              make_float4(o[t][4 * g], o[t][4 * g + 1], o[t][4 * g + 2], o[t][4 * g + 3]);
+      if (half == 0) { pr[D] = m * 0.6931471805599453f; pr[D + 1] = l; }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Retrieval backward, gradient w.r.t. the queries: same tiling as the forward pair kernel;
+// dqpart[(qn*R2 + su)][0..D) = scale * sum_m dl_m k_m over the keys of the pair.
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
+                                                          const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
+                                                          const float* __restrict__ LSE, const float* __restrict__ delta,
+                                                          const int32_t* __restrict__ off_k,
+                                                          const int32_t* __restrict__ pair_off,
+                                                          const uint2* __restrict__ hits, float* __restrict__ dqpart,
+                                                          size_t hit_cap, int N, int nb, int Ck, int Hq, int Hkv, int R2,
+                                                          float scale, float scale_log2e) {
+  constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
+  __shared__ __attribute__((aligned(16))) bf16_t kt_[D][32 + 8];
+  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
+  const int G_ = Hq / Hkv;
+  const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
+  const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
+  const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
+  const int hlo = po[0], hhi = po[1];
+  if (klo == khi || hlo == hhi) return;
+  const uint2* hh = hits + (size_t)hk * hit_cap;
+  for (int h0 = hlo; h0 < hhi; h0 += 32) {
+    const bool hvalid = h0 + col < hhi;
+    const uint2 hit = hh[hvalid ? h0 + col : hhi - 1];
+    const size_t qn = (hqbase + (hit.x >> 22)) * N + (hit.x & 0x3fffffu);
+    bf16x8_t qf[KS], gf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      qf[s] = *reinterpret_cast<const bf16x8_t*>(Q + qn * D + 16 * s + 8 * half);
+      gf[s] = *reinterpret_cast<const bf16x8_t*>(dO + qn * D + 16 * s + 8 * half);
+    }
+    const float lse2 = LSE[qn] * 1.4426950408889634f, dl = delta[qn];
+    f32x16_t dq[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dq[t][e] = 0.f;
+    for (int k0 = klo; k0 < khi; k0 += 32) {
+      __syncthreads();
+      for (int c = lane; c < 32 * CPR; c += 64) {
+        const int row = c / CPR, cc = c % CPR;
+        const int kr = k0 + row < khi ? k0 + row : khi - 1;
+        uint4 v = *reinterpret_cast<const uint4*>(Ks + ((size_t)hk * N + kr) * D + cc * 8);
+        const bf16_t* pv = reinterpret_cast<const bf16_t*>(&v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) kt_[cc * 8 + e][row] = pv[e];
+      }
+      __syncthreads();
+      const int kr = k0 + col < khi ? k0 + col : khi - 1;
+      f32x16_t s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+      for (int x = 0; x < KS; ++x) {
+        bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(Ks + ((size_t)hk * N + kr) * D + 16 * x + 8 * half);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[x], s, 0, 0, 0);
+        bf16x8_t av = *reinterpret_cast<const bf16x8_t*>(Vs + ((size_t)hk * N + kr) * D + 16 * x + 8 * half);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, gf[x], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int kg = k0 + 8 * (e / 4) + 4 * half + (e % 4);
+        float p = fast_exp2(fmaf(s[e], scale_log2e, -lse2));
+        p = kg < khi ? p : 0.f;
+        s[e] = p * (dp[e] - dl);
+      }
+#pragma unroll
+      for (int G = 0; G < 2; ++G) {
+        bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+          bf16x8_t a = ld_tr8(&kt_[32 * t + col][0], 16 * G, half);
+          dq[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, df, dq[t], 0, 0, 0);
+        }
+      }
+    }
+    if (hvalid) {
+      float* pr = dqpart + (qn * R2 + hit.y) * (size_t)D;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(pr + 32 * t + 8 * g + 4 * half) =
+              make_float4(scale * dq[t][4 * g], scale * dq[t][4 * g + 1], scale * dq[t][4 * g + 2], scale * dq[t][4 * g + 3]);
+    }
+  }
+}
+
 }  // namespace
+
+int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, const void* Vs, const int32_t* off_k,
+                              const int32_t* pair_off, const uint2* hits, size_t hit_cap, float* part, hipStream_t st) {
+  dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv);
+  float sl = d.scale * 1.4426950408889634f;
+  if (d.D == 64)
+    { MuseProf prof_("k_ret_fwd_pairs", st); hipLaunchKernelGGL(k_ret_fwd_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)Ks, (const bf16_t*)Vs, off_k, pair_off, hits, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, sl); }
+  else
+    { MuseProf prof_("k_ret_fwd_pairs", st); hipLaunchKernelGGL(k_ret_fwd_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)Ks, (const bf16_t*)Vs, off_k, pair_off, hits, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, sl); }
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
+
+int muse_launch_ret_bwd_dq_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
+                                 const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
+                                 const uint2* hits, size_t hit_cap, float* dqpart, hipStream_t st) {
+  dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv);
+  float sl = d.scale * 1.4426950408889634f;
+  if (d.D == 64)
+    { MuseProf prof_("k_ret_bwd_dq_pairs", st); hipLaunchKernelGGL(k_ret_bwd_dq_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks, (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dqpart, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, d.scale, sl); }
+  else
+    { MuseProf prof_("k_ret_bwd_dq_pairs", st); hipLaunchKernelGGL(k_ret_bwd_dq_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks, (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dqpart, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, d.scale, sl); }
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
 
 int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
                          const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
-                         const uint32_t* hits, size_t hit_cap, float* dKs, float* dVs, hipStream_t st) {
+                         const uint2* hits, size_t hit_cap, float* dKs, float* dVs, hipStream_t st) {
   dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64)

@@ -78,6 +78,7 @@ struct MuseDims {
   int B, Hq, Hkv, N, D, Cq, Ck, r, k2, k2e, Bs, nb, T;
   int dtype, grad_dtype;
   float scale;
+  bool keep_state;  // MUSE_FLAG_KEEP_FWD_STATE
 };
 
 #define MUSE_HIP_CHECK(expr)                      \

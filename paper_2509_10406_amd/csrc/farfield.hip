@@ -415,7 +415,7 @@ __global__ void __launch_bounds__(64) k_farfield_fwd(
           o[u / 4][4 * (u % 4) + 2] = o[u / 4][4 * (u % 4) + 2] * a + p * v4.z;
           o[u / 4][4 * (u % 4) + 3] = o[u / 4][4 * (u % 4) + 3] * a + p * v4.w;
         }
-      } else {  // component 3: exact attention over the keys of the retrieved (cluster, block)
+      } else if (sizeof(T) == 4) {  // component 3 (fp32 inputs; bf16 inputs use the pair kernels on the matrix cores)
         const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
         for (int p_ = klo; p_ < khi; ++p_) {
           const size_t krow = ((size_t)hk * N + p_) * D + 4 * half;
@@ -488,15 +488,19 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
   w->Vs = take(HK * N * D * es);
   w->ff_acc = (float*)take(HQ * N * (D + 2) * 4);
   w->ff_ml = w->ff_acc + HQ * N * D;
+  {
+    size_t W = (d.Ck + 31) / 32, NBm = d.nb > 1 ? d.nb - 1 : 1, R2 = (size_t)(d.r > 0 ? d.r : 1) * d.k2e;
+    w->pairmask = (uint32_t*)take(HQ * N * W * 4 * NBm);
+    w->pair_cnt = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
+    w->pair_off = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
+    w->hit_cap = (size_t)(d.Hq / d.Hkv) * N * R2;
+    w->hits = (uint2*)take(HQ * N * R2 * 8);
+    w->ret_part = (float*)take(HQ * N * R2 * (D + 4) * 4);
+  }
   if (bwd) {
     size_t W = (d.Ck + 31) / 32;
     w->delta = (float*)take(HQ * N * 4);
     w->selmask = (uint32_t*)take(HQ * N * W * 4);
-    w->pairmask = (uint32_t*)take(HQ * N * W * 4 * (size_t)(d.nb > 1 ? d.nb - 1 : 1));
-    w->pair_cnt = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
-    w->pair_off = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
-    w->hit_cap = (size_t)(d.Hq / d.Hkv) * N * (size_t)(d.r > 0 ? d.r : 1) * d.k2e;
-    w->hits = (uint32_t*)take(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * d.k2e * 4);
     w->dKs = (float*)take(HK * N * D * 4);
     w->dVs = (float*)take(HK * N * D * 4);
     if (d.grad_dtype != MUSE_DTYPE_FP32) {
@@ -604,6 +608,12 @@ int run_fwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const f
       MUSE_LAUNCH_CHECK();
     }
   }
+  if (d.nb > 1 && d.r > 0 && sizeof(T) == 2) {
+    // exact retrieval (Sec. 3.3): inverse index pair -> queries, one dense MFMA block per retrieved pair
+    if ((rc = muse_ff_build_inverse_index(d, selc, selb, w, true, st))) return rc;
+    if ((rc = muse_launch_ret_fwd_pairs(d, Q, w.Ks, w.Vs, w.off_k, w.pair_off, w.hits, w.hit_cap, w.ret_part, st))) return rc;
+    if ((rc = muse_launch_merge_ret(d, selb, w.ret_part, w.ff_acc, w.ff_ml, st))) return rc;
+  }
   return muse_launch_attn_fwd(d, d.Bs, Q, K, V, w.ff_acc, O, LSE, st);
 }
 
@@ -620,7 +630,8 @@ int muse_run_fwd(const MuseDims& d, const void* Q, const void* K, const void* V,
                  const int32_t* ak, void* O, float* LSE, int32_t* selc, int32_t* selb, void* ws, size_t ws_bytes,
                  hipStream_t st) {
   FFWorkspace w;
-  if (!muse_ff_carve(d, false, ws, ws_bytes, &w, nullptr, nullptr, nullptr)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  if (!muse_ff_carve(d, d.keep_state, ws, ws_bytes, &w, nullptr, nullptr, nullptr)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  if (d.keep_state && w.hc < d.B * d.Hq) return MUSE_ERR_WORKSPACE_TOO_SMALL;
   // block-0 queries and r = 0 leave the selection outputs untouched by the tile kernel: pad them
   if (d.r > 0) {
     size_t nq = (size_t)d.B * d.Hq * d.N;

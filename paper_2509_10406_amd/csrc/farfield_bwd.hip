@@ -31,24 +31,6 @@ __global__ void __launch_bounds__(256) k_selmask(const int32_t* __restrict__ sel
   mask[t] = m;
 }
 
-// bit j of pairmask[hq][b'][j/32][n]: query n of head hq retrieved the pair (key cluster j, key block b').
-// Word-major so that the owner of (b', tile of 32 clusters) reads consecutive queries.  Zero on entry.
-__global__ void __launch_bounds__(256) k_pairmask(const int32_t* __restrict__ selc, const int32_t* __restrict__ selb,
-                                                   uint32_t* __restrict__ pmask, int HQ, int N, int r, int k2e, int NBm,
-                                                   int W) {
-  size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= (size_t)HQ * N * r) return;
-  const int slot = (int)(t % r);
-  const size_t q = t / r;
-  const size_t hq = q / N, n = q % N;
-  const int j = selc[q * r + slot];
-  if (j < 0) return;
-  for (int u = 0; u < k2e; ++u) {
-    const int bp = selb[(q * r + slot) * k2e + u];
-    if (bp >= 0) atomicOr(&pmask[((hq * NBm + bp) * W + (j >> 5)) * N + n], 1u << (j & 31));
-  }
-}
-
 // ------------------------------------------------------------------------------------------
 // dQ of the far field, one wave per query tile (same tiling as the forward kernel)
 // ------------------------------------------------------------------------------------------
@@ -60,8 +42,8 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
     const float* __restrict__ A_k, const float* __restrict__ A_v, const int32_t* __restrict__ perm_q,
     const int32_t* __restrict__ off_q, const int32_t* __restrict__ off_k, const int32_t* __restrict__ tile_off,
     const float* __restrict__ LSE, const float* __restrict__ delta, const uint32_t* __restrict__ selmask,
-    const int32_t* __restrict__ selc, const int32_t* __restrict__ selb, float* __restrict__ dQ, int h0, int N, int nb,
-    int Cq, int Ck, int r, int k2e, int Hq, int Hkv, float scale) {
+    const int32_t* __restrict__ selc, const int32_t* __restrict__ selb, const float* __restrict__ dqpart,
+    float* __restrict__ dQ, int h0, int N, int nb, int Cq, int Ck, int r, int k2e, int Hq, int Hkv, float scale) {
   constexpr int U = D / 8, DT = D / 32;
   const int hl = blockIdx.z, hq = h0 + hl;
   const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
@@ -171,7 +153,7 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
           dq[u / 4][4 * (u % 4) + 0] += dlg * k4[u].x; dq[u / 4][4 * (u % 4) + 1] += dlg * k4[u].y;
           dq[u / 4][4 * (u % 4) + 2] += dlg * k4[u].z; dq[u / 4][4 * (u % 4) + 3] += dlg * k4[u].w;
         }
-      } else {
+      } else if (sizeof(T) == 4) {
         const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
         for (int p_ = klo; p_ < khi; ++p_) {
           const size_t krow = ((size_t)hk * N + p_) * D + 4 * half;
@@ -201,12 +183,26 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
     }
   }
   if (!valid) return;
+  float res[U][4];
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int x = 0; x < 4; ++x) res[u][x] = scale * dq[u / 4][4 * (u % 4) + x];
+  if (sizeof(T) == 2) {  // retrieval part, computed per retrieved pair (already scaled)
+    for (int su = 0; su < r * k2e; ++su) {
+      if (selb[qn * r * k2e + su] < 0) continue;
+      const float* pp = dqpart + (qn * r * k2e + su) * D + 4 * half;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float4 v = *reinterpret_cast<const float4*>(pp + 8 * u);
+        res[u][0] += v.x; res[u][1] += v.y; res[u][2] += v.z; res[u][3] += v.w;
+      }
+    }
+  }
   float* out = dQ + qn * D + 4 * half;
 #pragma unroll
   for (int u = 0; u < U; ++u)
-    *reinterpret_cast<float4*>(out + 8 * u) =
-        make_float4(scale * dq[u / 4][4 * (u % 4)], scale * dq[u / 4][4 * (u % 4) + 1],
-                    scale * dq[u / 4][4 * (u % 4) + 2], scale * dq[u / 4][4 * (u % 4) + 3]);
+    *reinterpret_cast<float4*>(out + 8 * u) = make_float4(res[u][0], res[u][1], res[u][2], res[u][3]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -704,78 +700,6 @@ __global__ void __launch_bounds__(64) k_c3_keys(const T* __restrict__ Q, const T
   c3_flush<T, D>(sorted, start, Q, dO, Ks, Vs, LSE, delta, ok, dKs, dVs, hk, hqbase, N, Ck, bp, jt, scale);
 }
 
-// ------------------------------------------------------------------------------------------
-// inverse index of the retrieval: for every (kv head, key block b', key cluster j) the list of
-// queries (of all heads of the group, ascending) that retrieved the pair.  Pass 1 (FILL = false)
-// counts, k_pair_scan turns counts into offsets, pass 2 (FILL = true) writes the lists in order.
-// One wave per (b', tile of 32 clusters); hit = n | g << 22.
-// ------------------------------------------------------------------------------------------
-template <bool FILL>
-__global__ void __launch_bounds__(64) k_pair_hits(const uint32_t* __restrict__ pmask, int32_t* __restrict__ pair_cnt,
-                                                   const int32_t* __restrict__ pair_off, uint32_t* __restrict__ hits,
-                                                   size_t hit_cap, int N, int Bs, int nb, int Ck, int Hq, int Hkv) {
-  __shared__ int cur[32];
-  const int jt = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
-  const int G_ = Hq / Hkv, W = (Ck + 31) / 32;
-  const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
-  const int lane = threadIdx.x;
-  const size_t pbase = (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + jt * 32;
-  if (lane < 32) cur[lane] = (FILL && jt * 32 + lane < Ck) ? pair_off[pbase + lane] : 0;
-  __syncthreads();
-  for (int g = 0; g < G_; ++g) {
-    const size_t hq = hqbase + g;
-    const uint32_t* colw = pmask + ((hq * NBm + bp) * W + jt) * N;
-    for (int n0 = (bp + 1) * Bs; n0 < N; n0 += 64) {
-      const int n = n0 + lane;
-      const uint32_t word = n < N ? colw[n] : 0u;
-      if (!__ballot(word != 0u)) continue;
-      for (int jl = 0; jl < 32; ++jl) {
-        const bool has = (word >> jl) & 1u;
-        const unsigned long long bal = __ballot(has);
-        if (!bal) continue;
-        const int base = cur[jl];
-        if (FILL && has) {
-          const int rank = __popcll(bal & ((1ull << lane) - 1ull));
-          hits[(size_t)hk * hit_cap + base + rank] = (uint32_t)n | ((uint32_t)g << 22);
-        }
-        __syncthreads();
-        if (lane == 0) cur[jl] = base + __popcll(bal);
-        __syncthreads();
-      }
-    }
-  }
-  if (!FILL && lane < 32 && jt * 32 + lane < Ck) pair_cnt[pbase + lane] = cur[lane];
-}
-
-// exclusive prefix of n counts per kv head, off[n] = total
-__global__ void __launch_bounds__(1024) k_pair_scan(const int32_t* __restrict__ cnt, int32_t* __restrict__ off, int n) {
-  __shared__ int wsum[16];
-  const int hk = blockIdx.x, lane = threadIdx.x % 64, wave = threadIdx.x / 64;
-  const int32_t* c = cnt + (size_t)hk * (n + 1);
-  int32_t* o = off + (size_t)hk * (n + 1);
-  const int per = (n + 1023) / 1024;
-  int mine = 0;
-  for (int u = 0; u < per; ++u) {
-    int i = threadIdx.x * per + u;
-    if (i < n) mine += c[i];
-  }
-  int incl = mine;
-  for (int d = 1; d < 64; d <<= 1) {
-    int v = __shfl_up(incl, d, 64);
-    if (lane >= d) incl += v;
-  }
-  if (lane == 63) wsum[wave] = incl;
-  __syncthreads();
-  int base = 0;
-  for (int w = 0; w < wave; ++w) base += wsum[w];
-  int run = base + incl - mine;
-  for (int u = 0; u < per; ++u) {
-    int i = threadIdx.x * per + u;
-    if (i < n) { o[i] = run; run += c[i]; }
-  }
-  if (threadIdx.x == 1023) o[n] = run;
-}
-
 // rows back to sequence order: dst[perm[p]] = src[p]
 __global__ void __launch_bounds__(256) k_scatter_rows(const float* __restrict__ src, const int32_t* __restrict__ perm,
                                                        float* __restrict__ dst, int N, int D) {
@@ -802,7 +726,7 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
   dim3 gt(d.Bs / 32 + d.Cq + 1, NBm, hn);
   { MuseProf prof_("k_ff_bwd_dq", st); hipLaunchKernelGGL((k_ff_bwd_dq<T, D>), gt, dim3(64), 0, st, Q, dO, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu,
                      w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q, w.off_k, w.tile_off, LSE, w.delta,
-                     w.selmask, selc, selb, w.dQacc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
+                     w.selmask, selc, selb, w.ret_part, w.dQacc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
   { MuseProf prof_("k_ff_bwd_cells", st); hipLaunchKernelGGL((k_ff_bwd_cells<T, D>), dim3(W, NBm * d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.A_mu, w.A_k, w.A_v,
                      w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.g_A_c, w.g_A_k, w.g_A_v, h0, d.N, d.nb, d.Cq, d.Ck,
                      d.scale); }
@@ -831,7 +755,8 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
   const int HQ = d.B * d.Hq, HK = d.B * d.Hkv, N = d.N, D = d.D;
   const size_t nq = (size_t)HQ * N, nk = (size_t)HK * N;
   int rc;
-  if ((rc = muse_ff_prepare<T>(d, K, V, aq, ak, w, st))) return rc;
+  const bool reuse = d.keep_state;  // bucketing, bucketed copies and summaries are still in the workspace
+  if (!reuse && (rc = muse_ff_prepare<T>(d, K, V, aq, ak, w, st))) return rc;
   if ((rc = muse_launch_delta(d, O, dO, w.delta, st))) return rc;
   if ((rc = muse_launch_fill(w.dQacc, nq * D, 0.f, st))) return rc;
   if ((rc = muse_launch_fill(w.dKs, nk * D, 0.f, st))) return rc;
@@ -844,35 +769,34 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
       if ((rc = muse_launch_fill_i32((int32_t*)w.selmask, nq * W, 0, st))) return rc;
     }
     MUSE_LAUNCH_CHECK();
-    for (int h0 = 0; h0 < HQ; h0 += w.hc) {
-      int hn = HQ - h0 < w.hc ? HQ - h0 : w.hc;
-      if ((rc = muse_ff_summaries<T>(d, qc, w, h0, hn, st))) return rc;
-      if (D == 64) rc = run_bwd_chunk<T, 64>(d, Q, dO, qc, LSE, selc, selb, w, h0, hn, st);
-      else rc = run_bwd_chunk<T, 128>(d, Q, dO, qc, LSE, selc, selb, w, h0, hn, st);
-      if (rc) return rc;
-    }
     if (d.r > 0) {
-      const size_t pm = (size_t)HQ * (d.nb - 1) * W * N;
-      if ((rc = muse_launch_fill_i32((int32_t*)w.pairmask, pm, 0, st))) return rc;
-      { MuseProf prof_("k_pairmask", st); hipLaunchKernelGGL(k_pairmask, dim3((unsigned)((nq * d.r + 255) / 256)), dim3(256), 0, st, selc, selb, w.pairmask, HQ, N, d.r, d.k2e, d.nb - 1, W); }
-      MUSE_LAUNCH_CHECK();
-      dim3 g((d.Ck + 31) / 32, d.nb - 1, HK);
+      // retrieval (component 3): inverse index (kept from the forward when the state is reused), then per pair
+      if (!reuse || sizeof(T) == 4)
+        if ((rc = muse_ff_build_inverse_index(d, selc, selb, w, sizeof(T) == 2, st))) return rc;
       if (sizeof(T) == 2) {
-        const int npair = (d.nb - 1) * d.Ck;
-        { MuseProf prof_("k_pair_hits", st); hipLaunchKernelGGL(k_pair_hits<false>, g, dim3(64), 0, st, w.pairmask, w.pair_cnt, w.pair_off, w.hits, w.hit_cap, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv); }
-        { MuseProf prof_("k_pair_scan", st); hipLaunchKernelGGL(k_pair_scan, dim3(HK), dim3(1024), 0, st, w.pair_cnt, w.pair_off, npair); }
-        { MuseProf prof_("k_pair_hits", st); hipLaunchKernelGGL(k_pair_hits<true>, g, dim3(64), 0, st, w.pairmask, w.pair_cnt, w.pair_off, w.hits, w.hit_cap, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv); }
-        MUSE_LAUNCH_CHECK();
         if ((rc = muse_launch_c3_pairs(d, Q, dO, w.Ks, w.Vs, LSE, w.delta, w.off_k, w.pair_off, w.hits, w.hit_cap, w.dKs,
                                        w.dVs, st)))
           return rc;
-      } else if (D == 64)
-        { MuseProf prof_("k_c3_keys", st); hipLaunchKernelGGL((k_c3_keys<T, 64>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
-                           w.pairmask, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv, d.scale); }
-      else
-        { MuseProf prof_("k_c3_keys", st); hipLaunchKernelGGL((k_c3_keys<T, 128>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
-                           w.pairmask, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv, d.scale); }
-      MUSE_LAUNCH_CHECK();
+        if ((rc = muse_launch_ret_bwd_dq_pairs(d, Q, dO, w.Ks, w.Vs, LSE, w.delta, w.off_k, w.pair_off, w.hits, w.hit_cap,
+                                               w.ret_part, st)))
+          return rc;
+      } else {
+        dim3 g((d.Ck + 31) / 32, d.nb - 1, HK);
+        if (D == 64)
+          { MuseProf prof_("k_c3_keys", st); hipLaunchKernelGGL((k_c3_keys<T, 64>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
+                             w.pairmask, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv, d.scale); }
+        else
+          { MuseProf prof_("k_c3_keys", st); hipLaunchKernelGGL((k_c3_keys<T, 128>), g, dim3(64), 0, st, Q, dO, (const T*)w.Ks, (const T*)w.Vs, LSE, w.delta,
+                             w.pairmask, w.off_k, w.dKs, w.dVs, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv, d.scale); }
+        MUSE_LAUNCH_CHECK();
+      }
+    }
+    for (int h0 = 0; h0 < HQ; h0 += w.hc) {
+      int hn = HQ - h0 < w.hc ? HQ - h0 : w.hc;
+      if (!reuse && (rc = muse_ff_summaries<T>(d, qc, w, h0, hn, st))) return rc;
+      if (D == 64) rc = run_bwd_chunk<T, 64>(d, Q, dO, qc, LSE, selc, selb, w, h0, hn, st);
+      else rc = run_bwd_chunk<T, 128>(d, Q, dO, qc, LSE, selc, selb, w, h0, hn, st);
+      if (rc) return rc;
     }
   }
   {
@@ -897,6 +821,7 @@ int muse_run_bwd(const MuseDims& d, const void* Q, const void* K, const void* V,
                  const int32_t* selb, void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, hipStream_t st) {
   FFWorkspace w;
   if (!muse_ff_carve(d, true, ws, ws_bytes, &w, dQ, dK, dV)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  if (d.keep_state && w.hc < d.B * d.Hq) return MUSE_ERR_WORKSPACE_TOO_SMALL;
   if (d.dtype == MUSE_DTYPE_FP32)
     return run_bwd_typed<float>(d, (const float*)Q, (const float*)K, (const float*)V, (const float*)O, LSE,
                                 (const float*)dO, qc, aq, ak, selc, selb, dQ, dK, dV, w, st);

@@ -65,8 +65,9 @@ struct FFWorkspace {
   uint32_t* selmask;
   uint32_t* pairmask;  // [HQ][nb-1][W][N]
   int32_t *pair_cnt, *pair_off;  // inverse index of the retrieval: (kv head, key block, key cluster) -> hits
-  uint32_t* hits;
+  uint2* hits;                   // x = n | g << 22 (query position, head inside the KV group), y = slot*k2e + u
   size_t hit_cap;                // hits per kv head
+  float* ret_part;               // per (query, slot, u): forward partial state [acc D | max | sum | pad2], or dq partial [D]
   float *dKs, *dVs;            // fp32 gradients in bucketed key order
   float *dQacc, *dKacc, *dVacc;  // fp32 gradients in sequence order (alias the outputs when they are fp32)
   // per chunk of `hc` query heads
@@ -82,14 +83,15 @@ static inline size_t ff_al(size_t x) { return (x + 255) & ~(size_t)255; }
 static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
   size_t HQ = (size_t)d.B * d.Hq, HK = (size_t)d.B * d.Hkv, N = d.N, D = d.D;
   size_t es = d.dtype == MUSE_DTYPE_BF16 ? 2 : 4;
+  size_t W = (d.Ck + 31) / 32, NBm = d.nb > 1 ? d.nb - 1 : 1, R2 = (size_t)(d.r > 0 ? d.r : 1) * d.k2e;
   size_t b = ff_al(HK * N * 4) + ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) + ff_al(HQ * N * 4) +
              ff_al(HQ * ((size_t)d.nb * d.Cq + 1) * 4) + ff_al(HQ * d.nb * ((size_t)d.Cq + 1) * 4) +
              2 * ff_al(HK * N * D * es) + ff_al(HQ * N * (D + 2) * 4);
+  // inverse index of the retrieval and its per-(query, slot) partial results
+  b += ff_al(HQ * N * W * 4 * NBm) + 2 * ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) + ff_al(HQ * N * R2 * 8) +
+       ff_al(HQ * N * R2 * (D + 4) * 4);
   if (bwd) {
-    size_t W = (d.Ck + 31) / 32;
-    b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + ff_al(HQ * N * W * 4 * (size_t)(d.nb > 1 ? d.nb - 1 : 1)) +
-         2 * ff_al(HK * N * D * 4) + 2 * ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) +
-         ff_al(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * d.k2e * 4);
+    b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + 2 * ff_al(HK * N * D * 4);
     if (d.grad_dtype != MUSE_DTYPE_FP32) b += ff_al(HQ * N * D * 4) + 2 * ff_al(HK * N * D * 4);
   }
   return b;
@@ -113,4 +115,14 @@ int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0
 // attn_mfma.hip
 int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
                          const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
-                         const uint32_t* hits, size_t hit_cap, float* dKs, float* dVs, hipStream_t st);
+                         const uint2* hits, size_t hit_cap, float* dKs, float* dVs, hipStream_t st);
+int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, const void* Vs, const int32_t* off_k,
+                              const int32_t* pair_off, const uint2* hits, size_t hit_cap, float* part, hipStream_t st);
+int muse_launch_ret_bwd_dq_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
+                                 const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
+                                 const uint2* hits, size_t hit_cap, float* dqpart, hipStream_t st);
+// retrieval.hip: pair bitmask + ordered hit lists from the exported selections; merge of the forward partials
+int muse_ff_build_inverse_index(const MuseDims& d, const int32_t* selc, const int32_t* selb, FFWorkspace& w,
+                                bool with_hits, hipStream_t st);
+int muse_launch_merge_ret(const MuseDims& d, const int32_t* selb, const float* part, float* ff_acc, float* ff_ml,
+                          hipStream_t st);

@@ -49,7 +49,8 @@ int make_dims(const muse_params* p, bool full, MuseDims* d) {
   if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->N < 1 || p->Hq % p->Hkv) return MUSE_ERR_INVALID_ARG;
   if (p->dtype != MUSE_DTYPE_FP32 && p->dtype != MUSE_DTYPE_BF16) return MUSE_ERR_INVALID_ARG;
   if (p->grad_dtype != MUSE_DTYPE_FP32 && p->grad_dtype != p->dtype) return MUSE_ERR_INVALID_ARG;
-  if (p->flags != 0) return MUSE_ERR_INVALID_ARG;
+  if (p->flags & ~(uint32_t)MUSE_FLAG_KEEP_FWD_STATE) return MUSE_ERR_INVALID_ARG;
+  d->keep_state = (p->flags & MUSE_FLAG_KEEP_FWD_STATE) != 0;
   if (!(p->scale >= 0.f) || isinf(p->scale)) return MUSE_ERR_INVALID_ARG;
   if (p->causal != 1) return MUSE_ERR_UNSUPPORTED;
   if (p->D != 64 && p->D != 128) return MUSE_ERR_UNSUPPORTED;
@@ -107,9 +108,9 @@ int muse_workspace_bytes(const muse_params* p, int which, size_t* min_bytes, siz
     case MUSE_WS_EXACT_BWD: mn = pref = exact_bwd_bytes(d); break;
     case MUSE_WS_FWD:
     case MUSE_WS_BWD: {
-      bool bwd = which == MUSE_WS_BWD;
-      mn = muse_farfield_fixed_bytes(d, bwd) + muse_farfield_ws_bytes(d, bwd, 1);
+      bool bwd = which == MUSE_WS_BWD || d.keep_state;
       pref = muse_farfield_fixed_bytes(d, bwd) + muse_farfield_ws_bytes(d, bwd, d.B * d.Hq);
+      mn = d.keep_state ? pref : muse_farfield_fixed_bytes(d, bwd) + muse_farfield_ws_bytes(d, bwd, 1);
       break;
     }
     default: return MUSE_ERR_INVALID_ARG;
@@ -150,7 +151,8 @@ int muse_fwd(const muse_params* p, const void* Q, const void* K, const void* V, 
   if (rc) return rc;
   if (!Q || !K || !V || !q_centroids || !q_assign || !k_assign || !O || !LSE || !ws) return MUSE_ERR_INVALID_ARG;
   if (d.r > 0 && (!sel_clusters || !sel_blocks)) return MUSE_ERR_INVALID_ARG;
-  size_t need = muse_farfield_fixed_bytes(d, false) + muse_farfield_ws_bytes(d, false, 1);
+  size_t need = d.keep_state ? muse_farfield_fixed_bytes(d, true) + muse_farfield_ws_bytes(d, true, d.B * d.Hq)
+                             : muse_farfield_fixed_bytes(d, false) + muse_farfield_ws_bytes(d, false, 1);
   if (ws_bytes < need) return MUSE_ERR_WORKSPACE_TOO_SMALL;
   return muse_run_fwd(d, Q, K, V, q_centroids, q_assign, k_assign, O, LSE, sel_clusters, sel_blocks, ws, ws_bytes,
                       (hipStream_t)stream);
@@ -166,7 +168,7 @@ int muse_bwd(const muse_params* p, const void* Q, const void* K, const void* V, 
   if (!Q || !K || !V || !O || !LSE || !dO || !q_centroids || !q_assign || !k_assign || !dQ || !dK || !dV || !ws)
     return MUSE_ERR_INVALID_ARG;
   if (d.r > 0 && (!sel_clusters || !sel_blocks)) return MUSE_ERR_INVALID_ARG;
-  size_t need = muse_farfield_fixed_bytes(d, true) + muse_farfield_ws_bytes(d, true, 1);
+  size_t need = muse_farfield_fixed_bytes(d, true) + muse_farfield_ws_bytes(d, true, d.keep_state ? d.B * d.Hq : 1);
   if (ws_bytes < need) return MUSE_ERR_WORKSPACE_TOO_SMALL;
   return muse_run_bwd(d, Q, K, V, O, LSE, dO, q_centroids, q_assign, k_assign, sel_clusters, sel_blocks, dQ, dK, dV,
                       ws, ws_bytes, (hipStream_t)stream);

@@ -153,3 +153,28 @@ def test_gpu_own_clustering_reports_rse(oracle):
     rse = (((O - Oe) ** 2).sum(-1) / (Oe ** 2).sum(-1)).mean().item()
     print(f"cfg1 RSE vs exact = {rse:.3e}")
     assert rse < 0.05
+
+
+def test_keep_forward_state_matches_recompute():
+    """MUSE_FLAG_KEEP_FWD_STATE (backward reuses the forward's bucketing, summaries and inverse index) must
+    give the same bits as the stateless path."""
+    base, kw = CASES["cfg4_gqa"]
+    w = small(base, **kw)
+    d = generate(w, need_dO=True)
+    p = mb.params_for(w)
+    pk = dataclasses.replace(p, flags=mb.FLAG_KEEP_FWD_STATE)
+    qc, aq, ak = oracle_clustering(w, d, p)
+    Q, K, V, dO = (dev(d[x], p) for x in ("Q", "K", "V", "dO"))
+    cl = (torch.tensor(qc).cuda(), torch.tensor(aq).cuda(), torch.tensor(ak).cuda())
+    O, LSE, selc, selb = mb.muse_fwd(p, Q, K, V, *cl)
+    g = mb.muse_bwd(p, Q, K, V, O, LSE, dO, *cl, selc, selb)
+    mn, pref = mb.muse_workspace_bytes(pk, mb.WS_FWD)
+    assert mn == pref == mb.muse_workspace_bytes(pk, mb.WS_BWD)[1]
+    ws = torch.empty(pref, dtype=torch.uint8, device="cuda")
+    O2, LSE2, selc2, selb2 = mb.muse_fwd(pk, Q, K, V, *cl, ws=ws)
+    g2 = mb.muse_bwd(pk, Q, K, V, O2, LSE2, dO, *cl, selc2, selb2, ws=ws)
+    assert torch.equal(O, O2) and torch.equal(LSE, LSE2) and torch.equal(selc, selc2) and torch.equal(selb, selb2)
+    for a, b in zip(g, g2):
+        assert torch.equal(a, b)
+    with pytest.raises(mb.MuseError, match="workspace"):
+        mb.muse_fwd(pk, Q, K, V, *cl, ws=ws[: pref - 4096])
