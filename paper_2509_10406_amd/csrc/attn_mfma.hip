@@ -697,7 +697,165 @@ __global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restric
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Gradients of the accumulated cells (component 1) for bf16 inputs: the (b, i) group's queries against
+// a tile of 32 key clusters is a dense attention-backward block with the accumulated summaries in the
+// role of keys and values.  Four waves share the staged query tile, each owns one cluster tile.
+//   g_A_k = sum dl q~,  g_A_v = sum p dO,  g_A_c = sum [dl (1 - q~.kbar) - p dO.vbar]
+// Operands are rounded to bf16 for the matrix cores (gradients only; no selection depends on them).
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ bf16x8_t cvt8(const float* __restrict__ p) {
+  float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  bf16x8_t r;
+  r[0] = (__bf16)a.x; r[1] = (__bf16)a.y; r[2] = (__bf16)a.z; r[3] = (__bf16)a.w;
+  r[4] = (__bf16)b.x; r[5] = (__bf16)b.y; r[6] = (__bf16)b.z; r[7] = (__bf16)b.w;
+  return r;
+}
+
+template <int D>
+__global__ void __launch_bounds__(256) k_ff_bwd_cells_mx(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO, const float* __restrict__ qc,
+    const float* __restrict__ A_mu, const float* __restrict__ A_k, const float* __restrict__ A_v,
+    const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q, const float* __restrict__ LSE,
+    const float* __restrict__ delta, const uint32_t* __restrict__ selmask, float* __restrict__ g_A_c,
+    float* __restrict__ g_A_k, float* __restrict__ g_A_v, int h0, int N, int nb, int Cq, int Ck, float scale) {
+  constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
+  __shared__ __attribute__((aligned(16))) bf16_t qs[32][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gs[32][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][32 + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][32 + 8];
+  __shared__ __attribute__((aligned(16))) float ls[32];
+  __shared__ __attribute__((aligned(16))) float ds[32];
+  __shared__ uint32_t mws[4][32];
+  const int hl = blockIdx.z, hq = h0 + hl;
+  const int NBm = nb - 1, W = (Ck + 31) / 32;
+  const int b = blockIdx.y / Cq + 1, i = blockIdx.y % Cq;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  const int jt = blockIdx.x * 4 + wave;
+  const bool active = jt < W;
+  const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
+  const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
+  const size_t acell = (((size_t)hl * NBm + (b - 1)) * Cq + i) * Ck;
+  const int jc = jt * 32 + col;
+  const bool jvalid = active && jc < Ck;
+  const int jcc = jvalid ? jc : Ck - 1;
+  bf16x8_t kf[KS], vf[KS];
+#pragma unroll
+  for (int x = 0; x < KS; ++x) {
+    kf[x] = cvt8(A_k + (acell + jcc) * D + 16 * x + 8 * half);
+    vf[x] = cvt8(A_v + (acell + jcc) * D + 16 * x + 8 * half);
+  }
+  const float amu2 = jvalid ? A_mu[acell + jcc] * 1.4426950408889634f : MUSE_NEG_INF;
+  const float* qci = qc + ((size_t)hq * Cq + i) * D;
+  f32x16_t gk[DT], gv[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { gk[t][e] = 0.f; gv[t][e] = 0.f; }
+  float csum = 0.f;
+  for (int q0 = qlo; q0 < qhi; q0 += 32) {
+    __syncthreads();
+    for (int c = threadIdx.x; c < 32 * CPR; c += 256) {
+      const int row = c / CPR, cc = c % CPR;
+      const int pos = q0 + row < qhi ? q0 + row : q0;
+      const size_t qn = (size_t)hq * N + perm_q[(size_t)hq * N + pos];
+      uint4 qv = *reinterpret_cast<const uint4*>(Q + qn * D + cc * 8);
+      uint4 gvv = *reinterpret_cast<const uint4*>(dO + qn * D + cc * 8);
+      const bf16_t* pq = reinterpret_cast<const bf16_t*>(&qv);
+      const bf16_t* pg = reinterpret_cast<const bf16_t*>(&gvv);
+      float4 c0 = *reinterpret_cast<const float4*>(qci + cc * 8), c1 = *reinterpret_cast<const float4*>(qci + cc * 8 + 4);
+      const float cv[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+      bf16_t qtl[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qtl[e] = f32_to_bf16_bits(scale * (bf16_bits_to_f32(pq[e]) - cv[e]));
+      *reinterpret_cast<uint4*>(&qs[row][cc * 8]) = *reinterpret_cast<const uint4*>(qtl);
+      *reinterpret_cast<uint4*>(&gs[row][cc * 8]) = gvv;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { qt_[cc * 8 + e][row] = qtl[e]; gt_[cc * 8 + e][row] = pg[e]; }
+    }
+    if (threadIdx.x < 128) {
+      const int row = threadIdx.x % 32, w2 = threadIdx.x / 32;
+      const bool ok = q0 + row < qhi;
+      const size_t qn = (size_t)hq * N + perm_q[(size_t)hq * N + (ok ? q0 + row : q0)];
+      const int jt2 = blockIdx.x * 4 + w2;
+      mws[w2][row] = jt2 < W ? selmask[qn * W + jt2] : 0u;
+      if (w2 == 0) {
+        ls[row] = ok ? LSE[qn] * 1.4426950408889634f : __builtin_huge_valf();  // +inf -> p = 0 for padding rows
+        ds[row] = delta[qn];
+      }
+    }
+    __syncthreads();
+    if (!active) continue;
+    f32x16_t s, dp;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+    for (int x = 0; x < KS; ++x) {
+      bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&qs[col][16 * x + 8 * half]);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[x], s, 0, 0, 0);
+      bf16x8_t ag = *reinterpret_cast<const bf16x8_t*>(&gs[col][16 * x + 8 * half]);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, vf[x], dp, 0, 0, 0);
+    }
+    f32x16_t pr;
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) {
+      float4 l4 = *reinterpret_cast<const float4*>(&ls[8 * gq + 4 * half]);
+      float4 d4 = *reinterpret_cast<const float4*>(&ds[8 * gq + 4 * half]);
+      const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = 4 * gq + u, row = 8 * gq + 4 * half + u;
+        float p = fast_exp2(fmaf(s[e], 1.4426950408889634f, amu2 - lv[u]));
+        p = ((mws[wave][row] >> col) & 1u) ? 0.f : p;
+        const float dlg = p * (dp[e] - dv4[u]);
+        csum += p > 0.f ? dlg * (1.f - s[e]) - p * dp[e] : 0.f;
+        pr[e] = p;
+        s[e] = dlg;
+      }
+    }
+#pragma unroll
+    for (int G = 0; G < 2; ++G) {
+      bf16x8_t pf = pack8(pr, 2 * G, 2 * G + 1);
+      bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
+#pragma unroll
+      for (int t = 0; t < DT; ++t) {
+        bf16x8_t ag = ld_tr8(&gt_[32 * t + col][0], 16 * G, half);
+        gv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, pf, gv[t], 0, 0, 0);
+        bf16x8_t aq = ld_tr8(&qt_[32 * t + col][0], 16 * G, half);
+        gk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, df, gk[t], 0, 0, 0);
+      }
+    }
+  }
+  csum += __shfl_xor(csum, 32, 64);
+  if (!jvalid) return;
+  float* ok_ = g_A_k + (acell + jc) * D;
+  float* ov_ = g_A_v + (acell + jc) * D;
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int d = 32 * t + 8 * g + 4 * half;
+      *reinterpret_cast<float4*>(ok_ + d) = make_float4(gk[t][4 * g], gk[t][4 * g + 1], gk[t][4 * g + 2], gk[t][4 * g + 3]);
+      *reinterpret_cast<float4*>(ov_ + d) = make_float4(gv[t][4 * g], gv[t][4 * g + 1], gv[t][4 * g + 2], gv[t][4 * g + 3]);
+    }
+  if (half == 0) g_A_c[acell + jc] = csum;
+}
+
 }  // namespace
+
+int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO, const float* qc, const float* A_mu,
+                                const float* A_k, const float* A_v, const int32_t* perm_q, const int32_t* off_q,
+                                const float* LSE, const float* delta, const uint32_t* selmask, float* g_A_c,
+                                float* g_A_k, float* g_A_v, int h0, int hn, hipStream_t st) {
+  const int W = (d.Ck + 31) / 32;
+  dim3 g((W + 3) / 4, (d.nb - 1) * d.Cq, hn);
+  if (d.D == 64)
+    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL(k_ff_bwd_cells_mx<64>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, A_k, A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, g_A_k, g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
+  else
+    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL(k_ff_bwd_cells_mx<128>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, A_k, A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, g_A_k, g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
 
 int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, const void* Vs, const int32_t* off_k,
                               const int32_t* pair_off, const uint2* hits, size_t hit_cap, float* part, hipStream_t st) {

@@ -316,134 +316,132 @@ __global__ void __launch_bounds__(64) k_ff_bwd_cells(
 }
 
 // ------------------------------------------------------------------------------------------
-// gradients of the per-block cells (component 2): one wave per (query cluster i, tile of 32 key
-// clusters) owns the cells (i, tile, all blocks); it walks the queries of cluster i, and for every
-// query that retrieved a cluster of the tile adds its non-retrieved-block terms.  Lanes = head dim.
-// The cells must be zero on entry.
+// Gradients of the per-block cells, finished: one wave per (query cluster i, tile of 32 key clusters)
+// owns the 32 chains (i, j, all blocks) and walks the key blocks a = nb-2 .. 0:
+//   1. component 2: every query of cluster i in a later block that retrieved cluster j but not block a
+//      adds  g_k += dl q~,  g_v += p dO,  g_c += dl (1 - q~.kbar) - p dO.vbar   (LDS tile, lanes = head dim)
+//   2. reverse accumulation  R[a] = gA[a] + exp(Amu[a] - Amu[a+1]) R[a+1]  (registers), and
+//      G[a] = g[a] + exp(mu[a] - Amu[a]) R[a]  is written out, 32 cells = one contiguous tile.
+// All factors are <= 1.  No zero-fill, no read-modify-write in global memory.
 // ------------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ void __launch_bounds__(64) k_c2_cells(
+__global__ void __launch_bounds__(256) k_cell_grads(
     const T* __restrict__ Q, const T* __restrict__ dO, const float* __restrict__ qc, const float* __restrict__ s_mu,
-    const float* __restrict__ s_k, const float* __restrict__ s_v, const int32_t* __restrict__ perm_q,
-    const int32_t* __restrict__ off_q, const float* __restrict__ LSE, const float* __restrict__ delta,
-    const uint32_t* __restrict__ selmask, const int32_t* __restrict__ selc, const int32_t* __restrict__ selb,
-    float* __restrict__ g_s_c, float* __restrict__ g_s_k, float* __restrict__ g_s_v, int h0, int N, int nb, int Cq,
-    int Ck, int r, int k2e, float scale) {
+    const float* __restrict__ s_k, const float* __restrict__ s_v, const float* __restrict__ A_mu,
+    const float* __restrict__ g_A_c, const float* __restrict__ g_A_k, const float* __restrict__ g_A_v,
+    const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q, const float* __restrict__ LSE,
+    const float* __restrict__ delta, const uint32_t* __restrict__ selmask, const uint32_t* __restrict__ pairmask,
+    float* __restrict__ G_c, float* __restrict__ G_k, float* __restrict__ G_v, int h0, int N, int nb, int Cq, int Ck,
+    int r, float scale) {
   constexpr int DL = D / 64;
+  __shared__ float gk[32][D];
+  __shared__ float gv[32][D];
+  __shared__ float gc[32];
   const int hl = blockIdx.z, hq = h0 + hl;
   const int i = blockIdx.y, jt = blockIdx.x;
-  const int lane = threadIdx.x, NBm = nb - 1;
+  // four waves; wave w owns the chains jl = w, w+4, ..., w+28 and their LDS rows (no cross-wave traffic)
+  const int lane = threadIdx.x % 64, wave = threadIdx.x / 64, NBm = nb - 1;
   const int W = (Ck + 31) / 32;
+  const uint32_t mine = 0x11111111u << wave;
   const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
   float qcv[DL];
 #pragma unroll
   for (int x = 0; x < DL; ++x) qcv[x] = qc[((size_t)hq * Cq + i) * D + lane + 64 * x];
-  for (int b = 1; b < nb; ++b) {
-    const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
-    for (int q0 = qlo; q0 < qhi; q0 += 64) {
-      const int pos = q0 + lane;
-      int n = 0;
-      uint32_t mw = 0;
-      if (pos < qhi) {
-        n = perm_q[(size_t)hq * N + pos];
-        mw = selmask[((size_t)hq * N + n) * W + jt];
-      }
-      unsigned long long live = __ballot(mw != 0);
-      while (live) {
-        const int src = __ffsll((long long)live) - 1;
-        live &= live - 1;
-        const int nn = __shfl(n, src, 64);
-        uint32_t bits = (uint32_t)__shfl((int)mw, src, 64);
-        const size_t qn = (size_t)hq * N + nn;
-        float qv[DL], gv[DL];
+  float Rk[8][DL], Rv[8][DL];
 #pragma unroll
-        for (int x = 0; x < DL; ++x) {
-          qv[x] = scale * (Elem<T>::ld(Q, qn * D + lane + 64 * x) - qcv[x]);
-          gv[x] = Elem<T>::ld(dO, qn * D + lane + 64 * x);
-        }
-        const float lse = LSE[qn], dl = delta[qn];
-        while (bits) {
-          const int jl = __ffs((int)bits) - 1;
-          bits &= bits - 1;
-          const int j = jt * 32 + jl;
-          int slot = -1;
-          for (int t = 0; t < r; ++t)
-            if (selc[qn * r + t] == j) slot = t;
-          if (slot < 0) continue;
-          unsigned selbits = 0;
-          for (int u = 0; u < k2e; ++u) {
-            int bb = selb[(qn * r + slot) * k2e + u];
-            if (bb >= 0) selbits |= 1u << bb;
+  for (int q = 0; q < 8; ++q)
+#pragma unroll
+    for (int x = 0; x < DL; ++x) { Rk[q][x] = 0.f; Rv[q][x] = 0.f; }
+  float an_l = 0.f, rc_l = 0.f;
+  for (int a = NBm - 1; a >= 0; --a) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+#pragma unroll
+      for (int x = 0; x < DL; ++x) { gk[wave + 4 * q][lane + 64 * x] = 0.f; gv[wave + 4 * q][lane + 64 * x] = 0.f; }
+    if (lane < 8) gc[wave + 4 * lane] = 0.f;
+    if (r > 0) {
+      const uint32_t* pmw = pairmask + (((size_t)hq * NBm + a) * W + jt) * N;
+      for (int b = a + 1; b < nb; ++b) {
+        const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
+        for (int q0 = qlo; q0 < qhi; q0 += 64) {
+          const int pos = q0 + lane;
+          int n = 0;
+          uint32_t mw = 0;
+          if (pos < qhi) {
+            n = perm_q[(size_t)hq * N + pos];
+            mw = selmask[((size_t)hq * N + n) * W + jt] & ~pmw[n] & mine;   // retrieved the cluster, not this block
           }
-          for (int bp = 0; bp < b; ++bp) {
-            if ((selbits >> bp) & 1u) continue;
-            const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
-            const float mu = s_mu[cell];
-            if (!(mu > MUSE_NEG_INF)) continue;
-            float kv[DL], vv[DL], part = 0.f, dpp = 0.f;
+          unsigned long long live = __ballot(mw != 0);
+          while (live) {
+            const int src = __ffsll((long long)live) - 1;
+            live &= live - 1;
+            const int nn = __shfl(n, src, 64);
+            uint32_t bits = (uint32_t)__shfl((int)mw, src, 64);
+            const size_t qn = (size_t)hq * N + nn;
+            float qv[DL], gvv[DL];
 #pragma unroll
             for (int x = 0; x < DL; ++x) {
-              kv[x] = s_k[cell * D + lane + 64 * x];
-              vv[x] = s_v[cell * D + lane + 64 * x];
-              part = fmaf(qv[x], kv[x], part);
-              dpp = fmaf(gv[x], vv[x], dpp);
+              qv[x] = scale * (Elem<T>::ld(Q, qn * D + lane + 64 * x) - qcv[x]);
+              gvv[x] = Elem<T>::ld(dO, qn * D + lane + 64 * x);
             }
-            part = wave_sum(part);
-            dpp = wave_sum(dpp);
-            const float p = __expf(part + mu - lse);
-            const float dlg = p * (dpp - dl);
+            const float lse = LSE[qn], dl = delta[qn];
+            while (bits) {
+              const int jl = __ffs((int)bits) - 1;
+              bits &= bits - 1;
+              const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + jt * 32 + jl;
+              const float mu = s_mu[cell];
+              if (!(mu > MUSE_NEG_INF)) continue;
+              float kv[DL], vv[DL], part = 0.f, dpp = 0.f;
 #pragma unroll
-            for (int x = 0; x < DL; ++x) {
-              g_s_k[cell * D + lane + 64 * x] += dlg * qv[x];
-              g_s_v[cell * D + lane + 64 * x] += p * gv[x];
+              for (int x = 0; x < DL; ++x) {
+                kv[x] = s_k[cell * D + lane + 64 * x];
+                vv[x] = s_v[cell * D + lane + 64 * x];
+                part = fmaf(qv[x], kv[x], part);
+                dpp = fmaf(gvv[x], vv[x], dpp);
+              }
+              part = wave_sum(part);
+              dpp = wave_sum(dpp);
+              const float p = __expf(part + mu - lse);
+              const float dlg = p * (dpp - dl);
+#pragma unroll
+              for (int x = 0; x < DL; ++x) {
+                gk[jl][lane + 64 * x] += dlg * qv[x];
+                gv[jl][lane + 64 * x] += p * gvv[x];
+              }
+              if (lane == 0) gc[jl] += dlg * (1.f - part) - p * dpp;
             }
-            if (lane == 0) g_s_c[cell] += dlg * (1.f - part) - p * dpp;
           }
         }
       }
     }
-  }
-}
-
-// ------------------------------------------------------------------------------------------
-// reverse accumulation: G[b'] = g_s[b'] + exp(mu[b'] - Amu[b']) R[b'],
-// R[a] = g_A[a] + exp(Amu[a] - Amu[a+1]) R[a+1]   (all factors <= 1).  In place into g_s_*.
-// One thread per (cell chain, group of 4 dims); the scalar c-terms ride on the first group.
-// ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_cell_scan_bwd(const float* __restrict__ s_mu, const float* __restrict__ A_mu,
-                                                        const float* __restrict__ g_A_c, const float* __restrict__ g_A_k,
-                                                        const float* __restrict__ g_A_v, float* __restrict__ g_s_c,
-                                                        float* __restrict__ g_s_k, float* __restrict__ g_s_v, int hn,
-                                                        int NBm, size_t chains, int D) {
-  const int D4 = D / 4;
-  size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= (size_t)hn * chains * D4) return;
-  const int d4 = (int)(t % D4);
-  const size_t ch = (t / D4) % chains;
-  const size_t hl = t / D4 / chains;
-  float4 Rk = make_float4(0, 0, 0, 0), Rv = make_float4(0, 0, 0, 0);
-  float Rc = 0.f, Anext = 0.f;
-  for (int a = NBm - 1; a >= 0; --a) {
-    const size_t cell = (hl * NBm + a) * chains + ch;
-    const float Am = A_mu[cell];
-    float f = 0.f;
-    if (a < NBm - 1 && Am > MUSE_NEG_INF) f = __expf(Am - Anext);
-    Anext = Am;
-    float4 gk = *reinterpret_cast<const float4*>(g_A_k + cell * D + 4 * d4);
-    float4 gv = *reinterpret_cast<const float4*>(g_A_v + cell * D + 4 * d4);
-    Rk.x = gk.x + f * Rk.x; Rk.y = gk.y + f * Rk.y; Rk.z = gk.z + f * Rk.z; Rk.w = gk.w + f * Rk.w;
-    Rv.x = gv.x + f * Rv.x; Rv.y = gv.y + f * Rv.y; Rv.z = gv.z + f * Rv.z; Rv.w = gv.w + f * Rv.w;
-    Rc = g_A_c[cell] + f * Rc;
-    const float mu = s_mu[cell];
-    if (mu > MUSE_NEG_INF) {
-      const float w = __expf(mu - Am);
-      float4 sk = *reinterpret_cast<float4*>(g_s_k + cell * D + 4 * d4);
-      float4 sv = *reinterpret_cast<float4*>(g_s_v + cell * D + 4 * d4);
-      sk.x += w * Rk.x; sk.y += w * Rk.y; sk.z += w * Rk.z; sk.w += w * Rk.w;
-      sv.x += w * Rv.x; sv.y += w * Rv.y; sv.z += w * Rv.z; sv.w += w * Rv.w;
-      *reinterpret_cast<float4*>(g_s_k + cell * D + 4 * d4) = sk;
-      *reinterpret_cast<float4*>(g_s_v + cell * D + 4 * d4) = sv;
-      if (d4 == 0) g_s_c[cell] += w * Rc;
+    // lane jl owns the scalars of chain jl
+    float f_l = 0.f, w_l = 0.f;
+    {
+      const int j = jt * 32 + (lane & 31);
+      if (lane < 32 && j < Ck) {
+        const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + j;
+        const float Am = A_mu[cell], mu = s_mu[cell];
+        f_l = (a < NBm - 1 && Am > MUSE_NEG_INF) ? __expf(Am - an_l) : 0.f;
+        w_l = mu > MUSE_NEG_INF ? __expf(mu - Am) : 0.f;
+        rc_l = g_A_c[cell] + f_l * rc_l;
+        an_l = Am;
+        if ((lane & 3) == wave) G_c[cell] = gc[lane] + w_l * rc_l;
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int jl = wave + 4 * q, j = jt * 32 + jl;
+      if (j < Ck) {
+        const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + j;
+        const float f = __shfl(f_l, jl, 64), wgt = __shfl(w_l, jl, 64);
+#pragma unroll
+        for (int x = 0; x < DL; ++x) {
+          Rk[q][x] = g_A_k[cell * D + lane + 64 * x] + f * Rk[q][x];
+          Rv[q][x] = g_A_v[cell * D + lane + 64 * x] + f * Rv[q][x];
+          G_k[cell * D + lane + 64 * x] = gk[jl][lane + 64 * x] + wgt * Rk[q][x];
+          G_v[cell * D + lane + 64 * x] = gv[jl][lane + 64 * x] + wgt * Rv[q][x];
+        }
+      }
     }
   }
 }
@@ -716,30 +714,22 @@ template <typename T, int D>
 int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, const float* LSE, const int32_t* selc,
                   const int32_t* selb, FFWorkspace& w, int h0, int hn, hipStream_t st) {
   const int NBm = d.nb - 1;
-  const size_t cells = (size_t)NBm * d.Cq * d.Ck;
   const int W = (d.Ck + 31) / 32;
-  int rc;
-  // component-2 cells are accumulated into: start from zero
-  if ((rc = muse_launch_fill(w.g_s_c, (size_t)hn * cells, 0.f, st))) return rc;
-  if ((rc = muse_launch_fill(w.g_s_k, (size_t)hn * cells * D, 0.f, st))) return rc;
-  if ((rc = muse_launch_fill(w.g_s_v, (size_t)hn * cells * D, 0.f, st))) return rc;
   dim3 gt(d.Bs / 32 + d.Cq + 1, NBm, hn);
   { MuseProf prof_("k_ff_bwd_dq", st); hipLaunchKernelGGL((k_ff_bwd_dq<T, D>), gt, dim3(64), 0, st, Q, dO, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu,
                      w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q, w.off_k, w.tile_off, LSE, w.delta,
                      w.selmask, selc, selb, w.ret_part, w.dQacc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
+  if (sizeof(T) == 2) {
+    int rc2 = muse_launch_ff_bwd_cells_mx(d, Q, dO, qc, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask,
+                                          w.g_A_c, w.g_A_k, w.g_A_v, h0, hn, st);
+    if (rc2) return rc2;
+  } else
   { MuseProf prof_("k_ff_bwd_cells", st); hipLaunchKernelGGL((k_ff_bwd_cells<T, D>), dim3(W, NBm * d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.A_mu, w.A_k, w.A_v,
                      w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.g_A_c, w.g_A_k, w.g_A_v, h0, d.N, d.nb, d.Cq, d.Ck,
                      d.scale); }
-  if (d.r > 0)
-    { MuseProf prof_("k_c2_cells", st); hipLaunchKernelGGL((k_c2_cells<T, D>), dim3(W, d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.s_mu, w.s_k, w.s_v, w.perm_q,
-                       w.off_q, LSE, w.delta, w.selmask, selc, selb, w.g_s_c, w.g_s_k, w.g_s_v, h0, d.N, d.nb, d.Cq,
-                       d.Ck, d.r, d.k2e, d.scale); }
-  {
-    size_t chains = (size_t)d.Cq * d.Ck;
-    size_t total = (size_t)hn * chains * (D / 4);
-    { MuseProf prof_("k_cell_scan_bwd", st); hipLaunchKernelGGL(k_cell_scan_bwd, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w.s_mu, w.A_mu, w.g_A_c,
-                       w.g_A_k, w.g_A_v, w.g_s_c, w.g_s_k, w.g_s_v, hn, NBm, chains, D); }
-  }
+  { MuseProf prof_("k_cell_grads", st); hipLaunchKernelGGL((k_cell_grads<T, D>), dim3(W, d.Cq, hn), dim3(256), 0, st, Q, dO, qc, w.s_mu, w.s_k, w.s_v, w.A_mu,
+                     w.g_A_c, w.g_A_k, w.g_A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.pairmask, w.g_s_c, w.g_s_k,
+                     w.g_s_v, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.scale); }
   const int G_ = d.Hq / d.Hkv;
   { MuseProf prof_("k_cells_to_keys", st); hipLaunchKernelGGL((k_cells_to_keys<T, D>), dim3(d.Ck, NBm, hn / G_), dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs,
                      qc, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq,

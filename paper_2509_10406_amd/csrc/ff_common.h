@@ -121,6 +121,10 @@ int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, 
 int muse_launch_ret_bwd_dq_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
                                  const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
                                  const uint2* hits, size_t hit_cap, float* dqpart, hipStream_t st);
+int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO, const float* qc, const float* A_mu,
+                                const float* A_k, const float* A_v, const int32_t* perm_q, const int32_t* off_q,
+                                const float* LSE, const float* delta, const uint32_t* selmask, float* g_A_c,
+                                float* g_A_k, float* g_A_v, int h0, int hn, hipStream_t st);
 // retrieval.hip: pair bitmask + ordered hit lists from the exported selections; merge of the forward partials
 int muse_ff_build_inverse_index(const MuseDims& d, const int32_t* selc, const int32_t* selb, FFWorkspace& w,
                                 bool with_hits, hipStream_t st);
