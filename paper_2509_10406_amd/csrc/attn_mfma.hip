@@ -841,7 +841,123 @@ __global__ void __launch_bounds__(256) k_ff_bwd_cells_mx(
   if (half == 0) g_A_c[acell + jc] = csum;
 }
 
+// ------------------------------------------------------------------------------------------
+// Summary gradients -> keys and values for bf16 inputs: one wave per (kv head, key block b', key
+// cluster j); the keys of the segment are the MFMA columns, 32 query clusters at a time the rows.
+//   W[i,m] = exp(L[i,m] - mu[i]),  T[i,m] = G_c[i] + G_k[i].k_m + G_v[i].v_m
+//   dv_m += sum_i W G_v[i],  dk_m += sum_i W G_k[i] + (W T) qbar_i
+// G and qbar are rounded to bf16 for the matrix cores (gradients only).
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
+                                                          const float* __restrict__ qc, const float* __restrict__ L,
+                                                          const float* __restrict__ s_mu, const float* __restrict__ G_c,
+                                                          const float* __restrict__ G_k, const float* __restrict__ G_v,
+                                                          const int32_t* __restrict__ off_k, float* __restrict__ dKs,
+                                                          float* __restrict__ dVs, int h0, int N, int nb, int Cq, int Ck,
+                                                          int Hq, int Hkv, float scale) {
+  constexpr int KS = D / 16, DT = D / 32;
+  const int G_ = Hq / Hkv;
+  const int hkl = blockIdx.z;
+  const int hq0 = h0 + hkl * G_;
+  const int hk = (hq0 / Hq) * Hkv + (hq0 % Hq) / G_;
+  const int bp = blockIdx.y, j = blockIdx.x, NBm = nb - 1;
+  const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
+  for (int m0 = klo; m0 < khi; m0 += 32) {
+    const int pm = m0 + col;
+    const bool mvalid = pm < khi;
+    const int pmc = mvalid ? pm : m0;
+    bf16x8_t kb[KS], vb[KS];
+#pragma unroll
+    for (int x = 0; x < KS; ++x) {
+      kb[x] = *reinterpret_cast<const bf16x8_t*>(Ks + ((size_t)hk * N + pmc) * D + 16 * x + 8 * half);
+      vb[x] = *reinterpret_cast<const bf16x8_t*>(Vs + ((size_t)hk * N + pmc) * D + 16 * x + 8 * half);
+    }
+    f32x16_t dk[DT], dv[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { dk[t][e] = 0.f; dv[t][e] = 0.f; }
+    for (int g = 0; g < G_; ++g) {
+      const int hl = hkl * G_ + g, hq = h0 + hl;
+      for (int i0 = 0; i0 < Cq; i0 += 32) {
+        const int ic = i0 + col < Cq ? i0 + col : Cq - 1;
+        const size_t cellA = (((size_t)hl * NBm + bp) * Cq + ic) * Ck + j;
+        f32x16_t tacc, wv;
+        size_t cellr[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          int ir = i0 + 8 * (e / 4) + 4 * half + (e % 4);
+          const bool iv = ir < Cq;
+          ir = iv ? ir : Cq - 1;
+          cellr[e] = (((size_t)hl * NBm + bp) * Cq + ir) * Ck + j;
+          tacc[e] = G_c[cellr[e]];
+          const float w = __expf(L[((size_t)hl * Cq + ir) * N + pmc] - s_mu[cellr[e]]);
+          wv[e] = (iv && mvalid) ? w : 0.f;
+        }
+#pragma unroll
+        for (int x = 0; x < KS; ++x) {
+          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cvt8(G_k + cellA * D + 16 * x + 8 * half), kb[x], tacc, 0, 0, 0);
+          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cvt8(G_v + cellA * D + 16 * x + 8 * half), vb[x], tacc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tacc[e] = wv[e] > 0.f ? wv[e] * tacc[e] : 0.f;
+#pragma unroll
+        for (int G = 0; G < 2; ++G) {
+          bf16x8_t wf = pack8(wv, 2 * G, 2 * G + 1);
+          bf16x8_t tf = pack8(tacc, 2 * G, 2 * G + 1);
+#pragma unroll
+          for (int t = 0; t < DT; ++t) {
+            bf16x8_t ak, av, aq;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {  // k-slot u of this half = row 4*(2G + u/4) + u%4 of the accumulator
+              const int e = 4 * (2 * G + u / 4) + (u % 4);
+              int ir = i0 + 8 * (e / 4) + 4 * half + (e % 4);
+              ir = ir < Cq ? ir : Cq - 1;
+              ak[u] = (__bf16)G_k[cellr[e] * D + 32 * t + col];
+              av[u] = (__bf16)G_v[cellr[e] * D + 32 * t + col];
+              aq[u] = (__bf16)(scale * qc[((size_t)hq * Cq + ir) * D + 32 * t + col]);
+            }
+            dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wf, dv[t], 0, 0, 0);
+            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, wf, dk[t], 0, 0, 0);
+            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, tf, dk[t], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (mvalid) {
+      float* ok_ = dKs + ((size_t)hk * N + pm) * D;
+      float* ov_ = dVs + ((size_t)hk * N + pm) * D;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {
+          const int d = 32 * t + 8 * gg + 4 * half;
+          float4 a = *reinterpret_cast<float4*>(ok_ + d), c = *reinterpret_cast<float4*>(ov_ + d);
+          a.x += dk[t][4 * gg]; a.y += dk[t][4 * gg + 1]; a.z += dk[t][4 * gg + 2]; a.w += dk[t][4 * gg + 3];
+          c.x += dv[t][4 * gg]; c.y += dv[t][4 * gg + 1]; c.z += dv[t][4 * gg + 2]; c.w += dv[t][4 * gg + 3];
+          *reinterpret_cast<float4*>(ok_ + d) = a;
+          *reinterpret_cast<float4*>(ov_ + d) = c;
+        }
+    }
+  }
+}
+
 }  // namespace
+
+int muse_launch_cells_to_keys_mx(const MuseDims& d, const void* Ks, const void* Vs, const float* qc, const float* L,
+                                 const float* s_mu, const float* G_c, const float* G_k, const float* G_v,
+                                 const int32_t* off_k, float* dKs, float* dVs, int h0, int hn, hipStream_t st) {
+  dim3 g(d.Ck, d.nb - 1, hn / (d.Hq / d.Hkv));
+  if (d.D == 64)
+    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<64>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, qc, L, s_mu, G_c, G_k, G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv, d.scale); }
+  else
+    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<128>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, qc, L, s_mu, G_c, G_k, G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv, d.scale); }
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
 
 int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO, const float* qc, const float* A_mu,
                                 const float* A_k, const float* A_v, const int32_t* perm_q, const int32_t* off_q,

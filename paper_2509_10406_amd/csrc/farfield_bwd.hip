@@ -731,6 +731,11 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
                      w.g_A_c, w.g_A_k, w.g_A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.pairmask, w.g_s_c, w.g_s_k,
                      w.g_s_v, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.scale); }
   const int G_ = d.Hq / d.Hkv;
+  if (sizeof(T) == 2) {
+    int rc2 = muse_launch_cells_to_keys_mx(d, w.Ks, w.Vs, qc, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs,
+                                           h0, hn, st);
+    if (rc2) return rc2;
+  } else
   { MuseProf prof_("k_cells_to_keys", st); hipLaunchKernelGGL((k_cells_to_keys<T, D>), dim3(d.Ck, NBm, hn / G_), dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs,
                      qc, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq,
                      d.Hkv, d.scale); }

@@ -125,6 +125,9 @@ int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO
                                 const float* A_k, const float* A_v, const int32_t* perm_q, const int32_t* off_q,
                                 const float* LSE, const float* delta, const uint32_t* selmask, float* g_A_c,
                                 float* g_A_k, float* g_A_v, int h0, int hn, hipStream_t st);
+int muse_launch_cells_to_keys_mx(const MuseDims& d, const void* Ks, const void* Vs, const float* qc, const float* L,
+                                 const float* s_mu, const float* G_c, const float* G_k, const float* G_v,
+                                 const int32_t* off_k, float* dKs, float* dVs, int h0, int hn, hipStream_t st);
 // retrieval.hip: pair bitmask + ordered hit lists from the exported selections; merge of the forward partials
 int muse_ff_build_inverse_index(const MuseDims& d, const int32_t* selc, const int32_t* selb, FFWorkspace& w,
                                 bool with_hits, hipStream_t st);
