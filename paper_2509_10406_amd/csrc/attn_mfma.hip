@@ -20,16 +20,6 @@ constexpr int BN = 64;  // rows staged in LDS per step
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ bf16x8_t pack8(const f32x16_t& s, int g0, int g1) {
-  bf16x8_t r;
-#pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    r[t] = (__bf16)s[4 * g0 + t];
-    r[4 + t] = (__bf16)s[4 * g1 + t];
-  }
-  return r;
-}
-
 // A operand for the second contraction from a transposed LDS tile `row` ([..][BN+8]): the 8 k-slots
 // of lane half `half` over the 16 rows starting at r0
 __device__ __forceinline__ bf16x8_t ld_tr8(const bf16_t* row, int r0, int half) {
@@ -704,14 +694,6 @@ __global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restric
 //   g_A_k = sum dl q~,  g_A_v = sum p dO,  g_A_c = sum [dl (1 - q~.kbar) - p dO.vbar]
 // Operands are rounded to bf16 for the matrix cores (gradients only; no selection depends on them).
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ bf16x8_t cvt8(const float* __restrict__ p) {
-  float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
-  bf16x8_t r;
-  r[0] = (__bf16)a.x; r[1] = (__bf16)a.y; r[2] = (__bf16)a.z; r[3] = (__bf16)a.w;
-  r[4] = (__bf16)b.x; r[5] = (__bf16)b.y; r[6] = (__bf16)b.z; r[7] = (__bf16)b.w;
-  return r;
-}
-
 template <int D>
 __global__ void __launch_bounds__(256) k_ff_bwd_cells_mx(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO, const float* __restrict__ qc,

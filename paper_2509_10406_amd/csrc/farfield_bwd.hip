@@ -93,6 +93,67 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
 #pragma unroll
   for (int t = 0; t < DT; ++t) dq[t] = zero16();
   // component 1
+  if (sizeof(T) == 2) {
+    // bf16 inputs: operands rounded to bf16 for the matrix cores (gradients only)
+    constexpr int KS = D / 16;
+    bf16x8_t qb[KS], gb[KS];
+    // the bf16 operand order (8 consecutive dims per lane half) differs from the fp32 row pattern of qt/gt
+    {
+      const float* qci = qc + ((size_t)hq * Cq + i) * D;
+#pragma unroll
+      for (int x = 0; x < KS; ++x) {
+        float q8[8], g8[8];
+        ld4(Q, qn * D + 16 * x + 8 * half, q8); ld4(Q, qn * D + 16 * x + 8 * half + 4, q8 + 4);
+        ld4(dO, qn * D + 16 * x + 8 * half, g8); ld4(dO, qn * D + 16 * x + 8 * half + 4, g8 + 4);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          qb[x][e] = (__bf16)(scale * (q8[e] - qci[16 * x + 8 * half + e]));
+          gb[x][e] = (__bf16)g8[e];
+        }
+      }
+    }
+    for (int jt = 0; jt < ntile; ++jt) {
+      const int j0 = jt * 32;
+      int c = j0 + col;
+      c = c < Ck ? c : Ck - 1;
+      f32x16_t s, dp;
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          int jr = j0 + 8 * g + 4 * half + t;
+          s[4 * g + t] = jr < Ck ? Amu[jr] : MUSE_NEG_INF;
+          dp[4 * g + t] = 0.f;
+        }
+#pragma unroll
+      for (int x = 0; x < KS; ++x) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cvt8(Ak + (size_t)c * D + 16 * x + 8 * half), qb[x], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cvt8(Av + (size_t)c * D + 16 * x + 8 * half), gb[x], dp, 0, 0, 0);
+      }
+      const uint32_t mw = selmask[qn * W + jt];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        int row = 8 * (e / 4) + 4 * half + (e % 4);
+        float p = ((mw >> row) & 1u) ? 0.f : __expf(s[e] - lse);
+        s[e] = p * (dp[e] - dl);
+      }
+#pragma unroll
+      for (int G = 0; G < 2; ++G) {
+        bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
+#pragma unroll
+        for (int x = 0; x < DT; ++x) {
+          bf16x8_t ak;
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            int jr = j0 + 8 * (2 * G + u / 4) + 4 * half + (u % 4);
+            jr = jr < Ck ? jr : Ck - 1;
+            ak[u] = (__bf16)Ak[(size_t)jr * D + 32 * x + col];
+          }
+          dq[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, df, dq[x], 0, 0, 0);
+        }
+      }
+    }
+  } else
   for (int jt = 0; jt < ntile; ++jt) {
     const int j0 = jt * 32;
     f32x16_t s = score_tile<D>(Amu, Ak, j0, Ck, qt, col, half);

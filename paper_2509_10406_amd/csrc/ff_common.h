@@ -55,6 +55,27 @@ __device__ __forceinline__ f32x16_t score_tile(const float* __restrict__ Amu, co
   return mfma_rows<D>(acc, Ak + (size_t)c * D + 4 * half, qt);
 }
 
+// bf16 MFMA (v_mfma_f32_32x32x16_bf16) helpers.  pack8: accumulator rows 4*g0..+3 and 4*g1..+3 of a lane
+// become the 8 k-slots of a B (or A) operand; the matching other operand must use the same row order.
+__device__ __forceinline__ bf16x8_t pack8(const f32x16_t& s, int g0, int g1) {
+  bf16x8_t r;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    r[t] = (__bf16)s[4 * g0 + t];
+    r[4 + t] = (__bf16)s[4 * g1 + t];
+  }
+  return r;
+}
+
+__device__ __forceinline__ bf16x8_t cvt8(const float* __restrict__ p) {
+  float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  bf16x8_t r;
+  r[0] = (__bf16)a.x; r[1] = (__bf16)a.y; r[2] = (__bf16)a.z; r[3] = (__bf16)a.w;
+  r[4] = (__bf16)b.x; r[5] = (__bf16)b.y; r[6] = (__bf16)b.z; r[7] = (__bf16)b.w;
+  return r;
+}
+
+
 struct FFWorkspace {
   // all heads
   int32_t *perm_k, *off_k, *perm_q, *off_q, *tile_off;
