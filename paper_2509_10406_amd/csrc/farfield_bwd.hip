@@ -400,10 +400,10 @@ __global__ void __launch_bounds__(256) k_cell_grads(
   __shared__ float gc[32];
   const int hl = blockIdx.z, hq = h0 + hl;
   const int i = blockIdx.y, jt = blockIdx.x;
-  // four waves; wave w owns the chains jl = w, w+4, ..., w+28 and their LDS rows (no cross-wave traffic)
+  // four waves; wave w owns the chains jl = 8w .. 8w+7 (consecutive cells: 2 KB bursts) and their LDS rows (no cross-wave traffic)
   const int lane = threadIdx.x % 64, wave = threadIdx.x / 64, NBm = nb - 1;
   const int W = (Ck + 31) / 32;
-  const uint32_t mine = 0x11111111u << wave;
+  const uint32_t mine = 0xffu << (8 * wave);
   const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
   float qcv[DL];
 #pragma unroll
@@ -414,63 +414,108 @@ __global__ void __launch_bounds__(256) k_cell_grads(
 #pragma unroll
     for (int x = 0; x < DL; ++x) { Rk[q][x] = 0.f; Rv[q][x] = 0.f; }
   float an_l = 0.f, rc_l = 0.f;
+  // the queries of cluster i in blocks >= 1 (bucketed order is block-major, so they are visited block by
+  // block); the first kCache*64 of them are kept in registers: position n, block, selected-cluster word
+  constexpr int kCache = 4;
+  int cn[kCache], cb[kCache];
+  uint32_t cm[kCache];
+  int ncached = 0;       // chunks held in registers
+  int rest_b = nb, rest_q = 0;  // where the uncached remainder starts
+  {
+    int slot = 0;
+    for (int b = 1; b < nb && r > 0; ++b) {
+      const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
+      for (int q0 = qlo; q0 < qhi; q0 += 64) {
+        if (slot == kCache) { if (rest_b == nb) { rest_b = b; rest_q = q0; } continue; }
+        const int pos = q0 + lane;
+        int n = 0;
+        uint32_t mw = 0;
+        if (pos < qhi) {
+          n = perm_q[(size_t)hq * N + pos];
+          mw = selmask[((size_t)hq * N + n) * W + jt] & mine;
+        }
+#pragma unroll
+        for (int c = 0; c < kCache; ++c)
+          if (c == slot) { cn[c] = n; cb[c] = b; cm[c] = mw; }
+        ++slot;
+      }
+    }
+    ncached = slot;
+#pragma unroll
+    for (int c = 0; c < kCache; ++c)
+      if (c >= ncached) { cn[c] = 0; cb[c] = 0; cm[c] = 0; }
+  }
+  auto process = [&](int a, int nn, uint32_t bits) {
+    const size_t qn = (size_t)hq * N + nn;
+    float qv[DL], gvv[DL];
+#pragma unroll
+    for (int x = 0; x < DL; ++x) {
+      qv[x] = scale * (Elem<T>::ld(Q, qn * D + lane + 64 * x) - qcv[x]);
+      gvv[x] = Elem<T>::ld(dO, qn * D + lane + 64 * x);
+    }
+    const float lse = LSE[qn], dl = delta[qn];
+    while (bits) {
+      const int jl = __ffs((int)bits) - 1;
+      bits &= bits - 1;
+      const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + jt * 32 + jl;
+      const float mu = s_mu[cell];  // an empty cell has mu = -inf and zero rows: p = 0, nothing is added
+      float kv[DL], vv[DL], part = 0.f, dpp = 0.f;
+#pragma unroll
+      for (int x = 0; x < DL; ++x) {
+        kv[x] = s_k[cell * D + lane + 64 * x];
+        vv[x] = s_v[cell * D + lane + 64 * x];
+        part = fmaf(qv[x], kv[x], part);
+        dpp = fmaf(gvv[x], vv[x], dpp);
+      }
+      part = wave_sum(part);
+      dpp = wave_sum(dpp);
+      const float p = __expf(part + mu - lse);
+      const float dlg = p * (dpp - dl);
+#pragma unroll
+      for (int x = 0; x < DL; ++x) {
+        gk[jl][lane + 64 * x] += dlg * qv[x];
+        gv[jl][lane + 64 * x] += p * gvv[x];
+      }
+      if (lane == 0) gc[jl] += dlg * (1.f - part) - p * dpp;
+    }
+  };
   for (int a = NBm - 1; a >= 0; --a) {
 #pragma unroll
     for (int q = 0; q < 8; ++q)
 #pragma unroll
-      for (int x = 0; x < DL; ++x) { gk[wave + 4 * q][lane + 64 * x] = 0.f; gv[wave + 4 * q][lane + 64 * x] = 0.f; }
-    if (lane < 8) gc[wave + 4 * lane] = 0.f;
+      for (int x = 0; x < DL; ++x) { gk[8 * wave + q][lane + 64 * x] = 0.f; gv[8 * wave + q][lane + 64 * x] = 0.f; }
+    if (lane < 8) gc[8 * wave + lane] = 0.f;
     if (r > 0) {
       const uint32_t* pmw = pairmask + (((size_t)hq * NBm + a) * W + jt) * N;
-      for (int b = a + 1; b < nb; ++b) {
+      // cached chunks: retrieved the cluster (cm) in a later block (cb > a), but not this block (pairmask)
+      uint32_t hit[kCache];
+#pragma unroll
+      for (int c = 0; c < kCache; ++c) hit[c] = (c < ncached && cb[c] > a && cm[c]) ? (cm[c] & ~pmw[cn[c]]) : 0u;
+#pragma unroll
+      for (int c = 0; c < kCache; ++c) {
+        unsigned long long live = __ballot(hit[c] != 0);
+        while (live) {
+          const int src = __ffsll((long long)live) - 1;
+          live &= live - 1;
+          process(a, __shfl(cn[c], src, 64), (uint32_t)__shfl((int)hit[c], src, 64));
+        }
+      }
+      // remainder (clusters with more than kCache*64 queries in later blocks)
+      for (int b = rest_b > a + 1 ? rest_b : a + 1; b < nb; ++b) {
         const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
-        for (int q0 = qlo; q0 < qhi; q0 += 64) {
+        for (int q0 = (b == rest_b ? rest_q : qlo); q0 < qhi; q0 += 64) {
           const int pos = q0 + lane;
           int n = 0;
           uint32_t mw = 0;
           if (pos < qhi) {
             n = perm_q[(size_t)hq * N + pos];
-            mw = selmask[((size_t)hq * N + n) * W + jt] & ~pmw[n] & mine;   // retrieved the cluster, not this block
+            mw = selmask[((size_t)hq * N + n) * W + jt] & ~pmw[n] & mine;
           }
           unsigned long long live = __ballot(mw != 0);
           while (live) {
             const int src = __ffsll((long long)live) - 1;
             live &= live - 1;
-            const int nn = __shfl(n, src, 64);
-            uint32_t bits = (uint32_t)__shfl((int)mw, src, 64);
-            const size_t qn = (size_t)hq * N + nn;
-            float qv[DL], gvv[DL];
-#pragma unroll
-            for (int x = 0; x < DL; ++x) {
-              qv[x] = scale * (Elem<T>::ld(Q, qn * D + lane + 64 * x) - qcv[x]);
-              gvv[x] = Elem<T>::ld(dO, qn * D + lane + 64 * x);
-            }
-            const float lse = LSE[qn], dl = delta[qn];
-            while (bits) {
-              const int jl = __ffs((int)bits) - 1;
-              bits &= bits - 1;
-              const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + jt * 32 + jl;
-              const float mu = s_mu[cell];
-              if (!(mu > MUSE_NEG_INF)) continue;
-              float kv[DL], vv[DL], part = 0.f, dpp = 0.f;
-#pragma unroll
-              for (int x = 0; x < DL; ++x) {
-                kv[x] = s_k[cell * D + lane + 64 * x];
-                vv[x] = s_v[cell * D + lane + 64 * x];
-                part = fmaf(qv[x], kv[x], part);
-                dpp = fmaf(gvv[x], vv[x], dpp);
-              }
-              part = wave_sum(part);
-              dpp = wave_sum(dpp);
-              const float p = __expf(part + mu - lse);
-              const float dlg = p * (dpp - dl);
-#pragma unroll
-              for (int x = 0; x < DL; ++x) {
-                gk[jl][lane + 64 * x] += dlg * qv[x];
-                gv[jl][lane + 64 * x] += p * gvv[x];
-              }
-              if (lane == 0) gc[jl] += dlg * (1.f - part) - p * dpp;
-            }
+            process(a, __shfl(n, src, 64), (uint32_t)__shfl((int)mw, src, 64));
           }
         }
       }
@@ -486,12 +531,12 @@ __global__ void __launch_bounds__(256) k_cell_grads(
         w_l = mu > MUSE_NEG_INF ? __expf(mu - Am) : 0.f;
         rc_l = g_A_c[cell] + f_l * rc_l;
         an_l = Am;
-        if ((lane & 3) == wave) G_c[cell] = gc[lane] + w_l * rc_l;
+        if ((lane >> 3) == wave) G_c[cell] = gc[lane] + w_l * rc_l;
       }
     }
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-      const int jl = wave + 4 * q, j = jt * 32 + jl;
+      const int jl = 8 * wave + q, j = jt * 32 + jl;
       if (j < Ck) {
         const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + j;
         const float f = __shfl(f_l, jl, 64), wgt = __shfl(w_l, jl, 64);
