@@ -73,6 +73,15 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Orders LDS traffic between the lanes of ONE wave (a block of 64 threads): the LDS pipeline serves a
+// wave's requests in issue order, so a compiler-level fence is all that is needed; unlike
+// __syncthreads() it does not wait for outstanding global stores.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // host-side launch parameters shared by the translation units
 struct MuseDims {
   int B, Hq, Hkv, N, D, Cq, Ck, r, k2, k2e, Bs, nb, T;

@@ -97,6 +97,7 @@ __global__ void __launch_bounds__(64) k_summaries(const T* __restrict__ Ks, cons
                                                    float* __restrict__ A_k, float* __restrict__ A_v, int h0, int N,
                                                    int nb, int Cq, int Ck, int Hq, int Hkv) {
   constexpr int DS = D / 64;  // slices of the head dim
+  __shared__ float tr[32][68];
   const int j = blockIdx.x, hl = blockIdx.z, hq = h0 + hl;
   const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
   const int it = blockIdx.y / DS, d0 = (blockIdx.y % DS) * 64;
@@ -168,25 +169,39 @@ __global__ void __launch_bounds__(64) k_summaries(const T* __restrict__ Ks, cons
         }
       Amx = nm;
     }
-    if (!iv) continue;
-    const size_t cell = (((size_t)hl * NBm + b) * Cq + i) * Ck + j;
+    const size_t cell = (((size_t)hl * NBm + b) * Cq + ic) * Ck + j;
     const float inv = empty ? 0.f : 1.f / S;
     const bool aempty = AS == 0.f;
     const float ainv = aempty ? 0.f : 1.f / AS;
-    if (half == 0 && d0 == 0) {
+    if (iv && half == 0 && d0 == 0) {
       s_mu[cell] = empty ? MUSE_NEG_INF : mx + __logf(S);
       A_mu[cell] = aempty ? MUSE_NEG_INF : Amx + __logf(AS);
     }
+    // transpose each 64 x 32 accumulator slice through LDS so that a store instruction writes four whole
+    // 256-byte row segments instead of 32 fragments of 32 bytes
+    const size_t rowbase = (((size_t)hl * NBm + b) * Cq + it * 32) * Ck + j;
+    auto emit = [&](float* __restrict__ dst, const f32x16_t(&a)[2], float sc) {
 #pragma unroll
-    for (int x = 0; x < 2; ++x)
+      for (int x = 0; x < 2; ++x)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const size_t o = cell * D + d0 + 32 * x + 8 * g + 4 * half;
-        *reinterpret_cast<float4*>(s_k + o) = make_float4(ak[x][4 * g] * inv, ak[x][4 * g + 1] * inv, ak[x][4 * g + 2] * inv, ak[x][4 * g + 3] * inv);
-        *reinterpret_cast<float4*>(s_v + o) = make_float4(av[x][4 * g] * inv, av[x][4 * g + 1] * inv, av[x][4 * g + 2] * inv, av[x][4 * g + 3] * inv);
-        *reinterpret_cast<float4*>(A_k + o) = make_float4(Aak[x][4 * g] * ainv, Aak[x][4 * g + 1] * ainv, Aak[x][4 * g + 2] * ainv, Aak[x][4 * g + 3] * ainv);
-        *reinterpret_cast<float4*>(A_v + o) = make_float4(Aav[x][4 * g] * ainv, Aav[x][4 * g + 1] * ainv, Aav[x][4 * g + 2] * ainv, Aav[x][4 * g + 3] * ainv);
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(&tr[col][32 * x + 8 * g + 4 * half]) =
+              make_float4(a[x][4 * g] * sc, a[x][4 * g + 1] * sc, a[x][4 * g + 2] * sc, a[x][4 * g + 3] * sc);
+      wave_lds_fence();
+#pragma unroll
+      for (int ps = 0; ps < 8; ++ps) {
+        const int row = 4 * ps + lane / 16;
+        if (it * 32 + row < Cq) {
+          float4 v = *reinterpret_cast<const float4*>(&tr[row][4 * (lane % 16)]);
+          *reinterpret_cast<float4*>(dst + (rowbase + (size_t)row * Ck) * D + d0 + 4 * (lane % 16)) = v;
+        }
       }
+      wave_lds_fence();
+    };
+    emit(s_k, ak, inv);
+    emit(s_v, av, inv);
+    emit(A_k, Aak, ainv);
+    emit(A_v, Aav, ainv);
   }
 }
 

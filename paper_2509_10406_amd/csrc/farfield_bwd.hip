@@ -377,13 +377,20 @@ __global__ void __launch_bounds__(64) k_ff_bwd_cells(
 }
 
 // ------------------------------------------------------------------------------------------
-// Gradients of the per-block cells, finished: one wave per (query cluster i, tile of 32 key clusters)
-// owns the 32 chains (i, j, all blocks) and walks the key blocks a = nb-2 .. 0:
+// Gradients of the per-block cells, finished: one block of 256 threads per (query cluster i, tile of 32
+// key clusters); wave w owns the 8 chains (i, j, all blocks), j = 32 jt + 8 w + c.  A wave is 8 groups of
+// 8 lanes; a lane holds D/8 elements of a row (d = 32 x + 4 l8 + t).  Walking the key blocks
+// a = nb-2 .. 0:
 //   1. component 2: every query of cluster i in a later block that retrieved cluster j but not block a
-//      adds  g_k += dl q~,  g_v += p dO,  g_c += dl (1 - q~.kbar) - p dO.vbar   (LDS tile, lanes = head dim)
-//   2. reverse accumulation  R[a] = gA[a] + exp(Amu[a] - Amu[a+1]) R[a+1]  (registers), and
-//      G[a] = g[a] + exp(mu[a] - Amu[a]) R[a]  is written out, 32 cells = one contiguous tile.
-// All factors are <= 1.  No zero-fill, no read-modify-write in global memory.
+//      adds  g_k += dl q~,  g_v += p dO,  g_c += dl (1 - q~.kbar) - p dO.vbar.  The retrievals concentrate
+//      on few chains, so the entries of ONE chain are dealt round-robin to the 8 groups, summed in
+//      registers and combined by a butterfly across the groups; group c keeps the sums of chain c.
+//   2. reverse accumulation  R[a] = gA[a] + exp(Amu[a] - Amu[a+1]) R[a+1]  (registers of group c), and
+//      G[a] = g[a] + exp(mu[a] - Amu[a]) R[a]  is written out.
+// The queries that retrieved a chain are listed once per block of threads, in bucketed order, by a
+// counting sort on wave ballots: (position n, block of n, bitmask of the retrieved key blocks).
+// All factors are <= 1.  No zero-fill, no read-modify-write in global memory, no atomics: the order of
+// every sum is fixed.
 // ------------------------------------------------------------------------------------------
 template <typename T, int D>
 __global__ void __launch_bounds__(256) k_cell_grads(
@@ -391,162 +398,223 @@ __global__ void __launch_bounds__(256) k_cell_grads(
     const float* __restrict__ s_k, const float* __restrict__ s_v, const float* __restrict__ A_mu,
     const float* __restrict__ g_A_c, const float* __restrict__ g_A_k, const float* __restrict__ g_A_v,
     const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q, const float* __restrict__ LSE,
-    const float* __restrict__ delta, const uint32_t* __restrict__ selmask, const uint32_t* __restrict__ pairmask,
-    float* __restrict__ G_c, float* __restrict__ G_k, float* __restrict__ G_v, int h0, int N, int nb, int Cq, int Ck,
-    int r, float scale) {
-  constexpr int DL = D / 64;
-  __shared__ float gk[32][D];
-  __shared__ float gv[32][D];
-  __shared__ float gc[32];
+    const float* __restrict__ delta, const uint32_t* __restrict__ selmask, const int32_t* __restrict__ selc,
+    const int32_t* __restrict__ selb, float* __restrict__ G_c, float* __restrict__ G_k, float* __restrict__ G_v, int h0,
+    int N, int nb, int Bs, int Cq, int Ck, int r, int k2e, float scale) {
+  constexpr int NV = D / 32;
+  constexpr int POOL = 2048;
+  __shared__ int2 pool[POOL];
+  __shared__ int cnt[4][32];
+  __shared__ int wbase[4][32];
+  __shared__ int off[33];
+  __shared__ int cum[18];  // cum[b] = queries of cluster i in blocks 1 .. b-1
   const int hl = blockIdx.z, hq = h0 + hl;
   const int i = blockIdx.y, jt = blockIdx.x;
-  // four waves; wave w owns the chains jl = 8w .. 8w+7 (consecutive cells: 2 KB bursts) and their LDS rows (no cross-wave traffic)
-  const int lane = threadIdx.x % 64, wave = threadIdx.x / 64, NBm = nb - 1;
-  const int W = (Ck + 31) / 32;
-  const uint32_t mine = 0xffu << (8 * wave);
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, s8 = lane / 8, l8 = lane % 8;
+  const int NBm = nb - 1, W = (Ck + 31) / 32;
   const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
-  float qcv[DL];
-#pragma unroll
-  for (int x = 0; x < DL; ++x) qcv[x] = qc[((size_t)hq * Cq + i) * D + lane + 64 * x];
-  float Rk[8][DL], Rv[8][DL];
-#pragma unroll
-  for (int q = 0; q < 8; ++q)
-#pragma unroll
-    for (int x = 0; x < DL; ++x) { Rk[q][x] = 0.f; Rv[q][x] = 0.f; }
-  float an_l = 0.f, rc_l = 0.f;
-  // the queries of cluster i in blocks >= 1 (bucketed order is block-major, so they are visited block by
-  // block); the first kCache*64 of them are kept in registers: position n, block, selected-cluster word
-  constexpr int kCache = 4;
-  int cn[kCache], cb[kCache];
-  uint32_t cm[kCache];
-  int ncached = 0;       // chunks held in registers
-  int rest_b = nb, rest_q = 0;  // where the uncached remainder starts
-  {
-    int slot = 0;
-    for (int b = 1; b < nb && r > 0; ++b) {
-      const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
-      for (int q0 = qlo; q0 < qhi; q0 += 64) {
-        if (slot == kCache) { if (rest_b == nb) { rest_b = b; rest_q = q0; } continue; }
-        const int pos = q0 + lane;
-        int n = 0;
-        uint32_t mw = 0;
-        if (pos < qhi) {
-          n = perm_q[(size_t)hq * N + pos];
-          mw = selmask[((size_t)hq * N + n) * W + jt] & mine;
-        }
-#pragma unroll
-        for (int c = 0; c < kCache; ++c)
-          if (c == slot) { cn[c] = n; cb[c] = b; cm[c] = mw; }
-        ++slot;
-      }
+  const int CH = r > 0 ? (POOL / r < 256 ? POOL / r : 256) : 256;  // queries listed per pass: at most POOL entries
+
+  if (tid < 33) off[tid] = 0;
+  if (tid == 0) {
+    int run = 0;
+    cum[0] = 0;
+    cum[1] = 0;
+    for (int b = 1; b < nb; ++b) {
+      run += oq[b * Cq + i + 1] - oq[b * Cq + i];
+      cum[b + 1] = run;
     }
-    ncached = slot;
-#pragma unroll
-    for (int c = 0; c < kCache; ++c)
-      if (c >= ncached) { cn[c] = 0; cb[c] = 0; cm[c] = 0; }
   }
-  auto process = [&](int a, int nn, uint32_t bits) {
-    const size_t qn = (size_t)hq * N + nn;
-    float qv[DL], gvv[DL];
+  __syncthreads();
+  const int Tq = r > 0 ? cum[nb] : 0;
+  const int nchunks = (Tq + CH - 1) / CH;
+
+  float qcv[NV][4];
 #pragma unroll
-    for (int x = 0; x < DL; ++x) {
-      qv[x] = scale * (Elem<T>::ld(Q, qn * D + lane + 64 * x) - qcv[x]);
-      gvv[x] = Elem<T>::ld(dO, qn * D + lane + 64 * x);
+  for (int x = 0; x < NV; ++x) {
+    float4 c4 = *reinterpret_cast<const float4*>(qc + ((size_t)hq * Cq + i) * D + 32 * x + 4 * l8);
+    qcv[x][0] = c4.x; qcv[x][1] = c4.y; qcv[x][2] = c4.z; qcv[x][3] = c4.w;
+  }
+
+  auto build = [&](int ch) {
+    const int idx = ch * CH + tid;
+    int n = 0;
+    uint32_t word = 0;  // chains of this tile the query retrieved
+    if (tid < CH && idx < Tq) {
+      int b = 1;
+      while (idx >= cum[b + 1]) ++b;
+      n = perm_q[(size_t)hq * N + oq[b * Cq + i] + idx - cum[b]];
+      word = selmask[((size_t)hq * N + n) * W + jt];
     }
-    const float lse = LSE[qn], dl = delta[qn];
-    while (bits) {
-      const int jl = __ffs((int)bits) - 1;
-      bits &= bits - 1;
-      const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + jt * 32 + jl;
-      const float mu = s_mu[cell];  // an empty cell has mu = -inf and zero rows: p = 0, nothing is added
-      float kv[DL], vv[DL], part = 0.f, dpp = 0.f;
-#pragma unroll
-      for (int x = 0; x < DL; ++x) {
-        kv[x] = s_k[cell * D + lane + 64 * x];
-        vv[x] = s_v[cell * D + lane + 64 * x];
-        part = fmaf(qv[x], kv[x], part);
-        dpp = fmaf(gvv[x], vv[x], dpp);
-      }
-      part = wave_sum(part);
-      dpp = wave_sum(dpp);
-      const float p = __expf(part + mu - lse);
-      const float dlg = p * (dpp - dl);
-#pragma unroll
-      for (int x = 0; x < DL; ++x) {
-        gk[jl][lane + 64 * x] += dlg * qv[x];
-        gv[jl][lane + 64 * x] += p * gvv[x];
-      }
-      if (lane == 0) gc[jl] += dlg * (1.f - part) - p * dpp;
+#pragma unroll 4
+    for (int c = 0; c < 32; ++c) {
+      const unsigned long long bal = __ballot((word >> c) & 1u);
+      if (lane == 0) cnt[wave][c] = __popcll(bal);
     }
+    __syncthreads();
+    if (tid < 32) {
+      int tot = 0;
+#pragma unroll
+      for (int w_ = 0; w_ < 4; ++w_) { const int v = cnt[w_][tid]; cnt[w_][tid] = tot; tot += v; }
+      int incl = tot;
+#pragma unroll
+      for (int o = 1; o < 32; o <<= 1) {
+        const int v = __shfl_up(incl, o, 64);
+        if (tid >= o) incl += v;
+      }
+      const int excl = incl - tot;
+      off[tid] = excl;
+      if (tid == 31) off[32] = incl;
+#pragma unroll
+      for (int w_ = 0; w_ < 4; ++w_) wbase[w_][tid] = cnt[w_][tid] + excl;
+    }
+    __syncthreads();
+    // ranks inside a chain follow the bucketed order of the queries
+    if (__ballot(word != 0) != 0ull) {
+#pragma unroll 4
+      for (int c = 0; c < 32; ++c) {
+        const bool bit = (word >> c) & 1u;
+        const unsigned long long bal = __ballot(bit);
+        if (bit) pool[wbase[wave][c] + __popcll(bal & ((1ull << lane) - 1ull))] = make_int2(n, c);
+      }
+    }
+    __syncthreads();
+    // one thread per entry: the slot of the chain in the query's selection, then the key blocks it retrieved
+    const int total = off[32];
+    for (int e = tid; e < total; e += 256) {
+      const int2 en = pool[e];
+      const int32_t* sc = selc + ((size_t)hq * N + en.x) * r;
+      const int want = jt * 32 + en.y;
+      int t = 0;
+      for (int t0 = 0; t0 < r; t0 += 8) {
+        int js[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) js[u] = t0 + u < r ? sc[t0 + u] : -1;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t = js[u] == want ? t0 + u : t;
+      }
+      const int32_t* sb = selb + (((size_t)hq * N + en.x) * r + t) * k2e;
+      uint32_t bm = 0;
+      for (int u = 0; u < k2e; ++u) {
+        const int bb = sb[u];
+        bm |= bb >= 0 ? 1u << bb : 0u;
+      }
+      pool[e].y = (int)(((uint32_t)(en.x / Bs) << 16) | bm);
+    }
+    __syncthreads();
   };
+
+  float Rk[NV][4], Rv[NV][4], an = 0.f, rc = 0.f;
+#pragma unroll
+  for (int x = 0; x < NV; ++x)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) { Rk[x][t] = 0.f; Rv[x][t] = 0.f; }
+  const int jl0 = 8 * wave;
   for (int a = NBm - 1; a >= 0; --a) {
+    float gkK[NV][4], gvK[NV][4], gcK = 0.f;  // component-2 sums of this group's own chain
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
+    for (int x = 0; x < NV; ++x)
 #pragma unroll
-      for (int x = 0; x < DL; ++x) { gk[8 * wave + q][lane + 64 * x] = 0.f; gv[8 * wave + q][lane + 64 * x] = 0.f; }
-    if (lane < 8) gc[8 * wave + lane] = 0.f;
-    if (r > 0) {
-      const uint32_t* pmw = pairmask + (((size_t)hq * NBm + a) * W + jt) * N;
-      // cached chunks: retrieved the cluster (cm) in a later block (cb > a), but not this block (pairmask)
-      uint32_t hit[kCache];
+      for (int t = 0; t < 4; ++t) { gkK[x][t] = 0.f; gvK[x][t] = 0.f; }
+    for (int ch = 0; ch < nchunks; ++ch) {
+      if (nchunks > 1 || a == NBm - 1) build(ch);
+      for (int c = 0; c < 8; ++c) {
+        const int e0 = off[jl0 + c], e1 = off[jl0 + c + 1];
+        if (e0 == e1) continue;
+        float gk[NV][4], gv[NV][4], gc = 0.f;
 #pragma unroll
-      for (int c = 0; c < kCache; ++c) hit[c] = (c < ncached && cb[c] > a && cm[c]) ? (cm[c] & ~pmw[cn[c]]) : 0u;
+        for (int x = 0; x < NV; ++x)
 #pragma unroll
-      for (int c = 0; c < kCache; ++c) {
-        unsigned long long live = __ballot(hit[c] != 0);
-        while (live) {
-          const int src = __ffsll((long long)live) - 1;
-          live &= live - 1;
-          process(a, __shfl(cn[c], src, 64), (uint32_t)__shfl((int)hit[c], src, 64));
+          for (int t = 0; t < 4; ++t) { gk[x][t] = 0.f; gv[x][t] = 0.f; }
+        const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + jt * 32 + jl0 + c;
+        const float mu = s_mu[cell];  // an empty cell has mu = -inf and zero rows: p = 0, nothing is added
+        float4 kv[NV], vv[NV];
+#pragma unroll
+        for (int x = 0; x < NV; ++x) {
+          kv[x] = *reinterpret_cast<const float4*>(s_k + cell * D + 32 * x + 4 * l8);
+          vv[x] = *reinterpret_cast<const float4*>(s_v + cell * D + 32 * x + 4 * l8);
         }
-      }
-      // remainder (clusters with more than kCache*64 queries in later blocks)
-      for (int b = rest_b > a + 1 ? rest_b : a + 1; b < nb; ++b) {
-        const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
-        for (int q0 = (b == rest_b ? rest_q : qlo); q0 < qhi; q0 += 64) {
-          const int pos = q0 + lane;
-          int n = 0;
-          uint32_t mw = 0;
-          if (pos < qhi) {
-            n = perm_q[(size_t)hq * N + pos];
-            mw = selmask[((size_t)hq * N + n) * W + jt] & ~pmw[n] & mine;
+        for (int e = e0 + s8; e < e1; e += 8) {
+          const int2 en = pool[e];
+          if ((en.y >> 16) <= a || ((en.y >> a) & 1)) continue;
+          const size_t qn = (size_t)hq * N + en.x;
+          float qv[NV][4], dv[NV][4];
+#pragma unroll
+          for (int x = 0; x < NV; ++x) {
+            ld4(Q, qn * D + 32 * x + 4 * l8, qv[x]);
+            ld4(dO, qn * D + 32 * x + 4 * l8, dv[x]);
           }
-          unsigned long long live = __ballot(mw != 0);
-          while (live) {
-            const int src = __ffsll((long long)live) - 1;
-            live &= live - 1;
-            process(a, __shfl(n, src, 64), (uint32_t)__shfl((int)mw, src, 64));
+          const float lse = LSE[qn], dl = delta[qn];
+          float part = 0.f, dpp = 0.f;
+#pragma unroll
+          for (int x = 0; x < NV; ++x) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) qv[x][t] = scale * (qv[x][t] - qcv[x][t]);
+            part = fmaf(qv[x][0], kv[x].x, part); part = fmaf(qv[x][1], kv[x].y, part);
+            part = fmaf(qv[x][2], kv[x].z, part); part = fmaf(qv[x][3], kv[x].w, part);
+            dpp = fmaf(dv[x][0], vv[x].x, dpp); dpp = fmaf(dv[x][1], vv[x].y, dpp);
+            dpp = fmaf(dv[x][2], vv[x].z, dpp); dpp = fmaf(dv[x][3], vv[x].w, dpp);
           }
+#pragma unroll
+          for (int o = 1; o < 8; o <<= 1) {
+            part += __shfl_xor(part, o, 64);
+            dpp += __shfl_xor(dpp, o, 64);
+          }
+          const float p = __expf(part + mu - lse);
+          const float dlg = p * (dpp - dl);
+#pragma unroll
+          for (int x = 0; x < NV; ++x)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              gk[x][t] = fmaf(dlg, qv[x][t], gk[x][t]);
+              gv[x][t] = fmaf(p, dv[x][t], gv[x][t]);
+            }
+          gc += dlg * (1.f - part) - p * dpp;
+        }
+        // butterfly over the 8 groups: every group ends with the same sums, group c keeps them
+#pragma unroll
+        for (int o = 8; o < 64; o <<= 1) {
+          gc += __shfl_xor(gc, o, 64);
+#pragma unroll
+          for (int x = 0; x < NV; ++x)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              gk[x][t] += __shfl_xor(gk[x][t], o, 64);
+              gv[x][t] += __shfl_xor(gv[x][t], o, 64);
+            }
+        }
+        if (s8 == c) {
+          gcK += gc;
+#pragma unroll
+          for (int x = 0; x < NV; ++x)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { gkK[x][t] += gk[x][t]; gvK[x][t] += gv[x][t]; }
         }
       }
+      if (nchunks > 1) __syncthreads();  // the pool is rebuilt for the next pass
     }
-    // lane jl owns the scalars of chain jl
-    float f_l = 0.f, w_l = 0.f;
-    {
-      const int j = jt * 32 + (lane & 31);
-      if (lane < 32 && j < Ck) {
-        const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + j;
-        const float Am = A_mu[cell], mu = s_mu[cell];
-        f_l = (a < NBm - 1 && Am > MUSE_NEG_INF) ? __expf(Am - an_l) : 0.f;
-        w_l = mu > MUSE_NEG_INF ? __expf(mu - Am) : 0.f;
-        rc_l = g_A_c[cell] + f_l * rc_l;
-        an_l = Am;
-        if ((lane >> 3) == wave) G_c[cell] = gc[lane] + w_l * rc_l;
-      }
-    }
+    const int j = jt * 32 + jl0 + s8;
+    if (j < Ck) {
+      const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + j;
+      const float Am = A_mu[cell], mu = s_mu[cell];
+      const float f = (a < NBm - 1 && Am > MUSE_NEG_INF) ? __expf(Am - an) : 0.f;
+      const float wgt = mu > MUSE_NEG_INF ? __expf(mu - Am) : 0.f;
+      rc = g_A_c[cell] + f * rc;
+      an = Am;
+      if (l8 == 0) G_c[cell] = gcK + wgt * rc;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int jl = 8 * wave + q, j = jt * 32 + jl;
-      if (j < Ck) {
-        const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + j;
-        const float f = __shfl(f_l, jl, 64), wgt = __shfl(w_l, jl, 64);
-#pragma unroll
-        for (int x = 0; x < DL; ++x) {
-          Rk[q][x] = g_A_k[cell * D + lane + 64 * x] + f * Rk[q][x];
-          Rv[q][x] = g_A_v[cell * D + lane + 64 * x] + f * Rv[q][x];
-          G_k[cell * D + lane + 64 * x] = gk[jl][lane + 64 * x] + wgt * Rk[q][x];
-          G_v[cell * D + lane + 64 * x] = gv[jl][lane + 64 * x] + wgt * Rv[q][x];
-        }
+      for (int x = 0; x < NV; ++x) {
+        const size_t o = cell * D + 32 * x + 4 * l8;
+        const float4 ak4 = *reinterpret_cast<const float4*>(g_A_k + o);
+        const float4 av4 = *reinterpret_cast<const float4*>(g_A_v + o);
+        Rk[x][0] = ak4.x + f * Rk[x][0]; Rk[x][1] = ak4.y + f * Rk[x][1];
+        Rk[x][2] = ak4.z + f * Rk[x][2]; Rk[x][3] = ak4.w + f * Rk[x][3];
+        Rv[x][0] = av4.x + f * Rv[x][0]; Rv[x][1] = av4.y + f * Rv[x][1];
+        Rv[x][2] = av4.z + f * Rv[x][2]; Rv[x][3] = av4.w + f * Rv[x][3];
+        *reinterpret_cast<float4*>(G_k + o) = make_float4(gkK[x][0] + wgt * Rk[x][0], gkK[x][1] + wgt * Rk[x][1],
+                                                          gkK[x][2] + wgt * Rk[x][2], gkK[x][3] + wgt * Rk[x][3]);
+        *reinterpret_cast<float4*>(G_v + o) = make_float4(gvK[x][0] + wgt * Rv[x][0], gvK[x][1] + wgt * Rv[x][1],
+                                                          gvK[x][2] + wgt * Rv[x][2], gvK[x][3] + wgt * Rv[x][3]);
       }
     }
   }
@@ -834,8 +902,8 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
                      w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.g_A_c, w.g_A_k, w.g_A_v, h0, d.N, d.nb, d.Cq, d.Ck,
                      d.scale); }
   { MuseProf prof_("k_cell_grads", st); hipLaunchKernelGGL((k_cell_grads<T, D>), dim3(W, d.Cq, hn), dim3(256), 0, st, Q, dO, qc, w.s_mu, w.s_k, w.s_v, w.A_mu,
-                     w.g_A_c, w.g_A_k, w.g_A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.pairmask, w.g_s_c, w.g_s_k,
-                     w.g_s_v, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.scale); }
+                     w.g_A_c, w.g_A_k, w.g_A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask, selc, selb, w.g_s_c, w.g_s_k,
+                     w.g_s_v, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
   const int G_ = d.Hq / d.Hkv;
   if (sizeof(T) == 2) {
     int rc2 = muse_launch_cells_to_keys_mx(d, w.Ks, w.Vs, qc, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs,
