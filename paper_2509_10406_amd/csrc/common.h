@@ -55,6 +55,23 @@ __device__ __forceinline__ void ld4(const bf16_t* p, size_t i, float out[4]) {
   out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xffff0000u);
   out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xffff0000u);
 }
+// a pair of consecutive elements, raw (address aligned to 2 elements), and its two halves as floats
+template <typename T>
+struct Pair;
+template <>
+struct Pair<float> {
+  using raw = float2;
+  __device__ static __forceinline__ raw ld(const float* p, size_t i) { return *reinterpret_cast<const float2*>(p + i); }
+  __device__ static __forceinline__ float lo(raw v) { return v.x; }
+  __device__ static __forceinline__ float hi(raw v) { return v.y; }
+};
+template <>
+struct Pair<bf16_t> {
+  using raw = uint32_t;
+  __device__ static __forceinline__ raw ld(const bf16_t* p, size_t i) { return *reinterpret_cast<const uint32_t*>(p + i); }
+  __device__ static __forceinline__ float lo(raw v) { return __uint_as_float(v << 16); }
+  __device__ static __forceinline__ float hi(raw v) { return __uint_as_float(v & 0xffff0000u); }
+};
 __device__ __forceinline__ void st4(float* p, size_t i, const float v[4]) {
   *reinterpret_cast<float4*>(p + i) = make_float4(v[0], v[1], v[2], v[3]);
 }

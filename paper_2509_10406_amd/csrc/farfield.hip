@@ -90,13 +90,14 @@ __global__ void __launch_bounds__(256) k_tilt_logits(const T* __restrict__ Ks, c
 // sees), b = 0..nb-2.
 // ------------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ void __launch_bounds__(64) k_summaries(const T* __restrict__ Ks, const T* __restrict__ Vs,
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) k_summaries(const T* __restrict__ Ks, const T* __restrict__ Vs,
                                                    const float* __restrict__ L, const int32_t* __restrict__ off_k,
                                                    float* __restrict__ s_mu, float* __restrict__ s_k,
                                                    float* __restrict__ s_v, float* __restrict__ A_mu,
                                                    float* __restrict__ A_k, float* __restrict__ A_v, int h0, int N,
                                                    int nb, int Cq, int Ck, int Hq, int Hkv) {
   constexpr int DS = D / 64;  // slices of the head dim
+  constexpr int KCH = sizeof(T) == 2 ? 16 : 8;  // keys per chunk
   __shared__ float tr[32][68];
   const int j = blockIdx.x, hl = blockIdx.z, hq = h0 + hl;
   const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
@@ -108,8 +109,9 @@ __global__ void __launch_bounds__(64) k_summaries(const T* __restrict__ Ks, cons
   const int NBm = nb - 1;
   const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
   const float* Li = L + ((size_t)hl * Cq + ic) * N;
-  const T* Kh = Ks + (size_t)hk * N * D + d0 + col;
-  const T* Vh = Vs + (size_t)hk * N * D + d0 + col;
+  // accumulator tile x, row m holds head dim d0 + 2 m + x: one paired load feeds both tiles
+  const T* Kh = Ks + (size_t)hk * N * D + d0 + 2 * col;
+  const T* Vh = Vs + (size_t)hk * N * D + d0 + 2 * col;
 
   float Amx = MUSE_NEG_INF, AS = 0.f;
   f32x16_t Aak[2], Aav[2];
@@ -119,15 +121,26 @@ __global__ void __launch_bounds__(64) k_summaries(const T* __restrict__ Ks, cons
     float mx = MUSE_NEG_INF, S = 0.f;
     f32x16_t ak[2], av[2];
     ak[0] = zero16(); ak[1] = zero16(); av[0] = zero16(); av[1] = zero16();
-    for (int c0 = lo; c0 < hi; c0 += 16) {
-      float lg[2][4];
-      float cm = MUSE_NEG_INF;
+    for (int c0 = lo; c0 < hi; c0 += KCH) {
+      // every load of the chunk is issued before the first use: one round trip per chunk
+      float lg[KCH / 8][4];
+      typename Pair<T>::raw kk[KCH / 8][4], vv[KCH / 8][4];
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+      for (int u = 0; u < KCH / 8; ++u)
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          int p = c0 + 8 * u + 4 * half + t;
-          lg[u][t] = p < hi ? Li[p] : MUSE_NEG_INF;
+          const int p = c0 + 8 * u + 4 * half + t;
+          const int pc = p < hi ? p : hi - 1;
+          lg[u][t] = Li[pc];
+          kk[u][t] = Pair<T>::ld(Kh, (size_t)pc * D);
+          vv[u][t] = Pair<T>::ld(Vh, (size_t)pc * D);
+        }
+      float cm = MUSE_NEG_INF;
+#pragma unroll
+      for (int u = 0; u < KCH / 8; ++u)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          lg[u][t] = c0 + 8 * u + 4 * half + t < hi ? lg[u][t] : MUSE_NEG_INF;
           cm = fmaxf(cm, lg[u][t]);
         }
       cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
@@ -140,18 +153,15 @@ __global__ void __launch_bounds__(64) k_summaries(const T* __restrict__ Ks, cons
 #pragma unroll
         for (int e = 0; e < 16; ++e) { ak[x][e] *= resc; av[x][e] *= resc; }
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+      for (int u = 0; u < KCH / 8; ++u)
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const float e = __expf(lg[u][t] - nm);
           S += e;
-          int p = c0 + 8 * u + 4 * half + t;
-          p = p < hi ? p : hi - 1;
-#pragma unroll
-          for (int x = 0; x < 2; ++x) {
-            ak[x] = mfma32(Elem<T>::ld(Kh, (size_t)p * D + 32 * x), e, ak[x]);
-            av[x] = mfma32(Elem<T>::ld(Vh, (size_t)p * D + 32 * x), e, av[x]);
-          }
+          ak[0] = mfma32(Pair<T>::lo(kk[u][t]), e, ak[0]);
+          ak[1] = mfma32(Pair<T>::hi(kk[u][t]), e, ak[1]);
+          av[0] = mfma32(Pair<T>::lo(vv[u][t]), e, av[0]);
+          av[1] = mfma32(Pair<T>::hi(vv[u][t]), e, av[1]);
         }
     }
     S += __shfl_xor(S, 32, 64);
@@ -182,11 +192,10 @@ __global__ void __launch_bounds__(64) k_summaries(const T* __restrict__ Ks, cons
     const size_t rowbase = (((size_t)hl * NBm + b) * Cq + it * 32) * Ck + j;
     auto emit = [&](float* __restrict__ dst, const f32x16_t(&a)[2], float sc) {
 #pragma unroll
-      for (int x = 0; x < 2; ++x)
+      for (int g = 0; g < 4; ++g)
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-          *reinterpret_cast<float4*>(&tr[col][32 * x + 8 * g + 4 * half]) =
-              make_float4(a[x][4 * g] * sc, a[x][4 * g + 1] * sc, a[x][4 * g + 2] * sc, a[x][4 * g + 3] * sc);
+        for (int t = 0; t < 4; ++t)
+          *reinterpret_cast<float2*>(&tr[col][2 * (8 * g + 4 * half + t)]) = make_float2(a[0][4 * g + t] * sc, a[1][4 * g + t] * sc);
       wave_lds_fence();
 #pragma unroll
       for (int ps = 0; ps < 8; ++ps) {
