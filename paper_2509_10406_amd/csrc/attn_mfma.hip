@@ -49,7 +49,7 @@ __device__ __forceinline__ void load_tile(const bf16_t* __restrict__ src, int r0
 }
 
 template <int D>
-__global__ void __launch_bounds__(256) k_flash_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2, D == 64 ? 4 : 2))) k_flash_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                     const bf16_t* __restrict__ V, const float* __restrict__ ff,
                                                     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, int Bs,
                                                     int Hq, int Hkv, float scale_log2e) {
@@ -179,7 +179,7 @@ __global__ void __launch_bounds__(256) k_flash_fwd(const bf16_t* __restrict__ Q,
 }
 
 template <int D>
-__global__ void __launch_bounds__(256) k_flash_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2, D == 64 ? 4 : 2))) k_flash_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                        const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO,
                                                        const float* __restrict__ LSE, const float* __restrict__ delta,
                                                        float* __restrict__ dQ, int N, int Bs, int Hq, int Hkv,
@@ -260,7 +260,7 @@ __global__ void __launch_bounds__(256) k_flash_bwd_dq(const bf16_t* __restrict__
 }
 
 template <int D>
-__global__ void __launch_bounds__(256) k_flash_bwd_dkv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, D == 64 ? 2 : 1))) k_flash_bwd_dkv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                         const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO,
                                                         const float* __restrict__ LSE, const float* __restrict__ delta,
                                                         float* __restrict__ dK, float* __restrict__ dV, int N, int Bs,
