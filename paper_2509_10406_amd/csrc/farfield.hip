@@ -216,23 +216,20 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 // ------------------------------------------------------------------------------------------
 // the per-query-tile far-field kernel: one wave per tile of up to 32 queries of one
-// (spatial block b >= 1, query cluster i)
+// (spatial block b >= 1, query cluster i): cluster scores (Eq. 7), the r retrieved clusters, and the
+// monopole attention over all other clusters (component 1) as a partial softmax state
 // ------------------------------------------------------------------------------------------
 template <typename T, int D, int RCAP>
-__global__ void __launch_bounds__(64) k_farfield_fwd(
-    const T* __restrict__ Q, const float* __restrict__ qc, const T* __restrict__ Ks, const T* __restrict__ Vs,
-    const float* __restrict__ L, const float* __restrict__ s_mu, const float* __restrict__ s_k,
-    const float* __restrict__ s_v, const float* __restrict__ A_mu, const float* __restrict__ A_k,
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2))) k_farfield_fwd(
+    const T* __restrict__ Q, const float* __restrict__ qc, const float* __restrict__ A_mu, const float* __restrict__ A_k,
     const float* __restrict__ A_v, const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q,
-    const int32_t* __restrict__ off_k, const int32_t* __restrict__ tile_off, float* __restrict__ ff_acc,
-    float* __restrict__ ff_ml, int32_t* __restrict__ selc, int32_t* __restrict__ selb, int h0, int N, int nb, int Cq,
-    int Ck, int r, int k2e, int Hq, int Hkv, float scale) {
+    const int32_t* __restrict__ tile_off, float* __restrict__ ff_acc, float* __restrict__ ff_ml,
+    int32_t* __restrict__ selc, int h0, int N, int nb, int Cq, int Ck, int r, float scale) {
   constexpr int U = D / 8, DT = D / 32;
   __shared__ float cs[64][RCAP];
   __shared__ int ci[64][RCAP];
   __shared__ int sel_s[32][RCAP];
   const int hl = blockIdx.z, hq = h0 + hl;
-  const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
   const int b = blockIdx.y + 1, NBm = nb - 1;
   const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
 
@@ -246,7 +243,6 @@ __global__ void __launch_bounds__(64) k_farfield_fwd(
   }
   const int i = lo_, tt = tile - to[lo_];
   const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
-  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
   const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
   int pos = qlo + 32 * tt + col;
   const bool valid = pos < qhi;
@@ -386,89 +382,6 @@ __global__ void __launch_bounds__(64) k_farfield_fwd(
       for (int k = 0; k < r; ++k) out[k] = k < total ? sel_s[col][k] : -1;
     }
   }
-  // ---- per selected cluster: block selection on the per-block summaries, components 2 and 3 ----
-  for (int t = 0; t < r; ++t) {
-    const int j = sel_s[col][t];
-    if (j < 0) continue;
-    float sc2[15];
-#pragma unroll
-    for (int bp = 0; bp < 15; ++bp) {
-      sc2[bp] = MUSE_NEG_INF;
-      if (bp < b) {
-        const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
-        const float mu = s_mu[cell];
-        if (mu > MUSE_NEG_INF) {
-          const float* kr = s_k + cell * D + 4 * half;
-          float part = 0.f;
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            float4 k4 = *reinterpret_cast<const float4*>(kr + 8 * u);
-            part = fmaf(qt[u][0], k4.x, part); part = fmaf(qt[u][1], k4.y, part);
-            part = fmaf(qt[u][2], k4.z, part); part = fmaf(qt[u][3], k4.w, part);
-          }
-          part += __shfl_xor(part, 32, 64);
-          sc2[bp] = part + mu;
-        }
-      }
-    }
-    unsigned selbits = 0;
-    for (int u = 0; u < k2e; ++u) {
-      float best = MUSE_NEG_INF;
-      int bi = -1;
-#pragma unroll
-      for (int bp = 0; bp < 15; ++bp)
-        if (!((selbits >> bp) & 1u) && sc2[bp] > best) { best = sc2[bp]; bi = bp; }
-      if (bi >= 0) selbits |= 1u << bi;
-      if (valid && half == 0) selb[(((size_t)hq * N + n) * r + t) * k2e + u] = bi;
-    }
-#pragma unroll
-    for (int bp = 0; bp < 15; ++bp) {
-      if (!(sc2[bp] > MUSE_NEG_INF)) continue;
-      if (!((selbits >> bp) & 1u)) {  // component 2: summary of a non-retrieved block
-        const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
-        const float* vr = s_v + cell * D + 4 * half;
-        float mn = fmaxf(m, sc2[bp]);
-        float a = __expf(m - mn), p = __expf(sc2[bp] - mn);
-        l = l * a + (half == 0 ? p : 0.f);
-        m = mn;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          float4 v4 = *reinterpret_cast<const float4*>(vr + 8 * u);
-          o[u / 4][4 * (u % 4) + 0] = o[u / 4][4 * (u % 4) + 0] * a + p * v4.x;
-          o[u / 4][4 * (u % 4) + 1] = o[u / 4][4 * (u % 4) + 1] * a + p * v4.y;
-          o[u / 4][4 * (u % 4) + 2] = o[u / 4][4 * (u % 4) + 2] * a + p * v4.z;
-          o[u / 4][4 * (u % 4) + 3] = o[u / 4][4 * (u % 4) + 3] * a + p * v4.w;
-        }
-      } else if (sizeof(T) == 4) {  // component 3 (fp32 inputs; bf16 inputs use the pair kernels on the matrix cores)
-        const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
-        for (int p_ = klo; p_ < khi; ++p_) {
-          const size_t krow = ((size_t)hk * N + p_) * D + 4 * half;
-          float part = 0.f;
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            float k4[4];
-            ld4(Ks, krow + 8 * u, k4);
-            part = fmaf(qt[u][0], k4[0], part); part = fmaf(qt[u][1], k4[1], part);
-            part = fmaf(qt[u][2], k4[2], part); part = fmaf(qt[u][3], k4[3], part);
-          }
-          part += __shfl_xor(part, 32, 64);
-          const float lg = part + L[((size_t)hl * Cq + i) * N + p_];  // q.k = q~.k + q-bar.k
-          float mn = fmaxf(m, lg);
-          float a = __expf(m - mn), p = __expf(lg - mn);
-          l = l * a + (half == 0 ? p : 0.f);
-          m = mn;
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            float v4[4];
-            ld4(Vs, krow + 8 * u, v4);
-#pragma unroll
-            for (int x = 0; x < 4; ++x)
-              o[u / 4][4 * (u % 4) + x] = o[u / 4][4 * (u % 4) + x] * a + p * v4[x];
-          }
-        }
-      }
-    }
-  }
   l += __shfl_xor(l, 32, 64);
   if (!valid) return;
   float* fa = ff_acc + ((size_t)hq * N + n) * D + 4 * half;
@@ -480,6 +393,184 @@ __global__ void __launch_bounds__(64) k_farfield_fwd(
   if (half == 0) {
     ff_ml[((size_t)hq * N + n) * 2] = m;
     ff_ml[((size_t)hq * N + n) * 2 + 1] = l;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Per query (blocks >= 1), over its r retrieved clusters: block selection on the per-block summaries
+// (scores q~.k-bar + mu-bar of the preceding blocks, the k2 largest are retrieved, ties to the earlier
+// block), then component 2 = monopole attention over the per-block summaries of the blocks NOT
+// retrieved; fp32 inputs also take component 3 (exact attention over the retrieved pairs) here, bf16
+// inputs take it on the matrix cores in the pair kernels.  The result is merged into the query's
+// far-field state.  16 lanes per query, a lane owns the dims 64 x + 4 l16 + t; queries are visited in
+// bucketed order so that neighbours share the summary rows.
+// ------------------------------------------------------------------------------------------
+template <typename T, int D, int NBC>
+__global__ void __launch_bounds__(256) k_comp2_fwd(
+    const T* __restrict__ Q, const float* __restrict__ qc, const T* __restrict__ Ks, const T* __restrict__ Vs,
+    const float* __restrict__ L, const float* __restrict__ s_mu, const float* __restrict__ s_k,
+    const float* __restrict__ s_v, const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_k,
+    const int32_t* __restrict__ aq, const int32_t* __restrict__ selc, int32_t* __restrict__ selb,
+    float* __restrict__ ff_acc, float* __restrict__ ff_ml, int h0, int N, int nb, int Bs, int Cq, int Ck, int r,
+    int k2e, int Hq, int Hkv, float scale) {
+  constexpr int NG = D / 64;
+  const int hl = blockIdx.y, hq = h0 + hl;
+  const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
+  const int l16 = threadIdx.x % 16;
+  const int pos = Bs + blockIdx.x * 16 + threadIdx.x / 16;  // bucketed order is block-major: block 0 comes first
+  if (pos >= N) return;
+  const int n = perm_q[(size_t)hq * N + pos];
+  const size_t qn = (size_t)hq * N + n;
+  const int b = n / Bs, NBm = nb - 1;
+  const int i = aq[qn];
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  float qt[NG][4];
+#pragma unroll
+  for (int x = 0; x < NG; ++x) {
+    float q4[4];
+    ld4(Q, qn * D + 64 * x + 4 * l16, q4);
+    const float4 c4 = *reinterpret_cast<const float4*>(qc + ((size_t)hq * Cq + i) * D + 64 * x + 4 * l16);
+    qt[x][0] = scale * (q4[0] - c4.x); qt[x][1] = scale * (q4[1] - c4.y);
+    qt[x][2] = scale * (q4[2] - c4.z); qt[x][3] = scale * (q4[3] - c4.w);
+  }
+  float m = MUSE_NEG_INF, l = 0.f, o[NG][4];
+#pragma unroll
+  for (int x = 0; x < NG; ++x)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) o[x][t] = 0.f;
+  auto add = [&](float lg, const float (&v)[NG][4]) {  // one more (logit, value row) into the running state
+    const float mn = fmaxf(m, lg);
+    const float a = __expf(m - mn), p = __expf(lg - mn);
+    l = l * a + p;
+    m = mn;
+#pragma unroll
+    for (int x = 0; x < NG; ++x)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) o[x][t] = o[x][t] * a + p * v[x][t];
+  };
+  for (int t = 0; t < r; ++t) {
+    const int j = selc[qn * r + t];
+    if (j < 0) continue;
+    // scores of the preceding blocks, 8 at a time: every load of a chunk is in flight together (with at
+    // most 8 preceding blocks the value rows ride along, one round trip per retrieved cluster)
+    float sc2[8 * NBC];
+#pragma unroll
+    for (int bp = 0; bp < 8 * NBC; ++bp) sc2[bp] = MUSE_NEG_INF;
+    float4 vr[8][NG];
+#pragma unroll
+    for (int c0 = 0; c0 < 8 * NBC; c0 += 8) {
+      if (c0 >= b) break;
+      float mu[8], part[8];
+      float4 kr[8][NG];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int bp = c0 + u < b ? c0 + u : b - 1;
+        const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
+        mu[u] = s_mu[cell];
+#pragma unroll
+        for (int x = 0; x < NG; ++x) {
+          kr[u][x] = *reinterpret_cast<const float4*>(s_k + cell * D + 64 * x + 4 * l16);
+          if (NBC == 1) vr[u][x] = *reinterpret_cast<const float4*>(s_v + cell * D + 64 * x + 4 * l16);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        float pa = 0.f;
+#pragma unroll
+        for (int x = 0; x < NG; ++x) {
+          pa = fmaf(qt[x][0], kr[u][x].x, pa); pa = fmaf(qt[x][1], kr[u][x].y, pa);
+          pa = fmaf(qt[x][2], kr[u][x].z, pa); pa = fmaf(qt[x][3], kr[u][x].w, pa);
+        }
+        part[u] = pa;
+      }
+#pragma unroll
+      for (int sh = 1; sh < 16; sh <<= 1)
+#pragma unroll
+        for (int u = 0; u < 8; ++u) part[u] += __shfl_xor(part[u], sh, 64);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (c0 + u < b && mu[u] > MUSE_NEG_INF) sc2[c0 + u] = part[u] + mu[u];
+    }
+    unsigned selbits = 0;
+    for (int u = 0; u < k2e; ++u) {
+      float best = MUSE_NEG_INF;
+      int bi = -1;
+#pragma unroll
+      for (int bp = 0; bp < 8 * NBC; ++bp)
+        if (!((selbits >> bp) & 1u) && sc2[bp] > best) { best = sc2[bp]; bi = bp; }
+      if (bi >= 0) selbits |= 1u << bi;
+      if (l16 == 0) selb[(qn * r + t) * k2e + u] = bi;
+    }
+    // component 2: value summaries of the blocks that are not retrieved
+#pragma unroll
+    for (int c0 = 0; c0 < 8 * NBC; c0 += 8) {
+      if (c0 >= b) break;
+      if (NBC > 1) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int bp = c0 + u < b ? c0 + u : b - 1;
+          const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
+#pragma unroll
+          for (int x = 0; x < NG; ++x) vr[u][x] = *reinterpret_cast<const float4*>(s_v + cell * D + 64 * x + 4 * l16);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (!(sc2[c0 + u] > MUSE_NEG_INF) || ((selbits >> (c0 + u)) & 1u)) continue;
+        float v[NG][4];
+#pragma unroll
+        for (int x = 0; x < NG; ++x) { v[x][0] = vr[u][x].x; v[x][1] = vr[u][x].y; v[x][2] = vr[u][x].z; v[x][3] = vr[u][x].w; }
+        add(sc2[c0 + u], v);
+      }
+    }
+    if (sizeof(T) == 4) {  // component 3: the keys of the retrieved (cluster, block) pairs, with the full query
+      for (int bp = 0; bp < b; ++bp) {
+        if (!((selbits >> bp) & 1u)) continue;
+        const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
+        for (int p_ = klo; p_ < khi; ++p_) {
+          const size_t krow = ((size_t)hk * N + p_) * D;
+          float pa = 0.f, v[NG][4];
+#pragma unroll
+          for (int x = 0; x < NG; ++x) {
+            float k4[4];
+            ld4(Ks, krow + 64 * x + 4 * l16, k4);
+            ld4(Vs, krow + 64 * x + 4 * l16, v[x]);
+            pa = fmaf(qt[x][0], k4[0], pa); pa = fmaf(qt[x][1], k4[1], pa);
+            pa = fmaf(qt[x][2], k4[2], pa); pa = fmaf(qt[x][3], k4[3], pa);
+          }
+#pragma unroll
+          for (int sh = 1; sh < 16; sh <<= 1) pa += __shfl_xor(pa, sh, 64);
+          add(pa + L[((size_t)hl * Cq + i) * N + p_], v);  // q.k = q~.k + q-bar.k
+        }
+      }
+    }
+  }
+  if (!(l > 0.f)) return;
+  // merge into the far-field state left by the tile kernel
+  float fm = ff_ml[qn * 2], fl = ff_ml[qn * 2 + 1];
+  float fa[NG][4];
+#pragma unroll
+  for (int x = 0; x < NG; ++x) {
+    const float4 a4 = *reinterpret_cast<const float4*>(ff_acc + qn * D + 64 * x + 4 * l16);
+    fa[x][0] = a4.x; fa[x][1] = a4.y; fa[x][2] = a4.z; fa[x][3] = a4.w;
+  }
+  if (!(fl > 0.f)) {
+    fm = MUSE_NEG_INF; fl = 0.f;
+#pragma unroll
+    for (int x = 0; x < NG; ++x)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) fa[x][t] = 0.f;
+  }
+  const float mn = fmaxf(fm, m);
+  const float ca = __expf(fm - mn), cb = __expf(m - mn);
+#pragma unroll
+  for (int x = 0; x < NG; ++x)
+    *reinterpret_cast<float4*>(ff_acc + qn * D + 64 * x + 4 * l16) =
+        make_float4(fa[x][0] * ca + o[x][0] * cb, fa[x][1] * ca + o[x][1] * cb, fa[x][2] * ca + o[x][2] * cb,
+                    fa[x][3] * ca + o[x][3] * cb);
+  if (l16 == 0) {
+    ff_ml[qn * 2] = mn;
+    ff_ml[qn * 2 + 1] = fl * ca + l * cb;
   }
 }
 
@@ -599,20 +690,30 @@ template int muse_ff_summaries<bf16_t>(const MuseDims&, const float*, FFWorkspac
 namespace {
 
 template <typename T, int D, int RCAP>
-void launch_ff_fwd(const MuseDims& d, const T* Q, const float* qc, FFWorkspace& w, int32_t* selc, int32_t* selb, int h0,
-                   int hn, hipStream_t st) {
+void launch_ff_fwd(const MuseDims& d, const T* Q, const float* qc, FFWorkspace& w, int32_t* selc, int h0, int hn,
+                   hipStream_t st) {
   dim3 g(d.Bs / 32 + d.Cq + 1, d.nb - 1, hn);
-  { MuseProf prof_("k_farfield_fwd", st); hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, (const T*)w.Ks, (const T*)w.Vs, w.L,
-                     w.s_mu, w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q, w.off_k, w.tile_off, w.ff_acc,
-                     w.ff_ml, selc, selb, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
+  { MuseProf prof_("k_farfield_fwd", st); hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q,
+                     w.tile_off, w.ff_acc, w.ff_ml, selc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.scale); }
 }
 
 template <typename T, int D>
-void launch_ff_fwd_r(const MuseDims& d, const T* Q, const float* qc, FFWorkspace& w, int32_t* selc, int32_t* selb,
-                     int h0, int hn, hipStream_t st) {
-  if (d.r <= 8) launch_ff_fwd<T, D, 8>(d, Q, qc, w, selc, selb, h0, hn, st);
-  else if (d.r <= 16) launch_ff_fwd<T, D, 16>(d, Q, qc, w, selc, selb, h0, hn, st);
-  else launch_ff_fwd<T, D, 32>(d, Q, qc, w, selc, selb, h0, hn, st);
+void launch_ff_fwd_r(const MuseDims& d, const T* Q, const float* qc, const int32_t* aq, FFWorkspace& w, int32_t* selc,
+                     int32_t* selb, int h0, int hn, hipStream_t st) {
+  if (d.r <= 8) launch_ff_fwd<T, D, 8>(d, Q, qc, w, selc, h0, hn, st);
+  else if (d.r <= 16) launch_ff_fwd<T, D, 16>(d, Q, qc, w, selc, h0, hn, st);
+  else launch_ff_fwd<T, D, 32>(d, Q, qc, w, selc, h0, hn, st);
+  if (d.r > 0) {
+    dim3 g((d.N - d.Bs + 15) / 16, hn);
+    if (d.nb <= 9)
+      { MuseProf prof_("k_comp2_fwd", st); hipLaunchKernelGGL((k_comp2_fwd<T, D, 1>), g, dim3(256), 0, st, Q, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu, w.s_k,
+                         w.s_v, w.perm_q, w.off_k, aq, selc, selb, w.ff_acc, w.ff_ml, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r,
+                         d.k2e, d.Hq, d.Hkv, d.scale); }
+    else
+      { MuseProf prof_("k_comp2_fwd", st); hipLaunchKernelGGL((k_comp2_fwd<T, D, 2>), g, dim3(256), 0, st, Q, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu, w.s_k,
+                         w.s_v, w.perm_q, w.off_k, aq, selc, selb, w.ff_acc, w.ff_ml, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r,
+                         d.k2e, d.Hq, d.Hkv, d.scale); }
+  }
 }
 
 template <typename T>
@@ -627,8 +728,8 @@ int run_fwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const f
     for (int h0 = 0; h0 < HQ; h0 += w.hc) {
       int hn = HQ - h0 < w.hc ? HQ - h0 : w.hc;
       if ((rc = muse_ff_summaries<T>(d, qc, w, h0, hn, st))) return rc;
-      if (d.D == 64) launch_ff_fwd_r<T, 64>(d, Q, qc, w, selc, selb, h0, hn, st);
-      else launch_ff_fwd_r<T, 128>(d, Q, qc, w, selc, selb, h0, hn, st);
+      if (d.D == 64) launch_ff_fwd_r<T, 64>(d, Q, qc, aq, w, selc, selb, h0, hn, st);
+      else launch_ff_fwd_r<T, 128>(d, Q, qc, aq, w, selc, selb, h0, hn, st);
       MUSE_LAUNCH_CHECK();
     }
   }
