@@ -25,27 +25,37 @@ PEAK = {"mfma_bf16": 2.5e15, "mfma_fp32": 157.3e12, "hbm": 8.0e12}
 
 def kernel_models(w, p):
     """Algorithmic work per LAUNCH of each kernel at workload w (all heads of one launch).
-    Masked (causal) tiles count at half.  Returns {kernel: (bound, peak, amount, unit)}."""
-    H, Hk, N, D, Bs, Cq, Ck = w.B * w.Hq, w.B * w.Hkv, w.N, w.D, w.Bs, w.Cq, w.Ck
+    Masked (causal) tiles count at half.  Returns {kernel: (bound, peak, amount, unit)}; kernels that are
+    not listed (index building, merges, fills) take no part in the choice of the dominant kernel."""
+    H, Hk, N, D, Bs, Cq, Ck, r = w.B * w.Hq, w.B * w.Hkv, w.N, w.D, w.Bs, w.Cq, w.Ck, w.r
     nb = N // Bs
+    k2e = w.k2 if w.k2 > 0 else max(nb - 1, 1)
     Nff = N * (nb - 1) // nb           # queries that have a far field / keys that are summarised
     cells = (nb - 1) * Cq * Ck
-    cellb = cells * (2 * D + 1) * 4    # bytes of one copy of the summaries tensor, one head
+    cellb = cells * (2 * D + 1) * 4    # bytes of one copy of the summaries tensor (mu, k-bar, v-bar), one head
     es = 2 if w.dtype == "bf16" else 4
+    far = "mfma_bf16" if w.dtype == "bf16" else "mfma_fp32"   # gradient contractions of the far field
+    pair_keys = Nff * r * k2e * (Bs / Ck)                     # (query, retrieved pair) x keys of an average pair
     m = {}
     m["k_flash_fwd"] = ("mfma", PEAK["mfma_bf16"], 2 * N * Bs * D * H, "flop")          # QK^T + PV
     m["k_flash_bwd_dq"] = ("mfma", PEAK["mfma_bf16"], 3 * N * Bs * D * H, "flop")        # S, dP, dQ
     m["k_flash_bwd_dkv"] = ("mfma", PEAK["mfma_bf16"], 4 * N * Bs * D * H, "flop")       # S, dP, dV, dK
     # k-means assignment: one launch per tensor per pass; report the key launch (larger C)
     m["k_assign_bf16"] = ("mfma", PEAK["mfma_bf16"], 2 * N * Ck * D * Hk, "flop")
-    m["k_farfield_fwd"] = ("mfma", PEAK["mfma_fp32"], 2 * 2 * Nff * Ck * D * H, "flop")  # scores + PV
-    m["k_ff_bwd_dq"] = ("mfma", PEAK["mfma_fp32"], 3 * 2 * Nff * Ck * D * H, "flop")
-    m["k_ff_bwd_cells"] = ("mfma", PEAK["mfma_fp32"], 4 * 2 * Nff * Ck * D * H, "flop")
-    m["k_cells_to_keys"] = ("mfma", PEAK["mfma_fp32"], 5 * 2 * Cq * Nff * D * H, "flop")
+    # forward tile kernel: cluster scores (fp32, they decide the selection) + monopole PV
+    m["k_farfield_fwd"] = ("mfma", PEAK["mfma_fp32"], 2 * 2 * Nff * Ck * D * H, "flop")
+    for name, nmm in (("k_ff_bwd_dq", 3), ("k_ff_bwd_cells_mx", 4), ("k_ff_bwd_cells", 4)):
+        m[name] = ("mfma", PEAK[far], nmm * 2 * Nff * Ck * D * H, "flop")
+    for name in ("k_cells_to_keys_mx", "k_cells_to_keys"):
+        m[name] = ("mfma", PEAK[far], 5 * 2 * Cq * Nff * D * H, "flop")
+    m["k_ret_fwd_pairs"] = ("mfma", PEAK["mfma_bf16"], 2 * 2 * pair_keys * D * H, "flop")
+    m["k_ret_bwd_dq_pairs"] = ("mfma", PEAK["mfma_bf16"], 3 * 2 * pair_keys * D * H, "flop")
+    m["k_c3_pairs"] = ("mfma", PEAK["mfma_bf16"], 4 * 2 * pair_keys * D * H, "flop")
+    # writes both copies of the summaries (per block, accumulated); reads the tilt logits and K, V once
     m["k_summaries"] = ("hbm", PEAK["hbm"], (2 * cellb + Cq * Nff * 4 + 2 * Nff * D * es) * H, "byte")
-    m["k_cell_scan_bwd"] = ("hbm", PEAK["hbm"], 3 * cellb * H, "byte")                   # read gA, gs; write G
+    # reads the gradients of the accumulated cells and mu of both copies, writes the gradients of the per-block cells
+    m["k_cell_grads"] = ("hbm", PEAK["hbm"], (2 * cellb + 2 * cells * 4) * H, "byte")
     m["k_tilt_logits"] = ("hbm", PEAK["hbm"], (Cq * N * 4 + N * D * es) * H, "byte")
-    m["k_fill"] = ("hbm", PEAK["hbm"], None, "byte")
     return m
 
 
@@ -148,7 +158,7 @@ def main():
     ach = amount / avg_s
     roofline = {"kernel": dom, "bound": bound, "achieved": ach / (1e12 if unit == "flop" else 1e9),
                 "peak": peak / (1e12 if unit == "flop" else 1e9), "unit": "TFLOP/s" if unit == "flop" else "GB/s",
-                "frac": ach / peak, "traffic": None, "avg_launch_ms": tms / cnt, "launches_per_step": cnt / nprof,
+                "frac": ach / peak, "traffic": measured_traffic(dom, a.workload), "avg_launch_ms": tms / cnt, "launches_per_step": cnt / nprof,
                 "share_of_step": tms / tot}
     breakdown = {k: round(v[1] / nprof, 3) for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])}
     fracs = {}
@@ -182,6 +192,18 @@ def main():
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, d, p)
     print(json.dumps(out))
+
+
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` from the committed counter summary (rocprofv3 --pmc FETCH_SIZE and
+    WRITE_SIZE runs, scaled as the design doc states), or None when no summary covers it."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.json")
+    try:
+        with open(path) as f:
+            t = json.load(f)["kernels"].get(kernel)
+        return None if t is None else float(t["fetch_bytes"] + t["write_bytes"])
+    except (OSError, ValueError, KeyError):
+        return None
 
 
 def cpu_baseline(w, d, p):

@@ -112,8 +112,8 @@ int muse_fwd(const muse_params* p, const void* Q, const void* K, const void* V,
  * into K and V through the tilted aggregation weights (the default of App. C "Aggregation Weight
  * Gradient Flow").  O, LSE, sel_* are the outputs of muse_fwd for the same inputs.
  *   dQ [B,Hq,N,D], dK, dV [B,Hkv,N,D] of grad_dtype (summed over the query heads of a group)   (out)
- * Sums over many queries into one key use fp32 atomics in the retrieval stage, so the last bits of
- * dK, dV may differ between runs. */
+ * Every sum has a single owner and a fixed order (no floating-point atomics): repeated calls, and calls
+ * whose workspace forces a different chunking of the heads, return identical bits. */
 int muse_bwd(const muse_params* p, const void* Q, const void* K, const void* V,
              const void* O, const float* LSE, const void* dO,
              const float* q_centroids, const int32_t* q_assign, const int32_t* k_assign,

@@ -9,6 +9,8 @@
 // contractions), so the discrete choices agree with an fp64 evaluation up to fp32 rounding.
 #include "ff_common.h"
 
+#include <type_traits>
+
 namespace {
 
 // ------------------------------------------------------------------------------------------
@@ -220,12 +222,14 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 // monopole attention over all other clusters (component 1) as a partial softmax state
 // ------------------------------------------------------------------------------------------
 template <typename T, int D, int RCAP>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2))) k_farfield_fwd(
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, D == 64 ? 2 : 2))) k_farfield_fwd(
     const T* __restrict__ Q, const float* __restrict__ qc, const float* __restrict__ A_mu, const float* __restrict__ A_k,
     const float* __restrict__ A_v, const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q,
     const int32_t* __restrict__ tile_off, float* __restrict__ ff_acc, float* __restrict__ ff_ml,
     int32_t* __restrict__ selc, int h0, int N, int nb, int Cq, int Ck, int r, float scale) {
   constexpr int U = D / 8, DT = D / 32;
+  // output tile x, row m holds head dim DT*m + x: a lane reads DT consecutive dims of a value row at once
+  using VRow = typename std::conditional<DT == 2, float2, float4>::type;
   __shared__ float cs[64][RCAP];
   __shared__ int ci[64][RCAP];
   __shared__ int sel_s[32][RCAP];
@@ -272,16 +276,26 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
   float list[RCAP];
 #pragma unroll
   for (int k = 0; k < RCAP; ++k) list[k] = MUSE_NEG_INF;
-  for (int jt = 0; jt < ntile; ++jt) {
-    f32x16_t acc = score_tile<D>(Amu, Ak, jt * 32, Ck, qt, col, half);
+  {
+    // insertion into the sorted list: new l_k = med3(x, l_{k-1}, l_k), new l_0 = max(x, l_0)
+    auto insert = [&](const f32x16_t& acc) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      float x = acc[e];
+      for (int e = 0; e < 16; ++e) {
+        const float x = acc[e];
 #pragma unroll
-      for (int k = 0; k < RCAP; ++k) {
-        float hi = fmaxf(list[k], x);
-        x = fminf(list[k], x);
-        list[k] = hi;
+        for (int k = RCAP - 1; k > 0; --k) list[k] = __builtin_amdgcn_fmed3f(x, list[k - 1], list[k]);
+        list[0] = fmaxf(list[0], x);
+      }
+    };
+    // two tile buffers: the loads of the next tile are in flight while this one is scored
+    KTile<D> ka, kb;
+    load_ktile<D>(ka, Amu, Ak, 0, Ck, col, half);
+    for (int jt = 0; jt < ntile; jt += 2) {
+      if (jt + 1 < ntile) load_ktile<D>(kb, Amu, Ak, (jt + 1) * 32, Ck, col, half);
+      insert(score_ktile<D>(ka, jt * 32, Ck, qt, half));
+      if (jt + 1 < ntile) {
+        if (jt + 2 < ntile) load_ktile<D>(ka, Amu, Ak, (jt + 2) * 32, Ck, col, half);
+        insert(score_ktile<D>(kb, (jt + 1) * 32, Ck, qt, half));
       }
     }
   }
@@ -317,7 +331,17 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
   int eqc = 0, ncand = 0;
   for (int jt = 0; jt < ntile; ++jt) {
     const int j0 = jt * 32;
-    f32x16_t acc = score_tile<D>(Amu, Ak, j0, Ck, qt, col, half);
+    // all loads of the tile first: k-bar rows, mu-bar, and the DT consecutive dims DT*col .. of the 16 value rows
+    KTile<D> kt;
+    load_ktile<D>(kt, Amu, Ak, j0, Ck, col, half);
+    VRow vv[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+      jr = jr < Ck ? jr : Ck - 1;
+      vv[e] = *reinterpret_cast<const VRow*>(Av + (size_t)jr * D + DT * col);
+    }
+    f32x16_t acc = score_ktile<D>(kt, j0, Ck, qt, half);
     float tmax = MUSE_NEG_INF;
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
@@ -351,15 +375,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
 #pragma unroll
       for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
+    for (int e = 0; e < 16; ++e) {
+      const float* vf = reinterpret_cast<const float*>(&vv[e]);
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        int jr = j0 + 8 * g + 4 * half + t;
-        jr = jr < Ck ? jr : Ck - 1;
-        const float* vrow = Av + (size_t)jr * D + col;
-#pragma unroll
-        for (int x = 0; x < DT; ++x) o[x] = mfma32(vrow[32 * x], acc[4 * g + t], o[x]);
-      }
+      for (int x = 0; x < DT; ++x) o[x] = mfma32(vf[x], acc[e], o[x]);
+    }
   }
   // ---- order the selected clusters of each query by (score desc, index asc) ----
   for (int k = lane; k < 32 * RCAP; k += 64) (&sel_s[0][0])[k] = -1;
@@ -384,11 +404,20 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
   }
   l += __shfl_xor(l, 32, 64);
   if (!valid) return;
-  float* fa = ff_acc + ((size_t)hq * N + n) * D + 4 * half;
+  float* fa = ff_acc + ((size_t)hq * N + n) * D;
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
-    *reinterpret_cast<float4*>(fa + 8 * u) = make_float4(o[u / 4][4 * (u % 4)], o[u / 4][4 * (u % 4) + 1],
-                                                         o[u / 4][4 * (u % 4) + 2], o[u / 4][4 * (u % 4) + 3]);
+  for (int g = 0; g < 4; ++g) {
+    if (DT == 2) {
+#pragma unroll
+      for (int tp = 0; tp < 2; ++tp)
+        *reinterpret_cast<float4*>(fa + 2 * (8 * g + 4 * half + 2 * tp)) =
+            make_float4(o[0][4 * g + 2 * tp], o[1][4 * g + 2 * tp], o[0][4 * g + 2 * tp + 1], o[1][4 * g + 2 * tp + 1]);
+    } else {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        *reinterpret_cast<float4*>(fa + 4 * (8 * g + 4 * half + t)) =
+            make_float4(o[0][4 * g + t], o[1][4 * g + t], o[2 % DT][4 * g + t], o[3 % DT][4 * g + t]);
+    }
   }
   if (half == 0) {
     ff_ml[((size_t)hq * N + n) * 2] = m;

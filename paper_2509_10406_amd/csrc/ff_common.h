@@ -37,22 +37,66 @@ __device__ __forceinline__ f32x16_t mfma_rows(f32x16_t acc, const float* __restr
   return acc;
 }
 
+// One tile of 32 accumulated key summaries as the score MFMAs consume it: the lane's row-pattern groups
+// of k-bar and its 16 mu-bar values.  Loading is separate from use so that every load of a tile is in
+// flight before the first MFMA waits on one.
+template <int D>
+struct KTile {
+  float4 a[D / 8];
+  float mu[16];
+};
+
+template <int D>
+__device__ __forceinline__ void load_ktile(KTile<D>& kt, const float* __restrict__ Amu, const float* __restrict__ Ak,
+                                           int j0, int Ck, int col, int half) {
+  int c = j0 + col;
+  c = c < Ck ? c : Ck - 1;
+  const float* row = Ak + (size_t)c * D + 4 * half;
+#pragma unroll
+  for (int u = 0; u < D / 8; ++u) kt.a[u] = *reinterpret_cast<const float4*>(row + 8 * u);
+  if ((Ck & 3) == 0) {  // rows 8g + 4 half + t, t = 0..3, are one aligned float4
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      int base = j0 + 8 * g + 4 * half;
+      base = base < Ck ? base : Ck - 4;
+      const float4 m4 = *reinterpret_cast<const float4*>(Amu + base);
+      kt.mu[4 * g] = m4.x; kt.mu[4 * g + 1] = m4.y; kt.mu[4 * g + 2] = m4.z; kt.mu[4 * g + 3] = m4.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+      kt.mu[e] = Amu[jr < Ck ? jr : Ck - 1];
+    }
+  }
+}
+
 // scores^T of 32 key clusters (rows) x 32 queries (columns) against accumulated summaries, Eq. 7:
 // accumulator preloaded with mu-bar, then += k-bar . q~
 template <int D>
-__device__ __forceinline__ f32x16_t score_tile(const float* __restrict__ Amu, const float* __restrict__ Ak, int j0,
-                                               int Ck, const float (&qt)[D / 8][4], int col, int half) {
+__device__ __forceinline__ f32x16_t score_ktile(const KTile<D>& kt, int j0, int Ck, const float (&qt)[D / 8][4], int half) {
   f32x16_t acc;
 #pragma unroll
-  for (int g = 0; g < 4; ++g)
+  for (int e = 0; e < 16; ++e) {
+    const int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+    acc[e] = jr < Ck ? kt.mu[e] : MUSE_NEG_INF;
+  }
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      int jr = j0 + 8 * g + 4 * half + t;
-      acc[4 * g + t] = jr < Ck ? Amu[jr] : MUSE_NEG_INF;
-    }
-  int c = j0 + col;
-  c = c < Ck ? c : Ck - 1;
-  return mfma_rows<D>(acc, Ak + (size_t)c * D + 4 * half, qt);
+  for (int u = 0; u < D / 8; ++u) {
+    acc = mfma32(kt.a[u].x, qt[u][0], acc);
+    acc = mfma32(kt.a[u].y, qt[u][1], acc);
+    acc = mfma32(kt.a[u].z, qt[u][2], acc);
+    acc = mfma32(kt.a[u].w, qt[u][3], acc);
+  }
+  return acc;
+}
+
+template <int D>
+__device__ __forceinline__ f32x16_t score_tile(const float* __restrict__ Amu, const float* __restrict__ Ak, int j0,
+                                               int Ck, const float (&qt)[D / 8][4], int col, int half) {
+  KTile<D> kt;
+  load_ktile<D>(kt, Amu, Ak, j0, Ck, col, half);
+  return score_ktile<D>(kt, j0, Ck, qt, half);
 }
 
 // bf16 MFMA (v_mfma_f32_32x32x16_bf16) helpers.  pack8: accumulator rows 4*g0..+3 and 4*g1..+3 of a lane
