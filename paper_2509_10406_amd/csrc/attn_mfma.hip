@@ -697,10 +697,10 @@ __global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restric
 template <int D>
 __global__ void __launch_bounds__(256) k_ff_bwd_cells_mx(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO, const float* __restrict__ qc,
-    const float* __restrict__ A_mu, const float* __restrict__ A_k, const float* __restrict__ A_v,
+    const float* __restrict__ A_mu, const bf16_t* __restrict__ A_kb, const bf16_t* __restrict__ A_v,
     const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q, const float* __restrict__ LSE,
     const float* __restrict__ delta, const uint32_t* __restrict__ selmask, float* __restrict__ g_A_c,
-    float* __restrict__ g_A_k, float* __restrict__ g_A_v, int h0, int N, int nb, int Cq, int Ck, float scale) {
+    bf16_t* __restrict__ g_A_k, bf16_t* __restrict__ g_A_v, int h0, int N, int nb, int Cq, int Ck, float scale) {
   constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
   __shared__ __attribute__((aligned(16))) bf16_t qs[32][D + 8];
   __shared__ __attribute__((aligned(16))) bf16_t gs[32][D + 8];
@@ -724,8 +724,8 @@ __global__ void __launch_bounds__(256) k_ff_bwd_cells_mx(
   bf16x8_t kf[KS], vf[KS];
 #pragma unroll
   for (int x = 0; x < KS; ++x) {
-    kf[x] = cvt8(A_k + (acell + jcc) * D + 16 * x + 8 * half);
-    vf[x] = cvt8(A_v + (acell + jcc) * D + 16 * x + 8 * half);
+    kf[x] = *reinterpret_cast<const bf16x8_t*>(A_kb + (acell + jcc) * D + 16 * x + 8 * half);
+    vf[x] = *reinterpret_cast<const bf16x8_t*>(A_v + (acell + jcc) * D + 16 * x + 8 * half);
   }
   const float amu2 = jvalid ? A_mu[acell + jcc] * 1.4426950408889634f : MUSE_NEG_INF;
   const float* qci = qc + ((size_t)hq * Cq + i) * D;
@@ -810,15 +810,15 @@ __global__ void __launch_bounds__(256) k_ff_bwd_cells_mx(
   }
   csum += __shfl_xor(csum, 32, 64);
   if (!jvalid) return;
-  float* ok_ = g_A_k + (acell + jc) * D;
-  float* ov_ = g_A_v + (acell + jc) * D;
+  bf16_t* ok_ = g_A_k + (acell + jc) * D;
+  bf16_t* ov_ = g_A_v + (acell + jc) * D;
 #pragma unroll
   for (int t = 0; t < DT; ++t)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int d = 32 * t + 8 * g + 4 * half;
-      *reinterpret_cast<float4*>(ok_ + d) = make_float4(gk[t][4 * g], gk[t][4 * g + 1], gk[t][4 * g + 2], gk[t][4 * g + 3]);
-      *reinterpret_cast<float4*>(ov_ + d) = make_float4(gv[t][4 * g], gv[t][4 * g + 1], gv[t][4 * g + 2], gv[t][4 * g + 3]);
+      *reinterpret_cast<uint2*>(ok_ + d) = make_uint2(pack_bf16x2(gk[t][4 * g], gk[t][4 * g + 1]), pack_bf16x2(gk[t][4 * g + 2], gk[t][4 * g + 3]));
+      *reinterpret_cast<uint2*>(ov_ + d) = make_uint2(pack_bf16x2(gv[t][4 * g], gv[t][4 * g + 1]), pack_bf16x2(gv[t][4 * g + 2], gv[t][4 * g + 3]));
     }
   if (half == 0) g_A_c[acell + jc] = csum;
 }
@@ -834,7 +834,7 @@ template <int D>
 __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
                                                           const float* __restrict__ qc, const float* __restrict__ L,
                                                           const float* __restrict__ s_mu, const float* __restrict__ G_c,
-                                                          const float* __restrict__ G_k, const float* __restrict__ G_v,
+                                                          const bf16_t* __restrict__ G_k, const bf16_t* __restrict__ G_v,
                                                           const int32_t* __restrict__ off_k, float* __restrict__ dKs,
                                                           float* __restrict__ dVs, int h0, int N, int nb, int Cq, int Ck,
                                                           int Hq, int Hkv, float scale) {
@@ -881,8 +881,8 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
         }
 #pragma unroll
         for (int x = 0; x < KS; ++x) {
-          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cvt8(G_k + cellA * D + 16 * x + 8 * half), kb[x], tacc, 0, 0, 0);
-          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cvt8(G_v + cellA * D + 16 * x + 8 * half), vb[x], tacc, 0, 0, 0);
+          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(G_k + cellA * D + 16 * x + 8 * half), kb[x], tacc, 0, 0, 0);
+          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(G_v + cellA * D + 16 * x + 8 * half), vb[x], tacc, 0, 0, 0);
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) tacc[e] = wv[e] > 0.f ? wv[e] * tacc[e] : 0.f;
@@ -898,8 +898,8 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
               const int e = 4 * (2 * G + u / 4) + (u % 4);
               int ir = i0 + 8 * (e / 4) + 4 * half + (e % 4);
               ir = ir < Cq ? ir : Cq - 1;
-              ak[u] = (__bf16)G_k[cellr[e] * D + 32 * t + col];
-              av[u] = (__bf16)G_v[cellr[e] * D + 32 * t + col];
+              ak[u] = bits_to_bf16(G_k[cellr[e] * D + 32 * t + col]);
+              av[u] = bits_to_bf16(G_v[cellr[e] * D + 32 * t + col]);
               aq[u] = (__bf16)(scale * qc[((size_t)hq * Cq + ir) * D + 32 * t + col]);
             }
             dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wf, dv[t], 0, 0, 0);
@@ -930,27 +930,27 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
 }  // namespace
 
 int muse_launch_cells_to_keys_mx(const MuseDims& d, const void* Ks, const void* Vs, const float* qc, const float* L,
-                                 const float* s_mu, const float* G_c, const float* G_k, const float* G_v,
+                                 const float* s_mu, const float* G_c, const void* G_k, const void* G_v,
                                  const int32_t* off_k, float* dKs, float* dVs, int h0, int hn, hipStream_t st) {
   dim3 g(d.Ck, d.nb - 1, hn / (d.Hq / d.Hkv));
   if (d.D == 64)
-    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<64>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, qc, L, s_mu, G_c, G_k, G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv, d.scale); }
+    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<64>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, qc, L, s_mu, G_c, (const bf16_t*)G_k, (const bf16_t*)G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv, d.scale); }
   else
-    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<128>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, qc, L, s_mu, G_c, G_k, G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv, d.scale); }
+    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<128>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, qc, L, s_mu, G_c, (const bf16_t*)G_k, (const bf16_t*)G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv, d.scale); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
 
 int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO, const float* qc, const float* A_mu,
-                                const float* A_k, const float* A_v, const int32_t* perm_q, const int32_t* off_q,
+                                const void* A_kb, const void* A_v, const int32_t* perm_q, const int32_t* off_q,
                                 const float* LSE, const float* delta, const uint32_t* selmask, float* g_A_c,
-                                float* g_A_k, float* g_A_v, int h0, int hn, hipStream_t st) {
+                                void* g_A_k, void* g_A_v, int h0, int hn, hipStream_t st) {
   const int W = (d.Ck + 31) / 32;
   dim3 g((W + 3) / 4, (d.nb - 1) * d.Cq, hn);
   if (d.D == 64)
-    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL(k_ff_bwd_cells_mx<64>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, A_k, A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, g_A_k, g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
+    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL(k_ff_bwd_cells_mx<64>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, (const bf16_t*)A_kb, (const bf16_t*)A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, (bf16_t*)g_A_k, (bf16_t*)g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
   else
-    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL(k_ff_bwd_cells_mx<128>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, A_k, A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, g_A_k, g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
+    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL(k_ff_bwd_cells_mx<128>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, (const bf16_t*)A_kb, (const bf16_t*)A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, (bf16_t*)g_A_k, (bf16_t*)g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }

@@ -72,6 +72,36 @@ struct Pair<bf16_t> {
   __device__ static __forceinline__ float lo(raw v) { return __uint_as_float(v << 16); }
   __device__ static __forceinline__ float hi(raw v) { return __uint_as_float(v & 0xffff0000u); }
 };
+// DT consecutive elements (DT = 2 or 4, address aligned to DT elements), raw, with compile-time element access
+template <typename T, int DT>
+struct Frag;
+template <>
+struct Frag<float, 2> {
+  using raw = float2;
+  __device__ static __forceinline__ raw ld(const float* p, size_t i) { return *reinterpret_cast<const float2*>(p + i); }
+  __device__ static __forceinline__ float get(const raw& v, int x) { return x ? v.y : v.x; }
+};
+template <>
+struct Frag<float, 4> {
+  using raw = float4;
+  __device__ static __forceinline__ raw ld(const float* p, size_t i) { return *reinterpret_cast<const float4*>(p + i); }
+  __device__ static __forceinline__ float get(const raw& v, int x) { return x == 0 ? v.x : x == 1 ? v.y : x == 2 ? v.z : v.w; }
+};
+template <>
+struct Frag<bf16_t, 2> {
+  using raw = uint32_t;
+  __device__ static __forceinline__ raw ld(const bf16_t* p, size_t i) { return *reinterpret_cast<const uint32_t*>(p + i); }
+  __device__ static __forceinline__ float get(const raw& v, int x) { return __uint_as_float(x ? (v & 0xffff0000u) : (v << 16)); }
+};
+template <>
+struct Frag<bf16_t, 4> {
+  using raw = uint2;
+  __device__ static __forceinline__ raw ld(const bf16_t* p, size_t i) { return *reinterpret_cast<const uint2*>(p + i); }
+  __device__ static __forceinline__ float get(const raw& v, int x) {
+    const uint32_t w = x < 2 ? v.x : v.y;
+    return __uint_as_float((x & 1) ? (w & 0xffff0000u) : (w << 16));
+  }
+};
 __device__ __forceinline__ void st4(float* p, size_t i, const float v[4]) {
   *reinterpret_cast<float4*>(p + i) = make_float4(v[0], v[1], v[2], v[3]);
 }

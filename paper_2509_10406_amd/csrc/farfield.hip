@@ -95,9 +95,10 @@ template <typename T, int D>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) k_summaries(const T* __restrict__ Ks, const T* __restrict__ Vs,
                                                    const float* __restrict__ L, const int32_t* __restrict__ off_k,
                                                    float* __restrict__ s_mu, float* __restrict__ s_k,
-                                                   float* __restrict__ s_v, float* __restrict__ A_mu,
-                                                   float* __restrict__ A_k, float* __restrict__ A_v, int h0, int N,
-                                                   int nb, int Cq, int Ck, int Hq, int Hkv) {
+                                                   T* __restrict__ s_v, float* __restrict__ A_mu,
+                                                   float* __restrict__ A_k, T* __restrict__ A_v,
+                                                   bf16_t* __restrict__ A_kb, int h0, int N, int nb, int Cq, int Ck,
+                                                   int Hq, int Hkv) {
   constexpr int DS = D / 64;  // slices of the head dim
   constexpr int KCH = sizeof(T) == 2 ? 16 : 8;  // keys per chunk
   __shared__ float tr[32][68];
@@ -192,7 +193,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // transpose each 64 x 32 accumulator slice through LDS so that a store instruction writes four whole
     // 256-byte row segments instead of 32 fragments of 32 bytes
     const size_t rowbase = (((size_t)hl * NBm + b) * Cq + it * 32) * Ck + j;
-    auto emit = [&](float* __restrict__ dst, const f32x16_t(&a)[2], float sc) {
+    auto emit = [&](float* __restrict__ dstf, bf16_t* __restrict__ dsth, const f32x16_t(&a)[2], float sc) {
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll
@@ -203,16 +204,21 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int ps = 0; ps < 8; ++ps) {
         const int row = 4 * ps + lane / 16;
         if (it * 32 + row < Cq) {
-          float4 v = *reinterpret_cast<const float4*>(&tr[row][4 * (lane % 16)]);
-          *reinterpret_cast<float4*>(dst + (rowbase + (size_t)row * Ck) * D + d0 + 4 * (lane % 16)) = v;
+          const float4 v = *reinterpret_cast<const float4*>(&tr[row][4 * (lane % 16)]);
+          const size_t o = (rowbase + (size_t)row * Ck) * D + d0 + 4 * (lane % 16);
+          if (dstf) *reinterpret_cast<float4*>(dstf + o) = v;
+          if (dsth) *reinterpret_cast<uint2*>(dsth + o) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
         }
       }
       wave_lds_fence();
     };
-    emit(s_k, ak, inv);
-    emit(s_v, av, inv);
-    emit(A_k, Aak, ainv);
-    emit(A_v, Aav, ainv);
+    // k-bar stays fp32 (it decides selections); values go out in the input type; bf16 inputs also get a
+    // bf16 copy of the accumulated k-bar for the gradient contractions
+    constexpr bool kH = sizeof(T) == 2;
+    emit(s_k, nullptr, ak, inv);
+    emit(kH ? nullptr : reinterpret_cast<float*>(s_v), kH ? reinterpret_cast<bf16_t*>(s_v) : nullptr, av, inv);
+    emit(A_k, kH ? A_kb : nullptr, Aak, ainv);
+    emit(kH ? nullptr : reinterpret_cast<float*>(A_v), kH ? reinterpret_cast<bf16_t*>(A_v) : nullptr, Aav, ainv);
   }
 }
 
@@ -224,12 +230,12 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 template <typename T, int D, int RCAP>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, D == 64 ? 2 : 2))) k_farfield_fwd(
     const T* __restrict__ Q, const float* __restrict__ qc, const float* __restrict__ A_mu, const float* __restrict__ A_k,
-    const float* __restrict__ A_v, const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q,
+    const T* __restrict__ A_v, const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q,
     const int32_t* __restrict__ tile_off, float* __restrict__ ff_acc, float* __restrict__ ff_ml,
     int32_t* __restrict__ selc, int h0, int N, int nb, int Cq, int Ck, int r, float scale) {
   constexpr int U = D / 8, DT = D / 32;
   // output tile x, row m holds head dim DT*m + x: a lane reads DT consecutive dims of a value row at once
-  using VRow = typename std::conditional<DT == 2, float2, float4>::type;
+  using VF = Frag<T, DT>;
   __shared__ float cs[64][RCAP];
   __shared__ int ci[64][RCAP];
   __shared__ int sel_s[32][RCAP];
@@ -269,7 +275,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
   const size_t acell = (((size_t)hl * NBm + (b - 1)) * Cq + i) * Ck;
   const float* Amu = A_mu + acell;
   const float* Ak = A_k + acell * D;
-  const float* Av = A_v + acell * D;
+  const T* Av = A_v + acell * D;
   const int ntile = (Ck + 31) / 32;
 
   // ---- pass 1: the r largest scores seen by this lane half (values only) ----
@@ -334,12 +340,12 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
     // all loads of the tile first: k-bar rows, mu-bar, and the DT consecutive dims DT*col .. of the 16 value rows
     KTile<D> kt;
     load_ktile<D>(kt, Amu, Ak, j0, Ck, col, half);
-    VRow vv[16];
+    typename VF::raw vv[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
       jr = jr < Ck ? jr : Ck - 1;
-      vv[e] = *reinterpret_cast<const VRow*>(Av + (size_t)jr * D + DT * col);
+      vv[e] = VF::ld(Av, (size_t)jr * D + DT * col);
     }
     f32x16_t acc = score_ktile<D>(kt, j0, Ck, qt, half);
     float tmax = MUSE_NEG_INF;
@@ -376,9 +382,8 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
       for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      const float* vf = reinterpret_cast<const float*>(&vv[e]);
 #pragma unroll
-      for (int x = 0; x < DT; ++x) o[x] = mfma32(vf[x], acc[e], o[x]);
+      for (int x = 0; x < DT; ++x) o[x] = mfma32(VF::get(vv[e], x), acc[e], o[x]);
     }
   }
   // ---- order the selected clusters of each query by (score desc, index asc) ----
@@ -438,7 +443,7 @@ template <typename T, int D, int NBC>
 __global__ void __launch_bounds__(256) k_comp2_fwd(
     const T* __restrict__ Q, const float* __restrict__ qc, const T* __restrict__ Ks, const T* __restrict__ Vs,
     const float* __restrict__ L, const float* __restrict__ s_mu, const float* __restrict__ s_k,
-    const float* __restrict__ s_v, const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_k,
+    const T* __restrict__ s_v, const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_k,
     const int32_t* __restrict__ aq, const int32_t* __restrict__ selc, int32_t* __restrict__ selb,
     float* __restrict__ ff_acc, float* __restrict__ ff_ml, int h0, int N, int nb, int Bs, int Cq, int Ck, int r,
     int k2e, int Hq, int Hkv, float scale) {
@@ -485,7 +490,7 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
     float sc2[8 * NBC];
 #pragma unroll
     for (int bp = 0; bp < 8 * NBC; ++bp) sc2[bp] = MUSE_NEG_INF;
-    float4 vr[8][NG];
+    float vr[8][NG][4];
 #pragma unroll
     for (int c0 = 0; c0 < 8 * NBC; c0 += 8) {
       if (c0 >= b) break;
@@ -499,7 +504,7 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
 #pragma unroll
         for (int x = 0; x < NG; ++x) {
           kr[u][x] = *reinterpret_cast<const float4*>(s_k + cell * D + 64 * x + 4 * l16);
-          if (NBC == 1) vr[u][x] = *reinterpret_cast<const float4*>(s_v + cell * D + 64 * x + 4 * l16);
+          if (NBC == 1) ld4(s_v, cell * D + 64 * x + 4 * l16, vr[u][x]);
         }
       }
 #pragma unroll
@@ -540,16 +545,13 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
           const int bp = c0 + u < b ? c0 + u : b - 1;
           const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
 #pragma unroll
-          for (int x = 0; x < NG; ++x) vr[u][x] = *reinterpret_cast<const float4*>(s_v + cell * D + 64 * x + 4 * l16);
+          for (int x = 0; x < NG; ++x) ld4(s_v, cell * D + 64 * x + 4 * l16, vr[u][x]);
         }
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         if (!(sc2[c0 + u] > MUSE_NEG_INF) || ((selbits >> (c0 + u)) & 1u)) continue;
-        float v[NG][4];
-#pragma unroll
-        for (int x = 0; x < NG; ++x) { v[x][0] = vr[u][x].x; v[x][1] = vr[u][x].y; v[x][2] = vr[u][x].z; v[x][3] = vr[u][x].w; }
-        add(sc2[c0 + u], v);
+        add(sc2[c0 + u], vr[u]);
       }
     }
     if (sizeof(T) == 4) {  // component 3: the keys of the retrieved (cluster, block) pairs, with the full query
@@ -660,16 +662,17 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
   w->s_mu = (float*)take(hc * cells * 4);
   w->A_mu = (float*)take(hc * cells * 4);
   w->s_k = (float*)take(hc * cells * D * 4);
-  w->s_v = (float*)take(hc * cells * D * 4);
   w->A_k = (float*)take(hc * cells * D * 4);
-  w->A_v = (float*)take(hc * cells * D * 4);
+  w->s_v = take(hc * cells * D * es);
+  w->A_v = take(hc * cells * D * es);
+  w->A_kb = es == 2 ? take(hc * cells * D * 2) : nullptr;
   if (bwd) {
     w->g_s_c = (float*)take(hc * cells * 4);
     w->g_A_c = (float*)take(hc * cells * 4);
-    w->g_s_k = (float*)take(hc * cells * D * 4);
-    w->g_s_v = (float*)take(hc * cells * D * 4);
-    w->g_A_k = (float*)take(hc * cells * D * 4);
-    w->g_A_v = (float*)take(hc * cells * D * 4);
+    w->g_s_k = take(hc * cells * D * es);
+    w->g_s_v = take(hc * cells * D * es);
+    w->g_A_k = take(hc * cells * D * es);
+    w->g_A_v = take(hc * cells * D * es);
   }
   w->hc = (int)hc;
   return (int)hc;
@@ -701,11 +704,11 @@ int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0
   if (d.D == 64) {
     { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 64>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
     { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 64>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
-                       w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
+                       w.s_k, (T*)w.s_v, w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   } else {
     { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 128>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
     { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 128>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
-                       w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
+                       w.s_k, (T*)w.s_v, w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
@@ -722,7 +725,7 @@ template <typename T, int D, int RCAP>
 void launch_ff_fwd(const MuseDims& d, const T* Q, const float* qc, FFWorkspace& w, int32_t* selc, int h0, int hn,
                    hipStream_t st) {
   dim3 g(d.Bs / 32 + d.Cq + 1, d.nb - 1, hn);
-  { MuseProf prof_("k_farfield_fwd", st); hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q,
+  { MuseProf prof_("k_farfield_fwd", st); hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, w.A_mu, w.A_k, (const T*)w.A_v, w.perm_q, w.off_q,
                      w.tile_off, w.ff_acc, w.ff_ml, selc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.scale); }
 }
 
@@ -736,11 +739,11 @@ void launch_ff_fwd_r(const MuseDims& d, const T* Q, const float* qc, const int32
     dim3 g((d.N - d.Bs + 15) / 16, hn);
     if (d.nb <= 9)
       { MuseProf prof_("k_comp2_fwd", st); hipLaunchKernelGGL((k_comp2_fwd<T, D, 1>), g, dim3(256), 0, st, Q, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu, w.s_k,
-                         w.s_v, w.perm_q, w.off_k, aq, selc, selb, w.ff_acc, w.ff_ml, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r,
+                         (const T*)w.s_v, w.perm_q, w.off_k, aq, selc, selb, w.ff_acc, w.ff_ml, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r,
                          d.k2e, d.Hq, d.Hkv, d.scale); }
     else
       { MuseProf prof_("k_comp2_fwd", st); hipLaunchKernelGGL((k_comp2_fwd<T, D, 2>), g, dim3(256), 0, st, Q, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu, w.s_k,
-                         w.s_v, w.perm_q, w.off_k, aq, selc, selb, w.ff_acc, w.ff_ml, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r,
+                         (const T*)w.s_v, w.perm_q, w.off_k, aq, selc, selb, w.ff_acc, w.ff_ml, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r,
                          d.k2e, d.Hq, d.Hkv, d.scale); }
   }
 }

@@ -38,8 +38,9 @@ template <typename T, int D>
 __global__ void __launch_bounds__(64) k_ff_bwd_dq(
     const T* __restrict__ Q, const T* __restrict__ dO, const float* __restrict__ qc, const T* __restrict__ Ks,
     const T* __restrict__ Vs, const float* __restrict__ L, const float* __restrict__ s_mu,
-    const float* __restrict__ s_k, const float* __restrict__ s_v, const float* __restrict__ A_mu,
-    const float* __restrict__ A_k, const float* __restrict__ A_v, const int32_t* __restrict__ perm_q,
+    const float* __restrict__ s_k, const T* __restrict__ s_v, const float* __restrict__ A_mu,
+    const float* __restrict__ A_k, const T* __restrict__ A_v, const bf16_t* __restrict__ A_kb,
+    const int32_t* __restrict__ perm_q,
     const int32_t* __restrict__ off_q, const int32_t* __restrict__ off_k, const int32_t* __restrict__ tile_off,
     const float* __restrict__ LSE, const float* __restrict__ delta, const uint32_t* __restrict__ selmask,
     const int32_t* __restrict__ selc, const int32_t* __restrict__ selb, const float* __restrict__ dqpart,
@@ -86,7 +87,9 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
   const size_t acell = (((size_t)hl * NBm + (b - 1)) * Cq + i) * Ck;
   const float* Amu = A_mu + acell;
   const float* Ak = A_k + acell * D;
-  const float* Av = A_v + acell * D;
+  const float* Avf = reinterpret_cast<const float*>(A_v) + acell * D;   // fp32 inputs
+  const bf16_t* Akh = A_kb + acell * D;                                  // bf16 inputs
+  const bf16_t* Avh = reinterpret_cast<const bf16_t*>(A_v) + acell * D;
   const int ntile = (Ck + 31) / 32;
 
   f32x16_t dq[DT];
@@ -127,8 +130,8 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
         }
 #pragma unroll
       for (int x = 0; x < KS; ++x) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cvt8(Ak + (size_t)c * D + 16 * x + 8 * half), qb[x], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cvt8(Av + (size_t)c * D + 16 * x + 8 * half), gb[x], dp, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(Akh + (size_t)c * D + 16 * x + 8 * half), qb[x], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(Avh + (size_t)c * D + 16 * x + 8 * half), gb[x], dp, 0, 0, 0);
       }
       const uint32_t mw = selmask[qn * W + jt];
 #pragma unroll
@@ -147,7 +150,7 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
           for (int u = 0; u < 8; ++u) {
             int jr = j0 + 8 * (2 * G + u / 4) + 4 * half + (u % 4);
             jr = jr < Ck ? jr : Ck - 1;
-            ak[u] = (__bf16)Ak[(size_t)jr * D + 32 * x + col];
+            ak[u] = bits_to_bf16(Akh[(size_t)jr * D + 32 * x + col]);
           }
           dq[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, df, dq[x], 0, 0, 0);
         }
@@ -159,7 +162,7 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
     f32x16_t s = score_tile<D>(Amu, Ak, j0, Ck, qt, col, half);
     int c = j0 + col;
     c = c < Ck ? c : Ck - 1;
-    f32x16_t dp = mfma_rows<D>(zero16(), Av + (size_t)c * D + 4 * half, gt);
+    f32x16_t dp = mfma_rows<D>(zero16(), Avf + (size_t)c * D + 4 * half, gt);
     const uint32_t mw = selmask[qn * W + jt];
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
@@ -193,17 +196,17 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
       if (!(mu > MUSE_NEG_INF)) continue;
       if (!((selbits >> bp) & 1u)) {
         const float* kr = s_k + cell * D + 4 * half;
-        const float* vr = s_v + cell * D + 4 * half;
         float part = 0.f, dpp = 0.f;
         float4 k4[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           k4[u] = *reinterpret_cast<const float4*>(kr + 8 * u);
-          float4 v4 = *reinterpret_cast<const float4*>(vr + 8 * u);
+          float v4[4];
+          ld4(s_v, cell * D + 4 * half + 8 * u, v4);
           part = fmaf(qt[u][0], k4[u].x, part); part = fmaf(qt[u][1], k4[u].y, part);
           part = fmaf(qt[u][2], k4[u].z, part); part = fmaf(qt[u][3], k4[u].w, part);
-          dpp = fmaf(gt[u][0], v4.x, dpp); dpp = fmaf(gt[u][1], v4.y, dpp);
-          dpp = fmaf(gt[u][2], v4.z, dpp); dpp = fmaf(gt[u][3], v4.w, dpp);
+          dpp = fmaf(gt[u][0], v4[0], dpp); dpp = fmaf(gt[u][1], v4[1], dpp);
+          dpp = fmaf(gt[u][2], v4[2], dpp); dpp = fmaf(gt[u][3], v4[3], dpp);
         }
         part += __shfl_xor(part, 32, 64);
         dpp += __shfl_xor(dpp, 32, 64);
@@ -395,11 +398,11 @@ __global__ void __launch_bounds__(64) k_ff_bwd_cells(
 template <typename T, int D>
 __global__ void __launch_bounds__(256) k_cell_grads(
     const T* __restrict__ Q, const T* __restrict__ dO, const float* __restrict__ qc, const float* __restrict__ s_mu,
-    const float* __restrict__ s_k, const float* __restrict__ s_v, const float* __restrict__ A_mu,
-    const float* __restrict__ g_A_c, const float* __restrict__ g_A_k, const float* __restrict__ g_A_v,
+    const float* __restrict__ s_k, const T* __restrict__ s_v, const float* __restrict__ A_mu,
+    const float* __restrict__ g_A_c, const T* __restrict__ g_A_k, const T* __restrict__ g_A_v,
     const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q, const float* __restrict__ LSE,
     const float* __restrict__ delta, const uint32_t* __restrict__ selmask, const int32_t* __restrict__ selc,
-    const int32_t* __restrict__ selb, float* __restrict__ G_c, float* __restrict__ G_k, float* __restrict__ G_v, int h0,
+    const int32_t* __restrict__ selb, float* __restrict__ G_c, T* __restrict__ G_k, T* __restrict__ G_v, int h0,
     int N, int nb, int Bs, int Cq, int Ck, int r, int k2e, float scale) {
   constexpr int NV = D / 32;
   constexpr int POOL = 2048;
@@ -528,11 +531,12 @@ __global__ void __launch_bounds__(256) k_cell_grads(
           for (int t = 0; t < 4; ++t) { gk[x][t] = 0.f; gv[x][t] = 0.f; }
         const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + jt * 32 + jl0 + c;
         const float mu = s_mu[cell];  // an empty cell has mu = -inf and zero rows: p = 0, nothing is added
-        float4 kv[NV], vv[NV];
+        float4 kv[NV];
+        float vv[NV][4];
 #pragma unroll
         for (int x = 0; x < NV; ++x) {
           kv[x] = *reinterpret_cast<const float4*>(s_k + cell * D + 32 * x + 4 * l8);
-          vv[x] = *reinterpret_cast<const float4*>(s_v + cell * D + 32 * x + 4 * l8);
+          ld4(s_v, cell * D + 32 * x + 4 * l8, vv[x]);
         }
         for (int e = e0 + s8; e < e1; e += 8) {
           const int2 en = pool[e];
@@ -552,8 +556,8 @@ __global__ void __launch_bounds__(256) k_cell_grads(
             for (int t = 0; t < 4; ++t) qv[x][t] = scale * (qv[x][t] - qcv[x][t]);
             part = fmaf(qv[x][0], kv[x].x, part); part = fmaf(qv[x][1], kv[x].y, part);
             part = fmaf(qv[x][2], kv[x].z, part); part = fmaf(qv[x][3], kv[x].w, part);
-            dpp = fmaf(dv[x][0], vv[x].x, dpp); dpp = fmaf(dv[x][1], vv[x].y, dpp);
-            dpp = fmaf(dv[x][2], vv[x].z, dpp); dpp = fmaf(dv[x][3], vv[x].w, dpp);
+            dpp = fmaf(dv[x][0], vv[x][0], dpp); dpp = fmaf(dv[x][1], vv[x][1], dpp);
+            dpp = fmaf(dv[x][2], vv[x][2], dpp); dpp = fmaf(dv[x][3], vv[x][3], dpp);
           }
 #pragma unroll
           for (int o = 1; o < 8; o <<= 1) {
@@ -605,16 +609,18 @@ __global__ void __launch_bounds__(256) k_cell_grads(
 #pragma unroll
       for (int x = 0; x < NV; ++x) {
         const size_t o = cell * D + 32 * x + 4 * l8;
-        const float4 ak4 = *reinterpret_cast<const float4*>(g_A_k + o);
-        const float4 av4 = *reinterpret_cast<const float4*>(g_A_v + o);
-        Rk[x][0] = ak4.x + f * Rk[x][0]; Rk[x][1] = ak4.y + f * Rk[x][1];
-        Rk[x][2] = ak4.z + f * Rk[x][2]; Rk[x][3] = ak4.w + f * Rk[x][3];
-        Rv[x][0] = av4.x + f * Rv[x][0]; Rv[x][1] = av4.y + f * Rv[x][1];
-        Rv[x][2] = av4.z + f * Rv[x][2]; Rv[x][3] = av4.w + f * Rv[x][3];
-        *reinterpret_cast<float4*>(G_k + o) = make_float4(gkK[x][0] + wgt * Rk[x][0], gkK[x][1] + wgt * Rk[x][1],
-                                                          gkK[x][2] + wgt * Rk[x][2], gkK[x][3] + wgt * Rk[x][3]);
-        *reinterpret_cast<float4*>(G_v + o) = make_float4(gvK[x][0] + wgt * Rv[x][0], gvK[x][1] + wgt * Rv[x][1],
-                                                          gvK[x][2] + wgt * Rv[x][2], gvK[x][3] + wgt * Rv[x][3]);
+        float ak4[4], av4[4], ok4[4], ov4[4];
+        ld4(g_A_k, o, ak4);
+        ld4(g_A_v, o, av4);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          Rk[x][t] = ak4[t] + f * Rk[x][t];
+          Rv[x][t] = av4[t] + f * Rv[x][t];
+          ok4[t] = gkK[x][t] + wgt * Rk[x][t];
+          ov4[t] = gvK[x][t] + wgt * Rv[x][t];
+        }
+        st4(G_k, o, ok4);
+        st4(G_v, o, ov4);
       }
     }
   }
@@ -891,19 +897,19 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
   const int W = (d.Ck + 31) / 32;
   dim3 gt(d.Bs / 32 + d.Cq + 1, NBm, hn);
   { MuseProf prof_("k_ff_bwd_dq", st); hipLaunchKernelGGL((k_ff_bwd_dq<T, D>), gt, dim3(64), 0, st, Q, dO, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu,
-                     w.s_k, w.s_v, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q, w.off_k, w.tile_off, LSE, w.delta,
+                     w.s_k, (const T*)w.s_v, w.A_mu, w.A_k, (const T*)w.A_v, (const bf16_t*)w.A_kb, w.perm_q, w.off_q, w.off_k, w.tile_off, LSE, w.delta,
                      w.selmask, selc, selb, w.ret_part, w.dQacc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
   if (sizeof(T) == 2) {
-    int rc2 = muse_launch_ff_bwd_cells_mx(d, Q, dO, qc, w.A_mu, w.A_k, w.A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask,
+    int rc2 = muse_launch_ff_bwd_cells_mx(d, Q, dO, qc, w.A_mu, w.A_kb, w.A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask,
                                           w.g_A_c, w.g_A_k, w.g_A_v, h0, hn, st);
     if (rc2) return rc2;
   } else
-  { MuseProf prof_("k_ff_bwd_cells", st); hipLaunchKernelGGL((k_ff_bwd_cells<T, D>), dim3(W, NBm * d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.A_mu, w.A_k, w.A_v,
-                     w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.g_A_c, w.g_A_k, w.g_A_v, h0, d.N, d.nb, d.Cq, d.Ck,
+  { MuseProf prof_("k_ff_bwd_cells", st); hipLaunchKernelGGL((k_ff_bwd_cells<T, D>), dim3(W, NBm * d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.A_mu, w.A_k, (const float*)w.A_v,
+                     w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.g_A_c, (float*)w.g_A_k, (float*)w.g_A_v, h0, d.N, d.nb, d.Cq, d.Ck,
                      d.scale); }
-  { MuseProf prof_("k_cell_grads", st); hipLaunchKernelGGL((k_cell_grads<T, D>), dim3(W, d.Cq, hn), dim3(256), 0, st, Q, dO, qc, w.s_mu, w.s_k, w.s_v, w.A_mu,
-                     w.g_A_c, w.g_A_k, w.g_A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask, selc, selb, w.g_s_c, w.g_s_k,
-                     w.g_s_v, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
+  { MuseProf prof_("k_cell_grads", st); hipLaunchKernelGGL((k_cell_grads<T, D>), dim3(W, d.Cq, hn), dim3(256), 0, st, Q, dO, qc, w.s_mu, w.s_k, (const T*)w.s_v, w.A_mu,
+                     w.g_A_c, (const T*)w.g_A_k, (const T*)w.g_A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask, selc, selb, w.g_s_c, (T*)w.g_s_k,
+                     (T*)w.g_s_v, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
   const int G_ = d.Hq / d.Hkv;
   if (sizeof(T) == 2) {
     int rc2 = muse_launch_cells_to_keys_mx(d, w.Ks, w.Vs, qc, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs,
@@ -911,7 +917,7 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
     if (rc2) return rc2;
   } else
   { MuseProf prof_("k_cells_to_keys", st); hipLaunchKernelGGL((k_cells_to_keys<T, D>), dim3(d.Ck, NBm, hn / G_), dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs,
-                     qc, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq,
+                     qc, w.L, w.s_mu, w.g_s_c, (const float*)w.g_s_k, (const float*)w.g_s_v, w.off_k, w.dKs, w.dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq,
                      d.Hkv, d.scale); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;

@@ -111,6 +111,8 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& s, int g0, int g1) {
   return r;
 }
 
+__device__ __forceinline__ __bf16 bits_to_bf16(bf16_t b) { return __builtin_bit_cast(__bf16, b); }
+
 __device__ __forceinline__ bf16x8_t cvt8(const float* __restrict__ p) {
   float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
   bf16x8_t r;
@@ -137,8 +139,12 @@ struct FFWorkspace {
   float *dQacc, *dKacc, *dVacc;  // fp32 gradients in sequence order (alias the outputs when they are fp32)
   // per chunk of `hc` query heads
   float* L;
-  float *s_mu, *s_k, *s_v, *A_mu, *A_k, *A_v;
-  float *g_s_c, *g_s_k, *g_s_v, *g_A_c, *g_A_k, *g_A_v;
+  // decision-deciding summaries stay fp32; value summaries and every cell gradient are stored in the input
+  // type (bf16 for bf16 inputs); A_kb is a bf16 copy of A_k for the gradient contractions (bf16 inputs only)
+  float *s_mu, *s_k, *A_mu, *A_k;
+  void *s_v, *A_v, *A_kb;
+  float *g_s_c, *g_A_c;
+  void *g_s_k, *g_s_v, *g_A_k, *g_A_v;
   int hc;
 };
 
@@ -164,8 +170,10 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
 
 static inline size_t ff_head_bytes(const MuseDims& d, bool bwd) {
   size_t cells = (size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * d.Ck, D = d.D;
-  size_t b = ff_al((size_t)d.Cq * d.N * 4) + 2 * ff_al(cells * 4) + 4 * ff_al(cells * D * 4);
-  if (bwd) b += 2 * ff_al(cells * 4) + 4 * ff_al(cells * D * 4);
+  size_t es = d.dtype == MUSE_DTYPE_BF16 ? 2 : 4;
+  size_t b = ff_al((size_t)d.Cq * d.N * 4) + 2 * ff_al(cells * 4) + 2 * ff_al(cells * D * 4) + 2 * ff_al(cells * D * es);
+  if (es == 2) b += ff_al(cells * D * 2);
+  if (bwd) b += 2 * ff_al(cells * 4) + 4 * ff_al(cells * D * es);
   return b;
 }
 
@@ -187,11 +195,11 @@ int muse_launch_ret_bwd_dq_pairs(const MuseDims& d, const void* Q, const void* d
                                  const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
                                  const uint2* hits, size_t hit_cap, float* dqpart, hipStream_t st);
 int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO, const float* qc, const float* A_mu,
-                                const float* A_k, const float* A_v, const int32_t* perm_q, const int32_t* off_q,
+                                const void* A_kb, const void* A_v, const int32_t* perm_q, const int32_t* off_q,
                                 const float* LSE, const float* delta, const uint32_t* selmask, float* g_A_c,
-                                float* g_A_k, float* g_A_v, int h0, int hn, hipStream_t st);
+                                void* g_A_k, void* g_A_v, int h0, int hn, hipStream_t st);
 int muse_launch_cells_to_keys_mx(const MuseDims& d, const void* Ks, const void* Vs, const float* qc, const float* L,
-                                 const float* s_mu, const float* G_c, const float* G_k, const float* G_v,
+                                 const float* s_mu, const float* G_c, const void* G_k, const void* G_v,
                                  const int32_t* off_k, float* dKs, float* dVs, int h0, int hn, hipStream_t st);
 // retrieval.hip: pair bitmask + ordered hit lists from the exported selections; merge of the forward partials
 int muse_ff_build_inverse_index(const MuseDims& d, const int32_t* selc, const int32_t* selb, FFWorkspace& w,
