@@ -760,7 +760,7 @@ __global__ void __launch_bounds__(256) k_ff_bwd_cells_mx(
       const bool ok = q0 + row < qhi;
       const size_t qn = (size_t)hq * N + perm_q[(size_t)hq * N + (ok ? q0 + row : q0)];
       const int jt2 = blockIdx.x * 4 + w2;
-      mws[w2][row] = jt2 < W ? selmask[qn * W + jt2] : 0u;
+      mws[w2][row] = jt2 < W ? selmask[((size_t)hq * W + jt2) * N + (ok ? q0 + row : q0)] : 0u;
       if (w2 == 0) {
         ls[row] = ok ? LSE[qn] * 1.4426950408889634f : __builtin_huge_valf();  // +inf -> p = 0 for padding rows
         ds[row] = delta[qn];

@@ -647,6 +647,7 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
     size_t W = (d.Ck + 31) / 32;
     w->delta = (float*)take(HQ * N * 4);
     w->selmask = (uint32_t*)take(HQ * N * W * 4);
+    w->slotinfo = (int32_t*)take(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * 4);
     w->dKs = (float*)take(HK * N * D * 4);
     w->dVs = (float*)take(HK * N * D * 4);
     if (d.grad_dtype != MUSE_DTYPE_FP32) {

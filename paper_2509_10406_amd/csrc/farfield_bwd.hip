@@ -16,19 +16,50 @@
 
 namespace {
 
-// bit j of selmask[q][j/32]: query q retrieved key cluster j
-__global__ void __launch_bounds__(256) k_selmask(const int32_t* __restrict__ selc, uint32_t* __restrict__ mask,
-                                                  size_t nq, int r, int W) {
-  size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= nq * W) return;
-  size_t q = t / W;
-  int w = (int)(t % W);
-  uint32_t m = 0;
-  for (int k = 0; k < r; ++k) {
-    int j = selc[q * r + k];
-    if (j >= 0 && (j >> 5) == w) m |= 1u << (j & 31);
+// The exported selections, re-indexed by bucketed query position p (consecutive p = one (block, cluster)
+// group, so that every later read is coalesced):
+//   slotinfo[hq][p][t] = j | (bitmask of the retrieved key blocks) << 16 for slot t, -1 when the slot is empty
+//   selmask[hq][j/32][p]: bit j%32 set when query p retrieved key cluster j
+__global__ void __launch_bounds__(256) k_selinfo(const int32_t* __restrict__ selc, const int32_t* __restrict__ selb,
+                                                  const int32_t* __restrict__ perm_q, uint32_t* __restrict__ mask,
+                                                  int32_t* __restrict__ slotinfo, int N, int r, int k2e, int W) {
+  const size_t hq = blockIdx.y;
+  const int p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= N) return;
+  const size_t q = hq * N + perm_q[hq * N + p];
+  int32_t* si = slotinfo + (hq * N + p) * r;
+  int info[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) info[t] = -1;
+  for (int t = 0; t < r; ++t) {
+    const int j = selc[q * r + t];
+    int v = -1;
+    if (j >= 0) {
+      uint32_t bm = 0;
+      for (int u = 0; u < k2e; ++u) {
+        const int bb = selb[(q * r + t) * k2e + u];
+        bm |= bb >= 0 ? 1u << bb : 0u;
+      }
+      v = (int)((uint32_t)j | (bm << 16));
+    }
+    si[t] = v;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (k == t) info[k] = v;
   }
-  mask[t] = m;
+  for (int w = 0; w < W; ++w) {
+    uint32_t m = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int j = info[k] & 0xffff;
+      if (info[k] >= 0 && (j >> 5) == w) m |= 1u << (j & 31);
+    }
+    for (int t = 8; t < r; ++t) {
+      const int v = si[t], j = v & 0xffff;
+      if (v >= 0 && (j >> 5) == w) m |= 1u << (j & 31);
+    }
+    mask[(hq * W + w) * N + p] = m;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -133,7 +164,7 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(Akh + (size_t)c * D + 16 * x + 8 * half), qb[x], s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(Avh + (size_t)c * D + 16 * x + 8 * half), gb[x], dp, 0, 0, 0);
       }
-      const uint32_t mw = selmask[qn * W + jt];
+      const uint32_t mw = selmask[((size_t)hq * W + jt) * N + pos];
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         int row = 8 * (e / 4) + 4 * half + (e % 4);
@@ -163,7 +194,7 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
     int c = j0 + col;
     c = c < Ck ? c : Ck - 1;
     f32x16_t dp = mfma_rows<D>(zero16(), Avf + (size_t)c * D + 4 * half, gt);
-    const uint32_t mw = selmask[qn * W + jt];
+    const uint32_t mw = selmask[((size_t)hq * W + jt) * N + pos];
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       int row = 8 * (e / 4) + 4 * half + (e % 4);
@@ -321,7 +352,7 @@ __global__ void __launch_bounds__(64) k_ff_bwd_cells(
       ns[col] = n;
       ls[col] = ok_ ? LSE[(size_t)hq * N + n] : __builtin_huge_valf();  // +inf -> p = 0 for padding rows
       ds[col] = delta[(size_t)hq * N + n];
-      mws[col] = selmask[((size_t)hq * N + n) * W + jt];
+      mws[col] = selmask[((size_t)hq * W + jt) * N + (ok_ ? pos : q0)];
     }
     __syncthreads();
     // A operands (row pattern): this lane's query row
@@ -382,18 +413,18 @@ __global__ void __launch_bounds__(64) k_ff_bwd_cells(
 // ------------------------------------------------------------------------------------------
 // Gradients of the per-block cells, finished: one block of 256 threads per (query cluster i, tile of 32
 // key clusters); wave w owns the 8 chains (i, j, all blocks), j = 32 jt + 8 w + c.  A wave is 8 groups of
-// 8 lanes; a lane holds D/8 elements of a row (d = 32 x + 4 l8 + t).  Walking the key blocks
-// a = nb-2 .. 0:
-//   1. component 2: every query of cluster i in a later block that retrieved cluster j but not block a
-//      adds  g_k += dl q~,  g_v += p dO,  g_c += dl (1 - q~.kbar) - p dO.vbar.  The retrievals concentrate
-//      on few chains, so the entries of ONE chain are dealt round-robin to the 8 groups, summed in
-//      registers and combined by a butterfly across the groups; group c keeps the sums of chain c.
-//   2. reverse accumulation  R[a] = gA[a] + exp(Amu[a] - Amu[a+1]) R[a+1]  (registers of group c), and
-//      G[a] = g[a] + exp(mu[a] - Amu[a]) R[a]  is written out.
+// 8 lanes; a lane holds D/8 elements of a row (d = 32 x + 4 l8 + t); group c owns chain c.
+//   phase 1, reverse accumulation over the key blocks a = nb-2 .. 0, in registers:
+//      R[a] = gA[a] + exp(Amu[a] - Amu[a+1]) R[a+1],   G[a] = exp(mu[a] - Amu[a]) R[a]   (written out)
+//   phase 2, component 2: every query of cluster i in a later block that retrieved cluster j but not
+//      block a adds  g_k += dl q~,  g_v += p dO,  g_c += dl (1 - q~.kbar) - p dO.vbar  to G[a] of the chain.
+//      Few chains have such queries at all (about one in ten), and those that do have many: the entries of
+//      ONE chain are dealt round-robin to the 8 groups, summed in registers, combined by a butterfly across
+//      the groups, and group c adds the sum to the row it wrote in phase 1 (same lanes, same addresses).
 // The queries that retrieved a chain are listed once per block of threads, in bucketed order, by a
-// counting sort on wave ballots: (position n, block of n, bitmask of the retrieved key blocks).
-// All factors are <= 1.  No zero-fill, no read-modify-write in global memory, no atomics: the order of
-// every sum is fixed.
+// counting sort on wave ballots: (position n, block of n, bitmask of the retrieved key blocks); their
+// loads are issued before phase 1 and their Q / dO rows are staged in LDS once for all key blocks.
+// All factors are <= 1.  No zero-fill, no atomics, one owner per cell: the order of every sum is fixed.
 // ------------------------------------------------------------------------------------------
 template <typename T, int D>
 __global__ void __launch_bounds__(256) k_cell_grads(
@@ -401,12 +432,17 @@ __global__ void __launch_bounds__(256) k_cell_grads(
     const float* __restrict__ s_k, const T* __restrict__ s_v, const float* __restrict__ A_mu,
     const float* __restrict__ g_A_c, const T* __restrict__ g_A_k, const T* __restrict__ g_A_v,
     const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q, const float* __restrict__ LSE,
-    const float* __restrict__ delta, const uint32_t* __restrict__ selmask, const int32_t* __restrict__ selc,
-    const int32_t* __restrict__ selb, float* __restrict__ G_c, T* __restrict__ G_k, T* __restrict__ G_v, int h0,
-    int N, int nb, int Bs, int Cq, int Ck, int r, int k2e, float scale) {
+    const float* __restrict__ delta, const uint32_t* __restrict__ selmask, const int32_t* __restrict__ slotinfo,
+    float* __restrict__ G_c, T* __restrict__ G_k, T* __restrict__ G_v, int h0, int N, int nb, int Bs, int Cq, int Ck,
+    int r, float scale) {
   constexpr int NV = D / 32;
   constexpr int POOL = 2048;
+  constexpr int ECACHE = sizeof(T) == 2 ? 64 : 32;  // entries whose query rows are kept in LDS
+  using F4 = Frag<T, 4>;
   __shared__ int2 pool[POOL];
+  __shared__ __attribute__((aligned(16))) T qS[ECACHE][D];
+  __shared__ __attribute__((aligned(16))) T gS[ECACHE][D];
+  __shared__ float2 ldS[ECACHE];  // (LSE, delta)
   __shared__ int cnt[4][32];
   __shared__ int wbase[4][32];
   __shared__ int off[33];
@@ -432,26 +468,101 @@ __global__ void __launch_bounds__(256) k_cell_grads(
   const int Tq = r > 0 ? cum[nb] : 0;
   const int nchunks = (Tq + CH - 1) / CH;
 
+  // the listing's inputs of one pass: position, its word of the selection mask, its first 8 slots
+  struct QIn {
+    int n, pq;
+    uint32_t word;
+    int info[8];
+  };
+  auto load_qin = [&](int ch, QIn& qi) {
+    const int idx = ch * CH + tid;
+    qi.n = 0; qi.pq = 0; qi.word = 0;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) qi.info[t] = -1;
+    if (tid < CH && idx < Tq) {
+      int b = 1;
+      while (idx >= cum[b + 1]) ++b;
+      qi.pq = oq[b * Cq + i] + idx - cum[b];
+      qi.n = perm_q[(size_t)hq * N + qi.pq];
+      qi.word = selmask[((size_t)hq * W + jt) * N + qi.pq];
+      const int32_t* si = slotinfo + ((size_t)hq * N + qi.pq) * r;
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        if (t < r) qi.info[t] = si[t];
+    }
+  };
+  QIn qin;
+  if (nchunks > 0) load_qin(0, qin);  // in flight during phase 1
+
+  // ---- phase 1: reverse accumulation of the chain owned by this group ----
+  const int jown = jt * 32 + 8 * wave + s8;
+  const bool jok = jown < Ck;
+  {
+    float Rk[NV][4], Rv[NV][4], an = 0.f, rc = 0.f;
+#pragma unroll
+    for (int x = 0; x < NV; ++x)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) { Rk[x][t] = 0.f; Rv[x][t] = 0.f; }
+    struct Step {
+      float Am, mu, gac;
+      typename F4::raw gak[NV], gav[NV];
+    };
+    auto load_step = [&](int a, Step& st) {
+      const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + (jok ? jown : Ck - 1);
+      st.Am = A_mu[cell]; st.mu = s_mu[cell]; st.gac = g_A_c[cell];
+#pragma unroll
+      for (int x = 0; x < NV; ++x) {
+        st.gak[x] = F4::ld(g_A_k, cell * D + 32 * x + 4 * l8);
+        st.gav[x] = F4::ld(g_A_v, cell * D + 32 * x + 4 * l8);
+      }
+    };
+    Step cur, nxt;
+    load_step(NBm - 1, cur);
+    for (int a = NBm - 1; a >= 0; --a) {
+      if (a > 0) load_step(a - 1, nxt);
+      if (jok) {
+        const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + jown;
+        const float f = (a < NBm - 1 && cur.Am > MUSE_NEG_INF) ? __expf(cur.Am - an) : 0.f;
+        const float wgt = cur.mu > MUSE_NEG_INF ? __expf(cur.mu - cur.Am) : 0.f;
+        rc = cur.gac + f * rc;
+        an = cur.Am;
+        if (l8 == 0) G_c[cell] = wgt * rc;
+#pragma unroll
+        for (int x = 0; x < NV; ++x) {
+          float ok4[4], ov4[4];
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            Rk[x][t] = F4::get(cur.gak[x], t) + f * Rk[x][t];
+            Rv[x][t] = F4::get(cur.gav[x], t) + f * Rv[x][t];
+            ok4[t] = wgt * Rk[x][t];
+            ov4[t] = wgt * Rv[x][t];
+          }
+          st4(G_k, cell * D + 32 * x + 4 * l8, ok4);
+          st4(G_v, cell * D + 32 * x + 4 * l8, ov4);
+        }
+      }
+      cur = nxt;
+    }
+  }
+  if (nchunks == 0) return;
+
+  // ---- phase 2: component 2 ----
   float qcv[NV][4];
 #pragma unroll
   for (int x = 0; x < NV; ++x) {
     float4 c4 = *reinterpret_cast<const float4*>(qc + ((size_t)hq * Cq + i) * D + 32 * x + 4 * l8);
     qcv[x][0] = c4.x; qcv[x][1] = c4.y; qcv[x][2] = c4.z; qcv[x][3] = c4.w;
   }
-
-  auto build = [&](int ch) {
-    const int idx = ch * CH + tid;
-    int n = 0;
-    uint32_t word = 0;  // chains of this tile the query retrieved
-    if (tid < CH && idx < Tq) {
-      int b = 1;
-      while (idx >= cum[b + 1]) ++b;
-      n = perm_q[(size_t)hq * N + oq[b * Cq + i] + idx - cum[b]];
-      word = selmask[((size_t)hq * N + n) * W + jt];
+  const int jl0 = 8 * wave;
+  for (int ch = 0; ch < nchunks; ++ch) {
+    if (ch > 0) {
+      __syncthreads();  // the pool is rebuilt
+      load_qin(ch, qin);
     }
+    // -- chain lists: counting sort of the (query, chain) hits by chain, stable in the bucketed order
 #pragma unroll 4
     for (int c = 0; c < 32; ++c) {
-      const unsigned long long bal = __ballot((word >> c) & 1u);
+      const unsigned long long bal = __ballot((qin.word >> c) & 1u);
       if (lane == 0) cnt[wave][c] = __popcll(bal);
     }
     __syncthreads();
@@ -472,83 +583,93 @@ __global__ void __launch_bounds__(256) k_cell_grads(
       for (int w_ = 0; w_ < 4; ++w_) wbase[w_][tid] = cnt[w_][tid] + excl;
     }
     __syncthreads();
-    // ranks inside a chain follow the bucketed order of the queries
-    if (__ballot(word != 0) != 0ull) {
+    if (__ballot(qin.word != 0) != 0ull) {
+      const int bq = qin.pq / Bs;  // bucketed order is block-major
 #pragma unroll 4
       for (int c = 0; c < 32; ++c) {
-        const bool bit = (word >> c) & 1u;
+        const bool bit = (qin.word >> c) & 1u;
         const unsigned long long bal = __ballot(bit);
-        if (bit) pool[wbase[wave][c] + __popcll(bal & ((1ull << lane) - 1ull))] = make_int2(n, c);
+        if (bit) {
+          const int want = jt * 32 + c;
+          int v = -1;
+#pragma unroll
+          for (int t = 0; t < 8; ++t) v = (qin.info[t] >= 0 && (qin.info[t] & 0xffff) == want) ? qin.info[t] : v;
+          if (v < 0) {
+            const int32_t* si = slotinfo + ((size_t)hq * N + qin.pq) * r;
+            for (int t = 8; t < r; ++t) {
+              const int x = si[t];
+              if (x >= 0 && (x & 0xffff) == want) v = x;
+            }
+          }
+          pool[wbase[wave][c] + __popcll(bal & ((1ull << lane) - 1ull))] =
+              make_int2(qin.n, (int)(((uint32_t)bq << 16) | ((uint32_t)v >> 16)));
+        }
       }
     }
     __syncthreads();
-    // one thread per entry: the slot of the chain in the query's selection, then the key blocks it retrieved
+    // -- the Q and dO rows, LSE and delta of the first entries are staged once: every key block reuses them
     const int total = off[32];
-    for (int e = tid; e < total; e += 256) {
-      const int2 en = pool[e];
-      const int32_t* sc = selc + ((size_t)hq * N + en.x) * r;
-      const int want = jt * 32 + en.y;
-      int t = 0;
-      for (int t0 = 0; t0 < r; t0 += 8) {
-        int js[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) js[u] = t0 + u < r ? sc[t0 + u] : -1;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) t = js[u] == want ? t0 + u : t;
+    const int ncache = total < ECACHE ? total : ECACHE;
+    {
+      constexpr int CPR = D * (int)sizeof(T) / 16;
+      for (int idx = tid; idx < ncache * CPR; idx += 256) {
+        const int e = idx / CPR, cc = idx % CPR;
+        const size_t qn = (size_t)hq * N + pool[e].x;
+        reinterpret_cast<uint4*>(&qS[e][0])[cc] = reinterpret_cast<const uint4*>(Q + qn * D)[cc];
+        reinterpret_cast<uint4*>(&gS[e][0])[cc] = reinterpret_cast<const uint4*>(dO + qn * D)[cc];
       }
-      const int32_t* sb = selb + (((size_t)hq * N + en.x) * r + t) * k2e;
-      uint32_t bm = 0;
-      for (int u = 0; u < k2e; ++u) {
-        const int bb = sb[u];
-        bm |= bb >= 0 ? 1u << bb : 0u;
+      if (tid < ncache) {
+        const size_t qn = (size_t)hq * N + pool[tid].x;
+        ldS[tid] = make_float2(LSE[qn], delta[qn]);
       }
-      pool[e].y = (int)(((uint32_t)(en.x / Bs) << 16) | bm);
     }
     __syncthreads();
-  };
-
-  float Rk[NV][4], Rv[NV][4], an = 0.f, rc = 0.f;
+    if (off[jl0 + 8] == off[jl0]) continue;  // none of this wave's chains was retrieved (the common case)
+    for (int c = 0; c < 8; ++c) {
+      const int e0 = off[jl0 + c], e1 = off[jl0 + c + 1];
+      if (e0 == e1) continue;
+      for (int a = NBm - 1; a >= 0; --a) {
+        const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + jt * 32 + jl0 + c;
+        const float mu = s_mu[cell];  // an empty cell has mu = -inf and zero rows: p = 0, nothing is added
+        float4 kv[NV];
+        float vv[NV][4];
+        typename F4::raw ogk[NV], ogv[NV];  // the row written in phase 1 (used by group c only)
+        const float ogc = G_c[cell];
 #pragma unroll
-  for (int x = 0; x < NV; ++x)
-#pragma unroll
-    for (int t = 0; t < 4; ++t) { Rk[x][t] = 0.f; Rv[x][t] = 0.f; }
-  const int jl0 = 8 * wave;
-  for (int a = NBm - 1; a >= 0; --a) {
-    float gkK[NV][4], gvK[NV][4], gcK = 0.f;  // component-2 sums of this group's own chain
-#pragma unroll
-    for (int x = 0; x < NV; ++x)
-#pragma unroll
-      for (int t = 0; t < 4; ++t) { gkK[x][t] = 0.f; gvK[x][t] = 0.f; }
-    for (int ch = 0; ch < nchunks; ++ch) {
-      if (nchunks > 1 || a == NBm - 1) build(ch);
-      for (int c = 0; c < 8; ++c) {
-        const int e0 = off[jl0 + c], e1 = off[jl0 + c + 1];
-        if (e0 == e1) continue;
+        for (int x = 0; x < NV; ++x) {
+          kv[x] = *reinterpret_cast<const float4*>(s_k + cell * D + 32 * x + 4 * l8);
+          ld4(s_v, cell * D + 32 * x + 4 * l8, vv[x]);
+          ogk[x] = F4::ld(G_k, cell * D + 32 * x + 4 * l8);
+          ogv[x] = F4::ld(G_v, cell * D + 32 * x + 4 * l8);
+        }
         float gk[NV][4], gv[NV][4], gc = 0.f;
 #pragma unroll
         for (int x = 0; x < NV; ++x)
 #pragma unroll
           for (int t = 0; t < 4; ++t) { gk[x][t] = 0.f; gv[x][t] = 0.f; }
-        const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + jt * 32 + jl0 + c;
-        const float mu = s_mu[cell];  // an empty cell has mu = -inf and zero rows: p = 0, nothing is added
-        float4 kv[NV];
-        float vv[NV][4];
-#pragma unroll
-        for (int x = 0; x < NV; ++x) {
-          kv[x] = *reinterpret_cast<const float4*>(s_k + cell * D + 32 * x + 4 * l8);
-          ld4(s_v, cell * D + 32 * x + 4 * l8, vv[x]);
-        }
+        bool any = false;
         for (int e = e0 + s8; e < e1; e += 8) {
           const int2 en = pool[e];
           if ((en.y >> 16) <= a || ((en.y >> a) & 1)) continue;
-          const size_t qn = (size_t)hq * N + en.x;
-          float qv[NV][4], dv[NV][4];
+          any = true;
+          float qv[NV][4], dv[NV][4], lse, dl;
+          if (e < ncache) {
 #pragma unroll
-          for (int x = 0; x < NV; ++x) {
-            ld4(Q, qn * D + 32 * x + 4 * l8, qv[x]);
-            ld4(dO, qn * D + 32 * x + 4 * l8, dv[x]);
+            for (int x = 0; x < NV; ++x) {
+              ld4(&qS[e][0], 32 * x + 4 * l8, qv[x]);
+              ld4(&gS[e][0], 32 * x + 4 * l8, dv[x]);
+            }
+            const float2 ld2 = ldS[e];
+            lse = ld2.x; dl = ld2.y;
+          } else {
+            const size_t qn = (size_t)hq * N + en.x;
+#pragma unroll
+            for (int x = 0; x < NV; ++x) {
+              ld4(Q, qn * D + 32 * x + 4 * l8, qv[x]);
+              ld4(dO, qn * D + 32 * x + 4 * l8, dv[x]);
+            }
+            lse = LSE[qn]; dl = delta[qn];
           }
-          const float lse = LSE[qn], dl = delta[qn];
           float part = 0.f, dpp = 0.f;
 #pragma unroll
           for (int x = 0; x < NV; ++x) {
@@ -575,7 +696,8 @@ __global__ void __launch_bounds__(256) k_cell_grads(
             }
           gc += dlg * (1.f - part) - p * dpp;
         }
-        // butterfly over the 8 groups: every group ends with the same sums, group c keeps them
+        if (__ballot(any) == 0ull) continue;  // no query of this chain attends block a through component 2
+        // butterfly over the 8 groups: every group ends with the same sums, group c adds them to its row
 #pragma unroll
         for (int o = 8; o < 64; o <<= 1) {
           gc += __shfl_xor(gc, o, 64);
@@ -588,39 +710,19 @@ __global__ void __launch_bounds__(256) k_cell_grads(
             }
         }
         if (s8 == c) {
-          gcK += gc;
+          if (l8 == 0) G_c[cell] = ogc + gc;
 #pragma unroll
-          for (int x = 0; x < NV; ++x)
+          for (int x = 0; x < NV; ++x) {
+            float ok4[4], ov4[4];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) { gkK[x][t] += gk[x][t]; gvK[x][t] += gv[x][t]; }
+            for (int t = 0; t < 4; ++t) {
+              ok4[t] = F4::get(ogk[x], t) + gk[x][t];
+              ov4[t] = F4::get(ogv[x], t) + gv[x][t];
+            }
+            st4(G_k, cell * D + 32 * x + 4 * l8, ok4);
+            st4(G_v, cell * D + 32 * x + 4 * l8, ov4);
+          }
         }
-      }
-      if (nchunks > 1) __syncthreads();  // the pool is rebuilt for the next pass
-    }
-    const int j = jt * 32 + jl0 + s8;
-    if (j < Ck) {
-      const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + j;
-      const float Am = A_mu[cell], mu = s_mu[cell];
-      const float f = (a < NBm - 1 && Am > MUSE_NEG_INF) ? __expf(Am - an) : 0.f;
-      const float wgt = mu > MUSE_NEG_INF ? __expf(mu - Am) : 0.f;
-      rc = g_A_c[cell] + f * rc;
-      an = Am;
-      if (l8 == 0) G_c[cell] = gcK + wgt * rc;
-#pragma unroll
-      for (int x = 0; x < NV; ++x) {
-        const size_t o = cell * D + 32 * x + 4 * l8;
-        float ak4[4], av4[4], ok4[4], ov4[4];
-        ld4(g_A_k, o, ak4);
-        ld4(g_A_v, o, av4);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          Rk[x][t] = ak4[t] + f * Rk[x][t];
-          Rv[x][t] = av4[t] + f * Rv[x][t];
-          ok4[t] = gkK[x][t] + wgt * Rk[x][t];
-          ov4[t] = gvK[x][t] + wgt * Rv[x][t];
-        }
-        st4(G_k, o, ok4);
-        st4(G_v, o, ov4);
       }
     }
   }
@@ -908,8 +1010,8 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
                      w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.g_A_c, (float*)w.g_A_k, (float*)w.g_A_v, h0, d.N, d.nb, d.Cq, d.Ck,
                      d.scale); }
   { MuseProf prof_("k_cell_grads", st); hipLaunchKernelGGL((k_cell_grads<T, D>), dim3(W, d.Cq, hn), dim3(256), 0, st, Q, dO, qc, w.s_mu, w.s_k, (const T*)w.s_v, w.A_mu,
-                     w.g_A_c, (const T*)w.g_A_k, (const T*)w.g_A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask, selc, selb, w.g_s_c, (T*)w.g_s_k,
-                     (T*)w.g_s_v, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
+                     w.g_A_c, (const T*)w.g_A_k, (const T*)w.g_A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.slotinfo, w.g_s_c, (T*)w.g_s_k,
+                     (T*)w.g_s_v, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.scale); }
   const int G_ = d.Hq / d.Hkv;
   if (sizeof(T) == 2) {
     int rc2 = muse_launch_cells_to_keys_mx(d, w.Ks, w.Vs, qc, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs,
@@ -939,7 +1041,7 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
   if (d.nb > 1) {
     const int W = (d.Ck + 31) / 32;
     if (d.r > 0) {
-      { MuseProf prof_("k_selmask", st); hipLaunchKernelGGL(k_selmask, dim3((unsigned)((nq * W + 255) / 256)), dim3(256), 0, st, selc, w.selmask, nq, d.r, W); }
+      { MuseProf prof_("k_selinfo", st); hipLaunchKernelGGL(k_selinfo, dim3((N + 255) / 256, HQ), dim3(256), 0, st, selc, selb, w.perm_q, w.selmask, w.slotinfo, N, d.r, d.k2e, W); }
     } else {
       if ((rc = muse_launch_fill_i32((int32_t*)w.selmask, nq * W, 0, st))) return rc;
     }

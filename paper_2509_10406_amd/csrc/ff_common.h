@@ -129,7 +129,8 @@ struct FFWorkspace {
   float *ff_acc, *ff_ml;  // contiguous: [HQ,N,D] then [HQ,N,2]
   // backward only, all heads
   float* delta;
-  uint32_t* selmask;
+  uint32_t* selmask;   // [HQ][W][N] by bucketed query position
+  int32_t* slotinfo;   // [HQ][N][r] by bucketed query position: cluster | retrieved-block mask << 16
   uint32_t* pairmask;  // [HQ][nb-1][W][N]
   int32_t *pair_cnt, *pair_off;  // inverse index of the retrieval: (kv head, key block, key cluster) -> hits
   uint2* hits;                   // x = n | g << 22 (query position, head inside the KV group), y = slot*k2e + u
@@ -162,7 +163,7 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
   b += ff_al(HQ * N * W * 4 * NBm) + 2 * ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) + ff_al(HQ * N * R2 * 8) +
        ff_al(HQ * N * R2 * (D + 4) * 4);
   if (bwd) {
-    b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + 2 * ff_al(HK * N * D * 4);
+    b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + ff_al(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * 4) + 2 * ff_al(HK * N * D * 4);
     if (d.grad_dtype != MUSE_DTYPE_FP32) b += ff_al(HQ * N * D * 4) + 2 * ff_al(HK * N * D * 4);
   }
   return b;
