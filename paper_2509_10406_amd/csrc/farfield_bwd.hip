@@ -418,12 +418,12 @@ __global__ void __launch_bounds__(64) k_ff_bwd_cells(
 //      R[a] = gA[a] + exp(Amu[a] - Amu[a+1]) R[a+1],   G[a] = exp(mu[a] - Amu[a]) R[a]   (written out)
 //   phase 2, component 2: every query of cluster i in a later block that retrieved cluster j but not
 //      block a adds  g_k += dl q~,  g_v += p dO,  g_c += dl (1 - q~.kbar) - p dO.vbar  to G[a] of the chain.
-//      Few chains have such queries at all (about one in ten), and those that do have many: the entries of
-//      ONE chain are dealt round-robin to the 8 groups, summed in registers, combined by a butterfly across
-//      the groups, and group c adds the sum to the row it wrote in phase 1 (same lanes, same addresses).
+//      Few chains have such queries at all (about one in ten), and those that do have many.  For one chain,
+//      group g takes key block a = g, so the loads of all its blocks are one round trip, walks the chain's
+//      entries (rows staged in LDS) and adds its sum to the row of (chain, a) written in phase 1.
 // The queries that retrieved a chain are listed once per block of threads, in bucketed order, by a
-// counting sort on wave ballots: (position n, block of n, bitmask of the retrieved key blocks); their
-// loads are issued before phase 1 and their Q / dO rows are staged in LDS once for all key blocks.
+// counting sort on wave ballots: (position n, block of n, bitmask of the retrieved key blocks); the
+// listing's loads are issued before phase 1.
 // All factors are <= 1.  No zero-fill, no atomics, one owner per cell: the order of every sum is fixed.
 // ------------------------------------------------------------------------------------------
 template <typename T, int D>
@@ -437,7 +437,7 @@ __global__ void __launch_bounds__(256) k_cell_grads(
     int r, float scale) {
   constexpr int NV = D / 32;
   constexpr int POOL = 2048;
-  constexpr int ECACHE = sizeof(T) == 2 ? 64 : 32;  // entries whose query rows are kept in LDS
+  constexpr int ECACHE = 16384 / (D * (int)sizeof(T));  // entries staged at a time (2 x 16 KB of rows)
   using F4 = Frag<T, 4>;
   __shared__ int2 pool[POOL];
   __shared__ __attribute__((aligned(16))) T qS[ECACHE][D];
@@ -607,120 +607,103 @@ __global__ void __launch_bounds__(256) k_cell_grads(
       }
     }
     __syncthreads();
-    // -- the Q and dO rows, LSE and delta of the first entries are staged once: every key block reuses them
+    // -- component 2, ECACHE entries at a time: their Q and dO rows, LSE and delta are staged in LDS; for a
+    //    chain, group g takes key block a = g (all blocks of the chain in flight together: one round trip),
+    //    walks the chain's staged entries and adds its sum to the row written in phase 1
     const int total = off[32];
-    const int ncache = total < ECACHE ? total : ECACHE;
-    {
-      constexpr int CPR = D * (int)sizeof(T) / 16;
-      for (int idx = tid; idx < ncache * CPR; idx += 256) {
-        const int e = idx / CPR, cc = idx % CPR;
-        const size_t qn = (size_t)hq * N + pool[e].x;
-        reinterpret_cast<uint4*>(&qS[e][0])[cc] = reinterpret_cast<const uint4*>(Q + qn * D)[cc];
-        reinterpret_cast<uint4*>(&gS[e][0])[cc] = reinterpret_cast<const uint4*>(dO + qn * D)[cc];
-      }
-      if (tid < ncache) {
-        const size_t qn = (size_t)hq * N + pool[tid].x;
-        ldS[tid] = make_float2(LSE[qn], delta[qn]);
-      }
-    }
-    __syncthreads();
-    if (off[jl0 + 8] == off[jl0]) continue;  // none of this wave's chains was retrieved (the common case)
-    for (int c = 0; c < 8; ++c) {
-      const int e0 = off[jl0 + c], e1 = off[jl0 + c + 1];
-      if (e0 == e1) continue;
-      for (int a = NBm - 1; a >= 0; --a) {
-        const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + jt * 32 + jl0 + c;
-        const float mu = s_mu[cell];  // an empty cell has mu = -inf and zero rows: p = 0, nothing is added
-        float4 kv[NV];
-        float vv[NV][4];
-        typename F4::raw ogk[NV], ogv[NV];  // the row written in phase 1 (used by group c only)
-        const float ogc = G_c[cell];
-#pragma unroll
-        for (int x = 0; x < NV; ++x) {
-          kv[x] = *reinterpret_cast<const float4*>(s_k + cell * D + 32 * x + 4 * l8);
-          ld4(s_v, cell * D + 32 * x + 4 * l8, vv[x]);
-          ogk[x] = F4::ld(G_k, cell * D + 32 * x + 4 * l8);
-          ogv[x] = F4::ld(G_v, cell * D + 32 * x + 4 * l8);
+    for (int r0 = 0; r0 < total; r0 += ECACHE) {
+      const int nst = total - r0 < ECACHE ? total - r0 : ECACHE;
+      if (r0 > 0) __syncthreads();
+      {
+        constexpr int CPR = D * (int)sizeof(T) / 16;
+        for (int idx = tid; idx < nst * CPR; idx += 256) {
+          const int e = idx / CPR, cc = idx % CPR;
+          const size_t qn = (size_t)hq * N + pool[r0 + e].x;
+          reinterpret_cast<uint4*>(&qS[e][0])[cc] = reinterpret_cast<const uint4*>(Q + qn * D)[cc];
+          reinterpret_cast<uint4*>(&gS[e][0])[cc] = reinterpret_cast<const uint4*>(dO + qn * D)[cc];
         }
-        float gk[NV][4], gv[NV][4], gc = 0.f;
-#pragma unroll
-        for (int x = 0; x < NV; ++x)
-#pragma unroll
-          for (int t = 0; t < 4; ++t) { gk[x][t] = 0.f; gv[x][t] = 0.f; }
-        bool any = false;
-        for (int e = e0 + s8; e < e1; e += 8) {
-          const int2 en = pool[e];
-          if ((en.y >> 16) <= a || ((en.y >> a) & 1)) continue;
-          any = true;
-          float qv[NV][4], dv[NV][4], lse, dl;
-          if (e < ncache) {
-#pragma unroll
-            for (int x = 0; x < NV; ++x) {
-              ld4(&qS[e][0], 32 * x + 4 * l8, qv[x]);
-              ld4(&gS[e][0], 32 * x + 4 * l8, dv[x]);
-            }
-            const float2 ld2 = ldS[e];
-            lse = ld2.x; dl = ld2.y;
-          } else {
-            const size_t qn = (size_t)hq * N + en.x;
-#pragma unroll
-            for (int x = 0; x < NV; ++x) {
-              ld4(Q, qn * D + 32 * x + 4 * l8, qv[x]);
-              ld4(dO, qn * D + 32 * x + 4 * l8, dv[x]);
-            }
-            lse = LSE[qn]; dl = delta[qn];
-          }
-          float part = 0.f, dpp = 0.f;
+        if (tid < nst) {
+          const size_t qn = (size_t)hq * N + pool[r0 + tid].x;
+          ldS[tid] = make_float2(LSE[qn], delta[qn]);
+        }
+      }
+      __syncthreads();
+      for (int c = 0; c < 8; ++c) {
+        const int e0 = off[jl0 + c] > r0 ? off[jl0 + c] : r0;
+        const int e1 = off[jl0 + c + 1] < r0 + nst ? off[jl0 + c + 1] : r0 + nst;
+        if (e0 >= e1) continue;
+        for (int a0 = 0; a0 < NBm; a0 += 8) {
+          const int a = a0 + s8;
+          const bool act = a < NBm;
+          const size_t cell = (((size_t)hl * NBm + (act ? a : 0)) * Cq + i) * Ck + jt * 32 + jl0 + c;
+          const float mu = s_mu[cell];  // an empty cell has mu = -inf and zero rows: p = 0, nothing is added
+          float4 kv[NV];
+          float vv[NV][4];
+          typename F4::raw ogk[NV], ogv[NV];  // the row written in phase 1
+          const float ogc = G_c[cell];
 #pragma unroll
           for (int x = 0; x < NV; ++x) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) qv[x][t] = scale * (qv[x][t] - qcv[x][t]);
-            part = fmaf(qv[x][0], kv[x].x, part); part = fmaf(qv[x][1], kv[x].y, part);
-            part = fmaf(qv[x][2], kv[x].z, part); part = fmaf(qv[x][3], kv[x].w, part);
-            dpp = fmaf(dv[x][0], vv[x][0], dpp); dpp = fmaf(dv[x][1], vv[x][1], dpp);
-            dpp = fmaf(dv[x][2], vv[x][2], dpp); dpp = fmaf(dv[x][3], vv[x][3], dpp);
+            kv[x] = *reinterpret_cast<const float4*>(s_k + cell * D + 32 * x + 4 * l8);
+            ld4(s_v, cell * D + 32 * x + 4 * l8, vv[x]);
+            ogk[x] = F4::ld(G_k, cell * D + 32 * x + 4 * l8);
+            ogv[x] = F4::ld(G_v, cell * D + 32 * x + 4 * l8);
           }
-#pragma unroll
-          for (int o = 1; o < 8; o <<= 1) {
-            part += __shfl_xor(part, o, 64);
-            dpp += __shfl_xor(dpp, o, 64);
-          }
-          const float p = __expf(part + mu - lse);
-          const float dlg = p * (dpp - dl);
+          float gk[NV][4], gv[NV][4], gc = 0.f;
 #pragma unroll
           for (int x = 0; x < NV; ++x)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-              gk[x][t] = fmaf(dlg, qv[x][t], gk[x][t]);
-              gv[x][t] = fmaf(p, dv[x][t], gv[x][t]);
+            for (int t = 0; t < 4; ++t) { gk[x][t] = 0.f; gv[x][t] = 0.f; }
+          bool any = false;
+          for (int e = e0; e < e1; ++e) {
+            const int2 en = pool[e];
+            if (!act || (en.y >> 16) <= a || ((en.y >> a) & 1)) continue;
+            any = true;
+            float qv[NV][4], dv[NV][4];
+#pragma unroll
+            for (int x = 0; x < NV; ++x) {
+              ld4(&qS[e - r0][0], 32 * x + 4 * l8, qv[x]);
+              ld4(&gS[e - r0][0], 32 * x + 4 * l8, dv[x]);
             }
-          gc += dlg * (1.f - part) - p * dpp;
-        }
-        if (__ballot(any) == 0ull) continue;  // no query of this chain attends block a through component 2
-        // butterfly over the 8 groups: every group ends with the same sums, group c adds them to its row
+            const float2 ld2 = ldS[e - r0];
+            float part = 0.f, dpp = 0.f;
 #pragma unroll
-        for (int o = 8; o < 64; o <<= 1) {
-          gc += __shfl_xor(gc, o, 64);
+            for (int x = 0; x < NV; ++x) {
 #pragma unroll
-          for (int x = 0; x < NV; ++x)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-              gk[x][t] += __shfl_xor(gk[x][t], o, 64);
-              gv[x][t] += __shfl_xor(gv[x][t], o, 64);
+              for (int t = 0; t < 4; ++t) qv[x][t] = scale * (qv[x][t] - qcv[x][t]);
+              part = fmaf(qv[x][0], kv[x].x, part); part = fmaf(qv[x][1], kv[x].y, part);
+              part = fmaf(qv[x][2], kv[x].z, part); part = fmaf(qv[x][3], kv[x].w, part);
+              dpp = fmaf(dv[x][0], vv[x][0], dpp); dpp = fmaf(dv[x][1], vv[x][1], dpp);
+              dpp = fmaf(dv[x][2], vv[x][2], dpp); dpp = fmaf(dv[x][3], vv[x][3], dpp);
             }
-        }
-        if (s8 == c) {
-          if (l8 == 0) G_c[cell] = ogc + gc;
 #pragma unroll
-          for (int x = 0; x < NV; ++x) {
-            float ok4[4], ov4[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-              ok4[t] = F4::get(ogk[x], t) + gk[x][t];
-              ov4[t] = F4::get(ogv[x], t) + gv[x][t];
+            for (int o = 1; o < 8; o <<= 1) {
+              part += __shfl_xor(part, o, 64);
+              dpp += __shfl_xor(dpp, o, 64);
             }
-            st4(G_k, cell * D + 32 * x + 4 * l8, ok4);
-            st4(G_v, cell * D + 32 * x + 4 * l8, ov4);
+            const float p = __expf(part + mu - ld2.x);
+            const float dlg = p * (dpp - ld2.y);
+#pragma unroll
+            for (int x = 0; x < NV; ++x)
+#pragma unroll
+              for (int t = 0; t < 4; ++t) {
+                gk[x][t] = fmaf(dlg, qv[x][t], gk[x][t]);
+                gv[x][t] = fmaf(p, dv[x][t], gv[x][t]);
+              }
+            gc += dlg * (1.f - part) - p * dpp;
+          }
+          if (any) {
+            if (l8 == 0) G_c[cell] = ogc + gc;
+#pragma unroll
+            for (int x = 0; x < NV; ++x) {
+              float ok4[4], ov4[4];
+#pragma unroll
+              for (int t = 0; t < 4; ++t) {
+                ok4[t] = F4::get(ogk[x], t) + gk[x][t];
+                ov4[t] = F4::get(ogv[x], t) + gv[x][t];
+              }
+              st4(G_k, cell * D + 32 * x + 4 * l8, ok4);
+              st4(G_v, cell * D + 32 * x + 4 * l8, ov4);
+            }
           }
         }
       }
