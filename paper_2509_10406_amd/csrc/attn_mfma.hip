@@ -492,8 +492,10 @@ __global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, c
 }
 
 // ------------------------------------------------------------------------------------------
-// Retrieval forward (Sec. 3.3 "Exact retrieval"): one wave per retrieved pair; the queries that
-// retrieved it are the MFMA columns (32 at a time, rows read straight from Q), its keys the rows.
+// Retrieval forward (Sec. 3.3 "Exact retrieval"): one wave per retrieved pair and hit slice; the queries
+// that retrieved it are the MFMA columns (32 at a time, rows read straight from Q), its keys the rows.
+// A pair rarely has more than 32 keys: its key fragments and transposed value tile are then loaded once
+// and reused by every hit tile; the hit list of the next tile is fetched while this one is computed.
 // Writes, per (query, slot), the partial softmax state over the keys of the pair:
 //   part[(qn*R2 + su)][0..D) = sum_m exp(l_m - max) v_m,  [D] = max (natural log units),  [D+1] = sum.
 // ------------------------------------------------------------------------------------------
@@ -502,23 +504,51 @@ __global__ void __launch_bounds__(64) k_ret_fwd_pairs(const bf16_t* __restrict__
                                                        const bf16_t* __restrict__ Vs, const int32_t* __restrict__ off_k,
                                                        const int32_t* __restrict__ pair_off, const uint2* __restrict__ hits,
                                                        float* __restrict__ part, size_t hit_cap, int N, int nb, int Ck,
-                                                       int Hq, int Hkv, int R2, float scale_log2e) {
-  constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
+                                                       int Hq, int Hkv, int R2, int S, float scale_log2e) {
+  constexpr int KS = D / 16, DT = D / 32, CPR = D / 8, NIT = 32 * CPR / 64;
   __shared__ __attribute__((aligned(16))) bf16_t vt[D][32 + 8];
-  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
+  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z / S, sl = blockIdx.z % S, NBm = nb - 1;
   const int G_ = Hq / Hkv;
   const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
   const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
   const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
   const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
   const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
-  const int hlo = po[0], hhi = po[1];
-  if (klo == khi || hlo == hhi) return;
+  const int hlo = po[0] + 32 * sl, hhi = po[1];
+  if (klo == khi || hlo >= hhi) return;
   const uint2* hh = hits + (size_t)hk * hit_cap;
-  for (int h0 = hlo; h0 < hhi; h0 += 32) {
+  const bool single = khi - klo <= 32;
+  bf16x8_t kf[KS];
+  auto stage = [&](int k0) {  // key fragments of row `col` and the transposed value tile of keys k0 .. k0+31
+    uint4 v[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+      const int kr = k0 + row < khi ? k0 + row : khi - 1;
+      v[it] = *reinterpret_cast<const uint4*>(Vs + ((size_t)hk * N + kr) * D + cc * 8);
+    }
+    const int kr = k0 + col < khi ? k0 + col : khi - 1;
+#pragma unroll
+    for (int x = 0; x < KS; ++x)
+      kf[x] = *reinterpret_cast<const bf16x8_t*>(Ks + ((size_t)hk * N + kr) * D + 16 * x + 8 * half);
+    wave_lds_fence();
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+      const bf16_t* pv = reinterpret_cast<const bf16_t*>(&v[it]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vt[cc * 8 + e][row] = pv[e];
+    }
+    wave_lds_fence();
+  };
+  if (single) stage(klo);
+  uint2 hit = hh[hlo + col < hhi ? hlo + col : hhi - 1];
+  for (int h0 = hlo; h0 < hhi; h0 += 32 * S) {
     const bool hvalid = h0 + col < hhi;
-    const uint2 hit = hh[hvalid ? h0 + col : hhi - 1];
-    const size_t qn = (hqbase + (hit.x >> 22)) * N + (hit.x & 0x3fffffu);
+    const uint2 hcur = hit;
+    const int hn = h0 + 32 * S;
+    if (hn < hhi) hit = hh[hn + col < hhi ? hn + col : hhi - 1];
+    const size_t qn = (hqbase + (hcur.x >> 22)) * N + (hcur.x & 0x3fffffu);
     bf16x8_t qf[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) qf[s] = *reinterpret_cast<const bf16x8_t*>(Q + qn * D + 16 * s + 8 * half);
@@ -529,25 +559,12 @@ __global__ void __launch_bounds__(64) k_ret_fwd_pairs(const bf16_t* __restrict__
       for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
     float m = MUSE_NEG_INF, l = 0.f;
     for (int k0 = klo; k0 < khi; k0 += 32) {
-      __syncthreads();
-      for (int c = lane; c < 32 * CPR; c += 64) {
-        const int row = c / CPR, cc = c % CPR;
-        const int kr = k0 + row < khi ? k0 + row : khi - 1;
-        uint4 v = *reinterpret_cast<const uint4*>(Vs + ((size_t)hk * N + kr) * D + cc * 8);
-        const bf16_t* pv = reinterpret_cast<const bf16_t*>(&v);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) vt[cc * 8 + e][row] = pv[e];
-      }
-      __syncthreads();
-      const int kr = k0 + col < khi ? k0 + col : khi - 1;
+      if (!single) stage(k0);
       f32x16_t s;
 #pragma unroll
       for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
-      for (int x = 0; x < KS; ++x) {
-        bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(Ks + ((size_t)hk * N + kr) * D + 16 * x + 8 * half);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[x], s, 0, 0, 0);
-      }
+      for (int x = 0; x < KS; ++x) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[x], qf[x], s, 0, 0, 0);
       float tmax = MUSE_NEG_INF;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
@@ -583,7 +600,7 @@ __global__ void __launch_bounds__(64) k_ret_fwd_pairs(const bf16_t* __restrict__
     }
     l += __shfl_xor(l, 32, 64);
     if (hvalid) {
-      float* pr = part + (qn * R2 + hit.y) * (size_t)(D + 4);
+      float* pr = part + (qn * R2 + hcur.y) * (size_t)(D + 4);
 #pragma unroll
       for (int t = 0; t < DT; ++t)
 #pragma unroll
@@ -607,23 +624,53 @@ __global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restric
                                                           const int32_t* __restrict__ pair_off,
                                                           const uint2* __restrict__ hits, float* __restrict__ dqpart,
                                                           size_t hit_cap, int N, int nb, int Ck, int Hq, int Hkv, int R2,
-                                                          float scale, float scale_log2e) {
-  constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
+                                                          int S, float scale, float scale_log2e) {
+  constexpr int KS = D / 16, DT = D / 32, CPR = D / 8, NIT = 32 * CPR / 64;
   __shared__ __attribute__((aligned(16))) bf16_t kt_[D][32 + 8];
-  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
+  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z / S, sl = blockIdx.z % S, NBm = nb - 1;
   const int G_ = Hq / Hkv;
   const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
   const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
   const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
   const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
   const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
-  const int hlo = po[0], hhi = po[1];
-  if (klo == khi || hlo == hhi) return;
+  const int hlo = po[0] + 32 * sl, hhi = po[1];
+  if (klo == khi || hlo >= hhi) return;
   const uint2* hh = hits + (size_t)hk * hit_cap;
-  for (int h0 = hlo; h0 < hhi; h0 += 32) {
+  const bool single = khi - klo <= 32;
+  bf16x8_t kf[KS], vf[KS];
+  auto stage = [&](int k0) {  // key / value fragments of row `col` and the transposed key tile of keys k0 .. k0+31
+    uint4 v[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+      const int kr = k0 + row < khi ? k0 + row : khi - 1;
+      v[it] = *reinterpret_cast<const uint4*>(Ks + ((size_t)hk * N + kr) * D + cc * 8);
+    }
+    const int kr = k0 + col < khi ? k0 + col : khi - 1;
+#pragma unroll
+    for (int x = 0; x < KS; ++x) {
+      kf[x] = *reinterpret_cast<const bf16x8_t*>(Ks + ((size_t)hk * N + kr) * D + 16 * x + 8 * half);
+      vf[x] = *reinterpret_cast<const bf16x8_t*>(Vs + ((size_t)hk * N + kr) * D + 16 * x + 8 * half);
+    }
+    wave_lds_fence();
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+      const bf16_t* pv = reinterpret_cast<const bf16_t*>(&v[it]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) kt_[cc * 8 + e][row] = pv[e];
+    }
+    wave_lds_fence();
+  };
+  if (single) stage(klo);
+  uint2 hit = hh[hlo + col < hhi ? hlo + col : hhi - 1];
+  for (int h0 = hlo; h0 < hhi; h0 += 32 * S) {
     const bool hvalid = h0 + col < hhi;
-    const uint2 hit = hh[hvalid ? h0 + col : hhi - 1];
-    const size_t qn = (hqbase + (hit.x >> 22)) * N + (hit.x & 0x3fffffu);
+    const uint2 hcur = hit;
+    const int hn = h0 + 32 * S;
+    if (hn < hhi) hit = hh[hn + col < hhi ? hn + col : hhi - 1];
+    const size_t qn = (hqbase + (hcur.x >> 22)) * N + (hcur.x & 0x3fffffu);
     bf16x8_t qf[KS], gf[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
@@ -637,26 +684,14 @@ __global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restric
 #pragma unroll
       for (int e = 0; e < 16; ++e) dq[t][e] = 0.f;
     for (int k0 = klo; k0 < khi; k0 += 32) {
-      __syncthreads();
-      for (int c = lane; c < 32 * CPR; c += 64) {
-        const int row = c / CPR, cc = c % CPR;
-        const int kr = k0 + row < khi ? k0 + row : khi - 1;
-        uint4 v = *reinterpret_cast<const uint4*>(Ks + ((size_t)hk * N + kr) * D + cc * 8);
-        const bf16_t* pv = reinterpret_cast<const bf16_t*>(&v);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) kt_[cc * 8 + e][row] = pv[e];
-      }
-      __syncthreads();
-      const int kr = k0 + col < khi ? k0 + col : khi - 1;
+      if (!single) stage(k0);
       f32x16_t s, dp;
 #pragma unroll
       for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
       for (int x = 0; x < KS; ++x) {
-        bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(Ks + ((size_t)hk * N + kr) * D + 16 * x + 8 * half);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[x], s, 0, 0, 0);
-        bf16x8_t av = *reinterpret_cast<const bf16x8_t*>(Vs + ((size_t)hk * N + kr) * D + 16 * x + 8 * half);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, gf[x], dp, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[x], qf[x], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[x], gf[x], dp, 0, 0, 0);
       }
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
@@ -676,7 +711,7 @@ __global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restric
       }
     }
     if (hvalid) {
-      float* pr = dqpart + (qn * R2 + hit.y) * (size_t)D;
+      float* pr = dqpart + (qn * R2 + hcur.y) * (size_t)D;
 #pragma unroll
       for (int t = 0; t < DT; ++t)
 #pragma unroll
@@ -957,12 +992,13 @@ int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO
 
 int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, const void* Vs, const int32_t* off_k,
                               const int32_t* pair_off, const uint2* hits, size_t hit_cap, float* part, hipStream_t st) {
-  dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv);
+  const int S = 4;  // hit slices per pair: slice s takes the hit tiles s, s + S, ... (a few pairs hold thousands of hits)
+  dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv * S);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64)
-    { MuseProf prof_("k_ret_fwd_pairs", st); hipLaunchKernelGGL(k_ret_fwd_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)Ks, (const bf16_t*)Vs, off_k, pair_off, hits, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, sl); }
+    { MuseProf prof_("k_ret_fwd_pairs", st); hipLaunchKernelGGL(k_ret_fwd_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)Ks, (const bf16_t*)Vs, off_k, pair_off, hits, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, S, sl); }
   else
-    { MuseProf prof_("k_ret_fwd_pairs", st); hipLaunchKernelGGL(k_ret_fwd_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)Ks, (const bf16_t*)Vs, off_k, pair_off, hits, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, sl); }
+    { MuseProf prof_("k_ret_fwd_pairs", st); hipLaunchKernelGGL(k_ret_fwd_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)Ks, (const bf16_t*)Vs, off_k, pair_off, hits, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, S, sl); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
@@ -970,12 +1006,13 @@ int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, 
 int muse_launch_ret_bwd_dq_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
                                  const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
                                  const uint2* hits, size_t hit_cap, float* dqpart, hipStream_t st) {
-  dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv);
+  const int S = 4;  // hit slices per pair, as in the forward
+  dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv * S);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64)
-    { MuseProf prof_("k_ret_bwd_dq_pairs", st); hipLaunchKernelGGL(k_ret_bwd_dq_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks, (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dqpart, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, d.scale, sl); }
+    { MuseProf prof_("k_ret_bwd_dq_pairs", st); hipLaunchKernelGGL(k_ret_bwd_dq_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks, (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dqpart, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, S, d.scale, sl); }
   else
-    { MuseProf prof_("k_ret_bwd_dq_pairs", st); hipLaunchKernelGGL(k_ret_bwd_dq_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks, (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dqpart, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, d.scale, sl); }
+    { MuseProf prof_("k_ret_bwd_dq_pairs", st); hipLaunchKernelGGL(k_ret_bwd_dq_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks, (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dqpart, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, S, d.scale, sl); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
