@@ -414,28 +414,41 @@ __global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, c
     for (int t = 0; t < DT; ++t)
 #pragma unroll
       for (int e = 0; e < 16; ++e) { dk[t][e] = 0.f; dv[t][e] = 0.f; }
+    // the hit list of a tile is one coalesced load (lane -> row), fetched one tile ahead
+    uint32_t hitn = hh[hlo + col < hhi ? hlo + col : hhi - 1].x;
     for (int h0 = hlo; h0 < hhi; h0 += 32) {
-      __syncthreads();
-      for (int c = lane; c < 32 * CPR; c += 64) {
-        const int row = c / CPR, cc = c % CPR;
-        const int hi_ = h0 + row < hhi ? h0 + row : hhi - 1;
-        const uint32_t hit = hh[hi_].x;
+      const uint32_t hitc = hitn;
+      if (h0 + 32 < hhi) hitn = hh[h0 + 32 + col < hhi ? h0 + 32 + col : hhi - 1].x;
+      // gather: every row load of the tile is issued before the first LDS write
+      constexpr int NIT = 32 * CPR / 64;
+      uint4 qv[NIT], gv[NIT];
+      float lv = 0.f, dv_ = 0.f;
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+        const uint32_t hit = (uint32_t)__shfl((int)hitc, row, 64);
         const size_t qn = (hqbase + (hit >> 22)) * N + (hit & 0x3fffffu);
-        uint4 qv = *reinterpret_cast<const uint4*>(Q + qn * D + cc * 8);
-        uint4 gv = *reinterpret_cast<const uint4*>(dO + qn * D + cc * 8);
-        *reinterpret_cast<uint4*>(&qs[row][cc * 8]) = qv;
-        *reinterpret_cast<uint4*>(&gs[row][cc * 8]) = gv;
-        const bf16_t* pq = reinterpret_cast<const bf16_t*>(&qv);
-        const bf16_t* pg = reinterpret_cast<const bf16_t*>(&gv);
+        qv[it] = *reinterpret_cast<const uint4*>(Q + qn * D + cc * 8);
+        gv[it] = *reinterpret_cast<const uint4*>(dO + qn * D + cc * 8);
+      }
+      if (lane < 32) {
+        const size_t qn = (hqbase + (hitc >> 22)) * N + (hitc & 0x3fffffu);
+        lv = h0 + lane < hhi ? LSE[qn] * 1.4426950408889634f : __builtin_huge_valf();  // +inf -> p = 0
+        dv_ = delta[qn];
+      }
+      wave_lds_fence();
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+        *reinterpret_cast<uint4*>(&qs[row][cc * 8]) = qv[it];
+        *reinterpret_cast<uint4*>(&gs[row][cc * 8]) = gv[it];
+        const bf16_t* pq = reinterpret_cast<const bf16_t*>(&qv[it]);
+        const bf16_t* pg = reinterpret_cast<const bf16_t*>(&gv[it]);
 #pragma unroll
         for (int e = 0; e < 8; ++e) { qt_[cc * 8 + e][row] = pq[e]; gt_[cc * 8 + e][row] = pg[e]; }
-        if (cc == 0) {
-          const bool ok2 = h0 + row < hhi;
-          lse_s[row] = ok2 ? LSE[qn] * 1.4426950408889634f : __builtin_huge_valf();  // +inf -> p = 0
-          dl_s[row] = delta[qn];
-        }
       }
-      __syncthreads();
+      if (lane < 32) { lse_s[lane] = lv; dl_s[lane] = dv_; }
+      wave_lds_fence();
       f32x16_t s, dp;
 #pragma unroll
       for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
