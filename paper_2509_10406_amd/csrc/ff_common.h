@@ -122,6 +122,8 @@ __device__ __forceinline__ bf16x8_t cvt8(const float* __restrict__ p) {
 }
 
 
+constexpr int kHitSeg = 8;  // query-range slices per (pair, head) when the hit lists are built
+
 struct FFWorkspace {
   // all heads
   int32_t *perm_k, *off_k, *perm_q, *off_q, *tile_off;
@@ -132,7 +134,8 @@ struct FFWorkspace {
   uint32_t* selmask;   // [HQ][W][N] by bucketed query position
   int32_t* slotinfo;   // [HQ][N][r] by bucketed query position: cluster | retrieved-block mask << 16
   uint32_t* pairmask;  // [HQ][nb-1][W][N]
-  int32_t *pair_cnt, *pair_off;  // inverse index of the retrieval: (kv head, key block, key cluster) -> hits
+  int32_t* pair_off;             // inverse index of the retrieval: (kv head, key block, key cluster) -> hits
+  int32_t *seg_cnt, *seg_off;    // its construction: counts / offsets per (pair, head of the group, query slice)
   uint2* hits;                   // x = n | g << 22 (query position, head inside the KV group), y = slot*k2e + u
   size_t hit_cap;                // hits per kv head
   float* ret_part;               // per (query, slot, u): forward partial state [acc D | max | sum | pad2], or dq partial [D]
@@ -160,7 +163,8 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
              ff_al(HQ * ((size_t)d.nb * d.Cq + 1) * 4) + ff_al(HQ * d.nb * ((size_t)d.Cq + 1) * 4) +
              2 * ff_al(HK * N * D * es) + ff_al(HQ * N * (D + 2) * 4);
   // inverse index of the retrieval and its per-(query, slot) partial results
-  b += ff_al(HQ * N * W * 4 * NBm) + 2 * ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) + ff_al(HQ * N * R2 * 8) +
+  b += ff_al(HQ * N * W * 4 * NBm) + ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) +
+       2 * ff_al(HK * ((size_t)d.nb * d.Ck * (d.Hq / d.Hkv) * kHitSeg + 1) * 4) + ff_al(HQ * N * R2 * 8) +
        ff_al(HQ * N * R2 * (D + 4) * 4);
   if (bwd) {
     b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + ff_al(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * 4) + 2 * ff_al(HK * N * D * 4);

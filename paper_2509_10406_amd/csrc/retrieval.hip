@@ -25,47 +25,69 @@ __global__ void __launch_bounds__(256) k_pairmask(const int32_t* __restrict__ se
   }
 }
 
-// Pass 1 (FILL = false) counts the hits of every pair, k_pair_scan turns counts into offsets, pass 2
-// (FILL = true) writes the lists in order.  One wave per (key block b', tile of 32 clusters).
+// Pass 1 (FILL = false) counts the hits of every (pair, head of the group, slice of the query range),
+// k_pair_scan turns the counts into offsets (pair-major, then head, then slice: the order of the lists),
+// pass 2 (FILL = true) writes the lists.  One wave per (key block b', tile of 32 clusters, head, slice);
+// lane jl keeps the running offset of cluster 32 jt + jl in a register.
 template <bool FILL>
-__global__ void __launch_bounds__(64) k_pair_hits(const uint32_t* __restrict__ pmask, const int32_t* __restrict__ selc,
-                                                   const int32_t* __restrict__ selb, int32_t* __restrict__ pair_cnt,
-                                                   const int32_t* __restrict__ pair_off, uint2* __restrict__ hits,
-                                                   size_t hit_cap, int N, int Bs, int nb, int Ck, int r, int k2e, int Hq,
-                                                   int Hkv) {
-  __shared__ int cur[32];
-  const int jt = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
-  const int G_ = Hq / Hkv, W = (Ck + 31) / 32;
-  const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
+__global__ void __launch_bounds__(64) k_pair_hits(const uint32_t* __restrict__ pmask, int32_t* __restrict__ seg_cnt,
+                                                   const int32_t* __restrict__ seg_off, uint2* __restrict__ hits,
+                                                   size_t hit_cap, int N, int Bs, int nb, int Ck, int Hq, int Hkv) {
+  const int jt = blockIdx.x, bp = blockIdx.y, NBm = nb - 1;
+  const int G_ = Hq / Hkv, W = (Ck + 31) / 32, SEGT = G_ * kHitSeg;
+  const int hk = blockIdx.z / SEGT, gs = blockIdx.z % SEGT, g = gs / kHitSeg, sg = gs % kHitSeg;
+  const size_t hq = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_ + g;
   const int lane = threadIdx.x;
-  const size_t pbase = (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + jt * 32;
-  if (lane < 32) cur[lane] = (FILL && jt * 32 + lane < Ck) ? pair_off[pbase + lane] : 0;
-  __syncthreads();
-  for (int g = 0; g < G_; ++g) {
-    const size_t hq = hqbase + g;
-    const uint32_t* colw = pmask + ((hq * NBm + bp) * W + jt) * N;
-    for (int n0 = (bp + 1) * Bs; n0 < N; n0 += 64) {
-      const int n = n0 + lane;
-      const uint32_t word = n < N ? colw[n] : 0u;
-      if (!__ballot(word != 0u)) continue;
-      for (int jl = 0; jl < 32; ++jl) {
+  const int nlo = (bp + 1) * Bs;
+  const int per = ((N - nlo + kHitSeg * 64 - 1) / (kHitSeg * 64)) * 64;  // queries per slice, a multiple of 64
+  const int nbeg = nlo + sg * per, nend = nbeg + per < N ? nbeg + per : N;
+  const size_t sbase = (size_t)hk * ((size_t)NBm * Ck * SEGT + 1);
+  const int jmine = jt * 32 + (lane & 31);
+  const size_t sidx = sbase + ((size_t)bp * Ck + jmine) * SEGT + gs;
+  int curv = (FILL && lane < 32 && jmine < Ck) ? seg_off[sidx] : 0;
+  const uint32_t* colw = pmask + ((hq * NBm + bp) * W + jt) * N;
+  for (int n0 = nbeg; n0 < nend; n0 += 256) {
+    uint32_t words[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int n = n0 + 64 * u + lane;
+      words[u] = n < nend ? colw[n] : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t word = words[u];
+      unsigned long long nz = __ballot(word != 0u);
+      uint32_t U = 0;  // clusters present in this chunk
+      while (nz) {
+        const int src = __ffsll((long long)nz) - 1;
+        nz &= nz - 1;
+        U |= (uint32_t)__builtin_amdgcn_readlane((int)word, src);
+      }
+      while (U) {
+        const int jl = __ffs((int)U) - 1;
+        U &= U - 1;
         const bool has = (word >> jl) & 1u;
         const unsigned long long bal = __ballot(has);
-        if (!bal) continue;
-        const int base = cur[jl];
+        const int base = __shfl(curv, jl, 64);
         if (FILL && has) {
           const int rank = __popcll(bal & ((1ull << lane) - 1ull));
           // y holds the pair for now; k_hit_slots replaces it with the query's slot index
           hits[(size_t)hk * hit_cap + base + rank] =
-              make_uint2((uint32_t)n | ((uint32_t)g << 22), (uint32_t)(bp * Ck + jt * 32 + jl));
+              make_uint2((uint32_t)(n0 + 64 * u + lane) | ((uint32_t)g << 22), (uint32_t)(bp * Ck + jt * 32 + jl));
         }
-        __syncthreads();
-        if (lane == 0) cur[jl] = base + __popcll(bal);
-        __syncthreads();
+        if (lane == jl) curv += __popcll(bal);
       }
     }
   }
-  if (!FILL && lane < 32 && jt * 32 + lane < Ck) pair_cnt[pbase + lane] = cur[lane];
+  if (!FILL && lane < 32 && jmine < Ck) seg_cnt[sidx] = curv;
+}
+
+// pair_off[hk][p] = seg_off[hk][p * SEGT]: where the list of pair p starts (p = npair: the total)
+__global__ void __launch_bounds__(256) k_pair_offsets(const int32_t* __restrict__ seg_off, int32_t* __restrict__ pair_off,
+                                                       int npair, int SEGT) {
+  const int hk = blockIdx.y, p = blockIdx.x * 256 + threadIdx.x;
+  if (p > npair) return;
+  pair_off[(size_t)hk * (npair + 1) + p] = seg_off[(size_t)hk * ((size_t)npair * SEGT + 1) + (size_t)p * SEGT];
 }
 
 // hits[].y: pair id -> slot*k2e + u of that pair in the query's exported selections (one thread per hit)
@@ -161,10 +183,12 @@ int muse_ff_build_inverse_index(const MuseDims& d, const int32_t* selc, const in
   { MuseProf prof_("k_pairmask", st); hipLaunchKernelGGL(k_pairmask, dim3((unsigned)((nq * d.r + 255) / 256)), dim3(256), 0, st, selc, selb, w.pairmask, HQ, N, d.r, d.k2e, NBm, W); }
   MUSE_LAUNCH_CHECK();
   if (!with_hits) return MUSE_OK;
-  dim3 g(W, NBm, HK);
-  { MuseProf prof_("k_pair_hits", st); hipLaunchKernelGGL(k_pair_hits<false>, g, dim3(64), 0, st, w.pairmask, selc, selb, w.pair_cnt, w.pair_off, w.hits, w.hit_cap, N, d.Bs, d.nb, d.Ck, d.r, d.k2e, d.Hq, d.Hkv); }
-  { MuseProf prof_("k_pair_scan", st); hipLaunchKernelGGL(k_pair_scan, dim3(HK), dim3(1024), 0, st, w.pair_cnt, w.pair_off, NBm * d.Ck); }
-  { MuseProf prof_("k_pair_hits", st); hipLaunchKernelGGL(k_pair_hits<true>, g, dim3(64), 0, st, w.pairmask, selc, selb, w.pair_cnt, w.pair_off, w.hits, w.hit_cap, N, d.Bs, d.nb, d.Ck, d.r, d.k2e, d.Hq, d.Hkv); }
+  const int SEGT = (d.Hq / d.Hkv) * kHitSeg, npair = NBm * d.Ck;
+  dim3 g(W, NBm, HK * SEGT);
+  { MuseProf prof_("k_pair_hits", st); hipLaunchKernelGGL(k_pair_hits<false>, g, dim3(64), 0, st, w.pairmask, w.seg_cnt, w.seg_off, w.hits, w.hit_cap, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv); }
+  { MuseProf prof_("k_pair_scan", st); hipLaunchKernelGGL(k_pair_scan, dim3(HK), dim3(1024), 0, st, w.seg_cnt, w.seg_off, npair * SEGT); }
+  { MuseProf prof_("k_pair_offsets", st); hipLaunchKernelGGL(k_pair_offsets, dim3((npair + 256) / 256, HK), dim3(256), 0, st, w.seg_off, w.pair_off, npair, SEGT); }
+  { MuseProf prof_("k_pair_hits", st); hipLaunchKernelGGL(k_pair_hits<true>, g, dim3(64), 0, st, w.pairmask, w.seg_cnt, w.seg_off, w.hits, w.hit_cap, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv); }
   {
     dim3 gh((unsigned)((w.hit_cap + 255) / 256), HK);
     { MuseProf prof_("k_hit_slots", st); hipLaunchKernelGGL(k_hit_slots, gh, dim3(256), 0, st, selc, selb, w.pair_off, w.hits, w.hit_cap, NBm * d.Ck, N, d.Ck, d.r, d.k2e, d.Hq, d.Hkv); }
