@@ -86,14 +86,18 @@ __global__ void __launch_bounds__(256) k_assign_f32(const float* __restrict__ X,
 // ------------------------------------------------------------------------------------------
 // assignment, bf16 inputs: S^T = Chat X^T on MFMA, accumulator preloaded with -||c||^2/2, so the
 // nearest centroid is the row-argmax.  Each wave owns PT tiles of 32 points (one point per lane
-// column, two lane halves hold different centroid rows).
+// column, two lane halves hold different centroid rows).  The four waves of a block share the
+// centroids: chunks of CCH rows go through LDS (two buffers, the next chunk's loads are in flight
+// while this one is scored), so the inner loop has no global-memory round trip.
 // ------------------------------------------------------------------------------------------
 template <int D, int PT>
-__global__ void __launch_bounds__(256) k_assign_bf16(const bf16_t* __restrict__ X,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2))) k_assign_bf16(const bf16_t* __restrict__ X,
                                                       const bf16_t* __restrict__ chat,
                                                       const float* __restrict__ nhc2,
                                                       int32_t* __restrict__ assign, int N, int C) {
-  constexpr int KS = D / 16;
+  constexpr int KS = D / 16, CCH = 8192 / D, CPR = D / 8, NLD = CCH * CPR / 256;
+  __shared__ __attribute__((aligned(16))) bf16_t cs[2][CCH][D + 8];
+  __shared__ __attribute__((aligned(16))) float c2s[2][CCH];
   const int h = blockIdx.y;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
   const int col = lane % 32, half = lane / 32;
@@ -118,34 +122,58 @@ __global__ void __launch_bounds__(256) k_assign_bf16(const bf16_t* __restrict__ 
 #pragma unroll
     for (int e = 0; e < 16; ++e) { best[t][e] = MUSE_NEG_INF; btile[t][e] = 0; }
 
-  const int ntile = (C + 31) / 32;
-  for (int ct = 0; ct < ntile; ++ct) {
-    int j = ct * 32 + col;
-    int jc = j < C ? j : C - 1;
-    bf16x8_t ca[KS];
+  uint4 stg[NLD];
+  float stg2 = MUSE_NEG_INF;
+  auto load_chunk = [&](int c0) {  // this thread's share of rows c0 .. c0+CCH-1 (zero rows / -inf past C)
 #pragma unroll
-    for (int s = 0; s < KS; ++s)
-      ca[s] = *reinterpret_cast<const bf16x8_t*>(Ch + (size_t)jc * D + 16 * s + 8 * half);
-    f32x16_t init;
+    for (int u = 0; u < NLD; ++u) {
+      const int c = threadIdx.x + 256 * u, row = c / CPR, cc = c % CPR;
+      stg[u] = c0 + row < C ? *reinterpret_cast<const uint4*>(Ch + (size_t)(c0 + row) * D + cc * 8) : make_uint4(0u, 0u, 0u, 0u);
+    }
+    if (threadIdx.x < CCH) stg2 = c0 + (int)threadIdx.x < C ? c2h[c0 + threadIdx.x] : MUSE_NEG_INF;
+  };
+  auto store_chunk = [&](int buf) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g)
+    for (int u = 0; u < NLD; ++u) {
+      const int c = threadIdx.x + 256 * u, row = c / CPR, cc = c % CPR;
+      *reinterpret_cast<uint4*>(&cs[buf][row][cc * 8]) = stg[u];
+    }
+    if (threadIdx.x < CCH) c2s[buf][threadIdx.x] = stg2;
+  };
+  const int nch = (C + CCH - 1) / CCH;
+  load_chunk(0);
+  store_chunk(0);
+  __syncthreads();
+  for (int ch = 0; ch < nch; ++ch) {
+    const int buf = ch & 1;
+    if (ch + 1 < nch) load_chunk((ch + 1) * CCH);
+#pragma unroll 2
+    for (int ct = 0; ct < CCH / 32; ++ct) {
+      bf16x8_t ca[KS];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        int jr = ct * 32 + 8 * g + 4 * half + u;
-        init[4 * g + u] = jr < C ? c2h[jr] : MUSE_NEG_INF;
+      for (int s = 0; s < KS; ++s) ca[s] = *reinterpret_cast<const bf16x8_t*>(&cs[buf][ct * 32 + col][16 * s + 8 * half]);
+      f32x16_t init;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 c4 = *reinterpret_cast<const float4*>(&c2s[buf][ct * 32 + 8 * g + 4 * half]);
+        init[4 * g] = c4.x; init[4 * g + 1] = c4.y; init[4 * g + 2] = c4.z; init[4 * g + 3] = c4.w;
       }
+      const int gt_ = ch * (CCH / 32) + ct;  // global centroid tile
 #pragma unroll
-    for (int t = 0; t < PT; ++t) {
-      f32x16_t acc = init;
+      for (int t = 0; t < PT; ++t) {
+        f32x16_t acc = init;
 #pragma unroll
-      for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[s], xb[t][s], acc, 0, 0, 0);
+        for (int s = 0; s < KS; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[s], xb[t][s], acc, 0, 0, 0);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        bool gt = acc[e] > best[t][e];
-        best[t][e] = gt ? acc[e] : best[t][e];
-        btile[t][e] = gt ? ct : btile[t][e];
+        for (int e = 0; e < 16; ++e) {
+          bool gt = acc[e] > best[t][e];
+          best[t][e] = gt ? acc[e] : best[t][e];
+          btile[t][e] = gt ? gt_ : btile[t][e];
+        }
       }
     }
+    if (ch + 1 < nch) store_chunk(buf ^ 1);
+    __syncthreads();
   }
 #pragma unroll
   for (int t = 0; t < PT; ++t) {
