@@ -91,7 +91,7 @@ __global__ void __launch_bounds__(256) k_assign_f32(const float* __restrict__ X,
 // while this one is scored), so the inner loop has no global-memory round trip.
 // ------------------------------------------------------------------------------------------
 template <int D, int PT>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2))) k_assign_bf16(const bf16_t* __restrict__ X,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, 2))) k_assign_bf16(const bf16_t* __restrict__ X,
                                                       const bf16_t* __restrict__ chat,
                                                       const float* __restrict__ nhc2,
                                                       int32_t* __restrict__ assign, int N, int C) {
