@@ -20,15 +20,6 @@ constexpr int BN = 64;  // rows staged in LDS per step
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// A operand for the second contraction from a transposed LDS tile `row` ([..][BN+8]): the 8 k-slots
-// of lane half `half` over the 16 rows starting at r0
-__device__ __forceinline__ bf16x8_t ld_tr8(const bf16_t* row, int r0, int half) {
-  uint2 a = *reinterpret_cast<const uint2*>(row + r0 + 4 * half);
-  uint2 b = *reinterpret_cast<const uint2*>(row + r0 + 8 + 4 * half);
-  uint4 v = make_uint4(a.x, a.y, b.x, b.y);
-  return *reinterpret_cast<bf16x8_t*>(&v);
-}
-
 // cooperative load of `rows` x D bf16 into a row-major tile (pad 8) and optionally a transposed one
 template <int D, int ROWS, bool ROWM, bool TRANS>
 __device__ __forceinline__ void load_tile(const bf16_t* __restrict__ src, int r0, int N,

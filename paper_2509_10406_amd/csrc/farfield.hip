@@ -234,8 +234,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
     const int32_t* __restrict__ tile_off, float* __restrict__ ff_acc, float* __restrict__ ff_ml,
     int32_t* __restrict__ selc, int h0, int N, int nb, int Cq, int Ck, int r, float scale) {
   constexpr int U = D / 8, DT = D / 32;
-  // output tile x, row m holds head dim DT*m + x: a lane reads DT consecutive dims of a value row at once
+  // fp32 inputs: output tile x, row m holds head dim DT*m + x (a lane reads DT consecutive dims of a value row)
   using VF = Frag<T, DT>;
+  constexpr bool kH = sizeof(T) == 2;  // bf16 inputs: P V on bf16 MFMA through a transposed value tile in LDS
+  constexpr int CPR = D / 8, NIT = 32 * CPR / 64;
+  __shared__ __attribute__((aligned(16))) bf16_t vt[kH ? D : 1][32 + 8];
   __shared__ float cs[64][RCAP];
   __shared__ int ci[64][RCAP];
   __shared__ int sel_s[32][RCAP];
@@ -340,12 +343,22 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
     // all loads of the tile first: k-bar rows, mu-bar, and the DT consecutive dims DT*col .. of the 16 value rows
     KTile<D> kt;
     load_ktile<D>(kt, Amu, Ak, j0, Ck, col, half);
-    typename VF::raw vv[16];
+    typename VF::raw vv[kH ? 1 : 16];
+    uint4 vch[kH ? NIT : 1];
+    if constexpr (kH) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
-      jr = jr < Ck ? jr : Ck - 1;
-      vv[e] = VF::ld(Av, (size_t)jr * D + DT * col);
+      for (int it = 0; it < NIT; ++it) {
+        const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+        const int jr = j0 + row < Ck ? j0 + row : Ck - 1;
+        vch[it] = *reinterpret_cast<const uint4*>(Av + (size_t)jr * D + cc * 8);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+        jr = jr < Ck ? jr : Ck - 1;
+        vv[e] = VF::ld(Av, (size_t)jr * D + DT * col);
+      }
     }
     f32x16_t acc = score_ktile<D>(kt, j0, Ck, qt, half);
     float tmax = MUSE_NEG_INF;
@@ -380,10 +393,29 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
     for (int t = 0; t < DT; ++t)
 #pragma unroll
       for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+    if constexpr (kH) {
+      wave_lds_fence();
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
+      for (int it = 0; it < NIT; ++it) {
+        const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+        const bf16_t* pv = reinterpret_cast<const bf16_t*>(&vch[it]);
 #pragma unroll
-      for (int x = 0; x < DT; ++x) o[x] = mfma32(VF::get(vv[e], x), acc[e], o[x]);
+        for (int e = 0; e < 8; ++e) vt[cc * 8 + e][row] = pv[e];
+      }
+      wave_lds_fence();
+#pragma unroll
+      for (int G = 0; G < 2; ++G) {
+        const bf16x8_t pf = pack8(acc, 2 * G, 2 * G + 1);
+#pragma unroll
+        for (int x = 0; x < DT; ++x)
+          o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_tr8(&vt[32 * x + col][0], 16 * G, half), pf, o[x], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+#pragma unroll
+        for (int x = 0; x < DT; ++x) o[x] = mfma32(VF::get(vv[e], x), acc[e], o[x]);
+      }
     }
   }
   // ---- order the selected clusters of each query by (score desc, index asc) ----
@@ -412,7 +444,12 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
   float* fa = ff_acc + ((size_t)hq * N + n) * D;
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
-    if (DT == 2) {
+    if (kH) {  // output tile x, row m holds head dim 32 x + m
+#pragma unroll
+      for (int x = 0; x < DT; ++x)
+        *reinterpret_cast<float4*>(fa + 32 * x + 8 * g + 4 * half) =
+            make_float4(o[x][4 * g], o[x][4 * g + 1], o[x][4 * g + 2], o[x][4 * g + 3]);
+    } else if (DT == 2) {
 #pragma unroll
       for (int tp = 0; tp < 2; ++tp)
         *reinterpret_cast<float4*>(fa + 2 * (8 * g + 4 * half + 2 * tp)) =

@@ -111,6 +111,15 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& s, int g0, int g1) {
   return r;
 }
 
+// A operand for the second contraction from a transposed LDS tile `row` ([..][BN+8]): the 8 k-slots
+// of lane half `half` over the 16 rows starting at r0
+__device__ __forceinline__ bf16x8_t ld_tr8(const bf16_t* row, int r0, int half) {
+  uint2 a = *reinterpret_cast<const uint2*>(row + r0 + 4 * half);
+  uint2 b = *reinterpret_cast<const uint2*>(row + r0 + 8 + 4 * half);
+  uint4 v = make_uint4(a.x, a.y, b.x, b.y);
+  return *reinterpret_cast<bf16x8_t*>(&v);
+}
+
 __device__ __forceinline__ __bf16 bits_to_bf16(bf16_t b) { return __builtin_bit_cast(__bf16, b); }
 
 __device__ __forceinline__ bf16x8_t cvt8(const float* __restrict__ p) {
