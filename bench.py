@@ -32,8 +32,9 @@ def kernel_models(w, p):
     k2e = w.k2 if w.k2 > 0 else max(nb - 1, 1)
     Nff = N * (nb - 1) // nb           # queries that have a far field / keys that are summarised
     cells = (nb - 1) * Cq * Ck
-    cellb = cells * (2 * D + 1) * 4    # bytes of one copy of the summaries tensor (mu, k-bar, v-bar), one head
-    es = 2 if w.dtype == "bf16" else 4
+    es = 2 if w.dtype == "bf16" else 4   # storage type of inputs, value summaries and cell gradients
+    cell_kv = cells * D * (4 + es) + cells * 4   # one copy of the summaries: k-bar fp32, v-bar, mu-bar
+    cell_g = cells * 2 * D * es + cells * 4      # one copy of the cell gradients (k, v, scalar)
     far = "mfma_bf16" if w.dtype == "bf16" else "mfma_fp32"   # gradient contractions of the far field
     pair_keys = Nff * r * k2e * (Bs / Ck)                     # (query, retrieved pair) x keys of an average pair
     m = {}
@@ -51,10 +52,12 @@ def kernel_models(w, p):
     m["k_ret_fwd_pairs"] = ("mfma", PEAK["mfma_bf16"], 2 * 2 * pair_keys * D * H, "flop")
     m["k_ret_bwd_dq_pairs"] = ("mfma", PEAK["mfma_bf16"], 3 * 2 * pair_keys * D * H, "flop")
     m["k_c3_pairs"] = ("mfma", PEAK["mfma_bf16"], 4 * 2 * pair_keys * D * H, "flop")
-    # writes both copies of the summaries (per block, accumulated); reads the tilt logits and K, V once
-    m["k_summaries"] = ("hbm", PEAK["hbm"], (2 * cellb + Cq * Nff * 4 + 2 * Nff * D * es) * H, "byte")
+    # writes both copies of the summaries (per block, accumulated) and, for bf16 inputs, the bf16 copy of the
+    # accumulated k-bar; reads the tilt logits and K, V once
+    m["k_summaries"] = ("hbm", PEAK["hbm"], (2 * cell_kv + (cells * D * 2 if es == 2 else 0) + Cq * Nff * 4
+                                              + 2 * Nff * D * es) * H, "byte")
     # reads the gradients of the accumulated cells and mu of both copies, writes the gradients of the per-block cells
-    m["k_cell_grads"] = ("hbm", PEAK["hbm"], (2 * cellb + 2 * cells * 4) * H, "byte")
+    m["k_cell_grads"] = ("hbm", PEAK["hbm"], (2 * cell_g + 2 * cells * 4) * H, "byte")
     m["k_tilt_logits"] = ("hbm", PEAK["hbm"], (Cq * N * 4 + N * D * es) * H, "byte")
     return m
 
