@@ -560,8 +560,19 @@ __global__ void __launch_bounds__(256) k_cell_grads(
       load_qin(ch, qin);
     }
     // -- chain lists: counting sort of the (query, chain) hits by chain, stable in the bucketed order
-#pragma unroll 4
-    for (int c = 0; c < 32; ++c) {
+    // the chains present in this wave's 64 queries (typically a handful of the 32): only those are ranked
+    uint32_t present = 0;
+    {
+      unsigned long long nz = __ballot(qin.word != 0u);
+      while (nz) {
+        const int src = __ffsll((long long)nz) - 1;
+        nz &= nz - 1;
+        present |= (uint32_t)__builtin_amdgcn_readlane((int)qin.word, src);
+      }
+    }
+    if (lane < 32) cnt[wave][lane] = 0;
+    for (uint32_t u = present; u; u &= u - 1) {
+      const int c = __ffs((int)u) - 1;
       const unsigned long long bal = __ballot((qin.word >> c) & 1u);
       if (lane == 0) cnt[wave][c] = __popcll(bal);
     }
@@ -583,10 +594,10 @@ __global__ void __launch_bounds__(256) k_cell_grads(
       for (int w_ = 0; w_ < 4; ++w_) wbase[w_][tid] = cnt[w_][tid] + excl;
     }
     __syncthreads();
-    if (__ballot(qin.word != 0) != 0ull) {
+    {
       const int bq = qin.pq / Bs;  // bucketed order is block-major
-#pragma unroll 4
-      for (int c = 0; c < 32; ++c) {
+      for (uint32_t u = present; u; u &= u - 1) {
+        const int c = __ffs((int)u) - 1;
         const bool bit = (qin.word >> c) & 1u;
         const unsigned long long bal = __ballot(bit);
         if (bit) {
