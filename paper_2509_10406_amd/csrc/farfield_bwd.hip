@@ -516,11 +516,17 @@ __global__ void __launch_bounds__(256) k_cell_grads(
         st.gav[x] = F4::ld(g_A_v, cell * D + 32 * x + 4 * l8);
       }
     };
-    Step cur, nxt;
-    load_step(NBm - 1, cur);
-    for (int a = NBm - 1; a >= 0; --a) {
-      if (a > 0) load_step(a - 1, nxt);
-      if (jok) {
+    // the loads of up to 8 steps are issued together: the recurrence itself is a few multiply-adds per step
+    for (int a1 = NBm - 1; a1 >= 0; a1 -= 8) {
+      Step st[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (a1 - u >= 0) load_step(a1 - u, st[u]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int a = a1 - u;
+        if (a < 0 || !jok) continue;
+        const Step& cur = st[u];
         const size_t cell = (((size_t)hl * NBm + a) * Cq + i) * Ck + jown;
         const float f = (a < NBm - 1 && cur.Am > MUSE_NEG_INF) ? __expf(cur.Am - an) : 0.f;
         const float wgt = cur.mu > MUSE_NEG_INF ? __expf(cur.mu - cur.Am) : 0.f;
@@ -541,7 +547,6 @@ __global__ void __launch_bounds__(256) k_cell_grads(
           st4(G_v, cell * D + 32 * x + 4 * l8, ov4);
         }
       }
-      cur = nxt;
     }
   }
   if (nchunks == 0) return;
