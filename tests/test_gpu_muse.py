@@ -30,6 +30,9 @@ CASES = {
     "cfg5_d128": ("cfg5", dict(N=1024, Hq=2, Hkv=1, Cq=8, Ck=33, r=9, block=128, kmeans_iters=2)),
     "bf16_one_block": ("cfg2", dict(N=512, Hq=1, Hkv=1, Cq=4, Ck=8, r=2, block=512, kmeans_iters=1)),
     "bf16_r17": ("cfg2", dict(N=1024, Hq=1, Hkv=1, Cq=4, Ck=70, r=17, block=128, kmeans_iters=1)),
+    # more than 8 preceding blocks: the second chunk of the block loops
+    "bf16_nb16_k2_2": ("cfg2", dict(N=2048, Hq=2, Hkv=1, Cq=8, Ck=32, r=3, k2=2, block=128, kmeans_iters=2)),
+    "fp32_nb12": ("cfg1", dict(N=1536, Cq=6, Ck=24, r=2, block=128, kmeans_iters=2)),
 }
 
 
