@@ -212,8 +212,8 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
         for (int x = 0; x < DT; ++x) dq[x] = mfma32(krow[32 * x], s[4 * g + t], dq[x]);
       }
   }
-  // components 2 and 3
-  for (int t = 0; t < r; ++t) {
+  // components 2 and 3 (fp32 inputs; bf16 inputs take them in the per-query and per-pair kernels)
+  for (int t = 0; t < (sizeof(T) == 4 ? r : 0); ++t) {
     const int j = selc[qn * r + t];
     if (j < 0) continue;
     unsigned selbits = 0;
@@ -283,21 +283,128 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
   for (int u = 0; u < U; ++u)
 #pragma unroll
     for (int x = 0; x < 4; ++x) res[u][x] = scale * dq[u / 4][4 * (u % 4) + x];
-  if (sizeof(T) == 2) {  // retrieval part, computed per retrieved pair (already scaled)
-    for (int su = 0; su < r * k2e; ++su) {
-      if (selb[qn * r * k2e + su] < 0) continue;
-      const float* pp = dqpart + (qn * r * k2e + su) * D + 4 * half;
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        float4 v = *reinterpret_cast<const float4*>(pp + 8 * u);
-        res[u][0] += v.x; res[u][1] += v.y; res[u][2] += v.z; res[u][3] += v.w;
-      }
-    }
-  }
   float* out = dQ + qn * D + 4 * half;
 #pragma unroll
   for (int u = 0; u < U; ++u)
     *reinterpret_cast<float4*>(out + 8 * u) = make_float4(res[u][0], res[u][1], res[u][2], res[u][3]);
+}
+
+// ------------------------------------------------------------------------------------------
+// dQ of component 2 for bf16 inputs, per query (16 lanes, dims 64 x + 4 l16 + t, bucketed order, as in the
+// forward): for every retrieved cluster, the summaries of the preceding blocks that were NOT retrieved
+// contribute  dl k-bar  with  dl = p (dO.v-bar - delta),  p = exp(q~.k-bar + mu-bar - LSE).  The retrieval's
+// per-pair dq partials are added here too, and the sum is added to the row the tile kernel wrote.
+// ------------------------------------------------------------------------------------------
+template <int D, int NBC>
+__global__ void __launch_bounds__(256) k_comp2_bwd_dq(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO, const float* __restrict__ qc,
+    const float* __restrict__ s_mu, const float* __restrict__ s_k, const bf16_t* __restrict__ s_v,
+    const int32_t* __restrict__ perm_q, const int32_t* __restrict__ aq, const float* __restrict__ LSE,
+    const float* __restrict__ delta, const int32_t* __restrict__ slotinfo, const float* __restrict__ dqpart,
+    float* __restrict__ dQ, int h0, int N, int nb, int Bs, int Cq, int Ck, int r, int k2e, float scale) {
+  constexpr int NG = D / 64;
+  const int hl = blockIdx.y, hq = h0 + hl;
+  const int l16 = threadIdx.x % 16;
+  const int pos = Bs + blockIdx.x * 16 + threadIdx.x / 16;  // bucketed order is block-major: block 0 comes first
+  if (pos >= N) return;
+  const int n = perm_q[(size_t)hq * N + pos];
+  const size_t qn = (size_t)hq * N + n;
+  const int b = pos / Bs, NBm = nb - 1;
+  const int i = aq[qn];
+  const float lse = LSE[qn], dl = delta[qn];
+  float qt[NG][4], gt[NG][4], dq[NG][4];
+#pragma unroll
+  for (int x = 0; x < NG; ++x) {
+    float q4[4];
+    ld4(Q, qn * D + 64 * x + 4 * l16, q4);
+    ld4(dO, qn * D + 64 * x + 4 * l16, gt[x]);
+    const float4 c4 = *reinterpret_cast<const float4*>(qc + ((size_t)hq * Cq + i) * D + 64 * x + 4 * l16);
+    qt[x][0] = scale * (q4[0] - c4.x); qt[x][1] = scale * (q4[1] - c4.y);
+    qt[x][2] = scale * (q4[2] - c4.z); qt[x][3] = scale * (q4[3] - c4.w);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) dq[x][t] = 0.f;
+  }
+  const int32_t* si = slotinfo + ((size_t)hq * N + pos) * r;
+  for (int t = 0; t < r; ++t) {
+    const int info = si[t];
+    if (info < 0) continue;
+    const int j = info & 0xffff;
+    const unsigned selbits = (unsigned)info >> 16;
+#pragma unroll
+    for (int c0 = 0; c0 < 8 * NBC; c0 += 8) {
+      if (c0 >= b) break;
+      float mu[8], part[8], dpp[8];
+      float4 kr[8][NG];
+      float vr[8][NG][4];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int bp = c0 + u < b ? c0 + u : b - 1;
+        const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
+        mu[u] = s_mu[cell];
+#pragma unroll
+        for (int x = 0; x < NG; ++x) {
+          kr[u][x] = *reinterpret_cast<const float4*>(s_k + cell * D + 64 * x + 4 * l16);
+          ld4(s_v, cell * D + 64 * x + 4 * l16, vr[u][x]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        float pa = 0.f, pd = 0.f;
+#pragma unroll
+        for (int x = 0; x < NG; ++x) {
+          pa = fmaf(qt[x][0], kr[u][x].x, pa); pa = fmaf(qt[x][1], kr[u][x].y, pa);
+          pa = fmaf(qt[x][2], kr[u][x].z, pa); pa = fmaf(qt[x][3], kr[u][x].w, pa);
+          pd = fmaf(gt[x][0], vr[u][x][0], pd); pd = fmaf(gt[x][1], vr[u][x][1], pd);
+          pd = fmaf(gt[x][2], vr[u][x][2], pd); pd = fmaf(gt[x][3], vr[u][x][3], pd);
+        }
+        part[u] = pa; dpp[u] = pd;
+      }
+#pragma unroll
+      for (int sh = 1; sh < 16; sh <<= 1)
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          part[u] += __shfl_xor(part[u], sh, 64);
+          dpp[u] += __shfl_xor(dpp[u], sh, 64);
+        }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const bool use = c0 + u < b && mu[u] > MUSE_NEG_INF && !((selbits >> (c0 + u)) & 1u);
+        const float p = use ? __expf(part[u] + mu[u] - lse) : 0.f;
+        const float dlg = p * (dpp[u] - dl);
+#pragma unroll
+        for (int x = 0; x < NG; ++x) {
+          dq[x][0] = fmaf(dlg, kr[u][x].x, dq[x][0]); dq[x][1] = fmaf(dlg, kr[u][x].y, dq[x][1]);
+          dq[x][2] = fmaf(dlg, kr[u][x].z, dq[x][2]); dq[x][3] = fmaf(dlg, kr[u][x].w, dq[x][3]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int x = 0; x < NG; ++x)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) dq[x][t] *= scale;
+  // retrieval part, computed per retrieved pair (already scaled); a slot's pair u exists iff its block bit is set
+  for (int t = 0; t < r; ++t) {
+    const int info = si[t];
+    if (info < 0 || ((unsigned)info >> 16) == 0u) continue;
+    for (int u = 0; u < k2e; ++u) {
+      const float* pp = dqpart + (qn * r * k2e + t * k2e + u) * D;
+      if (u < __popc((unsigned)info >> 16)) {
+#pragma unroll
+        for (int x = 0; x < NG; ++x) {
+          const float4 v = *reinterpret_cast<const float4*>(pp + 64 * x + 4 * l16);
+          dq[x][0] += v.x; dq[x][1] += v.y; dq[x][2] += v.z; dq[x][3] += v.w;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int x = 0; x < NG; ++x) {
+    float4* out = reinterpret_cast<float4*>(dQ + qn * D + 64 * x + 4 * l16);
+    float4 o = *out;
+    o.x += dq[x][0]; o.y += dq[x][1]; o.z += dq[x][2]; o.w += dq[x][3];
+    *out = o;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -992,14 +1099,23 @@ __global__ void __launch_bounds__(256) k_scatter_rows(const float* __restrict__ 
 }
 
 template <typename T, int D>
-int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, const float* LSE, const int32_t* selc,
-                  const int32_t* selb, FFWorkspace& w, int h0, int hn, hipStream_t st) {
+int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, const int32_t* aq, const float* LSE,
+                  const int32_t* selc, const int32_t* selb, FFWorkspace& w, int h0, int hn, hipStream_t st) {
   const int NBm = d.nb - 1;
   const int W = (d.Ck + 31) / 32;
   dim3 gt(d.Bs / 32 + d.Cq + 1, NBm, hn);
   { MuseProf prof_("k_ff_bwd_dq", st); hipLaunchKernelGGL((k_ff_bwd_dq<T, D>), gt, dim3(64), 0, st, Q, dO, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu,
                      w.s_k, (const T*)w.s_v, w.A_mu, w.A_k, (const T*)w.A_v, (const bf16_t*)w.A_kb, w.perm_q, w.off_q, w.off_k, w.tile_off, LSE, w.delta,
                      w.selmask, selc, selb, w.ret_part, w.dQacc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
+  if (sizeof(T) == 2 && d.r > 0) {
+    dim3 g2((d.N - d.Bs + 15) / 16, hn);
+    if (d.nb <= 9)
+      { MuseProf prof_("k_comp2_bwd_dq", st); hipLaunchKernelGGL((k_comp2_bwd_dq<D, 1>), g2, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, w.s_mu, w.s_k, (const bf16_t*)w.s_v,
+                         w.perm_q, aq, LSE, w.delta, w.slotinfo, w.ret_part, w.dQacc, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
+    else
+      { MuseProf prof_("k_comp2_bwd_dq", st); hipLaunchKernelGGL((k_comp2_bwd_dq<D, 2>), g2, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, w.s_mu, w.s_k, (const bf16_t*)w.s_v,
+                         w.perm_q, aq, LSE, w.delta, w.slotinfo, w.ret_part, w.dQacc, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
+  }
   if (sizeof(T) == 2) {
     int rc2 = muse_launch_ff_bwd_cells_mx(d, Q, dO, qc, w.A_mu, w.A_kb, w.A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask,
                                           w.g_A_c, w.g_A_k, w.g_A_v, h0, hn, st);
@@ -1070,8 +1186,8 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
     for (int h0 = 0; h0 < HQ; h0 += w.hc) {
       int hn = HQ - h0 < w.hc ? HQ - h0 : w.hc;
       if (!reuse && (rc = muse_ff_summaries<T>(d, qc, w, h0, hn, st))) return rc;
-      if (D == 64) rc = run_bwd_chunk<T, 64>(d, Q, dO, qc, LSE, selc, selb, w, h0, hn, st);
-      else rc = run_bwd_chunk<T, 128>(d, Q, dO, qc, LSE, selc, selb, w, h0, hn, st);
+      if (D == 64) rc = run_bwd_chunk<T, 64>(d, Q, dO, qc, aq, LSE, selc, selb, w, h0, hn, st);
+      else rc = run_bwd_chunk<T, 128>(d, Q, dO, qc, aq, LSE, selc, selb, w, h0, hn, st);
       if (rc) return rc;
     }
   }
