@@ -729,54 +729,55 @@ __global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restric
 // ------------------------------------------------------------------------------------------
 // Gradients of the accumulated cells (component 1) for bf16 inputs: the (b, i) group's queries against
 // a tile of 32 key clusters is a dense attention-backward block with the accumulated summaries in the
-// role of keys and values.  Four waves share the staged query tile, each owns one cluster tile.
+// role of keys and values.  One block per group: its queries (QT tiles of 32 at a time, nearly always
+// all of them) are staged in LDS once, and every wave walks its share of the cluster tiles with the
+// next tile's summaries already in flight.
 //   g_A_k = sum dl q~,  g_A_v = sum p dO,  g_A_c = sum [dl (1 - q~.kbar) - p dO.vbar]
 // Operands are rounded to bf16 for the matrix cores (gradients only; no selection depends on them).
+// A group with more than 32 QT queries takes further passes that add to the rows of the first.
 // ------------------------------------------------------------------------------------------
-template <int D>
-__global__ void __launch_bounds__(256) k_ff_bwd_cells_mx(
+template <int D, int QT>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, 2))) k_ff_bwd_cells_mx(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO, const float* __restrict__ qc,
     const float* __restrict__ A_mu, const bf16_t* __restrict__ A_kb, const bf16_t* __restrict__ A_v,
     const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q, const float* __restrict__ LSE,
     const float* __restrict__ delta, const uint32_t* __restrict__ selmask, float* __restrict__ g_A_c,
     bf16_t* __restrict__ g_A_k, bf16_t* __restrict__ g_A_v, int h0, int N, int nb, int Cq, int Ck, float scale) {
-  constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
-  __shared__ __attribute__((aligned(16))) bf16_t qs[32][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t gs[32][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][32 + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][32 + 8];
-  __shared__ __attribute__((aligned(16))) float ls[32];
-  __shared__ __attribute__((aligned(16))) float ds[32];
-  __shared__ uint32_t mws[4][32];
+  constexpr int KS = D / 16, DT = D / 32, CPR = D / 8, QR = 32 * QT;
+  __shared__ __attribute__((aligned(16))) bf16_t qs[QR][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gs[QR][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][QR + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][QR + 8];
+  __shared__ __attribute__((aligned(16))) float ls[QR];
+  __shared__ __attribute__((aligned(16))) float ds[QR];
+  __shared__ uint32_t mws[4][QR];
+  __shared__ __attribute__((aligned(16))) bf16_t tw[4][32][D + 8];
   const int hl = blockIdx.z, hq = h0 + hl;
   const int NBm = nb - 1, W = (Ck + 31) / 32;
   const int b = blockIdx.y / Cq + 1, i = blockIdx.y % Cq;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
-  const int jt = blockIdx.x * 4 + wave;
-  const bool active = jt < W;
   const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
   const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
   const size_t acell = (((size_t)hl * NBm + (b - 1)) * Cq + i) * Ck;
-  const int jc = jt * 32 + col;
-  const bool jvalid = active && jc < Ck;
-  const int jcc = jvalid ? jc : Ck - 1;
-  bf16x8_t kf[KS], vf[KS];
-#pragma unroll
-  for (int x = 0; x < KS; ++x) {
-    kf[x] = *reinterpret_cast<const bf16x8_t*>(A_kb + (acell + jcc) * D + 16 * x + 8 * half);
-    vf[x] = *reinterpret_cast<const bf16x8_t*>(A_v + (acell + jcc) * D + 16 * x + 8 * half);
-  }
-  const float amu2 = jvalid ? A_mu[acell + jcc] * 1.4426950408889634f : MUSE_NEG_INF;
   const float* qci = qc + ((size_t)hq * Cq + i) * D;
-  f32x16_t gk[DT], gv[DT];
+  struct CT {  // one tile of 32 accumulated summaries as this lane's operand fragments
+    bf16x8_t kf[KS], vf[KS];
+    float amu2;
+  };
+  auto load_ct = [&](int jt, CT& c) {
+    const int jc = jt * 32 + col;
+    const int jcc = jc < Ck ? jc : Ck - 1;
 #pragma unroll
-  for (int t = 0; t < DT; ++t)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) { gk[t][e] = 0.f; gv[t][e] = 0.f; }
-  float csum = 0.f;
-  for (int q0 = qlo; q0 < qhi; q0 += 32) {
+    for (int x = 0; x < KS; ++x) {
+      c.kf[x] = *reinterpret_cast<const bf16x8_t*>(A_kb + (acell + jcc) * D + 16 * x + 8 * half);
+      c.vf[x] = *reinterpret_cast<const bf16x8_t*>(A_v + (acell + jcc) * D + 16 * x + 8 * half);
+    }
+    c.amu2 = jc < Ck ? A_mu[acell + jcc] * 1.4426950408889634f : MUSE_NEG_INF;
+  };
+  for (int q0 = qlo; q0 < qhi || q0 == qlo; q0 += QR) {  // an empty group still writes its (zero) cells
+    const bool first = q0 == qlo;
     __syncthreads();
-    for (int c = threadIdx.x; c < 32 * CPR; c += 256) {
+    for (int c = threadIdx.x; c < (q0 < qhi ? QR * CPR : 0); c += 256) {
       const int row = c / CPR, cc = c % CPR;
       const int pos = q0 + row < qhi ? q0 + row : q0;
       const size_t qn = (size_t)hq * N + perm_q[(size_t)hq * N + pos];
@@ -794,72 +795,114 @@ __global__ void __launch_bounds__(256) k_ff_bwd_cells_mx(
 #pragma unroll
       for (int e = 0; e < 8; ++e) { qt_[cc * 8 + e][row] = qtl[e]; gt_[cc * 8 + e][row] = pg[e]; }
     }
-    if (threadIdx.x < 128) {
-      const int row = threadIdx.x % 32, w2 = threadIdx.x / 32;
+    if (threadIdx.x < QR && q0 < qhi) {
+      const int row = threadIdx.x;
       const bool ok = q0 + row < qhi;
       const size_t qn = (size_t)hq * N + perm_q[(size_t)hq * N + (ok ? q0 + row : q0)];
-      const int jt2 = blockIdx.x * 4 + w2;
-      mws[w2][row] = jt2 < W ? selmask[((size_t)hq * W + jt2) * N + (ok ? q0 + row : q0)] : 0u;
-      if (w2 == 0) {
-        ls[row] = ok ? LSE[qn] * 1.4426950408889634f : __builtin_huge_valf();  // +inf -> p = 0 for padding rows
-        ds[row] = delta[qn];
-      }
+      ls[row] = ok ? LSE[qn] * 1.4426950408889634f : __builtin_huge_valf();  // +inf -> p = 0 for padding rows
+      ds[row] = delta[qn];
     }
     __syncthreads();
-    if (!active) continue;
-    f32x16_t s, dp;
+    const int ntl = (qhi - q0 + 31) / 32 < QT ? (qhi - q0 + 31) / 32 : QT;  // staged query tiles (0 for an empty group)
+    CT cur, nxt;
+    if (wave < W) load_ct(wave, cur);
+    for (int jt = wave; jt < W; jt += 4) {
+      if (jt + 4 < W) load_ct(jt + 4, nxt);
+      // this wave's words of the selection mask: one per staged query, for cluster tile jt
+      for (int rr = lane; rr < 32 * ntl; rr += 64)
+        mws[wave][rr] = selmask[((size_t)hq * W + jt) * N + (q0 + rr < qhi ? q0 + rr : q0)];
+      wave_lds_fence();
+      const int jc = jt * 32 + col;
+      const bool jvalid = jc < Ck;
+      f32x16_t gk[DT], gv[DT];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+      for (int t = 0; t < DT; ++t)
 #pragma unroll
-    for (int x = 0; x < KS; ++x) {
-      bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&qs[col][16 * x + 8 * half]);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[x], s, 0, 0, 0);
-      bf16x8_t ag = *reinterpret_cast<const bf16x8_t*>(&gs[col][16 * x + 8 * half]);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, vf[x], dp, 0, 0, 0);
-    }
-    f32x16_t pr;
+        for (int e = 0; e < 16; ++e) { gk[t][e] = 0.f; gv[t][e] = 0.f; }
+      float csum = 0.f;
+      for (int qt = 0; qt < ntl; ++qt) {
+        f32x16_t s, dp;
 #pragma unroll
-    for (int gq = 0; gq < 4; ++gq) {
-      float4 l4 = *reinterpret_cast<const float4*>(&ls[8 * gq + 4 * half]);
-      float4 d4 = *reinterpret_cast<const float4*>(&ds[8 * gq + 4 * half]);
-      const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int e = 4 * gq + u, row = 8 * gq + 4 * half + u;
-        float p = fast_exp2(fmaf(s[e], 1.4426950408889634f, amu2 - lv[u]));
-        p = ((mws[wave][row] >> col) & 1u) ? 0.f : p;
-        const float dlg = p * (dp[e] - dv4[u]);
-        csum += p > 0.f ? dlg * (1.f - s[e]) - p * dp[e] : 0.f;
-        pr[e] = p;
-        s[e] = dlg;
+        for (int x = 0; x < KS; ++x) {
+          bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&qs[32 * qt + col][16 * x + 8 * half]);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, cur.kf[x], s, 0, 0, 0);
+          bf16x8_t ag = *reinterpret_cast<const bf16x8_t*>(&gs[32 * qt + col][16 * x + 8 * half]);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, cur.vf[x], dp, 0, 0, 0);
+        }
+        f32x16_t pr;
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          float4 l4 = *reinterpret_cast<const float4*>(&ls[32 * qt + 8 * gq + 4 * half]);
+          float4 d4 = *reinterpret_cast<const float4*>(&ds[32 * qt + 8 * gq + 4 * half]);
+          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int e = 4 * gq + u, row = 32 * qt + 8 * gq + 4 * half + u;
+            float p = fast_exp2(fmaf(s[e], 1.4426950408889634f, cur.amu2 - lv[u]));
+            p = ((mws[wave][row] >> col) & 1u) ? 0.f : p;
+            const float dlg = p * (dp[e] - dv4[u]);
+            csum += p > 0.f ? dlg * (1.f - s[e]) - p * dp[e] : 0.f;
+            pr[e] = p;
+            s[e] = dlg;
+          }
+        }
+#pragma unroll
+        for (int G = 0; G < 2; ++G) {
+          bf16x8_t pf = pack8(pr, 2 * G, 2 * G + 1);
+          bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
+#pragma unroll
+          for (int t = 0; t < DT; ++t) {
+            bf16x8_t ag = ld_tr8(&gt_[32 * t + col][0], 32 * qt + 16 * G, half);
+            gv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, pf, gv[t], 0, 0, 0);
+            bf16x8_t aq = ld_tr8(&qt_[32 * t + col][0], 32 * qt + 16 * G, half);
+            gk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, df, gk[t], 0, 0, 0);
+          }
+        }
       }
-    }
+      wave_lds_fence();  // mws is rewritten for the next cluster tile
+      csum += __shfl_xor(csum, 32, 64);
+      // rows go out through a per-wave LDS tile: a store instruction then writes 64 / (D/8) whole rows of
+      // consecutive clusters (contiguous memory) instead of 32 fragments of 8 bytes
 #pragma unroll
-    for (int G = 0; G < 2; ++G) {
-      bf16x8_t pf = pack8(pr, 2 * G, 2 * G + 1);
-      bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
+      for (int arr = 0; arr < 2; ++arr) {
+        wave_lds_fence();
 #pragma unroll
-      for (int t = 0; t < DT; ++t) {
-        bf16x8_t ag = ld_tr8(&gt_[32 * t + col][0], 16 * G, half);
-        gv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, pf, gv[t], 0, 0, 0);
-        bf16x8_t aq = ld_tr8(&qt_[32 * t + col][0], 16 * G, half);
-        gk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, df, gk[t], 0, 0, 0);
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x16_t& a = arr == 0 ? gk[t] : gv[t];
+            *reinterpret_cast<uint2*>(&tw[wave][col][32 * t + 8 * g + 4 * half]) =
+                make_uint2(pack_bf16x2(a[4 * g], a[4 * g + 1]), pack_bf16x2(a[4 * g + 2], a[4 * g + 3]));
+          }
+        wave_lds_fence();
+        bf16_t* dst = arr == 0 ? g_A_k : g_A_v;
+#pragma unroll
+        for (int it = 0; it < 32 * CPR / 64; ++it) {
+          const int row = it * (64 / CPR) + lane / CPR, cc = lane % CPR;
+          if (jt * 32 + row < Ck) {
+            uint4 v = *reinterpret_cast<const uint4*>(&tw[wave][row][cc * 8]);
+            uint4* o = reinterpret_cast<uint4*>(dst + (acell + jt * 32 + row) * D + cc * 8);
+            if (!first) {  // further pass of a large group: add to what the earlier passes wrote
+              const uint4 old = *o;
+              const uint32_t* pn = reinterpret_cast<const uint32_t*>(&v);
+              const uint32_t* po = reinterpret_cast<const uint32_t*>(&old);
+              uint32_t rr[4];
+#pragma unroll
+              for (int u = 0; u < 4; ++u)
+                rr[u] = pack_bf16x2(__uint_as_float(pn[u] << 16) + __uint_as_float(po[u] << 16),
+                                    __uint_as_float(pn[u] & 0xffff0000u) + __uint_as_float(po[u] & 0xffff0000u));
+              v = make_uint4(rr[0], rr[1], rr[2], rr[3]);
+            }
+            *o = v;
+          }
+        }
       }
+      if (jvalid && half == 0) g_A_c[acell + jc] = first ? csum : g_A_c[acell + jc] + csum;
+      cur = nxt;
     }
   }
-  csum += __shfl_xor(csum, 32, 64);
-  if (!jvalid) return;
-  bf16_t* ok_ = g_A_k + (acell + jc) * D;
-  bf16_t* ov_ = g_A_v + (acell + jc) * D;
-#pragma unroll
-  for (int t = 0; t < DT; ++t)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int d = 32 * t + 8 * g + 4 * half;
-      *reinterpret_cast<uint2*>(ok_ + d) = make_uint2(pack_bf16x2(gk[t][4 * g], gk[t][4 * g + 1]), pack_bf16x2(gk[t][4 * g + 2], gk[t][4 * g + 3]));
-      *reinterpret_cast<uint2*>(ov_ + d) = make_uint2(pack_bf16x2(gv[t][4 * g], gv[t][4 * g + 1]), pack_bf16x2(gv[t][4 * g + 2], gv[t][4 * g + 3]));
-    }
-  if (half == 0) g_A_c[acell + jc] = csum;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -984,12 +1027,11 @@ int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO
                                 const void* A_kb, const void* A_v, const int32_t* perm_q, const int32_t* off_q,
                                 const float* LSE, const float* delta, const uint32_t* selmask, float* g_A_c,
                                 void* g_A_k, void* g_A_v, int h0, int hn, hipStream_t st) {
-  const int W = (d.Ck + 31) / 32;
-  dim3 g((W + 3) / 4, (d.nb - 1) * d.Cq, hn);
+  dim3 g(1, (d.nb - 1) * d.Cq, hn);
   if (d.D == 64)
-    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL(k_ff_bwd_cells_mx<64>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, (const bf16_t*)A_kb, (const bf16_t*)A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, (bf16_t*)g_A_k, (bf16_t*)g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
+    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL((k_ff_bwd_cells_mx<64, 2>), g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, (const bf16_t*)A_kb, (const bf16_t*)A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, (bf16_t*)g_A_k, (bf16_t*)g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
   else
-    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL(k_ff_bwd_cells_mx<128>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, (const bf16_t*)A_kb, (const bf16_t*)A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, (bf16_t*)g_A_k, (bf16_t*)g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
+    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL((k_ff_bwd_cells_mx<128, 1>), g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, (const bf16_t*)A_kb, (const bf16_t*)A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, (bf16_t*)g_A_k, (bf16_t*)g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
