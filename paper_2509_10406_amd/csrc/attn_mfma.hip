@@ -763,8 +763,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   struct CT {  // one tile of 32 accumulated summaries as this lane's operand fragments
     bf16x8_t kf[KS], vf[KS];
     float amu2;
+    uint32_t mw[QT];  // word of the selection mask of staged query 32 qt + col for this cluster tile
   };
-  auto load_ct = [&](int jt, CT& c) {
+  auto load_ct = [&](int jt, int q0, int qhi, CT& c) {
     const int jc = jt * 32 + col;
     const int jcc = jc < Ck ? jc : Ck - 1;
 #pragma unroll
@@ -773,6 +774,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
       c.vf[x] = *reinterpret_cast<const bf16x8_t*>(A_v + (acell + jcc) * D + 16 * x + 8 * half);
     }
     c.amu2 = jc < Ck ? A_mu[acell + jcc] * 1.4426950408889634f : MUSE_NEG_INF;
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      const int pq = q0 + 32 * qt + col;
+      c.mw[qt] = selmask[((size_t)hq * W + jt) * N + (pq < qhi ? pq : q0)];
+    }
   };
   for (int q0 = qlo; q0 < qhi || q0 == qlo; q0 += QR) {  // an empty group still writes its (zero) cells
     const bool first = q0 == qlo;
@@ -805,12 +811,14 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     __syncthreads();
     const int ntl = (qhi - q0 + 31) / 32 < QT ? (qhi - q0 + 31) / 32 : QT;  // staged query tiles (0 for an empty group)
     CT cur, nxt;
-    if (wave < W) load_ct(wave, cur);
+    if (wave < W) load_ct(wave, q0 < qhi ? q0 : 0, qhi, cur);
     for (int jt = wave; jt < W; jt += 4) {
-      if (jt + 4 < W) load_ct(jt + 4, nxt);
+      if (jt + 4 < W) load_ct(jt + 4, q0 < qhi ? q0 : 0, qhi, nxt);
       // this wave's words of the selection mask: one per staged query, for cluster tile jt
-      for (int rr = lane; rr < 32 * ntl; rr += 64)
-        mws[wave][rr] = selmask[((size_t)hq * W + jt) * N + (q0 + rr < qhi ? q0 + rr : q0)];
+      if (half == 0) {
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) mws[wave][32 * qt + col] = cur.mw[qt];
+      }
       wave_lds_fence();
       const int jc = jt * 32 + col;
       const bool jvalid = jc < Ck;
