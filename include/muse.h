@@ -69,6 +69,17 @@ typedef struct {
   float scale;          /* logit scale applied to q (Eq. 1 has none written); 0 -> 1/sqrt(D) */
 } muse_params;
 
+/* Streams: every entry point is asynchronous on `stream` (a hipStream_t; NULL = the null stream).  muse_cluster
+ * and muse_bwd run stages that do not depend on each other (the two K-means problems; the block-diagonal
+ * backward beside the far field) on a second, library-owned, non-blocking stream of the current device,
+ * created on first use; the two streams meet through events before the entry point's last kernels, so work
+ * enqueued on `stream` afterwards sees every output.  One host thread at a time may issue calls on a
+ * device.  If the second stream cannot be created everything runs on `stream`.
+ *
+ * Storage: for bf16 inputs the value summaries, the gradients of the summaries and a copy of the
+ * accumulated key summaries used by the backward are kept in bf16 in the workspace; every quantity that
+ * decides a selection (key summaries, scores) is fp32. */
+
 /* Bytes of device scratch that entry point `which` (MUSE_WS_*) needs for `p`.  The far-field
  * stages keep the summaries tensor of Sec. 3 ([Cq, Ck, N/block] cells of 2D+1 floats) in the
  * workspace for as many heads at a time as fit: any size >= the returned minimum works, and

@@ -148,8 +148,22 @@ struct MuseDims {
     if (hipGetLastError() != hipSuccess) return MUSE_ERR_HIP; \
   } while (0)
 
+// A second stream per device for stages that are independent of each other until a later join (the two
+// K-means problems; the block-diagonal backward beside the far field).  Created on first use, default
+// priority, non-blocking w.r.t. the null stream; the streams meet through the two events.  state: 0 untried,
+// 1 ready, -1 unavailable (everything then runs on the caller's stream).  Calls of one process that overlap
+// in time on one device would share it: they must be issued from one host thread at a time.
+struct MuseAux {
+  hipStream_t s = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  int state = 0;
+};
+MuseAux& muse_aux_stream();
+
 // Optional per-kernel timing (diagnostics for the benchmark): when enabled through
 // muse_profile_enable, every launch is bracketed by HIP events on its stream.
+// While profiling is on, everything runs on the caller's stream so that durations do not overlap.
+bool muse_profiling();
 struct MuseProf {
   MuseProf(const char* name, hipStream_t st);
   ~MuseProf();

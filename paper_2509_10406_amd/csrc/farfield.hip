@@ -688,6 +688,7 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
     w->slotinfo = (int32_t*)take(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * 4);
     w->dKs = (float*)take(HK * N * D * 4);
     w->dVs = (float*)take(HK * N * D * 4);
+    w->dQff = (float*)take(HQ * N * D * 4);
     if (d.grad_dtype != MUSE_DTYPE_FP32) {
       w->dQacc = (float*)take(HQ * N * D * 4);
       w->dKacc = (float*)take(HK * N * D * 4);

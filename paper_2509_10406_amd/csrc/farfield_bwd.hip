@@ -1086,7 +1086,7 @@ __global__ void __launch_bounds__(64) k_c3_keys(const T* __restrict__ Q, const T
   c3_flush<T, D>(sorted, start, Q, dO, Ks, Vs, LSE, delta, ok, dKs, dVs, hk, hqbase, N, Ck, bp, jt, scale);
 }
 
-// rows back to sequence order: dst[perm[p]] = src[p]
+// rows back to sequence order, added to what the block-diagonal kernels left: dst[perm[p]] += src[p]
 __global__ void __launch_bounds__(256) k_scatter_rows(const float* __restrict__ src, const int32_t* __restrict__ perm,
                                                        float* __restrict__ dst, int N, int D) {
   const int CPR = D / 4;
@@ -1095,7 +1095,24 @@ __global__ void __launch_bounds__(256) k_scatter_rows(const float* __restrict__ 
   if (c >= (size_t)N * CPR) return;
   int p = (int)(c / CPR), cc = (int)(c % CPR);
   int to = perm[h * N + p];
-  reinterpret_cast<float4*>(dst + (h * N + to) * D)[cc] = reinterpret_cast<const float4*>(src + (h * N + p) * D)[cc];
+  float4* o = reinterpret_cast<float4*>(dst + (h * N + to) * D) + cc;
+  const float4 a = reinterpret_cast<const float4*>(src + (h * N + p) * D)[cc];
+  float4 v = *o;
+  v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+  *o = v;
+}
+
+// dst[h][n] += src[h][n] for the rows n >= n0 of every head (the queries that have a far field)
+__global__ void __launch_bounds__(256) k_add_rows(const float* __restrict__ src, float* __restrict__ dst, int N, int n0,
+                                                   int D) {
+  const size_t per = (size_t)(N - n0) * (D / 4);
+  const size_t c = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= per) return;
+  const size_t o = ((size_t)blockIdx.y * N + n0) * (D / 4) + c;
+  const float4 a = reinterpret_cast<const float4*>(src)[o];
+  float4 v = reinterpret_cast<float4*>(dst)[o];
+  v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+  reinterpret_cast<float4*>(dst)[o] = v;
 }
 
 template <typename T, int D>
@@ -1106,15 +1123,15 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
   dim3 gt(d.Bs / 32 + d.Cq + 1, NBm, hn);
   { MuseProf prof_("k_ff_bwd_dq", st); hipLaunchKernelGGL((k_ff_bwd_dq<T, D>), gt, dim3(64), 0, st, Q, dO, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu,
                      w.s_k, (const T*)w.s_v, w.A_mu, w.A_k, (const T*)w.A_v, (const bf16_t*)w.A_kb, w.perm_q, w.off_q, w.off_k, w.tile_off, LSE, w.delta,
-                     w.selmask, selc, selb, w.ret_part, w.dQacc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
+                     w.selmask, selc, selb, w.ret_part, w.dQff, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
   if (sizeof(T) == 2 && d.r > 0) {
     dim3 g2((d.N - d.Bs + 15) / 16, hn);
     if (d.nb <= 9)
       { MuseProf prof_("k_comp2_bwd_dq", st); hipLaunchKernelGGL((k_comp2_bwd_dq<D, 1>), g2, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, w.s_mu, w.s_k, (const bf16_t*)w.s_v,
-                         w.perm_q, aq, LSE, w.delta, w.slotinfo, w.ret_part, w.dQacc, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
+                         w.perm_q, aq, LSE, w.delta, w.slotinfo, w.ret_part, w.dQff, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
     else
       { MuseProf prof_("k_comp2_bwd_dq", st); hipLaunchKernelGGL((k_comp2_bwd_dq<D, 2>), g2, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, w.s_mu, w.s_k, (const bf16_t*)w.s_v,
-                         w.perm_q, aq, LSE, w.delta, w.slotinfo, w.ret_part, w.dQacc, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
+                         w.perm_q, aq, LSE, w.delta, w.slotinfo, w.ret_part, w.dQff, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
   }
   if (sizeof(T) == 2) {
     int rc2 = muse_launch_ff_bwd_cells_mx(d, Q, dO, qc, w.A_mu, w.A_kb, w.A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask,
@@ -1150,7 +1167,20 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
   const bool reuse = d.keep_state;  // bucketing, bucketed copies and summaries are still in the workspace
   if (!reuse && (rc = muse_ff_prepare<T>(d, K, V, aq, ak, w, st))) return rc;
   if ((rc = muse_launch_delta(d, O, dO, w.delta, st))) return rc;
-  if ((rc = muse_launch_fill(w.dQacc, nq * D, 0.f, st))) return rc;
+  // the block-diagonal backward (matrix-core bound) runs beside the far field (memory bound) on a second
+  // stream; it starts from zero and the far-field results are added after the join
+  MuseAux& ax = muse_aux_stream();
+  const bool two = ax.state == 1 && !muse_profiling();
+  hipStream_t sb = two ? ax.s : st;
+  if (two) {
+    MUSE_HIP_CHECK(hipEventRecord(ax.fork, st));
+    MUSE_HIP_CHECK(hipStreamWaitEvent(sb, ax.fork, 0));
+  }
+  if ((rc = muse_launch_fill(w.dQacc, nq * D, 0.f, sb))) return rc;
+  if ((rc = muse_launch_fill(w.dKacc, nk * D, 0.f, sb))) return rc;
+  if ((rc = muse_launch_fill(w.dVacc, nk * D, 0.f, sb))) return rc;
+  if ((rc = muse_launch_attn_bwd(d, d.Bs, Q, K, V, dO, LSE, w.delta, w.dQacc, w.dKacc, w.dVacc, sb))) return rc;
+  if (two) MUSE_HIP_CHECK(hipEventRecord(ax.join, sb));
   if ((rc = muse_launch_fill(w.dKs, nk * D, 0.f, st))) return rc;
   if ((rc = muse_launch_fill(w.dVs, nk * D, 0.f, st))) return rc;
   if (d.nb > 1) {
@@ -1191,13 +1221,18 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
       if (rc) return rc;
     }
   }
+  if (two) MUSE_HIP_CHECK(hipStreamWaitEvent(st, ax.join, 0));
   {
     dim3 g((unsigned)(((size_t)N * (D / 4) + 255) / 256), HK);
     { MuseProf prof_("k_scatter_rows", st); hipLaunchKernelGGL(k_scatter_rows, g, dim3(256), 0, st, w.dKs, w.perm_k, w.dKacc, N, D); }
     { MuseProf prof_("k_scatter_rows", st); hipLaunchKernelGGL(k_scatter_rows, g, dim3(256), 0, st, w.dVs, w.perm_k, w.dVacc, N, D); }
     MUSE_LAUNCH_CHECK();
   }
-  if ((rc = muse_launch_attn_bwd(d, d.Bs, Q, K, V, dO, LSE, w.delta, w.dQacc, w.dKacc, w.dVacc, st))) return rc;
+  if (d.nb > 1) {
+    dim3 g((unsigned)(((size_t)(N - d.Bs) * (D / 4) + 255) / 256), HQ);
+    { MuseProf prof_("k_add_rows", st); hipLaunchKernelGGL(k_add_rows, g, dim3(256), 0, st, w.dQff, w.dQacc, N, d.Bs, D); }
+    MUSE_LAUNCH_CHECK();
+  }
   if (d.grad_dtype != MUSE_DTYPE_FP32) {
     if ((rc = muse_launch_cast(w.dQacc, dQ, nq * D, d.grad_dtype, 1.f, st))) return rc;
     if ((rc = muse_launch_cast(w.dKacc, dK, nk * D, d.grad_dtype, 1.f, st))) return rc;

@@ -150,6 +150,7 @@ struct FFWorkspace {
   float* ret_part;               // per (query, slot, u): forward partial state [acc D | max | sum | pad2], or dq partial [D]
   float *dKs, *dVs;            // fp32 gradients in bucketed key order
   float *dQacc, *dKacc, *dVacc;  // fp32 gradients in sequence order (alias the outputs when they are fp32)
+  float* dQff;                   // far-field part of dQ, added to dQacc once the block-diagonal backward has finished
   // per chunk of `hc` query heads
   float* L;
   // decision-deciding summaries stay fp32; value summaries and every cell gradient are stored in the input
@@ -176,7 +177,8 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
        2 * ff_al(HK * ((size_t)d.nb * d.Ck * (d.Hq / d.Hkv) * kHitSeg + 1) * 4) + ff_al(HQ * N * R2 * 8) +
        ff_al(HQ * N * R2 * (D + 4) * 4);
   if (bwd) {
-    b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + ff_al(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * 4) + 2 * ff_al(HK * N * D * 4);
+    b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + ff_al(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * 4) + 2 * ff_al(HK * N * D * 4) +
+         ff_al(HQ * N * D * 4);
     if (d.grad_dtype != MUSE_DTYPE_FP32) b += ff_al(HQ * N * D * 4) + 2 * ff_al(HK * N * D * 4);
   }
   return b;

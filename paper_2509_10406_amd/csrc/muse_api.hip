@@ -24,6 +24,23 @@ int muse_run_bwd(const MuseDims& d, const void* Q, const void* K, const void* V,
 namespace {
 struct ProfRec { const char* name; hipEvent_t a, b; };
 bool g_prof_on = false;
+}  // namespace
+bool muse_profiling() { return g_prof_on; }
+
+MuseAux& muse_aux_stream() {
+  static MuseAux a[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+  MuseAux& x = a[dev];
+  if (x.state == 0) {
+    x.state = (hipStreamCreateWithFlags(&x.s, hipStreamNonBlocking) == hipSuccess &&
+               hipEventCreateWithFlags(&x.fork, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&x.join, hipEventDisableTiming) == hipSuccess)
+                  ? 1 : -1;
+  }
+  return x;
+}
+namespace {
 std::vector<ProfRec> g_prof;
 }  // namespace
 
@@ -103,7 +120,7 @@ int muse_workspace_bytes(const muse_params* p, int which, size_t* min_bytes, siz
   if (rc) return rc;
   size_t mn = 0, pref = 0;
   switch (which) {
-    case MUSE_WS_CLUSTER: mn = pref = muse_cluster_ws_bytes(d); break;
+    case MUSE_WS_CLUSTER: mn = pref = 2 * muse_cluster_ws_bytes(d); break;  // queries and keys side by side
     case MUSE_WS_EXACT_FWD: mn = pref = 256; break;
     case MUSE_WS_EXACT_BWD: mn = pref = exact_bwd_bytes(d); break;
     case MUSE_WS_FWD:
@@ -130,16 +147,26 @@ int muse_cluster(const muse_params* p, const void* Q, const void* K, const int32
   if (Q && (!q_centroids || !q_assign)) return MUSE_ERR_INVALID_ARG;
   if (K && (!k_centroids || !k_assign)) return MUSE_ERR_INVALID_ARG;
   if (!ws) return MUSE_ERR_INVALID_ARG;
-  if (ws_bytes < muse_cluster_ws_bytes(d)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  if (ws_bytes < 2 * muse_cluster_ws_bytes(d)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t st = (hipStream_t)stream;
+  // the two problems are independent: the keys go to the second stream (own half of the workspace)
+  MuseAux& ax = muse_aux_stream();
+  const bool two = Q && K && ax.state == 1 && !muse_profiling();
+  hipStream_t sk = two ? ax.s : st;
+  if (two) {
+    MUSE_HIP_CHECK(hipEventRecord(ax.fork, st));
+    MUSE_HIP_CHECK(hipStreamWaitEvent(sk, ax.fork, 0));
+  }
+  if (K) {
+    rc = muse_launch_cluster(d, K, d.Hkv, d.Ck, k_init_idx, k_centroids, k_assign, (char*)ws + muse_cluster_ws_bytes(d), sk);
+    if (rc) return rc;
+  }
+  if (two) MUSE_HIP_CHECK(hipEventRecord(ax.join, sk));
   if (Q) {
     rc = muse_launch_cluster(d, Q, d.Hq, d.Cq, q_init_idx, q_centroids, q_assign, ws, st);
     if (rc) return rc;
   }
-  if (K) {
-    rc = muse_launch_cluster(d, K, d.Hkv, d.Ck, k_init_idx, k_centroids, k_assign, ws, st);
-    if (rc) return rc;
-  }
+  if (two) MUSE_HIP_CHECK(hipStreamWaitEvent(st, ax.join, 0));
   return MUSE_OK;
 }
 
