@@ -83,22 +83,22 @@ __global__ void __launch_bounds__(256) k_tilt_logits(const T* __restrict__ Ks, c
 }
 
 // ------------------------------------------------------------------------------------------
-// per-block summaries (Eq. 4-6) + exclusive accumulation on fp32 MFMA.  One wave per (key cluster j,
+// exclusive accumulation of the per-block summaries (Eq. 4-6) on fp32 MFMA.  One wave per (key cluster j,
 // tile of 32 query clusters, 64-wide slice of the head dim); it walks the key blocks in order and
 // keeps the running accumulation in registers.  For a segment (j, b):
 //   E^T[key, i] = exp(L[i, key] - max_i)         (B operand, row pattern over the keys)
 //   Ksum^T[d, i] += K^T[d, key] E^T[key, i]      (A operand = bucketed K rows, column pattern)
-// s_*[b] is the summary of key block b, A_*[b] the accumulation of blocks 0..b (what query block b+1
-// sees), b = 0..nb-2.
+// A_*[b] is the accumulation of blocks 0..b (what query block b+1 sees), b = 0..nb-2; of the summary of
+// key block b alone only mu-bar (s_mu) is written here.
 // ------------------------------------------------------------------------------------------
 template <typename T, int D>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) k_summaries(const T* __restrict__ Ks, const T* __restrict__ Vs,
                                                    const float* __restrict__ L, const int32_t* __restrict__ off_k,
-                                                   float* __restrict__ s_mu, float* __restrict__ s_k,
-                                                   T* __restrict__ s_v, float* __restrict__ A_mu,
+                                                   float* __restrict__ s_mu, float* __restrict__ A_mu,
                                                    float* __restrict__ A_k, T* __restrict__ A_v,
-                                                   bf16_t* __restrict__ A_kb, int h0, int N, int nb, int Cq, int Ck,
-                                                   int Hq, int Hkv) {
+                                                   bf16_t* __restrict__ A_kb, uint16_t* __restrict__ A_km,
+                                                   float* __restrict__ A_c, const float* __restrict__ qc, float scale,
+                                                   int h0, int N, int nb, int Cq, int Ck, int Hq, int Hkv) {
   constexpr int DS = D / 64;  // slices of the head dim
   constexpr int KCH = sizeof(T) == 2 ? 16 : 8;  // keys per chunk
   __shared__ float tr[32][68];
@@ -116,79 +116,95 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const T* Kh = Ks + (size_t)hk * N * D + d0 + 2 * col;
   const T* Vh = Vs + (size_t)hk * N * D + d0 + 2 * col;
 
+  // One chunk of keys as the lane consumes it; the loads of the next chunk (of this block or of the next
+  // non-empty one) are issued before the current chunk is used.
+  struct Chunk {
+    float lg[KCH / 8][4];
+    typename Pair<T>::raw kk[KCH / 8][4], vv[KCH / 8][4];
+  };
+  auto load_chunk = [&](Chunk& c, int c0, int hi) {
+#pragma unroll
+    for (int u = 0; u < KCH / 8; ++u)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int p = c0 + 8 * u + 4 * half + t;
+        const int pc = p < hi ? p : hi - 1;
+        c.lg[u][t] = Li[pc];
+        c.kk[u][t] = Pair<T>::ld(Kh, (size_t)pc * D);
+        c.vv[u][t] = Pair<T>::ld(Vh, (size_t)pc * D);
+      }
+  };
+  // position of the chunk in flight: block nb_, first key nc0, end of its cell nhi (nb_ == NBm: none)
+  int nb_ = 0, nc0 = 0, nhi = 0;
+  Chunk nxt;
+  auto seek = [&]() {  // first non-empty cell at or after block nb_
+    while (nb_ < NBm) {
+      nc0 = ok[nb_ * Ck + j];
+      nhi = ok[nb_ * Ck + j + 1];
+      if (nc0 < nhi) break;
+      ++nb_;
+    }
+    if (nb_ < NBm) load_chunk(nxt, nc0, nhi);
+  };
+  seek();
+
+  // The accumulation runs directly in the accumulated summaries' registers, relative to the running maximum
+  // Amx of all blocks so far; the block's own log-sum-exp (mu-bar of the block) is kept beside it as scalars.
   float Amx = MUSE_NEG_INF, AS = 0.f;
   f32x16_t Aak[2], Aav[2];
   Aak[0] = zero16(); Aak[1] = zero16(); Aav[0] = zero16(); Aav[1] = zero16();
   for (int b = 0; b < NBm; ++b) {
-    const int lo = ok[b * Ck + j], hi = ok[b * Ck + j + 1];
     float mx = MUSE_NEG_INF, S = 0.f;
-    f32x16_t ak[2], av[2];
-    ak[0] = zero16(); ak[1] = zero16(); av[0] = zero16(); av[1] = zero16();
-    for (int c0 = lo; c0 < hi; c0 += KCH) {
-      // every load of the chunk is issued before the first use: one round trip per chunk
+    bool empty = true;
+    while (nb_ == b) {
+      empty = false;
+      const Chunk cur = nxt;
+      const int c0 = nc0, hi = nhi;
+      nc0 += KCH;
+      if (nc0 < nhi) load_chunk(nxt, nc0, nhi);
+      else { ++nb_; seek(); }
       float lg[KCH / 8][4];
-      typename Pair<T>::raw kk[KCH / 8][4], vv[KCH / 8][4];
-#pragma unroll
-      for (int u = 0; u < KCH / 8; ++u)
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int p = c0 + 8 * u + 4 * half + t;
-          const int pc = p < hi ? p : hi - 1;
-          lg[u][t] = Li[pc];
-          kk[u][t] = Pair<T>::ld(Kh, (size_t)pc * D);
-          vv[u][t] = Pair<T>::ld(Vh, (size_t)pc * D);
-        }
       float cm = MUSE_NEG_INF;
 #pragma unroll
       for (int u = 0; u < KCH / 8; ++u)
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          lg[u][t] = c0 + 8 * u + 4 * half + t < hi ? lg[u][t] : MUSE_NEG_INF;
+          lg[u][t] = c0 + 8 * u + 4 * half + t < hi ? cur.lg[u][t] : MUSE_NEG_INF;
           cm = fmaxf(cm, lg[u][t]);
         }
       cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
-      const float nm = fmaxf(mx, cm);
-      const float resc = __expf(mx - nm);
-      mx = nm;
-      S *= resc;
+      const float nmb = fmaxf(mx, cm);
+      S *= __expf(mx - nmb);
+      mx = nmb;
+      const float nm = fmaxf(Amx, cm);
+      const float resc = __expf(Amx - nm);
+      Amx = nm;
+      AS *= resc;
 #pragma unroll
       for (int x = 0; x < 2; ++x)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { ak[x][e] *= resc; av[x][e] *= resc; }
+        for (int e = 0; e < 16; ++e) { Aak[x][e] *= resc; Aav[x][e] *= resc; }
 #pragma unroll
       for (int u = 0; u < KCH / 8; ++u)
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
+          S += __expf(lg[u][t] - nmb);
           const float e = __expf(lg[u][t] - nm);
-          S += e;
-          ak[0] = mfma32(Pair<T>::lo(kk[u][t]), e, ak[0]);
-          ak[1] = mfma32(Pair<T>::hi(kk[u][t]), e, ak[1]);
-          av[0] = mfma32(Pair<T>::lo(vv[u][t]), e, av[0]);
-          av[1] = mfma32(Pair<T>::hi(vv[u][t]), e, av[1]);
+          AS += e;
+          Aak[0] = mfma32(Pair<T>::lo(cur.kk[u][t]), e, Aak[0]);
+          Aak[1] = mfma32(Pair<T>::hi(cur.kk[u][t]), e, Aak[1]);
+          Aav[0] = mfma32(Pair<T>::lo(cur.vv[u][t]), e, Aav[0]);
+          Aav[1] = mfma32(Pair<T>::hi(cur.vv[u][t]), e, Aav[1]);
         }
     }
     S += __shfl_xor(S, 32, 64);
-    const bool empty = hi == lo;
-    if (!empty) {  // running sums relative to the running max
-      const float nm = fmaxf(Amx, mx);
-      const float ra = __expf(Amx - nm), rb = __expf(mx - nm);
-      AS = AS * ra + S * rb;
-#pragma unroll
-      for (int x = 0; x < 2; ++x)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          Aak[x][e] = Aak[x][e] * ra + ak[x][e] * rb;
-          Aav[x][e] = Aav[x][e] * ra + av[x][e] * rb;
-        }
-      Amx = nm;
-    }
+    const float ASt = AS + __shfl_xor(AS, 32, 64);
     const size_t cell = (((size_t)hl * NBm + b) * Cq + ic) * Ck + j;
-    const float inv = empty ? 0.f : 1.f / S;
-    const bool aempty = AS == 0.f;
-    const float ainv = aempty ? 0.f : 1.f / AS;
+    const bool aempty = ASt == 0.f;
+    const float ainv = aempty ? 0.f : 1.f / ASt;
     if (iv && half == 0 && d0 == 0) {
       s_mu[cell] = empty ? MUSE_NEG_INF : mx + __logf(S);
-      A_mu[cell] = aempty ? MUSE_NEG_INF : Amx + __logf(AS);
+      A_mu[cell] = aempty ? MUSE_NEG_INF : Amx + __logf(ASt);
     }
     // transpose each 64 x 32 accumulator slice through LDS so that a store instruction writes four whole
     // 256-byte row segments instead of 32 fragments of 32 bytes
@@ -212,13 +228,121 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
       wave_lds_fence();
     };
-    // k-bar stays fp32 (it decides selections); values go out in the input type; bf16 inputs also get a
-    // bf16 copy of the accumulated k-bar for the gradient contractions
+    // the accumulated k-bar of bf16 inputs as a bf16 plane, an fp16 plane of the remainder, and the slice's
+    // share of scale * qc_i . k-bar (what the 16-bit score MFMAs of the tile kernel take)
+    auto emit_planes = [&](const f32x16_t(&a)[2], float sc) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          *reinterpret_cast<float2*>(&tr[col][2 * (8 * g + 4 * half + t)]) = make_float2(a[0][4 * g + t] * sc, a[1][4 * g + t] * sc);
+      wave_lds_fence();
+#pragma unroll
+      for (int ps = 0; ps < 8; ++ps) {
+        const int row = 4 * ps + lane / 16;
+        const bool rv = it * 32 + row < Cq;
+        float part = 0.f;
+        const size_t crow = rowbase + (size_t)row * Ck;
+        if (rv) {
+          const float4 v = *reinterpret_cast<const float4*>(&tr[row][4 * (lane % 16)]);
+          const size_t o = crow * D + d0 + 4 * (lane % 16);
+          const uint32_t h01 = pack_bf16x2(v.x, v.y), h23 = pack_bf16x2(v.z, v.w);
+          *reinterpret_cast<uint2*>(A_kb + o) = make_uint2(h01, h23);
+          const float r0 = v.x - __uint_as_float(h01 << 16), r1 = v.y - __uint_as_float(h01 & 0xffff0000u);
+          const float r2 = v.z - __uint_as_float(h23 << 16), r3 = v.w - __uint_as_float(h23 & 0xffff0000u);
+          auto hb = [](float x) { return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)x); };
+          *reinterpret_cast<uint2*>(A_km + o) = make_uint2(hb(r0) | hb(r1) << 16, hb(r2) | hb(r3) << 16);
+          const float4 c = *reinterpret_cast<const float4*>(qc + ((size_t)hq * Cq + it * 32 + row) * D + d0 + 4 * (lane % 16));
+          part = fmaf(c.x, v.x, fmaf(c.y, v.y, fmaf(c.z, v.z, c.w * v.w)));
+        }
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) part += __shfl_xor(part, o, 64);
+        if (rv && lane % 16 == 0) A_c[crow * DS + d0 / 64] = scale * part;
+      }
+      wave_lds_fence();
+    };
+    // values go out in the input type; the accumulated k-bar in fp32 for fp32 inputs, as planes for bf16 inputs
+    // The per-block rows s_k, s_v are read for retrieved (query cluster, key cluster) chains only, about one
+    // chain in ten: they are written later, for those chains, by k_block_summaries; mu-bar is dense.
     constexpr bool kH = sizeof(T) == 2;
-    emit(s_k, nullptr, ak, inv);
-    emit(kH ? nullptr : reinterpret_cast<float*>(s_v), kH ? reinterpret_cast<bf16_t*>(s_v) : nullptr, av, inv);
-    emit(A_k, kH ? A_kb : nullptr, Aak, ainv);
+    if constexpr (kH) emit_planes(Aak, ainv);
+    else emit(A_k, nullptr, Aak, ainv);
     emit(kH ? nullptr : reinterpret_cast<float*>(A_v), kH ? reinterpret_cast<bf16_t*>(A_v) : nullptr, Aav, ainv);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Per-block summaries (Eq. 4-6) of the retrieved chains.  chainmask[hl][i][j/32] has bit j%32 set when some
+// query of cluster i (blocks >= 1) retrieved key cluster j; only those (i, j) chains are ever read at block
+// granularity (block selection and component 2, forward and backward).
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_chainmask(const int32_t* __restrict__ selc, const int32_t* __restrict__ aq,
+                                                    uint32_t* __restrict__ chainmask, int h0, int N, int Bs, int r,
+                                                    int Cq, int W) {
+  const int hl = blockIdx.y;
+  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= (size_t)(N - Bs) * r) return;
+  const size_t qn = (size_t)(h0 + hl) * N + Bs + t / r;
+  const int j = selc[qn * r + t % r];
+  if (j >= 0) atomicOr(&chainmask[((size_t)hl * Cq + aq[qn]) * W + (j >> 5)], 1u << (j & 31));
+}
+
+// One wave per (query cluster i, tile of 32 key clusters).  A chain's blocks go to the wave's eight 8-lane
+// groups (block b to group b % 8), each lane holding D/8 adjacent head dims.  With mu-bar known, the normalised
+// weight of key p in cell (b, i, j) is exp(L[i][p] - mu-bar), so a row is one pass over the cell's keys.
+template <typename T, int D>
+__global__ void __launch_bounds__(64) k_block_summaries(const T* __restrict__ Ks, const T* __restrict__ Vs,
+                                                         const float* __restrict__ L, const int32_t* __restrict__ off_k,
+                                                         const uint32_t* __restrict__ chainmask,
+                                                         const float* __restrict__ s_mu, float* __restrict__ s_k,
+                                                         T* __restrict__ s_v, int h0, int N, int nb, int Cq, int Ck,
+                                                         int Hq, int Hkv) {
+  constexpr int DL = D / 8, NV = DL / 4, KB = 4;
+  const int jt = blockIdx.x, i = blockIdx.y, hl = blockIdx.z, hq = h0 + hl;
+  const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
+  const int g = threadIdx.x >> 3, l8 = threadIdx.x & 7, NBm = nb - 1, W = (Ck + 31) / 32;
+  uint32_t word = chainmask[((size_t)hl * Cq + i) * W + jt];
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  const float* Li = L + ((size_t)hl * Cq + i) * N;
+  const T* Kh = Ks + (size_t)hk * N * D + DL * l8;
+  const T* Vh = Vs + (size_t)hk * N * D + DL * l8;
+  for (; word; word &= word - 1) {
+    const int j = jt * 32 + __ffs((int)word) - 1;
+    for (int b = g; b < NBm; b += 8) {
+      const int lo = ok[b * Ck + j], hi = ok[b * Ck + j + 1];
+      const size_t cell = (((size_t)hl * NBm + b) * Cq + i) * Ck + j;
+      const float mu = s_mu[cell];
+      float ak[DL], av[DL];
+#pragma unroll
+      for (int x = 0; x < DL; ++x) { ak[x] = 0.f; av[x] = 0.f; }
+      for (int p0 = lo; p0 < hi; p0 += KB) {
+        float lg[KB], kv[KB][DL], vv[KB][DL];
+#pragma unroll
+        for (int u = 0; u < KB; ++u) {  // all loads of the batch first
+          const int p = p0 + u < hi ? p0 + u : hi - 1;
+          lg[u] = Li[p];
+#pragma unroll
+          for (int x = 0; x < NV; ++x) {
+            ld4(Kh, (size_t)p * D + 4 * x, &kv[u][4 * x]);
+            ld4(Vh, (size_t)p * D + 4 * x, &vv[u][4 * x]);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < KB; ++u) {
+          const float wgt = p0 + u < hi ? __expf(lg[u] - mu) : 0.f;
+#pragma unroll
+          for (int x = 0; x < DL; ++x) {
+            ak[x] = fmaf(wgt, kv[u][x], ak[x]);
+            av[x] = fmaf(wgt, vv[u][x], av[x]);
+          }
+        }
+      }
+#pragma unroll
+      for (int x = 0; x < NV; ++x) {  // an empty cell gets zero rows
+        st4(s_k, cell * D + DL * l8 + 4 * x, &ak[4 * x]);
+        st4(s_v, cell * D + DL * l8 + 4 * x, &av[4 * x]);
+      }
+    }
   }
 }
 
@@ -230,6 +354,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 template <typename T, int D, int RCAP>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, D == 64 ? 2 : 2))) k_farfield_fwd(
     const T* __restrict__ Q, const float* __restrict__ qc, const float* __restrict__ A_mu, const float* __restrict__ A_k,
+    const bf16_t* __restrict__ A_kb, const uint16_t* __restrict__ A_km, const float* __restrict__ A_c,
     const T* __restrict__ A_v, const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q,
     const int32_t* __restrict__ tile_off, float* __restrict__ ff_acc, float* __restrict__ ff_ml,
     int32_t* __restrict__ selc, int h0, int N, int nb, int Cq, int Ck, int r, float scale) {
@@ -262,24 +387,44 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
   pos = valid ? pos : qlo + 32 * tt;
   const int n = perm_q[(size_t)hq * N + pos];
 
-  float qt[U][4];
+  // fp32 inputs: q~ in the row pattern of the fp32 score MFMAs; bf16 inputs: the query itself as bf16 and fp16
+  float qt[kH ? 1 : U][4];
+  bf16x8_t qb[kH ? D / 16 : 1];
+  f16x8_t qh[kH ? D / 16 : 1];
   {
     const T* qrow = Q + ((size_t)hq * N + n) * D;
-    const float* qci = qc + ((size_t)hq * Cq + i) * D;
+    if constexpr (kH) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float x[4];
-      ld4(qrow, 8 * u + 4 * half, x);
-      float4 c = *reinterpret_cast<const float4*>(qci + 8 * u + 4 * half);
-      qt[u][0] = scale * (x[0] - c.x); qt[u][1] = scale * (x[1] - c.y);
-      qt[u][2] = scale * (x[2] - c.z); qt[u][3] = scale * (x[3] - c.w);
+      for (int ks = 0; ks < D / 16; ++ks) {
+        qb[ks] = *reinterpret_cast<const bf16x8_t*>(qrow + 16 * ks + 8 * half);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qh[ks][e] = (_Float16)(float)qb[ks][e];
+      }
+    } else {
+      const float* qci = qc + ((size_t)hq * Cq + i) * D;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float x[4];
+        ld4(qrow, 8 * u + 4 * half, x);
+        float4 c = *reinterpret_cast<const float4*>(qci + 8 * u + 4 * half);
+        qt[u][0] = scale * (x[0] - c.x); qt[u][1] = scale * (x[1] - c.y);
+        qt[u][2] = scale * (x[2] - c.z); qt[u][3] = scale * (x[3] - c.w);
+      }
     }
   }
   const size_t acell = (((size_t)hl * NBm + (b - 1)) * Cq + i) * Ck;
   const float* Amu = A_mu + acell;
-  const float* Ak = A_k + acell * D;
   const T* Av = A_v + acell * D;
   const int ntile = (Ck + 31) / 32;
+  using KT = typename std::conditional<kH, KTileH<D>, KTile<D>>::type;
+  auto load_kt = [&](KT& kt, int j0) {
+    if constexpr (kH) load_ktile_h<D>(kt, Amu, A_c + acell * (D / 64), A_kb + acell * D, A_km + acell * D, j0, Ck, col, half);
+    else load_ktile<D>(kt, Amu, A_k + acell * D, j0, Ck, col, half);
+  };
+  auto score_kt = [&](const KT& kt, int j0) {
+    if constexpr (kH) return score_ktile_h<D>(kt, j0, Ck, qb, qh, scale, half);
+    else return score_ktile<D>(kt, j0, Ck, qt, half);
+  };
 
   // ---- pass 1: the r largest scores seen by this lane half (values only) ----
   float list[RCAP];
@@ -297,14 +442,14 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
       }
     };
     // two tile buffers: the loads of the next tile are in flight while this one is scored
-    KTile<D> ka, kb;
-    load_ktile<D>(ka, Amu, Ak, 0, Ck, col, half);
+    KT ka, kb;
+    load_kt(ka, 0);
     for (int jt = 0; jt < ntile; jt += 2) {
-      if (jt + 1 < ntile) load_ktile<D>(kb, Amu, Ak, (jt + 1) * 32, Ck, col, half);
-      insert(score_ktile<D>(ka, jt * 32, Ck, qt, half));
+      if (jt + 1 < ntile) load_kt(kb, (jt + 1) * 32);
+      insert(score_kt(ka, jt * 32));
       if (jt + 1 < ntile) {
-        if (jt + 2 < ntile) load_ktile<D>(ka, Amu, Ak, (jt + 2) * 32, Ck, col, half);
-        insert(score_ktile<D>(kb, (jt + 1) * 32, Ck, qt, half));
+        if (jt + 2 < ntile) load_kt(ka, (jt + 2) * 32);
+        insert(score_kt(kb, (jt + 1) * 32));
       }
     }
   }
@@ -338,29 +483,36 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
 #pragma unroll
   for (int t = 0; t < DT; ++t) o[t] = zero16();
   int eqc = 0, ncand = 0;
-  for (int jt = 0; jt < ntile; ++jt) {
-    const int j0 = jt * 32;
-    // all loads of the tile first: k-bar rows, mu-bar, and the DT consecutive dims DT*col .. of the 16 value rows
-    KTile<D> kt;
-    load_ktile<D>(kt, Amu, Ak, j0, Ck, col, half);
+  // a tile's operands: k-bar rows, mu-bar, and the value rows (bf16: this lane's chunks of the 32 x D tile;
+  // fp32: the DT consecutive dims DT*col .. of its 16 rows), all loaded before the first use
+  struct PTile {
+    KT kt;
     typename VF::raw vv[kH ? 1 : 16];
     uint4 vch[kH ? NIT : 1];
+  };
+  auto load_ptile = [&](PTile& pt, int j0) {
+    load_kt(pt.kt, j0);
     if constexpr (kH) {
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
         const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
         const int jr = j0 + row < Ck ? j0 + row : Ck - 1;
-        vch[it] = *reinterpret_cast<const uint4*>(Av + (size_t)jr * D + cc * 8);
+        pt.vch[it] = *reinterpret_cast<const uint4*>(Av + (size_t)jr * D + cc * 8);
       }
     } else {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
         jr = jr < Ck ? jr : Ck - 1;
-        vv[e] = VF::ld(Av, (size_t)jr * D + DT * col);
+        pt.vv[e] = VF::ld(Av, (size_t)jr * D + DT * col);
       }
     }
-    f32x16_t acc = score_ktile<D>(kt, j0, Ck, qt, half);
+  };
+  auto process = [&](const PTile& pt, int j0) {
+    const KT& kt = pt.kt;
+    const auto& vv = pt.vv;
+    const auto& vch = pt.vch;
+    f32x16_t acc = score_kt(kt, j0);
     float tmax = MUSE_NEG_INF;
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
@@ -417,6 +569,12 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
         for (int x = 0; x < DT; ++x) o[x] = mfma32(VF::get(vv[e], x), acc[e], o[x]);
       }
     }
+  };
+  // (two tile buffers, as in pass 1, need more registers than two waves per SIMD leave: measured slower)
+  for (int jt = 0; jt < ntile; ++jt) {
+    PTile pt;
+    load_ptile(pt, jt * 32);
+    process(pt, jt * 32);
   }
   // ---- order the selected clusters of each query by (score desc, index asc) ----
   for (int k = lane; k < 32 * RCAP; k += 64) (&sel_s[0][0])[k] = -1;
@@ -699,13 +857,20 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
   }
   size_t cells = (size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * d.Ck;
   w->L = (float*)take(hc * d.Cq * N * 4);
+  w->chainmask = (uint32_t*)take(hc * d.Cq * ((d.Ck + 31) / 32) * 4);
   w->s_mu = (float*)take(hc * cells * 4);
   w->A_mu = (float*)take(hc * cells * 4);
   w->s_k = (float*)take(hc * cells * D * 4);
-  w->A_k = (float*)take(hc * cells * D * 4);
   w->s_v = take(hc * cells * D * es);
   w->A_v = take(hc * cells * D * es);
-  w->A_kb = es == 2 ? take(hc * cells * D * 2) : nullptr;
+  w->A_k = nullptr; w->A_kb = nullptr; w->A_km = nullptr; w->A_c = nullptr;
+  if (es == 2) {
+    w->A_kb = take(hc * cells * D * 2);
+    w->A_km = take(hc * cells * D * 2);
+    w->A_c = (float*)take(hc * cells * (D / 64) * 4);
+  } else {
+    w->A_k = (float*)take(hc * cells * D * 4);
+  }
   if (bwd) {
     w->g_s_c = (float*)take(hc * cells * 4);
     w->g_A_c = (float*)take(hc * cells * 4);
@@ -744,15 +909,38 @@ int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0
   if (d.D == 64) {
     { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 64>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
     { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 64>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
-                       w.s_k, (T*)w.s_v, w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
+                       w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, (uint16_t*)w.A_km, w.A_c, qc, d.scale, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   } else {
     { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 128>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
     { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 128>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
-                       w.s_k, (T*)w.s_v, w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
+                       w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, (uint16_t*)w.A_km, w.A_c, qc, d.scale, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
+
+// per-block summaries of the retrieved chains of the query heads [h0, h0+hn): needs selc of these heads
+template <typename T>
+int muse_ff_block_summaries(const MuseDims& d, const int32_t* selc, const int32_t* aq, FFWorkspace& w, int h0, int hn,
+                            hipStream_t st) {
+  if (d.nb <= 1 || d.r <= 0) return MUSE_OK;
+  const int W = (d.Ck + 31) / 32;
+  int rc;
+  if ((rc = muse_launch_fill_i32((int32_t*)w.chainmask, (size_t)hn * d.Cq * W, 0, st))) return rc;
+  dim3 gm((unsigned)(((size_t)(d.N - d.Bs) * d.r + 255) / 256), hn);
+  { MuseProf prof_("k_chainmask", st); hipLaunchKernelGGL(k_chainmask, gm, dim3(256), 0, st, selc, aq, w.chainmask, h0, d.N, d.Bs, d.r, d.Cq, W); }
+  dim3 gs(W, d.Cq, hn);
+  if (d.D == 64)
+    { MuseProf prof_("k_block_summaries", st); hipLaunchKernelGGL((k_block_summaries<T, 64>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k,
+                       w.chainmask, w.s_mu, w.s_k, (T*)w.s_v, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
+  else
+    { MuseProf prof_("k_block_summaries", st); hipLaunchKernelGGL((k_block_summaries<T, 128>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k,
+                       w.chainmask, w.s_mu, w.s_k, (T*)w.s_v, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
+template int muse_ff_block_summaries<float>(const MuseDims&, const int32_t*, const int32_t*, FFWorkspace&, int, int, hipStream_t);
+template int muse_ff_block_summaries<bf16_t>(const MuseDims&, const int32_t*, const int32_t*, FFWorkspace&, int, int, hipStream_t);
 
 template int muse_ff_prepare<float>(const MuseDims&, const float*, const float*, const int32_t*, const int32_t*, FFWorkspace&, hipStream_t);
 template int muse_ff_prepare<bf16_t>(const MuseDims&, const bf16_t*, const bf16_t*, const int32_t*, const int32_t*, FFWorkspace&, hipStream_t);
@@ -765,8 +953,8 @@ template <typename T, int D, int RCAP>
 void launch_ff_fwd(const MuseDims& d, const T* Q, const float* qc, FFWorkspace& w, int32_t* selc, int h0, int hn,
                    hipStream_t st) {
   dim3 g(d.Bs / 32 + d.Cq + 1, d.nb - 1, hn);
-  { MuseProf prof_("k_farfield_fwd", st); hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, w.A_mu, w.A_k, (const T*)w.A_v, w.perm_q, w.off_q,
-                     w.tile_off, w.ff_acc, w.ff_ml, selc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.scale); }
+  { MuseProf prof_("k_farfield_fwd", st); hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, w.A_mu, w.A_k, (const bf16_t*)w.A_kb, (const uint16_t*)w.A_km, w.A_c,
+                     (const T*)w.A_v, w.perm_q, w.off_q, w.tile_off, w.ff_acc, w.ff_ml, selc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.scale); }
 }
 
 template <typename T, int D>
@@ -776,6 +964,7 @@ void launch_ff_fwd_r(const MuseDims& d, const T* Q, const float* qc, const int32
   else if (d.r <= 16) launch_ff_fwd<T, D, 16>(d, Q, qc, w, selc, h0, hn, st);
   else launch_ff_fwd<T, D, 32>(d, Q, qc, w, selc, h0, hn, st);
   if (d.r > 0) {
+    (void)muse_ff_block_summaries<T>(d, selc, aq, w, h0, hn, st);
     dim3 g((d.N - d.Bs + 15) / 16, hn);
     if (d.nb <= 9)
       { MuseProf prof_("k_comp2_fwd", st); hipLaunchKernelGGL((k_comp2_fwd<T, D, 1>), g, dim3(256), 0, st, Q, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu, w.s_k,

@@ -1216,6 +1216,7 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
     for (int h0 = 0; h0 < HQ; h0 += w.hc) {
       int hn = HQ - h0 < w.hc ? HQ - h0 : w.hc;
       if (!reuse && (rc = muse_ff_summaries<T>(d, qc, w, h0, hn, st))) return rc;
+      if (!reuse && (rc = muse_ff_block_summaries<T>(d, selc, aq, w, h0, hn, st))) return rc;
       if (D == 64) rc = run_bwd_chunk<T, 64>(d, Q, dO, qc, aq, LSE, selc, selb, w, h0, hn, st);
       else rc = run_bwd_chunk<T, 128>(d, Q, dO, qc, aq, LSE, selc, selb, w, h0, hn, st);
       if (rc) return rc;

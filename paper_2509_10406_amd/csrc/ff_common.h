@@ -99,6 +99,74 @@ __device__ __forceinline__ f32x16_t score_tile(const float* __restrict__ Amu, co
   return score_ktile<D>(kt, j0, Ck, qt, half);
 }
 
+// The same tile for bf16 inputs, where the scores run on the 16-bit matrix cores without losing the precision
+// that decides selections: k-bar is stored as a bf16 plane plus an fp16 plane of the remainder (together 19
+// significant bits or more), the query operand is the bf16 query itself (exact, also as fp16), and the query
+// centroid's share of q~ . k-bar is a per-cell scalar c = scale * qc_i . k-bar computed in fp32 by the kernel
+// that wrote the planes:  score = scale * q . (hi + mid) + (mu-bar - c).
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+template <int D>
+struct KTileH {
+  uint4 h[D / 16], m[D / 16];
+  float mu[16];
+};
+
+template <int D>
+__device__ __forceinline__ void load_ktile_h(KTileH<D>& kt, const float* __restrict__ Amu, const float* __restrict__ Ac,
+                                             const bf16_t* __restrict__ Akb, const uint16_t* __restrict__ Akm, int j0,
+                                             int Ck, int col, int half) {
+  constexpr int DS = D / 64;
+  int c = j0 + col;
+  c = c < Ck ? c : Ck - 1;
+  const bf16_t* rh = Akb + (size_t)c * D + 8 * half;
+  const uint16_t* rm = Akm + (size_t)c * D + 8 * half;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    kt.h[ks] = *reinterpret_cast<const uint4*>(rh + 16 * ks);
+    kt.m[ks] = *reinterpret_cast<const uint4*>(rm + 16 * ks);
+  }
+  if (DS == 1 && (Ck & 3) == 0) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      int base = j0 + 8 * g + 4 * half;
+      base = base < Ck ? base : Ck - 4;
+      const float4 m4 = *reinterpret_cast<const float4*>(Amu + base);
+      const float4 c4 = *reinterpret_cast<const float4*>(Ac + base);
+      kt.mu[4 * g] = m4.x - c4.x; kt.mu[4 * g + 1] = m4.y - c4.y;
+      kt.mu[4 * g + 2] = m4.z - c4.z; kt.mu[4 * g + 3] = m4.w - c4.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+      jr = jr < Ck ? jr : Ck - 1;
+      float cc = Ac[(size_t)jr * DS];
+      if (DS == 2) cc += Ac[(size_t)jr * DS + 1];
+      kt.mu[e] = Amu[jr] - cc;
+    }
+  }
+}
+
+// qb / qh: the lane's query (column) dims 16 ks + 8 half .. + 7 as bf16 and as fp16
+template <int D>
+__device__ __forceinline__ f32x16_t score_ktile_h(const KTileH<D>& kt, int j0, int Ck, const bf16x8_t (&qb)[D / 16],
+                                                  const f16x8_t (&qh)[D / 16], float scale, int half) {
+  f32x16_t acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kt.h[ks]), qb[ks], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, kt.m[ks]), qh[ks], acc, 0, 0, 0);
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+    acc[e] = jr < Ck ? fmaf(scale, acc[e], kt.mu[e]) : MUSE_NEG_INF;
+  }
+  return acc;
+}
+
 // bf16 MFMA (v_mfma_f32_32x32x16_bf16) helpers.  pack8: accumulator rows 4*g0..+3 and 4*g1..+3 of a lane
 // become the 8 k-slots of a B (or A) operand; the matching other operand must use the same row order.
 __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& s, int g0, int g1) {
@@ -153,10 +221,13 @@ struct FFWorkspace {
   float* dQff;                   // far-field part of dQ, added to dQacc once the block-diagonal backward has finished
   // per chunk of `hc` query heads
   float* L;
-  // decision-deciding summaries stay fp32; value summaries and every cell gradient are stored in the input
-  // type (bf16 for bf16 inputs); A_kb is a bf16 copy of A_k for the gradient contractions (bf16 inputs only)
-  float *s_mu, *s_k, *A_mu, *A_k;
-  void *s_v, *A_v, *A_kb;
+  uint32_t* chainmask;  // [hc][Cq][ceil(Ck/32)]: key clusters retrieved by some query of the query cluster
+  // Value summaries and every cell gradient are stored in the input type.  The accumulated k-bar decides
+  // selections: fp32 inputs keep it in fp32 (A_k); bf16 inputs keep a bf16 plane A_kb (also the operand of the
+  // gradient contractions), an fp16 plane A_km of the remainder and the scalar A_c = scale * qc_i . k-bar per
+  // cell and 64-wide head-dim slice.
+  float *s_mu, *s_k, *A_mu, *A_k, *A_c;
+  void *s_v, *A_v, *A_kb, *A_km;
   float *g_s_c, *g_A_c;
   void *g_s_k, *g_s_v, *g_A_k, *g_A_v;
   int hc;
@@ -187,8 +258,8 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
 static inline size_t ff_head_bytes(const MuseDims& d, bool bwd) {
   size_t cells = (size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * d.Ck, D = d.D;
   size_t es = d.dtype == MUSE_DTYPE_BF16 ? 2 : 4;
-  size_t b = ff_al((size_t)d.Cq * d.N * 4) + 2 * ff_al(cells * 4) + 2 * ff_al(cells * D * 4) + 2 * ff_al(cells * D * es);
-  if (es == 2) b += ff_al(cells * D * 2);
+  size_t b = ff_al((size_t)d.Cq * d.N * 4) + ff_al((size_t)d.Cq * ((d.Ck + 31) / 32) * 4) + 2 * ff_al(cells * 4) + ff_al(cells * D * 4) + 2 * ff_al(cells * D * es);
+  b += es == 2 ? 2 * ff_al(cells * D * 2) + ff_al(cells * (D / 64) * 4) : ff_al(cells * D * 4);
   if (bwd) b += 2 * ff_al(cells * 4) + 4 * ff_al(cells * D * es);
   return b;
 }
@@ -200,6 +271,9 @@ int muse_ff_prepare(const MuseDims& d, const T* K, const T* V, const int32_t* aq
                     hipStream_t st);
 template <typename T>
 int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0, int hn, hipStream_t st);
+template <typename T>
+int muse_ff_block_summaries(const MuseDims& d, const int32_t* selc, const int32_t* aq, FFWorkspace& w, int h0, int hn,
+                            hipStream_t st);
 
 // attn_mfma.hip
 int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
