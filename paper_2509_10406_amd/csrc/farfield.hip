@@ -92,15 +92,15 @@ __global__ void __launch_bounds__(256) k_tilt_logits(const T* __restrict__ Ks, c
 // key block b alone only mu-bar (s_mu) is written here.
 // ------------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) k_summaries(const T* __restrict__ Ks, const T* __restrict__ Vs,
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 4))) k_summaries(const T* __restrict__ Ks, const T* __restrict__ Vs,
                                                    const float* __restrict__ L, const int32_t* __restrict__ off_k,
                                                    float* __restrict__ s_mu, float* __restrict__ A_mu,
                                                    float* __restrict__ A_k, T* __restrict__ A_v,
                                                    bf16_t* __restrict__ A_kb, uint16_t* __restrict__ A_km,
-                                                   float* __restrict__ A_c, const float* __restrict__ qc, float scale,
-                                                   int h0, int N, int nb, int Cq, int Ck, int Hq, int Hkv) {
+                                                   float* __restrict__ A_muq, int h0, int N, int nb, int Cq, int Ck,
+                                                   int Hq, int Hkv) {
   constexpr int DS = D / 64;  // slices of the head dim
-  constexpr int KCH = sizeof(T) == 2 ? 16 : 8;  // keys per chunk
+  constexpr int KCH = 8;  // keys per chunk
   __shared__ float tr[32][68];
   const int j = blockIdx.x, hl = blockIdx.z, hq = h0 + hl;
   const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
@@ -116,6 +116,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const T* Kh = Ks + (size_t)hk * N * D + d0 + 2 * col;
   const T* Vh = Vs + (size_t)hk * N * D + d0 + 2 * col;
 
+  // output rows of the lane after the LDS transpose: rows 4 ps + lane/16 of the tile, 4 head dims from 4 (lane%16)
+  const int lrow = lane / 16, nrow = Cq - it * 32 < 32 ? Cq - it * 32 : 32;
+  const uint32_t loff = (uint32_t)lrow * Ck * D + d0 + 4 * (lane % 16), pstr = 4u * Ck * D;
   // One chunk of keys as the lane consumes it; the loads of the next chunk (of this block or of the next
   // non-empty one) are issued before the current chunk is used.
   struct Chunk {
@@ -150,7 +153,8 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   // The accumulation runs directly in the accumulated summaries' registers, relative to the running maximum
   // Amx of all blocks so far; the block's own log-sum-exp (mu-bar of the block) is kept beside it as scalars.
-  float Amx = MUSE_NEG_INF, AS = 0.f;
+  // AL: the weights' sum of the logits themselves, L = scale * qc_i . k, so AL / AS = scale * qc_i . k-bar
+  float Amx = MUSE_NEG_INF, AS = 0.f, AL = 0.f;
   f32x16_t Aak[2], Aav[2];
   Aak[0] = zero16(); Aak[1] = zero16(); Aav[0] = zero16(); Aav[1] = zero16();
   for (int b = 0; b < NBm; ++b) {
@@ -180,6 +184,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const float resc = __expf(Amx - nm);
       Amx = nm;
       AS *= resc;
+      AL *= resc;
 #pragma unroll
       for (int x = 0; x < 2; ++x)
 #pragma unroll
@@ -191,6 +196,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
           S += __expf(lg[u][t] - nmb);
           const float e = __expf(lg[u][t] - nm);
           AS += e;
+          AL = fmaf(e, c0 + 8 * u + 4 * half + t < hi ? cur.lg[u][t] : 0.f, AL);
           Aak[0] = mfma32(Pair<T>::lo(cur.kk[u][t]), e, Aak[0]);
           Aak[1] = mfma32(Pair<T>::hi(cur.kk[u][t]), e, Aak[1]);
           Aav[0] = mfma32(Pair<T>::lo(cur.vv[u][t]), e, Aav[0]);
@@ -199,17 +205,24 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     S += __shfl_xor(S, 32, 64);
     const float ASt = AS + __shfl_xor(AS, 32, 64);
+    const float ALt = AL + __shfl_xor(AL, 32, 64);
     const size_t cell = (((size_t)hl * NBm + b) * Cq + ic) * Ck + j;
     const bool aempty = ASt == 0.f;
     const float ainv = aempty ? 0.f : 1.f / ASt;
     if (iv && half == 0 && d0 == 0) {
       s_mu[cell] = empty ? MUSE_NEG_INF : mx + __logf(S);
-      A_mu[cell] = aempty ? MUSE_NEG_INF : Amx + __logf(ASt);
+      const float amu = aempty ? MUSE_NEG_INF : Amx + __logf(ASt);
+      A_mu[cell] = amu;
+      if (sizeof(T) == 2) A_muq[cell] = aempty ? MUSE_NEG_INF : amu - ALt * ainv;
     }
     // transpose each 64 x 32 accumulator slice through LDS so that a store instruction writes four whole
     // 256-byte row segments instead of 32 fragments of 32 bytes
+    // Addresses: a uniform base per block plus 32-bit lane offsets that do not change over the blocks.
     const size_t rowbase = (((size_t)hl * NBm + b) * Cq + it * 32) * Ck + j;
+    const size_t slab = rowbase * D;
     auto emit = [&](float* __restrict__ dstf, bf16_t* __restrict__ dsth, const f32x16_t(&a)[2], float sc) {
+      float* pf = dstf ? dstf + slab : nullptr;
+      bf16_t* ph = dsth ? dsth + slab : nullptr;
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll
@@ -218,19 +231,20 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       wave_lds_fence();
 #pragma unroll
       for (int ps = 0; ps < 8; ++ps) {
-        const int row = 4 * ps + lane / 16;
-        if (it * 32 + row < Cq) {
-          const float4 v = *reinterpret_cast<const float4*>(&tr[row][4 * (lane % 16)]);
-          const size_t o = (rowbase + (size_t)row * Ck) * D + d0 + 4 * (lane % 16);
-          if (dstf) *reinterpret_cast<float4*>(dstf + o) = v;
-          if (dsth) *reinterpret_cast<uint2*>(dsth + o) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+        if (4 * ps + lrow < nrow) {
+          const float4 v = *reinterpret_cast<const float4*>(&tr[4 * ps + lrow][4 * (lane % 16)]);
+          const uint32_t o = loff + ps * pstr;
+          if (dstf) *reinterpret_cast<float4*>(pf + o) = v;
+          if (dsth) *reinterpret_cast<uint2*>(ph + o) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
         }
       }
       wave_lds_fence();
     };
-    // the accumulated k-bar of bf16 inputs as a bf16 plane, an fp16 plane of the remainder, and the slice's
-    // share of scale * qc_i . k-bar (what the 16-bit score MFMAs of the tile kernel take)
+    // the accumulated k-bar of bf16 inputs as a bf16 plane and an fp16 plane of the remainder (what the 16-bit
+    // score MFMAs of the tile kernel take)
     auto emit_planes = [&](const f32x16_t(&a)[2], float sc) {
+      bf16_t* ph = A_kb + slab;
+      uint16_t* pm = A_km + slab;
 #pragma unroll
       for (int g = 0; g < 4; ++g)
 #pragma unroll
@@ -239,25 +253,16 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       wave_lds_fence();
 #pragma unroll
       for (int ps = 0; ps < 8; ++ps) {
-        const int row = 4 * ps + lane / 16;
-        const bool rv = it * 32 + row < Cq;
-        float part = 0.f;
-        const size_t crow = rowbase + (size_t)row * Ck;
-        if (rv) {
-          const float4 v = *reinterpret_cast<const float4*>(&tr[row][4 * (lane % 16)]);
-          const size_t o = crow * D + d0 + 4 * (lane % 16);
+        if (4 * ps + lrow < nrow) {
+          const float4 v = *reinterpret_cast<const float4*>(&tr[4 * ps + lrow][4 * (lane % 16)]);
+          const uint32_t o = loff + ps * pstr;
           const uint32_t h01 = pack_bf16x2(v.x, v.y), h23 = pack_bf16x2(v.z, v.w);
-          *reinterpret_cast<uint2*>(A_kb + o) = make_uint2(h01, h23);
+          *reinterpret_cast<uint2*>(ph + o) = make_uint2(h01, h23);
           const float r0 = v.x - __uint_as_float(h01 << 16), r1 = v.y - __uint_as_float(h01 & 0xffff0000u);
           const float r2 = v.z - __uint_as_float(h23 << 16), r3 = v.w - __uint_as_float(h23 & 0xffff0000u);
           auto hb = [](float x) { return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)x); };
-          *reinterpret_cast<uint2*>(A_km + o) = make_uint2(hb(r0) | hb(r1) << 16, hb(r2) | hb(r3) << 16);
-          const float4 c = *reinterpret_cast<const float4*>(qc + ((size_t)hq * Cq + it * 32 + row) * D + d0 + 4 * (lane % 16));
-          part = fmaf(c.x, v.x, fmaf(c.y, v.y, fmaf(c.z, v.z, c.w * v.w)));
+          *reinterpret_cast<uint2*>(pm + o) = make_uint2(hb(r0) | hb(r1) << 16, hb(r2) | hb(r3) << 16);
         }
-#pragma unroll
-        for (int o = 1; o < 16; o <<= 1) part += __shfl_xor(part, o, 64);
-        if (rv && lane % 16 == 0) A_c[crow * DS + d0 / 64] = scale * part;
       }
       wave_lds_fence();
     };
@@ -418,7 +423,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
   const int ntile = (Ck + 31) / 32;
   using KT = typename std::conditional<kH, KTileH<D>, KTile<D>>::type;
   auto load_kt = [&](KT& kt, int j0) {
-    if constexpr (kH) load_ktile_h<D>(kt, Amu, A_c + acell * (D / 64), A_kb + acell * D, A_km + acell * D, j0, Ck, col, half);
+    if constexpr (kH) load_ktile_h<D>(kt, A_c + acell, A_kb + acell * D, A_km + acell * D, j0, Ck, col, half);
     else load_ktile<D>(kt, Amu, A_k + acell * D, j0, Ck, col, half);
   };
   auto score_kt = [&](const KT& kt, int j0) {
@@ -867,7 +872,7 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
   if (es == 2) {
     w->A_kb = take(hc * cells * D * 2);
     w->A_km = take(hc * cells * D * 2);
-    w->A_c = (float*)take(hc * cells * (D / 64) * 4);
+    w->A_c = (float*)take(hc * cells * 4);
   } else {
     w->A_k = (float*)take(hc * cells * D * 4);
   }
@@ -909,11 +914,11 @@ int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0
   if (d.D == 64) {
     { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 64>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
     { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 64>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
-                       w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, (uint16_t*)w.A_km, w.A_c, qc, d.scale, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
+                       w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, (uint16_t*)w.A_km, w.A_c, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   } else {
     { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 128>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
     { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 128>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
-                       w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, (uint16_t*)w.A_km, w.A_c, qc, d.scale, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
+                       w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, (uint16_t*)w.A_km, w.A_c, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;

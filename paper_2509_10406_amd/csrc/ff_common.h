@@ -102,8 +102,8 @@ __device__ __forceinline__ f32x16_t score_tile(const float* __restrict__ Amu, co
 // The same tile for bf16 inputs, where the scores run on the 16-bit matrix cores without losing the precision
 // that decides selections: k-bar is stored as a bf16 plane plus an fp16 plane of the remainder (together 19
 // significant bits or more), the query operand is the bf16 query itself (exact, also as fp16), and the query
-// centroid's share of q~ . k-bar is a per-cell scalar c = scale * qc_i . k-bar computed in fp32 by the kernel
-// that wrote the planes:  score = scale * q . (hi + mid) + (mu-bar - c).
+// centroid's share of q~ . k-bar is a per-cell scalar c = scale * qc_i . k-bar, the weighted mean of the tilt
+// logits that the kernel which wrote the planes has at hand:  score = scale * q . (hi + mid) + (mu-bar - c).
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 template <int D>
 struct KTileH {
@@ -112,10 +112,9 @@ struct KTileH {
 };
 
 template <int D>
-__device__ __forceinline__ void load_ktile_h(KTileH<D>& kt, const float* __restrict__ Amu, const float* __restrict__ Ac,
+__device__ __forceinline__ void load_ktile_h(KTileH<D>& kt, const float* __restrict__ Amuq,
                                              const bf16_t* __restrict__ Akb, const uint16_t* __restrict__ Akm, int j0,
                                              int Ck, int col, int half) {
-  constexpr int DS = D / 64;
   int c = j0 + col;
   c = c < Ck ? c : Ck - 1;
   const bf16_t* rh = Akb + (size_t)c * D + 8 * half;
@@ -125,24 +124,19 @@ __device__ __forceinline__ void load_ktile_h(KTileH<D>& kt, const float* __restr
     kt.h[ks] = *reinterpret_cast<const uint4*>(rh + 16 * ks);
     kt.m[ks] = *reinterpret_cast<const uint4*>(rm + 16 * ks);
   }
-  if (DS == 1 && (Ck & 3) == 0) {
+  if ((Ck & 3) == 0) {
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       int base = j0 + 8 * g + 4 * half;
       base = base < Ck ? base : Ck - 4;
-      const float4 m4 = *reinterpret_cast<const float4*>(Amu + base);
-      const float4 c4 = *reinterpret_cast<const float4*>(Ac + base);
-      kt.mu[4 * g] = m4.x - c4.x; kt.mu[4 * g + 1] = m4.y - c4.y;
-      kt.mu[4 * g + 2] = m4.z - c4.z; kt.mu[4 * g + 3] = m4.w - c4.w;
+      const float4 m4 = *reinterpret_cast<const float4*>(Amuq + base);
+      kt.mu[4 * g] = m4.x; kt.mu[4 * g + 1] = m4.y; kt.mu[4 * g + 2] = m4.z; kt.mu[4 * g + 3] = m4.w;
     }
   } else {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
-      jr = jr < Ck ? jr : Ck - 1;
-      float cc = Ac[(size_t)jr * DS];
-      if (DS == 2) cc += Ac[(size_t)jr * DS + 1];
-      kt.mu[e] = Amu[jr] - cc;
+      kt.mu[e] = Amuq[jr < Ck ? jr : Ck - 1];
     }
   }
 }
@@ -224,8 +218,8 @@ struct FFWorkspace {
   uint32_t* chainmask;  // [hc][Cq][ceil(Ck/32)]: key clusters retrieved by some query of the query cluster
   // Value summaries and every cell gradient are stored in the input type.  The accumulated k-bar decides
   // selections: fp32 inputs keep it in fp32 (A_k); bf16 inputs keep a bf16 plane A_kb (also the operand of the
-  // gradient contractions), an fp16 plane A_km of the remainder and the scalar A_c = scale * qc_i . k-bar per
-  // cell and 64-wide head-dim slice.
+  // gradient contractions), an fp16 plane A_km of the remainder and the scalar A_c = mu-bar - scale * qc_i . k-bar
+  // per cell.
   float *s_mu, *s_k, *A_mu, *A_k, *A_c;
   void *s_v, *A_v, *A_kb, *A_km;
   float *g_s_c, *g_A_c;
@@ -259,7 +253,7 @@ static inline size_t ff_head_bytes(const MuseDims& d, bool bwd) {
   size_t cells = (size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * d.Ck, D = d.D;
   size_t es = d.dtype == MUSE_DTYPE_BF16 ? 2 : 4;
   size_t b = ff_al((size_t)d.Cq * d.N * 4) + ff_al((size_t)d.Cq * ((d.Ck + 31) / 32) * 4) + 2 * ff_al(cells * 4) + ff_al(cells * D * 4) + 2 * ff_al(cells * D * es);
-  b += es == 2 ? 2 * ff_al(cells * D * 2) + ff_al(cells * (D / 64) * 4) : ff_al(cells * D * 4);
+  b += es == 2 ? 2 * ff_al(cells * D * 2) + ff_al(cells * 4) : ff_al(cells * D * 4);
   if (bwd) b += 2 * ff_al(cells * 4) + 4 * ff_al(cells * D * es);
   return b;
 }
