@@ -918,17 +918,33 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 // cluster j); the keys of the segment are the MFMA columns, 32 query clusters at a time the rows.
 //   W[i,m] = exp(L[i,m] - mu[i]),  T[i,m] = G_c[i] + G_k[i].k_m + G_v[i].v_m
 //   dv_m += sum_i W G_v[i],  dk_m += sum_i W G_k[i] + (W T) qbar_i
-// G and qbar are rounded to bf16 for the matrix cores (gradients only).
+// G and qbar are rounded to bf16 for the matrix cores (gradients only).  The gradient rows are read once, as
+// the row operands of T; for the contractions over i they go through a transposed tile in LDS, and qbar comes
+// from a transposed bf16 copy qcT[head][d][i] (scale folded in, i padded to a multiple of 32 with zeros).
 // ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_qc_transpose(const float* __restrict__ qc, bf16_t* __restrict__ qcT, int D,
+                                                       int Cq, int CqP, float scale) {
+  const int h = blockIdx.y;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= D * CqP) return;
+  const int d = t / CqP, i = t % CqP;
+  qcT[(size_t)h * D * CqP + t] = f32_to_bf16_bits(i < Cq ? scale * qc[((size_t)h * Cq + i) * D + d] : 0.f);
+}
+
 template <int D>
 __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
-                                                          const float* __restrict__ qc, const float* __restrict__ L,
+                                                          const bf16_t* __restrict__ qcT, const float* __restrict__ L,
                                                           const float* __restrict__ s_mu, const float* __restrict__ G_c,
                                                           const bf16_t* __restrict__ G_k, const bf16_t* __restrict__ G_v,
                                                           const int32_t* __restrict__ off_k, float* __restrict__ dKs,
-                                                          float* __restrict__ dVs, int h0, int N, int nb, int Cq, int Ck,
-                                                          int Hq, int Hkv, float scale) {
+                                                          float* __restrict__ dVs, int h0, int N, int nb, int Cq, int CqP,
+                                                          int Ck, int Hq, int Hkv) {
   constexpr int KS = D / 16, DT = D / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t gkT[D][32 + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gvT[D][32 + 8];
+  __shared__ __attribute__((aligned(16))) float mus[32];
+  __shared__ __attribute__((aligned(16))) float gcs[32];
+  __shared__ uint4 kbs[KS][64], vbs[KS][64];
   const int G_ = Hq / Hkv;
   const int hkl = blockIdx.z;
   const int hq0 = h0 + hkl * G_;
@@ -941,11 +957,12 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
     const int pm = m0 + col;
     const bool mvalid = pm < khi;
     const int pmc = mvalid ? pm : m0;
-    bf16x8_t kb[KS], vb[KS];
+    // the lane's key and value fragments wait in LDS (they are needed once per tile of query clusters)
+    wave_lds_fence();
 #pragma unroll
     for (int x = 0; x < KS; ++x) {
-      kb[x] = *reinterpret_cast<const bf16x8_t*>(Ks + ((size_t)hk * N + pmc) * D + 16 * x + 8 * half);
-      vb[x] = *reinterpret_cast<const bf16x8_t*>(Vs + ((size_t)hk * N + pmc) * D + 16 * x + 8 * half);
+      kbs[x][lane] = *reinterpret_cast<const uint4*>(Ks + ((size_t)hk * N + pmc) * D + 16 * x + 8 * half);
+      vbs[x][lane] = *reinterpret_cast<const uint4*>(Vs + ((size_t)hk * N + pmc) * D + 16 * x + 8 * half);
     }
     f32x16_t dk[DT], dv[DT];
 #pragma unroll
@@ -953,26 +970,70 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
 #pragma unroll
       for (int e = 0; e < 16; ++e) { dk[t][e] = 0.f; dv[t][e] = 0.f; }
     for (int g = 0; g < G_; ++g) {
-      const int hl = hkl * G_ + g, hq = h0 + hl;
-      for (int i0 = 0; i0 < Cq; i0 += 32) {
+      const int hl = hkl * G_ + g;
+      const bf16_t* qT = qcT + (size_t)hl * D * CqP;
+      const float* Lh = L + (size_t)hl * Cq * N + pmc;
+      // a tile's loads: the lane's gradient row (query cluster i0 + col), its scalars, the logits of the lane's
+      // key against the 16 query clusters of its accumulator rows, all issued before the first use
+      struct GT {
+        bf16x8_t gkr[KS], gvr[KS];
+        float mu, gc, lg[16];
+      };
+      auto load_gt = [&](GT& gt, int i0) {
         const int ic = i0 + col < Cq ? i0 + col : Cq - 1;
         const size_t cellA = (((size_t)hl * NBm + bp) * Cq + ic) * Ck + j;
-        f32x16_t tacc, wv;
-        size_t cellr[16];
+#pragma unroll
+        for (int x = 0; x < KS; ++x) {
+          gt.gkr[x] = *reinterpret_cast<const bf16x8_t*>(G_k + cellA * D + 16 * x + 8 * half);
+          gt.gvr[x] = *reinterpret_cast<const bf16x8_t*>(G_v + cellA * D + 16 * x + 8 * half);
+        }
+        gt.mu = s_mu[cellA];
+        gt.gc = G_c[cellA];
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           int ir = i0 + 8 * (e / 4) + 4 * half + (e % 4);
-          const bool iv = ir < Cq;
-          ir = iv ? ir : Cq - 1;
-          cellr[e] = (((size_t)hl * NBm + bp) * Cq + ir) * Ck + j;
-          tacc[e] = G_c[cellr[e]];
-          const float w = __expf(L[((size_t)hl * Cq + ir) * N + pmc] - s_mu[cellr[e]]);
-          wv[e] = (iv && mvalid) ? w : 0.f;
+          ir = ir < Cq ? ir : Cq - 1;
+          gt.lg[e] = Lh[(size_t)ir * N];
+        }
+      };
+      for (int i0 = 0; i0 < Cq; i0 += 32) {
+        GT cur;
+        load_gt(cur, i0);
+        const bf16x8_t(&gkr)[KS] = cur.gkr;
+        const bf16x8_t(&gvr)[KS] = cur.gvr;
+        const float mu_l = cur.mu, gc_l = cur.gc;
+        const float(&lg)[16] = cur.lg;
+        wave_lds_fence();  // the previous tile's operand reads are done
+        if (half == 0) { mus[col] = mu_l; gcs[col] = gc_l; }
+#pragma unroll
+        for (int x = 0; x < KS; ++x) {
+          const bf16_t* pk = reinterpret_cast<const bf16_t*>(&gkr[x]);
+          const bf16_t* pv = reinterpret_cast<const bf16_t*>(&gvr[x]);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            gkT[16 * x + 8 * half + e][col] = pk[e];
+            gvT[16 * x + 8 * half + e][col] = pv[e];
+          }
+        }
+        wave_lds_fence();
+        f32x16_t tacc, wv;
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const float4 m4 = *reinterpret_cast<const float4*>(&mus[8 * gq + 4 * half]);
+          const float4 c4 = *reinterpret_cast<const float4*>(&gcs[8 * gq + 4 * half]);
+          const float mv[4] = {m4.x, m4.y, m4.z, m4.w}, cv[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int e = 4 * gq + u;
+            const bool iv = i0 + 8 * gq + 4 * half + u < Cq;
+            tacc[e] = cv[u];
+            wv[e] = (iv && mvalid) ? __expf(lg[e] - mv[u]) : 0.f;
+          }
         }
 #pragma unroll
         for (int x = 0; x < KS; ++x) {
-          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(G_k + cellA * D + 16 * x + 8 * half), kb[x], tacc, 0, 0, 0);
-          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(G_v + cellA * D + 16 * x + 8 * half), vb[x], tacc, 0, 0, 0);
+          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gkr[x], __builtin_bit_cast(bf16x8_t, kbs[x][lane]), tacc, 0, 0, 0);
+          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gvr[x], __builtin_bit_cast(bf16x8_t, vbs[x][lane]), tacc, 0, 0, 0);
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) tacc[e] = wv[e] > 0.f ? wv[e] * tacc[e] : 0.f;
@@ -982,16 +1043,9 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
           bf16x8_t tf = pack8(tacc, 2 * G, 2 * G + 1);
 #pragma unroll
           for (int t = 0; t < DT; ++t) {
-            bf16x8_t ak, av, aq;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {  // k-slot u of this half = row 4*(2G + u/4) + u%4 of the accumulator
-              const int e = 4 * (2 * G + u / 4) + (u % 4);
-              int ir = i0 + 8 * (e / 4) + 4 * half + (e % 4);
-              ir = ir < Cq ? ir : Cq - 1;
-              ak[u] = bits_to_bf16(G_k[cellr[e] * D + 32 * t + col]);
-              av[u] = bits_to_bf16(G_v[cellr[e] * D + 32 * t + col]);
-              aq[u] = (__bf16)(scale * qc[((size_t)hq * Cq + ir) * D + 32 * t + col]);
-            }
+            const bf16x8_t ak = ld_tr8(&gkT[32 * t + col][0], 16 * G, half);
+            const bf16x8_t av = ld_tr8(&gvT[32 * t + col][0], 16 * G, half);
+            const bf16x8_t aq = ld_tr8(qT + (size_t)(32 * t + col) * CqP + i0, 16 * G, half);
             dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wf, dv[t], 0, 0, 0);
             dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, wf, dk[t], 0, 0, 0);
             dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, tf, dk[t], 0, 0, 0);
@@ -1019,14 +1073,17 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
 
 }  // namespace
 
-int muse_launch_cells_to_keys_mx(const MuseDims& d, const void* Ks, const void* Vs, const float* qc, const float* L,
-                                 const float* s_mu, const float* G_c, const void* G_k, const void* G_v,
+int muse_launch_cells_to_keys_mx(const MuseDims& d, const void* Ks, const void* Vs, const float* qc, void* qcT,
+                                 const float* L, const float* s_mu, const float* G_c, const void* G_k, const void* G_v,
                                  const int32_t* off_k, float* dKs, float* dVs, int h0, int hn, hipStream_t st) {
+  const int CqP = (d.Cq + 31) / 32 * 32;
+  // qcT holds the transposed centroids of the chunk's heads [h0, h0 + hn)
+  { MuseProf prof_("k_qc_transpose", st); hipLaunchKernelGGL(k_qc_transpose, dim3((d.D * CqP + 255) / 256, hn), dim3(256), 0, st, qc + (size_t)h0 * d.Cq * d.D, (bf16_t*)qcT, d.D, d.Cq, CqP, d.scale); }
   dim3 g(d.Ck, d.nb - 1, hn / (d.Hq / d.Hkv));
   if (d.D == 64)
-    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<64>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, qc, L, s_mu, G_c, (const bf16_t*)G_k, (const bf16_t*)G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv, d.scale); }
+    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<64>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, (const bf16_t*)qcT, L, s_mu, G_c, (const bf16_t*)G_k, (const bf16_t*)G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, CqP, d.Ck, d.Hq, d.Hkv); }
   else
-    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<128>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, qc, L, s_mu, G_c, (const bf16_t*)G_k, (const bf16_t*)G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv, d.scale); }
+    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<128>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, (const bf16_t*)qcT, L, s_mu, G_c, (const bf16_t*)G_k, (const bf16_t*)G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, CqP, d.Ck, d.Hq, d.Hkv); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }

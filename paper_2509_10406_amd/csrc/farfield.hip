@@ -852,6 +852,7 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
     w->dKs = (float*)take(HK * N * D * 4);
     w->dVs = (float*)take(HK * N * D * 4);
     w->dQff = (float*)take(HQ * N * D * 4);
+    w->qcT = take(HQ * D * (size_t)((d.Cq + 31) / 32 * 32) * 2);
     if (d.grad_dtype != MUSE_DTYPE_FP32) {
       w->dQacc = (float*)take(HQ * N * D * 4);
       w->dKacc = (float*)take(HK * N * D * 4);

@@ -1146,7 +1146,7 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
                      (T*)w.g_s_v, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.scale); }
   const int G_ = d.Hq / d.Hkv;
   if (sizeof(T) == 2) {
-    int rc2 = muse_launch_cells_to_keys_mx(d, w.Ks, w.Vs, qc, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs,
+    int rc2 = muse_launch_cells_to_keys_mx(d, w.Ks, w.Vs, qc, w.qcT, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs,
                                            h0, hn, st);
     if (rc2) return rc2;
   } else

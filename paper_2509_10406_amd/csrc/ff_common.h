@@ -213,6 +213,7 @@ struct FFWorkspace {
   float *dKs, *dVs;            // fp32 gradients in bucketed key order
   float *dQacc, *dKacc, *dVacc;  // fp32 gradients in sequence order (alias the outputs when they are fp32)
   float* dQff;                   // far-field part of dQ, added to dQacc once the block-diagonal backward has finished
+  void* qcT;                     // bf16 [hc][D][Cq padded to 32]: scaled query centroids of a head chunk, transposed
   // per chunk of `hc` query heads
   float* L;
   uint32_t* chainmask;  // [hc][Cq][ceil(Ck/32)]: key clusters retrieved by some query of the query cluster
@@ -243,7 +244,7 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
        ff_al(HQ * N * R2 * (D + 4) * 4);
   if (bwd) {
     b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + ff_al(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * 4) + 2 * ff_al(HK * N * D * 4) +
-         ff_al(HQ * N * D * 4);
+         ff_al(HQ * N * D * 4) + ff_al(HQ * D * (size_t)((d.Cq + 31) / 32 * 32) * 2);
     if (d.grad_dtype != MUSE_DTYPE_FP32) b += ff_al(HQ * N * D * 4) + 2 * ff_al(HK * N * D * 4);
   }
   return b;
@@ -282,8 +283,8 @@ int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO
                                 const void* A_kb, const void* A_v, const int32_t* perm_q, const int32_t* off_q,
                                 const float* LSE, const float* delta, const uint32_t* selmask, float* g_A_c,
                                 void* g_A_k, void* g_A_v, int h0, int hn, hipStream_t st);
-int muse_launch_cells_to_keys_mx(const MuseDims& d, const void* Ks, const void* Vs, const float* qc, const float* L,
-                                 const float* s_mu, const float* G_c, const void* G_k, const void* G_v,
+int muse_launch_cells_to_keys_mx(const MuseDims& d, const void* Ks, const void* Vs, const float* qc, void* qcT,
+                                 const float* L, const float* s_mu, const float* G_c, const void* G_k, const void* G_v,
                                  const int32_t* off_k, float* dKs, float* dVs, int h0, int hn, hipStream_t st);
 // retrieval.hip: pair bitmask + ordered hit lists from the exported selections; merge of the forward partials
 int muse_ff_build_inverse_index(const MuseDims& d, const int32_t* selc, const int32_t* selb, FFWorkspace& w,
