@@ -17,16 +17,20 @@
 namespace {
 
 constexpr int BN = 64;  // rows staged in LDS per step
+constexpr int TPAD = 4;  // padding of a transposed tile's rows: 34 dwords apart, conflict-free 8-byte operand reads
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// cooperative load of `rows` x D bf16 into a row-major tile (pad 8) and optionally a transposed one
+// cooperative load of `rows` x D bf16 into a row-major tile (pad 8) and optionally a transposed one.
+// Consecutive lanes take consecutive rows (one 16-byte chunk each): the 2-byte stores into the transposed tile
+// then fall into consecutive LDS banks, and the row-major 16-byte stores are 36 dwords apart, which is
+// conflict-free for the 16 lanes served together.
 template <int D, int ROWS, bool ROWM, bool TRANS>
 __device__ __forceinline__ void load_tile(const bf16_t* __restrict__ src, int r0, int N,
-                                          bf16_t (*rm)[D + 8], bf16_t (*tr)[ROWS + 8]) {
+                                          bf16_t (*rm)[D + 8], bf16_t (*tr)[ROWS + TPAD]) {
   constexpr int CPR = D / 8;
   for (int c = threadIdx.x; c < ROWS * CPR; c += 256) {
-    int row = c / CPR, cc = c % CPR;
+    int row = c % ROWS, cc = c / ROWS;
     int gr = r0 + row;
     gr = gr < N ? gr : N - 1;
     uint4 v = *reinterpret_cast<const uint4*>(src + (size_t)gr * D + cc * 8);
@@ -46,7 +50,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
                                                     int Hq, int Hkv, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(16))) bf16_t ks[BN][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t vt[D][BN + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t vt[D][BN + TPAD];
   const int hq = blockIdx.y, b = blockIdx.z, hk = hq / (Hq / Hkv);
   const size_t qh = ((size_t)b * Hq + hq) * N, kh = ((size_t)b * Hkv + hk) * N;
   const int q0 = (gridDim.x - 1 - blockIdx.x) * 128;  // long rows first
@@ -178,7 +182,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   constexpr int KS = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(16))) bf16_t ks[BN][D + 8];
   __shared__ __attribute__((aligned(16))) bf16_t vs[BN][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t kt_[D][BN + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t kt_[D][BN + TPAD];
   const int hq = blockIdx.y, b = blockIdx.z, hk = hq / (Hq / Hkv);
   const size_t qh = ((size_t)b * Hq + hq) * N, kh = ((size_t)b * Hkv + hk) * N;
   const int q0 = (gridDim.x - 1 - blockIdx.x) * 128;
@@ -260,8 +264,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   constexpr int BQ = D == 64 ? 64 : 32;  // queries staged per step (LDS budget)
   __shared__ __attribute__((aligned(16))) bf16_t qs[BQ][D + 8];
   __shared__ __attribute__((aligned(16))) bf16_t gs[BQ][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][BQ + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][BQ + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][BQ + TPAD];
+  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][BQ + TPAD];
   __shared__ __attribute__((aligned(16))) float lse_s[BQ];
   __shared__ __attribute__((aligned(16))) float dl_s[BQ];
   const int hk = blockIdx.y, b = blockIdx.z, G_ = Hq / Hkv;
