@@ -380,8 +380,8 @@ __global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, c
   constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
   __shared__ __attribute__((aligned(16))) bf16_t qs[32][D + 8];
   __shared__ __attribute__((aligned(16))) bf16_t gs[32][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][32 + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][32 + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][32 + TPAD];
+  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][32 + TPAD];
   __shared__ __attribute__((aligned(16))) float lse_s[32];
   __shared__ __attribute__((aligned(16))) float dl_s[32];
   const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
@@ -420,7 +420,7 @@ __global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, c
       float lv = 0.f, dv_ = 0.f;
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
-        const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+        const int c = lane + 64 * it, row = c % 32, cc = c / 32;  // lanes along the rows: conflict-free transposed stores
         const uint32_t hit = (uint32_t)__shfl((int)hitc, row, 64);
         const size_t qn = (hqbase + (hit >> 22)) * N + (hit & 0x3fffffu);
         qv[it] = *reinterpret_cast<const uint4*>(Q + qn * D + cc * 8);
@@ -434,7 +434,7 @@ __global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, c
       wave_lds_fence();
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
-        const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+        const int c = lane + 64 * it, row = c % 32, cc = c / 32;  // lanes along the rows: conflict-free transposed stores
         *reinterpret_cast<uint4*>(&qs[row][cc * 8]) = qv[it];
         *reinterpret_cast<uint4*>(&gs[row][cc * 8]) = gv[it];
         const bf16_t* pq = reinterpret_cast<const bf16_t*>(&qv[it]);
@@ -514,7 +514,7 @@ __global__ void __launch_bounds__(64) k_ret_fwd_pairs(const bf16_t* __restrict__
                                                        float* __restrict__ part, size_t hit_cap, int N, int nb, int Ck,
                                                        int Hq, int Hkv, int R2, int S, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32, CPR = D / 8, NIT = 32 * CPR / 64;
-  __shared__ __attribute__((aligned(16))) bf16_t vt[D][32 + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t vt[D][32 + TPAD];
   const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z / S, sl = blockIdx.z % S, NBm = nb - 1;
   const int G_ = Hq / Hkv;
   const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
@@ -531,7 +531,7 @@ __global__ void __launch_bounds__(64) k_ret_fwd_pairs(const bf16_t* __restrict__
     uint4 v[NIT];
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-      const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+      const int c = lane + 64 * it, row = c % 32, cc = c / 32;  // lanes along the rows: conflict-free transposed stores
       const int kr = k0 + row < khi ? k0 + row : khi - 1;
       v[it] = *reinterpret_cast<const uint4*>(Vs + ((size_t)hk * N + kr) * D + cc * 8);
     }
@@ -542,7 +542,7 @@ __global__ void __launch_bounds__(64) k_ret_fwd_pairs(const bf16_t* __restrict__
     wave_lds_fence();
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-      const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+      const int c = lane + 64 * it, row = c % 32, cc = c / 32;  // lanes along the rows: conflict-free transposed stores
       const bf16_t* pv = reinterpret_cast<const bf16_t*>(&v[it]);
 #pragma unroll
       for (int e = 0; e < 8; ++e) vt[cc * 8 + e][row] = pv[e];
@@ -634,7 +634,7 @@ __global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restric
                                                           size_t hit_cap, int N, int nb, int Ck, int Hq, int Hkv, int R2,
                                                           int S, float scale, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32, CPR = D / 8, NIT = 32 * CPR / 64;
-  __shared__ __attribute__((aligned(16))) bf16_t kt_[D][32 + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t kt_[D][32 + TPAD];
   const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z / S, sl = blockIdx.z % S, NBm = nb - 1;
   const int G_ = Hq / Hkv;
   const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
@@ -651,7 +651,7 @@ __global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restric
     uint4 v[NIT];
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-      const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+      const int c = lane + 64 * it, row = c % 32, cc = c / 32;  // lanes along the rows: conflict-free transposed stores
       const int kr = k0 + row < khi ? k0 + row : khi - 1;
       v[it] = *reinterpret_cast<const uint4*>(Ks + ((size_t)hk * N + kr) * D + cc * 8);
     }
@@ -664,7 +664,7 @@ __global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restric
     wave_lds_fence();
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-      const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+      const int c = lane + 64 * it, row = c % 32, cc = c / 32;  // lanes along the rows: conflict-free transposed stores
       const bf16_t* pv = reinterpret_cast<const bf16_t*>(&v[it]);
 #pragma unroll
       for (int e = 0; e < 8; ++e) kt_[cc * 8 + e][row] = pv[e];
@@ -750,8 +750,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   constexpr int KS = D / 16, DT = D / 32, CPR = D / 8, QR = 32 * QT;
   __shared__ __attribute__((aligned(16))) bf16_t qs[QR][D + 8];
   __shared__ __attribute__((aligned(16))) bf16_t gs[QR][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][QR + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][QR + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][QR + TPAD];
+  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][QR + TPAD];
   __shared__ __attribute__((aligned(16))) float ls[QR];
   __shared__ __attribute__((aligned(16))) float ds[QR];
   __shared__ uint32_t mws[4][QR];
@@ -788,7 +788,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     const bool first = q0 == qlo;
     __syncthreads();
     for (int c = threadIdx.x; c < (q0 < qhi ? QR * CPR : 0); c += 256) {
-      const int row = c / CPR, cc = c % CPR;
+      const int row = c % QR, cc = c / QR;  // lanes along the rows: conflict-free transposed stores
       const int pos = q0 + row < qhi ? q0 + row : q0;
       const size_t qn = (size_t)hq * N + perm_q[(size_t)hq * N + pos];
       uint4 qv = *reinterpret_cast<const uint4*>(Q + qn * D + cc * 8);
@@ -944,8 +944,8 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
                                                           float* __restrict__ dVs, int h0, int N, int nb, int Cq, int CqP,
                                                           int Ck, int Hq, int Hkv) {
   constexpr int KS = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t gkT[D][32 + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t gvT[D][32 + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gkT[D][32 + TPAD];
+  __shared__ __attribute__((aligned(16))) bf16_t gvT[D][32 + TPAD];
   __shared__ __attribute__((aligned(16))) float mus[32];
   __shared__ __attribute__((aligned(16))) float gcs[32];
   __shared__ uint4 kbs[KS][64], vbs[KS][64];

@@ -368,7 +368,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
   using VF = Frag<T, DT>;
   constexpr bool kH = sizeof(T) == 2;  // bf16 inputs: P V on bf16 MFMA through a transposed value tile in LDS
   constexpr int CPR = D / 8, NIT = 32 * CPR / 64;
-  __shared__ __attribute__((aligned(16))) bf16_t vt[kH ? D : 1][32 + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t vt[kH ? D : 1][32 + 4];
   __shared__ float cs[64][RCAP];
   __shared__ int ci[64][RCAP];
   __shared__ int sel_s[32][RCAP];
@@ -500,7 +500,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
     if constexpr (kH) {
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
-        const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+        const int c = lane + 64 * it, row = c % 32, cc = c / 32;  // lanes along the rows: conflict-free transposed stores
         const int jr = j0 + row < Ck ? j0 + row : Ck - 1;
         pt.vch[it] = *reinterpret_cast<const uint4*>(Av + (size_t)jr * D + cc * 8);
       }
@@ -554,7 +554,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
       wave_lds_fence();
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
-        const int c = lane + 64 * it, row = c / CPR, cc = c % CPR;
+        const int c = lane + 64 * it, row = c % 32, cc = c / 32;  // lanes along the rows: conflict-free transposed stores
         const bf16_t* pv = reinterpret_cast<const bf16_t*>(&vch[it]);
 #pragma unroll
         for (int e = 0; e < 8; ++e) vt[cc * 8 + e][row] = pv[e];
