@@ -43,6 +43,33 @@ __device__ __forceinline__ void load_tile(const bf16_t* __restrict__ src, int r0
   }
 }
 
+// the same in two halves, so that the global loads of the next tile are in flight while the current one is
+// consumed: fetch_tile into registers, commit_tile from registers into LDS
+template <int D, int ROWS>
+__device__ __forceinline__ void fetch_tile(const bf16_t* __restrict__ src, int r0, int N, uint4 (&reg)[ROWS * (D / 8) / 256]) {
+#pragma unroll
+  for (int it = 0; it < ROWS * (D / 8) / 256; ++it) {
+    const int c = threadIdx.x + 256 * it;
+    int gr = r0 + c % ROWS;
+    gr = gr < N ? gr : N - 1;
+    reg[it] = *reinterpret_cast<const uint4*>(src + (size_t)gr * D + (c / ROWS) * 8);
+  }
+}
+template <int D, int ROWS, bool ROWM, bool TRANS>
+__device__ __forceinline__ void commit_tile(const uint4 (&reg)[ROWS * (D / 8) / 256], bf16_t (*rm)[D + 8],
+                                            bf16_t (*tr)[ROWS + TPAD]) {
+#pragma unroll
+  for (int it = 0; it < ROWS * (D / 8) / 256; ++it) {
+    const int c = threadIdx.x + 256 * it, row = c % ROWS, cc = c / ROWS;
+    if (ROWM) *reinterpret_cast<uint4*>(&rm[row][cc * 8]) = reg[it];
+    if (TRANS) {
+      const bf16_t* pv = reinterpret_cast<const bf16_t*>(&reg[it]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) tr[cc * 8 + e][row] = pv[e];
+    }
+  }
+}
+
 template <int D>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2, D == 64 ? 4 : 2))) k_flash_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                     const bf16_t* __restrict__ V, const float* __restrict__ ff,
@@ -291,17 +318,29 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 
   for (int g = 0; g < G_; ++g) {
     const size_t qh = ((size_t)b * Hq + (size_t)hk * G_ + g) * N;
-    for (int q0 = k0; q0 < qend; q0 += BQ) {
-      __syncthreads();
-      load_tile<D, BQ, true, true>(Q + qh * D, q0, N, qs, qt_);
-      load_tile<D, BQ, true, true>(dO + qh * D, q0, N, gs, gt_);
+    uint4 qreg[BQ * (D / 8) / 256], greg[BQ * (D / 8) / 256];
+    float lreg = 0.f, dreg = 0.f;
+    auto fetch = [&](int q0) {
+      fetch_tile<D, BQ>(Q + qh * D, q0, N, qreg);
+      fetch_tile<D, BQ>(dO + qh * D, q0, N, greg);
       if (threadIdx.x < BQ) {
         int n = q0 + threadIdx.x;
         n = n < N ? n : N - 1;
-        lse_s[threadIdx.x] = LSE[qh + n] * 1.4426950408889634f;
-        dl_s[threadIdx.x] = delta[qh + n];
+        lreg = LSE[qh + n];
+        dreg = delta[qh + n];
+      }
+    };
+    if (k0 < qend) fetch(k0);
+    for (int q0 = k0; q0 < qend; q0 += BQ) {
+      __syncthreads();
+      commit_tile<D, BQ, true, true>(qreg, qs, qt_);
+      commit_tile<D, BQ, true, true>(greg, gs, gt_);
+      if (threadIdx.x < BQ) {
+        lse_s[threadIdx.x] = lreg * 1.4426950408889634f;
+        dl_s[threadIdx.x] = dreg;
       }
       __syncthreads();
+      if (q0 + BQ < qend) fetch(q0 + BQ);  // in flight while this tile is consumed
       if (q0 + BQ - 1 < k0 + 32 * wave) continue;  // every query of the tile precedes this wave's keys
 #pragma unroll
       for (int qt = 0; qt < BQ / 32; ++qt) {
