@@ -99,11 +99,18 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   float m = MUSE_NEG_INF, l = 0.f;
 
   const int kbeg = (q0 / Bs) * Bs, kend = min(q0 + 128, N);
+  uint4 kreg[BN * (D / 8) / 256], vreg[BN * (D / 8) / 256];
+  fetch_tile<D, BN>(K + kh * D, kbeg, N, kreg);
+  fetch_tile<D, BN>(V + kh * D, kbeg, N, vreg);
   for (int k0 = kbeg; k0 < kend; k0 += BN) {
     __syncthreads();
-    load_tile<D, BN, true, false>(K + kh * D, k0, N, ks, nullptr);
-    load_tile<D, BN, false, true>(V + kh * D, k0, N, nullptr, vt);
+    commit_tile<D, BN, true, false>(kreg, ks, nullptr);
+    commit_tile<D, BN, false, true>(vreg, nullptr, vt);
     __syncthreads();
+    if (k0 + BN < kend) {  // in flight while this tile is consumed
+      fetch_tile<D, BN>(K + kh * D, k0 + BN, N, kreg);
+      fetch_tile<D, BN>(V + kh * D, k0 + BN, N, vreg);
+    }
     if (k0 > q0 + 32 * wave + 31) continue;  // every key of the tile is in this wave's future
     f32x16_t s[2];
 #pragma unroll
