@@ -33,7 +33,9 @@ def kernel_models(w, p):
     Nff = N * (nb - 1) // nb           # queries that have a far field / keys that are summarised
     cells = (nb - 1) * Cq * Ck
     es = 2 if w.dtype == "bf16" else 4   # storage type of inputs, value summaries and cell gradients
-    cell_kv = cells * D * (4 + es) + cells * 4   # one copy of the summaries: k-bar fp32, v-bar, mu-bar
+    # the accumulated summaries of one head: k-bar (fp32, or a bf16 plane plus an fp16 remainder plane), v-bar,
+    # and the scalars (mu-bar of the block, accumulated mu-bar, the latter also with the centroid term folded in)
+    cell_kv = cells * D * (4 + es) + cells * (12 if es == 2 else 8)
     cell_g = cells * 2 * D * es + cells * 4      # one copy of the cell gradients (k, v, scalar)
     far = "mfma_bf16" if w.dtype == "bf16" else "mfma_fp32"   # gradient contractions of the far field
     pair_keys = Nff * r * k2e * (Bs / Ck)                     # (query, retrieved pair) x keys of an average pair
@@ -43,8 +45,13 @@ def kernel_models(w, p):
     m["k_flash_bwd_dkv"] = ("mfma", PEAK["mfma_bf16"], 4 * N * Bs * D * H, "flop")       # S, dP, dV, dK
     # k-means assignment: one launch per tensor per pass; report the key launch (larger C)
     m["k_assign_bf16"] = ("mfma", PEAK["mfma_bf16"], 2 * N * Ck * D * Hk, "flop")
-    # forward tile kernel: cluster scores (fp32, they decide the selection) + monopole PV
-    m["k_farfield_fwd"] = ("mfma", PEAK["mfma_fp32"], 2 * 2 * Nff * Ck * D * H, "flop")
+    # forward tile kernel: two passes over k-bar (scores for the selection, then scores again + monopole PV).
+    # bf16 inputs: the scores run on 16-bit MFMA and the kernel streams each (block, query cluster) group's
+    # summaries once per pass; fp32 inputs: fp32 MFMA decides
+    if es == 2:
+        m["k_farfield_fwd"] = ("hbm", PEAK["hbm"], (cells * (2 * 2 * D * 2 + D * es + 2 * 4) + 2 * Nff * D * 4) * H, "byte")
+    else:
+        m["k_farfield_fwd"] = ("mfma", PEAK["mfma_fp32"], 2 * 2 * Nff * Ck * D * H, "flop")
     for name, nmm in (("k_ff_bwd_dq", 3), ("k_ff_bwd_cells_mx", 4), ("k_ff_bwd_cells", 4)):
         m[name] = ("mfma", PEAK[far], nmm * 2 * Nff * Ck * D * H, "flop")
     for name in ("k_cells_to_keys_mx", "k_cells_to_keys"):
@@ -52,10 +59,9 @@ def kernel_models(w, p):
     m["k_ret_fwd_pairs"] = ("mfma", PEAK["mfma_bf16"], 2 * 2 * pair_keys * D * H, "flop")
     m["k_ret_bwd_dq_pairs"] = ("mfma", PEAK["mfma_bf16"], 3 * 2 * pair_keys * D * H, "flop")
     m["k_c3_pairs"] = ("mfma", PEAK["mfma_bf16"], 4 * 2 * pair_keys * D * H, "flop")
-    # writes both copies of the summaries (per block, accumulated) and, for bf16 inputs, the bf16 copy of the
-    # accumulated k-bar; reads the tilt logits and K, V once
-    m["k_summaries"] = ("hbm", PEAK["hbm"], (2 * cell_kv + (cells * D * 2 if es == 2 else 0) + Cq * Nff * 4
-                                              + 2 * Nff * D * es) * H, "byte")
+    # writes the accumulated summaries (the per-block ones follow, for retrieved chains only, in
+    # k_block_summaries); reads the tilt logits and K, V once per tile of 32 query clusters
+    m["k_summaries"] = ("hbm", PEAK["hbm"], (cell_kv + Cq * Nff * 4 + 2 * Nff * D * es) * H, "byte")
     # reads the gradients of the accumulated cells and mu of both copies, writes the gradients of the per-block cells
     m["k_cell_grads"] = ("hbm", PEAK["hbm"], (2 * cell_g + 2 * cells * 4) * H, "byte")
     m["k_tilt_logits"] = ("hbm", PEAK["hbm"], (Cq * N * 4 + N * D * es) * H, "byte")
