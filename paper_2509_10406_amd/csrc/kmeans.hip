@@ -296,26 +296,43 @@ __global__ void __launch_bounds__(256) k_update(const T* __restrict__ X, const i
   float acc[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+  // a row slot takes every slots-th spatial block and walks its members four at a time (positions, then rows:
+  // two round trips for four members)
   int count = 0;
-  for (int b = 0; b < nb; ++b) {
-    int lo = oh[b * C + j], hi = oh[b * C + j + 1];
+  for (int b = slot; b < nb; b += slots) {
+    const int lo = oh[b * C + j], hi = oh[b * C + j + 1];
     count += hi - lo;
-    for (int p = lo + slot; p < hi; p += slots) {
-      int row = ph[p];
-      if constexpr (EPL == 8) {
-        uint4 v = *reinterpret_cast<const uint4*>(Xh + (size_t)row * D + chunk * 8);
-        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    for (int p = lo; p < hi; p += 4) {
+      int row[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          acc[2 * e] += __uint_as_float(w[e] << 16);
-          acc[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+      for (int u = 0; u < 4; ++u) row[u] = ph[p + u < hi ? p + u : hi - 1];
+      if constexpr (EPL == 8) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(Xh + (size_t)row[u] * D + chunk * 8);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (p + u >= hi) continue;
+          const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[2 * e] += __uint_as_float(w[e] << 16);
+            acc[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+          }
         }
       } else {
-        float4 v = *reinterpret_cast<const float4*>(Xh + (size_t)row * D + chunk * 4);
-        acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(Xh + (size_t)row[u] * D + chunk * 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (p + u >= hi) continue;
+          acc[0] += v[u].x; acc[1] += v[u].y; acc[2] += v[u].z; acc[3] += v[u].w;
+        }
       }
     }
   }
+  for (int o = RL; o < 64; o <<= 1) count += __shfl_xor(count, o, 64);
   for (int o = RL; o < 64; o <<= 1)
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
