@@ -518,90 +518,25 @@ __global__ void __launch_bounds__(64) k_ff_bwd_cells(
 }
 
 // ------------------------------------------------------------------------------------------
-// Gradients of the per-block cells, finished: one block of 256 threads per (query cluster i, tile of 32
-// key clusters); wave w owns the 8 chains (i, j, all blocks), j = 32 jt + 8 w + c.  A wave is 8 groups of
-// 8 lanes; a lane holds D/8 elements of a row (d = 32 x + 4 l8 + t); group c owns chain c.
-//   phase 1, reverse accumulation over the key blocks a = nb-2 .. 0, in registers:
+// Gradients of the per-block cells from those of the accumulated cells: one block of 256 threads per (query
+// cluster i, tile of 32 key clusters); wave w owns the 8 chains (i, j, all blocks), j = 32 jt + 8 w + c.  A
+// wave is 8 groups of 8 lanes; a lane holds D/8 elements of a row (d = 32 x + 4 l8 + t); group c owns chain c.
+// Reverse accumulation over the key blocks a = nb-2 .. 0, in registers:
 //      R[a] = gA[a] + exp(Amu[a] - Amu[a+1]) R[a+1],   G[a] = exp(mu[a] - Amu[a]) R[a]   (written out)
-//   phase 2, component 2: every query of cluster i in a later block that retrieved cluster j but not
-//      block a adds  g_k += dl q~,  g_v += p dO,  g_c += dl (1 - q~.kbar) - p dO.vbar  to G[a] of the chain.
-//      Few chains have such queries at all (about one in ten), and those that do have many.  For one chain,
-//      group g takes key block a = g, so the loads of all its blocks are one round trip, walks the chain's
-//      entries (rows staged in LDS) and adds its sum to the row of (chain, a) written in phase 1.
-// The queries that retrieved a chain are listed once per block of threads, in bucketed order, by a
-// counting sort on wave ballots: (position n, block of n, bitmask of the retrieved key blocks); the
-// listing's loads are issued before phase 1.
-// All factors are <= 1.  No zero-fill, no atomics, one owner per cell: the order of every sum is fixed.
+// All factors are <= 1.  One owner per cell.  Component 2 is added afterwards by k_chain_grads.
 // ------------------------------------------------------------------------------------------
 template <typename T, int D>
 __global__ void __launch_bounds__(256) k_cell_grads(
-    const T* __restrict__ Q, const T* __restrict__ dO, const float* __restrict__ qc, const float* __restrict__ s_mu,
-    const float* __restrict__ s_k, const T* __restrict__ s_v, const float* __restrict__ A_mu,
-    const float* __restrict__ g_A_c, const T* __restrict__ g_A_k, const T* __restrict__ g_A_v,
-    const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q, const float* __restrict__ LSE,
-    const float* __restrict__ delta, const uint32_t* __restrict__ selmask, const int32_t* __restrict__ slotinfo,
-    float* __restrict__ G_c, T* __restrict__ G_k, T* __restrict__ G_v, int h0, int N, int nb, int Bs, int Cq, int Ck,
-    int r, float scale) {
+    const float* __restrict__ s_mu, const float* __restrict__ A_mu, const float* __restrict__ g_A_c,
+    const T* __restrict__ g_A_k, const T* __restrict__ g_A_v, float* __restrict__ G_c, T* __restrict__ G_k,
+    T* __restrict__ G_v, int nb, int Cq, int Ck) {
   constexpr int NV = D / 32;
-  constexpr int POOL = 2048;
-  constexpr int ECACHE = 16384 / (D * (int)sizeof(T));  // entries staged at a time (2 x 16 KB of rows)
   using F4 = Frag<T, 4>;
-  __shared__ int2 pool[POOL];
-  __shared__ __attribute__((aligned(16))) T qS[ECACHE][D];
-  __shared__ __attribute__((aligned(16))) T gS[ECACHE][D];
-  __shared__ float2 ldS[ECACHE];  // (LSE, delta)
-  __shared__ int cnt[4][32];
-  __shared__ int wbase[4][32];
-  __shared__ int off[33];
-  __shared__ int cum[18];  // cum[b] = queries of cluster i in blocks 1 .. b-1
-  const int hl = blockIdx.z, hq = h0 + hl;
+  const int hl = blockIdx.z;
   const int i = blockIdx.y, jt = blockIdx.x;
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, s8 = lane / 8, l8 = lane % 8;
-  const int NBm = nb - 1, W = (Ck + 31) / 32;
-  const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
-  const int CH = r > 0 ? (POOL / r < 256 ? POOL / r : 256) : 256;  // queries listed per pass: at most POOL entries
+  const int NBm = nb - 1;
 
-  if (tid < 33) off[tid] = 0;
-  if (tid == 0) {
-    int run = 0;
-    cum[0] = 0;
-    cum[1] = 0;
-    for (int b = 1; b < nb; ++b) {
-      run += oq[b * Cq + i + 1] - oq[b * Cq + i];
-      cum[b + 1] = run;
-    }
-  }
-  __syncthreads();
-  const int Tq = r > 0 ? cum[nb] : 0;
-  const int nchunks = (Tq + CH - 1) / CH;
-
-  // the listing's inputs of one pass: position, its word of the selection mask, its first 8 slots
-  struct QIn {
-    int n, pq;
-    uint32_t word;
-    int info[8];
-  };
-  auto load_qin = [&](int ch, QIn& qi) {
-    const int idx = ch * CH + tid;
-    qi.n = 0; qi.pq = 0; qi.word = 0;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) qi.info[t] = -1;
-    if (tid < CH && idx < Tq) {
-      int b = 1;
-      while (idx >= cum[b + 1]) ++b;
-      qi.pq = oq[b * Cq + i] + idx - cum[b];
-      qi.n = perm_q[(size_t)hq * N + qi.pq];
-      qi.word = selmask[((size_t)hq * W + jt) * N + qi.pq];
-      const int32_t* si = slotinfo + ((size_t)hq * N + qi.pq) * r;
-#pragma unroll
-      for (int t = 0; t < 8; ++t)
-        if (t < r) qi.info[t] = si[t];
-    }
-  };
-  QIn qin;
-  if (nchunks > 0) load_qin(0, qin);  // in flight during phase 1
-
-  // ---- phase 1: reverse accumulation of the chain owned by this group ----
   const int jown = jt * 32 + 8 * wave + s8;
   const bool jok = jown < Ck;
   {
@@ -656,113 +591,154 @@ __global__ void __launch_bounds__(256) k_cell_grads(
       }
     }
   }
-  if (nchunks == 0) return;
+}
 
-  // ---- phase 2: component 2 ----
+// ------------------------------------------------------------------------------------------
+// Component 2 of the per-block cell gradients: every query of cluster i in a later block that retrieved
+// cluster j but not block a adds  g_k += dl q~,  g_v += p dO,  g_c += dl (1 - q~.kbar) - p dO.vbar  to the
+// cell (a, i, j) that k_cell_grads wrote.  One block of 256 threads per (head, query cluster i): it takes the
+// cluster's queries (bucketed order, blocks >= 1) a chunk at a time, stages their Q and dO rows, LSE and delta
+// in LDS once, lists the (query, slot) entries by chain j with a counting sort over all Ck chains, and gives
+// each non-empty chain to a wave.  About one chain in ten has entries, and those that do have many.  For a
+// chain, the 8-lane group g takes key block a = g, so that the loads of all its blocks are one round trip; a
+// lane holds D/8 elements of a row (d = 32 x + 4 l8 + t).  The counting sort places entries in arrival order;
+// the wave that owns a chain then orders them by query, so every sum has a fixed order.  One owner per cell
+// (chain j -> wave (j / 64) % 4, block a -> group): no atomics on floats.
+// ------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ void __launch_bounds__(256) k_chain_grads(
+    const T* __restrict__ Q, const T* __restrict__ dO, const float* __restrict__ qc, const float* __restrict__ s_mu,
+    const float* __restrict__ s_k, const T* __restrict__ s_v, const int32_t* __restrict__ perm_q,
+    const int32_t* __restrict__ off_q, const float* __restrict__ LSE, const float* __restrict__ delta,
+    const int32_t* __restrict__ slotinfo, float* __restrict__ G_c, T* __restrict__ G_k, T* __restrict__ G_v, int h0,
+    int N, int nb, int Bs, int Cq, int Ck, int r, float scale) {
+  constexpr int NV = D / 32;
+  constexpr int POOL = 1024;                                   // entries per chunk
+  constexpr int CHB = 32768 / (2 * D * (int)sizeof(T));        // queries whose rows fit 32 KB
+  constexpr int CHMAX = CHB < 128 ? CHB : 128;                 // at most two entries of a chain per lane
+  using F4 = Frag<T, 4>;
+  __shared__ int2 pool[POOL];                                  // x = query of the chunk, y = its block << 16 | retrieved blocks
+  __shared__ __attribute__((aligned(16))) T qS[CHMAX][D];
+  __shared__ __attribute__((aligned(16))) T gS[CHMAX][D];
+  __shared__ float2 ldS[CHMAX];                                // (LSE, delta)
+  __shared__ int nS[CHMAX];
+  __shared__ int bins[kMaxCk + 1];
+  __shared__ int wsum[4];
+  __shared__ int cum[18];                                      // cum[b] = queries of cluster i in blocks 1 .. b-1
+  const int hl = blockIdx.y, hq = h0 + hl, i = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, s8 = lane / 8, l8 = lane % 8;
+  const int NBm = nb - 1;
+  const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
+  const int CH = POOL / r < CHMAX ? POOL / r : CHMAX;          // queries per chunk
+  if (tid == 0) {
+    int run = 0;
+    cum[0] = 0;
+    cum[1] = 0;
+    for (int b = 1; b < nb; ++b) {
+      run += oq[b * Cq + i + 1] - oq[b * Cq + i];
+      cum[b + 1] = run;
+    }
+  }
+  __syncthreads();
+  const int Tq = cum[nb];
   float qcv[NV][4];
 #pragma unroll
   for (int x = 0; x < NV; ++x) {
     float4 c4 = *reinterpret_cast<const float4*>(qc + ((size_t)hq * Cq + i) * D + 32 * x + 4 * l8);
     qcv[x][0] = c4.x; qcv[x][1] = c4.y; qcv[x][2] = c4.z; qcv[x][3] = c4.w;
   }
-  const int jl0 = 8 * wave;
-  for (int ch = 0; ch < nchunks; ++ch) {
-    if (ch > 0) {
-      __syncthreads();  // the pool is rebuilt
-      load_qin(ch, qin);
-    }
-    // -- chain lists: counting sort of the (query, chain) hits by chain, stable in the bucketed order
-    // the chains present in this wave's 64 queries (typically a handful of the 32): only those are ranked
-    uint32_t present = 0;
-    {
-      unsigned long long nz = __ballot(qin.word != 0u);
-      while (nz) {
-        const int src = __ffsll((long long)nz) - 1;
-        nz &= nz - 1;
-        present |= (uint32_t)__builtin_amdgcn_readlane((int)qin.word, src);
-      }
-    }
-    if (lane < 32) cnt[wave][lane] = 0;
-    for (uint32_t u = present; u; u &= u - 1) {
-      const int c = __ffs((int)u) - 1;
-      const unsigned long long bal = __ballot((qin.word >> c) & 1u);
-      if (lane == 0) cnt[wave][c] = __popcll(bal);
+  for (int c0 = 0; c0 < Tq; c0 += CH) {
+    const int nq = Tq - c0 < CH ? Tq - c0 : CH;
+    __syncthreads();  // the previous chunk is consumed
+    for (int t = tid; t <= Ck; t += 256) bins[t] = 0;
+    // this thread's query: position, block, slots
+    int mybq = 0;
+    int info[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) info[t] = -1;
+    const int32_t* si = slotinfo;
+    if (tid < nq) {
+      const int idx = c0 + tid;
+      int b = 1;
+      while (idx >= cum[b + 1]) ++b;
+      const int pq = oq[b * Cq + i] + idx - cum[b];
+      const int n = perm_q[(size_t)hq * N + pq];
+      mybq = b;
+      si = slotinfo + ((size_t)hq * N + pq) * r;
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        if (t < r) info[t] = si[t];
+      nS[tid] = n;
+      ldS[tid] = make_float2(LSE[(size_t)hq * N + n], delta[(size_t)hq * N + n]);
     }
     __syncthreads();
-    if (tid < 32) {
-      int tot = 0;
+    if (tid < nq) {
+      for (int t = 0; t < r; ++t) {
+        const int x = t < 8 ? info[t] : si[t];
+        if (x >= 0) atomicAdd(&bins[x & 0xffff], 1);
+      }
+    }
+    {
+      constexpr int CPR = D * (int)sizeof(T) / 16;
+      for (int idx = tid; idx < nq * CPR; idx += 256) {
+        const int e = idx / CPR, cc = idx % CPR;
+        const size_t qn = (size_t)hq * N + nS[e];
+        reinterpret_cast<uint4*>(&qS[e][0])[cc] = reinterpret_cast<const uint4*>(Q + qn * D)[cc];
+        reinterpret_cast<uint4*>(&gS[e][0])[cc] = reinterpret_cast<const uint4*>(dO + qn * D)[cc];
+      }
+    }
+    __syncthreads();
+    // exclusive scan of the chain counts: bins[j] becomes the cursor of chain j
+    {
+      const int per = (Ck + 255) / 256, base = tid * per;
+      int loc = 0;
+      for (int k = 0; k < per; ++k) loc += base + k < Ck ? bins[base + k] : 0;
+      int incl = loc;
 #pragma unroll
-      for (int w_ = 0; w_ < 4; ++w_) { const int v = cnt[w_][tid]; cnt[w_][tid] = tot; tot += v; }
-      int incl = tot;
-#pragma unroll
-      for (int o = 1; o < 32; o <<= 1) {
+      for (int o = 1; o < 64; o <<= 1) {
         const int v = __shfl_up(incl, o, 64);
-        if (tid >= o) incl += v;
+        if (lane >= o) incl += v;
       }
-      const int excl = incl - tot;
-      off[tid] = excl;
-      if (tid == 31) off[32] = incl;
-#pragma unroll
-      for (int w_ = 0; w_ < 4; ++w_) wbase[w_][tid] = cnt[w_][tid] + excl;
-    }
-    __syncthreads();
-    {
-      const int bq = qin.pq / Bs;  // bucketed order is block-major
-      for (uint32_t u = present; u; u &= u - 1) {
-        const int c = __ffs((int)u) - 1;
-        const bool bit = (qin.word >> c) & 1u;
-        const unsigned long long bal = __ballot(bit);
-        if (bit) {
-          const int want = jt * 32 + c;
-          int v = -1;
-#pragma unroll
-          for (int t = 0; t < 8; ++t) v = (qin.info[t] >= 0 && (qin.info[t] & 0xffff) == want) ? qin.info[t] : v;
-          if (v < 0) {
-            const int32_t* si = slotinfo + ((size_t)hq * N + qin.pq) * r;
-            for (int t = 8; t < r; ++t) {
-              const int x = si[t];
-              if (x >= 0 && (x & 0xffff) == want) v = x;
-            }
-          }
-          pool[wbase[wave][c] + __popcll(bal & ((1ull << lane) - 1ull))] =
-              make_int2(qin.n, (int)(((uint32_t)bq << 16) | ((uint32_t)v >> 16)));
-        }
-      }
-    }
-    __syncthreads();
-    // -- component 2, ECACHE entries at a time: their Q and dO rows, LSE and delta are staged in LDS; for a
-    //    chain, group g takes key block a = g (all blocks of the chain in flight together: one round trip),
-    //    walks the chain's staged entries and adds its sum to the row written in phase 1
-    const int total = off[32];
-    for (int r0 = 0; r0 < total; r0 += ECACHE) {
-      const int nst = total - r0 < ECACHE ? total - r0 : ECACHE;
-      if (r0 > 0) __syncthreads();
-      {
-        constexpr int CPR = D * (int)sizeof(T) / 16;
-        for (int idx = tid; idx < nst * CPR; idx += 256) {
-          const int e = idx / CPR, cc = idx % CPR;
-          const size_t qn = (size_t)hq * N + pool[r0 + e].x;
-          reinterpret_cast<uint4*>(&qS[e][0])[cc] = reinterpret_cast<const uint4*>(Q + qn * D)[cc];
-          reinterpret_cast<uint4*>(&gS[e][0])[cc] = reinterpret_cast<const uint4*>(dO + qn * D)[cc];
-        }
-        if (tid < nst) {
-          const size_t qn = (size_t)hq * N + pool[r0 + tid].x;
-          ldS[tid] = make_float2(LSE[qn], delta[qn]);
-        }
-      }
+      if (lane == 63) wsum[wave] = incl;
       __syncthreads();
-      for (int c = 0; c < 8; ++c) {
-        const int e0 = off[jl0 + c] > r0 ? off[jl0 + c] : r0;
-        const int e1 = off[jl0 + c + 1] < r0 + nst ? off[jl0 + c + 1] : r0 + nst;
-        if (e0 >= e1) continue;
+      int run = incl - loc;
+      for (int w_ = 0; w_ < wave; ++w_) run += wsum[w_];
+      for (int k = 0; k < per; ++k) {
+        if (base + k < Ck) {
+          const int c = bins[base + k];
+          bins[base + k] = run;
+          run += c;
+        }
+      }
+    }
+    __syncthreads();
+    if (tid < nq) {
+      for (int t = 0; t < r; ++t) {
+        const int x = t < 8 ? info[t] : si[t];
+        if (x >= 0) pool[atomicAdd(&bins[x & 0xffff], 1)] = make_int2(tid, (int)(((uint32_t)mybq << 16) | ((uint32_t)x >> 16)));
+      }
+    }
+    __syncthreads();
+    // chain j now is pool[bins[j-1] .. bins[j])
+    for (int jb = 64 * wave; jb < Ck; jb += 256) {
+      const int jmine = jb + lane;
+      const int e1m = jmine < Ck ? bins[jmine] : 0;
+      const int e0m = jmine < Ck ? (jmine > 0 ? bins[jmine - 1] : 0) : 0;
+      unsigned long long todo = __ballot(e1m > e0m);
+      while (todo) {
+        const int src = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        const int j = jb + src;
+        const int e0 = __builtin_amdgcn_readlane(e0m, src), e1 = __builtin_amdgcn_readlane(e1m, src);
+        const int ne = e1 - e0;
         for (int a0 = 0; a0 < NBm; a0 += 8) {
           const int a = a0 + s8;
           const bool act = a < NBm;
-          const size_t cell = (((size_t)hl * NBm + (act ? a : 0)) * Cq + i) * Ck + jt * 32 + jl0 + c;
+          const size_t cell = (((size_t)hl * NBm + (act ? a : 0)) * Cq + i) * Ck + j;
           const float mu = s_mu[cell];  // an empty cell has mu = -inf and zero rows: p = 0, nothing is added
           float4 kv[NV];
           float vv[NV][4];
-          typename F4::raw ogk[NV], ogv[NV];  // the row written in phase 1
+          typename F4::raw ogk[NV], ogv[NV];  // the row written by k_cell_grads
           const float ogc = G_c[cell];
 #pragma unroll
           for (int x = 0; x < NV; ++x) {
@@ -770,6 +746,23 @@ __global__ void __launch_bounds__(256) k_cell_grads(
             ld4(s_v, cell * D + 32 * x + 4 * l8, vv[x]);
             ogk[x] = F4::ld(G_k, cell * D + 32 * x + 4 * l8);
             ogv[x] = F4::ld(G_v, cell * D + 32 * x + 4 * l8);
+          }
+          if (a0 == 0 && ne > 1) {
+            // order the chain's entries by query (each lane ranks up to two of them against all)
+            int2 mine[2];
+            int rank[2] = {0, 0};
+#pragma unroll
+            for (int u = 0; u < 2; ++u) mine[u] = e0 + lane + 64 * u < e1 ? pool[e0 + lane + 64 * u] : make_int2(0x7fffffff, 0);
+            for (int e = e0; e < e1; ++e) {
+              const int k = pool[e].x;
+              rank[0] += k < mine[0].x;
+              rank[1] += k < mine[1].x;
+            }
+            wave_lds_fence();
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+              if (e0 + lane + 64 * u < e1) pool[e0 + rank[u]] = mine[u];
+            wave_lds_fence();
           }
           float gk[NV][4], gv[NV][4], gc = 0.f;
 #pragma unroll
@@ -784,10 +777,10 @@ __global__ void __launch_bounds__(256) k_cell_grads(
             float qv[NV][4], dv[NV][4];
 #pragma unroll
             for (int x = 0; x < NV; ++x) {
-              ld4(&qS[e - r0][0], 32 * x + 4 * l8, qv[x]);
-              ld4(&gS[e - r0][0], 32 * x + 4 * l8, dv[x]);
+              ld4(&qS[en.x][0], 32 * x + 4 * l8, qv[x]);
+              ld4(&gS[en.x][0], 32 * x + 4 * l8, dv[x]);
             }
-            const float2 ld2 = ldS[e - r0];
+            const float2 ld2 = ldS[en.x];
             float part = 0.f, dpp = 0.f;
 #pragma unroll
             for (int x = 0; x < NV; ++x) {
@@ -1141,9 +1134,13 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
   { MuseProf prof_("k_ff_bwd_cells", st); hipLaunchKernelGGL((k_ff_bwd_cells<T, D>), dim3(W, NBm * d.Cq, hn), dim3(64), 0, st, Q, dO, qc, w.A_mu, w.A_k, (const float*)w.A_v,
                      w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.g_A_c, (float*)w.g_A_k, (float*)w.g_A_v, h0, d.N, d.nb, d.Cq, d.Ck,
                      d.scale); }
-  { MuseProf prof_("k_cell_grads", st); hipLaunchKernelGGL((k_cell_grads<T, D>), dim3(W, d.Cq, hn), dim3(256), 0, st, Q, dO, qc, w.s_mu, w.s_k, (const T*)w.s_v, w.A_mu,
-                     w.g_A_c, (const T*)w.g_A_k, (const T*)w.g_A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask, w.slotinfo, w.g_s_c, (T*)w.g_s_k,
-                     (T*)w.g_s_v, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.scale); }
+  { MuseProf prof_("k_cell_grads", st); hipLaunchKernelGGL((k_cell_grads<T, D>), dim3(W, d.Cq, hn), dim3(256), 0, st, w.s_mu, w.A_mu, w.g_A_c,
+                     (const T*)w.g_A_k, (const T*)w.g_A_v, w.g_s_c, (T*)w.g_s_k, (T*)w.g_s_v, d.nb, d.Cq, d.Ck); }
+  if (d.r > 0 && d.Ck > kMaxCk) return MUSE_ERR_UNSUPPORTED;
+  if (d.r > 0)
+    { MuseProf prof_("k_chain_grads", st); hipLaunchKernelGGL((k_chain_grads<T, D>), dim3(d.Cq, hn), dim3(256), 0, st, Q, dO, qc, w.s_mu, w.s_k,
+                       (const T*)w.s_v, w.perm_q, w.off_q, LSE, w.delta, w.slotinfo, w.g_s_c, (T*)w.g_s_k, (T*)w.g_s_v, h0, d.N,
+                       d.nb, d.Bs, d.Cq, d.Ck, d.r, d.scale); }
   const int G_ = d.Hq / d.Hkv;
   if (sizeof(T) == 2) {
     int rc2 = muse_launch_cells_to_keys_mx(d, w.Ks, w.Vs, qc, w.qcT, w.L, w.s_mu, w.g_s_c, w.g_s_k, w.g_s_v, w.off_k, w.dKs, w.dVs,

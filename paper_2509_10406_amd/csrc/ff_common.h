@@ -193,6 +193,7 @@ __device__ __forceinline__ bf16x8_t cvt8(const float* __restrict__ p) {
 }
 
 
+constexpr int kMaxCk = 2304;  // key clusters a kernel can index in LDS (the bucketing kernel's own limit is lower)
 constexpr int kHitSeg = 8;  // query-range slices per (pair, head) when the hit lists are built
 
 struct FFWorkspace {
