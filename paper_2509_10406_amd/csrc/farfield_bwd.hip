@@ -770,42 +770,60 @@ __global__ void __launch_bounds__(256) k_chain_grads(
 #pragma unroll
             for (int t = 0; t < 4; ++t) { gk[x][t] = 0.f; gv[x][t] = 0.f; }
           bool any = false;
-          for (int e = e0; e < e1; ++e) {
-            const int2 en = pool[e];
-            if (!act || (en.y >> 16) <= a || ((en.y >> a) & 1)) continue;
+          // two entries per step: their LDS reads and 8-lane reductions are independent and overlap
+          for (int e = e0; e < e1; e += 2) {
+            int2 en[2];
+            bool use[2];
+#pragma unroll
+            for (int z = 0; z < 2; ++z) {
+              en[z] = e + z < e1 ? pool[e + z] : make_int2(0, 0);  // block 0: precedes no key block
+              use[z] = act && (en[z].y >> 16) > a && !((en[z].y >> a) & 1);
+            }
+            if (!use[0] && !use[1]) continue;
             any = true;
-            float qv[NV][4], dv[NV][4];
+            float qv[2][NV][4], dv[2][NV][4];
+            float2 ld2[2];
+            float part[2] = {0.f, 0.f}, dpp[2] = {0.f, 0.f};
 #pragma unroll
-            for (int x = 0; x < NV; ++x) {
-              ld4(&qS[en.x][0], 32 * x + 4 * l8, qv[x]);
-              ld4(&gS[en.x][0], 32 * x + 4 * l8, dv[x]);
-            }
-            const float2 ld2 = ldS[en.x];
-            float part = 0.f, dpp = 0.f;
+            for (int z = 0; z < 2; ++z) {
 #pragma unroll
-            for (int x = 0; x < NV; ++x) {
-#pragma unroll
-              for (int t = 0; t < 4; ++t) qv[x][t] = scale * (qv[x][t] - qcv[x][t]);
-              part = fmaf(qv[x][0], kv[x].x, part); part = fmaf(qv[x][1], kv[x].y, part);
-              part = fmaf(qv[x][2], kv[x].z, part); part = fmaf(qv[x][3], kv[x].w, part);
-              dpp = fmaf(dv[x][0], vv[x][0], dpp); dpp = fmaf(dv[x][1], vv[x][1], dpp);
-              dpp = fmaf(dv[x][2], vv[x][2], dpp); dpp = fmaf(dv[x][3], vv[x][3], dpp);
-            }
-#pragma unroll
-            for (int o = 1; o < 8; o <<= 1) {
-              part += __shfl_xor(part, o, 64);
-              dpp += __shfl_xor(dpp, o, 64);
-            }
-            const float p = __expf(part + mu - ld2.x);
-            const float dlg = p * (dpp - ld2.y);
-#pragma unroll
-            for (int x = 0; x < NV; ++x)
-#pragma unroll
-              for (int t = 0; t < 4; ++t) {
-                gk[x][t] = fmaf(dlg, qv[x][t], gk[x][t]);
-                gv[x][t] = fmaf(p, dv[x][t], gv[x][t]);
+              for (int x = 0; x < NV; ++x) {
+                ld4(&qS[en[z].x][0], 32 * x + 4 * l8, qv[z][x]);
+                ld4(&gS[en[z].x][0], 32 * x + 4 * l8, dv[z][x]);
               }
-            gc += dlg * (1.f - part) - p * dpp;
+              ld2[z] = ldS[en[z].x];
+            }
+#pragma unroll
+            for (int z = 0; z < 2; ++z)
+#pragma unroll
+              for (int x = 0; x < NV; ++x) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) qv[z][x][t] = scale * (qv[z][x][t] - qcv[x][t]);
+                part[z] = fmaf(qv[z][x][0], kv[x].x, part[z]); part[z] = fmaf(qv[z][x][1], kv[x].y, part[z]);
+                part[z] = fmaf(qv[z][x][2], kv[x].z, part[z]); part[z] = fmaf(qv[z][x][3], kv[x].w, part[z]);
+                dpp[z] = fmaf(dv[z][x][0], vv[x][0], dpp[z]); dpp[z] = fmaf(dv[z][x][1], vv[x][1], dpp[z]);
+                dpp[z] = fmaf(dv[z][x][2], vv[x][2], dpp[z]); dpp[z] = fmaf(dv[z][x][3], vv[x][3], dpp[z]);
+              }
+#pragma unroll
+            for (int o = 1; o < 8; o <<= 1)
+#pragma unroll
+              for (int z = 0; z < 2; ++z) {
+                part[z] += __shfl_xor(part[z], o, 64);
+                dpp[z] += __shfl_xor(dpp[z], o, 64);
+              }
+#pragma unroll
+            for (int z = 0; z < 2; ++z) {  // entry e first, then e + 1: the order of the sums stays that of the list
+              const float p = use[z] ? __expf(part[z] + mu - ld2[z].x) : 0.f;
+              const float dlg = p * (dpp[z] - ld2[z].y);
+#pragma unroll
+              for (int x = 0; x < NV; ++x)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                  gk[x][t] = fmaf(dlg, qv[z][x][t], gk[x][t]);
+                  gv[x][t] = fmaf(p, dv[z][x][t], gv[x][t]);
+                }
+              gc += dlg * (1.f - part[z]) - p * dpp[z];
+            }
           }
           if (any) {
             if (l8 == 0) G_c[cell] = ogc + gc;
