@@ -155,7 +155,7 @@ struct MuseDims {
 // in time on one device would share it: they must be issued from one host thread at a time.
 struct MuseAux {
   hipStream_t s = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr, mid = nullptr;
   int state = 0;
 };
 MuseAux& muse_aux_stream();

@@ -1128,10 +1128,13 @@ __global__ void __launch_bounds__(256) k_add_rows(const float* __restrict__ src,
 
 template <typename T, int D>
 int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, const int32_t* aq, const float* LSE,
-                  const int32_t* selc, const int32_t* selb, FFWorkspace& w, int h0, int hn, hipStream_t st) {
+                  const int32_t* selc, const int32_t* selb, FFWorkspace& w, int h0, int hn, hipStream_t sq_, hipStream_t sk_) {
+  // the far-field part of dQ goes to stream sq_, the cell gradients and what they give to keys and values to
+  // stream sk_: the two share inputs only
   const int NBm = d.nb - 1;
   const int W = (d.Ck + 31) / 32;
   dim3 gt(d.Bs / 32 + d.Cq + 1, NBm, hn);
+  hipStream_t st = sq_;
   { MuseProf prof_("k_ff_bwd_dq", st); hipLaunchKernelGGL((k_ff_bwd_dq<T, D>), gt, dim3(64), 0, st, Q, dO, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu,
                      w.s_k, (const T*)w.s_v, w.A_mu, w.A_k, (const T*)w.A_v, (const bf16_t*)w.A_kb, w.perm_q, w.off_q, w.off_k, w.tile_off, LSE, w.delta,
                      w.selmask, selc, selb, w.ret_part, w.dQff, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
@@ -1144,6 +1147,7 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
       { MuseProf prof_("k_comp2_bwd_dq", st); hipLaunchKernelGGL((k_comp2_bwd_dq<D, 2>), g2, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, w.s_mu, w.s_k, (const bf16_t*)w.s_v,
                          w.perm_q, aq, LSE, w.delta, w.slotinfo, w.ret_part, w.dQff, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
   }
+  st = sk_;
   if (sizeof(T) == 2) {
     int rc2 = muse_launch_ff_bwd_cells_mx(d, Q, dO, qc, w.A_mu, w.A_kb, w.A_v, w.perm_q, w.off_q, LSE, w.delta, w.selmask,
                                           w.g_A_c, w.g_A_k, w.g_A_v, h0, hn, st);
@@ -1195,7 +1199,10 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
   if ((rc = muse_launch_fill(w.dKacc, nk * D, 0.f, sb))) return rc;
   if ((rc = muse_launch_fill(w.dVacc, nk * D, 0.f, sb))) return rc;
   if ((rc = muse_launch_attn_bwd(d, d.Bs, Q, K, V, dO, LSE, w.delta, w.dQacc, w.dKacc, w.dVacc, sb))) return rc;
-  if (two) MUSE_HIP_CHECK(hipEventRecord(ax.join, sb));
+  // With all heads in one chunk the far-field part of dQ follows on the second stream (it needs the selection
+  // info and the inverse index, which the first stream builds: event `mid`), beside the cell gradients.
+  const bool split = two && w.hc >= HQ;
+  if (two && !split) MUSE_HIP_CHECK(hipEventRecord(ax.join, sb));
   if ((rc = muse_launch_fill(w.dKs, nk * D, 0.f, st))) return rc;
   if ((rc = muse_launch_fill(w.dVs, nk * D, 0.f, st))) return rc;
   if (d.nb > 1) {
@@ -1214,8 +1221,12 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
         if ((rc = muse_launch_c3_pairs(d, Q, dO, w.Ks, w.Vs, LSE, w.delta, w.off_k, w.pair_off, w.hits, w.hit_cap, w.dKs,
                                        w.dVs, st)))
           return rc;
+        if (split) {
+          MUSE_HIP_CHECK(hipEventRecord(ax.mid, st));
+          MUSE_HIP_CHECK(hipStreamWaitEvent(sb, ax.mid, 0));
+        }
         if ((rc = muse_launch_ret_bwd_dq_pairs(d, Q, dO, w.Ks, w.Vs, LSE, w.delta, w.off_k, w.pair_off, w.hits, w.hit_cap,
-                                               w.ret_part, st)))
+                                               w.ret_part, split ? sb : st)))
           return rc;
       } else {
         dim3 g((d.Ck + 31) / 32, d.nb - 1, HK);
@@ -1232,11 +1243,16 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
       int hn = HQ - h0 < w.hc ? HQ - h0 : w.hc;
       if (!reuse && (rc = muse_ff_summaries<T>(d, qc, w, h0, hn, st))) return rc;
       if (!reuse && (rc = muse_ff_block_summaries<T>(d, selc, aq, w, h0, hn, st))) return rc;
-      if (D == 64) rc = run_bwd_chunk<T, 64>(d, Q, dO, qc, aq, LSE, selc, selb, w, h0, hn, st);
-      else rc = run_bwd_chunk<T, 128>(d, Q, dO, qc, aq, LSE, selc, selb, w, h0, hn, st);
+      if (split) {  // everything the dQ side reads is now queued on the first stream
+        MUSE_HIP_CHECK(hipEventRecord(ax.mid, st));
+        MUSE_HIP_CHECK(hipStreamWaitEvent(sb, ax.mid, 0));
+      }
+      if (D == 64) rc = run_bwd_chunk<T, 64>(d, Q, dO, qc, aq, LSE, selc, selb, w, h0, hn, split ? sb : st, st);
+      else rc = run_bwd_chunk<T, 128>(d, Q, dO, qc, aq, LSE, selc, selb, w, h0, hn, split ? sb : st, st);
       if (rc) return rc;
     }
   }
+  if (split) MUSE_HIP_CHECK(hipEventRecord(ax.join, sb));
   if (two) MUSE_HIP_CHECK(hipStreamWaitEvent(st, ax.join, 0));
   {
     dim3 g((unsigned)(((size_t)N * (D / 4) + 255) / 256), HK);

@@ -35,7 +35,8 @@ MuseAux& muse_aux_stream() {
   if (x.state == 0) {
     x.state = (hipStreamCreateWithFlags(&x.s, hipStreamNonBlocking) == hipSuccess &&
                hipEventCreateWithFlags(&x.fork, hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&x.join, hipEventDisableTiming) == hipSuccess)
+               hipEventCreateWithFlags(&x.join, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&x.mid, hipEventDisableTiming) == hipSuccess)
                   ? 1 : -1;
   }
   return x;
