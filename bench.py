@@ -52,10 +52,21 @@ def kernel_models(w, p):
         m["k_farfield_fwd"] = ("hbm", PEAK["hbm"], (cells * (2 * 2 * D * 2 + D * es + 2 * 4) + 2 * Nff * D * 4) * H, "byte")
     else:
         m["k_farfield_fwd"] = ("mfma", PEAK["mfma_fp32"], 2 * 2 * Nff * Ck * D * H, "flop")
-    for name, nmm in (("k_ff_bwd_dq", 3), ("k_ff_bwd_cells_mx", 4), ("k_ff_bwd_cells", 4)):
-        m[name] = ("mfma", PEAK[far], nmm * 2 * Nff * Ck * D * H, "flop")
-    for name in ("k_cells_to_keys_mx", "k_cells_to_keys"):
-        m[name] = ("mfma", PEAK[far], 5 * 2 * Cq * Nff * D * H, "flop")
+    if es == 2:
+        # bf16 inputs: the gradient contractions run on bf16 MFMA at a few flop per byte of summaries, so the
+        # kernels that walk all cells are bound by streaming them: accumulated k-bar (bf16 plane), v-bar, mu-bar in;
+        # cell gradients out (tile dQ kernel: the far-field dQ rows out)
+        cell_in = cells * (D * 2 + D * es + 4)
+        rows_qg = 2 * Nff * D * es
+        m["k_ff_bwd_dq"] = ("hbm", PEAK["hbm"], (cell_in + rows_qg + Nff * D * 4) * H, "byte")
+        m["k_ff_bwd_cells_mx"] = ("hbm", PEAK["hbm"], (cell_in + rows_qg + cell_g) * H, "byte")
+        # per-block cell gradients and mu-bar in, tilt logits in, key/value rows in, fp32 gradient rows read-modify-write
+        m["k_cells_to_keys_mx"] = ("hbm", PEAK["hbm"], (cell_g + cells * 4 + Cq * Nff * 4 + 2 * Nff * D * es) * H
+                                   + 2 * 2 * Nff * D * 4 * Hk, "byte")
+    else:
+        for name, nmm in (("k_ff_bwd_dq", 3), ("k_ff_bwd_cells", 4)):
+            m[name] = ("mfma", PEAK[far], nmm * 2 * Nff * Ck * D * H, "flop")
+        m["k_cells_to_keys"] = ("mfma", PEAK[far], 5 * 2 * Cq * Nff * D * H, "flop")
     m["k_ret_fwd_pairs"] = ("mfma", PEAK["mfma_bf16"], 2 * 2 * pair_keys * D * H, "flop")
     m["k_ret_bwd_dq_pairs"] = ("mfma", PEAK["mfma_bf16"], 3 * 2 * pair_keys * D * H, "flop")
     m["k_c3_pairs"] = ("mfma", PEAK["mfma_bf16"], 4 * 2 * pair_keys * D * H, "flop")
@@ -75,6 +86,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--serial-streams", action="store_true",
+                    help="run every stage on one stream (as the per-kernel timing pass does): for kernel profiles")
     ap.add_argument("--ws-gib", type=float, default=0.0, help="cap of the backward workspace (0 = all heads at once)")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -82,6 +95,8 @@ def main():
               "would shard); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
+    if a.serial_streams:
+        os.environ["MUSE_SERIAL_STREAMS"] = "1"   # read by the library when it first runs on the device
     import torch
 
     from paper_2509_10406_amd import binding as mb

@@ -74,11 +74,13 @@ typedef struct {
  * backward beside the far field) on a second, library-owned, non-blocking stream of the current device,
  * created on first use; the two streams meet through events before the entry point's last kernels, so work
  * enqueued on `stream` afterwards sees every output.  One host thread at a time may issue calls on a
- * device.  If the second stream cannot be created everything runs on `stream`.
+ * device.  If the second stream cannot be created, or the environment variable MUSE_SERIAL_STREAMS is "1" when
+ * the library first runs on the device, everything runs on `stream`.
  *
- * Storage: for bf16 inputs the value summaries, the gradients of the summaries and a copy of the
- * accumulated key summaries used by the backward are kept in bf16 in the workspace; every quantity that
- * decides a selection (key summaries, scores) is fp32. */
+ * Storage: for bf16 inputs the value summaries, the gradients of the summaries and the bf16 part of the
+ * accumulated key summaries are kept in bf16 in the workspace.  Every quantity that decides a selection keeps
+ * fp32 precision: the accumulated key summaries of bf16 inputs are a bf16 plane plus an fp16 plane of the
+ * remainder, and their scores against the (exact) bf16 queries accumulate in fp32. */
 
 /* Bytes of device scratch that entry point `which` (MUSE_WS_*) needs for `p`.  The far-field
  * stages keep the summaries tensor of Sec. 3 ([Cq, Ck, N/block] cells of 2D+1 floats) in the

@@ -1,4 +1,5 @@
 // C-ABI entry points of libmuse: argument validation on the host, workspace carving, stage order.
+#include <cstdlib>
 #include <math.h>
 
 #include <stdio.h>
@@ -33,6 +34,8 @@ MuseAux& muse_aux_stream() {
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
   MuseAux& x = a[dev];
   if (x.state == 0) {
+    const char* serial = getenv("MUSE_SERIAL_STREAMS");  // "1": everything on the caller's stream
+    if (serial && serial[0] == '1') { x.state = -1; return x; }
     x.state = (hipStreamCreateWithFlags(&x.s, hipStreamNonBlocking) == hipSuccess &&
                hipEventCreateWithFlags(&x.fork, hipEventDisableTiming) == hipSuccess &&
                hipEventCreateWithFlags(&x.join, hipEventDisableTiming) == hipSuccess &&
