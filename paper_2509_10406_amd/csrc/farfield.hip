@@ -377,8 +377,12 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
   const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
 
   const int32_t* to = tile_off + ((size_t)hq * nb + b) * (Cq + 1);
-  const int tile = blockIdx.x;
-  if (tile >= to[Cq]) return;
+  // Workgroups go to the 8 XCDs round-robin by their linear id and the grid's x extent is a multiple of 8, so
+  // x % 8 is the XCD: each XCD takes a contiguous run of the tiles, and the tiles of one (block, query cluster)
+  // group, which stream the same cells at about the same time, share its L2.
+  const int ntl = to[Cq], run = (ntl + 7) / 8;
+  const int tile = (blockIdx.x % 8) * run + blockIdx.x / 8;
+  if ((int)blockIdx.x / 8 >= run || tile >= ntl) return;
   int lo_ = 0, hi_ = Cq;
   while (hi_ - lo_ > 1) {
     int mid = (lo_ + hi_) >> 1;
@@ -958,7 +962,7 @@ namespace {
 template <typename T, int D, int RCAP>
 void launch_ff_fwd(const MuseDims& d, const T* Q, const float* qc, FFWorkspace& w, int32_t* selc, int h0, int hn,
                    hipStream_t st) {
-  dim3 g(d.Bs / 32 + d.Cq + 1, d.nb - 1, hn);
+  dim3 g((d.Bs / 32 + d.Cq + 1 + 7) / 8 * 8, d.nb - 1, hn);
   { MuseProf prof_("k_farfield_fwd", st); hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, w.A_mu, w.A_k, (const bf16_t*)w.A_kb, (const uint16_t*)w.A_km, w.A_c,
                      (const T*)w.A_v, w.perm_q, w.off_q, w.tile_off, w.ff_acc, w.ff_ml, selc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.scale); }
 }

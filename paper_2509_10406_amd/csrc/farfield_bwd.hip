@@ -84,8 +84,11 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
   const int W = (Ck + 31) / 32;
 
   const int32_t* to = tile_off + ((size_t)hq * nb + b) * (Cq + 1);
-  const int tile = blockIdx.x;
-  if (tile >= to[Cq]) return;
+  // x % 8 is the XCD (grid x extent a multiple of 8): each XCD takes a contiguous run of the tiles, so the
+  // tiles of one (block, query cluster) group share its L2
+  const int ntl = to[Cq], run = (ntl + 7) / 8;
+  const int tile = (blockIdx.x % 8) * run + blockIdx.x / 8;
+  if ((int)blockIdx.x / 8 >= run || tile >= ntl) return;
   int lo_ = 0, hi_ = Cq;
   while (hi_ - lo_ > 1) {
     int mid = (lo_ + hi_) >> 1;
@@ -1133,7 +1136,7 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
   // stream sk_: the two share inputs only
   const int NBm = d.nb - 1;
   const int W = (d.Ck + 31) / 32;
-  dim3 gt(d.Bs / 32 + d.Cq + 1, NBm, hn);
+  dim3 gt((d.Bs / 32 + d.Cq + 1 + 7) / 8 * 8, NBm, hn);
   hipStream_t st = sq_;
   { MuseProf prof_("k_ff_bwd_dq", st); hipLaunchKernelGGL((k_ff_bwd_dq<T, D>), gt, dim3(64), 0, st, Q, dO, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu,
                      w.s_k, (const T*)w.s_v, w.A_mu, w.A_k, (const T*)w.A_v, (const bf16_t*)w.A_kb, w.perm_q, w.off_q, w.off_k, w.tile_off, LSE, w.delta,
