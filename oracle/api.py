@@ -31,6 +31,7 @@ class _P(C.Structure):
     _fields_ = [
         ("N", C.c_int32), ("D", C.c_int32), ("Bs", C.c_int32), ("Cq", C.c_int32),
         ("Ck", C.c_int32), ("r", C.c_int32), ("k2", C.c_int32), ("scale", C.c_double),
+        ("frozen_weights", C.c_int32), ("Kw", C.c_void_p),
     ]
 
 
@@ -44,10 +45,13 @@ class MuseParams:
     r: int
     k2: int = 1
     scale: float = 0.0  # 0 -> 1/sqrt(D)
+    frozen_weights: bool = False  # backward: aggregation weights and mu-bar are constants (App. C)
 
-    def c(self) -> _P:
+    def c(self, Kw=None) -> _P:
+        """Kw: float64 [N, D] array (kept alive by the caller) of the keys inside the tilted weights."""
         sc = self.scale if self.scale != 0.0 else 1.0 / np.sqrt(self.D)
-        return _P(self.N, self.D, self.Bs, self.Cq, self.Ck, self.r, self.k2, sc)
+        return _P(self.N, self.D, self.Bs, self.Cq, self.Ck, self.r, self.k2, sc, int(self.frozen_weights),
+                  None if Kw is None else Kw.ctypes.data)
 
     @property
     def nb(self) -> int:
@@ -149,9 +153,11 @@ def summaries(p: MuseParams, K, V, qc, ak, i):
     return dict(mu=mu, kb=kb, vb=vb, Amu=Amu, Akb=Akb, Avb=Avb)
 
 
-def muse_fwd(p: MuseParams, Q, K, V, qc, aq, ak, rows=None, sel=None):
-    """MuSe forward.  sel = (selc [N,r], selb [N,r,k2e]) teacher-forces the selections."""
+def muse_fwd(p: MuseParams, Q, K, V, qc, aq, ak, rows=None, sel=None, weight_keys=None):
+    """MuSe forward.  sel = (selc [N,r], selb [N,r,k2e]) teacher-forces the selections.
+    weight_keys: keys used inside the tilted weights of the summaries instead of K (for the pins)."""
     Q, Qp = _d(Q); K, Kp = _d(K); V, Vp = _d(V); qc, qp = _d(qc)
+    Kw = None if weight_keys is None else np.ascontiguousarray(weight_keys, dtype=np.float64)
     aq, aqp = _i(aq); ak, akp = _i(ak)
     N, D = Q.shape
     O = np.zeros((N, D)); LSE = np.zeros(N)
@@ -166,7 +172,7 @@ def muse_fwd(p: MuseParams, Q, K, V, qc, aq, ak, rows=None, sel=None):
         given = 1
     mc = np.full(N, np.inf); mb = np.full(N, np.inf); mass = np.zeros((N, 4))
     r, nr, rp = _rows(rows)
-    pc = p.c()
+    pc = p.c(Kw)
     rc = _L().oracle_muse_fwd(C.byref(pc), Qp, Kp, Vp, qp, aqp, akp, C.c_int(nr), rp, C.c_int(given),
                               _d(O)[1], _d(LSE)[1], _i(selc)[1], _i(selb)[1], _d(mc)[1], _d(mb)[1],
                               _d(mass)[1])

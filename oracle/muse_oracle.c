@@ -49,6 +49,13 @@
 typedef struct {
   int32_t N, D, Bs, Cq, Ck, r, k2;
   double scale;
+  /* App. C "Aggregation Weight Gradient Flow", non-differentiable variant: the tilted aggregation
+   * weights e_m / S and the log-mass mu-bar of every summary are constants of the backward. */
+  int32_t frozen_weights;
+  /* Keys inside the tilted weights exp(q-bar . k) of Eq. 4-6 when they are to differ from the keys
+   * that are aggregated (NULL: the same K).  Only the pins use it: with Kw held at K the forward is the
+   * function whose derivative the frozen-weights backward is. */
+  const double* Kw;
 } omuse_params;
 
 /* ------------------------------------------------------------------ */
@@ -277,6 +284,7 @@ static void summaries_for_cluster(const omuse_params* p, const double* K, const 
   s->Akb[i] = (double*)calloc(cells * D, sizeof(double));
   s->Avb[i] = (double*)calloc(cells * D, sizeof(double));
   const double* qb = s->qbar + (size_t)i * D;
+  const double* Kw = p->Kw ? p->Kw : K; /* the keys inside the weights */
   for (int j = 0; j < Ck; ++j) {
     for (int b = 0; b < nb; ++b) {
       size_t c = (size_t)j * nb + b;
@@ -288,13 +296,13 @@ static void summaries_for_cluster(const omuse_params* p, const double* K, const 
       /* attention from the query centroid to the keys of (j, b): Eq. 4-6 */
       double mx = -INFINITY;
       for (int t = lo; t < hi; ++t) {
-        double l = dot(qb, K + (size_t)s->seg_idx[t] * D, D);
+        double l = dot(qb, Kw + (size_t)s->seg_idx[t] * D, D);
         if (l > mx) mx = l;
       }
       double S = 0.0;
       for (int t = lo; t < hi; ++t) {
         int m = s->seg_idx[t];
-        double e = exp(dot(qb, K + (size_t)m * D, D) - mx);
+        double e = exp(dot(qb, Kw + (size_t)m * D, D) - mx);
         S += e;
         for (int d = 0; d < D; ++d) {
           s->kb[i][c * D + d] += e * K[(size_t)m * D + d];
@@ -681,14 +689,15 @@ int oracle_muse_bwd(const omuse_params* p, const double* Q, const double* K, con
           }
         }
         /* through the tilted weights to the keys and values of the cell;
-         * nothing goes to q-bar */
+         * nothing goes to q-bar.  With frozen weights e_m and S are constants: only the aggregated
+         * keys and values receive a gradient (coef = 0). */
         int lo = s->seg_off[bp * Ck + j], hi = s->seg_off[bp * Ck + j + 1];
         for (int u = lo; u < hi; ++u) {
           int m = s->seg_idx[u];
           const double* k = K + (size_t)m * D;
           const double* v = V + (size_t)m * D;
           double e = exp(dot(qb, k, D));
-          double coef = e * (dS + dot(dKsum, k, D) + dot(dVsum, v, D));
+          double coef = p->frozen_weights ? 0.0 : e * (dS + dot(dKsum, k, D) + dot(dVsum, v, D));
           for (int d = 0; d < D; ++d) {
             dV[(size_t)m * D + d] += e * dVsum[d];
             dK[(size_t)m * D + d] += e * dKsum[d] + coef * qb[d];

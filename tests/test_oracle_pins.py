@@ -325,6 +325,41 @@ def test_backward_matches_finite_differences(oracle, r, k2):
             assert abs(fd - G[n, d]) <= 1e-6 * max(1.0, abs(fd)), (which, n, d, fd, G[n, d])
 
 
+@pytest.mark.parametrize("r,k2", [(2, 1), (0, 1), (3, 2)])
+def test_frozen_weights_backward_matches_finite_differences(oracle, r, k2):
+    """App. C "Aggregation Weight Gradient Flow", non-differentiable variant: the backward with frozen
+    weights is the derivative of the forward in which the keys inside the tilted weights exp(q-bar . k)
+    (and so mu-bar) are a constant copy, while the aggregated keys, the retrieved and the local keys move."""
+    N, D, Bs, Cq, Ck = 32, 3, 8, 3, 5
+    Q, K, V, qc, aq, ak = _data(180 + r, N, D, Cq, Ck)
+    p = MuseParams(N, D, Bs, Cq, Ck, r, k2, 0.5)
+    pf = MuseParams(N, D, Bs, Cq, Ck, r, k2, 0.5, frozen_weights=True)
+    dO = np.random.default_rng(181).normal(size=(N, D))
+    f = oracle.muse_fwd(p, Q, K, V, qc, aq, ak)
+    sel = (f["selc"], f["selb"])
+    dQ, dK, dV = oracle.muse_bwd(pf, Q, K, V, qc, aq, ak, f["O"], f["LSE"], dO, *sel)
+    full = oracle.muse_bwd(p, Q, K, V, qc, aq, ak, f["O"], f["LSE"], dO, *sel)
+    # queries and values do not pass through the weights; keys do
+    np.testing.assert_allclose(dQ, full[0], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(dV, full[2], rtol=1e-12, atol=1e-14)
+    assert np.abs(dK - full[1]).max() > 1e-4
+
+    def loss(K_):
+        return (oracle.muse_fwd(p, Q, K_, V, qc, aq, ak, sel=sel, weight_keys=K)["O"] * dO).sum()
+
+    eps = 1e-5
+    rng = np.random.default_rng(182)
+    for _ in range(40):
+        n, d = rng.integers(N), rng.integers(D)
+        a = K.copy()
+        a[n, d] += eps
+        up = loss(a)
+        a[n, d] -= 2 * eps
+        dn = loss(a)
+        fd = (up - dn) / (2 * eps)
+        assert abs(fd - dK[n, d]) <= 1e-6 * max(1.0, abs(fd)), (n, d, fd, dK[n, d])
+
+
 def test_backward_row_subset_is_additive(oracle):
     N, D, Bs, Cq, Ck = 32, 4, 8, 3, 5
     Q, K, V, qc, aq, ak = _data(90, N, D, Cq, Ck)
