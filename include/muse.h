@@ -49,7 +49,13 @@ enum { MUSE_DTYPE_FP32 = 0, MUSE_DTYPE_BF16 = 1 };
  * workspace reuses them instead of recomputing (the usual save-for-backward of a training step).  Needs a
  * workspace that holds all heads at once (the `preferred` size of MUSE_WS_BWD), else
  * MUSE_ERR_WORKSPACE_TOO_SMALL. */
-enum { MUSE_FLAG_KEEP_FWD_STATE = 1 };
+enum { MUSE_FLAG_KEEP_FWD_STATE = 1,
+/* MUSE_FLAG_FROZEN_WEIGHTS (muse_bwd only; App. C "Aggregation Weight Gradient Flow", the non-differentiable
+ * variant): the tilted aggregation weights e_m / S of every summary and its log-mass mu-bar are constants of
+ * the backward, so a summarised key receives a gradient only through the aggregated key, dk_m = (e_m / S) g_kbar
+ * (and dv_m = (e_m / S) g_vbar as before); dQ and dV are unchanged.  The default differentiates through the
+ * weights. */
+       MUSE_FLAG_FROZEN_WEIGHTS = 2 };
 enum { MUSE_WS_CLUSTER = 0, MUSE_WS_FWD = 1, MUSE_WS_BWD = 2, MUSE_WS_EXACT_FWD = 3, MUSE_WS_EXACT_BWD = 4 };
 
 typedef struct {

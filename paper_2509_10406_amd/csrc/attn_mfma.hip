@@ -988,7 +988,7 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
                                                           const bf16_t* __restrict__ G_k, const bf16_t* __restrict__ G_v,
                                                           const int32_t* __restrict__ off_k, float* __restrict__ dKs,
                                                           float* __restrict__ dVs, int h0, int N, int nb, int Cq, int CqP,
-                                                          int Ck, int Hq, int Hkv) {
+                                                          int Ck, int Hq, int Hkv, int frozen) {
   constexpr int KS = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(16))) bf16_t gkT[D][32 + TPAD];
   __shared__ __attribute__((aligned(16))) bf16_t gvT[D][32 + TPAD];
@@ -1080,13 +1080,16 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
             wv[e] = (iv && mvalid) ? __expf(lg[e] - mv[u]) : 0.f;
           }
         }
+        // frozen aggregation weights: nothing flows through W (the T term and its contraction with qbar drop out)
+        if (!frozen) {
 #pragma unroll
-        for (int x = 0; x < KS; ++x) {
-          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gkr[x], __builtin_bit_cast(bf16x8_t, kbs[x][lane]), tacc, 0, 0, 0);
-          tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gvr[x], __builtin_bit_cast(bf16x8_t, vbs[x][lane]), tacc, 0, 0, 0);
+          for (int x = 0; x < KS; ++x) {
+            tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gkr[x], __builtin_bit_cast(bf16x8_t, kbs[x][lane]), tacc, 0, 0, 0);
+            tacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gvr[x], __builtin_bit_cast(bf16x8_t, vbs[x][lane]), tacc, 0, 0, 0);
+          }
         }
 #pragma unroll
-        for (int e = 0; e < 16; ++e) tacc[e] = wv[e] > 0.f ? wv[e] * tacc[e] : 0.f;
+        for (int e = 0; e < 16; ++e) tacc[e] = (wv[e] > 0.f && !frozen) ? wv[e] * tacc[e] : 0.f;
 #pragma unroll
         for (int G = 0; G < 2; ++G) {
           bf16x8_t wf = pack8(wv, 2 * G, 2 * G + 1);
@@ -1098,7 +1101,7 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
             const bf16x8_t aq = ld_tr8(qT + (size_t)(32 * t + col) * CqP + i0, 16 * G, half);
             dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, wf, dv[t], 0, 0, 0);
             dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, wf, dk[t], 0, 0, 0);
-            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, tf, dk[t], 0, 0, 0);
+            if (!frozen) dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, tf, dk[t], 0, 0, 0);
           }
         }
       }
@@ -1131,9 +1134,9 @@ int muse_launch_cells_to_keys_mx(const MuseDims& d, const void* Ks, const void* 
   { MuseProf prof_("k_qc_transpose", st); hipLaunchKernelGGL(k_qc_transpose, dim3((d.D * CqP + 255) / 256, hn), dim3(256), 0, st, qc + (size_t)h0 * d.Cq * d.D, (bf16_t*)qcT, d.D, d.Cq, CqP, d.scale); }
   dim3 g(d.Ck, d.nb - 1, hn / (d.Hq / d.Hkv));
   if (d.D == 64)
-    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<64>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, (const bf16_t*)qcT, L, s_mu, G_c, (const bf16_t*)G_k, (const bf16_t*)G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, CqP, d.Ck, d.Hq, d.Hkv); }
+    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<64>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, (const bf16_t*)qcT, L, s_mu, G_c, (const bf16_t*)G_k, (const bf16_t*)G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, CqP, d.Ck, d.Hq, d.Hkv, d.frozen_weights ? 1 : 0); }
   else
-    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<128>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, (const bf16_t*)qcT, L, s_mu, G_c, (const bf16_t*)G_k, (const bf16_t*)G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, CqP, d.Ck, d.Hq, d.Hkv); }
+    { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<128>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, (const bf16_t*)qcT, L, s_mu, G_c, (const bf16_t*)G_k, (const bf16_t*)G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, CqP, d.Ck, d.Hq, d.Hkv, d.frozen_weights ? 1 : 0); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }

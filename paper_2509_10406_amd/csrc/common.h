@@ -135,6 +135,7 @@ struct MuseDims {
   int dtype, grad_dtype;
   float scale;
   bool keep_state;  // MUSE_FLAG_KEEP_FWD_STATE
+  bool frozen_weights;  // MUSE_FLAG_FROZEN_WEIGHTS
 };
 
 #define MUSE_HIP_CHECK(expr)                      \

@@ -861,7 +861,7 @@ __global__ void __launch_bounds__(64) k_cells_to_keys(const T* __restrict__ Ks, 
                                                        const float* __restrict__ G_k, const float* __restrict__ G_v,
                                                        const int32_t* __restrict__ off_k, float* __restrict__ dKs,
                                                        float* __restrict__ dVs, int h0, int N, int nb, int Cq, int Ck,
-                                                       int Hq, int Hkv, float scale) {
+                                                       int Hq, int Hkv, float scale, int frozen) {
   constexpr int U = D / 8, DT = D / 32;
   const int G_ = Hq / Hkv;
   const int hkl = blockIdx.z;                 // kv head inside the chunk
@@ -903,8 +903,9 @@ __global__ void __launch_bounds__(64) k_cells_to_keys(const T* __restrict__ Ks, 
         }
         tacc = mfma_rows<D>(tacc, G_k + cellA * D + 4 * half, kb);
         tacc = mfma_rows<D>(tacc, G_v + cellA * D + 4 * half, vb);
+        // frozen aggregation weights: nothing flows through W (the T term drops out)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) tacc[e] = wv[e] > 0.f ? wv[e] * tacc[e] : 0.f;
+        for (int e = 0; e < 16; ++e) tacc[e] = (wv[e] > 0.f && !frozen) ? wv[e] * tacc[e] : 0.f;
 #pragma unroll
         for (int gg = 0; gg < 4; ++gg)
 #pragma unroll
@@ -1174,7 +1175,7 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
   } else
   { MuseProf prof_("k_cells_to_keys", st); hipLaunchKernelGGL((k_cells_to_keys<T, D>), dim3(d.Ck, NBm, hn / G_), dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs,
                      qc, w.L, w.s_mu, w.g_s_c, (const float*)w.g_s_k, (const float*)w.g_s_v, w.off_k, w.dKs, w.dVs, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq,
-                     d.Hkv, d.scale); }
+                     d.Hkv, d.scale, d.frozen_weights ? 1 : 0); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }

@@ -56,11 +56,11 @@ def as_sets(sel):
     return s
 
 
-def run_case(name, with_bwd):
+def run_case(name, with_bwd, frozen_weights=False):
     base, kw = CASES[name]
     w = small(base, **kw)
     d = generate(w, need_dO=True)
-    p = mb.params_for(w)
+    p = mb.params_for(w, flags=mb.FLAG_FROZEN_WEIGHTS if frozen_weights else 0)
     qc, aq, ak = oracle_clustering(w, d, p)
     Q, K, V, dO = (dev(d[x], p) for x in ("Q", "K", "V", "dO"))
     qc_d, aq_d, ak_d = torch.tensor(qc).cuda(), torch.tensor(aq).cuda(), torch.tensor(ak).cuda()
@@ -68,7 +68,7 @@ def run_case(name, with_bwd):
     if with_bwd:
         dQ, dK, dV = mb.muse_bwd(p, Q, K, V, O, LSE, dO, qc_d, aq_d, ak_d, selc, selb)
     torch.cuda.synchronize()
-    op = orc.MuseParams(w.N, w.D, w.Bs, w.Cq, w.Ck, w.r, w.k2, p.eff_scale)
+    op = orc.MuseParams(w.N, w.D, w.Bs, w.Cq, w.Ck, w.r, w.k2, p.eff_scale, frozen_weights=frozen_weights)
     G = w.Hq // w.Hkv
     selc_h, selb_h = selc.cpu().numpy()[0], selb.cpu().numpy()[0]
 
@@ -123,6 +123,12 @@ def test_muse_forward(name):
 @pytest.mark.parametrize("name", list(CASES))
 def test_muse_backward(name):
     run_case(name, with_bwd=True)
+
+
+@pytest.mark.parametrize("name", ["cfg1_full", "cfg2_small", "cfg4_gqa", "cfg5_d128", "fp32_nb12"])
+def test_muse_backward_frozen_weights(name):
+    """App. C "Aggregation Weight Gradient Flow", non-differentiable variant (MUSE_FLAG_FROZEN_WEIGHTS)."""
+    run_case(name, with_bwd=True, frozen_weights=True)
 
 
 def test_forward_with_small_workspace_chunks_heads():
