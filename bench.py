@@ -202,7 +202,8 @@ def main():
         "warmup": a.warmup, "ms_per_step": ms_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} Hq={w.Hq} Hkv={w.Hkv} N={w.N} D={w.D} Cq={w.Cq} Ck={w.Ck} r={w.r} "
-                               f"k2={w.k2} block={w.Bs} kmeans_iters={w.kmeans_iters} (BASELINE.json configs[2])",
+                               f"k2={w.k2} block={w.Bs} kmeans_iters={w.kmeans_iters}" +
+                               (" (BASELINE.json configs[2])" if w.name == "cfg3" else ""),
                    "step": "muse_cluster + muse_fwd + muse_bwd" + (" (frozen aggregation weights)" if a.frozen_weights else "")},
         "ms": {"cluster": ms_cluster, "fwd": ms_fwd, "bwd": ms_bwd, "exact_attn_fwd_bwd": ms_exact},
         "effective_attention_tflops": eff_flops / (ms_step * 1e-3) / 1e12,

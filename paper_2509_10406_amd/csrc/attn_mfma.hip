@@ -416,7 +416,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 // Results are added to the bucketed-order gradient rows this wave owns.
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, 2))) k_c3_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
                                                   const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
                                                   const float* __restrict__ LSE, const float* __restrict__ delta,
                                                   const int32_t* __restrict__ off_k, const int32_t* __restrict__ pair_off,
@@ -554,7 +554,7 @@ __global__ void __launch_bounds__(64) k_c3_pairs(const bf16_t* __restrict__ Q, c
 //   part[(qn*R2 + su)][0..D) = sum_m exp(l_m - max) v_m,  [D] = max (natural log units),  [D+1] = sum.
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(64) k_ret_fwd_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Ks,
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2, 4))) k_ret_fwd_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Ks,
                                                        const bf16_t* __restrict__ Vs, const int32_t* __restrict__ off_k,
                                                        const int32_t* __restrict__ pair_off, const uint2* __restrict__ hits,
                                                        float* __restrict__ part, size_t hit_cap, int N, int nb, int Ck,
@@ -671,7 +671,7 @@ __global__ void __launch_bounds__(64) k_ret_fwd_pairs(const bf16_t* __restrict__
 // dqpart[(qn*R2 + su)][0..D) = scale * sum_m dl_m k_m over the keys of the pair.
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(64) k_ret_bwd_dq_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 1, 3))) k_ret_bwd_dq_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
                                                           const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
                                                           const float* __restrict__ LSE, const float* __restrict__ delta,
                                                           const int32_t* __restrict__ off_k,

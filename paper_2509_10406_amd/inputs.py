@@ -57,6 +57,10 @@ CONFIGS = {
                      gen_args=dict(rank=16, amp=2.0, base=1.0e5), seed=1004),
     "cfg5": Workload("cfg5", 1, 32, 8, 131072, 128, 512, 2048, 16, "bf16", gen="lowrank_rope",
                      gen_args=dict(rank=32, amp=2.0, base=1.0e5), seed=1005),
+    # the paper's operating ratio C = N/512 at the shape of cfg3 (Sec. 4: 128 query and 128 key clusters, 8
+    # retrieved clusters, 8 blocks of 8k): about 64 keys per retrieved (cluster, block) pair
+    "cfg3_qk128": Workload("cfg3_qk128", 1, 16, 16, 65536, 64, 128, 128, 8, "bf16", gen="embed",
+                           gen_args=dict(embed=1024, components=1024, sd=0.3), seed=1003),
 }
 
 
