@@ -44,34 +44,50 @@ __device__ __forceinline__ void load_tile(const bf16_t* __restrict__ src, int r0
 }
 
 // the same in two halves, so that the global loads of the next tile are in flight while the current one is
-// consumed: fetch_tile into registers, commit_tile from registers into LDS
+// consumed: fetch_tile into registers, commit_tile from registers into LDS.  The registers are named members,
+// not an array: an array that is passed around and read through pointer casts ends up in memory (the compiler
+// parks it in LDS), and the wait for its loads then comes right after they are issued.
+struct TileRegs {
+  uint4 a, b, c, d;
+};
 template <int D, int ROWS>
-__device__ __forceinline__ void fetch_tile(const bf16_t* __restrict__ src, int r0, int N, uint4 (&reg)[ROWS * (D / 8) / 256]) {
-#pragma unroll
-  for (int it = 0; it < ROWS * (D / 8) / 256; ++it) {
-    const int c = threadIdx.x + 256 * it;
-    int gr = r0 + c % ROWS;
-    gr = gr < N ? gr : N - 1;
-    reg[it] = *reinterpret_cast<const uint4*>(src + (size_t)gr * D + (c / ROWS) * 8);
+__device__ __forceinline__ uint4 fetch_chunk(const bf16_t* __restrict__ src, int r0, int N, int it) {
+  const int c = threadIdx.x + 256 * it;
+  int gr = r0 + c % ROWS;
+  gr = gr < N ? gr : N - 1;
+  return *reinterpret_cast<const uint4*>(src + (size_t)gr * D + (c / ROWS) * 8);
+}
+template <int D, int ROWS>
+__device__ __forceinline__ void fetch_tile(const bf16_t* __restrict__ src, int r0, int N, TileRegs& r) {
+  constexpr int NCH = ROWS * (D / 8) / 256;
+  static_assert(NCH >= 1 && NCH <= 4, "tile does not fit four chunks per thread");
+  r.a = fetch_chunk<D, ROWS>(src, r0, N, 0);
+  if constexpr (NCH > 1) r.b = fetch_chunk<D, ROWS>(src, r0, N, 1);
+  if constexpr (NCH > 2) r.c = fetch_chunk<D, ROWS>(src, r0, N, 2);
+  if constexpr (NCH > 3) r.d = fetch_chunk<D, ROWS>(src, r0, N, 3);
+}
+template <int D, int ROWS, bool ROWM, bool TRANS>
+__device__ __forceinline__ void commit_chunk(const uint4 v, int it, bf16_t (*rm)[D + 8], bf16_t (*tr)[ROWS + TPAD]) {
+  const int c = threadIdx.x + 256 * it, row = c % ROWS, cc = c / ROWS;
+  if (ROWM) *reinterpret_cast<uint4*>(&rm[row][cc * 8]) = v;
+  if (TRANS) {
+    tr[cc * 8 + 0][row] = (bf16_t)(v.x & 0xffffu); tr[cc * 8 + 1][row] = (bf16_t)(v.x >> 16);
+    tr[cc * 8 + 2][row] = (bf16_t)(v.y & 0xffffu); tr[cc * 8 + 3][row] = (bf16_t)(v.y >> 16);
+    tr[cc * 8 + 4][row] = (bf16_t)(v.z & 0xffffu); tr[cc * 8 + 5][row] = (bf16_t)(v.z >> 16);
+    tr[cc * 8 + 6][row] = (bf16_t)(v.w & 0xffffu); tr[cc * 8 + 7][row] = (bf16_t)(v.w >> 16);
   }
 }
 template <int D, int ROWS, bool ROWM, bool TRANS>
-__device__ __forceinline__ void commit_tile(const uint4 (&reg)[ROWS * (D / 8) / 256], bf16_t (*rm)[D + 8],
-                                            bf16_t (*tr)[ROWS + TPAD]) {
-#pragma unroll
-  for (int it = 0; it < ROWS * (D / 8) / 256; ++it) {
-    const int c = threadIdx.x + 256 * it, row = c % ROWS, cc = c / ROWS;
-    if (ROWM) *reinterpret_cast<uint4*>(&rm[row][cc * 8]) = reg[it];
-    if (TRANS) {
-      const bf16_t* pv = reinterpret_cast<const bf16_t*>(&reg[it]);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) tr[cc * 8 + e][row] = pv[e];
-    }
-  }
+__device__ __forceinline__ void commit_tile(const TileRegs& r, bf16_t (*rm)[D + 8], bf16_t (*tr)[ROWS + TPAD]) {
+  constexpr int NCH = ROWS * (D / 8) / 256;
+  commit_chunk<D, ROWS, ROWM, TRANS>(r.a, 0, rm, tr);
+  if constexpr (NCH > 1) commit_chunk<D, ROWS, ROWM, TRANS>(r.b, 1, rm, tr);
+  if constexpr (NCH > 2) commit_chunk<D, ROWS, ROWM, TRANS>(r.c, 2, rm, tr);
+  if constexpr (NCH > 3) commit_chunk<D, ROWS, ROWM, TRANS>(r.d, 3, rm, tr);
 }
 
 template <int D>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2, D == 64 ? 4 : 2))) k_flash_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2))) k_flash_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                     const bf16_t* __restrict__ V, const float* __restrict__ ff,
                                                     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, int Bs,
                                                     int Hq, int Hkv, float scale_log2e) {
@@ -99,7 +115,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   float m = MUSE_NEG_INF, l = 0.f;
 
   const int kbeg = (q0 / Bs) * Bs, kend = min(q0 + 128, N);
-  uint4 kreg[BN * (D / 8) / 256], vreg[BN * (D / 8) / 256];
+  TileRegs kreg, vreg;
   fetch_tile<D, BN>(K + kh * D, kbeg, N, kreg);
   fetch_tile<D, BN>(V + kh * D, kbeg, N, vreg);
   for (int k0 = kbeg; k0 < kend; k0 += BN) {
@@ -325,7 +341,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 
   for (int g = 0; g < G_; ++g) {
     const size_t qh = ((size_t)b * Hq + (size_t)hk * G_ + g) * N;
-    uint4 qreg[BQ * (D / 8) / 256], greg[BQ * (D / 8) / 256];
+    TileRegs qreg, greg;
     float lreg = 0.f, dreg = 0.f;
     auto fetch = [&](int q0) {
       fetch_tile<D, BQ>(Q + qh * D, q0, N, qreg);
