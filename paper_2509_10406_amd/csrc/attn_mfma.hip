@@ -224,7 +224,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 }
 
 template <int D>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2, D == 64 ? 4 : 2))) k_flash_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2))) k_flash_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                        const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO,
                                                        const float* __restrict__ LSE, const float* __restrict__ delta,
                                                        float* __restrict__ dQ, int N, int Bs, int Hq, int Hkv,
@@ -255,11 +255,18 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     for (int e = 0; e < 16; ++e) dq[t][e] = 0.f;
 
   const int kbeg = (q0 / Bs) * Bs, kend = min(q0 + 128, N);
+  TileRegs kreg, vreg;
+  fetch_tile<D, BN>(K + kh * D, kbeg, N, kreg);
+  fetch_tile<D, BN>(V + kh * D, kbeg, N, vreg);
   for (int k0 = kbeg; k0 < kend; k0 += BN) {
     __syncthreads();
-    load_tile<D, BN, true, true>(K + kh * D, k0, N, ks, kt_);
-    load_tile<D, BN, true, false>(V + kh * D, k0, N, vs, nullptr);
+    commit_tile<D, BN, true, true>(kreg, ks, kt_);
+    commit_tile<D, BN, true, false>(vreg, vs, nullptr);
     __syncthreads();
+    if (k0 + BN < kend) {  // in flight while this tile is consumed
+      fetch_tile<D, BN>(K + kh * D, k0 + BN, N, kreg);
+      fetch_tile<D, BN>(V + kh * D, k0 + BN, N, vreg);
+    }
     if (k0 > q0 + 32 * wave + 31) continue;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
