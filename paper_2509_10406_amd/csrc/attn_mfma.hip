@@ -835,7 +835,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   const float* qci = qc + ((size_t)hq * Cq + i) * D;
   struct CT {  // one tile of 32 accumulated summaries as this lane's operand fragments
     bf16x8_t kf[KS], vf[KS];
-    float amu2;
+    float amu;  // raw: any arithmetic on a prefetched value would wait for the whole prefetch at once
     uint32_t mw[QT];  // word of the selection mask of staged query 32 qt + col for this cluster tile
   };
   auto load_ct = [&](int jt, int q0, int qhi, CT& c) {
@@ -846,7 +846,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
       c.kf[x] = *reinterpret_cast<const bf16x8_t*>(A_kb + (acell + jcc) * D + 16 * x + 8 * half);
       c.vf[x] = *reinterpret_cast<const bf16x8_t*>(A_v + (acell + jcc) * D + 16 * x + 8 * half);
     }
-    c.amu2 = jc < Ck ? A_mu[acell + jcc] * 1.4426950408889634f : MUSE_NEG_INF;
+    c.amu = A_mu[acell + jcc];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
       const int pq = q0 + 32 * qt + col;
@@ -886,7 +886,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     CT cur, nxt;
     if (wave < W) load_ct(wave, q0 < qhi ? q0 : 0, qhi, cur);
     for (int jt = wave; jt < W; jt += 4) {
-      if (jt + 4 < W) load_ct(jt + 4, q0 < qhi ? q0 : 0, qhi, nxt);
+      // always issued (the last tile again at the end): with the same number of loads in flight on every path
+      // the wait for this tile's operands can leave the next tile's loads outstanding
+      load_ct(jt + 4 < W ? jt + 4 : jt, q0 < qhi ? q0 : 0, qhi, nxt);
       // this wave's words of the selection mask: one per staged query, for cluster tile jt
       if (half == 0) {
 #pragma unroll
@@ -895,6 +897,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
       wave_lds_fence();
       const int jc = jt * 32 + col;
       const bool jvalid = jc < Ck;
+      const float amu2 = jvalid ? cur.amu * 1.4426950408889634f : MUSE_NEG_INF;
       f32x16_t gk[DT], gv[DT];
 #pragma unroll
       for (int t = 0; t < DT; ++t)
@@ -921,7 +924,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             const int e = 4 * gq + u, row = 32 * qt + 8 * gq + 4 * half + u;
-            float p = fast_exp2(fmaf(s[e], 1.4426950408889634f, cur.amu2 - lv[u]));
+            float p = fast_exp2(fmaf(s[e], 1.4426950408889634f, amu2 - lv[u]));
             p = ((mws[wave][row] >> col) & 1u) ? 0.f : p;
             const float dlg = p * (dp[e] - dv4[u]);
             csum += p > 0.f ? dlg * (1.f - s[e]) - p * dp[e] : 0.f;

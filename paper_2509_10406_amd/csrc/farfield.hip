@@ -162,6 +162,12 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 4)))
     bool empty = true;
     while (nb_ == b) {
       empty = false;
+      // The prefetched chunk is first touched HERE: without this fence the compiler hoists the copy below (and
+      // with it the wait for the loads) above the previous block's stores, into the iteration that issued them.
+#pragma unroll
+      for (int u = 0; u < KCH / 8; ++u)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) asm volatile("" : "+v"(nxt.lg[u][t]), "+v"(nxt.kk[u][t]), "+v"(nxt.vv[u][t]) : : "memory");
       const Chunk cur = nxt;
       const int c0 = nc0, hi = nhi;
       nc0 += KCH;
