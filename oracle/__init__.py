@@ -12,8 +12,10 @@ from .api import (  # noqa: F401
     exact_bwd,
     exact_fwd,
     kmeans,
+    kmeans_stream,
     muse_bwd,
     muse_fwd,
     round_bf16,
+    round_fp16,
     summaries,
 )

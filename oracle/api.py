@@ -69,6 +69,8 @@ def _L():
         _lib = C.CDLL(_LIB)
         _lib.oracle_round_bf16.restype = C.c_double
         _lib.oracle_round_bf16.argtypes = [C.c_double]
+        _lib.oracle_round_fp16.restype = C.c_double
+        _lib.oracle_round_fp16.argtypes = [C.c_double]
         _lib.oracle_muse_fwd.restype = C.c_int
         _lib.oracle_muse_bwd.restype = C.c_int
     return _lib
@@ -139,6 +141,31 @@ def kmeans(X, Cn, T, init_idx=None, cent0=None, round_mode=0):
     _L().oracle_kmeans(C.c_int(N), C.c_int(D), C.c_int(Cn), C.c_int(T), C.c_int(round_mode), Xp, ip,
                        _d(cent)[1], _i(assign)[1], _d(margin)[1], _i(counts)[1], _d(obj)[1])
     return dict(cent=cent, assign=assign, margin=margin, counts=counts, objective=obj)
+
+
+def round_fp16(x):
+    """x rounded to IEEE binary16 (nearest even) by the oracle's own routine, elementwise."""
+    f = _L().oracle_round_fp16
+    return np.array([f(float(v)) for v in np.asarray(x, dtype=np.float64).ravel()]).reshape(np.shape(x))
+
+
+def kmeans_stream(X, Cn, init_idx, mb=64, beta=0.9, forced=None):
+    """Streaming centroid pass of App. C "Centroid Computation" (one pass, minibatches of mb rows).
+
+    forced [N]: assignments to follow instead of the nearest centroid (regret reports how far each is from
+    the best).  Returns dict(cent [C,D], t [C,D], c [C], assign [N] (as taken during the pass),
+    margin [N], regret [N])."""
+    X, Xp = _d(X)
+    N, D = X.shape
+    cent = np.zeros((Cn, D)); t = np.zeros((Cn, D)); c = np.zeros(Cn)
+    assign = np.zeros(N, dtype=np.int32); margin = np.zeros(N); regret = np.zeros(N)
+    ii, ip = _i(init_idx)
+    fp = None
+    if forced is not None:
+        ff, fp = _i(forced)
+    _L().oracle_kmeans_stream(C.c_int(N), C.c_int(D), C.c_int(Cn), C.c_int(mb), C.c_double(beta), Xp, ip, fp,
+                              _d(cent)[1], _d(t)[1], _d(c)[1], _i(assign)[1], _d(margin)[1], _d(regret)[1])
+    return dict(cent=cent, t=t, c=c, assign=assign, margin=margin, regret=regret)
 
 
 def summaries(p: MuseParams, K, V, qc, ak, i):

@@ -26,8 +26,12 @@
  *
  * Readings where the paper is silent (all listed in the design notes of the repo):
  *   - Lloyd iterations (assign + mean update) at a fixed count T followed by a
- *     final assignment replace the streaming mini-batch pass; empty cluster keeps
- *     its centroid; ties go to the lowest index.
+ *     final assignment are the default clustering; empty cluster keeps
+ *     its centroid; ties go to the lowest index.  The streaming mini-batch pass of
+ *     App. C is oracle_kmeans_stream (rows in sequence order, state in binary32,
+ *     similarity on binary16 values; pinned by a closed form for one cluster, the
+ *     running mean at beta = 1, a hand-worked minibatch and the decay weights
+ *     recomputed from the returned assignment).
  *   - logit scale: q is multiplied by `scale` before anything else; centroids are
  *     centroids of the raw rows, so q-bar = scale * centroid.
  *   - empty cells have mu = -inf and are never candidates; fewer than r finite
@@ -227,6 +231,116 @@ void oracle_kmeans(int N, int D, int C, int T, int round_mode, const double* X,
     objective[T] = obj;
   }
   free(sum);
+}
+
+/* ------------------------------------------------------------------ */
+/* Streaming centroid pass: App. C "Centroid Computation", step 2.      */
+/*                                                                     */
+/* One pass over the rows in sequence order, in minibatches of `mb`    */
+/* rows (the paper: 64).  All rows of a minibatch are assigned to their */
+/* nearest centroid as the centroids stand when the minibatch starts;  */
+/* then, row by row in order, the total and the count of the row's     */
+/* centroid decay and absorb the row: t <- beta t + x, c <- beta c + 1, */
+/* and the centroid is t / c.  Totals start at the initial centroid    */
+/* (the row init_idx[j]) with count 1.                                 */
+/*                                                                     */
+/* Precision (the paper fixes float16 for the clustering computations, */
+/* and says no more): rows and centroids enter the similarity as       */
+/* binary16 values (x^ = fp16(x), c^ = fp16(t / c)); the score         */
+/* ||c^||^2 - 2 <x^, c^> is evaluated exactly here (fp64 of exact      */
+/* products).  The state t, c is binary32, each update one fused       */
+/* multiply-add, t / c one binary32 division: these decide the rounded */
+/* centroid, so they are taken in that precision on purpose, not fp64. */
+/* Ties go to the lowest index.                                        */
+/*                                                                     */
+/* forced != NULL: row v is assigned to forced[v] instead of the       */
+/* nearest centroid, and regret[v] says how much worse that choice     */
+/* scores than the best one (relative, 0 when it is a best one).       */
+/* ------------------------------------------------------------------ */
+static double round_fp16(double x) {
+  if (x == 0.0 || !isfinite(x)) return x;
+  double a = fabs(x);
+  if (a >= 65520.0) return copysign(INFINITY, x); /* halfway to 2^16 rounds to even = overflow */
+  int e;
+  frexp(a, &e);             /* a = m 2^e, 0.5 <= m < 1 */
+  int ex = e - 1;           /* floor(log2 a) */
+  if (ex < -14) ex = -14;   /* subnormal range: fixed quantum 2^-24 */
+  double q = ldexp(1.0, ex - 10);
+  return copysign(nearbyint(a / q) * q, x); /* nearbyint: round to nearest, ties to even */
+}
+
+double oracle_round_fp16(double x) { return round_fp16(x); }
+
+void oracle_kmeans_stream(int N, int D, int C, int mb, double beta, const double* X,
+                          const int32_t* init_idx, const int32_t* forced, double* cent,
+                          double* t_out, double* c_out, int32_t* assign, double* margin,
+                          double* regret) {
+  const float bf = (float)beta;
+  double* xh = (double*)malloc(sizeof(double) * (size_t)N * D); /* x^ */
+  for (size_t k = 0; k < (size_t)N * D; ++k) xh[k] = round_fp16(X[k]);
+  float* t = (float*)malloc(sizeof(float) * (size_t)C * D);
+  float* c = (float*)malloc(sizeof(float) * (size_t)C);
+  double* ch = (double*)malloc(sizeof(double) * (size_t)C * D); /* c^ */
+  double* c2 = (double*)malloc(sizeof(double) * (size_t)C);
+  for (int j = 0; j < C; ++j) {
+    for (int d = 0; d < D; ++d) t[(size_t)j * D + d] = (float)xh[(size_t)init_idx[j] * D + d];
+    c[j] = 1.0f;
+  }
+  for (int v0 = 0; v0 < N; v0 += mb) {
+    int v1 = v0 + mb < N ? v0 + mb : N;
+    /* centroids as they stand now */
+    for (int j = 0; j < C; ++j) {
+      for (int d = 0; d < D; ++d) ch[(size_t)j * D + d] = round_fp16((double)(t[(size_t)j * D + d] / c[j]));
+      c2[j] = dot(ch + (size_t)j * D, ch + (size_t)j * D, D);
+    }
+    /* nearest centroid of every row of the minibatch */
+    for (int v = v0; v < v1; ++v) {
+      double best = INFINITY, second = INFINITY;
+      int bj = 0;
+      for (int j = 0; j < C; ++j) {
+        double s = c2[j] - 2.0 * dot(xh + (size_t)v * D, ch + (size_t)j * D, D);
+        if (s < best) {
+          second = best;
+          best = s;
+          bj = j;
+        } else if (s < second) {
+          second = s;
+        }
+      }
+      if (margin) {
+        double den = fmax(1.0, fmax(fabs(best), fabs(second)));
+        margin[v] = isfinite(second) ? (second - best) / den : INFINITY;
+      }
+      if (forced) {
+        int fj = forced[v];
+        double sf = c2[fj] - 2.0 * dot(xh + (size_t)v * D, ch + (size_t)fj * D, D);
+        if (regret) regret[v] = (sf - best) / fmax(1.0, fmax(fabs(best), fabs(sf)));
+        bj = fj;
+      } else if (regret) {
+        regret[v] = 0.0;
+      }
+      assign[v] = bj;
+    }
+    /* the rows update their centroids one after the other */
+    for (int v = v0; v < v1; ++v) {
+      int j = assign[v];
+      for (int d = 0; d < D; ++d)
+        t[(size_t)j * D + d] = fmaf(bf, t[(size_t)j * D + d], (float)xh[(size_t)v * D + d]);
+      c[j] = fmaf(bf, c[j], 1.0f);
+    }
+  }
+  for (int j = 0; j < C; ++j) {
+    for (int d = 0; d < D; ++d) {
+      cent[(size_t)j * D + d] = (double)(t[(size_t)j * D + d] / c[j]);
+      if (t_out) t_out[(size_t)j * D + d] = (double)t[(size_t)j * D + d];
+    }
+    if (c_out) c_out[j] = (double)c[j];
+  }
+  free(xh);
+  free(t);
+  free(c);
+  free(ch);
+  free(c2);
 }
 
 /* ------------------------------------------------------------------ */

@@ -463,6 +463,137 @@ def test_config1_mixture_clusters_are_pure(oracle):
 
 
 # ---------------------------------------------------------------------------
+# streaming centroid pass (App. C "Centroid Computation", step 2)
+# ---------------------------------------------------------------------------
+def test_fp16_rounding_matches_library(oracle):
+    rng = np.random.default_rng(7)
+    x = np.concatenate([rng.normal(size=2000), rng.normal(size=500) * 1e-5, rng.normal(size=500) * 3e4,
+                        [0.0, -0.0, 65504.0, 65519.9, 65520.0, -65520.0, 2.0 ** -24, 2.0 ** -25, 1.5 * 2.0 ** -24,
+                         1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 2049.0, 2051.0]])
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).astype(np.float64)
+    np.testing.assert_array_equal(oracle.round_fp16(x), want)
+
+
+@pytest.mark.parametrize("N,mb", [(300, 64), (10, 4), (7, 64)])
+def test_stream_single_cluster_closed_form(oracle, N, mb):
+    """One cluster takes every row: t_N = b^N x_init + sum_v b^(N-1-v) x_v, c_N = b^N + (1 - b^N) / (1 - b)."""
+    rng = np.random.default_rng(11)
+    beta = 0.9
+    X = rng.normal(size=(N, 8)).astype(np.float16).astype(np.float64)
+    got = oracle.kmeans_stream(X, 1, [3], mb=mb, beta=beta)
+    b = np.float64(np.float32(beta))
+    w = b ** np.arange(N - 1, -1, -1)
+    t = b ** N * X[3] + w @ X
+    c = b ** N + (1 - b ** N) / (1 - b)
+    np.testing.assert_allclose(got["c"][0], c, rtol=2e-6)
+    np.testing.assert_allclose(got["t"][0], t, rtol=0, atol=2e-6 * np.abs(t).max())
+    np.testing.assert_allclose(got["cent"][0], t / c, rtol=0, atol=2e-6 * np.abs(t / c).max())
+    assert (got["assign"] == 0).all()
+
+
+def test_stream_beta_one_is_the_running_mean(oracle):
+    """With beta = 1 and well separated groups the pass is sequential K-means: the centroid is the mean of its
+    initial row and of every row of its group (the initial row is also streamed, so it counts twice)."""
+    rng = np.random.default_rng(12)
+    Cn, N, D = 6, 700, 16
+    centres = 4.0 * rng.normal(size=(Cn, D))
+    lab = rng.integers(0, Cn, N)
+    lab[:Cn] = np.arange(Cn)
+    X = (centres[lab] + 0.05 * rng.normal(size=(N, D))).astype(np.float16).astype(np.float64)
+    init = rng.permutation(Cn)  # centroid j starts at row init[j], whose group is init[j]
+    got = oracle.kmeans_stream(X, Cn, init, mb=64, beta=1.0)
+    np.testing.assert_array_equal(init[got["assign"]], lab)
+    for j in range(Cn):
+        rows = X[lab == init[j]]
+        np.testing.assert_allclose(got["cent"][j], (X[init[j]] + rows.sum(0)) / (1 + len(rows)), rtol=0, atol=2e-5)
+        assert got["c"][j] == 1 + len(rows)
+
+
+def test_stream_hand_worked_minibatch(oracle):
+    """Rows 0, 10, 4, 5.5 on a line, centroids start at rows 0 and 1, beta = 0.9.
+    One minibatch of four: all four rows are assigned against the centroids 0 and 10, so 5.5 goes to the
+    second (4.5 away against 5.5); updates in row order give t = (4, 0.9 (0.9 10 + 10) + 5.5), c = 2.71 twice.
+    Minibatches of one: row 4 has already moved the first centroid to 4 / 2.71 = 1.476 when 5.5 is assigned,
+    4.02 away against 4.5 from the second, so it joins the first."""
+    X = np.zeros((4, 2))
+    X[:, 0] = [0.0, 10.0, 4.0, 5.5]
+    b = np.float64(np.float32(0.9))
+    one = oracle.kmeans_stream(X, 2, [0, 1], mb=4, beta=0.9)
+    np.testing.assert_array_equal(one["assign"], [0, 1, 0, 1])
+    c2 = b * (b + 1) + 1
+    np.testing.assert_allclose(one["c"], [c2, c2], rtol=1e-6)
+    np.testing.assert_allclose(one["t"][:, 0], [4.0, b * (b * 10 + 10) + 5.5], rtol=1e-6)
+    np.testing.assert_allclose(one["cent"][:, 0], [4.0 / c2, (b * (b * 10 + 10) + 5.5) / c2], rtol=1e-6)
+    assert (one["t"][:, 1] == 0).all()
+    seq = oracle.kmeans_stream(X, 2, [0, 1], mb=1, beta=0.9)
+    np.testing.assert_array_equal(seq["assign"], [0, 1, 0, 0])
+    np.testing.assert_allclose(seq["c"], [b * c2 + 1, b + 1], rtol=1e-6)
+    np.testing.assert_allclose(seq["t"][:, 0], [b * 4.0 + 5.5, b * 10 + 10], rtol=1e-6)
+
+
+def test_stream_ties_go_to_the_lowest_index(oracle):
+    X = np.ones((2, 4))
+    got = oracle.kmeans_stream(X, 2, [0, 1], mb=2, beta=0.9)
+    np.testing.assert_array_equal(got["assign"], [0, 0])
+    np.testing.assert_allclose(got["c"], [0.9 * 1.9 + 1, 1.0], rtol=1e-6)
+    assert (got["margin"] == 0).all()
+
+
+def test_stream_similarity_sees_fp16_centroids(oracle):
+    """Rows 1, 3, 3 - 2^-9, 2 in minibatches of one.  The third row joins the second centroid and pulls it to
+    8.128 / 2.71 = 2.99928, which binary16 (spacing 2^-9 there) rounds back to 3.  The last row, 2, is then
+    exactly between the rounded centroids 1 and 3 and the tie goes low; against the unrounded 2.99928 it would
+    have been nearer to the second."""
+    X = np.zeros((4, 1))
+    X[:, 0] = [1.0, 3.0, 3.0 - 2.0 ** -9, 2.0]
+    got = oracle.kmeans_stream(X, 2, [0, 1], mb=1, beta=0.9)
+    np.testing.assert_array_equal(got["assign"][:3], [0, 1, 1])
+    assert abs(got["t"][1, 0] / got["c"][1] - 2.99928) < 1e-4
+    assert got["assign"][3] == 0 and got["margin"][3] < 1e-6
+
+
+def test_stream_state_is_the_decayed_sum_of_the_assigned_rows(oracle):
+    """Totals and counts recomputed from the returned assignment with explicit decay weights b^(n - k)."""
+    from paper_2509_10406_amd.inputs import generate, small
+
+    w = small("cfg2", N=1000, Hq=1, Hkv=1, Cq=7, Ck=7, block=1000)
+    d = generate(w)
+    X = d["K"][0, 0].double().numpy()
+    init = d["k_init_idx"][0, 0].numpy()
+    got = oracle.kmeans_stream(X, 7, init, mb=64, beta=0.9)
+    Xh = X.astype(np.float16).astype(np.float64)
+    b = np.float64(np.float32(0.9))
+    assert len(np.unique(got["assign"])) > 3
+    for j in range(7):
+        rows = np.flatnonzero(got["assign"] == j)
+        n = len(rows)
+        wts = b ** np.arange(n - 1, -1, -1)
+        t = b ** n * Xh[init[j]] + wts @ Xh[rows]
+        c = b ** n + wts.sum()
+        np.testing.assert_allclose(got["c"][j], c, rtol=2e-6)
+        np.testing.assert_allclose(got["t"][j], t, rtol=0, atol=3e-6 * max(1.0, np.abs(t).max()))
+        np.testing.assert_allclose(got["cent"][j], t / c, rtol=0, atol=3e-6 * max(1.0, np.abs(t / c).max()))
+
+
+def test_stream_forced_assignments(oracle):
+    rng = np.random.default_rng(13)
+    X = rng.normal(size=(200, 8))
+    init = rng.choice(200, 5, replace=False)
+    free = oracle.kmeans_stream(X, 5, init, mb=64, beta=0.9)
+    same = oracle.kmeans_stream(X, 5, init, mb=64, beta=0.9, forced=free["assign"])
+    for k in ("cent", "t", "c", "assign"):
+        np.testing.assert_array_equal(free[k], same[k])
+    assert (same["regret"] == 0).all()
+    planted = free["assign"].copy()
+    planted[70] = (planted[70] + 1) % 5
+    other = oracle.kmeans_stream(X, 5, init, mb=64, beta=0.9, forced=planted)
+    assert other["regret"][70] > 0 and other["assign"][70] == planted[70]
+    assert (other["regret"][:64] == 0).all()
+    assert not np.array_equal(other["cent"], free["cent"])
+
+
+# ---------------------------------------------------------------------------
 # trends the paper reports (Table 2, App. E): error falls with more clusters and with larger r
 # ---------------------------------------------------------------------------
 def test_error_falls_with_clusters_and_retrieval(oracle):
