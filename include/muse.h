@@ -55,7 +55,11 @@ enum { MUSE_FLAG_KEEP_FWD_STATE = 1,
  * the backward, so a summarised key receives a gradient only through the aggregated key, dk_m = (e_m / S) g_kbar
  * (and dv_m = (e_m / S) g_vbar as before); dQ and dV are unchanged.  The default differentiates through the
  * weights. */
-       MUSE_FLAG_FROZEN_WEIGHTS = 2 };
+       MUSE_FLAG_FROZEN_WEIGHTS = 2,
+/* MUSE_FLAG_STREAMING_KMEANS (muse_cluster only; App. C "Centroid Computation"): the centroids come from the
+ * single streaming pass described at muse_kmeans_stream instead of Lloyd iterations (kmeans_iters is ignored);
+ * the final nearest-centroid assignment is the same. */
+       MUSE_FLAG_STREAMING_KMEANS = 4 };
 enum { MUSE_WS_CLUSTER = 0, MUSE_WS_FWD = 1, MUSE_WS_BWD = 2, MUSE_WS_EXACT_FWD = 3, MUSE_WS_EXACT_BWD = 4 };
 
 typedef struct {
@@ -111,6 +115,22 @@ int muse_cluster(const muse_params* p, const void* Q, const void* K,
                  float* q_centroids, int32_t* q_assign,
                  float* k_centroids, int32_t* k_assign,
                  void* ws, size_t ws_bytes, void* stream);
+
+/* The streaming centroid pass alone, for one side (App. C "Centroid Computation", step 2): per head, the rows
+ * are visited once in sequence order in minibatches of 64.  All rows of a minibatch are assigned to their
+ * nearest centroid as the centroids stand when the minibatch starts (smallest ||c^||^2 - 2 <x^, c^> on binary16
+ * values x^ = fp16(x), c^ = fp16(t / c), fp32 sums, lowest index on ties); then, row by row, the total and count
+ * of the row's centroid become t <- 0.9 t + x^, c <- 0.9 c + 1 (fp32, one fused multiply-add each).  Totals start
+ * at the row init_idx[j] with count 1; the centroid is t / c.  Rows must lie in the binary16 range.
+ *   side: 0 = query rows (B*Hq heads, Cq clusters), 1 = key rows (B*Hkv heads, Ck clusters)
+ *   X [B,H,N,D] dtype (in); init_idx [B,H,C] int32 (in; NULL: start from `centroids`)
+ *   centroids [B,H,C,D] fp32 (in/out)
+ *   stream_assign [B,H,N] int32: the centroid each row went to when its minibatch was processed (out, may be NULL)
+ *   counts [B,H,C] fp32: the decayed counts c (out, may be NULL)
+ *   ws: at least half of MUSE_WS_CLUSTER.
+ * Errors as muse_cluster. */
+int muse_kmeans_stream(const muse_params* p, int side, const void* X, const int32_t* init_idx, float* centroids,
+                       int32_t* stream_assign, float* counts, void* ws, size_t ws_bytes, void* stream);
 
 /* Forward (Sec. 3.1-3.3, Alg. 1): per-block tilted summaries (Eq. 4-6), exclusive causal
  * accumulation, cluster selection by Eq. 7, spatial block selection, exact attention on the

@@ -20,8 +20,9 @@ _lib = None
 FP32, BF16 = 0, 1
 FLAG_KEEP_FWD_STATE = 1
 FLAG_FROZEN_WEIGHTS = 2
+FLAG_STREAMING_KMEANS = 4
 WS_CLUSTER, WS_FWD, WS_BWD, WS_EXACT_FWD, WS_EXACT_BWD = range(5)
-SYMBOLS = ["muse_workspace_bytes", "muse_cluster", "muse_fwd", "muse_bwd", "exact_attn_fwd", "exact_attn_bwd",
+SYMBOLS = ["muse_workspace_bytes", "muse_cluster", "muse_kmeans_stream", "muse_fwd", "muse_bwd", "exact_attn_fwd", "exact_attn_bwd",
            "muse_profile_enable", "muse_profile_report", "muse_strerror"]
 
 
@@ -163,6 +164,22 @@ def muse_cluster(p: Params, Q, K, q_init_idx, k_init_idx, q_centroids=None, k_ce
                                _ptr(qa), _ptr(k_centroids), _ptr(ka), _ptr(ws), C.c_size_t(ws.numel()), _stream()),
            "muse_cluster")
     return q_centroids, qa, k_centroids, ka
+
+
+def muse_kmeans_stream(p: Params, side: int, X, init_idx, centroids=None, ws=None):
+    """The streaming centroid pass alone.  side 0: query rows, 1: key rows.
+    Returns (centroids, stream_assign, counts)."""
+    dev = X.device
+    H, Cn = (p.Hkv, p.Ck) if side else (p.Hq, p.Cq)
+    ws = ws if ws is not None else workspace(p, WS_CLUSTER, dev)
+    if centroids is None:
+        centroids = torch.empty(p.B, H, Cn, p.D, dtype=torch.float32, device=dev)
+    sa = torch.empty(p.B, H, p.N, dtype=torch.int32, device=dev)
+    cnt = torch.empty(p.B, H, Cn, dtype=torch.float32, device=dev)
+    pc = p.c()
+    _check(load().muse_kmeans_stream(C.byref(pc), C.c_int(side), _ptr(X), _ptr(init_idx), _ptr(centroids), _ptr(sa),
+                                     _ptr(cnt), _ptr(ws), C.c_size_t(ws.numel()), _stream()), "muse_kmeans_stream")
+    return centroids, sa, cnt
 
 
 def muse_fwd(p: Params, Q, K, V, q_centroids, q_assign, k_assign, ws=None, out=None):

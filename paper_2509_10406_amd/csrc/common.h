@@ -136,6 +136,7 @@ struct MuseDims {
   float scale;
   bool keep_state;  // MUSE_FLAG_KEEP_FWD_STATE
   bool frozen_weights;  // MUSE_FLAG_FROZEN_WEIGHTS
+  bool streaming;       // MUSE_FLAG_STREAMING_KMEANS
 };
 
 #define MUSE_HIP_CHECK(expr)                      \
@@ -176,8 +177,10 @@ struct MuseProf {
 // ---- stage launchers (one per translation unit) ------------------------------------------
 // kmeans.hip
 size_t muse_cluster_ws_bytes(const MuseDims& d);
+// d.streaming: the centroids come from the streaming pass (trace [heads,N], counts [heads,C]: optional outputs
+// of that pass; assign may then be NULL to stop after it)
 int muse_launch_cluster(const MuseDims& d, const void* X, int H, int C, const int32_t* init_idx,
-                        float* cent, int32_t* assign, void* ws, hipStream_t st);
+                        float* cent, int32_t* assign, int32_t* trace, float* counts, void* ws, hipStream_t st);
 // Stable bucketing of the N positions of every head by (spatial block, cluster):
 // perm [heads, N] position lists, off [heads, nb*C + 1] segment offsets.
 int muse_launch_bucket(const int32_t* assign, int heads, int N, int Bs, int C, int32_t* perm,

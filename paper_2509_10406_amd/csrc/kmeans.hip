@@ -343,22 +343,325 @@ __global__ void __launch_bounds__(256) k_update(const T* __restrict__ X, const i
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Streaming centroid pass (App. C "Centroid Computation", step 2): one pass over the rows of a head in
+// sequence order, minibatches of 64.  Every row of a minibatch is assigned to its nearest centroid as the
+// centroids stand when the minibatch starts; then, row by row, the total and the count of the row's centroid
+// decay and absorb it: t <- beta t + x, c <- beta c + 1 (beta = 0.9), centroid = t / c.
+//
+// The pass is sequential over the N / 64 minibatches, so one workgroup (4 waves) owns a head from start to
+// end.  Rows and centroids enter the similarity as binary16 (App. C: the clustering runs in float16) on
+// MFMA 32x32x16 f16 with fp32 accumulation: centroid tiles are the A operand (read from the L2-resident
+// binary16 copy), the 64 rows of the minibatch the B operand (LDS), each wave takes every fourth tile of 32
+// centroids.  The state t, c stays fp32 (one fma per update, one division per centroid); only the centroids
+// that a minibatch touches are rewritten, one wave per distinct centroid, all loads of a wave's centroids
+// issued before the first is used.
+// ------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) _Float16 kf16x8_t;
+constexpr int kStreamMB = 64;
+constexpr float kStreamBeta = 0.9f;
+// operands of TB tiles of 32 centroids: this lane's row of each tile (its half of every 16 dims) and the
+// -||c^||^2 / 2 of the 16 centroids whose scores land in this lane
+template <int D>
+struct CentBatch {
+  static constexpr int TB = 256 / D;  // registers: two batches are live
+  kf16x8_t ca[TB][D / 16];
+  float4 nv[TB][4];
+};
+
+template <typename T, int D>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+k_stream_kmeans(const T* __restrict__ X, const int32_t* __restrict__ init_idx, float* __restrict__ cent,
+                float* __restrict__ tst, float* __restrict__ cst, _Float16* __restrict__ chat,
+                float* __restrict__ nhc2, int32_t* __restrict__ trace, float* __restrict__ counts_out, int N, int C) {
+  // cst and nhc2 are [heads][CS], CS = C rounded up to a whole tile of 32 (16-byte reads of a tile's 32 values)
+  constexpr int KS = D / 16, DL = D / 64;         // k-steps of the similarity; dims per lane in the update
+  constexpr int CPR = D / 8, NCH = 64 * CPR / 256;  // 16-byte (bf16) / 32-byte (fp32) chunks of a minibatch per thread
+  __shared__ __attribute__((aligned(16))) _Float16 xs[kStreamMB][D + 8];
+  __shared__ float bval[4][kStreamMB];
+  __shared__ int bidx[4][kStreamMB];
+  const int h = blockIdx.x;
+  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, col = lane % 32, half = lane / 32;
+  const T* Xh = X + (size_t)h * N * D;
+  float* th = tst + (size_t)h * C * D;
+  const int CS = (C + 31) / 32 * 32;
+  float* ch_ = cst + (size_t)h * CS;
+  _Float16* hh = chat + (size_t)h * C * D;
+  float* nh = nhc2 + (size_t)h * CS;
+  float* ce = cent + (size_t)h * C * D;
+
+  // ---- initial state: t = the initial centroid (as binary16 values), c = 1 ----
+  for (int j = wave; j < C; j += 4) {
+    float s = 0.f;
+#pragma unroll
+    for (int x = 0; x < DL; ++x) {
+      const int d = lane + 64 * x;
+      float v = init_idx ? Elem<T>::ld(Xh, (size_t)init_idx[(size_t)h * C + j] * D + d) : ce[(size_t)j * D + d];
+      const _Float16 vh = (_Float16)v;
+      if (init_idx) v = (float)vh;
+      th[(size_t)j * D + d] = v;
+      hh[(size_t)j * D + d] = vh;
+      s += (float)vh * (float)vh;
+    }
+    s = wave_sum(s);
+    if (lane == 0) {
+      ch_[j] = 1.f;
+      nh[j] = -0.5f * s;
+    }
+  }
+
+  // raw rows of a minibatch, this thread's chunks (row = c % 64, 8 dims from 8 (c / 64)); rows past N repeat N - 1
+  auto row_ptr = [&](int v0, int it) {
+    const int c = tid + 256 * it;
+    int gr = v0 + c % 64;
+    gr = gr < N ? gr : N - 1;
+    return Xh + (size_t)gr * D + (c / 64) * 8;
+  };
+  uint4 ra[NCH], rb[sizeof(T) == 4 ? NCH : 1];
+#pragma unroll
+  for (int it = 0; it < NCH; ++it) {
+    ra[it] = *reinterpret_cast<const uint4*>(row_ptr(0, it));
+    if constexpr (sizeof(T) == 4) rb[it] = *reinterpret_cast<const uint4*>(row_ptr(0, it) + 4);
+  }
+  const int ntile = (C + 31) / 32;
+  const int nmb = (N + kStreamMB - 1) / kStreamMB;
+  for (int mbi = 0; mbi < nmb; ++mbi) {
+    const int v0 = mbi * kStreamMB;
+    __syncthreads();  // state of the previous minibatch is written; xs is free
+    // ---- the minibatch as binary16 in LDS ----
+#pragma unroll
+    for (int it = 0; it < NCH; ++it) {
+      const int c = tid + 256 * it, row = c % 64, cc = c / 64;
+      kf16x8_t o;
+      if constexpr (sizeof(T) == 2) {
+        const uint32_t w[4] = {ra[it].x, ra[it].y, ra[it].z, ra[it].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          o[2 * e] = (_Float16)__uint_as_float(w[e] << 16);
+          o[2 * e + 1] = (_Float16)__uint_as_float(w[e] & 0xffff0000u);
+        }
+      } else {
+        const uint32_t w[8] = {ra[it].x, ra[it].y, ra[it].z, ra[it].w, rb[it].x, rb[it].y, rb[it].z, rb[it].w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (_Float16)__uint_as_float(w[e]);
+      }
+      *reinterpret_cast<kf16x8_t*>(&xs[row][cc * 8]) = o;
+    }
+    __syncthreads();
+    // next minibatch's rows: independent of the state, in flight during this one
+    {
+      const int vn = mbi + 1 < nmb ? v0 + kStreamMB : v0;
+#pragma unroll
+      for (int it = 0; it < NCH; ++it) {
+        ra[it] = *reinterpret_cast<const uint4*>(row_ptr(vn, it));
+        if constexpr (sizeof(T) == 4) rb[it] = *reinterpret_cast<const uint4*>(row_ptr(vn, it) + 4);
+      }
+    }
+    // ---- similarity x^ . c^ - ||c^||^2 / 2 against every centroid, running argmax per lane ----
+    kf16x8_t xb[2][KS];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) xb[hf][ks] = *reinterpret_cast<const kf16x8_t*>(&xs[32 * hf + col][16 * ks + 8 * half]);
+    float best[2] = {MUSE_NEG_INF, MUSE_NEG_INF};
+    int bj[2] = {0x7fffffff, 0x7fffffff};
+    // this wave's tiles jt = wave + 4 k in batches of TB: the operands of a whole batch are requested before the
+    // first is used, and the next batch is in flight while this one is scored (loads are unconditional: tiles
+    // past the end re-read the last one and are skipped when scoring)
+    auto load_cb = [&](CentBatch<D>& cb, int k0) {
+#pragma unroll
+      for (int tb = 0; tb < CentBatch<D>::TB; ++tb) {
+        int jt = wave + 4 * (k0 + tb);
+        jt = jt < ntile ? jt : ntile - 1;
+        const int j0 = jt * 32;
+        const int jr = j0 + col < C ? j0 + col : C - 1;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          cb.ca[tb][ks] = *reinterpret_cast<const kf16x8_t*>(hh + (size_t)jr * D + 16 * ks + 8 * half);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) cb.nv[tb][g] = *reinterpret_cast<const float4*>(nh + j0 + 8 * g + 4 * half);
+      }
+    };
+    auto score_cb = [&](const CentBatch<D>& cb, int k0) {
+#pragma unroll
+      for (int tb = 0; tb < CentBatch<D>::TB; ++tb) {
+        const int jt = wave + 4 * (k0 + tb);
+        if (jt < ntile) {
+          const int j0 = jt * 32;
+#pragma unroll
+          for (int hf = 0; hf < 2; ++hf) {
+            f32x16_t acc;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+              acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(cb.ca[tb][ks], xb[hf][ks], acc, 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int j = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+              const float4 n4 = cb.nv[tb][e / 4];
+              const float nv = (e % 4) == 0 ? n4.x : (e % 4) == 1 ? n4.y : (e % 4) == 2 ? n4.z : n4.w;
+              const float sc = j < C ? acc[e] + nv : MUSE_NEG_INF;
+              if (sc > best[hf]) {
+                best[hf] = sc;
+                bj[hf] = j;
+              }
+            }
+          }
+        }
+      }
+    };
+    {
+      const int nk = (ntile - wave + 3) / 4;  // tiles of this wave
+      constexpr int TB = CentBatch<D>::TB;
+      CentBatch<D> ba, bb;
+      load_cb(ba, 0);
+      for (int k0 = 0; k0 < nk; k0 += 2 * TB) {
+        load_cb(bb, k0 + TB);
+        score_cb(ba, k0);
+        load_cb(ba, k0 + 2 * TB);
+        if (k0 + TB < nk) score_cb(bb, k0 + TB);
+      }
+    }
+    // the two halves of a row's centroids, then the four waves; ties go to the lowest index
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      const float ov = __shfl_xor(best[hf], 32, 64);
+      const int oj = __shfl_xor(bj[hf], 32, 64);
+      if (ov > best[hf] || (ov == best[hf] && oj < bj[hf])) {
+        best[hf] = ov;
+        bj[hf] = oj;
+      }
+    }
+    if (half == 0) {
+      bval[wave][col] = best[0]; bidx[wave][col] = bj[0];
+      bval[wave][32 + col] = best[1]; bidx[wave][32 + col] = bj[1];
+    }
+    __syncthreads();
+    // every wave derives the assignment of all 64 rows (lane = row of the minibatch)
+    int a;
+    {
+      float bv = bval[0][lane];
+      a = bidx[0][lane];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {
+        const float ov = bval[w][lane];
+        const int oj = bidx[w][lane];
+        if (ov > bv || (ov == bv && oj < a)) {
+          bv = ov;
+          a = oj;
+        }
+      }
+    }
+    const bool live = v0 + lane < N;
+    if (wave == 0 && live && trace) trace[(size_t)h * N + v0 + lane] = a;
+    if (!live) a = -1 - lane;  // a class of its own that nobody updates
+    // ---- classes of equal assignment: mask of the rows that share this row's centroid ----
+    unsigned long long cls = 0;
+    for (int u = 0; u < 64; ++u) {
+      const int au = __builtin_amdgcn_readlane(a, u);
+      const unsigned long long m = __ballot(a == au);
+      if (lane == u) cls = m;
+    }
+    const bool leader = live && (__ffsll((long long)cls) - 1 == lane);
+    const unsigned long long lead = __ballot(leader);
+    // ---- updates: the k-th leader's centroid belongs to wave k % 4; a lane owns the dims lane + 64 x ----
+    constexpr int MAXL = 16;  // at most 64 distinct centroids per minibatch, 16 per wave
+    int lj[MAXL];
+    unsigned long long lm[MAXL];
+    float tv[MAXL][DL], cv[MAXL];
+    int nl = 0;
+    {
+      unsigned long long rest = lead;  // wave-uniform
+      for (int w = 0; w < wave; ++w) rest &= rest - 1;
+#pragma unroll
+      for (int q = 0; q < MAXL; ++q) {
+        if (rest) {
+          const int u = __ffsll((long long)rest) - 1;
+          const int j = __builtin_amdgcn_readlane(a, u);
+          const unsigned lo = __builtin_amdgcn_readlane((unsigned)cls, u), hi = __builtin_amdgcn_readlane((unsigned)(cls >> 32), u);
+          lj[q] = j;
+          lm[q] = ((unsigned long long)hi << 32) | lo;
+#pragma unroll
+          for (int x = 0; x < DL; ++x) tv[q][x] = th[(size_t)j * D + lane + 64 * x];
+          cv[q] = ch_[j];
+          nl = q + 1;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) rest &= rest - 1;
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < MAXL; ++q) {
+      if (q < nl) {
+        const int j = lj[q];
+        unsigned long long m = lm[q];
+        float c = cv[q];
+        float t[DL];
+#pragma unroll
+        for (int x = 0; x < DL; ++x) t[x] = tv[q][x];
+        while (m) {  // rows of the class in order
+          const int u = __ffsll((long long)m) - 1;
+          m &= m - 1;
+#pragma unroll
+          for (int x = 0; x < DL; ++x) t[x] = fmaf(kStreamBeta, t[x], (float)xs[u][lane + 64 * x]);
+          c = fmaf(kStreamBeta, c, 1.f);
+        }
+        float s = 0.f;
+#pragma unroll
+        for (int x = 0; x < DL; ++x) {
+          th[(size_t)j * D + lane + 64 * x] = t[x];
+          const _Float16 vh = (_Float16)(t[x] / c);
+          hh[(size_t)j * D + lane + 64 * x] = vh;
+          s += (float)vh * (float)vh;
+        }
+        s = wave_sum(s);
+        if (lane == 0) {
+          ch_[j] = c;
+          nh[j] = -0.5f * s;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  // ---- centroids of the raw rows: t / c ----
+  for (int j = wave; j < C; j += 4) {
+    const float c = ch_[j];
+#pragma unroll
+    for (int x = 0; x < DL; ++x) ce[(size_t)j * D + lane + 64 * x] = th[(size_t)j * D + lane + 64 * x] / c;
+    if (lane == 0 && counts_out) counts_out[(size_t)h * C + j] = c;
+  }
+}
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 template <typename T>
 int cluster_impl(const MuseDims& d, const T* X, int H, int C, const int32_t* init_idx, float* cent,
-                 int32_t* assign, void* ws, hipStream_t st) {
+                 int32_t* assign, int32_t* trace, float* counts, void* ws, hipStream_t st) {
   const int N = d.N, D = d.D, heads = d.B * H;
   char* w = (char*)ws;
   T* chat = (T*)w;                w += align256((size_t)heads * C * D * sizeof(T));
   float* nhc2 = (float*)w;        w += align256((size_t)heads * C * sizeof(float));
   int32_t* perm = (int32_t*)w;    w += align256((size_t)heads * N * sizeof(int32_t));
-  int32_t* off = (int32_t*)w;
-  if (init_idx) {
+  int32_t* off = (int32_t*)w;   w += align256((size_t)heads * ((size_t)d.nb * C + 1) * sizeof(int32_t));
+  if (d.streaming) {
+    // App. C "Centroid Computation": the streaming pass gives the centroids, one final assignment follows
+    const size_t CS = (size_t)(C + 31) / 32 * 32;
+    float* tst = (float*)w;        w += align256((size_t)heads * C * D * sizeof(float));
+    float* cst = (float*)w;        w += align256((size_t)heads * CS * sizeof(float));
+    _Float16* shat = (_Float16*)w; w += align256((size_t)heads * C * D * sizeof(_Float16));
+    float* snh = (float*)w;
+    if (D == 64) { MuseProf prof_("k_stream_kmeans", st); hipLaunchKernelGGL((k_stream_kmeans<T, 64>), dim3(heads), dim3(256), 0, st, X, init_idx, cent, tst, cst, shat, snh, trace, counts, N, C); }
+    else { MuseProf prof_("k_stream_kmeans", st); hipLaunchKernelGGL((k_stream_kmeans<T, 128>), dim3(heads), dim3(256), 0, st, X, init_idx, cent, tst, cst, shat, snh, trace, counts, N, C); }
+    MUSE_LAUNCH_CHECK();
+    if (!assign) return MUSE_OK;
+  }
+  const int T_ = d.streaming ? 0 : d.T;
+  if (init_idx && !d.streaming) {
     { MuseProf prof_("k_init_centroids", st); hipLaunchKernelGGL(k_init_centroids<T>, dim3(C, heads), dim3(64), 0, st, X, init_idx, cent, N, D, C); }
     MUSE_LAUNCH_CHECK();
   }
-  for (int it = 0; it <= d.T; ++it) {
+  for (int it = 0; it <= T_; ++it) {
     int rows = heads * C;
     { MuseProf prof_("k_prep_centroids", st); hipLaunchKernelGGL(k_prep_centroids<T>, dim3((rows + 3) / 4), dim3(256), 0, st, cent, chat, nhc2, D, rows); }
     MUSE_LAUNCH_CHECK();
@@ -373,7 +676,7 @@ int cluster_impl(const MuseDims& d, const T* X, int H, int C, const int32_t* ini
       else { MuseProf prof_("k_assign_bf16", st); hipLaunchKernelGGL((k_assign_bf16<128, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C); }
     }
     MUSE_LAUNCH_CHECK();
-    if (it == d.T) break;
+    if (it == T_) break;
     int rc = muse_launch_bucket(assign, heads, N, d.Bs, C, perm, off, st);
     if (rc) return rc;
     { MuseProf prof_("k_update", st); hipLaunchKernelGGL(k_update<T>, dim3((rows + 3) / 4), dim3(256), 0, st, X, perm, off, cent, N, D, C, d.nb, rows); }
@@ -387,8 +690,11 @@ int cluster_impl(const MuseDims& d, const T* X, int H, int C, const int32_t* ini
 size_t muse_cluster_ws_bytes(const MuseDims& d) {
   size_t heads = (size_t)d.B * (d.Hq > d.Hkv ? d.Hq : d.Hkv);
   size_t C = d.Cq > d.Ck ? d.Cq : d.Ck;
+  size_t CS = (C + 31) / 32 * 32;
   return align256(heads * C * d.D * 4) + align256(heads * C * 4) + align256(heads * d.N * 4) +
-         align256(heads * ((size_t)d.nb * C + 1) * 4);
+         align256(heads * ((size_t)d.nb * C + 1) * 4) +
+         // state of the streaming pass: totals, counts, binary16 centroids and their -||c^||^2 / 2
+         align256(heads * C * d.D * 4) + align256(heads * CS * 4) + align256(heads * C * d.D * 2) + align256(heads * CS * 4);
 }
 
 int muse_launch_bucket(const int32_t* assign, int heads, int N, int Bs, int C, int32_t* perm,
@@ -406,7 +712,7 @@ int muse_launch_bucket(const int32_t* assign, int heads, int N, int Bs, int C, i
 }
 
 int muse_launch_cluster(const MuseDims& d, const void* X, int H, int C, const int32_t* init_idx,
-                        float* cent, int32_t* assign, void* ws, hipStream_t st) {
-  if (d.dtype == MUSE_DTYPE_FP32) return cluster_impl<float>(d, (const float*)X, H, C, init_idx, cent, assign, ws, st);
-  return cluster_impl<bf16_t>(d, (const bf16_t*)X, H, C, init_idx, cent, assign, ws, st);
+                        float* cent, int32_t* assign, int32_t* trace, float* counts, void* ws, hipStream_t st) {
+  if (d.dtype == MUSE_DTYPE_FP32) return cluster_impl<float>(d, (const float*)X, H, C, init_idx, cent, assign, trace, counts, ws, st);
+  return cluster_impl<bf16_t>(d, (const bf16_t*)X, H, C, init_idx, cent, assign, trace, counts, ws, st);
 }

@@ -70,9 +70,10 @@ int make_dims(const muse_params* p, bool full, MuseDims* d) {
   if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->N < 1 || p->Hq % p->Hkv) return MUSE_ERR_INVALID_ARG;
   if (p->dtype != MUSE_DTYPE_FP32 && p->dtype != MUSE_DTYPE_BF16) return MUSE_ERR_INVALID_ARG;
   if (p->grad_dtype != MUSE_DTYPE_FP32 && p->grad_dtype != p->dtype) return MUSE_ERR_INVALID_ARG;
-  if (p->flags & ~(uint32_t)(MUSE_FLAG_KEEP_FWD_STATE | MUSE_FLAG_FROZEN_WEIGHTS)) return MUSE_ERR_INVALID_ARG;
+  if (p->flags & ~(uint32_t)(MUSE_FLAG_KEEP_FWD_STATE | MUSE_FLAG_FROZEN_WEIGHTS | MUSE_FLAG_STREAMING_KMEANS)) return MUSE_ERR_INVALID_ARG;
   d->keep_state = (p->flags & MUSE_FLAG_KEEP_FWD_STATE) != 0;
   d->frozen_weights = (p->flags & MUSE_FLAG_FROZEN_WEIGHTS) != 0;
+  d->streaming = (p->flags & MUSE_FLAG_STREAMING_KMEANS) != 0;
   if (!(p->scale >= 0.f) || isinf(p->scale)) return MUSE_ERR_INVALID_ARG;
   if (p->causal != 1) return MUSE_ERR_UNSUPPORTED;
   if (p->D != 64 && p->D != 128) return MUSE_ERR_UNSUPPORTED;
@@ -163,16 +164,28 @@ int muse_cluster(const muse_params* p, const void* Q, const void* K, const int32
     MUSE_HIP_CHECK(hipStreamWaitEvent(sk, ax.fork, 0));
   }
   if (K) {
-    rc = muse_launch_cluster(d, K, d.Hkv, d.Ck, k_init_idx, k_centroids, k_assign, (char*)ws + muse_cluster_ws_bytes(d), sk);
+    rc = muse_launch_cluster(d, K, d.Hkv, d.Ck, k_init_idx, k_centroids, k_assign, nullptr, nullptr, (char*)ws + muse_cluster_ws_bytes(d), sk);
     if (rc) return rc;
   }
   if (two) MUSE_HIP_CHECK(hipEventRecord(ax.join, sk));
   if (Q) {
-    rc = muse_launch_cluster(d, Q, d.Hq, d.Cq, q_init_idx, q_centroids, q_assign, ws, st);
+    rc = muse_launch_cluster(d, Q, d.Hq, d.Cq, q_init_idx, q_centroids, q_assign, nullptr, nullptr, ws, st);
     if (rc) return rc;
   }
   if (two) MUSE_HIP_CHECK(hipStreamWaitEvent(st, ax.join, 0));
   return MUSE_OK;
+}
+
+int muse_kmeans_stream(const muse_params* p, int side, const void* X, const int32_t* init_idx, float* centroids,
+                       int32_t* stream_assign, float* counts, void* ws, size_t ws_bytes, void* stream) {
+  MuseDims d;
+  int rc = make_dims(p, true, &d);
+  if (rc) return rc;
+  if ((side != 0 && side != 1) || !X || !centroids || !ws) return MUSE_ERR_INVALID_ARG;
+  if (ws_bytes < muse_cluster_ws_bytes(d)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  d.streaming = true;
+  return muse_launch_cluster(d, X, side ? d.Hkv : d.Hq, side ? d.Ck : d.Cq, init_idx, centroids, nullptr, stream_assign,
+                             counts, ws, (hipStream_t)stream);
 }
 
 int muse_fwd(const muse_params* p, const void* Q, const void* K, const void* V, const float* q_centroids,

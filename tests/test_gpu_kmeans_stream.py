@@ -1,0 +1,118 @@
+"""GPU parity of the streaming centroid pass (App. C "Centroid Computation", step 2) against the CPU oracle,
+through the C ABI.
+
+The pass is sequential and chaotic: one different assignment changes a centroid and everything after it.  So
+the oracle replays the pass along the library's own assignments (teacher forcing) and checks two things:
+every assignment the library took is a nearest centroid (its score is within MARGIN of the best one, relative,
+evaluated exactly on the same binary16 values), and, given those assignments, the decayed counts and the
+centroids are bit-identical (the state arithmetic is fp32 fused multiply-adds and one division on both sides).
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_10406_amd import binding as mb
+from paper_2509_10406_amd.inputs import CONFIGS, generate, small
+from tests.util import dev, f64
+
+pytestmark = pytest.mark.gpu
+
+MARGIN = 1e-5
+
+CASES = {
+    "fp32_cfg1": ("cfg1", dict(N=2048)),
+    "fp32_ragged": ("cfg1", dict(N=1000, Cq=5, Ck=37, block=125)),
+    "fp32_one_cluster": ("cfg1", dict(N=300, Cq=1, Ck=2, block=300)),
+    "bf16_cfg2": ("cfg2", dict(N=4096, Hq=2, Hkv=2, Cq=48, Ck=200, block=512)),
+    "bf16_gqa": ("cfg4", dict(N=2048, Hq=4, Hkv=2, Cq=32, Ck=96, block=256)),
+    "bf16_d128": ("cfg5", dict(N=2080, Hq=2, Hkv=1, Cq=40, Ck=130, block=260)),
+    "bf16_many_tiles": ("cfg2", dict(N=3000, Hq=1, Hkv=1, Cq=300, Ck=1030, block=3000)),
+}
+
+
+def _sides(w, d, p):
+    Q, K = dev(d["Q"], p), dev(d["K"], p)
+    return ((0, Q, w.Hq, w.Cq, d["q_init_idx"]), (1, K, w.Hkv, w.Ck, d["k_init_idx"]))
+
+
+def _check_side(oracle, p, side, X, H, Cn, init, what):
+    cent, sa, cnt = mb.muse_kmeans_stream(p, side, X, init.cuda())
+    torch.cuda.synchronize()
+    for h in range(H):
+        got_a = sa[0, h].cpu().numpy()
+        assert (got_a >= 0).all() and (got_a < Cn).all(), what
+        o = oracle.kmeans_stream(f64(X[0, h]), Cn, init[0, h].numpy(), forced=got_a)
+        worst = float(o["regret"].max())
+        assert worst <= MARGIN, f"{what} head {h}: an assignment is {worst:.2e} (relative) from the nearest centroid"
+        np.testing.assert_array_equal(cnt[0, h].cpu().numpy(), o["c"].astype(np.float32), err_msg=f"{what} head {h}: counts")
+        np.testing.assert_array_equal(cent[0, h].cpu().numpy(), o["cent"].astype(np.float32),
+                                      err_msg=f"{what} head {h}: centroids")
+        # the oracle left alone takes the same assignments wherever its own margin is safe, until the first
+        # row where the two part (after that the centroids differ and nothing can be compared)
+        free = oracle.kmeans_stream(f64(X[0, h]), Cn, init[0, h].numpy())
+        diff = np.flatnonzero(free["assign"] != got_a)
+        if diff.size:
+            assert free["margin"][diff[0]] <= MARGIN, f"{what} head {h}: first difference at row {diff[0]} is not a near-tie"
+    return cent, sa, cnt
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_stream_pass_teacher_forced(oracle, name):
+    base, kw = CASES[name]
+    w = small(base, **kw)
+    d = generate(w)
+    p = mb.params_for(w)
+    for side, X, H, Cn, init in _sides(w, d, p):
+        _check_side(oracle, p, side, X, H, Cn, init, f"{name} side {side}")
+
+
+def test_cluster_with_streaming_flag(oracle):
+    """muse_cluster with MUSE_FLAG_STREAMING_KMEANS: the centroids of the pass, then the usual final assignment."""
+    w = small("cfg2", N=4096, Hq=2, Hkv=2, Cq=48, Ck=200, block=512)
+    d = generate(w)
+    p = mb.params_for(w, flags=mb.FLAG_STREAMING_KMEANS)
+    Q, K = dev(d["Q"], p), dev(d["K"], p)
+    qi, ki = d["q_init_idx"].cuda(), d["k_init_idx"].cuda()
+    qc, qa, kc, ka = mb.muse_cluster(p, Q, K, qi, ki)
+    again = mb.muse_cluster(p, Q, K, qi, ki)
+    for x, y in zip((qc, qa, kc, ka), again):
+        assert torch.equal(x, y)
+    for side, X, H, Cn, cent, asg, init in ((0, Q, w.Hq, w.Cq, qc, qa, qi), (1, K, w.Hkv, w.Ck, kc, ka, ki)):
+        alone, _, _ = mb.muse_kmeans_stream(p, side, X, init)
+        assert torch.equal(alone, cent)
+        for h in range(H):
+            chk = oracle.kmeans(f64(X[0, h]), Cn, 0, cent0=cent[0, h].cpu().double().numpy(), round_mode=1)
+            safe = chk["margin"] > MARGIN
+            assert safe.mean() > 0.99
+            np.testing.assert_array_equal(asg[0, h].cpu().numpy()[safe], chk["assign"][safe])
+    # the Lloyd iteration count plays no role
+    p5 = dataclasses.replace(p, kmeans_iters=5)
+    other = mb.muse_cluster(p5, Q, K, qi, ki)
+    assert torch.equal(other[0], qc) and torch.equal(other[3], ka)
+
+
+def test_stream_pass_starts_from_given_centroids(oracle):
+    """init_idx == NULL: the totals start at the centroid buffer.  Starting from the rows the initialisation
+    would pick gives the same run (they are binary16 values already)."""
+    w = small("cfg2", N=1024, Hq=1, Hkv=1, Cq=8, Ck=24, block=1024)
+    d = generate(w)
+    p = mb.params_for(w)
+    K = dev(d["K"], p)
+    ki = d["k_init_idx"]
+    a = mb.muse_kmeans_stream(p, 1, K, ki.cuda())
+    c0 = K[0, 0][ki[0, 0].long().cuda()].float().reshape(1, 1, w.Ck, w.D).contiguous()
+    b = mb.muse_kmeans_stream(p, 1, K, None, centroids=c0)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_stream_pass_full_size_one_head(oracle):
+    """The launch configuration the benchmark times (cfg3: N = 65536, 1024 key clusters), one head replayed by
+    the oracle along the library's assignments."""
+    w = dataclasses.replace(CONFIGS["cfg3"], Hq=1, Hkv=1)
+    d = generate(w)
+    p = mb.params_for(w)
+    K = dev(d["K"], p)
+    _check_side(oracle, p, 1, K, 1, w.Ck, d["k_init_idx"], "cfg3 keys")
