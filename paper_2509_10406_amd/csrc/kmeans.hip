@@ -349,49 +349,79 @@ __global__ void __launch_bounds__(256) k_update(const T* __restrict__ X, const i
 // centroids stand when the minibatch starts; then, row by row, the total and the count of the row's centroid
 // decay and absorb it: t <- beta t + x, c <- beta c + 1 (beta = 0.9), centroid = t / c.
 //
-// The pass is sequential over the N / 64 minibatches, so one workgroup (4 waves) owns a head from start to
-// end.  Rows and centroids enter the similarity as binary16 (App. C: the clustering runs in float16) on
-// MFMA 32x32x16 f16 with fp32 accumulation: centroid tiles are the A operand (read from the L2-resident
-// binary16 copy), the 64 rows of the minibatch the B operand (LDS), each wave takes every fourth tile of 32
-// centroids.  The state t, c stays fp32 (one fma per update, one division per centroid); only the centroids
-// that a minibatch touches are rewritten, one wave per distinct centroid, all loads of a wave's centroids
-// issued before the first is used.
+// The pass is sequential over the N / 64 minibatches, so one workgroup (8 waves, two per SIMD) owns a head from
+// start to end; a minibatch is a chain of dependent steps, and what counts is their latency, not throughput.
+// Rows and centroids enter the similarity as binary16 (App. C: the clustering runs in float16) on MFMA 32x32x16
+// f16 with fp32 accumulation that starts at -||c^||^2 / 2: centroid tiles are the A operand, the 64 rows of the
+// minibatch the B operand (LDS), each wave takes every eighth tile of 32 centroids and keeps a running argmax
+// (value, tile, accumulator element) per lane.  The state t, c stays fp32 (one fma per update, one division per
+// centroid); only the centroids that a minibatch touches are rewritten: centroid j belongs to wave j % 8, which
+// finds the distinct ones among its rows by ballots, requests all their totals before it uses any, and reduces
+// their norms with DPP row sums.  While C D is small the whole state sits in LDS (no global round trip inside
+// the pass); otherwise it sits in the workspace, L2-resident, and is re-read through the CU's L1 after the
+// workgroup barrier that ends a minibatch.
 // ------------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(8))) _Float16 kf16x8_t;
+
+// sum over the 64 lanes, in every lane: four DPP steps inside each row of 16 lanes (quad swaps, half-row and row
+// mirrors), then the four row sums through scalar registers.  No LDS traffic, unlike the shuffle-based wave_sum.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+  v = dpp_add<0x141>(v);  // row_half_mirror
+  v = dpp_add<0x140>(v);  // row_mirror
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+  return (r0 + r1) + (r2 + r3);
+}
 constexpr int kStreamMB = 64;
+constexpr int kStreamNW = 8;  // waves of the workgroup that owns a head (two per SIMD)
 constexpr float kStreamBeta = 0.9f;
 // operands of TB tiles of 32 centroids: this lane's row of each tile (its half of every 16 dims) and the
 // -||c^||^2 / 2 of the 16 centroids whose scores land in this lane
-template <int D>
+template <int D, int TB_>
 struct CentBatch {
-  static constexpr int TB = 256 / D;  // registers: two batches are live
+  static constexpr int TB = TB_;
   kf16x8_t ca[TB][D / 16];
-  float4 nv[TB][4];
+  f32x16_t nv[TB];
 };
 
-template <typename T, int D>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+// TBN: tiles per batch (two batches are live: registers).  LS: the whole state (totals, counts, binary16
+// centroids, their norms) lives in dynamic LDS instead of the L2-resident workspace arrays: no global round
+// trips inside the pass; possible while C D is small enough (the host decides).
+template <typename T, int D, int TBN, bool LS>
+__global__ void __launch_bounds__(64 * kStreamNW) __attribute__((amdgpu_waves_per_eu(kStreamNW / 4, kStreamNW / 4)))
 k_stream_kmeans(const T* __restrict__ X, const int32_t* __restrict__ init_idx, float* __restrict__ cent,
                 float* __restrict__ tst, float* __restrict__ cst, _Float16* __restrict__ chat,
                 float* __restrict__ nhc2, int32_t* __restrict__ trace, float* __restrict__ counts_out, int N, int C) {
   // cst and nhc2 are [heads][CS], CS = C rounded up to a whole tile of 32 (16-byte reads of a tile's 32 values)
   constexpr int KS = D / 16, DL = D / 64;         // k-steps of the similarity; dims per lane in the update
-  constexpr int CPR = D / 8, NCH = 64 * CPR / 256;  // 16-byte (bf16) / 32-byte (fp32) chunks of a minibatch per thread
+  constexpr int NW = kStreamNW, NT = 64 * NW;
+  constexpr int CPR = D / 8, NCH = 64 * CPR / NT;  // 16-byte (bf16) / 32-byte (fp32) chunks of a minibatch per thread
   __shared__ __attribute__((aligned(16))) _Float16 xs[kStreamMB][D + 8];
-  __shared__ float bval[4][kStreamMB];
-  __shared__ int bidx[4][kStreamMB];
+  __shared__ float bval[kStreamNW][kStreamMB];
+  __shared__ int bidx[kStreamNW][kStreamMB];
   const int h = blockIdx.x;
-  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, col = lane % 32, half = lane / 32;
+  const int tid = threadIdx.x, lane = tid % 64, col = lane % 32, half = lane / 32;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);  // in a scalar register: loops and branches on it are uniform
   const T* Xh = X + (size_t)h * N * D;
-  float* th = tst + (size_t)h * C * D;
   const int CS = (C + 31) / 32 * 32;
-  float* ch_ = cst + (size_t)h * CS;
-  _Float16* hh = chat + (size_t)h * C * D;
-  float* nh = nhc2 + (size_t)h * CS;
+  extern __shared__ __attribute__((aligned(16))) unsigned char stream_lds[];
+  constexpr int HS = LS ? D + 8 : D;  // row stride of the binary16 centroids (padded in LDS: conflict-free 16-byte reads)
+  float* th = LS ? reinterpret_cast<float*>(stream_lds) : tst + (size_t)h * C * D;
+  _Float16* hh = LS ? reinterpret_cast<_Float16*>(stream_lds + (size_t)C * D * 4) : chat + (size_t)h * C * D;
+  float* ch_ = LS ? reinterpret_cast<float*>(stream_lds + (size_t)C * D * 4 + (size_t)C * HS * 2) : cst + (size_t)h * CS;
+  float* nh = LS ? ch_ + CS : nhc2 + (size_t)h * CS;
   float* ce = cent + (size_t)h * C * D;
 
   // ---- initial state: t = the initial centroid (as binary16 values), c = 1 ----
-  for (int j = wave; j < C; j += 4) {
+  for (int j = wave; j < C; j += NW) {
     float s = 0.f;
 #pragma unroll
     for (int x = 0; x < DL; ++x) {
@@ -400,7 +430,7 @@ k_stream_kmeans(const T* __restrict__ X, const int32_t* __restrict__ init_idx, f
       const _Float16 vh = (_Float16)v;
       if (init_idx) v = (float)vh;
       th[(size_t)j * D + d] = v;
-      hh[(size_t)j * D + d] = vh;
+      hh[(size_t)j * HS + d] = vh;
       s += (float)vh * (float)vh;
     }
     s = wave_sum(s);
@@ -409,10 +439,12 @@ k_stream_kmeans(const T* __restrict__ X, const int32_t* __restrict__ init_idx, f
       nh[j] = -0.5f * s;
     }
   }
+  // the last tile's entries past C: never the nearest (their rows repeat the centroid C - 1)
+  for (int j = C + tid; j < CS; j += NT) nh[j] = MUSE_NEG_INF;
 
   // raw rows of a minibatch, this thread's chunks (row = c % 64, 8 dims from 8 (c / 64)); rows past N repeat N - 1
   auto row_ptr = [&](int v0, int it) {
-    const int c = tid + 256 * it;
+    const int c = tid + NT * it;
     int gr = v0 + c % 64;
     gr = gr < N ? gr : N - 1;
     return Xh + (size_t)gr * D + (c / 64) * 8;
@@ -431,7 +463,7 @@ k_stream_kmeans(const T* __restrict__ X, const int32_t* __restrict__ init_idx, f
     // ---- the minibatch as binary16 in LDS ----
 #pragma unroll
     for (int it = 0; it < NCH; ++it) {
-      const int c = tid + 256 * it, row = c % 64, cc = c / 64;
+      const int c = tid + NT * it, row = c % 64, cc = c / 64;
       kf16x8_t o;
       if constexpr (sizeof(T) == 2) {
         const uint32_t w[4] = {ra[it].x, ra[it].y, ra[it].z, ra[it].w};
@@ -463,58 +495,68 @@ k_stream_kmeans(const T* __restrict__ X, const int32_t* __restrict__ init_idx, f
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) xb[hf][ks] = *reinterpret_cast<const kf16x8_t*>(&xs[32 * hf + col][16 * ks + 8 * half]);
+    // running argmax per lane and half-minibatch: value, tile and the accumulator element (row of the tile)
     float best[2] = {MUSE_NEG_INF, MUSE_NEG_INF};
-    int bj[2] = {0x7fffffff, 0x7fffffff};
-    // this wave's tiles jt = wave + 4 k in batches of TB: the operands of a whole batch are requested before the
+    int bt[2] = {0x3fffff, 0x3fffff}, be[2] = {0, 0};
+    // this wave's tiles jt = wave + NW k in batches of TB: the operands of a whole batch are requested before the
     // first is used, and the next batch is in flight while this one is scored (loads are unconditional: tiles
     // past the end re-read the last one and are skipped when scoring)
-    auto load_cb = [&](CentBatch<D>& cb, int k0) {
+    auto load_cb = [&](CentBatch<D, TBN>& cb, int k0) {
 #pragma unroll
-      for (int tb = 0; tb < CentBatch<D>::TB; ++tb) {
-        int jt = wave + 4 * (k0 + tb);
+      for (int tb = 0; tb < CentBatch<D, TBN>::TB; ++tb) {
+        int jt = wave + NW * (k0 + tb);
         jt = jt < ntile ? jt : ntile - 1;
         const int j0 = jt * 32;
         const int jr = j0 + col < C ? j0 + col : C - 1;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          cb.ca[tb][ks] = *reinterpret_cast<const kf16x8_t*>(hh + (size_t)jr * D + 16 * ks + 8 * half);
+          cb.ca[tb][ks] = *reinterpret_cast<const kf16x8_t*>(hh + (size_t)jr * HS + 16 * ks + 8 * half);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) cb.nv[tb][g] = *reinterpret_cast<const float4*>(nh + j0 + 8 * g + 4 * half);
+        for (int g = 0; g < 4; ++g) {
+          const float4 n4 = *reinterpret_cast<const float4*>(nh + j0 + 8 * g + 4 * half);
+          cb.nv[tb][4 * g] = n4.x; cb.nv[tb][4 * g + 1] = n4.y; cb.nv[tb][4 * g + 2] = n4.z; cb.nv[tb][4 * g + 3] = n4.w;
+        }
       }
     };
-    auto score_cb = [&](const CentBatch<D>& cb, int k0) {
+    // Tiles past the end were loaded as copies of the last tile: scoring a tile twice changes nothing (only a
+    // strictly larger score replaces the best), so a batch is scored without branches and its independent
+    // MFMA chains (TB tiles x 2 halves) can be interleaved with the comparisons.
+    auto score_cb = [&](const CentBatch<D, TBN>& cb, int k0) {
+      constexpr int TB = CentBatch<D, TBN>::TB;
+      f32x16_t acc[TB][2];
 #pragma unroll
-      for (int tb = 0; tb < CentBatch<D>::TB; ++tb) {
-        const int jt = wave + 4 * (k0 + tb);
-        if (jt < ntile) {
-          const int j0 = jt * 32;
+      for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-          for (int hf = 0; hf < 2; ++hf) {
-            f32x16_t acc;
+        for (int hf = 0; hf < 2; ++hf)  // the accumulator starts at -||c^||^2 / 2 of its row's centroid
+          acc[tb][hf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(cb.ca[tb][0], xb[hf][0], cb.nv[tb], 0, 0, 0);
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+      for (int ks = 1; ks < KS; ++ks)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-              acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(cb.ca[tb][ks], xb[hf][ks], acc, 0, 0, 0);
+        for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              const int j = j0 + 8 * (e / 4) + 4 * half + (e % 4);
-              const float4 n4 = cb.nv[tb][e / 4];
-              const float nv = (e % 4) == 0 ? n4.x : (e % 4) == 1 ? n4.y : (e % 4) == 2 ? n4.z : n4.w;
-              const float sc = j < C ? acc[e] + nv : MUSE_NEG_INF;
-              if (sc > best[hf]) {
-                best[hf] = sc;
-                bj[hf] = j;
-              }
-            }
+          for (int hf = 0; hf < 2; ++hf)
+            acc[tb][hf] = __builtin_amdgcn_mfma_f32_32x32x16_f16(cb.ca[tb][ks], xb[hf][ks], acc[tb][hf], 0, 0, 0);
+#pragma unroll
+      for (int tb = 0; tb < TB; ++tb) {
+        int jt = wave + NW * (k0 + tb);
+        jt = jt < ntile ? jt : ntile - 1;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          const float before = best[hf];
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {  // rows in increasing centroid order: the first of equal scores stays
+            const bool up = acc[tb][hf][e] > best[hf];
+            be[hf] = up ? e : be[hf];
+            best[hf] = up ? acc[tb][hf][e] : best[hf];
           }
+          bt[hf] = best[hf] > before ? jt : bt[hf];
         }
       }
     };
     {
-      const int nk = (ntile - wave + 3) / 4;  // tiles of this wave
-      constexpr int TB = CentBatch<D>::TB;
-      CentBatch<D> ba, bb;
+      const int nk = (ntile - wave + NW - 1) / NW;  // tiles of this wave
+      constexpr int TB = CentBatch<D, TBN>::TB;
+      CentBatch<D, TBN> ba, bb;
       load_cb(ba, 0);
       for (int k0 = 0; k0 < nk; k0 += 2 * TB) {
         load_cb(bb, k0 + TB);
@@ -523,6 +565,9 @@ k_stream_kmeans(const T* __restrict__ X, const int32_t* __restrict__ init_idx, f
         if (k0 + TB < nk) score_cb(bb, k0 + TB);
       }
     }
+    int bj[2];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) bj[hf] = 32 * bt[hf] + 8 * (be[hf] / 4) + 4 * half + (be[hf] % 4);
     // the two halves of a row's centroids, then the four waves; ties go to the lowest index
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) {
@@ -544,7 +589,7 @@ k_stream_kmeans(const T* __restrict__ X, const int32_t* __restrict__ init_idx, f
       float bv = bval[0][lane];
       a = bidx[0][lane];
 #pragma unroll
-      for (int w = 1; w < 4; ++w) {
+      for (int w = 1; w < NW; ++w) {
         const float ov = bval[w][lane];
         const int oj = bidx[w][lane];
         if (ov > bv || (ov == bv && oj < a)) {
@@ -556,76 +601,86 @@ k_stream_kmeans(const T* __restrict__ X, const int32_t* __restrict__ init_idx, f
     const bool live = v0 + lane < N;
     if (wave == 0 && live && trace) trace[(size_t)h * N + v0 + lane] = a;
     if (!live) a = -1 - lane;  // a class of its own that nobody updates
-    // ---- classes of equal assignment: mask of the rows that share this row's centroid ----
-    unsigned long long cls = 0;
-    for (int u = 0; u < 64; ++u) {
-      const int au = __builtin_amdgcn_readlane(a, u);
-      const unsigned long long m = __ballot(a == au);
-      if (lane == u) cls = m;
-    }
-    const bool leader = live && (__ffsll((long long)cls) - 1 == lane);
-    const unsigned long long lead = __ballot(leader);
-    // ---- updates: the k-th leader's centroid belongs to wave k % 4; a lane owns the dims lane + 64 x ----
-    constexpr int MAXL = 16;  // at most 64 distinct centroids per minibatch, 16 per wave
-    int lj[MAXL];
-    unsigned long long lm[MAXL];
-    float tv[MAXL][DL], cv[MAXL];
-    int nl = 0;
-    {
-      unsigned long long rest = lead;  // wave-uniform
-      for (int w = 0; w < wave; ++w) rest &= rest - 1;
+    // ---- updates.  A centroid j belongs to wave j % NW; the wave walks the distinct centroids among its rows
+    //      (first row of each, then a ballot for the rows that share it) in rounds of up to MAXL: all loads of
+    //      a round are issued before any is used, and the reductions of a round run in lockstep.  A lane owns
+    //      the dims lane + 64 x. ----
+    constexpr int MAXL = 8;
+    unsigned long long rem = __ballot(live && (a & (NW - 1)) == wave);  // wave-uniform
+    while (rem) {
+      int lj[MAXL];
+      unsigned long long lm[MAXL];
+      float tv[MAXL][DL], cv[MAXL], x0[MAXL][DL];
+      int nl = 0;
 #pragma unroll
       for (int q = 0; q < MAXL; ++q) {
-        if (rest) {
-          const int u = __ffsll((long long)rest) - 1;
+        if (rem) {
+          const int u = __ffsll((long long)rem) - 1;
           const int j = __builtin_amdgcn_readlane(a, u);
-          const unsigned lo = __builtin_amdgcn_readlane((unsigned)cls, u), hi = __builtin_amdgcn_readlane((unsigned)(cls >> 32), u);
+          const unsigned long long m = __ballot(a == j);
           lj[q] = j;
-          lm[q] = ((unsigned long long)hi << 32) | lo;
+          lm[q] = m & (m - 1);  // rows after the first
 #pragma unroll
-          for (int x = 0; x < DL; ++x) tv[q][x] = th[(size_t)j * D + lane + 64 * x];
+          for (int x = 0; x < DL; ++x) {
+            tv[q][x] = th[(size_t)j * D + lane + 64 * x];
+            x0[q][x] = (float)xs[u][lane + 64 * x];
+          }
           cv[q] = ch_[j];
           nl = q + 1;
-#pragma unroll
-          for (int w = 0; w < 4; ++w) rest &= rest - 1;
+          rem &= ~m;
         }
       }
-    }
+      float sq[MAXL];
 #pragma unroll
-    for (int q = 0; q < MAXL; ++q) {
-      if (q < nl) {
-        const int j = lj[q];
-        unsigned long long m = lm[q];
-        float c = cv[q];
-        float t[DL];
+      for (int q = 0; q < MAXL; ++q) {
+        sq[q] = 0.f;
+        if (q < nl) {
+          const int j = lj[q];
+          unsigned long long m = lm[q];
+          float c = fmaf(kStreamBeta, cv[q], 1.f);
+          float t[DL];
 #pragma unroll
-        for (int x = 0; x < DL; ++x) t[x] = tv[q][x];
-        while (m) {  // rows of the class in order
-          const int u = __ffsll((long long)m) - 1;
-          m &= m - 1;
+          for (int x = 0; x < DL; ++x) t[x] = fmaf(kStreamBeta, tv[q][x], x0[q][x]);
+          while (m) {  // further rows of the class, in order
+            const int u = __ffsll((long long)m) - 1;
+            m &= m - 1;
 #pragma unroll
-          for (int x = 0; x < DL; ++x) t[x] = fmaf(kStreamBeta, t[x], (float)xs[u][lane + 64 * x]);
-          c = fmaf(kStreamBeta, c, 1.f);
+            for (int x = 0; x < DL; ++x) t[x] = fmaf(kStreamBeta, t[x], (float)xs[u][lane + 64 * x]);
+            c = fmaf(kStreamBeta, c, 1.f);
+          }
+          cv[q] = c;
+#pragma unroll
+          for (int x = 0; x < DL; ++x) {
+            th[(size_t)j * D + lane + 64 * x] = t[x];
+            const _Float16 vh = (_Float16)(t[x] / c);
+            hh[(size_t)j * HS + lane + 64 * x] = vh;
+            sq[q] += (float)vh * (float)vh;
+          }
         }
-        float s = 0.f;
+      }
+      // ||c^||^2 of the round's centroids: sums inside the rows of 16 lanes by DPP, then the four rows
 #pragma unroll
-        for (int x = 0; x < DL; ++x) {
-          th[(size_t)j * D + lane + 64 * x] = t[x];
-          const _Float16 vh = (_Float16)(t[x] / c);
-          hh[(size_t)j * D + lane + 64 * x] = vh;
-          s += (float)vh * (float)vh;
-        }
-        s = wave_sum(s);
-        if (lane == 0) {
-          ch_[j] = c;
-          nh[j] = -0.5f * s;
+      for (int q = 0; q < MAXL; ++q) sq[q] = wave_sum_dpp(sq[q]);
+      {  // lane q writes the scalars of the round's q-th centroid
+        int jq = 0;
+        float cq = 0.f, sv = 0.f;
+#pragma unroll
+        for (int q = 0; q < MAXL; ++q)
+          if (q < nl && lane == q) {
+            jq = lj[q];
+            cq = cv[q];
+            sv = sq[q];
+          }
+        if (lane < nl) {
+          ch_[jq] = cq;
+          nh[jq] = -0.5f * sv;
         }
       }
     }
   }
   __syncthreads();
   // ---- centroids of the raw rows: t / c ----
-  for (int j = wave; j < C; j += 4) {
+  for (int j = wave; j < C; j += NW) {
     const float c = ch_[j];
 #pragma unroll
     for (int x = 0; x < DL; ++x) ce[(size_t)j * D + lane + 64 * x] = th[(size_t)j * D + lane + 64 * x] / c;
@@ -651,8 +706,35 @@ int cluster_impl(const MuseDims& d, const T* X, int H, int C, const int32_t* ini
     float* cst = (float*)w;        w += align256((size_t)heads * CS * sizeof(float));
     _Float16* shat = (_Float16*)w; w += align256((size_t)heads * C * D * sizeof(_Float16));
     float* snh = (float*)w;
-    if (D == 64) { MuseProf prof_("k_stream_kmeans", st); hipLaunchKernelGGL((k_stream_kmeans<T, 64>), dim3(heads), dim3(256), 0, st, X, init_idx, cent, tst, cst, shat, snh, trace, counts, N, C); }
-    else { MuseProf prof_("k_stream_kmeans", st); hipLaunchKernelGGL((k_stream_kmeans<T, 128>), dim3(heads), dim3(256), 0, st, X, init_idx, cent, tst, cst, shat, snh, trace, counts, N, C); }
+    const int per_wave = ((C + 31) / 32 + kStreamNW - 1) / kStreamNW;  // centroid tiles of a wave
+    const int tbn = per_wave >= 4 && D == 64 ? 2 : 1;
+    // state in LDS when it fits beside the kernel's static arrays (totals fp32, centroids binary16 with padded rows,
+    // counts and norms)
+    const size_t lds_state = (size_t)C * D * 4 + (size_t)C * (D + 8) * 2 + 2 * CS * 4;
+    const bool ls = lds_state <= 128 * 1024;
+#define MUSE_STREAM_LAUNCH(DD, TT)                                                                                  \
+  {                                                                                                                 \
+    MuseProf prof_("k_stream_kmeans", st);                                                                          \
+    if (ls) {                                                                                                       \
+      static bool attr_ = false;                                                                                    \
+      if (!attr_) {                                                                                                 \
+        MUSE_HIP_CHECK(hipFuncSetAttribute((const void*)k_stream_kmeans<T, DD, 1, true>,                            \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));                \
+        attr_ = true;                                                                                               \
+      }                                                                                                             \
+      hipLaunchKernelGGL((k_stream_kmeans<T, DD, 1, true>), dim3(heads), dim3(64 * kStreamNW), lds_state, st, X,    \
+                         init_idx, cent, tst, cst, shat, snh, trace, counts, N, C);                                 \
+    } else {                                                                                                        \
+      hipLaunchKernelGGL((k_stream_kmeans<T, DD, TT, false>), dim3(heads), dim3(64 * kStreamNW), 0, st, X, init_idx, \
+                         cent, tst, cst, shat, snh, trace, counts, N, C);                                           \
+    }                                                                                                               \
+  }
+    if (D == 64) {
+      if (tbn == 2) MUSE_STREAM_LAUNCH(64, 2) else MUSE_STREAM_LAUNCH(64, 1)
+    } else {
+      MUSE_STREAM_LAUNCH(128, 1)
+    }
+#undef MUSE_STREAM_LAUNCH
     MUSE_LAUNCH_CHECK();
     if (!assign) return MUSE_OK;
   }
