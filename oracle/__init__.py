@@ -8,6 +8,7 @@ shares no code with it and never calls it.
 """
 from .api import (  # noqa: F401
     MuseParams,
+    balanced_assign,
     build,
     exact_bwd,
     exact_fwd,

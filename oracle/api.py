@@ -168,6 +168,22 @@ def kmeans_stream(X, Cn, init_idx, mb=64, beta=0.9, forced=None):
     return dict(cent=cent, t=t, c=c, assign=assign, margin=margin, regret=regret)
 
 
+def balanced_assign(X, cent, Bs, cap, round_mode=0, forced=None, tol=1e-5):
+    """Final assignment under the per-block cap of App. C "Balanced Assignment" (two phases in position order).
+    forced: replay along this assignment and check it.  Returns dict(assign, regret, broken)."""
+    X, Xp = _d(X); cent, cp = _d(cent)
+    N, D = X.shape
+    Cn = cent.shape[0]
+    assert Cn * cap >= min(Bs, N), "the cap leaves no room for every row of a block"
+    assign = np.zeros(N, dtype=np.int32); rep = np.zeros(2)
+    fp = None
+    if forced is not None:
+        ff, fp = _i(forced)
+    _L().oracle_balanced_assign(C.c_int(N), C.c_int(D), C.c_int(Cn), C.c_int(Bs), C.c_int(cap), C.c_int(round_mode),
+                                Xp, cp, fp, C.c_double(tol), _i(assign)[1], _d(rep)[1])
+    return dict(assign=assign, regret=float(rep[0]), broken=int(rep[1]))
+
+
 def summaries(p: MuseParams, K, V, qc, ak, i):
     """Per-block and accumulated summaries of query cluster i, each [Ck, nb(, D)]."""
     K, Kp = _d(K); V, Vp = _d(V); qc, qp = _d(qc); ak, ap = _i(ak)

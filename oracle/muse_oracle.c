@@ -234,6 +234,105 @@ void oracle_kmeans(int N, int D, int C, int T, int round_mode, const double* X,
 }
 
 /* ------------------------------------------------------------------ */
+/* Balanced assignment: App. C "Balanced Assignment".                    */
+/*                                                                     */
+/* Inside every spatial block a cluster holds at most `cap` rows (the  */
+/* paper: 4 B / K).  The paper does not say which rows give way; the   */
+/* reading here has two phases, both in position order:                */
+/*   A. every row names its nearest centroid (same score and ties as   */
+/*      assign_points); of the rows of a block that name centroid j    */
+/*      the first `cap` keep it;                                        */
+/*   B. the others, one after the other in position order, go to the   */
+/*      nearest centroid that still has room in the block at that      */
+/*      moment (rows kept in phase A and rows placed earlier in phase  */
+/*      B count), lowest index on ties.                                 */
+/* With forced != NULL the pass is replayed along the given assignment */
+/* and checked instead: a row whose forced cluster scores within `tol` */
+/* (relative) of its nearest one names that cluster in phase A; any    */
+/* other row names its nearest one and must be displaced; a displaced  */
+/* row's forced cluster must have room when its turn comes and score   */
+/* within `tol` of the best cluster with room.  report[0] = largest    */
+/* relative regret of a phase B choice, report[1] = number of rows     */
+/* that break a rule (kept beyond the cap, placed without room, placed */
+/* although their nearest cluster had room for them).                   */
+/* ------------------------------------------------------------------ */
+void oracle_balanced_assign(int N, int D, int C, int Bs, int cap, int round_mode, const double* X,
+                            const double* cent, const int32_t* forced, double tol, int32_t* assign,
+                            double* report) {
+  double* ch = (double*)malloc(sizeof(double) * (size_t)C * D);
+  double* c2 = (double*)malloc(sizeof(double) * (size_t)C);
+  double* sc = (double*)malloc(sizeof(double) * (size_t)C);
+  int32_t* named = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+  char* moved = (char*)malloc((size_t)N);
+  int32_t* count = (int32_t*)malloc(sizeof(int32_t) * (size_t)C);
+  double worst = 0.0, broken = 0.0;
+  for (int j = 0; j < C; ++j) {
+    for (int d = 0; d < D; ++d) {
+      double c = cent[(size_t)j * D + d];
+      ch[(size_t)j * D + d] = round_mode == 1 ? round_bf16(c) : round_f32(c);
+    }
+    c2[j] = dot(ch + (size_t)j * D, ch + (size_t)j * D, D);
+  }
+  for (int b0 = 0; b0 < N; b0 += Bs) {
+    int b1 = b0 + Bs < N ? b0 + Bs : N;
+    /* phase A */
+    for (int j = 0; j < C; ++j) count[j] = 0;
+    for (int n = b0; n < b1; ++n) {
+      double best = INFINITY;
+      int bj = 0;
+      for (int j = 0; j < C; ++j) {
+        sc[j] = c2[j] - 2.0 * dot(X + (size_t)n * D, ch + (size_t)j * D, D);
+        if (sc[j] < best) {
+          best = sc[j];
+          bj = j;
+        }
+      }
+      int name = bj;
+      if (forced) {
+        double sf = sc[forced[n]];
+        if ((sf - best) / fmax(1.0, fmax(fabs(best), fabs(sf))) <= tol) name = forced[n];
+      }
+      named[n] = name;
+      moved[n] = count[name] >= cap;
+      if (!moved[n]) count[name]++;
+      if (forced && !moved[n] && forced[n] != name) broken += 1.0; /* had room in its nearest cluster */
+      if (forced && moved[n] && forced[n] == name) broken += 1.0;  /* kept beyond the cap */
+      if (!moved[n]) assign[n] = name;
+    }
+    /* phase B */
+    for (int n = b0; n < b1; ++n) {
+      if (!moved[n]) continue;
+      double best = INFINITY;
+      int bj = -1;
+      for (int j = 0; j < C; ++j) {
+        sc[j] = c2[j] - 2.0 * dot(X + (size_t)n * D, ch + (size_t)j * D, D);
+        if (count[j] < cap && sc[j] < best) {
+          best = sc[j];
+          bj = j;
+        }
+      }
+      int take = bj;
+      if (forced) {
+        take = forced[n];
+        if (count[take] >= cap) {
+          broken += 1.0;
+        } else {
+          double reg = (sc[take] - best) / fmax(1.0, fmax(fabs(best), fabs(sc[take])));
+          if (reg > worst) worst = reg;
+        }
+      }
+      assign[n] = take;
+      if (take >= 0) count[take]++;
+    }
+  }
+  if (report) {
+    report[0] = worst;
+    report[1] = broken;
+  }
+  free(ch); free(c2); free(sc); free(named); free(moved); free(count);
+}
+
+/* ------------------------------------------------------------------ */
 /* Streaming centroid pass: App. C "Centroid Computation", step 2.      */
 /*                                                                     */
 /* One pass over the rows in sequence order, in minibatches of `mb`    */

@@ -594,6 +594,85 @@ def test_stream_forced_assignments(oracle):
 
 
 # ---------------------------------------------------------------------------
+# balanced assignment (App. C "Balanced Assignment": at most cap rows per cluster and spatial block)
+# ---------------------------------------------------------------------------
+def test_balanced_assign_hand_worked(oracle):
+    """Centroids 0, 1 and 5 on a line, one block, cap 2.  Rows 0.1 0.2 0.3 0.4 0.9 name 0 0 0 0 1: the first two
+    keep centroid 0; 0.3 and 0.4 are displaced in that order: 0.3 takes the last place of centroid 1
+    (0.9 holds the other), 0.4 finds 0 and 1 full and goes to centroid 5."""
+    X = np.zeros((5, 1)); X[:, 0] = [0.1, 0.2, 0.3, 0.4, 0.9]
+    cent = np.array([[0.0], [1.0], [5.0]])
+    got = oracle.balanced_assign(X, cent, Bs=5, cap=2)
+    np.testing.assert_array_equal(got["assign"], [0, 0, 1, 2, 1])
+    # a later row of the block keeps its place in phase A even though an earlier row is displaced towards it
+    X2 = np.zeros((4, 1)); X2[:, 0] = [0.1, 0.2, 0.3, 0.9]
+    np.testing.assert_array_equal(oracle.balanced_assign(X2, cent[:2], Bs=4, cap=2)["assign"], [0, 0, 1, 1])
+    # phase A comes first for every row of the block: with cap 1, rows 0.1 0.2 0.9 keep 0, -, 1 and the displaced
+    # 0.2 finds both full (a single pass in position order would have given it centroid 1 and displaced 0.9)
+    X3 = np.zeros((3, 1)); X3[:, 0] = [0.1, 0.2, 0.9]
+    np.testing.assert_array_equal(oracle.balanced_assign(X3, cent, Bs=3, cap=1)["assign"], [0, 2, 1])
+    # blocks are independent: the same rows split into blocks of two never meet the cap
+    np.testing.assert_array_equal(oracle.balanced_assign(X, cent, Bs=2, cap=2)["assign"], [0, 0, 0, 0, 1])
+
+
+def test_balanced_assign_without_pressure_is_nearest_centroid(oracle):
+    rng = np.random.default_rng(21)
+    X = rng.normal(size=(600, 8)); cent = np.float32(rng.normal(size=(9, 8))).astype(np.float64)
+    plain = oracle.kmeans(X, 9, 0, cent0=cent)["assign"]
+    np.testing.assert_array_equal(oracle.balanced_assign(X, cent, Bs=200, cap=200)["assign"], plain)
+    np.testing.assert_array_equal(oracle.balanced_assign(oracle.round_bf16(X), cent, Bs=200, cap=200, round_mode=1)["assign"],
+                                  oracle.kmeans(oracle.round_bf16(X), 9, 0, cent0=cent, round_mode=1)["assign"])
+
+
+def test_balanced_assign_invariants(oracle):
+    """Under pressure: no (block, cluster) exceeds the cap; a row sits in a cluster other than its nearest only
+    if every cluster that scores better for it is full in its block (places are never given back, so a cluster
+    with room at the end had room when the row was placed); rows that keep their nearest cluster are, per block
+    and cluster, exactly the first cap of those that named it."""
+    rng = np.random.default_rng(22)
+    N, D, Cn, Bs = 960, 6, 7, 240
+    X = rng.normal(size=(N, D)) + np.array([2.0, 0, 0, 0, 0, 0])   # lopsided: a few centroids attract most rows
+    cent = np.float32(rng.normal(size=(Cn, D))).astype(np.float64)
+    cap = 4 * Bs // Cn // 3   # tighter than the paper's factor so that it binds
+    got = oracle.balanced_assign(X, cent, Bs=Bs, cap=cap)["assign"]
+    score = (cent ** 2).sum(1)[None, :] - 2 * X @ cent.T
+    near = score.argmin(1)
+    assert (got != near).sum() > 50
+    for b in range(N // Bs):
+        rows = np.arange(b * Bs, (b + 1) * Bs)
+        size = np.bincount(got[rows], minlength=Cn)
+        assert size.max() <= cap
+        for n in rows:
+            better = np.flatnonzero(score[n] < score[n, got[n]])
+            assert (size[better] == cap).all()
+        for j in range(Cn):
+            named = rows[near[rows] == j]
+            np.testing.assert_array_equal(got[named[:cap]], j)
+            assert (got[named[cap:]] != j).all()
+
+
+def test_balanced_assign_replay_checks_a_given_assignment(oracle):
+    rng = np.random.default_rng(23)
+    X = rng.normal(size=(400, 5)) + 1.0; cent = np.float32(rng.normal(size=(6, 5))).astype(np.float64)
+    free = oracle.balanced_assign(X, cent, Bs=200, cap=50)
+    same = oracle.balanced_assign(X, cent, Bs=200, cap=50, forced=free["assign"])
+    np.testing.assert_array_equal(same["assign"], free["assign"])
+    assert same["broken"] == 0 and same["regret"] == 0.0
+    score = (cent ** 2).sum(1)[None, :] - 2 * X @ cent.T
+    moved = np.flatnonzero(free["assign"] != score.argmin(1))
+    assert moved.size > 10
+    bad = free["assign"].copy()
+    n = moved[-1]                       # send a displaced row to the worst cluster instead
+    bad[n] = score[n].argmax()
+    rep = oracle.balanced_assign(X, cent, Bs=200, cap=50, forced=bad)
+    assert rep["broken"] > 0 or rep["regret"] > 1e-3
+    bad = free["assign"].copy()
+    kept = np.flatnonzero(free["assign"] == score.argmin(1))
+    bad[kept[0]] = (bad[kept[0]] + 1) % 6   # move a row that had room in its nearest cluster
+    assert oracle.balanced_assign(X, cent, Bs=200, cap=50, forced=bad)["broken"] > 0
+
+
+# ---------------------------------------------------------------------------
 # trends the paper reports (Table 2, App. E): error falls with more clusters and with larger r
 # ---------------------------------------------------------------------------
 def test_error_falls_with_clusters_and_retrieval(oracle):
