@@ -92,6 +92,9 @@ def main():
     ap.add_argument("--streaming-kmeans", action="store_true",
                     help="centroids from the single streaming pass of App. C (MUSE_FLAG_STREAMING_KMEANS) instead of "
                          "Lloyd iterations; a variant, named in config.step")
+    ap.add_argument("--balanced-assign", action="store_true",
+                    help="final assignment under the per-block cap 4 block / C of App. C (MUSE_FLAG_BALANCED_ASSIGN); "
+                         "a variant, named in config.step")
     ap.add_argument("--serial-streams", action="store_true",
                     help="run every stage on one stream (as the per-kernel timing pass does): for kernel profiles")
     ap.add_argument("--ws-gib", type=float, default=0.0, help="cap of the backward workspace (0 = all heads at once)")
@@ -115,7 +118,8 @@ def main():
     w = CONFIGS[a.workload]
     d = generate(w, need_dO=True)
     p = mb.params_for(w, flags=mb.FLAG_KEEP_FWD_STATE | (mb.FLAG_FROZEN_WEIGHTS if a.frozen_weights else 0) |
-                      (mb.FLAG_STREAMING_KMEANS if a.streaming_kmeans else 0))   # backward reuses the forward's summaries
+                      (mb.FLAG_STREAMING_KMEANS if a.streaming_kmeans else 0) |
+                      (mb.FLAG_BALANCED_ASSIGN if a.balanced_assign else 0))   # backward reuses the forward's summaries
     Q, K, V, dO = (d[x].to(p.torch_dtype).cuda().contiguous() for x in ("Q", "K", "V", "dO"))
     qi, ki = d["q_init_idx"].cuda(), d["k_init_idx"].cuda()
     lim = int(a.ws_gib * 2 ** 30) if a.ws_gib > 0 else None
@@ -209,7 +213,8 @@ def main():
                                f"k2={w.k2} block={w.Bs} kmeans_iters={w.kmeans_iters}" +
                                (" (BASELINE.json configs[2])" if w.name == "cfg3" else ""),
                    "step": "muse_cluster + muse_fwd + muse_bwd" + (" (frozen aggregation weights)" if a.frozen_weights else "") +
-                           (" (streaming K-means)" if a.streaming_kmeans else "")},
+                           (" (streaming K-means)" if a.streaming_kmeans else "") +
+                           (" (balanced assignment)" if a.balanced_assign else "")},
         "ms": {"cluster": ms_cluster, "fwd": ms_fwd, "bwd": ms_bwd, "exact_attn_fwd_bwd": ms_exact},
         "effective_attention_tflops": eff_flops / (ms_step * 1e-3) / 1e12,
         "frac_of_bf16_mfma_peak_effective": eff_flops / (ms_step * 1e-3) / PEAK["mfma_bf16"],

@@ -59,7 +59,13 @@ enum { MUSE_FLAG_KEEP_FWD_STATE = 1,
 /* MUSE_FLAG_STREAMING_KMEANS (muse_cluster only; App. C "Centroid Computation"): the centroids come from the
  * single streaming pass described at muse_kmeans_stream instead of Lloyd iterations (kmeans_iters is ignored);
  * the final nearest-centroid assignment is the same. */
-       MUSE_FLAG_STREAMING_KMEANS = 4 };
+       MUSE_FLAG_STREAMING_KMEANS = 4,
+/* MUSE_FLAG_BALANCED_ASSIGN (muse_cluster only; App. C "Balanced Assignment"): in the final assignment a cluster
+ * holds at most cap = floor(4 block / C) rows of a spatial block.  Of the rows of a block that name centroid j
+ * as their nearest, the first cap in sequence order keep it; the others, one after the other in sequence order,
+ * go to the nearest centroid that still has room in the block at that moment (lowest index on ties).
+ * MUSE_ERR_UNSUPPORTED if cap < 1 or cap * C < block. */
+       MUSE_FLAG_BALANCED_ASSIGN = 8 };
 enum { MUSE_WS_CLUSTER = 0, MUSE_WS_FWD = 1, MUSE_WS_BWD = 2, MUSE_WS_EXACT_FWD = 3, MUSE_WS_EXACT_BWD = 4 };
 
 typedef struct {

@@ -137,6 +137,7 @@ struct MuseDims {
   bool keep_state;  // MUSE_FLAG_KEEP_FWD_STATE
   bool frozen_weights;  // MUSE_FLAG_FROZEN_WEIGHTS
   bool streaming;       // MUSE_FLAG_STREAMING_KMEANS
+  bool balanced;        // MUSE_FLAG_BALANCED_ASSIGN
 };
 
 #define MUSE_HIP_CHECK(expr)                      \

@@ -688,6 +688,133 @@ k_stream_kmeans(const T* __restrict__ X, const int32_t* __restrict__ init_idx, f
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Balanced assignment (App. C "Balanced Assignment"): inside a spatial block a cluster holds at most `cap` rows.
+// Phase A is the nearest-centroid assignment already in `assign`, bucketed by (block, cluster) in position
+// order: the first cap rows of a segment keep their cluster.  Phase B, here: the other rows of the block, one
+// after the other in position order, go to the nearest centroid that still has room (same score as the
+// assignment kernels: x . c^ - ||c^||^2 / 2 on the scoring-type centroids, fp32 sums, lowest index on ties).
+// One workgroup per (head, block); phase B is sequential by definition, a thread owns the centroids
+// tid + 256 k and the row being placed is staged in LDS one row ahead.
+// ------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ void __launch_bounds__(256) k_balance(const T* __restrict__ X, const T* __restrict__ chat,
+                                                 const float* __restrict__ nhc2, const int32_t* __restrict__ perm,
+                                                 const int32_t* __restrict__ off, int32_t* __restrict__ assign,
+                                                 int N, int Bs, int C, int cap) {
+  extern __shared__ int bal_lds[];
+  int* count = bal_lds;                                        // [C] rows held per cluster
+  unsigned* bits = reinterpret_cast<unsigned*>(count + C);     // [Bs / 32 (+1)] displaced rows of the block
+  unsigned short* evl = reinterpret_cast<unsigned short*>(bits + (Bs + 31) / 32);  // [Bs] the same, in order
+  __shared__ float xs[2][D];
+  __shared__ float rv[4];
+  __shared__ int rj[4];
+  __shared__ int wsum[4];
+  const int b = blockIdx.x, h = blockIdx.y, nbk = N / Bs;
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int32_t* oh = off + (size_t)h * ((size_t)nbk * C + 1) + (size_t)b * C;
+  const int32_t* ph = perm + (size_t)h * N;
+  int32_t* ah = assign + (size_t)h * N;
+  const T* Xh = X + (size_t)h * N * D;
+  const int nw = (Bs + 31) / 32;
+  for (int j = tid; j < C; j += 256) count[j] = min(oh[j + 1] - oh[j], cap);
+  for (int w = tid; w < nw; w += 256) bits[w] = 0u;
+  __syncthreads();
+  // rank of a row inside its segment = its index in the bucketed order minus the segment's start
+  for (int t = tid; t < Bs; t += 256) {
+    const int idx = b * Bs + t;
+    const int row = ph[idx];
+    const int j = ah[row];
+    if (idx - oh[j] >= cap) atomicOr(&bits[(row - b * Bs) >> 5], 1u << ((row - b * Bs) & 31));
+  }
+  __syncthreads();
+  // the displaced rows in position order
+  int nev = 0;
+  for (int w0 = 0; w0 < nw; w0 += 256) {
+    const int w = w0 + tid;
+    const unsigned word = w < nw ? bits[w] : 0u;
+    const int c = __popc(word);
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += v;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    int base = nev;
+    for (int q = 0; q < wave; ++q) base += wsum[q];
+    const int total = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    int pos = base + incl - c;
+    unsigned rest = word;
+    while (rest) {
+      evl[pos++] = (unsigned short)(32 * w + __ffs(rest) - 1);
+      rest &= rest - 1;
+    }
+    nev += total;
+    __syncthreads();
+  }
+  if (nev == 0) return;
+  if (tid < D) xs[0][tid] = Elem<T>::ld(Xh, (size_t)(b * Bs + evl[0]) * D + tid);
+  __syncthreads();
+  const T* ch = chat + (size_t)h * C * D;
+  const float* nh = nhc2 + (size_t)h * C;
+  for (int i = 0; i < nev; ++i) {
+    const int row = b * Bs + evl[i];
+    float xn = 0.f;  // next row, requested before this one is scored
+    if (tid < D && i + 1 < nev) xn = Elem<T>::ld(Xh, (size_t)(b * Bs + evl[i + 1]) * D + tid);
+    const float* x = xs[i & 1];
+    float best = MUSE_NEG_INF;
+    int bj = 0x7fffffff;
+    for (int j = tid; j < C; j += 256) {
+      if (count[j] >= cap) continue;
+      float acc = 0.f;
+#pragma unroll
+      for (int d0 = 0; d0 < D; d0 += 4) {
+        float c4[4];
+        ld4(ch, (size_t)j * D + d0, c4);
+        const float4 x4 = *reinterpret_cast<const float4*>(x + d0);
+        acc = fmaf(c4[0], x4.x, acc); acc = fmaf(c4[1], x4.y, acc);
+        acc = fmaf(c4[2], x4.z, acc); acc = fmaf(c4[3], x4.w, acc);
+      }
+      acc += nh[j];
+      if (acc > best) {  // j increases: the first of equal scores stays
+        best = acc;
+        bj = j;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      const float ov = __shfl_xor(best, o, 64);
+      const int oj = __shfl_xor(bj, o, 64);
+      if (ov > best || (ov == best && oj < bj)) {
+        best = ov;
+        bj = oj;
+      }
+    }
+    if (lane == 0) {
+      rv[wave] = best;
+      rj[wave] = bj;
+    }
+    if (tid < D) xs[(i + 1) & 1][tid] = xn;
+    __syncthreads();
+    if (tid == 0) {
+      float bv = rv[0];
+      int j = rj[0];
+      for (int q = 1; q < 4; ++q)
+        if (rv[q] > bv || (rv[q] == bv && rj[q] < j)) {
+          bv = rv[q];
+          j = rj[q];
+        }
+      if (j < C) {  // always: a place is free somewhere, C cap >= Bs is checked by the host
+        ah[row] = j;
+        count[j] += 1;
+      }
+    }
+    __syncthreads();
+  }
+}
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 template <typename T>
@@ -758,6 +885,18 @@ int cluster_impl(const MuseDims& d, const T* X, int H, int C, const int32_t* ini
       else { MuseProf prof_("k_assign_bf16", st); hipLaunchKernelGGL((k_assign_bf16<128, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C); }
     }
     MUSE_LAUNCH_CHECK();
+    if (it == T_ && d.balanced) {
+      // App. C "Balanced Assignment": the nearest-centroid assignment bucketed by (block, cluster), then the rows
+      // beyond the cap of their segment are placed again
+      const int cap = (int)((4LL * d.Bs) / C);
+      if (cap < 1 || (long long)cap * C < d.Bs) return MUSE_ERR_UNSUPPORTED;
+      int rc = muse_launch_bucket(assign, heads, N, d.Bs, C, perm, off, st);
+      if (rc) return rc;
+      const size_t lds = (size_t)C * 4 + (size_t)((d.Bs + 31) / 32) * 4 + (size_t)d.Bs * 2 + 16;
+      if (D == 64) { MuseProf prof_("k_balance", st); hipLaunchKernelGGL((k_balance<T, 64>), dim3(d.nb, heads), dim3(256), lds, st, X, chat, nhc2, perm, off, assign, N, d.Bs, C, cap); }
+      else { MuseProf prof_("k_balance", st); hipLaunchKernelGGL((k_balance<T, 128>), dim3(d.nb, heads), dim3(256), lds, st, X, chat, nhc2, perm, off, assign, N, d.Bs, C, cap); }
+      MUSE_LAUNCH_CHECK();
+    }
     if (it == T_) break;
     int rc = muse_launch_bucket(assign, heads, N, d.Bs, C, perm, off, st);
     if (rc) return rc;

@@ -70,10 +70,11 @@ int make_dims(const muse_params* p, bool full, MuseDims* d) {
   if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->N < 1 || p->Hq % p->Hkv) return MUSE_ERR_INVALID_ARG;
   if (p->dtype != MUSE_DTYPE_FP32 && p->dtype != MUSE_DTYPE_BF16) return MUSE_ERR_INVALID_ARG;
   if (p->grad_dtype != MUSE_DTYPE_FP32 && p->grad_dtype != p->dtype) return MUSE_ERR_INVALID_ARG;
-  if (p->flags & ~(uint32_t)(MUSE_FLAG_KEEP_FWD_STATE | MUSE_FLAG_FROZEN_WEIGHTS | MUSE_FLAG_STREAMING_KMEANS)) return MUSE_ERR_INVALID_ARG;
+  if (p->flags & ~(uint32_t)(MUSE_FLAG_KEEP_FWD_STATE | MUSE_FLAG_FROZEN_WEIGHTS | MUSE_FLAG_STREAMING_KMEANS | MUSE_FLAG_BALANCED_ASSIGN)) return MUSE_ERR_INVALID_ARG;
   d->keep_state = (p->flags & MUSE_FLAG_KEEP_FWD_STATE) != 0;
   d->frozen_weights = (p->flags & MUSE_FLAG_FROZEN_WEIGHTS) != 0;
   d->streaming = (p->flags & MUSE_FLAG_STREAMING_KMEANS) != 0;
+  d->balanced = (p->flags & MUSE_FLAG_BALANCED_ASSIGN) != 0;
   if (!(p->scale >= 0.f) || isinf(p->scale)) return MUSE_ERR_INVALID_ARG;
   if (p->causal != 1) return MUSE_ERR_UNSUPPORTED;
   if (p->D != 64 && p->D != 128) return MUSE_ERR_UNSUPPORTED;

@@ -36,7 +36,7 @@ def test_strerror_and_host_side_validation():
     assert mn > 0 and pref >= mn
     for bad, msg in ((dict(causal=0), "unsupported"), (dict(D=80), "unsupported"), (dict(Hkv=3), "invalid"),
                      (dict(block=1000), "invalid"), (dict(r=2000), "invalid"), (dict(Ck=4096), "unsupported"),
-                     (dict(flags=8), "invalid")):
+                     (dict(flags=16), "invalid")):
         import dataclasses
         with pytest.raises(mb.MuseError, match=msg):
             mb.muse_workspace_bytes(dataclasses.replace(good, **bad), mb.WS_FWD)

@@ -116,3 +116,76 @@ def test_stream_pass_full_size_one_head(oracle):
     p = mb.params_for(w)
     K = dev(d["K"], p)
     _check_side(oracle, p, 1, K, 1, w.Ck, d["k_init_idx"], "cfg3 keys")
+
+
+# ---------------------------------------------------------------------------
+# balanced assignment (App. C "Balanced Assignment", MUSE_FLAG_BALANCED_ASSIGN)
+# ---------------------------------------------------------------------------
+BALANCED = {
+    # name: (base, overrides, extra flags); cap = floor(4 block / C)
+    "bf16_lloyd": ("cfg2", dict(N=4096, Hq=2, Hkv=2, Cq=48, Ck=200, block=512, kmeans_iters=3), 0),
+    "bf16_streaming": ("cfg2", dict(N=4096, Hq=2, Hkv=2, Cq=48, Ck=200, block=512), mb.FLAG_STREAMING_KMEANS),
+    "bf16_tight": ("cfg4", dict(N=2048, Hq=2, Hkv=1, Cq=64, Ck=256, block=256, kmeans_iters=1), 0),   # cap 16 and 4
+    "fp32_ragged": ("cfg1", dict(N=1000, Cq=5, Ck=37, block=125, kmeans_iters=2), 0),
+    "bf16_d128": ("cfg5", dict(N=2080, Hq=2, Hkv=1, Cq=40, Ck=130, block=260, kmeans_iters=1), mb.FLAG_STREAMING_KMEANS),
+}
+
+
+@pytest.mark.parametrize("name", list(BALANCED))
+def test_balanced_assignment(oracle, name):
+    """The library's capped assignment replayed by the oracle along the library's own choices: nothing breaks the
+    rule, every displaced row sits within MARGIN of the best centroid that had room; and the oracle left free
+    gives the same assignment when no decision of either phase is a near-tie."""
+    base, kw, extra = BALANCED[name]
+    w = small(base, **kw)
+    d = generate(w)
+    p = mb.params_for(w, flags=mb.FLAG_BALANCED_ASSIGN | extra)
+    p_plain = mb.params_for(w, flags=extra)
+    Q, K = dev(d["Q"], p), dev(d["K"], p)
+    qi, ki = d["q_init_idx"].cuda(), d["k_init_idx"].cuda()
+    qc, qa, kc, ka = mb.muse_cluster(p, Q, K, qi, ki)
+    qc0, qa0, kc0, ka0 = mb.muse_cluster(p_plain, Q, K, qi, ki)
+    assert torch.equal(qc, qc0) and torch.equal(kc, kc0)   # the cap touches the assignment only
+    rm = 1 if w.dtype == "bf16" else 0
+    displaced = 0
+    for X, cent, asg, plain, H, Cn in ((Q, qc, qa, qa0, w.Hq, w.Cq), (K, kc, ka, ka0, w.Hkv, w.Ck)):
+        cap = 4 * w.Bs // Cn
+        for h in range(H):
+            got = asg[0, h].cpu().numpy()
+            sizes = np.stack([np.bincount(got[b * w.Bs:(b + 1) * w.Bs], minlength=Cn) for b in range(w.N // w.Bs)])
+            assert sizes.max() <= cap, f"{name}: a cluster holds {sizes.max()} rows of a block, cap {cap}"
+            displaced += int((got != plain[0, h].cpu().numpy()).sum())
+            Xh, ch = f64(X[0, h]), cent[0, h].cpu().double().numpy()
+            rep = oracle.balanced_assign(Xh, ch, w.Bs, cap, round_mode=rm, forced=got, tol=MARGIN)
+            assert rep["broken"] == 0, f"{name} head {h}: {rep['broken']} rows break the rule"
+            assert rep["regret"] <= MARGIN, f"{name} head {h}: a displaced row is {rep['regret']:.2e} from the best centroid with room"
+            free = oracle.balanced_assign(Xh, ch, w.Bs, cap, round_mode=rm)["assign"]
+            if oracle.kmeans(Xh, Cn, 0, cent0=ch, round_mode=rm)["margin"].min() > MARGIN:
+                diff = np.flatnonzero(free != got)
+                assert diff.size == 0, f"{name} head {h}: differs from the free oracle at rows {diff[:5]}"
+    if name in ("bf16_tight", "bf16_streaming"):
+        assert displaced > 0, "the case was meant to make the cap bind"
+
+
+def test_balanced_assignment_rejects_a_cap_without_room():
+    w = small("cfg2", N=1024, Hq=1, Hkv=1, Cq=2048 // 2, Ck=8, block=128)   # cap = floor(512 / 1024) = 0
+    d = generate(w)
+    p = mb.params_for(w, flags=mb.FLAG_BALANCED_ASSIGN)
+    with pytest.raises(mb.MuseError, match="unsupported"):
+        mb.muse_cluster(p, dev(d["Q"], p), None, d["q_init_idx"].cuda(), None)
+
+
+def test_paper_clustering_full_size_one_head(oracle):
+    """Streaming pass + balanced assignment at the benchmark's shape (cfg3 keys: N = 65536, 1024 clusters, blocks
+    of 8192, cap 32), one head: the cap holds and the oracle's replay finds nothing wrong."""
+    w = dataclasses.replace(CONFIGS["cfg3"], Hq=1, Hkv=1)
+    d = generate(w)
+    p = mb.params_for(w, flags=mb.FLAG_STREAMING_KMEANS | mb.FLAG_BALANCED_ASSIGN)
+    K = dev(d["K"], p)
+    _, _, kc, ka = mb.muse_cluster(p, None, K, None, d["k_init_idx"].cuda())
+    got = ka[0, 0].cpu().numpy()
+    cap = 4 * w.Bs // w.Ck
+    sizes = np.stack([np.bincount(got[b * w.Bs:(b + 1) * w.Bs], minlength=w.Ck) for b in range(w.N // w.Bs)])
+    assert sizes.max() <= cap
+    rep = oracle.balanced_assign(f64(K[0, 0]), kc[0, 0].cpu().double().numpy(), w.Bs, cap, round_mode=1, forced=got, tol=MARGIN)
+    assert rep["broken"] == 0 and rep["regret"] <= MARGIN, rep
