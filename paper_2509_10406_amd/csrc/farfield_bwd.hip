@@ -66,7 +66,7 @@ __global__ void __launch_bounds__(256) k_selinfo(const int32_t* __restrict__ sel
 // dQ of the far field, one wave per query tile (same tiling as the forward kernel)
 // ------------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ void __launch_bounds__(64) k_ff_bwd_dq(
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, 2))) k_ff_bwd_dq(
     const T* __restrict__ Q, const T* __restrict__ dO, const float* __restrict__ qc, const T* __restrict__ Ks,
     const T* __restrict__ Vs, const float* __restrict__ L, const float* __restrict__ s_mu,
     const float* __restrict__ s_k, const T* __restrict__ s_v, const float* __restrict__ A_mu,
@@ -149,45 +149,92 @@ __global__ void __launch_bounds__(64) k_ff_bwd_dq(
         }
       }
     }
-    for (int jt = 0; jt < ntile; ++jt) {
+    // a tile's operands: this lane's k-bar and v-bar rows (cluster j0 + col, its half of every 16 dims), the
+    // mu-bar of the 16 clusters whose scores land in this lane, and the retrieved-cluster mask of its query.
+    // Two buffers: the next tile's loads are in flight while this one is used; loads are unconditional (a tile
+    // index past the end repeats the last tile) and the values stay raw until they are used.
+    struct BT {
+      uint4 k[KS], v[KS];
+      float mu[16];
+      uint32_t mw;
+    };
+    auto load_bt = [&](BT& t, int jt) {
+      jt = jt < ntile ? jt : ntile - 1;
       const int j0 = jt * 32;
       int c = j0 + col;
       c = c < Ck ? c : Ck - 1;
-      f32x16_t s, dp;
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          int jr = j0 + 8 * g + 4 * half + t;
-          s[4 * g + t] = jr < Ck ? Amu[jr] : MUSE_NEG_INF;
-          dp[4 * g + t] = 0.f;
-        }
 #pragma unroll
       for (int x = 0; x < KS; ++x) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(Akh + (size_t)c * D + 16 * x + 8 * half), qb[x], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t*>(Avh + (size_t)c * D + 16 * x + 8 * half), gb[x], dp, 0, 0, 0);
+        t.k[x] = *reinterpret_cast<const uint4*>(Akh + (size_t)c * D + 16 * x + 8 * half);
+        t.v[x] = *reinterpret_cast<const uint4*>(Avh + (size_t)c * D + 16 * x + 8 * half);
       }
-      const uint32_t mw = selmask[((size_t)hq * W + jt) * N + pos];
+      if ((Ck & 3) == 0) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          int base = j0 + 8 * g + 4 * half;
+          base = base < Ck ? base : Ck - 4;
+          const float4 m4 = *reinterpret_cast<const float4*>(Amu + base);
+          t.mu[4 * g] = m4.x; t.mu[4 * g + 1] = m4.y; t.mu[4 * g + 2] = m4.z; t.mu[4 * g + 3] = m4.w;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+          t.mu[e] = Amu[jr < Ck ? jr : Ck - 1];
+        }
+      }
+      t.mw = selmask[((size_t)hq * W + jt) * N + pos];
+    };
+    // k-bar tile transposed ([dim][cluster]) for the dq contraction; lanes run along the clusters: 2-byte stores
+    // into consecutive banks
+    __shared__ __attribute__((aligned(16))) bf16_t kt[D][32 + 4];
+    auto process = [&](const BT& t, int jt) {
+      const int j0 = jt * 32;
+      f32x16_t s, dp;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        int row = 8 * (e / 4) + 4 * half + (e % 4);
-        float p = ((mw >> row) & 1u) ? 0.f : __expf(s[e] - lse);
+        s[e] = t.mu[e];
+        dp[e] = 0.f;
+      }
+#pragma unroll
+      for (int x = 0; x < KS; ++x) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, t.k[x]), qb[x], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, t.v[x]), gb[x], dp, 0, 0, 0);
+      }
+      wave_lds_fence();
+#pragma unroll
+      for (int x = 0; x < KS; ++x) {
+        const uint32_t w4[4] = {t.k[x].x, t.k[x].y, t.k[x].z, t.k[x].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          kt[16 * x + 8 * half + 2 * e][col] = (bf16_t)(w4[e] & 0xffffu);
+          kt[16 * x + 8 * half + 2 * e + 1][col] = (bf16_t)(w4[e] >> 16);
+        }
+      }
+      wave_lds_fence();
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = 8 * (e / 4) + 4 * half + (e % 4);
+        const bool off_ = ((t.mw >> row) & 1u) || j0 + row >= Ck;  // retrieved, or past the last cluster
+        const float p = off_ ? 0.f : __expf(s[e] - lse);
         s[e] = p * (dp[e] - dl);
       }
 #pragma unroll
       for (int G = 0; G < 2; ++G) {
-        bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
+        const bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
 #pragma unroll
-        for (int x = 0; x < DT; ++x) {
-          bf16x8_t ak;
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            int jr = j0 + 8 * (2 * G + u / 4) + 4 * half + (u % 4);
-            jr = jr < Ck ? jr : Ck - 1;
-            ak[u] = bits_to_bf16(Akh[(size_t)jr * D + 32 * x + col]);
-          }
-          dq[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, df, dq[x], 0, 0, 0);
-        }
+        for (int x = 0; x < DT; ++x)
+          dq[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_tr8(&kt[32 * x + col][0], 16 * G, half), df, dq[x], 0, 0, 0);
+      }
+    };
+    BT ta, tb;
+    load_bt(ta, 0);
+    for (int jt = 0; jt < ntile; jt += 2) {
+      load_bt(tb, jt + 1);
+      process(ta, jt);
+      if (jt + 1 < ntile) {
+        load_bt(ta, jt + 2);
+        process(tb, jt + 1);
       }
     }
   } else
