@@ -728,9 +728,7 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
         part[u] = pa;
       }
 #pragma unroll
-      for (int sh = 1; sh < 16; sh <<= 1)
-#pragma unroll
-        for (int u = 0; u < 8; ++u) part[u] += __shfl_xor(part[u], sh, 64);
+      for (int u = 0; u < 8; ++u) part[u] = group_sum<16>(part[u]);
 #pragma unroll
       for (int u = 0; u < 8; ++u)
         if (c0 + u < b && mu[u] > MUSE_NEG_INF) sc2[c0 + u] = part[u] + mu[u];
@@ -779,8 +777,7 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
             pa = fmaf(qt[x][0], k4[0], pa); pa = fmaf(qt[x][1], k4[1], pa);
             pa = fmaf(qt[x][2], k4[2], pa); pa = fmaf(qt[x][3], k4[3], pa);
           }
-#pragma unroll
-          for (int sh = 1; sh < 16; sh <<= 1) pa += __shfl_xor(pa, sh, 64);
+          pa = group_sum<16>(pa);
           add(pa + L[((size_t)hl * Cq + i) * N + p_], v);  // q.k = q~.k + q-bar.k
         }
       }

@@ -410,12 +410,10 @@ __global__ void __launch_bounds__(256) k_comp2_bwd_dq(
         part[u] = pa; dpp[u] = pd;
       }
 #pragma unroll
-      for (int sh = 1; sh < 16; sh <<= 1)
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          part[u] += __shfl_xor(part[u], sh, 64);
-          dpp[u] += __shfl_xor(dpp[u], sh, 64);
-        }
+      for (int u = 0; u < 8; ++u) {
+        part[u] = group_sum<16>(part[u]);
+        dpp[u] = group_sum<16>(dpp[u]);
+      }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const bool use = c0 + u < b && mu[u] > MUSE_NEG_INF && !((selbits >> (c0 + u)) & 1u);
@@ -855,12 +853,10 @@ __global__ void __launch_bounds__(256) k_chain_grads(
                 dpp[z] = fmaf(dv[z][x][2], vv[x][2], dpp[z]); dpp[z] = fmaf(dv[z][x][3], vv[x][3], dpp[z]);
               }
 #pragma unroll
-            for (int o = 1; o < 8; o <<= 1)
-#pragma unroll
-              for (int z = 0; z < 2; ++z) {
-                part[z] += __shfl_xor(part[z], o, 64);
-                dpp[z] += __shfl_xor(dpp[z], o, 64);
-              }
+            for (int z = 0; z < 2; ++z) {
+              part[z] = group_sum<8>(part[z]);
+              dpp[z] = group_sum<8>(dpp[z]);
+            }
 #pragma unroll
             for (int z = 0; z < 2; ++z) {  // entry e first, then e + 1: the order of the sums stays that of the list
               const float p = use[z] ? __expf(part[z] + mu - ld2[z].x) : 0.f;
@@ -1067,11 +1063,8 @@ __device__ __forceinline__ void c3_flush(const uint32_t* hits, const int* start,
           part = fmaf(q8[x], k8[x], part);
           dpp = fmaf(g8[x], v8[x], dpp);
         }
-#pragma unroll
-        for (int o = 1; o < CH; o <<= 1) {
-          part += __shfl_xor(part, o, 64);
-          dpp += __shfl_xor(dpp, o, 64);
-        }
+        part = group_sum<CH>(part);
+        dpp = group_sum<CH>(dpp);
         const float p = kvalid ? __expf(part - LSE[qn]) : 0.f;
         const float dlg = p * (dpp - delta[qn]);
 #pragma unroll

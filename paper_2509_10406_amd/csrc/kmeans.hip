@@ -363,23 +363,6 @@ __global__ void __launch_bounds__(256) k_update(const T* __restrict__ X, const i
 // ------------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(8))) _Float16 kf16x8_t;
 
-// sum over the 64 lanes, in every lane: four DPP steps inside each row of 16 lanes (quad swaps, half-row and row
-// mirrors), then the four row sums through scalar registers.  No LDS traffic, unlike the shuffle-based wave_sum.
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float v) {
-  return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
-}
-__device__ __forceinline__ float wave_sum_dpp(float v) {
-  v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
-  v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
-  v = dpp_add<0x141>(v);  // row_half_mirror
-  v = dpp_add<0x140>(v);  // row_mirror
-  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
-  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
-  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
-  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
-  return (r0 + r1) + (r2 + r3);
-}
 constexpr int kStreamMB = 64;
 constexpr int kStreamNW = 8;  // waves of the workgroup that owns a head (two per SIMD)
 constexpr float kStreamBeta = 0.9f;
