@@ -439,7 +439,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 // Results are added to the bucketed-order gradient rows this wave owns.
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, 2))) k_c3_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, D == 64 ? 2 : 1))) k_c3_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
                                                   const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
                                                   const float* __restrict__ LSE, const float* __restrict__ delta,
                                                   const int32_t* __restrict__ off_k, const int32_t* __restrict__ pair_off,
@@ -447,8 +447,6 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
                                                   float* __restrict__ dVs, size_t hit_cap, int N, int nb, int Ck,
                                                   int Hq, int Hkv, float scale, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
-  __shared__ __attribute__((aligned(16))) bf16_t qs[32][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t gs[32][D + 8];
   __shared__ __attribute__((aligned(16))) bf16_t qt_[D][32 + TPAD];
   __shared__ __attribute__((aligned(16))) bf16_t gt_[D][32 + TPAD];
   __shared__ __attribute__((aligned(16))) float lse_s[32];
@@ -478,50 +476,53 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
     for (int t = 0; t < DT; ++t)
 #pragma unroll
       for (int e = 0; e < 16; ++e) { dk[t][e] = 0.f; dv[t][e] = 0.f; }
-    // the hit list of a tile is one coalesced load (lane -> row), fetched one tile ahead
-    uint32_t hitn = hh[hlo + col < hhi ? hlo + col : hhi - 1].x;
-    for (int h0 = hlo; h0 < hhi; h0 += 32) {
-      const uint32_t hitc = hitn;
-      if (h0 + 32 < hhi) hitn = hh[h0 + 32 + col < hhi ? h0 + 32 + col : hhi - 1].x;
-      // gather: every row load of the tile is issued before the first LDS write
-      constexpr int NIT = 32 * CPR / 64;
-      uint4 qv[NIT], gv[NIT];
-      float lv = 0.f, dv_ = 0.f;
+    // A tile of 32 hits: the hit of row `col` (one coalesced load of the list), that query's q and dO rows as
+    // this lane's half of every 16 dims (the A operands of the score contractions as they are, and the source
+    // of the transposed LDS tiles), its LSE and delta.  The next tile is gathered while this one is used; a
+    // tile index past the end repeats the last hit, the values stay raw until they are used.
+    constexpr int NIT = KS;
+    struct HT {
+      uint4 q[NIT], g[NIT];
+      float lse, dl;
+    };
+    auto gather = [&](HT& t, int h0) {
+      const int hi = h0 + col < hhi ? h0 + col : hhi - 1;
+      const uint32_t hit = hh[hi].x;
+      const size_t qn = (hqbase + (hit >> 22)) * N + (hit & 0x3fffffu);
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
-        const int c = lane + 64 * it, row = c % 32, cc = c / 32;  // lanes along the rows: conflict-free transposed stores
-        const uint32_t hit = (uint32_t)__shfl((int)hitc, row, 64);
-        const size_t qn = (hqbase + (hit >> 22)) * N + (hit & 0x3fffffu);
-        qv[it] = *reinterpret_cast<const uint4*>(Q + qn * D + cc * 8);
-        gv[it] = *reinterpret_cast<const uint4*>(dO + qn * D + cc * 8);
+        t.q[it] = *reinterpret_cast<const uint4*>(Q + qn * D + 16 * it + 8 * half);
+        t.g[it] = *reinterpret_cast<const uint4*>(dO + qn * D + 16 * it + 8 * half);
       }
-      if (lane < 32) {
-        const size_t qn = (hqbase + (hitc >> 22)) * N + (hitc & 0x3fffffu);
-        lv = h0 + lane < hhi ? LSE[qn] * 1.4426950408889634f : __builtin_huge_valf();  // +inf -> p = 0
-        dv_ = delta[qn];
-      }
+      t.lse = LSE[qn];
+      t.dl = delta[qn];
+    };
+    auto use = [&](const HT& t, int h0) {
       wave_lds_fence();
 #pragma unroll
-      for (int it = 0; it < NIT; ++it) {
-        const int c = lane + 64 * it, row = c % 32, cc = c / 32;  // lanes along the rows: conflict-free transposed stores
-        *reinterpret_cast<uint4*>(&qs[row][cc * 8]) = qv[it];
-        *reinterpret_cast<uint4*>(&gs[row][cc * 8]) = gv[it];
-        const bf16_t* pq = reinterpret_cast<const bf16_t*>(&qv[it]);
-        const bf16_t* pg = reinterpret_cast<const bf16_t*>(&gv[it]);
+      for (int it = 0; it < NIT; ++it) {  // lanes run along the rows: conflict-free transposed stores
+        const uint32_t wq[4] = {t.q[it].x, t.q[it].y, t.q[it].z, t.q[it].w};
+        const uint32_t wg[4] = {t.g[it].x, t.g[it].y, t.g[it].z, t.g[it].w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { qt_[cc * 8 + e][row] = pq[e]; gt_[cc * 8 + e][row] = pg[e]; }
+        for (int e = 0; e < 4; ++e) {
+          qt_[16 * it + 8 * half + 2 * e][col] = (bf16_t)(wq[e] & 0xffffu);
+          qt_[16 * it + 8 * half + 2 * e + 1][col] = (bf16_t)(wq[e] >> 16);
+          gt_[16 * it + 8 * half + 2 * e][col] = (bf16_t)(wg[e] & 0xffffu);
+          gt_[16 * it + 8 * half + 2 * e + 1][col] = (bf16_t)(wg[e] >> 16);
+        }
       }
-      if (lane < 32) { lse_s[lane] = lv; dl_s[lane] = dv_; }
+      if (half == 0) {
+        lse_s[col] = h0 + col < hhi ? t.lse * 1.4426950408889634f : __builtin_huge_valf();  // +inf -> p = 0
+        dl_s[col] = t.dl;
+      }
       wave_lds_fence();
       f32x16_t s, dp;
 #pragma unroll
       for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
       for (int x = 0; x < KS; ++x) {
-        bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(&qs[col][16 * x + 8 * half]);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[x], s, 0, 0, 0);
-        bf16x8_t ag = *reinterpret_cast<const bf16x8_t*>(&gs[col][16 * x + 8 * half]);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, vf[x], dp, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, t.q[x]), kf[x], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, t.g[x]), vf[x], dp, 0, 0, 0);
       }
       f32x16_t pr;
 #pragma unroll
@@ -549,6 +550,24 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
           bf16x8_t aq = ld_tr8(&qt_[32 * t + col][0], 16 * G, half);
           dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, df, dk[t], 0, 0, 0);
         }
+      }
+    };
+    if constexpr (D == 64) {
+      HT ta, tb;
+      gather(ta, hlo);
+      for (int h0 = hlo; h0 < hhi; h0 += 64) {
+        gather(tb, h0 + 32);
+        use(ta, h0);
+        if (h0 + 32 < hhi) {
+          gather(ta, h0 + 64);
+          use(tb, h0 + 32);
+        }
+      }
+    } else {  // two buffers do not fit the registers at D = 128
+      for (int h0 = hlo; h0 < hhi; h0 += 32) {
+        HT ta;
+        gather(ta, h0);
+        use(ta, h0);
       }
     }
     if (kvalid) {
