@@ -296,16 +296,23 @@ __global__ void __launch_bounds__(256) k_update(const T* __restrict__ X, const i
   float acc[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-  // a row slot takes every slots-th spatial block and walks its members four at a time (positions, then rows:
-  // two round trips for four members)
+  // a row slot takes every slots-th spatial block and walks its members four at a time; the positions of the
+  // next four are requested together with the rows of these four (one round trip per four members)
   int count = 0;
   for (int b = slot; b < nb; b += slots) {
     const int lo = oh[b * C + j], hi = oh[b * C + j + 1];
     count += hi - lo;
+    if (lo >= hi) continue;
+    int rown[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) rown[u] = ph[lo + u < hi ? lo + u : hi - 1];
     for (int p = lo; p < hi; p += 4) {
       int row[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) row[u] = ph[p + u < hi ? p + u : hi - 1];
+      for (int u = 0; u < 4; ++u) {
+        row[u] = rown[u];
+        rown[u] = ph[p + 4 + u < hi ? p + 4 + u : hi - 1];
+      }
       if constexpr (EPL == 8) {
         uint4 v[4];
 #pragma unroll
