@@ -1044,7 +1044,11 @@ __global__ void __launch_bounds__(64) k_cells_to_keys_mx(const bf16_t* __restric
   const int hkl = blockIdx.z;
   const int hq0 = h0 + hkl * G_;
   const int hk = (hq0 / Hq) * Hkv + (hq0 % Hq) / G_;
-  const int bp = blockIdx.y, j = blockIdx.x, NBm = nb - 1;
+  // x % 8 is the XCD a workgroup lands on (the grid's x extent is a multiple of 8): each XCD takes a run of
+  // consecutive key clusters, whose per-cell scalars share 32-byte sectors, so a sector is fetched by one L2
+  const int run = gridDim.x / 8;
+  const int bp = blockIdx.y, j = (blockIdx.x % 8) * run + blockIdx.x / 8, NBm = nb - 1;
+  if (j >= Ck) return;
   const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
   const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
   const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
@@ -1177,7 +1181,7 @@ int muse_launch_cells_to_keys_mx(const MuseDims& d, const void* Ks, const void* 
   const int CqP = (d.Cq + 31) / 32 * 32;
   // qcT holds the transposed centroids of the chunk's heads [h0, h0 + hn)
   { MuseProf prof_("k_qc_transpose", st); hipLaunchKernelGGL(k_qc_transpose, dim3((d.D * CqP + 255) / 256, hn), dim3(256), 0, st, qc + (size_t)h0 * d.Cq * d.D, (bf16_t*)qcT, d.D, d.Cq, CqP, d.scale); }
-  dim3 g(d.Ck, d.nb - 1, hn / (d.Hq / d.Hkv));
+  dim3 g((d.Ck + 7) / 8 * 8, d.nb - 1, hn / (d.Hq / d.Hkv));
   if (d.D == 64)
     { MuseProf prof_("k_cells_to_keys_mx", st); hipLaunchKernelGGL(k_cells_to_keys_mx<64>, g, dim3(64), 0, st, (const bf16_t*)Ks, (const bf16_t*)Vs, (const bf16_t*)qcT, L, s_mu, G_c, (const bf16_t*)G_k, (const bf16_t*)G_v, off_k, dKs, dVs, h0, d.N, d.nb, d.Cq, CqP, d.Ck, d.Hq, d.Hkv, d.frozen_weights ? 1 : 0); }
   else

@@ -102,7 +102,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 4)))
   constexpr int DS = D / 64;  // slices of the head dim
   constexpr int KCH = 8;  // keys per chunk
   __shared__ float tr[32][68];
-  const int j = blockIdx.x, hl = blockIdx.z, hq = h0 + hl;
+  // x % 8 is the XCD a workgroup lands on (the grid's x extent is a multiple of 8): each XCD takes a run of
+  // consecutive key clusters, whose per-cell scalars share 32-byte sectors, so a sector is merged in one L2
+  const int j = (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;
+  if (j >= Ck) return;
+  const int hl = blockIdx.z, hq = h0 + hl;
   const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
   const int it = blockIdx.y / DS, d0 = (blockIdx.y % DS) * 64;
   const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
@@ -918,7 +922,7 @@ template <typename T>
 int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0, int hn, hipStream_t st) {
   const int N = d.N;
   dim3 gl((N + 255) / 256, hn);
-  dim3 gs(d.Ck, ((d.Cq + 31) / 32) * (d.D / 64), hn);
+  dim3 gs((d.Ck + 7) / 8 * 8, ((d.Cq + 31) / 32) * (d.D / 64), hn);
   if (d.D == 64) {
     { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 64>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
     { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 64>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
