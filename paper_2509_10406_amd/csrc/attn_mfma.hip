@@ -21,6 +21,35 @@ constexpr int TPAD = 4;  // padding of a transposed tile's rows: 34 dwords apart
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Numbering of the flash kernels' workgroups.  The tiles of 128 rows of one (batch, head, spatial block) group
+// stream the same keys and values (forward, dQ) or queries (dK/dV); workgroups go to the 8 XCDs round-robin by
+// their linear id, so with a grid of (8 tpg, ceil(groups / 8)) the workgroup (x, y) is on XCD x % 8 and takes
+// tile x / 8 of group 8 y + x % 8: a group's tiles run on one XCD, one after the other, and its operand rows
+// stay in that XCD's L2 instead of being fetched by all eight.  tpg = tiles per group (a block, or the whole
+// sequence when the block size is not a multiple of 128).
+struct FlashTile {
+  int t, blk, tpg, h, b;  // tile inside the group, block of the group, tiles per group, head, batch
+  bool ok;
+};
+__device__ __forceinline__ FlashTile flash_tile(int N, int Bs, int H, int nbatch) {
+  FlashTile r;
+  const bool al = (Bs % 128) == 0;
+  r.tpg = al ? Bs / 128 : (N + 127) / 128;
+  const int nblk = al ? N / Bs : 1;
+  const int g = blockIdx.y * 8 + blockIdx.x % 8;
+  r.t = blockIdx.x / 8;
+  r.ok = g < nbatch * H * nblk;
+  r.blk = g % nblk;
+  r.h = (g / nblk) % H;
+  r.b = g / nblk / H;
+  return r;
+}
+static dim3 flash_grid(int N, int Bs, int H, int nbatch) {
+  const bool al = (Bs % 128) == 0;
+  const int tpg = al ? Bs / 128 : (N + 127) / 128, nblk = al ? N / Bs : 1;
+  return dim3(8 * tpg, (nbatch * H * nblk + 7) / 8, 1);
+}
+
 // cooperative load of `rows` x D bf16 into a row-major tile (pad 8) and optionally a transposed one.
 // Consecutive lanes take consecutive rows (one 16-byte chunk each): the 2-byte stores into the transposed tile
 // then fall into consecutive LDS banks, and the row-major 16-byte stores are 36 dwords apart, which is
@@ -90,13 +119,15 @@ template <int D>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2))) k_flash_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                     const bf16_t* __restrict__ V, const float* __restrict__ ff,
                                                     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, int Bs,
-                                                    int Hq, int Hkv, float scale_log2e) {
+                                                    int Hq, int Hkv, int nbatch, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(16))) bf16_t ks[BN][D + 8];
   __shared__ __attribute__((aligned(16))) bf16_t vt[D][BN + TPAD];
-  const int hq = blockIdx.y, b = blockIdx.z, hk = hq / (Hq / Hkv);
+  const FlashTile ft = flash_tile(N, Bs, Hq, nbatch);
+  if (!ft.ok) return;
+  const int hq = ft.h, b = ft.b, hk = hq / (Hq / Hkv);
   const size_t qh = ((size_t)b * Hq + hq) * N, kh = ((size_t)b * Hkv + hk) * N;
-  const int q0 = (gridDim.x - 1 - blockIdx.x) * 128;  // long rows first
+  const int q0 = (ft.blk * ft.tpg + ft.tpg - 1 - ft.t) * 128;  // long rows first
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
   const int nq = q0 + 32 * wave + col;
   const int nqc = nq < N ? nq : N - 1;
@@ -191,7 +222,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   float cf = 0.f, lf = 0.f;
   const float* fa = nullptr;
   if (ff) {
-    const float* fm = ff + (size_t)gridDim.z * Hq * N * D + (qh + nq) * 2;  // [acc | (max,sum)] planes
+    const float* fm = ff + (size_t)nbatch * Hq * N * D + (qh + nq) * 2;  // [acc | (max,sum)] planes
     float mf = fm[0];
     lf = fm[1];
     if (lf > 0.f) {
@@ -228,14 +259,16 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
                                                        const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO,
                                                        const float* __restrict__ LSE, const float* __restrict__ delta,
                                                        float* __restrict__ dQ, int N, int Bs, int Hq, int Hkv,
-                                                       float scale, float scale_log2e) {
+                                                       int nbatch, float scale, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(16))) bf16_t ks[BN][D + 8];
   __shared__ __attribute__((aligned(16))) bf16_t vs[BN][D + 8];
   __shared__ __attribute__((aligned(16))) bf16_t kt_[D][BN + TPAD];
-  const int hq = blockIdx.y, b = blockIdx.z, hk = hq / (Hq / Hkv);
+  const FlashTile ft = flash_tile(N, Bs, Hq, nbatch);
+  if (!ft.ok) return;
+  const int hq = ft.h, b = ft.b, hk = hq / (Hq / Hkv);
   const size_t qh = ((size_t)b * Hq + hq) * N, kh = ((size_t)b * Hkv + hk) * N;
-  const int q0 = (gridDim.x - 1 - blockIdx.x) * 128;
+  const int q0 = (ft.blk * ft.tpg + ft.tpg - 1 - ft.t) * 128;
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
   const int nq = q0 + 32 * wave + col;
   const int nqc = nq < N ? nq : N - 1;
@@ -316,7 +349,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
                                                         const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO,
                                                         const float* __restrict__ LSE, const float* __restrict__ delta,
                                                         float* __restrict__ dK, float* __restrict__ dV, int N, int Bs,
-                                                        int Hq, int Hkv, float scale, float scale_log2e) {
+                                                        int Hq, int Hkv, int nbatch, float scale, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32;
   constexpr int BQ = D == 64 ? 64 : 32;  // queries staged per step (LDS budget)
   __shared__ __attribute__((aligned(16))) bf16_t qs[BQ][D + 8];
@@ -325,9 +358,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   __shared__ __attribute__((aligned(16))) bf16_t gt_[D][BQ + TPAD];
   __shared__ __attribute__((aligned(16))) float lse_s[BQ];
   __shared__ __attribute__((aligned(16))) float dl_s[BQ];
-  const int hk = blockIdx.y, b = blockIdx.z, G_ = Hq / Hkv;
+  const FlashTile ft = flash_tile(N, Bs, Hkv, nbatch);
+  if (!ft.ok) return;
+  const int hk = ft.h, b = ft.b, G_ = Hq / Hkv;
   const size_t kh = ((size_t)b * Hkv + hk) * N;
-  const int k0 = blockIdx.x * 128;
+  const int k0 = (ft.blk * ft.tpg + ft.t) * 128;  // the first key tiles of a block see the most queries
   const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
   const int mk = k0 + 32 * wave + col;
   const int mkc = mk < N ? mk : N - 1;
@@ -1247,14 +1282,14 @@ int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const
 
 int muse_launch_attn_fwd_mfma(const MuseDims& d, int Bs, const void* Q, const void* K, const void* V,
                               const float* ff, void* O, float* LSE, hipStream_t st) {
-  dim3 g((d.N + 127) / 128, d.Hq, d.B);
+  const dim3 g = flash_grid(d.N, Bs, d.Hq, d.B);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64)
     { MuseProf prof_("k_flash_fwd", st); hipLaunchKernelGGL(k_flash_fwd<64>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, ff,
-                       (bf16_t*)O, LSE, d.N, Bs, d.Hq, d.Hkv, sl); }
+                       (bf16_t*)O, LSE, d.N, Bs, d.Hq, d.Hkv, d.B, sl); }
   else
     { MuseProf prof_("k_flash_fwd", st); hipLaunchKernelGGL(k_flash_fwd<128>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, ff,
-                       (bf16_t*)O, LSE, d.N, Bs, d.Hq, d.Hkv, sl); }
+                       (bf16_t*)O, LSE, d.N, Bs, d.Hq, d.Hkv, d.B, sl); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
@@ -1262,15 +1297,15 @@ int muse_launch_attn_fwd_mfma(const MuseDims& d, int Bs, const void* Q, const vo
 int muse_launch_attn_bwd_mfma(const MuseDims& d, int Bs, const void* Q, const void* K, const void* V,
                               const void* dO, const float* LSE, const float* delta, float* dQacc,
                               float* dKacc, float* dVacc, hipStream_t st) {
-  dim3 gq((d.N + 127) / 128, d.Hq, d.B), gk((d.N + 127) / 128, d.Hkv, d.B);
+  const dim3 gq = flash_grid(d.N, Bs, d.Hq, d.B), gk = flash_grid(d.N, Bs, d.Hkv, d.B);
   float sl = d.scale * 1.4426950408889634f;
   const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V, *g = (const bf16_t*)dO;
   if (d.D == 64) {
-    { MuseProf prof_("k_flash_bwd_dq", st); hipLaunchKernelGGL(k_flash_bwd_dq<64>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl); }
-    { MuseProf prof_("k_flash_bwd_dkv", st); hipLaunchKernelGGL(k_flash_bwd_dkv<64>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl); }
+    { MuseProf prof_("k_flash_bwd_dq", st); hipLaunchKernelGGL(k_flash_bwd_dq<64>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.B, d.scale, sl); }
+    { MuseProf prof_("k_flash_bwd_dkv", st); hipLaunchKernelGGL(k_flash_bwd_dkv<64>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.B, d.scale, sl); }
   } else {
-    { MuseProf prof_("k_flash_bwd_dq", st); hipLaunchKernelGGL(k_flash_bwd_dq<128>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl); }
-    { MuseProf prof_("k_flash_bwd_dkv", st); hipLaunchKernelGGL(k_flash_bwd_dkv<128>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.scale, sl); }
+    { MuseProf prof_("k_flash_bwd_dq", st); hipLaunchKernelGGL(k_flash_bwd_dq<128>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.B, d.scale, sl); }
+    { MuseProf prof_("k_flash_bwd_dkv", st); hipLaunchKernelGGL(k_flash_bwd_dkv<128>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.B, d.scale, sl); }
   }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
