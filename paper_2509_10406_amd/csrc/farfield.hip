@@ -665,7 +665,12 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
   const int hl = blockIdx.y, hq = h0 + hl;
   const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
   const int l16 = threadIdx.x % 16;
-  const int pos = Bs + blockIdx.x * 16 + threadIdx.x / 16;  // bucketed order is block-major: block 0 comes first
+  // Workgroups go to the 8 XCDs round-robin by their linear id (the grid's x extent is a multiple of 256): an XCD
+  // takes runs of 32 consecutive workgroups of the bucketed order, so the queries of one cluster, which read the
+  // same summary rows, meet in one L2, while the late blocks (more work per query) still spread over all XCDs.
+  const int sq = blockIdx.x / 8;
+  const int wg = ((sq / 32) * 8 + blockIdx.x % 8) * 32 + sq % 32;
+  const int pos = Bs + wg * 16 + threadIdx.x / 16;  // bucketed order is block-major: block 0 comes first
   if (pos >= N) return;
   const int n = perm_q[(size_t)hq * N + pos];
   const size_t qn = (size_t)hq * N + n;
@@ -982,7 +987,7 @@ void launch_ff_fwd_r(const MuseDims& d, const T* Q, const float* qc, const int32
   else launch_ff_fwd<T, D, 32>(d, Q, qc, w, selc, h0, hn, st);
   if (d.r > 0) {
     (void)muse_ff_block_summaries<T>(d, selc, aq, w, h0, hn, st);
-    dim3 g((d.N - d.Bs + 15) / 16, hn);
+    dim3 g(((d.N - d.Bs + 15) / 16 + 255) / 256 * 256, hn);  // a multiple of 256 (see the kernel)
     if (d.nb <= 9)
       { MuseProf prof_("k_comp2_fwd", st); hipLaunchKernelGGL((k_comp2_fwd<T, D, 1>), g, dim3(256), 0, st, Q, qc, (const T*)w.Ks, (const T*)w.Vs, w.L, w.s_mu, w.s_k,
                          (const T*)w.s_v, w.perm_q, w.off_k, aq, selc, selb, w.ff_acc, w.ff_ml, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r,

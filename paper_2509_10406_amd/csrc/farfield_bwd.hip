@@ -355,7 +355,12 @@ __global__ void __launch_bounds__(256) k_comp2_bwd_dq(
   constexpr int NG = D / 64;
   const int hl = blockIdx.y, hq = h0 + hl;
   const int l16 = threadIdx.x % 16;
-  const int pos = Bs + blockIdx.x * 16 + threadIdx.x / 16;  // bucketed order is block-major: block 0 comes first
+  // Workgroups go to the 8 XCDs round-robin by their linear id (the grid's x extent is a multiple of 256): an XCD
+  // takes runs of 32 consecutive workgroups of the bucketed order, so the queries of one cluster, which read the
+  // same summary rows, meet in one L2, while the late blocks (more work per query) still spread over all XCDs.
+  const int sq = blockIdx.x / 8;
+  const int wg = ((sq / 32) * 8 + blockIdx.x % 8) * 32 + sq % 32;
+  const int pos = Bs + wg * 16 + threadIdx.x / 16;  // bucketed order is block-major: block 0 comes first
   if (pos >= N) return;
   const int n = perm_q[(size_t)hq * N + pos];
   const size_t qn = (size_t)hq * N + n;
@@ -1183,7 +1188,7 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
                      w.s_k, (const T*)w.s_v, w.A_mu, w.A_k, (const T*)w.A_v, (const bf16_t*)w.A_kb, w.perm_q, w.off_q, w.off_k, w.tile_off, LSE, w.delta,
                      w.selmask, selc, selb, w.ret_part, w.dQff, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, d.scale); }
   if (sizeof(T) == 2 && d.r > 0) {
-    dim3 g2((d.N - d.Bs + 15) / 16, hn);
+    dim3 g2(((d.N - d.Bs + 15) / 16 + 255) / 256 * 256, hn);  // a multiple of 256 (see the kernel)
     if (d.nb <= 9)
       { MuseProf prof_("k_comp2_bwd_dq", st); hipLaunchKernelGGL((k_comp2_bwd_dq<D, 1>), g2, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, w.s_mu, w.s_k, (const bf16_t*)w.s_v,
                          w.perm_q, aq, LSE, w.delta, w.slotinfo, w.ret_part, w.dQff, h0, d.N, d.nb, d.Bs, d.Cq, d.Ck, d.r, d.k2e, d.scale); }
