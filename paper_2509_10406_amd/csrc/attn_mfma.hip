@@ -1240,7 +1240,7 @@ int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO
 
 int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, const void* Vs, const int32_t* off_k,
                               const int32_t* pair_off, const uint2* hits, size_t hit_cap, float* part, hipStream_t st) {
-  const int S = 4;  // hit slices per pair: slice s takes the hit tiles s, s + S, ... (a few pairs hold thousands of hits)
+  const int S = 8;  // hit slices per pair: slice s takes the hit tiles s, s + S, ... (a few pairs hold thousands of hits)
   dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv * S);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64)
@@ -1254,7 +1254,7 @@ int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, 
 int muse_launch_ret_bwd_dq_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
                                  const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
                                  const uint2* hits, size_t hit_cap, float* dqpart, hipStream_t st) {
-  const int S = 4;  // hit slices per pair, as in the forward
+  const int S = 8;  // hit slices per pair, as in the forward
   dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv * S);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64)
