@@ -9,6 +9,8 @@
 //   bucket:        one workgroup per (head, spatial block), LDS histograms per wave, ballot-based
 //                  stable ranks -> no global atomics, order inside a segment = ascending position.
 //   update:        one wave per (head, cluster): fixed-order sum over its segments.
+//   streaming pass (App. C "Centroid Computation") and balanced assignment (App. C "Balanced Assignment"):
+//                  the paper's own clustering, behind flags; see k_stream_kmeans and k_balance.
 #include "common.h"
 
 namespace {
