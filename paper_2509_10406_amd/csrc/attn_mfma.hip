@@ -1231,7 +1231,7 @@ int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO
                                 void* g_A_k, void* g_A_v, int h0, int hn, hipStream_t st) {
   dim3 g(1, (d.nb - 1) * d.Cq, hn);
   if (d.D == 64)
-    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL((k_ff_bwd_cells_mx<64, 2>), g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, (const bf16_t*)A_kb, (const bf16_t*)A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, (bf16_t*)g_A_k, (bf16_t*)g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
+    { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL((k_ff_bwd_cells_mx<64, 3>), g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, (const bf16_t*)A_kb, (const bf16_t*)A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, (bf16_t*)g_A_k, (bf16_t*)g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
   else
     { MuseProf prof_("k_ff_bwd_cells_mx", st); hipLaunchKernelGGL((k_ff_bwd_cells_mx<128, 1>), g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, qc, A_mu, (const bf16_t*)A_kb, (const bf16_t*)A_v, perm_q, off_q, LSE, delta, selmask, g_A_c, (bf16_t*)g_A_k, (bf16_t*)g_A_v, h0, d.N, d.nb, d.Cq, d.Ck, d.scale); }
   MUSE_LAUNCH_CHECK();
