@@ -29,6 +29,9 @@ CASES = {
     "bf16_gqa": ("cfg4", dict(N=2048, Hq=4, Hkv=2, Cq=32, Ck=96, block=256)),
     "bf16_d128": ("cfg5", dict(N=2080, Hq=2, Hkv=1, Cq=40, Ck=130, block=260)),
     "bf16_many_tiles": ("cfg2", dict(N=3000, Hq=1, Hkv=1, Cq=300, Ck=1030, block=3000)),
+    # one full minibatch and a ragged one; fewer rows than a tile of centroids
+    "fp32_tiny": ("cfg1", dict(N=96, Cq=3, Ck=40, block=48)),
+    "bf16_single_minibatch": ("cfg2", dict(N=40, Hq=1, Hkv=1, Cq=2, Ck=7, block=40)),
 }
 
 
@@ -128,6 +131,8 @@ BALANCED = {
     "bf16_tight": ("cfg4", dict(N=2048, Hq=2, Hkv=1, Cq=64, Ck=256, block=256, kmeans_iters=1), 0),   # cap 16 and 4
     "fp32_ragged": ("cfg1", dict(N=1000, Cq=5, Ck=37, block=125, kmeans_iters=2), 0),
     "bf16_d128": ("cfg5", dict(N=2080, Hq=2, Hkv=1, Cq=40, Ck=130, block=260, kmeans_iters=1), mb.FLAG_STREAMING_KMEANS),
+    # the cap leaves exactly one place per row (cap 1 with as many clusters as rows in a block would; here cap 2, 4)
+    "fp32_full_house": ("cfg1", dict(N=256, Cq=64, Ck=32, block=32, kmeans_iters=1), 0),
 }
 
 
