@@ -51,6 +51,55 @@ __global__ void k_tile_schedule(const int32_t* __restrict__ off_q, int32_t* __re
 // ------------------------------------------------------------------------------------------
 // tilt logits L[hl][i][p] = (scale * qc_i) . Ks[p]   (keys in bucketed order)
 // ------------------------------------------------------------------------------------------
+// The same for bf16 keys on the matrix cores: the fp32 operand scale * qc is split into three bf16 terms
+// (hi + mid + lo carry its 24 significant bits, each remainder is exact in fp32), the products with the bf16 keys
+// are exact and the sums fp32, so L keeps fp32 accuracy; one wave per 32 keys, rows = query clusters.
+template <int D>
+__global__ void __launch_bounds__(256) k_tilt_logits_mx(const bf16_t* __restrict__ Ks, const float* __restrict__ qc,
+                                                         float* __restrict__ L, int h0, int N, int Cq, int Hq, int Hkv,
+                                                         float scale) {
+  constexpr int KS = D / 16;
+  const int hl = blockIdx.y, hq = h0 + hl;
+  const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  const int p0 = (blockIdx.x * 4 + wave) * 32;
+  if (p0 >= N) return;
+  const int p = p0 + col < N ? p0 + col : N - 1;
+  bf16x8_t kb[KS];
+#pragma unroll
+  for (int x = 0; x < KS; ++x)
+    kb[x] = *reinterpret_cast<const bf16x8_t*>(Ks + ((size_t)hk * N + p) * D + 16 * x + 8 * half);
+  for (int i0 = 0; i0 < Cq; i0 += 32) {
+    const int ic = i0 + col < Cq ? i0 + col : Cq - 1;
+    const float* qr = qc + ((size_t)hq * Cq + ic) * D + 8 * half;
+    f32x16_t acc = zero16();
+#pragma unroll
+    for (int x = 0; x < KS; ++x) {
+      const float4 a = *reinterpret_cast<const float4*>(qr + 16 * x), b = *reinterpret_cast<const float4*>(qr + 16 * x + 4);
+      const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+      bf16x8_t hi, mid, lo;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float s0 = scale * v[e];
+        hi[e] = (__bf16)s0;
+        const float r1 = s0 - (float)hi[e];
+        mid[e] = (__bf16)r1;
+        lo[e] = (__bf16)(r1 - (float)mid[e]);
+      }
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, kb[x], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mid, kb[x], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, kb[x], acc, 0, 0, 0);
+    }
+    if (p0 + col < N) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int i = i0 + 8 * (e / 4) + 4 * half + (e % 4);
+        if (i < Cq) L[((size_t)hl * Cq + i) * N + p0 + col] = acc[e];
+      }
+    }
+  }
+}
+
 template <typename T, int D>
 __global__ void __launch_bounds__(256) k_tilt_logits(const T* __restrict__ Ks, const float* __restrict__ qc,
                                                       float* __restrict__ L, int h0, int N, int Cq, int Hq, int Hkv,
@@ -929,11 +978,17 @@ int muse_ff_summaries(const MuseDims& d, const float* qc, FFWorkspace& w, int h0
   dim3 gl((N + 255) / 256, hn);
   dim3 gs((d.Ck + 7) / 8 * 8, ((d.Cq + 31) / 32) * (d.D / 64), hn);
   if (d.D == 64) {
-    { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 64>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
+    if constexpr (sizeof(T) == 2)
+      { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits_mx<64>), dim3((N + 127) / 128, hn), dim3(256), 0, st, (const bf16_t*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
+    else
+      { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 64>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
     { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 64>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
                        w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, (uint16_t*)w.A_km, w.A_c, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   } else {
-    { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 128>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
+    if constexpr (sizeof(T) == 2)
+      { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits_mx<128>), dim3((N + 127) / 128, hn), dim3(256), 0, st, (const bf16_t*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
+    else
+      { MuseProf prof_("k_tilt_logits", st); hipLaunchKernelGGL((k_tilt_logits<T, 128>), gl, dim3(256), 0, st, (const T*)w.Ks, qc, w.L, h0, N, d.Cq, d.Hq, d.Hkv, d.scale); }
     { MuseProf prof_("k_summaries", st); hipLaunchKernelGGL((k_summaries<T, 128>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k, w.s_mu,
                        w.A_mu, w.A_k, (T*)w.A_v, (bf16_t*)w.A_kb, (uint16_t*)w.A_km, w.A_c, h0, N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   }
