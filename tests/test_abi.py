@@ -44,3 +44,18 @@ def test_strerror_and_host_side_validation():
     pc = good.c()
     rc = mb.load().muse_fwd(C.byref(pc), *([C.c_void_p(0)] * 11), C.c_size_t(0), C.c_void_p(0))
     assert rc == -1
+
+
+def test_kmeans_stream_rejects_bad_arguments_on_the_host():
+    """muse_kmeans_stream: side must be 0 or 1, the row and centroid pointers and the workspace must be given;
+    nothing is launched (no GPU here)."""
+    good = mb.Params(1, 16, 16, 65536, 64, Cq=256, Ck=1024, r=8)
+    pc = good.c()
+    lib = mb.load()
+    null = C.c_void_p(0)
+    fake = C.c_void_p(4096)  # never dereferenced: every call below fails a host check first
+    assert lib.muse_kmeans_stream(C.byref(pc), C.c_int(2), fake, null, fake, null, null, fake, C.c_size_t(1 << 40), null) == -1
+    assert lib.muse_kmeans_stream(C.byref(pc), C.c_int(0), null, null, fake, null, null, fake, C.c_size_t(1 << 40), null) == -1
+    assert lib.muse_kmeans_stream(C.byref(pc), C.c_int(1), fake, null, null, null, null, fake, C.c_size_t(1 << 40), null) == -1
+    assert lib.muse_kmeans_stream(C.byref(pc), C.c_int(1), fake, null, fake, null, null, null, C.c_size_t(1 << 40), null) == -1
+    assert lib.muse_kmeans_stream(C.byref(pc), C.c_int(1), fake, null, fake, null, null, fake, C.c_size_t(16), null) == -3
