@@ -33,6 +33,8 @@ CASES = {
     # more than 8 preceding blocks: the second chunk of the block loops
     "bf16_nb16_k2_2": ("cfg2", dict(N=2048, Hq=2, Hkv=1, Cq=8, Ck=32, r=3, k2=2, block=128, kmeans_iters=2)),
     "fp32_nb12": ("cfg1", dict(N=1536, Cq=6, Ck=24, r=2, block=128, kmeans_iters=2)),
+    # bf16 with a block size that is not a multiple of the 128-row tiles of the block-diagonal kernels
+    "bf16_block96": ("cfg2", dict(N=768, Hq=2, Hkv=1, Cq=5, Ck=19, r=3, k2=2, block=96, kmeans_iters=2)),
 }
 
 
