@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--balanced-assign", action="store_true",
                     help="final assignment under the per-block cap 4 block / C of App. C (MUSE_FLAG_BALANCED_ASSIGN); "
                          "a variant, named in config.step")
+    ap.add_argument("--k2", type=int, default=-1,
+                    help="override the workload's k2 (blocks retrieved per retrieved cluster; 0 = every preceding block)")
     ap.add_argument("--serial-streams", action="store_true",
                     help="run every stage on one stream (as the per-kernel timing pass does): for kernel profiles")
     ap.add_argument("--ws-gib", type=float, default=0.0, help="cap of the backward workspace (0 = all heads at once)")
@@ -116,6 +118,9 @@ def main():
         sys.exit(1)
     mb.load()
     w = CONFIGS[a.workload]
+    if a.k2 >= 0:
+        import dataclasses
+        w = dataclasses.replace(w, k2=a.k2)
     d = generate(w, need_dO=True)
     p = mb.params_for(w, flags=mb.FLAG_KEEP_FWD_STATE | (mb.FLAG_FROZEN_WEIGHTS if a.frozen_weights else 0) |
                       (mb.FLAG_STREAMING_KMEANS if a.streaming_kmeans else 0) |
