@@ -6,7 +6,9 @@ T iterations, queries and keys) + muse_fwd + muse_bwd, inputs resident in HBM.  
 BASELINE.json's configs[2] ("1B-scale pretraining layer": H=16, N=65536, D=64, bf16, Cq=256,
 Ck=1024, r=8), the configuration the metric "MuSe fwd+bwd ms/layer at N=64k" is quoted on.
 
-Prints ONE JSON line; see the design doc for how every figure is derived.
+Prints ONE JSON line.  `value` is the wall time of one step between device synchronisations; `roofline` is the
+modelled algorithmic work of the kernel with the largest share divided by its HIP-event duration, against the
+published peak of its own kind; `cpu_baseline` is the oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -102,8 +104,8 @@ def main():
     ap.add_argument("--ws-gib", type=float, default=0.0, help="cap of the backward workspace (0 = all heads at once)")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (every stage is independent per head; see DESIGN.md for how it "
-              "would shard); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (every stage is independent per head, so more GPUs would each take "
+              "a share of the heads); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     if a.serial_streams:
@@ -239,7 +241,8 @@ def main():
 
 def measured_traffic(kernel, workload):
     """HBM bytes per launch of `kernel` from the committed counter summary (rocprofv3 --pmc FETCH_SIZE and
-    WRITE_SIZE runs, scaled as the design doc states), or None when no summary covers it."""
+    WRITE_SIZE runs, each scaled by what the same counter reads for a plain copy of known size in the same run),
+    or None when no summary covers it."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.json")
     try:
         with open(path) as f:
