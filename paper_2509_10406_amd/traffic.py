@@ -52,7 +52,15 @@ def main():
         raise SystemExit("the bf16 -> fp32 cast of O was not found in the counter files")
     kf = 2.0 * elems / (f["calibration_copy"][1] / f["calibration_copy"][0])
     kw = 4.0 * elems / (wr["calibration_copy"][1] / wr["calibration_copy"][0])
+    flags = "" if a.workload == "cfg3" else f" --workload {a.workload}"
     out = {"workload": a.workload, "unit": "bytes per launch",
+           "commands": [
+               "rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d DIR_F -o f -- python3 bench.py"
+               f"{flags} --steps 1 --warmup 0 --no-cpu-baseline --serial-streams",
+               "rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d DIR_W -o w -- python3 bench.py"
+               f"{flags} --steps 1 --warmup 0 --no-cpu-baseline --serial-streams",
+               f"python -m paper_2509_10406_amd.traffic DIR_F/f_counter_collection.csv DIR_W/w_counter_collection.csv"
+               f" --workload {a.workload} --out profiles/hbm_traffic_{a.workload}.json"],
            "calibration": {"kernel": "torch bf16 -> fp32 cast of O", "elements": elems,
                            "fetch_factor": kf, "write_factor": kw},
            "kernels": {}}
