@@ -298,29 +298,30 @@ __global__ void __launch_bounds__(256) k_update(const T* __restrict__ X, const i
   float acc[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-  // a row slot takes every slots-th spatial block and walks its members four at a time; the positions of the
-  // next four are requested together with the rows of these four (one round trip per four members)
+  // a row slot takes every slots-th spatial block and walks its members MPI at a time; the positions of the
+  // next MPI are requested together with the rows of these (one round trip per MPI members)
+  constexpr int MPI = 8;
   int count = 0;
   for (int b = slot; b < nb; b += slots) {
     const int lo = oh[b * C + j], hi = oh[b * C + j + 1];
     count += hi - lo;
     if (lo >= hi) continue;
-    int rown[4];
+    int rown[MPI];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) rown[u] = ph[lo + u < hi ? lo + u : hi - 1];
-    for (int p = lo; p < hi; p += 4) {
-      int row[4];
+    for (int u = 0; u < MPI; ++u) rown[u] = ph[lo + u < hi ? lo + u : hi - 1];
+    for (int p = lo; p < hi; p += MPI) {
+      int row[MPI];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < MPI; ++u) {
         row[u] = rown[u];
-        rown[u] = ph[p + 4 + u < hi ? p + 4 + u : hi - 1];
+        rown[u] = ph[p + MPI + u < hi ? p + MPI + u : hi - 1];
       }
       if constexpr (EPL == 8) {
-        uint4 v[4];
+        uint4 v[MPI];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(Xh + (size_t)row[u] * D + chunk * 8);
+        for (int u = 0; u < MPI; ++u) v[u] = *reinterpret_cast<const uint4*>(Xh + (size_t)row[u] * D + chunk * 8);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < MPI; ++u) {
           if (p + u >= hi) continue;
           const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
@@ -330,11 +331,11 @@ __global__ void __launch_bounds__(256) k_update(const T* __restrict__ X, const i
           }
         }
       } else {
-        float4 v[4];
+        float4 v[MPI];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(Xh + (size_t)row[u] * D + chunk * 4);
+        for (int u = 0; u < MPI; ++u) v[u] = *reinterpret_cast<const float4*>(Xh + (size_t)row[u] * D + chunk * 4);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < MPI; ++u) {
           if (p + u >= hi) continue;
           acc[0] += v[u].x; acc[1] += v[u].y; acc[2] += v[u].z; acc[3] += v[u].w;
         }
