@@ -300,7 +300,7 @@ __global__ void __launch_bounds__(256) k_update(const T* __restrict__ X, const i
   for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
   // a row slot takes every slots-th spatial block and walks its members MPI at a time; the positions of the
   // next MPI are requested together with the rows of these (one round trip per MPI members)
-  constexpr int MPI = 8;
+  constexpr int MPI = 16;
   int count = 0;
   for (int b = slot; b < nb; b += slots) {
     const int lo = oh[b * C + j], hi = oh[b * C + j + 1];
