@@ -13,17 +13,29 @@
  *     the caller; the library never allocates, frees or keeps them.  `ws` is a
  *     caller-owned device scratch buffer of `ws_bytes` bytes, 256-byte aligned;
  *     its required size comes from muse_workspace_bytes().  Its contents are
- *     undefined before and after a call.
+ *     undefined before and after a call (except under MUSE_FLAG_KEEP_FWD_STATE).
  *   - `p` is a HOST pointer.  `stream` is a hipStream_t passed as void* (NULL =
  *     default stream).  Work is enqueued on that stream; calls return without
- *     synchronising.  No global state; calls on different streams with different
- *     workspaces do not interfere.
+ *     synchronising (one exception: muse_bwd under MUSE_FLAG_KEEP_FWD_STATE, see there).
+ *   - Process state the library keeps: per device, one extra non-blocking stream and
+ *     three events, created on first use (see "Streams" below); per process, which
+ *     kernels have had their dynamic-LDS limit raised; the diagnostics of
+ *     muse_profile_*.  Nothing else survives a call.  Because the extra stream is
+ *     shared, ONE host thread at a time may issue calls on a device; calls that use
+ *     different workspaces may be queued on different streams back to back.
  *   - Layout: Q, O, dO, dQ are [B, Hq, N, D]; K, V, dK, dV are [B, Hkv, N, D];
  *     row-major, contiguous, element type given by p->dtype (fp32 or bf16).
  *     Hq % Hkv == 0; query head h uses kv head h / (Hq / Hkv) (GQA, Sec. 6).
- *   - Return value: MUSE_OK (0) or a negative MUSE_ERR_* code.  Arguments are
- *     validated on the host before anything is launched; a failed call has
- *     launched nothing.
+ *   - Index inputs are trusted: q_assign / k_assign entries must lie in [0, Cq) / [0, Ck),
+ *     init_idx entries in [0, N), and sel_clusters / sel_blocks must be what muse_fwd wrote
+ *     for the same inputs (entries < 0 are padding).  Other values are undefined behaviour.
+ *   - Return value: MUSE_OK (0) or a negative MUSE_ERR_* code.  Every check that
+ *     depends only on `p`, the pointers and ws_bytes is made on the host before
+ *     anything is launched: INVALID_ARG, UNSUPPORTED and WORKSPACE_TOO_SMALL mean
+ *     nothing was enqueued.  MUSE_ERR_HIP (a launch or runtime call failed) can
+ *     come after earlier kernels of the call were enqueued; the library's extra
+ *     stream has then still been joined to `stream`, so waiting for `stream`
+ *     waits for everything the call started.
  */
 #ifndef MUSE_H_
 #define MUSE_H_
@@ -40,7 +52,9 @@ enum {
   MUSE_ERR_INVALID_ARG = -1,        /* NULL pointer, non-positive size, N % block != 0, ... */
   MUSE_ERR_UNSUPPORTED = -2,        /* non-causal, D not in {64,128}, sizes beyond the kernels' limits */
   MUSE_ERR_WORKSPACE_TOO_SMALL = -3,
-  MUSE_ERR_HIP = -4                 /* a HIP call or launch failed */
+  MUSE_ERR_HIP = -4,                /* a HIP call or launch failed */
+  MUSE_ERR_STATE = -5               /* MUSE_FLAG_KEEP_FWD_STATE: the workspace does not hold the forward state
+                                       of these params (another workspace, other params, or overwritten) */
 };
 
 enum { MUSE_DTYPE_FP32 = 0, MUSE_DTYPE_BF16 = 1 };
@@ -48,7 +62,11 @@ enum { MUSE_DTYPE_FP32 = 0, MUSE_DTYPE_BF16 = 1 };
  * the summaries there; muse_bwd called with the same flag, the same params and the SAME, untouched
  * workspace reuses them instead of recomputing (the usual save-for-backward of a training step).  Needs a
  * workspace that holds all heads at once (the `preferred` size of MUSE_WS_BWD), else
- * MUSE_ERR_WORKSPACE_TOO_SMALL. */
+ * MUSE_ERR_WORKSPACE_TOO_SMALL.  muse_fwd stamps the head of the workspace (a hash of the params, the
+ * workspace address) after its last kernel; every other entry point that is handed a workspace clears the
+ * stamp.  muse_bwd reads the stamp back before it launches anything -- this waits for the work queued on
+ * `stream` so far, the one place where the library synchronises -- and returns MUSE_ERR_STATE if it does not
+ * match.  The stamp cannot see a caller who overwrites the middle of the workspace. */
 enum { MUSE_FLAG_KEEP_FWD_STATE = 1,
 /* MUSE_FLAG_FROZEN_WEIGHTS (muse_bwd only; App. C "Aggregation Weight Gradient Flow", the non-differentiable
  * variant): the tilted aggregation weights e_m / S of every summary and its log-mass mu-bar are constants of

@@ -198,7 +198,11 @@ def summaries(p: MuseParams, K, V, qc, ak, i):
 
 def muse_fwd(p: MuseParams, Q, K, V, qc, aq, ak, rows=None, sel=None, weight_keys=None):
     """MuSe forward.  sel = (selc [N,r], selb [N,r,k2e]) teacher-forces the selections.
-    weight_keys: keys used inside the tilted weights of the summaries instead of K (for the pins)."""
+    weight_keys: keys used inside the tilted weights of the summaries instead of K (for the pins).
+    margin_c / margin_b [N]: relative gap between the last selected and the best left-out cluster score /
+    the smallest such gap over the row's block selections (+inf when nothing is left out).  With sel given
+    they are the slack of THAT selection by the same formula: negative when a better candidate was left out,
+    -inf when the selection is malformed (out of range, repeated, not a candidate, too few entries)."""
     Q, Qp = _d(Q); K, Kp = _d(K); V, Vp = _d(V); qc, qp = _d(qc)
     Kw = None if weight_keys is None else np.ascontiguousarray(weight_keys, dtype=np.float64)
     aq, aqp = _i(aq); ak, akp = _i(ak)

@@ -631,6 +631,36 @@ static int top_select(int n, const double* val, const int* id, int want, int* ou
   return got;
 }
 
+/* Slack of a GIVEN selection chosen[0..nslots) (entries < 0 are padding) among the candidates
+ * val[0..n) (a candidate's id is its index; -inf = not a candidate): (lowest chosen value) -
+ * (highest value left out), relative to max(1,|a|,|b|) as in top_select.  For the selection that
+ * top_select takes it equals its gap (>= 0); a negative slack says a better candidate was left
+ * out.  +inf when nothing is left out; -inf when the selection is malformed: an entry out of
+ * range, not a candidate or chosen twice, or fewer entries than min(want, candidates). */
+static double selection_slack(int n, const double* val, int want, const int32_t* chosen,
+                              int nslots) {
+  char* used = (char*)calloc((size_t)n + 1, 1);
+  int got = 0, cand = 0, bad = 0;
+  double low = INFINITY, next = -INFINITY;
+  for (int t = 0; t < nslots; ++t) {
+    int c = chosen[t];
+    if (c < 0) continue;
+    if (c >= n || used[c] || val[c] == -INFINITY) { bad = 1; break; }
+    used[c] = 1;
+    ++got;
+    if (val[c] < low) low = val[c];
+  }
+  for (int t = 0; t < n; ++t) {
+    if (val[t] == -INFINITY) continue;
+    ++cand;
+    if (!used[t] && val[t] > next) next = val[t];
+  }
+  free(used);
+  if (bad || got != (want < cand ? want : cand)) return -INFINITY;
+  if (got == 0 || next == -INFINITY) return INFINITY;
+  return (low - next) / fmax(1.0, fmax(fabs(low), fabs(next)));
+}
+
 typedef struct {
   const omuse_params* p;
   const double *Q, *K, *V;
@@ -641,7 +671,9 @@ typedef struct {
 
 /* Builds the virtual keys of query n.  When sel_given, the selections in
  * selc[r] / selb[r*k2e] are used as they are (entries < 0 ignored); otherwise
- * they are computed (Eq. 7 and the block selection) and written there. */
+ * they are computed (Eq. 7 and the block selection) and written there.
+ * margin_c / margin_b (may be NULL): the gap of the cluster selection / the smallest gap of
+ * the block selections (top_select); for given selections their slack (selection_slack). */
 static int build_vkeys(const ctx_t* c, int n, int sel_given, int32_t* selc, int32_t* selb,
                        double* margin_c, double* margin_b, double* qs, double* qt,
                        vkey_t* vk, double* tmpv, int* tmpi, int* tmpo) {
@@ -671,6 +703,8 @@ static int build_vkeys(const ctx_t* c, int n, int sel_given, int32_t* selc, int3
     if (!sel_given) {
       int got = top_select(Ck, tmpv, tmpi, r, tmpo, margin_c);
       for (int t = 0; t < got; ++t) selc[t] = tmpo[t];
+    } else if (margin_c) {
+      *margin_c = selection_slack(Ck, tmpv, r, selc, r);
     }
     /* component 1: non-retrieved clusters, accumulated summaries */
     for (int j = 0; j < Ck; ++j) {
@@ -697,6 +731,9 @@ static int build_vkeys(const ctx_t* c, int n, int sel_given, int32_t* selc, int3
         int got = top_select(b, bv, bi, want, tmpo, &gap);
         for (int u = 0; u < got; ++u) selb[t * k2e + u] = tmpo[u];
         if (margin_b && gap < *margin_b) *margin_b = gap;
+      } else if (margin_b) {
+        double gap = selection_slack(b, bv, p->k2 == 0 ? b : p->k2, selb + t * k2e, k2e);
+        if (gap < *margin_b) *margin_b = gap;
       }
       for (int bp = 0; bp < b; ++bp) {
         if (bv[bp] == -INFINITY) continue;

@@ -134,7 +134,12 @@ def workspace(p: Params, which: int, device="cuda", limit_bytes: int | None = No
     """A cached uint8 device buffer of the preferred size (capped by limit_bytes, never below the minimum)."""
     mn, pref = muse_workspace_bytes(p, which)
     size = pref if limit_bytes is None else max(mn, min(pref, limit_bytes))
-    key = (str(device), which)
+    # under MUSE_FLAG_KEEP_FWD_STATE the backward must be handed the very buffer the forward filled
+    shared = (p.flags & FLAG_KEEP_FWD_STATE) and which in (WS_FWD, WS_BWD)
+    device = torch.device(device)
+    if device.index is None:   # "cuda" and "cuda:<current>" are one device: one buffer
+        device = torch.device(device.type, torch.cuda.current_device())
+    key = (str(device), "fwd+bwd" if shared else which)
     buf = _ws_cache.get(key)
     if buf is None or buf.numel() < size:
         _ws_cache.pop(key, None)

@@ -12,6 +12,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
 #define MUSE_WAVE 64
+#define MUSE_MAX_CLUSTERS 2048  // largest Cq / Ck the host accepts (LDS tables of the bucketing and chain kernels)
 #define MUSE_NEG_INF (-__builtin_huge_valf())
 
 __device__ __forceinline__ float bf16_bits_to_f32(bf16_t h) {

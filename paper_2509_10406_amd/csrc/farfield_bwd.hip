@@ -1207,7 +1207,6 @@ int run_bwd_chunk(const MuseDims& d, const T* Q, const T* dO, const float* qc, c
                      d.scale); }
   { MuseProf prof_("k_cell_grads", st); hipLaunchKernelGGL((k_cell_grads<T, D>), dim3(W, d.Cq, hn), dim3(256), 0, st, w.s_mu, w.A_mu, w.g_A_c,
                      (const T*)w.g_A_k, (const T*)w.g_A_v, w.g_s_c, (T*)w.g_s_k, (T*)w.g_s_v, d.nb, d.Cq, d.Ck); }
-  if (d.r > 0 && d.Ck > kMaxCk) return MUSE_ERR_UNSUPPORTED;
   if (d.r > 0)
     { MuseProf prof_("k_chain_grads", st); hipLaunchKernelGGL((k_chain_grads<T, D>), dim3(d.Cq, hn), dim3(256), 0, st, Q, dO, qc, w.s_mu, w.s_k,
                        (const T*)w.s_v, w.perm_q, w.off_q, LSE, w.delta, w.slotinfo, w.g_s_c, (T*)w.g_s_k, (T*)w.g_s_v, h0, d.N,
@@ -1240,9 +1239,17 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
   MuseAux& ax = muse_aux_stream();
   const bool two = ax.state == 1 && !muse_profiling();
   hipStream_t sb = two ? ax.s : st;
+  // on every way out after the fork, the caller's stream waits for what the second stream was given
+  struct AuxJoin {
+    MuseAux& ax; hipStream_t st, sb; bool armed;
+    ~AuxJoin() {
+      if (armed && hipEventRecord(ax.join, sb) == hipSuccess) (void)hipStreamWaitEvent(st, ax.join, 0);
+    }
+  } guard{ax, st, sb, false};
   if (two) {
     MUSE_HIP_CHECK(hipEventRecord(ax.fork, st));
     MUSE_HIP_CHECK(hipStreamWaitEvent(sb, ax.fork, 0));
+    guard.armed = true;
   }
   if ((rc = muse_launch_fill(w.dQacc, nq * D, 0.f, sb))) return rc;
   if ((rc = muse_launch_fill(w.dKacc, nk * D, 0.f, sb))) return rc;
@@ -1303,6 +1310,7 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
   }
   if (split) MUSE_HIP_CHECK(hipEventRecord(ax.join, sb));
   if (two) MUSE_HIP_CHECK(hipStreamWaitEvent(st, ax.join, 0));
+  guard.armed = false;
   {
     dim3 g((unsigned)(((size_t)N * (D / 4) + 255) / 256), HK);
     { MuseProf prof_("k_scatter_rows", st); hipLaunchKernelGGL(k_scatter_rows, g, dim3(256), 0, st, w.dKs, w.perm_k, w.dKacc, N, D); }

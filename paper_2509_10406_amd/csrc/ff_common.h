@@ -193,7 +193,8 @@ __device__ __forceinline__ bf16x8_t cvt8(const float* __restrict__ p) {
 }
 
 
-constexpr int kMaxCk = 2304;  // key clusters a kernel can index in LDS (the bucketing kernel's own limit is lower)
+constexpr int kMaxCk = 2304;  // key clusters a kernel can index in LDS
+static_assert(kMaxCk >= MUSE_MAX_CLUSTERS, "the host accepts more clusters than the kernels index");
 constexpr int kHitSeg = 8;  // query-range slices per (pair, head) when the hit lists are built
 
 struct FFWorkspace {

@@ -214,7 +214,8 @@ __global__ void __launch_bounds__(1024) k_bucket(const int32_t* __restrict__ ass
 
   for (int t = threadIdx.x; t < 17 * C; t += 1024) smem[t] = 0;
   __syncthreads();
-  for (int i = lo + lane; i < hi; i += 64) atomicAdd(&hist[wave * C + a[i]], 1u);
+  // entries outside [0, C) are the caller's error; clamped here so that they cannot index outside the histograms
+  for (int i = lo + lane; i < hi; i += 64) atomicAdd(&hist[wave * C + min(max(a[i], 0), C - 1)], 1u);
   __syncthreads();
   // per cluster: exclusive prefix over the waves, total per cluster
   for (int c = threadIdx.x; c < C; c += 1024) {
@@ -260,7 +261,7 @@ __global__ void __launch_bounds__(1024) k_bucket(const int32_t* __restrict__ ass
   for (int i0 = lo; i0 < hi; i0 += 64) {
     int i = i0 + lane;
     bool act = i < hi;
-    int key = act ? a[i] : 0;
+    int key = act ? min(max(a[i], 0), C - 1) : 0;
     unsigned long long m = __ballot(act);
 #pragma unroll
     for (int bit = 0; bit < 12; ++bit) {
@@ -913,8 +914,9 @@ size_t muse_cluster_ws_bytes(const MuseDims& d) {
 
 int muse_launch_bucket(const int32_t* assign, int heads, int N, int Bs, int C, int32_t* perm,
                        int32_t* off, hipStream_t st) {
+  static_assert((size_t)17 * MUSE_MAX_CLUSTERS * sizeof(uint32_t) <= 150 * 1024, "histograms of the largest accepted C fit the LDS");
   size_t lds = (size_t)17 * C * sizeof(uint32_t);
-  if (lds > 150 * 1024) return MUSE_ERR_UNSUPPORTED;
+  if (C > MUSE_MAX_CLUSTERS) return MUSE_ERR_UNSUPPORTED;  // the entry points have checked this already
   static bool attr_set = false;
   if (!attr_set) {
     MUSE_HIP_CHECK(hipFuncSetAttribute((const void*)k_bucket, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));

@@ -88,13 +88,66 @@ int make_dims(const muse_params* p, bool full, MuseDims* d) {
   if (p->block < 0 || Bs < 1 || p->N % Bs) return MUSE_ERR_INVALID_ARG;
   if (p->Cq < 1 || p->Ck < 1 || p->Cq > p->N || p->Ck > p->N) return MUSE_ERR_INVALID_ARG;
   if (p->r < 0 || p->r > p->Ck || p->k2 < 0 || p->kmeans_iters < 0) return MUSE_ERR_INVALID_ARG;
-  if (p->Cq > 2048 || p->Ck > 2048 || p->r > 32 || p->N / Bs > 16 || Bs > 16384) return MUSE_ERR_UNSUPPORTED;
+  if (p->Cq > MUSE_MAX_CLUSTERS || p->Ck > MUSE_MAX_CLUSTERS || p->r > 32 || p->N / Bs > 16 || Bs > 16384) return MUSE_ERR_UNSUPPORTED;
   d->Bs = Bs; d->nb = p->N / Bs; d->Cq = p->Cq; d->Ck = p->Ck;
   d->r = p->r;
   d->k2 = p->k2; d->T = p->kmeans_iters;
   d->k2e = p->k2 > 0 ? p->k2 : (d->nb > 1 ? d->nb - 1 : 1);
   if (d->k2e > 16) return MUSE_ERR_UNSUPPORTED;
   return MUSE_OK;
+}
+
+// ---- stamp at the head of every workspace (MUSE_FLAG_KEEP_FWD_STATE) -------------------------
+// The first kTagBytes of a workspace belong to the stamp; every layout starts behind it.
+constexpr size_t kTagBytes = 256;
+constexpr uint64_t kTagMagic = 0x4d755365a7c3f10bull;
+
+__global__ void k_stamp(uint64_t* tag, uint64_t a, uint64_t b, uint64_t c, uint64_t d) {
+  if (threadIdx.x == 0) { tag[0] = a; tag[1] = b; tag[2] = c; tag[3] = d; }
+}
+
+// what muse_bwd must find: the params that shape the forward state (the flags that only the backward reads
+// left out), folded FNV-1a style
+uint64_t params_hash(const muse_params* p) {
+  muse_params q = *p;
+  q.flags &= ~(uint32_t)MUSE_FLAG_FROZEN_WEIGHTS;
+  const int32_t f[] = {q.B, q.Hq, q.Hkv, q.N, q.D, q.Cq, q.Ck, q.r, q.k2, q.block, q.dtype, q.causal, (int32_t)q.flags};
+  uint64_t h = 0xcbf29ce484222325ull;
+  auto mix = [&](uint32_t v) { for (int i = 0; i < 4; ++i) { h ^= (v >> (8 * i)) & 0xffu; h *= 0x100000001b3ull; } };
+  for (int32_t v : f) mix((uint32_t)v);
+  uint32_t sc; memcpy(&sc, &q.scale, 4);
+  mix(sc);
+  return h;
+}
+
+int stamp_clear(void* ws, hipStream_t st) {
+  hipLaunchKernelGGL(k_stamp, dim3(1), dim3(64), 0, st, (uint64_t*)ws, 0ull, 0ull, 0ull, 0ull);
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
+int stamp_write(void* ws, size_t ws_bytes, const muse_params* p, hipStream_t st) {
+  hipLaunchKernelGGL(k_stamp, dim3(1), dim3(64), 0, st, (uint64_t*)ws, kTagMagic, params_hash(p),
+                     (uint64_t)(uintptr_t)ws, (uint64_t)ws_bytes);
+  MUSE_LAUNCH_CHECK();
+  return MUSE_OK;
+}
+// waits for the work queued on st so far (the stamp is the last thing muse_fwd enqueues)
+int stamp_check(void* ws, size_t ws_bytes, const muse_params* p, hipStream_t st) {
+  uint64_t got[4] = {0, 0, 0, 0};
+  MUSE_HIP_CHECK(hipMemcpyAsync(got, ws, sizeof(got), hipMemcpyDeviceToHost, st));
+  MUSE_HIP_CHECK(hipStreamSynchronize(st));
+  // the workspace may be larger than at the forward call as long as it starts at the same address: the layout
+  // of the kept state depends on the params only (all heads in one chunk)
+  if (got[0] != kTagMagic || got[1] != params_hash(p) || got[2] != (uint64_t)(uintptr_t)ws || got[3] > (uint64_t)ws_bytes)
+    return MUSE_ERR_STATE;
+  return MUSE_OK;
+}
+
+// App. C "Balanced Assignment": cap = floor(4 block / C) rows of a block per cluster must exist and leave room
+// for every row of the block
+bool balanced_cap_ok(const MuseDims& d, int C) {
+  const long long cap = (4LL * d.Bs) / C;
+  return cap >= 1 && cap * C >= d.Bs;
 }
 
 size_t exact_bwd_bytes(const MuseDims& d) {
@@ -115,6 +168,7 @@ const char* muse_strerror(int code) {
     case MUSE_ERR_UNSUPPORTED: return "unsupported configuration";
     case MUSE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case MUSE_ERR_HIP: return "HIP runtime error";
+    case MUSE_ERR_STATE: return "workspace does not hold the forward state of these params";
     default: return "unknown error code";
   }
 }
@@ -128,7 +182,7 @@ int muse_workspace_bytes(const muse_params* p, int which, size_t* min_bytes, siz
   size_t mn = 0, pref = 0;
   switch (which) {
     case MUSE_WS_CLUSTER: mn = pref = 2 * muse_cluster_ws_bytes(d); break;  // queries and keys side by side
-    case MUSE_WS_EXACT_FWD: mn = pref = 256; break;
+    case MUSE_WS_EXACT_FWD: mn = pref = 0; break;  // unused: the stamp slot alone
     case MUSE_WS_EXACT_BWD: mn = pref = exact_bwd_bytes(d); break;
     case MUSE_WS_FWD:
     case MUSE_WS_BWD: {
@@ -139,8 +193,8 @@ int muse_workspace_bytes(const muse_params* p, int which, size_t* min_bytes, siz
     }
     default: return MUSE_ERR_INVALID_ARG;
   }
-  *min_bytes = mn;
-  if (preferred) *preferred = pref;
+  *min_bytes = mn + kTagBytes;
+  if (preferred) *preferred = pref + kTagBytes;
   return MUSE_OK;
 }
 
@@ -154,8 +208,14 @@ int muse_cluster(const muse_params* p, const void* Q, const void* K, const int32
   if (Q && (!q_centroids || !q_assign)) return MUSE_ERR_INVALID_ARG;
   if (K && (!k_centroids || !k_assign)) return MUSE_ERR_INVALID_ARG;
   if (!ws) return MUSE_ERR_INVALID_ARG;
-  if (ws_bytes < 2 * muse_cluster_ws_bytes(d)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  if (d.balanced) {  // the cap of App. C must leave room for every row of a block
+    if (Q && !balanced_cap_ok(d, d.Cq)) return MUSE_ERR_UNSUPPORTED;
+    if (K && !balanced_cap_ok(d, d.Ck)) return MUSE_ERR_UNSUPPORTED;
+  }
+  if (ws_bytes < kTagBytes + 2 * muse_cluster_ws_bytes(d)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t st = (hipStream_t)stream;
+  if ((rc = stamp_clear(ws, st))) return rc;
+  char* w0 = (char*)ws + kTagBytes;
   // the two problems are independent: the keys go to the second stream (own half of the workspace)
   MuseAux& ax = muse_aux_stream();
   const bool two = Q && K && ax.state == 1 && !muse_profiling();
@@ -164,17 +224,13 @@ int muse_cluster(const muse_params* p, const void* Q, const void* K, const int32
     MUSE_HIP_CHECK(hipEventRecord(ax.fork, st));
     MUSE_HIP_CHECK(hipStreamWaitEvent(sk, ax.fork, 0));
   }
-  if (K) {
-    rc = muse_launch_cluster(d, K, d.Hkv, d.Ck, k_init_idx, k_centroids, k_assign, nullptr, nullptr, (char*)ws + muse_cluster_ws_bytes(d), sk);
-    if (rc) return rc;
-  }
-  if (two) MUSE_HIP_CHECK(hipEventRecord(ax.join, sk));
-  if (Q) {
-    rc = muse_launch_cluster(d, Q, d.Hq, d.Cq, q_init_idx, q_centroids, q_assign, nullptr, nullptr, ws, st);
-    if (rc) return rc;
-  }
-  if (two) MUSE_HIP_CHECK(hipStreamWaitEvent(st, ax.join, 0));
-  return MUSE_OK;
+  int rck = MUSE_OK, rcq = MUSE_OK;
+  if (K) rck = muse_launch_cluster(d, K, d.Hkv, d.Ck, k_init_idx, k_centroids, k_assign, nullptr, nullptr, w0 + muse_cluster_ws_bytes(d), sk);
+  // whatever happened, the caller's stream waits for what the second stream was given
+  if (two && (hipEventRecord(ax.join, sk) != hipSuccess || hipStreamWaitEvent(st, ax.join, 0) != hipSuccess)) return MUSE_ERR_HIP;
+  if (rck) return rck;
+  if (Q) rcq = muse_launch_cluster(d, Q, d.Hq, d.Cq, q_init_idx, q_centroids, q_assign, nullptr, nullptr, w0, st);
+  return rcq;
 }
 
 int muse_kmeans_stream(const muse_params* p, int side, const void* X, const int32_t* init_idx, float* centroids,
@@ -183,10 +239,11 @@ int muse_kmeans_stream(const muse_params* p, int side, const void* X, const int3
   int rc = make_dims(p, true, &d);
   if (rc) return rc;
   if ((side != 0 && side != 1) || !X || !centroids || !ws) return MUSE_ERR_INVALID_ARG;
-  if (ws_bytes < muse_cluster_ws_bytes(d)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  if (ws_bytes < kTagBytes + muse_cluster_ws_bytes(d)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
   d.streaming = true;
+  if ((rc = stamp_clear(ws, (hipStream_t)stream))) return rc;
   return muse_launch_cluster(d, X, side ? d.Hkv : d.Hq, side ? d.Ck : d.Cq, init_idx, centroids, nullptr, stream_assign,
-                             counts, ws, (hipStream_t)stream);
+                             counts, (char*)ws + kTagBytes, (hipStream_t)stream);
 }
 
 int muse_fwd(const muse_params* p, const void* Q, const void* K, const void* V, const float* q_centroids,
@@ -199,9 +256,13 @@ int muse_fwd(const muse_params* p, const void* Q, const void* K, const void* V, 
   if (d.r > 0 && (!sel_clusters || !sel_blocks)) return MUSE_ERR_INVALID_ARG;
   size_t need = d.keep_state ? muse_farfield_fixed_bytes(d, true) + muse_farfield_ws_bytes(d, true, d.B * d.Hq)
                              : muse_farfield_fixed_bytes(d, false) + muse_farfield_ws_bytes(d, false, 1);
-  if (ws_bytes < need) return MUSE_ERR_WORKSPACE_TOO_SMALL;
-  return muse_run_fwd(d, Q, K, V, q_centroids, q_assign, k_assign, O, LSE, sel_clusters, sel_blocks, ws, ws_bytes,
-                      (hipStream_t)stream);
+  if (ws_bytes < kTagBytes + need) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)stream;
+  if ((rc = stamp_clear(ws, st))) return rc;
+  rc = muse_run_fwd(d, Q, K, V, q_centroids, q_assign, k_assign, O, LSE, sel_clusters, sel_blocks, (char*)ws + kTagBytes,
+                    ws_bytes - kTagBytes, st);
+  if (rc == MUSE_OK && d.keep_state) rc = stamp_write(ws, ws_bytes, p, st);
+  return rc;
 }
 
 int muse_bwd(const muse_params* p, const void* Q, const void* K, const void* V, const void* O, const float* LSE,
@@ -215,9 +276,15 @@ int muse_bwd(const muse_params* p, const void* Q, const void* K, const void* V, 
     return MUSE_ERR_INVALID_ARG;
   if (d.r > 0 && (!sel_clusters || !sel_blocks)) return MUSE_ERR_INVALID_ARG;
   size_t need = muse_farfield_fixed_bytes(d, true) + muse_farfield_ws_bytes(d, true, d.keep_state ? d.B * d.Hq : 1);
-  if (ws_bytes < need) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  if (ws_bytes < kTagBytes + need) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)stream;
+  if (d.keep_state) {
+    if ((rc = stamp_check(ws, ws_bytes, p, st))) return rc;
+  } else if ((rc = stamp_clear(ws, st))) {
+    return rc;
+  }
   return muse_run_bwd(d, Q, K, V, O, LSE, dO, q_centroids, q_assign, k_assign, sel_clusters, sel_blocks, dQ, dK, dV,
-                      ws, ws_bytes, (hipStream_t)stream);
+                      (char*)ws + kTagBytes, ws_bytes - kTagBytes, st);
 }
 
 int exact_attn_fwd(const muse_params* p, const void* Q, const void* K, const void* V, void* O, float* LSE,
@@ -237,10 +304,11 @@ int exact_attn_bwd(const muse_params* p, const void* Q, const void* K, const voi
   int rc = make_dims(p, false, &d);
   if (rc) return rc;
   if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV || !ws) return MUSE_ERR_INVALID_ARG;
-  if (ws_bytes < exact_bwd_bytes(d)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
+  if (ws_bytes < kTagBytes + exact_bwd_bytes(d)) return MUSE_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t st = (hipStream_t)stream;
+  if ((rc = stamp_clear(ws, st))) return rc;
   size_t q = (size_t)d.B * d.Hq * d.N, k = (size_t)d.B * d.Hkv * d.N;
-  char* w = (char*)ws;
+  char* w = (char*)ws + kTagBytes;
   float* delta = (float*)w; w += al(q * 4);
   float *aq, *ak, *av;
   bool direct = d.grad_dtype == MUSE_DTYPE_FP32;

@@ -16,3 +16,21 @@ def oracle():
 
     o.build()
     return o
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Lists the worst error of every kind of comparison the parity tests made (bf16 bound: 2e-2 absolute)."""
+    try:
+        from tests.util import ERRORS
+    except Exception:
+        return
+    if not ERRORS:
+        return
+    worst = {}
+    for what, e, mx in ERRORS:
+        kind = " ".join(w for w in what.split() if not w.isdigit() and w != "head")
+        if kind not in worst or e > worst[kind][0]:
+            worst[kind] = (e, mx)
+    terminalreporter.write_line("parity errors (max abs err, max|want|), worst per comparison kind:")
+    for kind in sorted(worst):
+        terminalreporter.write_line(f"  {kind:40s} {worst[kind][0]:.3e}  {worst[kind][1]:.3g}")

@@ -6,7 +6,6 @@ oracle's relative score margin exceeds 1e-5; outputs and gradients are then comp
 oracle evaluated at the GPU's own selections (identical to the oracle's except at sub-margin ties).
 """
 import dataclasses
-from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
@@ -15,7 +14,7 @@ import torch
 import oracle as orc
 from paper_2509_10406_amd import binding as mb
 from paper_2509_10406_amd.inputs import generate, small
-from tests.util import assert_close, dev, f64
+from tests.util import assert_close, blocks_by_cluster, dev, f64, oracle_head, segment_sizes
 
 pytestmark = pytest.mark.gpu
 MARGIN = 1e-5
@@ -35,6 +34,12 @@ CASES = {
     "fp32_nb12": ("cfg1", dict(N=1536, Cq=6, Ck=24, r=2, block=128, kmeans_iters=2)),
     # bf16 with a block size that is not a multiple of the 128-row tiles of the block-diagonal kernels
     "bf16_block96": ("cfg2", dict(N=768, Hq=2, Hkv=1, Cq=5, Ck=19, r=3, k2=2, block=96, kmeans_iters=2)),
+    # the ratio of Sec. 3.3 "Complexity" (clusters = N / 512: about 64 keys per retrieved pair), where the pair
+    # kernels walk several 32-key tiles per pair, and query groups of several staging passes / tiles
+    "bf16_pairs64": ("cfg2", dict(N=4096, Hq=2, Hkv=1, Cq=4, Ck=8, r=2, block=512, kmeans_iters=2)),
+    "bf16_pairs64_k2all": ("cfg2", dict(N=4096, Hq=2, Hkv=1, Cq=4, Ck=8, r=2, k2=0, block=512, kmeans_iters=2)),
+    "bf16_groups200": ("cfg2", dict(N=4096, Hq=1, Hkv=1, Cq=2, Ck=12, r=3, k2=2, block=512, kmeans_iters=2)),
+    "bf16_d128_pairs40": ("cfg5", dict(N=2048, Hq=2, Hkv=1, Cq=3, Ck=6, r=2, block=256, kmeans_iters=2)),
 }
 
 
@@ -58,63 +63,90 @@ def as_sets(sel):
     return s
 
 
-def run_case(name, with_bwd, frozen_weights=False):
+# What a case must reach, asserted inside the run so that a change of generator or sizes cannot silently take
+# it off the code path it is there for: pair_keys = keys of the largest RETRIEVED (cluster, block) pair (the
+# pair kernels tile keys by 32); group = queries of the largest (block, query cluster) group (the tile kernels
+# take 32 per wave, the cell-gradient kernel stages 96 per pass at D = 64 and 32 at D = 128).
+REACH = {
+    "bf16_pairs64": dict(pair_keys=65, group=97),
+    "bf16_pairs64_k2all": dict(pair_keys=65, group=97),
+    "bf16_groups200": dict(pair_keys=33, group=193),
+    "bf16_d128_pairs40": dict(pair_keys=33, group=65),
+}
+
+
+def check_selections(name, h, w, op, got_c, got_b, free, forced):
+    """Retrieved clusters and blocks of one head against the oracle: equal as sets where the oracle's margin
+    allows a comparison; everywhere, the library's own choice must be a valid one (every chosen candidate
+    scores within the margin of the best one left out: slack >= -MARGIN by the oracle's fp64 scores)."""
+    far = np.arange(w.N) >= w.Bs
+    safe_c = free["margin_c"] > MARGIN
+    assert safe_c.mean() > 0.98, safe_c.mean()
+    np.testing.assert_array_equal(as_sets(got_c)[safe_c], as_sets(free["selc"])[safe_c],
+                                  err_msg=f"{name} head {h}: retrieved clusters")
+    assert (forced["margin_c"] >= -MARGIN).all(), (name, h, "cluster choice off by", forced["margin_c"].min())
+    assert (forced["margin_b"] >= -MARGIN).all(), (name, h, "block choice off by", forced["margin_b"].min())
+    # blocks of every retrieved cluster, whatever the slot order, where both margins are safe
+    safe = safe_c & (free["margin_b"] > MARGIN)
+    assert not far.any() or safe[far].mean() > 0.95, safe[far].mean()
+    np.testing.assert_array_equal(blocks_by_cluster(got_c, got_b)[safe],
+                                  blocks_by_cluster(free["selc"], free["selb"])[safe],
+                                  err_msg=f"{name} head {h}: retrieved blocks")
+    # export order: descending score, so where the oracle's scores are well separated the slots agree too
+    assert (got_c[~far] == -1).all() and (got_b[~far] == -1).all()
+
+
+def run_case(name, with_bwd, frozen_weights=False, flags=0):
     base, kw = CASES[name]
     w = small(base, **kw)
     d = generate(w, need_dO=True)
-    p = mb.params_for(w, flags=mb.FLAG_FROZEN_WEIGHTS if frozen_weights else 0)
+    p = mb.params_for(w, flags=(mb.FLAG_FROZEN_WEIGHTS if frozen_weights else 0) | flags)
     qc, aq, ak = oracle_clustering(w, d, p)
     Q, K, V, dO = (dev(d[x], p) for x in ("Q", "K", "V", "dO"))
     qc_d, aq_d, ak_d = torch.tensor(qc).cuda(), torch.tensor(aq).cuda(), torch.tensor(ak).cuda()
-    O, LSE, selc, selb = mb.muse_fwd(p, Q, K, V, qc_d, aq_d, ak_d)
+    ws = None
+    if flags & mb.FLAG_KEEP_FWD_STATE:
+        ws = torch.empty(mb.muse_workspace_bytes(p, mb.WS_BWD)[1], dtype=torch.uint8, device="cuda")
+    O, LSE, selc, selb = mb.muse_fwd(p, Q, K, V, qc_d, aq_d, ak_d, ws=ws)
     if with_bwd:
-        dQ, dK, dV = mb.muse_bwd(p, Q, K, V, O, LSE, dO, qc_d, aq_d, ak_d, selc, selb)
+        dQ, dK, dV = mb.muse_bwd(p, Q, K, V, O, LSE, dO, qc_d, aq_d, ak_d, selc, selb, ws=ws)
     torch.cuda.synchronize()
     op = orc.MuseParams(w.N, w.D, w.Bs, w.Cq, w.Ck, w.r, w.k2, p.eff_scale, frozen_weights=frozen_weights)
     G = w.Hq // w.Hkv
     selc_h, selb_h = selc.cpu().numpy()[0], selb.cpu().numpy()[0]
-
-    def head(h):
+    wantK = np.zeros((w.Hkv, w.N, w.D)); wantV = np.zeros((w.Hkv, w.N, w.D))
+    reach = dict(pair_keys=0, group=0)
+    for h in range(w.Hq):
         q, k, v, g = (f64(x) for x in (Q[0, h], K[0, h // G], V[0, h // G], dO[0, h]))
-        free = orc.muse_fwd(op, q, k, v, qc[0, h], aq[0, h], ak[0, h // G])
         sc = selc_h[h][:, : w.r]
         sb = selb_h[h][:, : w.r].reshape(w.N, w.r, op.k2e) if w.r else selb_h[h][:, :0].reshape(w.N, 0, op.k2e)
-        forced = orc.muse_fwd(op, q, k, v, qc[0, h], aq[0, h], ak[0, h // G], sel=(sc, sb))
-        grads = None
-        if with_bwd:
-            grads = orc.muse_bwd(op, q, k, v, qc[0, h], aq[0, h], ak[0, h // G], forced["O"], forced["LSE"], g, sc, sb)
-        return free, forced, grads
-
-    with ThreadPoolExecutor(8) as ex:
-        res = list(ex.map(head, range(w.Hq)))
-    wantK = np.zeros((w.Hkv, w.N, w.D)); wantV = np.zeros((w.Hkv, w.N, w.D))
-    for h, (free, forced, grads) in enumerate(res):
+        res = oracle_head(orc, op, q, k, v, g, qc[0, h], aq[0, h], ak[0, h // G], (sc, sb), threads=8, with_bwd=with_bwd)
+        free, forced, grads = res["free"], res["forced"], res["grads"]
         if name in ("cfg1_full", "cfg2_small"):
             # the far field must matter in these cases, or the parity below would say little about it
             far = free["mass"][w.Bs:, :3].sum(1)
             assert far.mean() > 0.2 and (free["mass"][w.Bs:, :3].mean(0) > 1e-3).all(), free["mass"][w.Bs:].mean(0)
         if w.r:
-            safe_c = free["margin_c"] > MARGIN
-            assert safe_c.mean() > 0.98, safe_c.mean()
-            got_c = as_sets(selc_h[h][:, : w.r]); want_c = as_sets(free["selc"])
-            np.testing.assert_array_equal(got_c[safe_c], want_c[safe_c], err_msg=f"{name} head {h}: retrieved clusters")
-            # descending-score export order, and the blocks of every slot, where both margins are safe
-            safe = safe_c & (free["margin_b"] > MARGIN)
-            same_order = (selc_h[h][:, : w.r] == free["selc"]).all(1)
-            chk = safe & same_order
-            got_b = selb_h[h][:, : w.r].reshape(w.N, w.r, op.k2e)
-            np.testing.assert_array_equal(np.sort(got_b[chk], -1), np.sort(free["selb"][chk], -1),
-                                          err_msg=f"{name} head {h}: retrieved blocks")
+            check_selections(name, h, w, op, sc, sb, free, forced)
+            keys = segment_sizes(ak[0, h // G], w.Bs, w.Ck)
+            ok = (sc[:, :, None] >= 0) & (sb >= 0)
+            if ok.any():
+                reach["pair_keys"] = max(reach["pair_keys"], int(keys[sb[ok], np.broadcast_to(sc[:, :, None], sb.shape)[ok]].max()))
+        if w.N > w.Bs:
+            reach["group"] = max(reach["group"], int(segment_sizes(aq[0, h], w.Bs, w.Cq)[1:].max()))
         assert_close(f64(O[0, h]), forced["O"], p, f"{name} O head {h}")
         lse_tol = 1e-4 if w.dtype == "fp32" else 2e-2
         np.testing.assert_allclose(LSE[0, h].cpu().numpy(), forced["LSE"], rtol=0, atol=lse_tol * max(1, np.abs(forced["LSE"]).max()))
         if with_bwd:
             assert_close(f64(dQ[0, h]), grads[0], p, f"{name} dQ head {h}", grad=True)
             wantK[h // G] += grads[1]; wantV[h // G] += grads[2]
+    for what, least in REACH.get(name, {}).items():
+        assert reach[what] >= least, f"{name} no longer reaches {what} >= {least}: {reach}"
     if with_bwd:
         for hk in range(w.Hkv):
             assert_close(f64(dK[0, hk]), wantK[hk], p, f"{name} dK head {hk}", grad=True)
             assert_close(f64(dV[0, hk]), wantV[hk], p, f"{name} dV head {hk}", grad=True)
+    return reach
 
 
 @pytest.mark.parametrize("name", list(CASES))
@@ -189,3 +221,41 @@ def test_keep_forward_state_matches_recompute():
         assert torch.equal(a, b)
     with pytest.raises(mb.MuseError, match="workspace"):
         mb.muse_fwd(pk, Q, K, V, *cl, ws=ws[: pref - 4096])
+
+
+def test_backward_with_kept_forward_state_multi_tile_paths():
+    """The flags bench.py times (MUSE_FLAG_KEEP_FWD_STATE, one workspace for forward and backward) on the case
+    with several key tiles per retrieved pair and several staging passes per query group."""
+    run_case("bf16_pairs64", with_bwd=True, flags=mb.FLAG_KEEP_FWD_STATE)
+
+
+def test_keep_forward_state_default_workspace_and_stamp():
+    """With ws=None the binding hands forward and backward the same cached buffer under the flag; the library
+    refuses a workspace that does not hold the forward state of these params (MUSE_ERR_STATE)."""
+    base, kw = CASES["cfg2_small"]
+    w = small(base, **kw)
+    d = generate(w, need_dO=True)
+    p = mb.params_for(w)
+    pk = dataclasses.replace(p, flags=mb.FLAG_KEEP_FWD_STATE)
+    qc, aq, ak = oracle_clustering(w, d, p)
+    Q, K, V, dO = (dev(d[x], p) for x in ("Q", "K", "V", "dO"))
+    cl = (torch.tensor(qc).cuda(), torch.tensor(aq).cuda(), torch.tensor(ak).cuda())
+    O, LSE, selc, selb = mb.muse_fwd(p, Q, K, V, *cl)
+    g = mb.muse_bwd(p, Q, K, V, O, LSE, dO, *cl, selc, selb)
+    mb.free_workspaces()
+    O2, LSE2, selc2, selb2 = mb.muse_fwd(pk, Q, K, V, *cl)          # default workspace
+    g2 = mb.muse_bwd(pk, Q, K, V, O2, LSE2, dO, *cl, selc2, selb2)   # must be the same buffer
+    assert torch.equal(O, O2) and torch.equal(selb, selb2)
+    for a, b in zip(g, g2):
+        assert torch.equal(a, b)
+    g3 = mb.muse_bwd(dataclasses.replace(pk, flags=pk.flags | mb.FLAG_FROZEN_WEIGHTS), Q, K, V, O2, LSE2, dO, *cl, selc2, selb2)
+    assert torch.equal(g3[0], g[0]) and torch.equal(g3[2], g[2])     # a backward-only flag keeps the state valid
+    size = mb.muse_workspace_bytes(pk, mb.WS_BWD)[1]
+    other = torch.zeros(size, dtype=torch.uint8, device="cuda")
+    with pytest.raises(mb.MuseError, match="forward state"):         # a buffer no forward has filled
+        mb.muse_bwd(pk, Q, K, V, O2, LSE2, dO, *cl, selc2, selb2, ws=other)
+    with pytest.raises(mb.MuseError, match="forward state"):         # other params than the forward's
+        mb.muse_bwd(dataclasses.replace(pk, scale=0.2), Q, K, V, O2, LSE2, dO, *cl, selc2, selb2)
+    mb.muse_fwd(p, Q, K, V, *cl, ws=mb.workspace(pk, mb.WS_BWD))     # a stateless call on the buffer clears the stamp
+    with pytest.raises(mb.MuseError, match="forward state"):
+        mb.muse_bwd(pk, Q, K, V, O2, LSE2, dO, *cl, selc2, selb2)

@@ -693,3 +693,70 @@ def test_error_falls_with_clusters_and_retrieval(oracle):
 
     assert rse(8, 32, 0) < rse(8, 8, 0)
     assert rse(8, 16, 4) < rse(8, 16, 0)
+
+
+def _hand_worked_selection_case():
+    """Three key clusters, three blocks of four positions, D = 2, one query cluster with q-bar = 0 and scale 1:
+    the tilted summaries are then plain means with mu-bar = log(count) and the scores are small integers plus
+    logarithms that can be written down by hand (see test_selection_margins_hand_worked)."""
+    K = np.array([[1, 0], [0, 1], [1, 1], [1, 1],      # block 0: clusters 0, 1, 2, 2
+                  [3, 0], [0, 1], [0, 0], [0, 0],      # block 1: clusters 0, 1, 2, 2
+                  [0, 0], [0, 0], [0, 0], [0, 0]], dtype=np.float64)
+    ak = np.array([0, 1, 2, 2, 0, 1, 2, 2, 0, 1, 2, 2], dtype=np.int32)
+    Q = np.zeros((12, 2)); Q[4] = Q[8] = (2.0, 1.0)
+    V = np.arange(24, dtype=np.float64).reshape(12, 2) / 7.0
+    return Q, K, V, np.zeros((1, 2)), np.zeros(12, dtype=np.int32), ak
+
+
+def test_selection_margins_hand_worked(oracle):
+    """margin_c / margin_b are the numbers the GPU parity tests rely on to decide which rows are compared:
+    pinned against scores worked out by hand.
+    Row 4 (block 1) sees block 0: scores 2, 1, 3 + log 2.  Row 8 (block 2) sees blocks 0-1: cluster 0 has keys
+    (1,0), (3,0): mean (2,0), mass 2 -> 4 + log 2; cluster 1: (0,1) twice -> 1 + log 2; cluster 2: mean
+    (1/2, 1/2), mass 4 -> 3/2 + log 4.  Blocks of cluster 0 for row 8: (1,0) -> 2 and (3,0) -> 6."""
+    Q, K, V, qc, aq, ak = _hand_worked_selection_case()
+    l2 = np.log(2.0)
+    got = oracle.muse_fwd(MuseParams(12, 2, 4, 1, 3, 1, 1, 1.0), Q, K, V, qc, aq, ak)
+    assert got["selc"][4, 0] == 2 and got["selc"][8, 0] == 0
+    np.testing.assert_allclose(got["margin_c"][4], (3 + l2 - 2) / (3 + l2), rtol=1e-12)
+    np.testing.assert_allclose(got["margin_c"][8], (4 + l2 - (1.5 + 2 * l2)) / (4 + l2), rtol=1e-12)
+    assert got["selb"][4, 0, 0] == 0 and got["margin_b"][4] == np.inf     # one preceding block: nothing left out
+    assert got["selb"][8, 0, 0] == 1
+    np.testing.assert_allclose(got["margin_b"][8], (6 - 2) / 6, rtol=1e-12)
+    assert (got["margin_c"][:4] == np.inf).all()                            # block 0 has no far field
+    got2 = oracle.muse_fwd(MuseParams(12, 2, 4, 1, 3, 2, 1, 1.0), Q, K, V, qc, aq, ak)
+    assert sorted(got2["selc"][4]) == [0, 2] and sorted(got2["selc"][8]) == [0, 2]
+    np.testing.assert_allclose(got2["margin_c"][4], (2 - 1) / 2, rtol=1e-12)
+    np.testing.assert_allclose(got2["margin_c"][8], (1.5 + 2 * l2 - (1 + l2)) / (1.5 + 2 * l2), rtol=1e-12)
+    # row 8, cluster 2: blocks (1,1) mass 2 -> 3 + log 2 and (0,0) mass 2 -> log 2; cluster 0 as above
+    np.testing.assert_allclose(got2["margin_b"][8], min((6 - 2) / 6, 3 / (3 + l2)), rtol=1e-12)
+    # r covers every cluster: nothing is left out
+    got3 = oracle.muse_fwd(MuseParams(12, 2, 4, 1, 3, 3, 1, 1.0), Q, K, V, qc, aq, ak)
+    assert got3["margin_c"][8] == np.inf
+
+
+def test_forced_selection_slack_hand_worked(oracle):
+    """With the selections given, the margins are the slack of that selection (same hand-worked scores):
+    equal to the free gap for the best selection, negative for a worse one, -inf for a malformed one."""
+    Q, K, V, qc, aq, ak = _hand_worked_selection_case()
+    l2 = np.log(2.0)
+    p = MuseParams(12, 2, 4, 1, 3, 1, 1, 1.0)
+    free = oracle.muse_fwd(p, Q, K, V, qc, aq, ak)
+    same = oracle.muse_fwd(p, Q, K, V, qc, aq, ak, sel=(free["selc"], free["selb"]))
+    np.testing.assert_array_equal(same["margin_c"], free["margin_c"])
+    np.testing.assert_array_equal(same["margin_b"], free["margin_b"])
+    sc, sb = free["selc"].copy(), free["selb"].copy()
+    sc[8, 0], sb[8, 0, 0] = 2, 1            # cluster 2 (3/2 + log 4) instead of cluster 0 (4 + log 2); its worse block
+    got = oracle.muse_fwd(p, Q, K, V, qc, aq, ak, sel=(sc, sb))
+    np.testing.assert_allclose(got["margin_c"][8], (1.5 + 2 * l2 - (4 + l2)) / (4 + l2), rtol=1e-12)
+    np.testing.assert_allclose(got["margin_b"][8], (l2 - (3 + l2)) / (3 + l2), rtol=1e-12)
+    for bad in (5, -1):                     # out of range; too few entries while candidates exist
+        sc2 = free["selc"].copy(); sc2[8, 0] = bad
+        sb2 = free["selb"].copy(); sb2[8] = -1
+        assert oracle.muse_fwd(p, Q, K, V, qc, aq, ak, sel=(sc2, sb2))["margin_c"][8] == -np.inf
+    p2 = MuseParams(12, 2, 4, 1, 3, 2, 1, 1.0)
+    f2 = oracle.muse_fwd(p2, Q, K, V, qc, aq, ak)
+    sc3 = f2["selc"].copy(); sc3[8] = (0, 0)  # the same cluster twice
+    assert oracle.muse_fwd(p2, Q, K, V, qc, aq, ak, sel=(sc3, f2["selb"]))["margin_c"][8] == -np.inf
+    sb3 = f2["selb"].copy(); sb3[8, 0, 0] = 2  # a block that is not before the query's
+    assert oracle.muse_fwd(p2, Q, K, V, qc, aq, ak, sel=(f2["selc"], sb3))["margin_b"][8] == -np.inf
