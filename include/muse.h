@@ -53,8 +53,9 @@ enum {
   MUSE_ERR_UNSUPPORTED = -2,        /* non-causal, D not in {64,128}, sizes beyond the kernels' limits */
   MUSE_ERR_WORKSPACE_TOO_SMALL = -3,
   MUSE_ERR_HIP = -4,                /* a HIP call or launch failed */
-  MUSE_ERR_STATE = -5               /* MUSE_FLAG_KEEP_FWD_STATE: the workspace does not hold the forward state
+  MUSE_ERR_STATE = -5,              /* MUSE_FLAG_KEEP_FWD_STATE: the workspace does not hold the forward state
                                        of these params (another workspace, other params, or overwritten) */
+  MUSE_ERR_SCRATCH_LIMIT = -6       /* exact_attn_bwd_static: the input needs more than MUSE_STATIC_SCRATCH_BYTES */
 };
 
 enum { MUSE_DTYPE_FP32 = 0, MUSE_DTYPE_BF16 = 1 };
@@ -192,6 +193,22 @@ int exact_attn_fwd(const muse_params* p, const void* Q, const void* K, const voi
 int exact_attn_bwd(const muse_params* p, const void* Q, const void* K, const void* V,
                    const void* O, const float* LSE, const void* dO,
                    void* dQ, void* dK, void* dV, void* ws, size_t ws_bytes, void* stream);
+
+/* exact_attn_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same results,
+ * bit for bit, as exact_attn_bwd; the scratch (one float per query row, plus fp32 accumulators of dQ, dK, dV when
+ * grad_dtype is not fp32) is a device array of MUSE_STATIC_SCRATCH_BYTES inside the library, which every device
+ * the library runs on holds until the process ends.  The call allocates nothing (no hipMalloc, no events):
+ *   - MUSE_ERR_SCRATCH_LIMIT if 256 + 4 B Hq N (+ 4 D N B (Hq + 2 Hkv) for non-fp32 gradients, each part rounded
+ *     up to 256) exceeds MUSE_STATIC_SCRATCH_BYTES; nothing is launched;
+ *   - MUSE_ERR_UNSUPPORTED while muse_profile_enable(1) is in force (the timing creates events);
+ *   - all calls on one device share the one array: two calls whose work overlaps in time on a device (different
+ *     streams, or different threads) race; calls on one stream are ordered and safe.  What must start at zero is
+ *     cleared by the call itself. */
+#define MUSE_STATIC_SCRATCH_BYTES (64u << 20)
+int exact_attn_bwd_static(const muse_params* p, const void* Q, const void* K, const void* V,
+                          const void* O, const float* LSE, const void* dO,
+                          void* dQ, void* dK, void* dV, void* stream);
 
 /* Diagnostics for benchmarks (not part of the method; process-wide, not thread-safe, allocates HIP
  * events): after muse_profile_enable(1) every kernel the library launches is bracketed by HIP events on

@@ -24,7 +24,8 @@ FLAG_STREAMING_KMEANS = 4
 FLAG_BALANCED_ASSIGN = 8
 WS_CLUSTER, WS_FWD, WS_BWD, WS_EXACT_FWD, WS_EXACT_BWD = range(5)
 SYMBOLS = ["muse_workspace_bytes", "muse_cluster", "muse_kmeans_stream", "muse_fwd", "muse_bwd", "exact_attn_fwd", "exact_attn_bwd",
-           "muse_profile_enable", "muse_profile_report", "muse_strerror"]
+           "exact_attn_bwd_static", "muse_profile_enable", "muse_profile_report", "muse_strerror"]
+STATIC_SCRATCH_BYTES = 64 << 20
 
 
 class MuseError(RuntimeError):
@@ -252,6 +253,16 @@ def exact_attn_bwd(p: Params, Q, K, V, O, LSE, dO, ws=None, out=None):
     pc = p.c()
     _check(load().exact_attn_bwd(C.byref(pc), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO), _ptr(dQ),
                                  _ptr(dK), _ptr(dV), _ptr(ws), C.c_size_t(ws.numel()), _stream()), "exact_attn_bwd")
+    return dQ, dK, dV
+
+
+def exact_attn_bwd_static(p: Params, Q, K, V, O, LSE, dO, out):
+    """exact_attn_bwd on the library's static scratch: no workspace, nothing allocated by the call.
+    out = (dQ, dK, dV), allocated by the caller beforehand."""
+    dQ, dK, dV = out
+    pc = p.c()
+    _check(load().exact_attn_bwd_static(C.byref(pc), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(dO), _ptr(dQ),
+                                        _ptr(dK), _ptr(dV), _stream()), "exact_attn_bwd_static")
     return dQ, dK, dV
 
 

@@ -169,6 +169,7 @@ const char* muse_strerror(int code) {
     case MUSE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case MUSE_ERR_HIP: return "HIP runtime error";
     case MUSE_ERR_STATE: return "workspace does not hold the forward state of these params";
+    case MUSE_ERR_SCRATCH_LIMIT: return "input needs more scratch than the no-allocation entry point holds";
     default: return "unknown error code";
   }
 }
@@ -330,6 +331,35 @@ int exact_attn_bwd(const muse_params* p, const void* Q, const void* K, const voi
     if ((rc = muse_launch_cast(av, dV, k * d.D, d.grad_dtype, 1.f, st))) return rc;
   }
   return MUSE_OK;
+}
+
+// ---- exact_attn_bwd for callers that cannot allocate ------------------------------------------
+// The scratch of exact_attn_bwd (delta, and the fp32 accumulators when the gradients leave in bf16) lives in a
+// file-scope device array instead of a caller workspace.  In host code the array's name is only a handle: its
+// device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[MUSE_STATIC_SCRATCH_BYTES];
+namespace {
+void* g_scratch_ptr[64];  // per device, NULL until the first call on it
+}
+
+int exact_attn_bwd_static(const muse_params* p, const void* Q, const void* K, const void* V, const void* O,
+                          const float* LSE, const void* dO, void* dQ, void* dK, void* dV, void* stream) {
+  MuseDims d;
+  int rc = make_dims(p, false, &d);
+  if (rc) return rc;
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV) return MUSE_ERR_INVALID_ARG;
+  if (kTagBytes + exact_bwd_bytes(d) > (size_t)MUSE_STATIC_SCRATCH_BYTES) return MUSE_ERR_SCRATCH_LIMIT;
+  if (muse_profiling()) return MUSE_ERR_UNSUPPORTED;  // the per-kernel timing creates events
+  int dev = 0;
+  MUSE_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return MUSE_ERR_UNSUPPORTED;
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    MUSE_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return MUSE_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return exact_attn_bwd(p, Q, K, V, O, LSE, dO, dQ, dK, dV, g_scratch_ptr[dev], (size_t)MUSE_STATIC_SCRATCH_BYTES, stream);
 }
 
 int muse_profile_enable(int on) {
