@@ -21,6 +21,21 @@ constexpr int TPAD = 4;  // padding of a transposed tile's rows: 34 dwords apart
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+constexpr float kLazyLog2 = 8.f;  // the softmax reference follows the running maximum in steps of more than 2^8
+
+// acc + the sum of the 8 bf16 values of an operand (v_dot2c_f32_bf16 against a pair of ones: two values per
+// instruction, where adding the fp32 values takes one each)
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ float sum8(const bf16x8_t& v, float acc) {
+  const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bf16x2_t p = {v[2 * i], v[2 * i + 1]};
+    acc = __builtin_amdgcn_fdot2_f32_bf16(p, ones, acc, false);
+  }
+  return acc;
+}
+
 // Numbering of the flash kernels' workgroups.  The tiles of 128 rows of one (batch, head, spatial block) group
 // stream the same keys and values (forward, dQ) or queries (dK/dV); workgroups go to the 8 XCDs round-robin by
 // their linear id, so with a grid of (8 tpg, ceil(groups / 8)) the workgroup (x, y) is on XCD x % 8 and takes
@@ -31,10 +46,11 @@ struct FlashTile {
   int t, blk, tpg, h, b;  // tile inside the group, block of the group, tiles per group, head, batch
   bool ok;
 };
+template <int TR = 128>  // rows of a workgroup's tile
 __device__ __forceinline__ FlashTile flash_tile(int N, int Bs, int H, int nbatch) {
   FlashTile r;
-  const bool al = (Bs % 128) == 0;
-  r.tpg = al ? Bs / 128 : (N + 127) / 128;
+  const bool al = (Bs % TR) == 0;
+  r.tpg = al ? Bs / TR : (N + TR - 1) / TR;
   const int nblk = al ? N / Bs : 1;
   const int g = blockIdx.y * 8 + blockIdx.x % 8;
   r.t = blockIdx.x / 8;
@@ -44,9 +60,9 @@ __device__ __forceinline__ FlashTile flash_tile(int N, int Bs, int H, int nbatch
   r.b = g / nblk / H;
   return r;
 }
-static dim3 flash_grid(int N, int Bs, int H, int nbatch) {
-  const bool al = (Bs % 128) == 0;
-  const int tpg = al ? Bs / 128 : (N + 127) / 128, nblk = al ? N / Bs : 1;
+static dim3 flash_grid(int N, int Bs, int H, int nbatch, int TR = 128) {
+  const bool al = (Bs % TR) == 0;
+  const int tpg = al ? Bs / TR : (N + TR - 1) / TR, nblk = al ? N / Bs : 1;
   return dim3(8 * tpg, (nbatch * H * nblk + 7) / 8, 1);
 }
 
@@ -143,7 +159,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   for (int t = 0; t < DT; ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
-  float m = MUSE_NEG_INF, l = 0.f;
+  float m = MUSE_NEG_INF, mref = 0.f, l = 0.f;
 
   const int kbeg = (q0 / Bs) * Bs, kend = min(q0 + 128, N);
   TileRegs kreg, vreg;
@@ -185,35 +201,41 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 #pragma unroll
       for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[kt][e]);
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    float mn = fmaxf(m, tmax * scale_log2e);
-    float mref = mn == MUSE_NEG_INF ? 0.f : mn;
-    float alpha = fast_exp2(m - mref);
+    // The reference m of the running softmax only moves when a tile's maximum exceeds it by more than 2^8:
+    // probabilities then stay below 256 (exact in bf16's range, sums in fp32), and the rescaling of the
+    // accumulators, a multiply per output element, is skipped on all other tiles (wave-uniform branch).
+    // O = o / l and LSE = m + log2 l hold for any reference as long as o, l and p use the same one.
+    const float ts = tmax * scale_log2e;
+    const bool up = ts > m + kLazyLog2;  // m = -inf: any finite maximum
+    if (__builtin_amdgcn_ballot_w64(up) != 0) {
+      const float mn = up ? ts : m;
+      mref = mn == MUSE_NEG_INF ? 0.f : mn;
+      const float alpha = fast_exp2(m - mref);
+      l *= alpha;
+      m = mn;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+    }
     float psum = 0.f;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float p = fast_exp2(fmaf(s[kt][e], scale_log2e, -mref));
-        s[kt][e] = p;
-        psum += p;
-      }
-    l = l * alpha + psum;
-    m = mn;
-#pragma unroll
-    for (int t = 0; t < DT; ++t)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+      for (int e = 0; e < 16; ++e) s[kt][e] = fast_exp2(fmaf(s[kt][e], scale_log2e, -mref));
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int G = 0; G < 2; ++G) {
         bf16x8_t pf = pack8(s[kt], 2 * G, 2 * G + 1);
+        psum = sum8(pf, psum);  // the normaliser sums the probabilities as the matrix cores see them
 #pragma unroll
         for (int t = 0; t < DT; ++t) {
           bf16x8_t a = ld_tr8(&vt[32 * t + col][0], 32 * kt + 16 * G, half);
           o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, o[t], 0, 0, 0);
         }
       }
+    l += psum;
   }
   l += __shfl_xor(l, 32, 64);
   if (nq >= N) return;
@@ -254,6 +276,172 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   if (half == 0) LSE[qh + nq] = mnat + __logf(lt);
 }
 
+// The forward for D = 64 with TWO query tiles per wave (a workgroup covers 256 queries): every key / value
+// operand read from LDS feeds two MFMAs, and a barrier pair covers twice the matrix work.  At D = 64 the
+// forward has only 4 D = 256 flop per score against a fixed cost per score in the vector unit, so what is
+// spent per score on LDS reads and barriers decides how close the matrix cores get to their peak.
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) k_flash_fwd2(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, const float* __restrict__ ff,
+    bf16_t* __restrict__ O, float* __restrict__ LSE, int N, int Bs, int Hq, int Hkv, int nbatch, float scale_log2e) {
+  constexpr int D = 64, KS = D / 16, DT = D / 32, TR = 256;
+  __shared__ __attribute__((aligned(16))) bf16_t ks[BN][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t vt[D][BN + TPAD];
+  const FlashTile ft = flash_tile<TR>(N, Bs, Hq, nbatch);
+  if (!ft.ok) return;
+  const int hq = ft.h, b = ft.b, hk = hq / (Hq / Hkv);
+  const size_t qh = ((size_t)b * Hq + hq) * N, kh = ((size_t)b * Hkv + hk) * N;
+  const int q0 = (ft.blk * ft.tpg + ft.tpg - 1 - ft.t) * TR;  // long rows first
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  const int w0 = q0 + 64 * wave;  // first query of this wave; tile a = 0, 1 holds queries w0 + 32 a + col
+  const bool unaligned = (Bs % TR) != 0;
+
+  bf16x8_t qf[2][KS];
+  int nq[2], myb[2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    nq[a] = w0 + 32 * a + col;
+    const int nqc = nq[a] < N ? nq[a] : N - 1;
+    myb[a] = (nqc / Bs) * Bs;
+#pragma unroll
+    for (int x = 0; x < KS; ++x)
+      qf[a][x] = *reinterpret_cast<const bf16x8_t*>(Q + (qh + nqc) * D + 16 * x + 8 * half);
+  }
+  f32x16_t o[2][DT];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[a][t][e] = 0.f;
+  float m[2] = {MUSE_NEG_INF, MUSE_NEG_INF}, mref[2] = {0.f, 0.f}, l[2] = {0.f, 0.f};
+
+  const int kbeg = (q0 / Bs) * Bs, kend = min(q0 + TR, N);
+  TileRegs kreg, vreg;
+  fetch_tile<D, BN>(K + kh * D, kbeg, N, kreg);
+  fetch_tile<D, BN>(V + kh * D, kbeg, N, vreg);
+  for (int k0 = kbeg; k0 < kend; k0 += BN) {
+    __syncthreads();
+    commit_tile<D, BN, true, false>(kreg, ks, nullptr);
+    commit_tile<D, BN, false, true>(vreg, nullptr, vt);
+    __syncthreads();
+    if (k0 + BN < kend) {  // in flight while this tile is consumed
+      fetch_tile<D, BN>(K + kh * D, k0 + BN, N, kreg);
+      fetch_tile<D, BN>(V + kh * D, k0 + BN, N, vreg);
+    }
+    if (k0 > w0 + 63) continue;  // every key of the tile is in this wave's future
+    f32x16_t s[2][2];            // [query tile][key half]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[a][kt][e] = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int x = 0; x < KS; ++x) {
+        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(&ks[32 * kt + col][16 * x + 8 * half]);
+        s[0][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][x], s[0][kt], 0, 0, 0);
+        s[1][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][x], s[1][kt], 0, 0, 0);
+      }
+    bf16x8_t pf[2][2][2];  // [query tile][key half][16-key group]
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      if (unaligned || k0 + BN - 1 > w0 + 32 * a || k0 + BN > N) {  // wave-uniform
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int kg = k0 + 32 * kt + 8 * (e / 4) + 4 * half + (e % 4);
+            if (kg > nq[a] || kg < myb[a]) s[a][kt][e] = MUSE_NEG_INF;
+          }
+      }
+      float tmax = MUSE_NEG_INF;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[a][kt][e]);
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      // lazy reference of the running softmax, as in k_flash_fwd
+      const float ts = tmax * scale_log2e;
+      const bool up = ts > m[a] + kLazyLog2;
+      if (__builtin_amdgcn_ballot_w64(up) != 0) {
+        const float mn = up ? ts : m[a];
+        mref[a] = mn == MUSE_NEG_INF ? 0.f : mn;
+        const float alpha = fast_exp2(m[a] - mref[a]);
+        l[a] *= alpha;
+        m[a] = mn;
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) o[a][t][e] *= alpha;
+      }
+      float psum = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[a][kt][e] = fast_exp2(fmaf(s[a][kt][e], scale_log2e, -mref[a]));
+#pragma unroll
+        for (int G = 0; G < 2; ++G) {
+          pf[a][kt][G] = pack8(s[a][kt], 2 * G, 2 * G + 1);
+          psum = sum8(pf[a][kt][G], psum);  // the normaliser sums the probabilities as the matrix cores see them
+        }
+      }
+      l[a] += psum;
+    }
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int G = 0; G < 2; ++G)
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+          const bf16x8_t vf = ld_tr8(&vt[32 * t + col][0], 32 * kt + 16 * G, half);
+          o[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[0][kt][G], o[0][t], 0, 0, 0);
+          o[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[1][kt][G], o[1][t], 0, 0, 0);
+        }
+  }
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    const float lt0 = l[a] + __shfl_xor(l[a], 32, 64);
+    if (nq[a] >= N) continue;
+    const int n = nq[a];
+    float mnat = m[a] * 0.6931471805599453f;  // natural-log units
+    float cl = 1.f, cf = 0.f, lf = 0.f;       // weights of the local and the far-field part after the merge
+    const float* fa = nullptr;
+    if (ff) {
+      const float* fm = ff + (size_t)nbatch * Hq * N * D + (qh + n) * 2;  // [acc | (max,sum)] planes
+      const float mf = fm[0];
+      lf = fm[1];
+      if (lf > 0.f) {
+        const float mx = fmaxf(mnat, mf);
+        cl = __expf(mnat - mx);
+        cf = __expf(mf - mx);
+        mnat = mx;
+        fa = ff + (qh + n) * D;
+      }
+    }
+    const float lt = lt0 * cl + lf * cf;
+    const float inv = 1.f / lt;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int d = 32 * t + 8 * g + 4 * half;
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = o[a][t][4 * g + u] * cl;
+        if (fa) {
+          const float4 f = *reinterpret_cast<const float4*>(fa + d);
+          v[0] += cf * f.x; v[1] += cf * f.y; v[2] += cf * f.z; v[3] += cf * f.w;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] *= inv;
+        st4(O, (qh + n) * D + d, v);
+      }
+    if (half == 0) LSE[qh + n] = mnat + __logf(lt);
+  }
+}
+
 template <int D>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2))) k_flash_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                        const bf16_t* __restrict__ V, const bf16_t* __restrict__ dO,
@@ -281,6 +469,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     gf[s] = *reinterpret_cast<const bf16x8_t*>(dO + (qh + nqc) * D + 16 * s + 8 * half);
   }
   const float lse2 = LSE[qh + nqc] * 1.4426950408889634f, dl = delta[qh + nqc];
+  const bool unaligned = (Bs % 128) != 0;
   f32x16_t dq[DT];
 #pragma unroll
   for (int t = 0; t < DT; ++t)
@@ -301,6 +490,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
       fetch_tile<D, BN>(V + kh * D, k0 + BN, N, vreg);
     }
     if (k0 > q0 + 32 * wave + 31) continue;
+    const bool edge = unaligned || k0 + BN - 1 > q0 + 32 * wave || k0 + BN > N;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
       f32x16_t s, dp;
@@ -313,11 +503,16 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
         bf16x8_t av = *reinterpret_cast<const bf16x8_t*>(&vs[32 * kt + col][16 * x + 8 * half]);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, gf[x], dp, 0, 0, 0);
       }
+      if (edge) {  // wave-uniform: only tiles on the diagonal or at the sequence end hold masked entries
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          int kg = k0 + 32 * kt + 8 * (e / 4) + 4 * half + (e % 4);
+          if (kg > nq || kg < myb) s[e] = MUSE_NEG_INF;  // p = 0
+        }
+      }
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        int kg = k0 + 32 * kt + 8 * (e / 4) + 4 * half + (e % 4);
-        float p = fast_exp2(fmaf(s[e], scale_log2e, -lse2));
-        p = (kg > nq || kg < myb) ? 0.f : p;
+        const float p = fast_exp2(fmaf(s[e], scale_log2e, -lse2));
         s[e] = p * (dp[e] - dl);
       }
 #pragma unroll
@@ -428,9 +623,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             int e = 4 * gq + u;
-            int n = q0 + 32 * qt + 8 * gq + 4 * half + u;
             float p = fast_exp2(fmaf(s[e], scale_log2e, -lv[u]));
-            p = (n < mk || n >= myend) ? 0.f : p;
+            {
+              int n = q0 + 32 * qt + 8 * gq + 4 * half + u;
+              p = (n < mk || n >= myend) ? 0.f : p;
+            }
             pr[e] = p;
             s[e] = p * (dp[e] - dv4[u]);
           }
@@ -1285,7 +1482,8 @@ int muse_launch_attn_fwd_mfma(const MuseDims& d, int Bs, const void* Q, const vo
   const dim3 g = flash_grid(d.N, Bs, d.Hq, d.B);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64)
-    { MuseProf prof_("k_flash_fwd", st); hipLaunchKernelGGL(k_flash_fwd<64>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, ff,
+    // two query tiles per wave (256-query workgroups)
+    { MuseProf prof_("k_flash_fwd", st); hipLaunchKernelGGL(k_flash_fwd2, flash_grid(d.N, Bs, d.Hq, d.B, 256), dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, ff,
                        (bf16_t*)O, LSE, d.N, Bs, d.Hq, d.Hkv, d.B, sl); }
   else
     { MuseProf prof_("k_flash_fwd", st); hipLaunchKernelGGL(k_flash_fwd<128>, g, dim3(256), 0, st, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, ff,
