@@ -31,7 +31,7 @@ class _P(C.Structure):
     _fields_ = [
         ("N", C.c_int32), ("D", C.c_int32), ("Bs", C.c_int32), ("Cq", C.c_int32),
         ("Ck", C.c_int32), ("r", C.c_int32), ("k2", C.c_int32), ("scale", C.c_double),
-        ("frozen_weights", C.c_int32), ("Kw", C.c_void_p),
+        ("frozen_weights", C.c_int32), ("dipole", C.c_int32), ("Kw", C.c_void_p),
     ]
 
 
@@ -46,12 +46,13 @@ class MuseParams:
     k2: int = 1
     scale: float = 0.0  # 0 -> 1/sqrt(D)
     frozen_weights: bool = False  # backward: aggregation weights and mu-bar are constants (App. C)
+    dipole: int = 0  # forward, r = 0 only (App. B): 1 per-cell tilted dipole, 2 pre-merged untilted dipole
 
     def c(self, Kw=None) -> _P:
         """Kw: float64 [N, D] array (kept alive by the caller) of the keys inside the tilted weights."""
         sc = self.scale if self.scale != 0.0 else 1.0 / np.sqrt(self.D)
         return _P(self.N, self.D, self.Bs, self.Cq, self.Ck, self.r, self.k2, sc, int(self.frozen_weights),
-                  None if Kw is None else Kw.ctypes.data)
+                  int(self.dipole), None if Kw is None else Kw.ctypes.data)
 
     @property
     def nb(self) -> int:
@@ -223,6 +224,8 @@ def muse_fwd(p: MuseParams, Q, K, V, qc, aq, ak, rows=None, sel=None, weight_key
     rc = _L().oracle_muse_fwd(C.byref(pc), Qp, Kp, Vp, qp, aqp, akp, C.c_int(nr), rp, C.c_int(given),
                               _d(O)[1], _d(LSE)[1], _i(selc)[1], _i(selb)[1], _d(mc)[1], _d(mb)[1],
                               _d(mass)[1])
+    if rc == -2:
+        raise ValueError("the dipole correction is defined for the monopole-only mode (r = 0)")
     assert rc == 0
     return dict(O=O, LSE=LSE, selc=selc, selb=selb, margin_c=mc, margin_b=mb, mass=mass)
 

@@ -19,6 +19,9 @@
  *     summaries, block-causal mask b_q > b_k         : Sec. 3.2 "Spatial block selection"
  *   - exact retrieval with the full query, local
  *     block-diagonal attention, 4-component merge    : Sec. 3.3
+ *   - dipole correction of the monopole-only mode, per cell
+ *     (tilted) and pre-merged with untilted covariances : App. B "Dipole Correction",
+ *                                                     "Untilted (Partially Specialized) Covariances"
  *   - backward: discrete choices frozen, query
  *     centroid a constant                            : App. C "Centroid Gradient Flow";
  *     gradient flows into K,V through the tilted aggregation weights (the default,
@@ -56,6 +59,19 @@ typedef struct {
   /* App. C "Aggregation Weight Gradient Flow", non-differentiable variant: the tilted aggregation
    * weights e_m / S and the log-mass mu-bar of every summary are constants of the backward. */
   int32_t frozen_weights;
+  /* App. B "Dipole Correction" (forward only, monopole-only mode r = 0):
+   *   0 none;
+   *   1 per-cell tilted dipole, Eq. "dipole-shift": the value of the accumulated summary (i,j,b)
+   *     becomes v-bar + Cov_ij(v,k) q~, Cov_ij the q-bar_i-tilted covariance of its keys;
+   *   2 pre-merged untilted dipole, Eq. "premerge" with the shared covariances of "Untilted
+   *     (Partially Specialized) Covariances": one matrix C-bar_ib = sum_j p_ib(j) Cov_0jb(v,k)
+   *     per (query cluster, query block), applied once per query as C-bar q~.
+   * Causal reading (the appendix has no blocks): the key set of cluster j seen from query block b
+   * is its keys in the blocks before b, as for the accumulated summaries; p_ib(j) is the softmax
+   * of the accumulated log-masses A-mu_ijb over j; and because the far field shares the one
+   * softmax with the query's own block, the merged correction enters the output with the far
+   * field's share of the softmax mass:  O_n += w_far(n) C-bar_ib q~_n. */
+  int32_t dipole;
   /* Keys inside the tilted weights exp(q-bar . k) of Eq. 4-6 when they are to differ from the keys
    * that are aggregated (NULL: the same K).  Only the pins use it: with Kw held at K the forward is the
    * function whose derivative the frozen-weights backward is. */
@@ -669,6 +685,65 @@ typedef struct {
   int k2e; /* slots per selected cluster: k2, or nb-1 when k2 == 0 */
 } ctx_t;
 
+/* Covariance Cov(v,k)[a*D + c] = E[(v_a - E v_a)(k_c - E k_c)] of the keys of cluster j in the
+ * blocks before b, under the weights exp(qb . k) (qb == NULL: equal weights, the untilted
+ * covariance Cov_0j of App. B).  Zero for an empty set. */
+static void cov_vk(const ctx_t* c, const double* qb, int j, int b, double* cov) {
+  int D = c->p->D, Ck = c->p->Ck;
+  for (int t = 0; t < D * D; ++t) cov[t] = 0.0;
+  double mx = -INFINITY;
+  for (int bp = 0; bp < b; ++bp)
+    for (int u = c->s->seg_off[bp * Ck + j]; u < c->s->seg_off[bp * Ck + j + 1]; ++u) {
+      double l = qb ? dot(qb, c->K + (size_t)c->s->seg_idx[u] * D, D) : 0.0;
+      if (l > mx) mx = l;
+    }
+  if (mx == -INFINITY) return;
+  double* km = (double*)calloc(2 * (size_t)D, sizeof(double));
+  double* vm = km + D;
+  double S = 0.0;
+  for (int bp = 0; bp < b; ++bp)
+    for (int u = c->s->seg_off[bp * Ck + j]; u < c->s->seg_off[bp * Ck + j + 1]; ++u) {
+      int m = c->s->seg_idx[u];
+      double w = exp((qb ? dot(qb, c->K + (size_t)m * D, D) : 0.0) - mx);
+      S += w;
+      for (int d = 0; d < D; ++d) {
+        km[d] += w * c->K[(size_t)m * D + d];
+        vm[d] += w * c->V[(size_t)m * D + d];
+      }
+    }
+  for (int d = 0; d < D; ++d) { km[d] /= S; vm[d] /= S; }
+  for (int bp = 0; bp < b; ++bp)
+    for (int u = c->s->seg_off[bp * Ck + j]; u < c->s->seg_off[bp * Ck + j + 1]; ++u) {
+      int m = c->s->seg_idx[u];
+      double w = exp((qb ? dot(qb, c->K + (size_t)m * D, D) : 0.0) - mx) / S;
+      for (int a = 0; a < D; ++a)
+        for (int d = 0; d < D; ++d)
+          cov[a * D + d] += w * (c->V[(size_t)m * D + a] - vm[a]) * (c->K[(size_t)m * D + d] - km[d]);
+    }
+  free(km);
+}
+
+/* Pre-merged dipole matrix of (query cluster i, query block b), App. B Eq. "premerge" with untilted
+ * covariances:  C-bar = sum_j p(j) Cov_0jb(v,k),  p = softmax over j of the accumulated log-masses. */
+static void merged_dipole(const ctx_t* c, int i, int b, double* cbar) {
+  int D = c->p->D, Ck = c->p->Ck, nb = c->s->nb;
+  for (int t = 0; t < D * D; ++t) cbar[t] = 0.0;
+  const double* Amu = c->s->Amu[i];
+  double mx = -INFINITY, Z = 0.0;
+  for (int j = 0; j < Ck; ++j)
+    if (Amu[(size_t)j * nb + b] > mx) mx = Amu[(size_t)j * nb + b];
+  if (mx == -INFINITY) return;
+  for (int j = 0; j < Ck; ++j) Z += exp(Amu[(size_t)j * nb + b] - mx);
+  double* cov = (double*)malloc(sizeof(double) * (size_t)D * D);
+  for (int j = 0; j < Ck; ++j) {
+    double pj = exp(Amu[(size_t)j * nb + b] - mx) / Z;
+    if (pj == 0.0) continue;
+    cov_vk(c, NULL, j, b, cov);
+    for (int t = 0; t < D * D; ++t) cbar[t] += pj * cov[t];
+  }
+  free(cov);
+}
+
 /* Builds the virtual keys of query n.  When sel_given, the selections in
  * selc[r] / selb[r*k2e] are used as they are (entries < 0 ignored); otherwise
  * they are computed (Eq. 7 and the block selection) and written there.
@@ -789,9 +864,19 @@ int oracle_muse_fwd(const omuse_params* p, const double* Q, const double* K, con
                     int32_t* selc, int32_t* selb, double* margin_c, double* margin_b,
                     double* comp_mass) {
   if (p->N % p->Bs) return -1;
+  if (p->dipole && p->r > 0) return -2; /* App. B "Compatibility with Retrieval": not combined */
   int D = p->D, nb = p->N / p->Bs;
   ctx_t c = {p, Q, K, V, aq, ak, summ_new(p, qc, ak), p->k2 == 0 ? (nb > 1 ? nb - 1 : 1) : p->k2};
   needed_clusters(p, K, V, aq, nrows, rows, c.s);
+  /* dipole: per-cell covariance / merged matrices are built when first needed and kept */
+  double** cbar = NULL; /* [Cq*nb] -> D*D, mode 2 */
+  double* covt = NULL;  /* D*D scratch, mode 1 */
+  double* dval = NULL;  /* D scratch */
+  if (p->dipole) {
+    cbar = (double**)calloc((size_t)p->Cq * nb, sizeof(double*));
+    covt = (double*)malloc(sizeof(double) * (size_t)D * D);
+    dval = (double*)malloc(sizeof(double) * (size_t)D);
+  }
   vkey_t* vk = (vkey_t*)malloc(sizeof(vkey_t) * max_vkeys(p));
   double* tmpv = (double*)malloc(sizeof(double) * ((size_t)p->Ck + nb + 1));
   int* tmpi = (int*)malloc(sizeof(int) * ((size_t)p->Ck + nb + 1));
@@ -813,13 +898,35 @@ int oracle_muse_fwd(const omuse_params* p, const double* Q, const double* K, con
     for (int d = 0; d < D; ++d) o[d] = 0.0;
     if (comp_mass)
       for (int u = 0; u < 4; ++u) comp_mass[(size_t)n * 4 + u] = 0.0;
+    double wfar = 0.0; /* share of the accumulated summaries (component 1) in the softmax */
     for (int u = 0; u < nv; ++u) {
       double w = exp(vk[u].logit - mx) / Z;
       const double* val = vkey_value(&c, aq[n], &vk[u]);
+      if (p->dipole == 1 && vk[u].type == VK_ACC) {
+        /* Eq. "dipole-shift": v-bar + Cov_ij(v,k) q~ with the tilted covariance of the cell */
+        cov_vk(&c, c.s->qbar + (size_t)aq[n] * D, vk[u].j, vk[u].b, covt);
+        for (int a = 0; a < D; ++a) dval[a] = val[a] + dot(covt + (size_t)a * D, qs + D, D);
+        val = dval;
+      }
       for (int d = 0; d < D; ++d) o[d] += w * val[d];
+      if (vk[u].type == VK_ACC) wfar += w;
       if (comp_mass) comp_mass[(size_t)n * 4 + vk[u].type - 1] += w;
     }
+    if (p->dipole == 2 && wfar > 0.0) {
+      /* Eq. "premerge": one matrix per (query cluster, query block), applied to q~ */
+      int b = n / p->Bs;
+      size_t slot = (size_t)aq[n] * nb + b;
+      if (!cbar[slot]) {
+        cbar[slot] = (double*)malloc(sizeof(double) * (size_t)D * D);
+        merged_dipole(&c, aq[n], b, cbar[slot]);
+      }
+      for (int a = 0; a < D; ++a) o[a] += wfar * dot(cbar[slot] + (size_t)a * D, qs + D, D);
+    }
     LSE[n] = mx + log(Z);
+  }
+  if (p->dipole) {
+    for (size_t t = 0; t < (size_t)p->Cq * nb; ++t) free(cbar[t]);
+    free(cbar); free(covt); free(dval);
   }
   free(vk); free(tmpv); free(tmpi); free(tmpo); free(qs);
   summ_free(c.s);
@@ -835,6 +942,7 @@ int oracle_muse_bwd(const omuse_params* p, const double* Q, const double* K, con
                     const double* dO, const int32_t* selc, const int32_t* selb, double* dQ,
                     double* dK, double* dV) {
   if (p->N % p->Bs) return -1;
+  if (p->dipole) return -2; /* the dipole correction is defined for the forward only here */
   int D = p->D, nb = p->N / p->Bs, Ck = p->Ck, Cq = p->Cq, N = p->N;
   ctx_t c = {p, Q, K, V, aq, ak, summ_new(p, qc, ak), p->k2 == 0 ? (nb > 1 ? nb - 1 : 1) : p->k2};
   summ_t* s = c.s;

@@ -760,3 +760,78 @@ def test_forced_selection_slack_hand_worked(oracle):
     assert oracle.muse_fwd(p2, Q, K, V, qc, aq, ak, sel=(sc3, f2["selb"]))["margin_c"][8] == -np.inf
     sb3 = f2["selb"].copy(); sb3[8, 0, 0] = 2  # a block that is not before the query's
     assert oracle.muse_fwd(p2, Q, K, V, qc, aq, ak, sel=(f2["selc"], sb3))["margin_b"][8] == -np.inf
+
+
+# ---------------------------------------------------------------------------
+# dipole correction of the monopole-only mode (App. B)
+# ---------------------------------------------------------------------------
+def _scaled_residual_errors(oracle, dipole, seed=95):
+    rng = np.random.default_rng(seed)
+    N, D, Cq, Ck = 64, 4, 3, 4
+    aq = rng.integers(0, Cq, N).astype(np.int32); ak = rng.integers(0, Ck, N).astype(np.int32)
+    qc = rng.normal(size=(Cq, D)); kc = rng.normal(size=(Ck, D))
+    rq = rng.normal(size=(N, D)); rk = rng.normal(size=(N, D)); V = rng.normal(size=(N, D))
+    for i in range(Cq):
+        rq[aq == i] -= rq[aq == i].mean(0)
+    errs = []
+    for eps in (0.2, 0.1, 0.05):
+        Q = qc[aq] + eps * rq; K = kc[ak] + eps * rk
+        f = oracle.muse_fwd(MuseParams(N, D, 8, Cq, Ck, 0, 1, 1.0, dipole=dipole), Q, K, V, qc, aq, ak)
+        O, _ = oracle.exact_fwd(Q, K, V, 1.0)
+        errs.append(np.abs(f["O"][8:] - O[8:]).max())
+    return errs
+
+
+def test_dipole_raises_the_error_order(oracle):
+    """App. B: with both residuals scaled by eps the monopole's output error is O(q~ k~) = eps^2 (pinned above);
+    the per-cell tilted dipole (Eq. "dipole-shift") leaves O(q~^2 k~^2) = eps^4; the pre-merged dipole with
+    untilted covariances (Eq. "premerge", "Untilted Covariances") leaves O(qbar q~ k~^2) and the O(q~) change
+    of the cluster weights times an O(q~ k~) correction: eps^3.  A wrong sign, a transposed covariance, a
+    missing mass factor or a non-causal key set all leave the eps^2 term in place."""
+    mono, tilted, merged = (_scaled_residual_errors(oracle, m) for m in (0, 1, 2))
+    assert 3.0 < mono[0] / mono[1] < 5.0 and 3.0 < mono[1] / mono[2] < 5.0, mono
+    assert 11.0 < tilted[0] / tilted[1] < 22.0 and 11.0 < tilted[1] / tilted[2] < 22.0, tilted
+    assert 6.0 < merged[0] / merged[1] < 11.0 and 6.0 < merged[1] / merged[2] < 11.0, merged
+    assert tilted[2] < merged[2] < mono[2]
+
+
+def test_dipole_vanishes_without_key_residuals(oracle):
+    """k~ = 0 (every key sits on its cluster's centroid): all covariances vanish, and monopole, dipole and
+    exact attention coincide (Sec. 3.1: the approximation drops only q~ . k~)."""
+    rng = np.random.default_rng(5)
+    N, D, Cq, Ck = 48, 3, 3, 4
+    aq = rng.integers(0, Cq, N).astype(np.int32); ak = rng.integers(0, Ck, N).astype(np.int32)
+    kc = rng.normal(size=(Ck, D)); vc = rng.normal(size=(Ck, D))
+    Q = rng.normal(size=(N, D)); K = kc[ak]; V = vc[ak]     # values constant per cluster too: Cov(v,k) = 0 exactly
+    qc = np.stack([Q[aq == i].mean(0) for i in range(Cq)])
+    O, _ = oracle.exact_fwd(Q, K, V, 1.0)
+    for mode in (0, 1, 2):
+        f = oracle.muse_fwd(MuseParams(N, D, 8, Cq, Ck, 0, 1, 1.0, dipole=mode), Q, K, V, qc, aq, ak)
+        np.testing.assert_allclose(f["O"], O, atol=1e-12)
+
+
+def test_merged_dipole_against_library_covariance(oracle):
+    """One key cluster: the pre-merged matrix is the plain covariance Cov(v, k) of the keys before the query's
+    block (numpy's routine), and it enters the output with the far field's share of the softmax mass:
+    O_dipole - O_monopole = w_far Cov(v,k) q~, row by row, block by block."""
+    rng = np.random.default_rng(17)
+    N, D, Bs, Cq = 24, 3, 8, 2
+    Q = rng.normal(size=(N, D)) + 0.3; K = rng.normal(size=(N, D)); V = rng.normal(size=(N, D))
+    aq = rng.integers(0, Cq, N).astype(np.int32); ak = np.zeros(N, dtype=np.int32)
+    qc = np.stack([Q[aq == i].mean(0) for i in range(Cq)])
+    scale = 0.7
+    mono = oracle.muse_fwd(MuseParams(N, D, Bs, Cq, 1, 0, 1, scale), Q, K, V, qc, aq, ak)
+    dip = oracle.muse_fwd(MuseParams(N, D, Bs, Cq, 1, 0, 1, scale, dipole=2), Q, K, V, qc, aq, ak)
+    np.testing.assert_array_equal(dip["O"][:Bs], mono["O"][:Bs])     # block 0 has no far field
+    np.testing.assert_array_equal(dip["LSE"], mono["LSE"])           # the mass is left unchanged
+    for n in range(Bs, N):
+        b = n // Bs
+        cov = np.cov(V[: b * Bs].T, K[: b * Bs].T, bias=True)[:D, D:]   # rows: value dims, columns: key dims
+        want = mono["mass"][n, 0] * cov @ (scale * (Q[n] - qc[aq[n]]))
+        np.testing.assert_allclose(dip["O"][n] - mono["O"][n], want, rtol=1e-9, atol=1e-12)
+
+
+def test_dipole_is_not_combined_with_retrieval(oracle):
+    Q, K, V, qc, aq, ak = _data(3, 32, 4, 2, 4)
+    with pytest.raises(ValueError, match="monopole-only"):
+        oracle.muse_fwd(MuseParams(32, 4, 8, 2, 4, 1, 1, 1.0, dipole=2), Q, K, V, qc, aq, ak)
