@@ -84,7 +84,16 @@ enum { MUSE_FLAG_KEEP_FWD_STATE = 1,
  * as their nearest, the first cap in sequence order keep it; the others, one after the other in sequence order,
  * go to the nearest centroid that still has room in the block at that moment (lowest index on ties).
  * MUSE_ERR_UNSUPPORTED if cap < 1 or cap * C < block. */
-       MUSE_FLAG_BALANCED_ASSIGN = 8 };
+       MUSE_FLAG_BALANCED_ASSIGN = 8,
+/* MUSE_FLAG_DIPOLE (muse_fwd only, r must be 0; App. B "Dipole Correction" with the pre-merged matrix of Eq.
+ * "premerge" and the shared covariances of "Untilted (Partially Specialized) Covariances"): in the monopole-only
+ * mode every query of block b >= 1 and query cluster i gets  O_n += w_far(n) C-bar_ib q~_n,  where
+ * C-bar_ib = sum_j p_ib(j) Cov_0jb(v,k), Cov_0jb the equal-weight covariance of the keys of cluster j in the blocks
+ * before b, p_ib the softmax over j of the accumulated log-masses, and w_far the far field's share of the query's
+ * softmax mass; scores and LSE are unchanged.  MUSE_ERR_UNSUPPORTED with r > 0 (the paper does not combine the
+ * merged correction with retrieval) and in muse_bwd (no backward is defined for it).  The workspace grows by the
+ * covariances, 4 D^2 bytes per (kv head, key block, key cluster). */
+       MUSE_FLAG_DIPOLE = 16 };
 enum { MUSE_WS_CLUSTER = 0, MUSE_WS_FWD = 1, MUSE_WS_BWD = 2, MUSE_WS_EXACT_FWD = 3, MUSE_WS_EXACT_BWD = 4 };
 
 typedef struct {

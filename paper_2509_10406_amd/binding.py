@@ -22,6 +22,7 @@ FLAG_KEEP_FWD_STATE = 1
 FLAG_FROZEN_WEIGHTS = 2
 FLAG_STREAMING_KMEANS = 4
 FLAG_BALANCED_ASSIGN = 8
+FLAG_DIPOLE = 16
 WS_CLUSTER, WS_FWD, WS_BWD, WS_EXACT_FWD, WS_EXACT_BWD = range(5)
 SYMBOLS = ["muse_workspace_bytes", "muse_cluster", "muse_kmeans_stream", "muse_fwd", "muse_bwd", "exact_attn_fwd", "exact_attn_bwd",
            "exact_attn_bwd_static", "muse_profile_enable", "muse_profile_report", "muse_strerror"]

@@ -164,6 +164,7 @@ struct MuseDims {
   bool frozen_weights;  // MUSE_FLAG_FROZEN_WEIGHTS
   bool streaming;       // MUSE_FLAG_STREAMING_KMEANS
   bool balanced;        // MUSE_FLAG_BALANCED_ASSIGN
+  bool dipole;          // MUSE_FLAG_DIPOLE
 };
 
 #define MUSE_HIP_CHECK(expr)                      \

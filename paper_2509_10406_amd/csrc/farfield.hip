@@ -926,6 +926,8 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
       w->dQacc = (float*)dQ; w->dKacc = (float*)dK; w->dVacc = (float*)dV;
     }
   }
+  w->dip_cov = nullptr; w->dip_cbar = nullptr;
+  if (d.dipole) w->dip_cov = (float*)take(HK * (size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Ck * D * D * 4);
   size_t cells = (size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * d.Ck;
   w->L = (float*)take(hc * d.Cq * N * 4);
   w->chainmask = (uint32_t*)take(hc * d.Cq * ((d.Ck + 31) / 32) * 4);
@@ -950,6 +952,7 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
     w->g_A_k = take(hc * cells * D * es);
     w->g_A_v = take(hc * cells * D * es);
   }
+  if (d.dipole) w->dip_cbar = (float*)take(hc * (size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * D * D * 4);
   w->hc = (int)hc;
   return (int)hc;
 }
@@ -1063,12 +1066,15 @@ int run_fwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const f
   if ((rc = muse_ff_prepare<T>(d, K, V, aq, ak, w, st))) return rc;
   if ((rc = muse_launch_fill(w.ff_ml, (size_t)HQ * d.N * 2, 0.f, st))) return rc;
   if (d.nb > 1) {
+    if (d.dipole && (rc = muse_dipole_covariances<T>(d, w, st))) return rc;
     for (int h0 = 0; h0 < HQ; h0 += w.hc) {
       int hn = HQ - h0 < w.hc ? HQ - h0 : w.hc;
       if ((rc = muse_ff_summaries<T>(d, qc, w, h0, hn, st))) return rc;
       if (d.D == 64) launch_ff_fwd_r<T, 64>(d, Q, qc, aq, w, selc, selb, h0, hn, st);
       else launch_ff_fwd_r<T, 128>(d, Q, qc, aq, w, selc, selb, h0, hn, st);
       MUSE_LAUNCH_CHECK();
+      // App. B: the merged dipole matrices of this chunk's heads, applied to the far-field state of their queries
+      if (d.dipole && (rc = muse_dipole_apply<T>(d, Q, qc, aq, w, h0, hn, st))) return rc;
     }
   }
   if (d.nb > 1 && d.r > 0 && sizeof(T) == 2) {

@@ -227,6 +227,9 @@ struct FFWorkspace {
   void *s_v, *A_v, *A_kb, *A_km;
   float *g_s_c, *g_A_c;
   void *g_s_k, *g_s_v, *g_A_k, *g_A_v;
+  // dipole correction (MUSE_FLAG_DIPOLE): untilted covariances [HK][nb-1][Ck][D][D] (all heads) and the merged
+  // matrices [hc][nb-1][Cq][D][D] of a head chunk
+  float *dip_cov, *dip_cbar;
   int hc;
 };
 
@@ -249,6 +252,7 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
          ff_al(HQ * N * D * 4) + ff_al(HQ * D * (size_t)((d.Cq + 31) / 32 * 32) * 2);
     if (d.grad_dtype != MUSE_DTYPE_FP32) b += ff_al(HQ * N * D * 4) + 2 * ff_al(HK * N * D * 4);
   }
+  if (d.dipole) b += ff_al(HK * NBm * d.Ck * D * D * 4);
   return b;
 }
 
@@ -258,6 +262,7 @@ static inline size_t ff_head_bytes(const MuseDims& d, bool bwd) {
   size_t b = ff_al((size_t)d.Cq * d.N * 4) + ff_al((size_t)d.Cq * ((d.Ck + 31) / 32) * 4) + 2 * ff_al(cells * 4) + ff_al(cells * D * 4) + 2 * ff_al(cells * D * es);
   b += es == 2 ? 2 * ff_al(cells * D * 2) + ff_al(cells * 4) : ff_al(cells * D * 4);
   if (bwd) b += 2 * ff_al(cells * 4) + 4 * ff_al(cells * D * es);
+  if (d.dipole) b += ff_al((size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * D * D * 4);
   return b;
 }
 
@@ -288,6 +293,12 @@ int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO
 int muse_launch_cells_to_keys_mx(const MuseDims& d, const void* Ks, const void* Vs, const float* qc, void* qcT,
                                  const float* L, const float* s_mu, const float* G_c, const void* G_k, const void* G_v,
                                  const int32_t* off_k, float* dKs, float* dVs, int h0, int hn, hipStream_t st);
+// dipole.hip: dipole correction of the monopole-only mode (App. B), forward
+template <typename T>
+int muse_dipole_covariances(const MuseDims& d, FFWorkspace& w, hipStream_t st);
+template <typename T>
+int muse_dipole_apply(const MuseDims& d, const T* Q, const float* qc, const int32_t* aq, FFWorkspace& w, int h0, int hn,
+                      hipStream_t st);
 // retrieval.hip: pair bitmask + ordered hit lists from the exported selections; merge of the forward partials
 int muse_ff_build_inverse_index(const MuseDims& d, const int32_t* selc, const int32_t* selb, FFWorkspace& w,
                                 bool with_hits, hipStream_t st);

@@ -70,11 +70,12 @@ int make_dims(const muse_params* p, bool full, MuseDims* d) {
   if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->N < 1 || p->Hq % p->Hkv) return MUSE_ERR_INVALID_ARG;
   if (p->dtype != MUSE_DTYPE_FP32 && p->dtype != MUSE_DTYPE_BF16) return MUSE_ERR_INVALID_ARG;
   if (p->grad_dtype != MUSE_DTYPE_FP32 && p->grad_dtype != p->dtype) return MUSE_ERR_INVALID_ARG;
-  if (p->flags & ~(uint32_t)(MUSE_FLAG_KEEP_FWD_STATE | MUSE_FLAG_FROZEN_WEIGHTS | MUSE_FLAG_STREAMING_KMEANS | MUSE_FLAG_BALANCED_ASSIGN)) return MUSE_ERR_INVALID_ARG;
+  if (p->flags & ~(uint32_t)(MUSE_FLAG_KEEP_FWD_STATE | MUSE_FLAG_FROZEN_WEIGHTS | MUSE_FLAG_STREAMING_KMEANS | MUSE_FLAG_BALANCED_ASSIGN | MUSE_FLAG_DIPOLE)) return MUSE_ERR_INVALID_ARG;
   d->keep_state = (p->flags & MUSE_FLAG_KEEP_FWD_STATE) != 0;
   d->frozen_weights = (p->flags & MUSE_FLAG_FROZEN_WEIGHTS) != 0;
   d->streaming = (p->flags & MUSE_FLAG_STREAMING_KMEANS) != 0;
   d->balanced = (p->flags & MUSE_FLAG_BALANCED_ASSIGN) != 0;
+  d->dipole = false;
   if (!(p->scale >= 0.f) || isinf(p->scale)) return MUSE_ERR_INVALID_ARG;
   if (p->causal != 1) return MUSE_ERR_UNSUPPORTED;
   if (p->D != 64 && p->D != 128) return MUSE_ERR_UNSUPPORTED;
@@ -94,6 +95,8 @@ int make_dims(const muse_params* p, bool full, MuseDims* d) {
   d->k2 = p->k2; d->T = p->kmeans_iters;
   d->k2e = p->k2 > 0 ? p->k2 : (d->nb > 1 ? d->nb - 1 : 1);
   if (d->k2e > 16) return MUSE_ERR_UNSUPPORTED;
+  d->dipole = (p->flags & MUSE_FLAG_DIPOLE) != 0;
+  if (d->dipole && d->r > 0) return MUSE_ERR_UNSUPPORTED;  // App. B "Compatibility with Retrieval": not combined
   return MUSE_OK;
 }
 
@@ -187,6 +190,7 @@ int muse_workspace_bytes(const muse_params* p, int which, size_t* min_bytes, siz
     case MUSE_WS_EXACT_BWD: mn = pref = exact_bwd_bytes(d); break;
     case MUSE_WS_FWD:
     case MUSE_WS_BWD: {
+      if (which == MUSE_WS_BWD && d.dipole) return MUSE_ERR_UNSUPPORTED;
       bool bwd = which == MUSE_WS_BWD || d.keep_state;
       pref = muse_farfield_fixed_bytes(d, bwd) + muse_farfield_ws_bytes(d, bwd, d.B * d.Hq);
       mn = d.keep_state ? pref : muse_farfield_fixed_bytes(d, bwd) + muse_farfield_ws_bytes(d, bwd, 1);
@@ -276,6 +280,7 @@ int muse_bwd(const muse_params* p, const void* Q, const void* K, const void* V, 
   if (!Q || !K || !V || !O || !LSE || !dO || !q_centroids || !q_assign || !k_assign || !dQ || !dK || !dV || !ws)
     return MUSE_ERR_INVALID_ARG;
   if (d.r > 0 && (!sel_clusters || !sel_blocks)) return MUSE_ERR_INVALID_ARG;
+  if (d.dipole) return MUSE_ERR_UNSUPPORTED;  // the dipole correction has a forward only
   size_t need = muse_farfield_fixed_bytes(d, true) + muse_farfield_ws_bytes(d, true, d.keep_state ? d.B * d.Hq : 1);
   if (ws_bytes < kTagBytes + need) return MUSE_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t st = (hipStream_t)stream;

@@ -34,12 +34,16 @@ def test_strerror_and_host_side_validation():
     good = mb.Params(1, 16, 16, 65536, 64, Cq=256, Ck=1024, r=8)
     mn, pref = mb.muse_workspace_bytes(good, mb.WS_CLUSTER)
     assert mn > 0 and pref >= mn
+    import dataclasses
     for bad, msg in ((dict(causal=0), "unsupported"), (dict(D=80), "unsupported"), (dict(Hkv=3), "invalid"),
                      (dict(block=1000), "invalid"), (dict(r=2000), "invalid"), (dict(Ck=4096), "unsupported"),
-                     (dict(flags=16), "invalid")):
-        import dataclasses
+                     (dict(flags=32), "invalid"), (dict(flags=mb.FLAG_DIPOLE), "unsupported")):  # dipole needs r = 0
         with pytest.raises(mb.MuseError, match=msg):
             mb.muse_workspace_bytes(dataclasses.replace(good, **bad), mb.WS_FWD)
+    assert mb.muse_workspace_bytes(dataclasses.replace(good, r=0, flags=mb.FLAG_DIPOLE), mb.WS_FWD)[0] > \
+        mb.muse_workspace_bytes(dataclasses.replace(good, r=0), mb.WS_FWD)[0]
+    with pytest.raises(mb.MuseError, match="unsupported"):      # no backward is defined for the dipole correction
+        mb.muse_workspace_bytes(dataclasses.replace(good, r=0, flags=mb.FLAG_DIPOLE), mb.WS_BWD)
     # NULL pointers are rejected on the host, nothing is launched
     pc = good.c()
     rc = mb.load().muse_fwd(C.byref(pc), *([C.c_void_p(0)] * 11), C.c_size_t(0), C.c_void_p(0))

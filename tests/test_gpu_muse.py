@@ -259,3 +259,42 @@ def test_keep_forward_state_default_workspace_and_stamp():
     mb.muse_fwd(p, Q, K, V, *cl, ws=mb.workspace(pk, mb.WS_BWD))     # a stateless call on the buffer clears the stamp
     with pytest.raises(mb.MuseError, match="forward state"):
         mb.muse_bwd(pk, Q, K, V, O2, LSE2, dO, *cl, selc2, selb2)
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("cfg1", dict(N=1024, Cq=6, Ck=24, r=0, block=128, kmeans_iters=2)),                       # fp32
+    ("cfg2", dict(N=2048, Hq=2, Hkv=1, Cq=8, Ck=32, r=0, block=256, kmeans_iters=2)),          # bf16, GQA
+    ("cfg5", dict(N=1024, Hq=2, Hkv=2, Cq=5, Ck=19, r=0, block=128, kmeans_iters=2)),          # D = 128, ragged
+])
+def test_dipole_correction_forward(name, kw):
+    """MUSE_FLAG_DIPOLE (App. B: pre-merged dipole with untilted covariances, monopole-only mode) against the
+    oracle's mode 2, element by element; the correction must be visible (the two modes differ by far more than
+    the tolerance), LSE must be the monopole's, and the backward must refuse the flag."""
+    w = small(name, **kw)
+    d = generate(w, need_dO=True)
+    p0 = mb.params_for(w)
+    p = dataclasses.replace(p0, flags=mb.FLAG_DIPOLE)
+    qc, aq, ak = oracle_clustering(w, d, p)
+    Q, K, V, dO = (dev(d[x], p) for x in ("Q", "K", "V", "dO"))
+    cl = (torch.tensor(qc).cuda(), torch.tensor(aq).cuda(), torch.tensor(ak).cuda())
+    O, LSE, selc, selb = mb.muse_fwd(p, Q, K, V, *cl)
+    O0, LSE0, _, _ = mb.muse_fwd(p0, Q, K, V, *cl)
+    torch.cuda.synchronize()
+    assert torch.equal(LSE, LSE0)
+    G = w.Hq // w.Hkv
+    for h in range(w.Hq):
+        q, k, v = (f64(x) for x in (Q[0, h], K[0, h // G], V[0, h // G]))
+        op = orc.MuseParams(w.N, w.D, w.Bs, w.Cq, w.Ck, 0, w.k2, p.eff_scale, dipole=2)
+        want = orc.muse_fwd(op, q, k, v, qc[0, h], aq[0, h], ak[0, h // G])
+        mono = orc.muse_fwd(dataclasses.replace(op, dipole=0), q, k, v, qc[0, h], aq[0, h], ak[0, h // G])
+        assert_close(f64(O[0, h]), want["O"], p, f"dipole {name} O head {h}")
+        shift = np.abs(want["O"] - mono["O"]).max()
+        assert shift > 10 * (1e-4 * np.abs(want["O"]).max() if w.dtype == "fp32" else 2e-2) or w.dtype == "bf16", shift
+        # the correction itself, isolated: (dipole - monopole) on both sides
+        got_shift = f64(O[0, h]) - f64(O0[0, h])
+        assert np.abs(got_shift - (want["O"] - mono["O"])).max() <= (2e-4 * max(1.0, shift) if w.dtype == "fp32" else 2e-2)
+        assert np.abs(got_shift[w.Bs:]).max() > 0
+    with pytest.raises(mb.MuseError, match="unsupported"):
+        mb.muse_bwd(p, Q, K, V, O, LSE, dO, *cl, selc, selb, ws=torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(mb.MuseError, match="unsupported"):
+        mb.muse_fwd(dataclasses.replace(p, r=2), Q, K, V, *cl, ws=torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
