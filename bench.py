@@ -81,6 +81,19 @@ def kernel_models(w, p):
     return m
 
 
+def algorithmic_bytes(w):
+    """What the METHOD must move per launch, whatever the kernel does (bf16 storage of the summaries, fp32 log-mass):
+    the tile kernel (cluster scores, top-r and monopole values) reads the accumulated summaries once,
+    Cq Ck (nb-1) (2 D 2 + 4) bytes per head; the summary kernel writes the summaries once, Cq Ck nb (2 D 2 + 4)
+    bytes per head.  The kernels' own byte models (kernel_models) count what THEY stream: a second plane of the
+    key summaries that keeps the selection reproducible, a second pass over them, fp32 scalars; measured traffic
+    above these figures is what a better kernel could still save."""
+    H, D, Cq, Ck = w.B * w.Hq, w.D, w.Cq, w.Ck
+    nb = w.N // w.Bs
+    cell = 2 * D * 2 + 4
+    return {"k_farfield_fwd": Cq * Ck * (nb - 1) * cell * H, "k_summaries": Cq * Ck * nb * cell * H}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,6 +115,7 @@ def main():
     ap.add_argument("--serial-streams", action="store_true",
                     help="run every stage on one stream (as the per-kernel timing pass does): for kernel profiles")
     ap.add_argument("--ws-gib", type=float, default=0.0, help="cap of the backward workspace (0 = all heads at once)")
+    ap.add_argument("--no-variants", action="store_true", help="skip the extra workloads reported under `variants`")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (every stage is independent per head, so more GPUs would each take "
@@ -157,6 +171,13 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n
 
+    def each(fn, n):
+        """n separately timed calls (a device synchronisation around each): for the spread."""
+        out = []
+        for _ in range(n):
+            out.append(timed(fn, 1))
+        return out
+
     for _ in range(a.warmup):
         step()
     ms_step = timed(step, a.steps)
@@ -176,8 +197,11 @@ def main():
         Oe, Le = mb.exact_attn_fwd(p, Q, K, V, out=eo)
         mb.exact_attn_bwd(p, Q, K, V, Oe, Le, dO, ws=ws_e, out=go)
 
-    exact()
-    ms_exact = timed(exact, 2)
+    for _ in range(max(a.warmup, 1)):
+        exact()
+    ms_exact = timed(exact, a.steps)                 # same steps and warm-up as the MuSe step
+    sp_exact = each(exact, min(a.steps, 5))
+    sp_step = each(step, min(a.steps, 5))
     Oe = eo[0].float()
     rse = (((O.float() - Oe) ** 2).sum(-1) / (Oe ** 2).sum(-1).clamp_min(1e-30)).mean().item()
     # MuSe at the same selections must not have been disturbed by the exact run (go was reused): fine.
@@ -197,19 +221,27 @@ def main():
     if dom == "k_assign_bf16":   # launched for queries (Cq) and keys (Ck): per-launch work is the mean of the two
         amount = amount * (w.Cq * w.Hq + w.Ck * w.Hkv) / (2 * w.Ck * w.Hkv)
     avg_s = tms / cnt * 1e-3
+    alg = algorithmic_bytes(w)
+    own = amount                      # the kernel's own model of what it streams / computes
+    if dom in alg:
+        amount = alg[dom]             # the method's bytes: what `achieved` and `frac` are quoted on
     ach = amount / avg_s
     roofline = {"kernel": dom, "bound": bound, "achieved": ach / (1e12 if unit == "flop" else 1e9),
                 "peak": peak / (1e12 if unit == "flop" else 1e9), "unit": "TFLOP/s" if unit == "flop" else "GB/s",
-                "frac": ach / peak, "traffic": measured_traffic(dom, a.workload), "avg_launch_ms": tms / cnt, "launches_per_step": cnt / nprof,
-                "share_of_step": tms / tot}
+                "frac": ach / peak, "traffic": measured_traffic(dom, a.workload),
+                "traffic_source": f"profiles/hbm_traffic_{a.workload}.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of "
+                                  "the committed code, not measured in this run)",
+                "algorithmic_amount": amount, "kernel_model_amount": own, "frac_of_kernel_model": own / avg_s / peak,
+                "avg_launch_ms": tms / cnt, "launches_per_step": cnt / nprof, "share_of_step": tms / tot}
     breakdown = {k: round(v[1] / nprof, 3) for k, v in sorted(prof.items(), key=lambda kv: -kv[1][1])}
-    fracs = {}
+    fracs, fracs_own = {}, {}
     for k, (c, t) in prof.items():
         if k in models and models[k][2]:
             amt = models[k][2]
             if k == "k_assign_bf16":
                 amt = amt * (w.Cq * w.Hq + w.Ck * w.Hkv) / (2 * w.Ck * w.Hkv)
-            fracs[k] = round(amt / (t / c * 1e-3) / models[k][1], 4)
+            fracs_own[k] = round(amt / (t / c * 1e-3) / models[k][1], 4)
+            fracs[k] = round(alg.get(k, amt) / (t / c * 1e-3) / models[k][1], 4)
 
     eff_flops = 7.0 * w.N * w.N * w.D * w.B * w.Hq
     out = {
@@ -222,7 +254,8 @@ def main():
                    "step": "muse_cluster + muse_fwd + muse_bwd" + (" (frozen aggregation weights)" if a.frozen_weights else "") +
                            (" (streaming K-means)" if a.streaming_kmeans else "") +
                            (" (balanced assignment)" if a.balanced_assign else "")},
-        "ms": {"cluster": ms_cluster, "fwd": ms_fwd, "bwd": ms_bwd, "exact_attn_fwd_bwd": ms_exact},
+        "ms": {"cluster": ms_cluster, "fwd": ms_fwd, "bwd": ms_bwd, "exact_attn_fwd_bwd": ms_exact,
+               "step_min_max": [min(sp_step), max(sp_step)], "exact_min_max": [min(sp_exact), max(sp_exact)]},
         "effective_attention_tflops": eff_flops / (ms_step * 1e-3) / 1e12,
         "frac_of_bf16_mfma_peak_effective": eff_flops / (ms_step * 1e-3) / PEAK["mfma_bf16"],
         "speedup_vs_own_exact": ms_exact / ms_step,
@@ -230,13 +263,52 @@ def main():
         "rse_vs_exact": rse,
         "roofline": roofline,
         "kernel_ms_per_step": breakdown,
-        "kernel_frac_of_peak": fracs,
+        "kernel_frac_of_peak": fracs,                     # far-field kernels: the method's bytes (algorithmic_bytes)
+        "kernel_frac_of_peak_own_model": fracs_own,       # every kernel: the bytes / flops its own design moves
         "paper_context": "paper: MuSe 114.1 ms vs cuDNN flash 225.6 ms (1.98x) for 16 head-sequences per A100 80GB at "
                          "Q128 K128 R8, another workload and machine",
     }
+    if a.workload == "cfg3" and not a.no_variants:
+        # the paper's operating ratio (Sec. 3.3 "Complexity": clusters = N / 512) at the same shape, so the same
+        # exact-attention time applies; not the headline
+        ms_v, wv = time_variant("cfg3_qk128", a.steps, a.warmup)
+        out["variants"] = {"cfg3_qk128": {
+            "workload": f"B={wv.B} Hq={wv.Hq} Hkv={wv.Hkv} N={wv.N} D={wv.D} Cq={wv.Cq} Ck={wv.Ck} r={wv.r} k2={wv.k2} "
+                        f"block={wv.Bs} kmeans_iters={wv.kmeans_iters}",
+            "ms_per_step": ms_v, "exact_attn_fwd_bwd_ms": ms_exact, "speedup_vs_own_exact": ms_exact / ms_v}}
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, d, p)
     print(json.dumps(out))
+
+
+def time_variant(name, steps, warmup):
+    """cluster + fwd + bwd of another named workload, timed like the headline step (own buffers; returns ms)."""
+    import torch
+
+    from paper_2509_10406_amd import binding as mb
+    from paper_2509_10406_amd.inputs import CONFIGS, generate
+
+    w = CONFIGS[name]
+    d = generate(w, need_dO=True)
+    p = mb.params_for(w, flags=mb.FLAG_KEEP_FWD_STATE)
+    Q, K, V, dO = (d[x].to(p.torch_dtype).cuda().contiguous() for x in ("Q", "K", "V", "dO"))
+    qi, ki = d["q_init_idx"].cuda(), d["k_init_idx"].cuda()
+    ws_c = torch.empty(mb.muse_workspace_bytes(p, mb.WS_CLUSTER)[1], dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(mb.muse_workspace_bytes(p, mb.WS_BWD)[1], dtype=torch.uint8, device="cuda")
+
+    def step():
+        qc, qa, _, ka = mb.muse_cluster(p, Q, K, qi, ki, ws=ws_c)
+        O, LSE, selc, selb = mb.muse_fwd(p, Q, K, V, qc, qa, ka, ws=ws_b)
+        mb.muse_bwd(p, Q, K, V, O, LSE, dO, qc, qa, ka, selc, selb, ws=ws_b)
+
+    for _ in range(max(warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps, w
 
 
 def measured_traffic(kernel, workload):
