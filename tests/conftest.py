@@ -31,6 +31,9 @@ def pytest_terminal_summary(terminalreporter):
         kind = " ".join(w for w in what.split() if not w.isdigit() and w != "head")
         if kind not in worst or e > worst[kind][0]:
             worst[kind] = (e, mx)
+    if os.environ.get("MUSE_TEST_ALL_ERRORS"):   # every comparison, not only the worst of its kind
+        for what, e, mx in ERRORS:
+            terminalreporter.write_line(f"  each: {what:44s} {e:.3e}  {mx:.3g}")
     terminalreporter.write_line("parity errors (max abs err, max|want|), worst per comparison kind:")
     for kind in sorted(worst):
         terminalreporter.write_line(f"  {kind:40s} {worst[kind][0]:.3e}  {worst[kind][1]:.3g}")
