@@ -5,8 +5,11 @@
 // (cluster, block) pairs.  The result is a partial softmax state (max, sum, acc) per query that the
 // block-diagonal attention kernel merges with the local part (Sec. 3.3 "Output merging").
 //
-// All summary arithmetic and every score that decides a selection is fp32 (fp32 MFMA for the
-// contractions), so the discrete choices agree with an fp64 evaluation up to fp32 rounding.
+// Summary arithmetic is fp32, and every score that decides a selection keeps fp32-like precision, so the
+// discrete choices agree with an fp64 evaluation at a 1e-5 margin: fp32 inputs score on fp32 MFMA; bf16 inputs
+// score the exact bf16 query against the accumulated key summary split into a bf16 plane plus an fp16 plane of
+// the remainder (>= 19 significant bits, exact products, fp32 accumulation) on the 16-bit matrix cores, and the
+// block selection scores stay fp32.
 #include "ff_common.h"
 
 #include <type_traits>
