@@ -668,22 +668,32 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 // inverse index: pair -> queries); they are gathered 32 at a time into LDS and the pair is treated as a
 // dense attention-backward block on the matrix cores, the keys of the pair being the MFMA columns.
 //   hit = n | g << 22  (query position, query head inside the KV group)
-// Results are added to the bucketed-order gradient rows this wave owns.
+// A pair with many hits (at the operating ratio of Sec. 3.3 a pair has some 500, with a heavy tail) is shared by
+// up to kC3Slices waves: slice s of S takes the hit tiles s, s + S, ...; slice 0 adds to the bucketed-order gradient
+// rows of the pair's keys, the others write partial rows, which k_c3_reduce adds in slice order (fixed order, no
+// atomics).  S depends on the pair's hit count only.
 // ------------------------------------------------------------------------------------------
+__device__ __forceinline__ int c3_slices(int nhits) {
+  const int nt = (nhits + 31) / 32;
+  const int s = nt / kC3TilesPerSlice;
+  return s < 1 ? 1 : (s > kC3Slices ? kC3Slices : s);
+}
+
 template <int D>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, D == 64 ? 2 : 1))) k_c3_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
                                                   const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
                                                   const float* __restrict__ LSE, const float* __restrict__ delta,
                                                   const int32_t* __restrict__ off_k, const int32_t* __restrict__ pair_off,
                                                   const uint2* __restrict__ hits, float* __restrict__ dKs,
-                                                  float* __restrict__ dVs, size_t hit_cap, int N, int nb, int Ck,
-                                                  int Hq, int Hkv, float scale, float scale_log2e) {
-  constexpr int KS = D / 16, DT = D / 32, CPR = D / 8;
+                                                  float* __restrict__ dVs, float* __restrict__ part, size_t hit_cap,
+                                                  int N, int nb, int Ck, int Hq, int Hkv, int HK, float scale,
+                                                  float scale_log2e) {
+  constexpr int KS = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(16))) bf16_t qt_[D][32 + TPAD];
   __shared__ __attribute__((aligned(16))) bf16_t gt_[D][32 + TPAD];
   __shared__ __attribute__((aligned(16))) float lse_s[32];
   __shared__ __attribute__((aligned(16))) float dl_s[32];
-  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
+  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z % HK, sl = blockIdx.z / HK, NBm = nb - 1;
   const int G_ = Hq / Hkv;
   const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
   const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
@@ -692,6 +702,10 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
   const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
   const int hlo = po[0], hhi = po[1];
   if (klo == khi || hlo == hhi) return;
+  const int S = c3_slices(hhi - hlo);
+  if (sl >= S) return;
+  const int step = 32 * S, hfirst = hlo + 32 * sl;  // this slice's hit tiles start at hfirst, hfirst + step, ...
+  if (hfirst >= hhi) return;
   const uint2* hh = hits + (size_t)hk * hit_cap;
   for (int k0 = klo; k0 < khi; k0 += 32) {
     const int mk = k0 + col;
@@ -786,37 +800,68 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
     };
     if constexpr (D == 64) {
       HT ta, tb;
-      gather(ta, hlo);
-      for (int h0 = hlo; h0 < hhi; h0 += 64) {
-        gather(tb, h0 + 32);
+      gather(ta, hfirst);
+      for (int h0 = hfirst; h0 < hhi; h0 += 2 * step) {
+        gather(tb, h0 + step);
         use(ta, h0);
-        if (h0 + 32 < hhi) {
-          gather(ta, h0 + 64);
-          use(tb, h0 + 32);
+        if (h0 + step < hhi) {
+          gather(ta, h0 + 2 * step);
+          use(tb, h0 + step);
         }
       }
     } else {  // two buffers do not fit the registers at D = 128
-      for (int h0 = hlo; h0 < hhi; h0 += 32) {
+      for (int h0 = hfirst; h0 < hhi; h0 += step) {
         HT ta;
         gather(ta, h0);
         use(ta, h0);
       }
     }
     if (kvalid) {
+      // slice 0 owns the gradient rows; a later slice leaves its share in its own partial rows [dK | dV]
+      float* pk = sl == 0 ? dKs + ((size_t)hk * N + mk) * D : part + ((((size_t)(sl - 1) * HK + hk) * N + mk) * 2) * D;
+      float* pv = sl == 0 ? dVs + ((size_t)hk * N + mk) * D : pk + D;
 #pragma unroll
       for (int t = 0; t < DT; ++t)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const size_t o = ((size_t)hk * N + mk) * D + 32 * t + 8 * g + 4 * half;
-          float4 a = *reinterpret_cast<float4*>(dKs + o), c = *reinterpret_cast<float4*>(dVs + o);
+          const int o = 32 * t + 8 * g + 4 * half;
+          float4 a = make_float4(0.f, 0.f, 0.f, 0.f), c = a;
+          if (sl == 0) { a = *reinterpret_cast<float4*>(pk + o); c = *reinterpret_cast<float4*>(pv + o); }
           a.x += scale * dk[t][4 * g + 0]; a.y += scale * dk[t][4 * g + 1];
           a.z += scale * dk[t][4 * g + 2]; a.w += scale * dk[t][4 * g + 3];
           c.x += dv[t][4 * g + 0]; c.y += dv[t][4 * g + 1]; c.z += dv[t][4 * g + 2]; c.w += dv[t][4 * g + 3];
-          *reinterpret_cast<float4*>(dKs + o) = a;
-          *reinterpret_cast<float4*>(dVs + o) = c;
+          *reinterpret_cast<float4*>(pk + o) = a;
+          *reinterpret_cast<float4*>(pv + o) = c;
         }
     }
   }
+}
+
+// adds the partial rows of the hit slices 1 .. S-1 of every pair to the rows slice 0 owns, in slice order: one wave per
+// (key cluster, key block, kv head), 16 lanes per key row
+template <int D>
+__global__ void __launch_bounds__(64) k_c3_reduce(const int32_t* __restrict__ off_k, const int32_t* __restrict__ pair_off,
+                                                   const float* __restrict__ part, float* __restrict__ dKs,
+                                                   float* __restrict__ dVs, int N, int nb, int Ck, int HK) {
+  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
+  const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
+  const int S = c3_slices(po[1] - po[0]);
+  if (po[1] == po[0] || S == 1) return;
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
+  const int lane = threadIdx.x, sub = lane / 16, l16 = lane % 16;
+  for (int m = klo + sub; m < khi; m += 4)
+    for (int d = 4 * l16; d < 2 * D; d += 64) {  // the row pair [dK | dV] as 2 D floats
+      float* dst = (d < D ? dKs : dVs - D) + ((size_t)hk * N + m) * D + d;
+      float4 a = *reinterpret_cast<float4*>(dst);
+      for (int s = 1; s < S; ++s) {
+        // a slice that got no hit tile wrote nothing
+        if (po[0] + 32 * s >= po[1]) break;
+        const float4 x = *reinterpret_cast<const float4*>(part + ((((size_t)(s - 1) * HK + hk) * N + m) * 2) * D + d);
+        a.x += x.x; a.y += x.y; a.z += x.z; a.w += x.w;
+      }
+      *reinterpret_cast<float4*>(dst) = a;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1464,15 +1509,19 @@ int muse_launch_ret_bwd_dq_pairs(const MuseDims& d, const void* Q, const void* d
 
 int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
                          const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
-                         const uint2* hits, size_t hit_cap, float* dKs, float* dVs, hipStream_t st) {
-  dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv);
+                         const uint2* hits, size_t hit_cap, float* dKs, float* dVs, float* part, hipStream_t st) {
+  const int HK = d.B * d.Hkv;
+  dim3 g(d.Ck, d.nb - 1, HK * kC3Slices), gr(d.Ck, d.nb - 1, HK);
   float sl = d.scale * 1.4426950408889634f;
-  if (d.D == 64)
+  if (d.D == 64) {
     { MuseProf prof_("k_c3_pairs", st); hipLaunchKernelGGL(k_c3_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks,
-                       (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dKs, dVs, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.scale, sl); }
-  else
+                       (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dKs, dVs, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, HK, d.scale, sl); }
+    { MuseProf prof_("k_c3_reduce", st); hipLaunchKernelGGL(k_c3_reduce<64>, gr, dim3(64), 0, st, off_k, pair_off, part, dKs, dVs, d.N, d.nb, d.Ck, HK); }
+  } else {
     { MuseProf prof_("k_c3_pairs", st); hipLaunchKernelGGL(k_c3_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks,
-                       (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dKs, dVs, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.scale, sl); }
+                       (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dKs, dVs, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, HK, d.scale, sl); }
+    { MuseProf prof_("k_c3_reduce", st); hipLaunchKernelGGL(k_c3_reduce<128>, gr, dim3(64), 0, st, off_k, pair_off, part, dKs, dVs, d.N, d.nb, d.Ck, HK); }
+  }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }

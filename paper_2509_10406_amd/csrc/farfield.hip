@@ -921,6 +921,8 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
     w->dVs = (float*)take(HK * N * D * 4);
     w->dQff = (float*)take(HQ * N * D * 4);
     w->qcT = take(HQ * D * (size_t)((d.Cq + 31) / 32 * 32) * 2);
+    w->c3_part = nullptr;
+    if (es == 2 && d.r > 0 && d.nb > 1) w->c3_part = (float*)take((size_t)(kC3Slices - 1) * HK * N * 2 * D * 4);
     if (d.grad_dtype != MUSE_DTYPE_FP32) {
       w->dQacc = (float*)take(HQ * N * D * 4);
       w->dKacc = (float*)take(HK * N * D * 4);

@@ -1275,7 +1275,7 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
         if ((rc = muse_ff_build_inverse_index(d, selc, selb, w, sizeof(T) == 2, st))) return rc;
       if (sizeof(T) == 2) {
         if ((rc = muse_launch_c3_pairs(d, Q, dO, w.Ks, w.Vs, LSE, w.delta, w.off_k, w.pair_off, w.hits, w.hit_cap, w.dKs,
-                                       w.dVs, st)))
+                                       w.dVs, w.c3_part, st)))
           return rc;
         if (split) {
           MUSE_HIP_CHECK(hipEventRecord(ax.mid, st));

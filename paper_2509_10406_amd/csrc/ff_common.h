@@ -196,6 +196,8 @@ __device__ __forceinline__ bf16x8_t cvt8(const float* __restrict__ p) {
 constexpr int kMaxCk = 2304;  // key clusters a kernel can index in LDS
 static_assert(kMaxCk >= MUSE_MAX_CLUSTERS, "the host accepts more clusters than the kernels index");
 constexpr int kHitSeg = 8;  // query-range slices per (pair, head) when the hit lists are built
+constexpr int kC3Slices = 8;  // most waves that share the hits of one retrieved pair in the key/value gradients
+constexpr int kC3TilesPerSlice = 4;  // a pair gets one slice per so many tiles of 32 hits
 
 struct FFWorkspace {
   // all heads
@@ -213,6 +215,7 @@ struct FFWorkspace {
   size_t hit_cap;                // hits per kv head
   float* ret_part;               // per (query, slot, u): forward partial state [acc D | max | sum | pad2], or dq partial [D]
   float *dKs, *dVs;            // fp32 gradients in bucketed key order
+  float* c3_part;              // bf16 inputs, r > 0: [kC3Slices - 1][HK][N][2][D] partial dK | dV rows of the later hit slices of a pair
   float *dQacc, *dKacc, *dVacc;  // fp32 gradients in sequence order (alias the outputs when they are fp32)
   float* dQff;                   // far-field part of dQ, added to dQacc once the block-diagonal backward has finished
   void* qcT;                     // bf16 [hc][D][Cq padded to 32]: scaled query centroids of a head chunk, transposed
@@ -251,6 +254,7 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
     b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + ff_al(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * 4) + 2 * ff_al(HK * N * D * 4) +
          ff_al(HQ * N * D * 4) + ff_al(HQ * D * (size_t)((d.Cq + 31) / 32 * 32) * 2);
     if (d.grad_dtype != MUSE_DTYPE_FP32) b += ff_al(HQ * N * D * 4) + 2 * ff_al(HK * N * D * 4);
+    if (es == 2 && d.r > 0 && d.nb > 1) b += ff_al((size_t)(kC3Slices - 1) * HK * N * 2 * D * 4);
   }
   if (d.dipole) b += ff_al(HK * NBm * d.Ck * D * D * 4);
   return b;
@@ -280,7 +284,7 @@ int muse_ff_block_summaries(const MuseDims& d, const int32_t* selc, const int32_
 // attn_mfma.hip
 int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
                          const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
-                         const uint2* hits, size_t hit_cap, float* dKs, float* dVs, hipStream_t st);
+                         const uint2* hits, size_t hit_cap, float* dKs, float* dVs, float* part, hipStream_t st);
 int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, const void* Vs, const int32_t* off_k,
                               const int32_t* pair_off, const uint2* hits, size_t hit_cap, float* part, hipStream_t st);
 int muse_launch_ret_bwd_dq_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,

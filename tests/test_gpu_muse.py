@@ -67,9 +67,11 @@ def as_sets(sel):
 # it off the code path it is there for: pair_keys = keys of the largest RETRIEVED (cluster, block) pair (the
 # pair kernels tile keys by 32); group = queries of the largest (block, query cluster) group (the tile kernels
 # take 32 per wave, the cell-gradient kernel stages 96 per pass at D = 64 and 32 at D = 128).
+# pair_hits = (query, slot) entries of the most retrieved pair of a KV head (all query heads of the group): the
+# key/value-gradient kernel of the retrieval shares a pair among several waves from 8 tiles of 32 hits on.
 REACH = {
-    "bf16_pairs64": dict(pair_keys=65, group=97),
-    "bf16_pairs64_k2all": dict(pair_keys=65, group=97),
+    "bf16_pairs64": dict(pair_keys=65, group=97, pair_hits=512),
+    "bf16_pairs64_k2all": dict(pair_keys=65, group=97, pair_hits=1024),
     "bf16_groups200": dict(pair_keys=33, group=193),
     "bf16_d128_pairs40": dict(pair_keys=33, group=65),
 }
@@ -115,7 +117,8 @@ def run_case(name, with_bwd, frozen_weights=False, flags=0):
     G = w.Hq // w.Hkv
     selc_h, selb_h = selc.cpu().numpy()[0], selb.cpu().numpy()[0]
     wantK = np.zeros((w.Hkv, w.N, w.D)); wantV = np.zeros((w.Hkv, w.N, w.D))
-    reach = dict(pair_keys=0, group=0)
+    reach = dict(pair_keys=0, group=0, pair_hits=0)
+    hits = np.zeros((w.Hkv, max(w.N // w.Bs, 1), w.Ck), np.int64)
     for h in range(w.Hq):
         q, k, v, g = (f64(x) for x in (Q[0, h], K[0, h // G], V[0, h // G], dO[0, h]))
         sc = selc_h[h][:, : w.r]
@@ -131,6 +134,7 @@ def run_case(name, with_bwd, frozen_weights=False, flags=0):
             keys = segment_sizes(ak[0, h // G], w.Bs, w.Ck)
             ok = (sc[:, :, None] >= 0) & (sb >= 0)
             if ok.any():
+                np.add.at(hits[h // G], (sb[ok], np.broadcast_to(sc[:, :, None], sb.shape)[ok]), 1)
                 reach["pair_keys"] = max(reach["pair_keys"], int(keys[sb[ok], np.broadcast_to(sc[:, :, None], sb.shape)[ok]].max()))
         if w.N > w.Bs:
             reach["group"] = max(reach["group"], int(segment_sizes(aq[0, h], w.Bs, w.Cq)[1:].max()))
@@ -140,6 +144,7 @@ def run_case(name, with_bwd, frozen_weights=False, flags=0):
         if with_bwd:
             assert_close(f64(dQ[0, h]), grads[0], p, f"{name} dQ head {h}", grad=True)
             wantK[h // G] += grads[1]; wantV[h // G] += grads[2]
+    reach["pair_hits"] = int(hits.max())
     for what, least in REACH.get(name, {}).items():
         assert reach[what] >= least, f"{name} no longer reaches {what} >= {least}: {reach}"
     if with_bwd:
