@@ -531,11 +531,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   for (int t = 0; t < DT; ++t)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      float* p = dQ + (qh + nq) * D + 32 * t + 8 * g + 4 * half;
-      float4 old = *reinterpret_cast<float4*>(p);
-      old.x += scale * dq[t][4 * g + 0]; old.y += scale * dq[t][4 * g + 1];
-      old.z += scale * dq[t][4 * g + 2]; old.w += scale * dq[t][4 * g + 3];
-      *reinterpret_cast<float4*>(p) = old;
+      // every query row belongs to exactly one tile: the row is written, not added to
+      *reinterpret_cast<float4*>(dQ + (qh + nq) * D + 32 * t + 8 * g + 4 * half) =
+          make_float4(scale * dq[t][4 * g + 0], scale * dq[t][4 * g + 1], scale * dq[t][4 * g + 2], scale * dq[t][4 * g + 3]);
     }
 }
 
@@ -652,13 +650,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   for (int t = 0; t < DT; ++t)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
+      // every key row belongs to exactly one tile (the query heads of the group are summed in registers)
       size_t o = (kh + mk) * D + 32 * t + 8 * g + 4 * half;
-      float4 a = *reinterpret_cast<float4*>(dK + o), c = *reinterpret_cast<float4*>(dV + o);
-      a.x += scale * dk[t][4 * g + 0]; a.y += scale * dk[t][4 * g + 1];
-      a.z += scale * dk[t][4 * g + 2]; a.w += scale * dk[t][4 * g + 3];
-      c.x += dv[t][4 * g + 0]; c.y += dv[t][4 * g + 1]; c.z += dv[t][4 * g + 2]; c.w += dv[t][4 * g + 3];
-      *reinterpret_cast<float4*>(dK + o) = a;
-      *reinterpret_cast<float4*>(dV + o) = c;
+      *reinterpret_cast<float4*>(dK + o) =
+          make_float4(scale * dk[t][4 * g + 0], scale * dk[t][4 * g + 1], scale * dk[t][4 * g + 2], scale * dk[t][4 * g + 3]);
+      *reinterpret_cast<float4*>(dV + o) = make_float4(dv[t][4 * g + 0], dv[t][4 * g + 1], dv[t][4 * g + 2], dv[t][4 * g + 3]);
     }
 }
 

@@ -280,8 +280,15 @@ int muse_launch_delta(const MuseDims& d, const void* O, const void* dO, float* d
 int muse_launch_attn_bwd(const MuseDims& d, int Bs, const void* Q, const void* K, const void* V,
                          const void* dO, const float* LSE, const float* delta, float* dQacc,
                          float* dKacc, float* dVacc, hipStream_t st) {
-  if (d.dtype == MUSE_DTYPE_BF16)
+  if (d.dtype == MUSE_DTYPE_BF16)  // the matrix-core kernels write every row once
     return muse_launch_attn_bwd_mfma(d, Bs, Q, K, V, dO, LSE, delta, dQacc, dKacc, dVacc, st);
+  {  // the fp32 kernels add to their rows
+    const size_t q = (size_t)d.B * d.Hq * d.N * d.D, k = (size_t)d.B * d.Hkv * d.N * d.D;
+    int rc;
+    if ((rc = muse_launch_fill(dQacc, q, 0.f, st)) || (rc = muse_launch_fill(dKacc, k, 0.f, st)) ||
+        (rc = muse_launch_fill(dVacc, k, 0.f, st)))
+      return rc;
+  }
   dim3 gq((d.N + 63) / 64, d.Hq, d.B), gk((d.N + 63) / 64, d.Hkv, d.B);
   const float *q = (const float*)Q, *k = (const float*)K, *v = (const float*)V, *g = (const float*)dO;
   if (d.D == 64) {

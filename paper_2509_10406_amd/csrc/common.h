@@ -221,8 +221,7 @@ int muse_launch_attn_fwd(const MuseDims& d, int Bs, const void* Q, const void* K
                          const float* ff, void* O, float* LSE, hipStream_t st);
 // delta [B,Hq,N] = dO . O
 int muse_launch_delta(const MuseDims& d, const void* O, const void* dO, float* delta, hipStream_t st);
-// dQacc [B,Hq,N,D], dKacc, dVacc [B,Hkv,N,D] fp32: += contribution (buffers hold the far-field part
-// or zeros on entry).
+// dQacc [B,Hq,N,D], dKacc, dVacc [B,Hkv,N,D] fp32: overwritten with the gradients of this attention.
 int muse_launch_attn_bwd(const MuseDims& d, int Bs, const void* Q, const void* K, const void* V,
                          const void* dO, const float* LSE, const float* delta, float* dQacc,
                          float* dKacc, float* dVacc, hipStream_t st);

@@ -1235,7 +1235,7 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
   if (!reuse && (rc = muse_ff_prepare<T>(d, K, V, aq, ak, w, st))) return rc;
   if ((rc = muse_launch_delta(d, O, dO, w.delta, st))) return rc;
   // the block-diagonal backward (matrix-core bound) runs beside the far field (memory bound) on a second
-  // stream; it starts from zero and the far-field results are added after the join
+  // stream; it writes the accumulators and the far-field results are added after the join
   MuseAux& ax = muse_aux_stream();
   const bool two = ax.state == 1 && !muse_profiling();
   hipStream_t sb = two ? ax.s : st;
@@ -1251,9 +1251,6 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
     MUSE_HIP_CHECK(hipStreamWaitEvent(sb, ax.fork, 0));
     guard.armed = true;
   }
-  if ((rc = muse_launch_fill(w.dQacc, nq * D, 0.f, sb))) return rc;
-  if ((rc = muse_launch_fill(w.dKacc, nk * D, 0.f, sb))) return rc;
-  if ((rc = muse_launch_fill(w.dVacc, nk * D, 0.f, sb))) return rc;
   if ((rc = muse_launch_attn_bwd(d, d.Bs, Q, K, V, dO, LSE, w.delta, w.dQacc, w.dKacc, w.dVacc, sb))) return rc;
   // With all heads in one chunk the far-field part of dQ follows on the second stream (it needs the selection
   // info and the inverse index, which the first stream builds: event `mid`), beside the cell gradients.

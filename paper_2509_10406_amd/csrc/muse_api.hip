@@ -325,9 +325,6 @@ int exact_attn_bwd(const muse_params* p, const void* Q, const void* K, const voi
     ak = (float*)w; w += al(k * d.D * 4);
     av = (float*)w;
   }
-  if ((rc = muse_launch_fill(aq, q * d.D, 0.f, st))) return rc;
-  if ((rc = muse_launch_fill(ak, k * d.D, 0.f, st))) return rc;
-  if ((rc = muse_launch_fill(av, k * d.D, 0.f, st))) return rc;
   if ((rc = muse_launch_delta(d, O, dO, delta, st))) return rc;
   if ((rc = muse_launch_attn_bwd(d, d.N, Q, K, V, dO, LSE, delta, aq, ak, av, st))) return rc;
   if (!direct) {
