@@ -227,6 +227,15 @@ int exact_attn_bwd_static(const muse_params* p, const void* Q, const void* K, co
 int muse_profile_enable(int on);
 int muse_profile_report(char* buf, size_t cap);
 
+/* Measurement aid (not part of the method; synchronises `stream`, creates and destroys two HIP events): runs a
+ * plain streaming copy of the first half of the DEVICE buffer buf (bytes >= 1 GiB, 256-byte aligned, contents
+ * overwritten) into its second half, and a loop of independent bf16 MFMA 32x32x16 instructions on every SIMD, five
+ * times each, and reports the best: *copy_gbps = bytes read plus bytes written per second / 1e9, *mfma_bf16_tflops =
+ * 2 x 32 x 32 x 16 flop per instruction / 1e12 (HOST pointers).  These are what the device delivers to the simplest
+ * kernel of each kind, to set beside the published peaks.  INVALID_ARG for null or misaligned pointers,
+ * WORKSPACE_TOO_SMALL below 1 GiB. */
+int muse_probe_peaks(void* buf, size_t bytes, double* copy_gbps, double* mfma_bf16_tflops, void* stream);
+
 /* Static, NUL-terminated description of a return code. */
 const char* muse_strerror(int code);
 

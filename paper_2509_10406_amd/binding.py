@@ -25,7 +25,7 @@ FLAG_BALANCED_ASSIGN = 8
 FLAG_DIPOLE = 16
 WS_CLUSTER, WS_FWD, WS_BWD, WS_EXACT_FWD, WS_EXACT_BWD = range(5)
 SYMBOLS = ["muse_workspace_bytes", "muse_cluster", "muse_kmeans_stream", "muse_fwd", "muse_bwd", "exact_attn_fwd", "exact_attn_bwd",
-           "exact_attn_bwd_static", "muse_profile_enable", "muse_profile_report", "muse_strerror"]
+           "exact_attn_bwd_static", "muse_profile_enable", "muse_profile_report", "muse_probe_peaks", "muse_strerror"]
 STATIC_SCRATCH_BYTES = 64 << 20
 
 
@@ -280,6 +280,15 @@ def muse_profile_report() -> dict:
         name, cnt, ms = line.split()
         out[name] = (int(cnt), float(ms))
     return out
+
+
+def muse_probe_peaks(buf) -> dict:
+    """{"copy_GBps", "mfma_bf16_TFLOPs"}: what a plain copy inside the device tensor `buf` (>= 1 GiB, overwritten) and
+    a loop of independent bf16 MFMAs reach on this device."""
+    gbps, tfl = C.c_double(0.0), C.c_double(0.0)
+    _check(load().muse_probe_peaks(_ptr(buf), C.c_size_t(buf.numel() * buf.element_size()), C.byref(gbps), C.byref(tfl),
+                                   _stream()), "muse_probe_peaks")
+    return {"copy_GBps": gbps.value, "mfma_bf16_TFLOPs": tfl.value}
 
 
 def params_for(w, **kw) -> Params:

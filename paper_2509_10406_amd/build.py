@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmuse.so")
-SOURCES = ["muse_api.hip", "kmeans.hip", "attn_simple.hip", "attn_mfma.hip", "farfield.hip", "farfield_bwd.hip", "retrieval.hip", "dipole.hip"]
+SOURCES = ["muse_api.hip", "kmeans.hip", "attn_simple.hip", "attn_mfma.hip", "farfield.hip", "farfield_bwd.hip", "retrieval.hip", "dipole.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

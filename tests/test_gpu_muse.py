@@ -303,3 +303,19 @@ def test_dipole_correction_forward(name, kw):
         mb.muse_bwd(p, Q, K, V, O, LSE, dO, *cl, selc, selb, ws=torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
     with pytest.raises(mb.MuseError, match="unsupported"):
         mb.muse_fwd(dataclasses.replace(p, r=2), Q, K, V, *cl, ws=torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
+
+
+def test_probe_peaks_copy_is_exact_and_rates_are_plausible():
+    """The measurement aid really copies (second half == first half afterwards) and reports rates between a tenth of
+    the published peaks (8 TB/s, 2.5 PFLOP/s bf16) and those peaks; a buffer below 1 GiB is refused."""
+    n = 2 << 30
+    buf = torch.empty(n, dtype=torch.uint8, device="cuda")
+    buf[: n // 2] = torch.arange(n // 2, device="cuda", dtype=torch.int64).mul_(2654435761).bitwise_and_(255).to(torch.uint8)
+    want = buf[: n // 2].clone()
+    got = mb.muse_probe_peaks(buf)
+    assert 800.0 < got["copy_GBps"] < 8000.0, got
+    assert 250.0 < got["mfma_bf16_TFLOPs"] < 2500.0, got
+    # the MFMA loop writes its sums into the head of the buffer afterwards; the copy's destination is untouched by it
+    assert torch.equal(buf[n // 2:], want)
+    with pytest.raises(mb.MuseError):
+        mb.muse_probe_peaks(torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
