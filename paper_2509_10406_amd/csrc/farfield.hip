@@ -738,6 +738,13 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
     qt[x][0] = scale * (q4[0] - c4.x); qt[x][1] = scale * (q4[1] - c4.y);
     qt[x][2] = scale * (q4[2] - c4.z); qt[x][3] = scale * (q4[3] - c4.w);
   }
+  // the four queries of a wave are neighbours in the block-major order: the largest b among them (wave-uniform)
+  // bounds the block loops, so a wave of block-1 queries handles one summary row per cluster, not eight
+  // (the bound is a template constant of the loop body below: one straight-line body per value, loads batched)
+  int bwv = b;
+  bwv = max(bwv, __shfl_xor(bwv, 16, 64));
+  bwv = max(bwv, __shfl_xor(bwv, 32, 64));
+  bwv = __builtin_amdgcn_readfirstlane(bwv);
   float m = MUSE_NEG_INF, l = 0.f, o[NG][4];
 #pragma unroll
   for (int x = 0; x < NG; ++x)
@@ -753,6 +760,8 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
 #pragma unroll
       for (int t = 0; t < 4; ++t) o[x][t] = o[x][t] * a + p * v[x][t];
   };
+  auto run = [&](auto bw_c) {
+  constexpr int bw = decltype(bw_c)::value;
   for (int t = 0; t < r; ++t) {
     const int j = selc[qn * r + t];
     if (j < 0) continue;
@@ -764,11 +773,12 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
     float vr[8][NG][4];
 #pragma unroll
     for (int c0 = 0; c0 < 8 * NBC; c0 += 8) {
-      if (c0 >= b) break;
+      if (c0 >= bw) break;
       float mu[8], part[8];
       float4 kr[8][NG];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
+        if (c0 + u >= bw) break;
         const int bp = c0 + u < b ? c0 + u : b - 1;
         const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
         mu[u] = s_mu[cell];
@@ -780,6 +790,7 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
+        if (c0 + u >= bw) break;
         float pa = 0.f;
 #pragma unroll
         for (int x = 0; x < NG; ++x) {
@@ -789,10 +800,15 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
         part[u] = pa;
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) part[u] = group_sum<16>(part[u]);
+      for (int u = 0; u < 8; ++u) {
+        if (c0 + u >= bw) break;
+        part[u] = group_sum<16>(part[u]);
+      }
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
+      for (int u = 0; u < 8; ++u) {
+        if (c0 + u >= bw) break;
         if (c0 + u < b && mu[u] > MUSE_NEG_INF) sc2[c0 + u] = part[u] + mu[u];
+      }
     }
     unsigned selbits = 0;
     for (int u = 0; u < k2e; ++u) {
@@ -807,10 +823,11 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
     // component 2: value summaries of the blocks that are not retrieved
 #pragma unroll
     for (int c0 = 0; c0 < 8 * NBC; c0 += 8) {
-      if (c0 >= b) break;
+      if (c0 >= bw) break;
       if (NBC > 1) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
+          if (c0 + u >= bw) break;
           const int bp = c0 + u < b ? c0 + u : b - 1;
           const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
 #pragma unroll
@@ -819,6 +836,7 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
+        if (c0 + u >= bw) break;
         if (!(sc2[c0 + u] > MUSE_NEG_INF) || ((selbits >> (c0 + u)) & 1u)) continue;
         add(sc2[c0 + u], vr[u]);
       }
@@ -843,6 +861,21 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
         }
       }
     }
+  }
+  };
+  if (NBC == 1) {
+    switch (bwv) {
+      case 1: run(std::integral_constant<int, 1>{}); break;
+      case 2: run(std::integral_constant<int, 2>{}); break;
+      case 3: run(std::integral_constant<int, 3>{}); break;
+      case 4: run(std::integral_constant<int, 4>{}); break;
+      case 5: run(std::integral_constant<int, 5>{}); break;
+      case 6: run(std::integral_constant<int, 6>{}); break;
+      case 7: run(std::integral_constant<int, 7>{}); break;
+      default: run(std::integral_constant<int, 8>{}); break;
+    }
+  } else {
+    run(std::integral_constant<int, 8 * NBC>{});
   }
   if (!(l > 0.f)) return;
   // merge into the far-field state left by the tile kernel

@@ -12,6 +12,8 @@
 //   where G = own gradient + sum over later accumulated cells a of exp(mu - Amu[a]) gA[a].
 // Every reduction has one owner (no float atomics): cells by (query cluster, key-cluster tile),
 // keys by (key block, key-cluster tile).
+#include <type_traits>
+
 #include "ff_common.h"
 
 namespace {
@@ -380,6 +382,15 @@ __global__ void __launch_bounds__(256) k_comp2_bwd_dq(
     for (int t = 0; t < 4; ++t) dq[x][t] = 0.f;
   }
   const int32_t* si = slotinfo + ((size_t)hq * N + pos) * r;
+  // the four queries of a wave are neighbours in the block-major order: the largest b among them (wave-uniform)
+  // bounds the block loops
+  // (the bound is a template constant of the loop body below: one straight-line body per value, loads batched)
+  int bwv = b;
+  bwv = max(bwv, __shfl_xor(bwv, 16, 64));
+  bwv = max(bwv, __shfl_xor(bwv, 32, 64));
+  bwv = __builtin_amdgcn_readfirstlane(bwv);
+  auto run = [&](auto bw_c) {
+  constexpr int bw = decltype(bw_c)::value;
   for (int t = 0; t < r; ++t) {
     const int info = si[t];
     if (info < 0) continue;
@@ -387,12 +398,13 @@ __global__ void __launch_bounds__(256) k_comp2_bwd_dq(
     const unsigned selbits = (unsigned)info >> 16;
 #pragma unroll
     for (int c0 = 0; c0 < 8 * NBC; c0 += 8) {
-      if (c0 >= b) break;
+      if (c0 >= bw) break;
       float mu[8], part[8], dpp[8];
       float4 kr[8][NG];
       float vr[8][NG][4];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
+        if (c0 + u >= bw) break;
         const int bp = c0 + u < b ? c0 + u : b - 1;
         const size_t cell = (((size_t)hl * NBm + bp) * Cq + i) * Ck + j;
         mu[u] = s_mu[cell];
@@ -404,6 +416,7 @@ __global__ void __launch_bounds__(256) k_comp2_bwd_dq(
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
+        if (c0 + u >= bw) break;
         float pa = 0.f, pd = 0.f;
 #pragma unroll
         for (int x = 0; x < NG; ++x) {
@@ -416,11 +429,13 @@ __global__ void __launch_bounds__(256) k_comp2_bwd_dq(
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
+        if (c0 + u >= bw) break;
         part[u] = group_sum<16>(part[u]);
         dpp[u] = group_sum<16>(dpp[u]);
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
+        if (c0 + u >= bw) break;
         const bool use = c0 + u < b && mu[u] > MUSE_NEG_INF && !((selbits >> (c0 + u)) & 1u);
         const float p = use ? __expf(part[u] + mu[u] - lse) : 0.f;
         const float dlg = p * (dpp[u] - dl);
@@ -431,6 +446,21 @@ __global__ void __launch_bounds__(256) k_comp2_bwd_dq(
         }
       }
     }
+  }
+  };
+  if (NBC == 1) {
+    switch (bwv) {
+      case 1: run(std::integral_constant<int, 1>{}); break;
+      case 2: run(std::integral_constant<int, 2>{}); break;
+      case 3: run(std::integral_constant<int, 3>{}); break;
+      case 4: run(std::integral_constant<int, 4>{}); break;
+      case 5: run(std::integral_constant<int, 5>{}); break;
+      case 6: run(std::integral_constant<int, 6>{}); break;
+      case 7: run(std::integral_constant<int, 7>{}); break;
+      default: run(std::integral_constant<int, 8>{}); break;
+    }
+  } else {
+    run(std::integral_constant<int, 8 * NBC>{});
   }
 #pragma unroll
   for (int x = 0; x < NG; ++x)

@@ -56,9 +56,9 @@ def main():
     out = {"workload": a.workload, "unit": "bytes per launch",
            "commands": [
                "rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d DIR_F -o f -- python3 bench.py"
-               f"{flags} --steps 1 --warmup 0 --no-cpu-baseline --serial-streams",
+               f"{flags} --steps 1 --warmup 0 --no-cpu-baseline --no-variants --serial-streams",
                "rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d DIR_W -o w -- python3 bench.py"
-               f"{flags} --steps 1 --warmup 0 --no-cpu-baseline --serial-streams",
+               f"{flags} --steps 1 --warmup 0 --no-cpu-baseline --no-variants --serial-streams",
                f"python -m paper_2509_10406_amd.traffic DIR_F/f_counter_collection.csv DIR_W/w_counter_collection.csv"
                f" --workload {a.workload} --out profiles/hbm_traffic_{a.workload}.json"],
            "calibration": {"kernel": "torch bf16 -> fp32 cast of O", "elements": elems,
