@@ -937,10 +937,11 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
   w->ff_ml = w->ff_acc + HQ * N * D;
   {
     size_t W = (d.Ck + 31) / 32, NBm = d.nb > 1 ? d.nb - 1 : 1, R2 = (size_t)(d.r > 0 ? d.r : 1) * d.k2e;
-    w->pairmask = (uint32_t*)take(HQ * N * W * 4 * NBm);
+    w->pairmask = (uint32_t*)take(ff_pairmask_bytes(d));
     w->pair_off = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
-    w->seg_cnt = (int32_t*)take(HK * ((size_t)d.nb * d.Ck * (d.Hq / d.Hkv) * kHitSeg + 1) * 4);
-    w->seg_off = (int32_t*)take(HK * ((size_t)d.nb * d.Ck * (d.Hq / d.Hkv) * kHitSeg + 1) * 4);
+    w->pair_cnt = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
+    w->seg_cnt = (int32_t*)take(ff_segcnt_bytes(d));
+    w->seg_off = (int32_t*)take(ff_segcnt_bytes(d));
     w->hit_cap = (size_t)(d.Hq / d.Hkv) * N * R2;
     w->hits = (uint2*)take(HQ * N * R2 * 8);
     w->ret_part = (float*)take(HQ * N * R2 * (D + 4) * 4);

@@ -195,7 +195,6 @@ __device__ __forceinline__ bf16x8_t cvt8(const float* __restrict__ p) {
 
 constexpr int kMaxCk = 2304;  // key clusters a kernel can index in LDS
 static_assert(kMaxCk >= MUSE_MAX_CLUSTERS, "the host accepts more clusters than the kernels index");
-constexpr int kHitSeg = 8;  // query-range slices per (pair, head) when the hit lists are built
 constexpr int kC3Slices = 8;  // most waves that share the hits of one retrieved pair in the key/value gradients
 constexpr int kC3TilesPerSlice = 4;  // a pair gets one slice per so many tiles of 32 hits
 
@@ -208,9 +207,10 @@ struct FFWorkspace {
   float* delta;
   uint32_t* selmask;   // [HQ][W][N] by bucketed query position
   int32_t* slotinfo;   // [HQ][N][r] by bucketed query position: cluster | retrieved-block mask << 16
-  uint32_t* pairmask;  // [HQ][nb-1][W][N]
+  uint32_t* pairmask;  // [HQ][nb-1][W][N], fp32 inputs only
   int32_t* pair_off;             // inverse index of the retrieval: (kv head, key block, key cluster) -> hits
-  int32_t *seg_cnt, *seg_off;    // its construction: counts / offsets per (pair, head of the group, query slice)
+  int32_t* pair_cnt;             // hits per pair, [HK][pairs + 1]
+  int32_t *seg_cnt, *seg_off;    // its construction: counts / list starts [HK][head of the group x query slice][pair]
   uint2* hits;                   // x = n | g << 22 (query position, head inside the KV group), y = slot*k2e + u
   size_t hit_cap;                // hits per kv head
   float* ret_part;               // per (query, slot, u): forward partial state [acc D | max | sum | pad2], or dq partial [D]
@@ -238,6 +238,24 @@ struct FFWorkspace {
 
 static inline size_t ff_al(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// query-range slices per head when the hit lists of the retrieval are built: enough (slice, head) waves to fill
+// the device, every slice a whole number of 64-query chunks
+static inline int ff_hit_segments(const MuseDims& d) {
+  const int HQ = d.B * d.Hq, chunks = (d.N - d.Bs + 63) / 64;
+  int seg = (2048 + HQ - 1) / HQ;
+  seg = seg > chunks ? chunks : seg;
+  return seg < 1 ? 1 : seg;
+}
+// bytes of the bit matrix (fp32 inputs) and of the segment counters (bf16 inputs) of the inverse index
+static inline size_t ff_pairmask_bytes(const MuseDims& d) {
+  size_t HQ = (size_t)d.B * d.Hq, W = (d.Ck + 31) / 32, NBm = d.nb > 1 ? d.nb - 1 : 1;
+  return d.dtype == MUSE_DTYPE_BF16 ? 0 : HQ * d.N * W * 4 * NBm;
+}
+static inline size_t ff_segcnt_bytes(const MuseDims& d) {
+  size_t HK = (size_t)d.B * d.Hkv, NBm = d.nb > 1 ? d.nb - 1 : 1;
+  return d.dtype == MUSE_DTYPE_BF16 ? HK * (d.Hq / d.Hkv) * ff_hit_segments(d) * NBm * d.Ck * 4 : 0;
+}
+
 // bytes of the all-heads part / of one query head of the chunked part
 static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
   size_t HQ = (size_t)d.B * d.Hq, HK = (size_t)d.B * d.Hkv, N = d.N, D = d.D;
@@ -247,8 +265,8 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
              ff_al(HQ * ((size_t)d.nb * d.Cq + 1) * 4) + ff_al(HQ * d.nb * ((size_t)d.Cq + 1) * 4) +
              2 * ff_al(HK * N * D * es) + ff_al(HQ * N * (D + 2) * 4);
   // inverse index of the retrieval and its per-(query, slot) partial results
-  b += ff_al(HQ * N * W * 4 * NBm) + ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) +
-       2 * ff_al(HK * ((size_t)d.nb * d.Ck * (d.Hq / d.Hkv) * kHitSeg + 1) * 4) + ff_al(HQ * N * R2 * 8) +
+  b += ff_al(ff_pairmask_bytes(d)) + 2 * ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) + 2 * ff_al(ff_segcnt_bytes(d)) +
+       ff_al(HQ * N * R2 * 8) +
        ff_al(HQ * N * R2 * (D + 4) * 4);
   if (bwd) {
     b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + ff_al(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * 4) + 2 * ff_al(HK * N * D * 4) +

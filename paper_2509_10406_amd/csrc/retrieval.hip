@@ -4,7 +4,8 @@
 //   pairmask[hq][b'][j/32][n]  bit j%32 set iff query n of head hq retrieved the pair (j, b')
 //   hits[hk][pair_off[hk][b'*Ck + j] ...]  the queries of all heads of the KV group that retrieved the
 //                                           pair, ascending (head, position): x = n | g << 22, y = slot*k2e + u
-// Ordered lists (ballot ranks, no atomics on the order) keep every later sum reproducible.
+// Ordered lists (ballot ranks, no atomics on the order) keep every later sum reproducible.  The bit matrix is
+// built for fp32 inputs only (their key/value gradient kernel walks it); bf16 inputs build the lists directly.
 #include "ff_common.h"
 
 namespace {
@@ -25,91 +26,84 @@ __global__ void __launch_bounds__(256) k_pairmask(const int32_t* __restrict__ se
   }
 }
 
-// Pass 1 (FILL = false) counts the hits of every (pair, head of the group, slice of the query range),
-// k_pair_scan turns the counts into offsets (pair-major, then head, then slice: the order of the lists),
-// pass 2 (FILL = true) writes the lists.  One wave per (key block b', tile of 32 clusters, head, slice);
-// lane jl keeps the running offset of cluster 32 jt + jl in a register.
+// The hit lists are built by a counting sort whose order is fixed by construction.  The queries with a far field
+// (positions Bs .. N-1) of every query head are cut into SEG slices of whole 64-query chunks; one workgroup owns a
+// (slice, head), walks its chunks in order and keeps one counter per pair in LDS.  Each of its kHitWaves waves
+// takes the pairs of one residue class (pair % kHitWaves), so a counter has one owner and the waves never wait
+// for each other.  For a chunk and a selection slot, the lanes that name the same pair are found by ballots (one
+// round per distinct pair of the wave's class among the 64 lanes) and ranked by lane, so a list is ascending in
+// (head of the group, position) without any atomic deciding an order.  Pass 1 (FILL = false) leaves the counts per (kv head, head of the group x slice, pair); k_pair_totals,
+// k_pair_scan and k_seg_offsets turn them into list starts (pair-major, then head of the group, then slice);
+// pass 2 (FILL = true) starts from those and writes the hits, with the slot index the pair has in the query's
+// exported selections.
+constexpr int kHitWaves = 8;
 template <bool FILL>
-__global__ void __launch_bounds__(64) k_pair_hits(const uint32_t* __restrict__ pmask, int32_t* __restrict__ seg_cnt,
-                                                   const int32_t* __restrict__ seg_off, uint2* __restrict__ hits,
-                                                   size_t hit_cap, int N, int Bs, int nb, int Ck, int Hq, int Hkv) {
-  const int jt = blockIdx.x, bp = blockIdx.y, NBm = nb - 1;
-  const int G_ = Hq / Hkv, W = (Ck + 31) / 32, SEGT = G_ * kHitSeg;
-  const int hk = blockIdx.z / SEGT, gs = blockIdx.z % SEGT, g = gs / kHitSeg, sg = gs % kHitSeg;
-  const size_t hq = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_ + g;
-  const int lane = threadIdx.x;
-  const int nlo = (bp + 1) * Bs;
-  const int per = ((N - nlo + kHitSeg * 64 - 1) / (kHitSeg * 64)) * 64;  // queries per slice, a multiple of 64
-  const int nbeg = nlo + sg * per, nend = nbeg + per < N ? nbeg + per : N;
-  const size_t sbase = (size_t)hk * ((size_t)NBm * Ck * SEGT + 1);
-  const int jmine = jt * 32 + (lane & 31);
-  const size_t sidx = sbase + ((size_t)bp * Ck + jmine) * SEGT + gs;
-  int curv = (FILL && lane < 32 && jmine < Ck) ? seg_off[sidx] : 0;
-  const uint32_t* colw = pmask + ((hq * NBm + bp) * W + jt) * N;
-  for (int n0 = nbeg; n0 < nend; n0 += 256) {
-    uint32_t words[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int n = n0 + 64 * u + lane;
-      words[u] = n < nend ? colw[n] : 0u;
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const uint32_t word = words[u];
-      unsigned long long nz = __ballot(word != 0u);
-      uint32_t U = 0;  // clusters present in this chunk
-      while (nz) {
-        const int src = __ffsll((long long)nz) - 1;
-        nz &= nz - 1;
-        U |= (uint32_t)__builtin_amdgcn_readlane((int)word, src);
-      }
-      while (U) {
-        const int jl = __ffs((int)U) - 1;
-        U &= U - 1;
-        const bool has = (word >> jl) & 1u;
-        const unsigned long long bal = __ballot(has);
-        const int base = __shfl(curv, jl, 64);
-        if (FILL && has) {
-          const int rank = __popcll(bal & ((1ull << lane) - 1ull));
-          // y holds the pair for now; k_hit_slots replaces it with the query's slot index
-          hits[(size_t)hk * hit_cap + base + rank] =
-              make_uint2((uint32_t)(n0 + 64 * u + lane) | ((uint32_t)g << 22), (uint32_t)(bp * Ck + jt * 32 + jl));
+__global__ void __launch_bounds__(64 * kHitWaves) k_hit_lists(const int32_t* __restrict__ selc, const int32_t* __restrict__ selb,
+                                                   int32_t* __restrict__ seg_cnt, const int32_t* __restrict__ seg_off,
+                                                   uint2* __restrict__ hits, size_t hit_cap, int N, int Bs, int Ck,
+                                                   int r, int k2e, int Hq, int Hkv, int npair, int SEG, int cps) {
+  extern __shared__ int cur[];  // per pair: hits counted so far (pass 1) / next list position (pass 2)
+  const int s = blockIdx.x, hq = blockIdx.y, lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+  const int G_ = Hq / Hkv, g = (hq % Hq) % G_;
+  const int hk = (hq / Hq) * Hkv + (hq % Hq) / G_;
+  const size_t sbase = ((size_t)hk * G_ * SEG + (size_t)g * SEG + s) * npair;
+  for (int p = threadIdx.x; p < npair; p += 64 * kHitWaves) cur[p] = FILL ? seg_off[sbase + p] : 0;
+  __syncthreads();
+  const int chunks = (N - Bs + 63) / 64;
+  const int c1 = (s + 1) * cps < chunks ? (s + 1) * cps : chunks;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  for (int c = s * cps; c < c1; ++c) {
+    const int n = Bs + 64 * c + lane;
+    const bool valid = n < N;
+    const size_t qn = (size_t)hq * N + (valid ? n : N - 1);
+    for (int t = 0; t < r; ++t) {
+      const int j = valid ? selc[qn * r + t] : -1;
+      for (int u = 0; u < k2e; ++u) {
+        const int bp = j >= 0 ? selb[(qn * r + t) * k2e + u] : -1;
+        const int pair = bp >= 0 ? bp * Ck + j : -1;
+        unsigned long long act = __ballot(pair >= 0 && pair % kHitWaves == wave);
+        while (act) {
+          const int src = __ffsll((long long)act) - 1;
+          const int pv = __builtin_amdgcn_readlane(pair, src);
+          const unsigned long long same = __ballot(pair == pv);
+          const int base = cur[pv];
+          if (FILL && pair == pv)
+            hits[(size_t)hk * hit_cap + base + __popcll(same & below)] =
+                make_uint2((uint32_t)n | ((uint32_t)g << 22), (uint32_t)(t * k2e + u));
+          if (lane == src) cur[pv] = base + __popcll(same);
+          act &= ~same;
         }
-        if (lane == jl) curv += __popcll(bal);
       }
     }
   }
-  if (!FILL && lane < 32 && jmine < Ck) seg_cnt[sidx] = curv;
+  if (!FILL) {
+    __syncthreads();
+    for (int p = threadIdx.x; p < npair; p += 64 * kHitWaves) seg_cnt[sbase + p] = cur[p];
+  }
 }
 
-// pair_off[hk][p] = seg_off[hk][p * SEGT]: where the list of pair p starts (p = npair: the total)
-__global__ void __launch_bounds__(256) k_pair_offsets(const int32_t* __restrict__ seg_off, int32_t* __restrict__ pair_off,
-                                                       int npair, int SEGT) {
+// pair_cnt[hk][p] = hits of pair p over all (head of the group, slice) segments
+__global__ void __launch_bounds__(256) k_pair_totals(const int32_t* __restrict__ seg_cnt, int32_t* __restrict__ pair_cnt,
+                                                      int npair, int SEGT) {
   const int hk = blockIdx.y, p = blockIdx.x * 256 + threadIdx.x;
-  if (p > npair) return;
-  pair_off[(size_t)hk * (npair + 1) + p] = seg_off[(size_t)hk * ((size_t)npair * SEGT + 1) + (size_t)p * SEGT];
+  if (p >= npair) return;
+  const int32_t* c = seg_cnt + (size_t)hk * SEGT * npair + p;
+  int tot = 0;
+  for (int gs = 0; gs < SEGT; ++gs) tot += c[(size_t)gs * npair];
+  pair_cnt[(size_t)hk * (npair + 1) + p] = tot;
 }
 
-// hits[].y: pair id -> slot*k2e + u of that pair in the query's exported selections (one thread per hit)
-__global__ void __launch_bounds__(256) k_hit_slots(const int32_t* __restrict__ selc, const int32_t* __restrict__ selb,
-                                                    const int32_t* __restrict__ pair_off, uint2* __restrict__ hits,
-                                                    size_t hit_cap, int npair, int N, int Ck, int r, int k2e, int Hq,
-                                                    int Hkv) {
-  const int hk = blockIdx.y;
-  const int total = pair_off[(size_t)hk * (npair + 1) + npair];
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= total) return;
-  const int G_ = Hq / Hkv;
-  const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
-  uint2 h = hits[(size_t)hk * hit_cap + i];
-  const size_t qn = (hqbase + (h.x >> 22)) * N + (h.x & 0x3fffffu);
-  const int bp = (int)h.y / Ck, j = (int)h.y % Ck;
-  int su = 0;
-  for (int t = 0; t < r; ++t)
-    if (selc[qn * r + t] == j)
-      for (int u = 0; u < k2e; ++u)
-        if (selb[(qn * r + t) * k2e + u] == bp) su = t * k2e + u;
-  hits[(size_t)hk * hit_cap + i].y = (uint32_t)su;
+// seg_off[hk][gs][p] = pair_off[hk][p] + hits of pair p in the segments before gs
+__global__ void __launch_bounds__(256) k_seg_offsets(const int32_t* __restrict__ seg_cnt, const int32_t* __restrict__ pair_off,
+                                                      int32_t* __restrict__ seg_off, int npair, int SEGT) {
+  const int hk = blockIdx.y, p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= npair) return;
+  const size_t base = (size_t)hk * SEGT * npair + p;
+  int run = pair_off[(size_t)hk * (npair + 1) + p];
+  for (int gs = 0; gs < SEGT; ++gs) {
+    seg_off[base + (size_t)gs * npair] = run;
+    run += seg_cnt[base + (size_t)gs * npair];
+  }
 }
 
 // exclusive prefix of n counts per kv head, off[n] = total
@@ -179,20 +173,28 @@ int muse_ff_build_inverse_index(const MuseDims& d, const int32_t* selc, const in
   const int HQ = d.B * d.Hq, HK = d.B * d.Hkv, N = d.N, NBm = d.nb - 1, W = (d.Ck + 31) / 32;
   const size_t nq = (size_t)HQ * N;
   int rc;
-  if ((rc = muse_launch_fill_i32((int32_t*)w.pairmask, nq * NBm * W, 0, st))) return rc;
-  { MuseProf prof_("k_pairmask", st); hipLaunchKernelGGL(k_pairmask, dim3((unsigned)((nq * d.r + 255) / 256)), dim3(256), 0, st, selc, selb, w.pairmask, HQ, N, d.r, d.k2e, NBm, W); }
-  MUSE_LAUNCH_CHECK();
-  if (!with_hits) return MUSE_OK;
-  const int SEGT = (d.Hq / d.Hkv) * kHitSeg, npair = NBm * d.Ck;
-  dim3 g(W, NBm, HK * SEGT);
-  { MuseProf prof_("k_pair_hits", st); hipLaunchKernelGGL(k_pair_hits<false>, g, dim3(64), 0, st, w.pairmask, w.seg_cnt, w.seg_off, w.hits, w.hit_cap, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv); }
-  { MuseProf prof_("k_pair_scan", st); hipLaunchKernelGGL(k_pair_scan, dim3(HK), dim3(1024), 0, st, w.seg_cnt, w.seg_off, npair * SEGT); }
-  { MuseProf prof_("k_pair_offsets", st); hipLaunchKernelGGL(k_pair_offsets, dim3((npair + 256) / 256, HK), dim3(256), 0, st, w.seg_off, w.pair_off, npair, SEGT); }
-  { MuseProf prof_("k_pair_hits", st); hipLaunchKernelGGL(k_pair_hits<true>, g, dim3(64), 0, st, w.pairmask, w.seg_cnt, w.seg_off, w.hits, w.hit_cap, N, d.Bs, d.nb, d.Ck, d.Hq, d.Hkv); }
-  {
-    dim3 gh((unsigned)((w.hit_cap + 255) / 256), HK);
-    { MuseProf prof_("k_hit_slots", st); hipLaunchKernelGGL(k_hit_slots, gh, dim3(256), 0, st, selc, selb, w.pair_off, w.hits, w.hit_cap, NBm * d.Ck, N, d.Ck, d.r, d.k2e, d.Hq, d.Hkv); }
+  if (!with_hits) {
+    if ((rc = muse_launch_fill_i32((int32_t*)w.pairmask, nq * NBm * W, 0, st))) return rc;
+    { MuseProf prof_("k_pairmask", st); hipLaunchKernelGGL(k_pairmask, dim3((unsigned)((nq * d.r + 255) / 256)), dim3(256), 0, st, selc, selb, w.pairmask, HQ, N, d.r, d.k2e, NBm, W); }
+    MUSE_LAUNCH_CHECK();
+    return MUSE_OK;
   }
+  const int SEG = ff_hit_segments(d), SEGT = (d.Hq / d.Hkv) * SEG, npair = NBm * d.Ck;
+  const int chunks = (N - d.Bs + 63) / 64, cps = (chunks + SEG - 1) / SEG;
+  const size_t lds = (size_t)npair * sizeof(int);
+  static_assert((size_t)15 * MUSE_MAX_CLUSTERS * sizeof(int) <= 128 * 1024, "the pair counters of the largest accepted shape fit the LDS");
+  static bool attr_set = false;
+  if (!attr_set) {
+    MUSE_HIP_CHECK(hipFuncSetAttribute((const void*)k_hit_lists<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+    MUSE_HIP_CHECK(hipFuncSetAttribute((const void*)k_hit_lists<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+    attr_set = true;
+  }
+  const dim3 g(SEG, HQ), gp((npair + 255) / 256, HK);
+  { MuseProf prof_("k_hit_lists", st); hipLaunchKernelGGL(k_hit_lists<false>, g, dim3(64 * kHitWaves), lds, st, selc, selb, w.seg_cnt, w.seg_off, w.hits, w.hit_cap, N, d.Bs, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, npair, SEG, cps); }
+  { MuseProf prof_("k_pair_totals", st); hipLaunchKernelGGL(k_pair_totals, gp, dim3(256), 0, st, w.seg_cnt, w.pair_cnt, npair, SEGT); }
+  { MuseProf prof_("k_pair_scan", st); hipLaunchKernelGGL(k_pair_scan, dim3(HK), dim3(1024), 0, st, w.pair_cnt, w.pair_off, npair); }
+  { MuseProf prof_("k_seg_offsets", st); hipLaunchKernelGGL(k_seg_offsets, gp, dim3(256), 0, st, w.seg_cnt, w.pair_off, w.seg_off, npair, SEGT); }
+  { MuseProf prof_("k_hit_lists", st); hipLaunchKernelGGL(k_hit_lists<true>, g, dim3(64 * kHitWaves), lds, st, selc, selb, w.seg_cnt, w.seg_off, w.hits, w.hit_cap, N, d.Bs, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, npair, SEG, cps); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
