@@ -197,6 +197,132 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 }
 
 // ------------------------------------------------------------------------------------------
+// The same assignment with ALL centroids of the head resident in LDS (C (D + 8) 2 + 4 C bytes <= 160 KB: every
+// shape but the largest C x D).  One workgroup of 8 waves per CU fills the LDS once and then walks batches of
+// 512 points (64 per wave), the rows of the next batch in flight while this one is scored: no chunk pipeline, no
+// barrier after the fill, and the fill is paid once per eight or so batches.  (D = 128: 32 points per wave.)
+// Running argmax in the accumulator layout, one (value, run) pair per accumulator element.  Inside a run of 16
+// centroid tiles the tile number rides in the low four mantissa bits of the score (15 - tile % 16, so the earlier
+// tile wins among scores equal above those bits): one v_and_or and half a v_max3 per score instead of a compare
+// and two selects.  The four bits cost a relative 2^-19 of a score, below the margin at which an assignment is
+// defined.  At the end of a run the packed maximum is folded into (gbest, grun) with compare and selects.
+// ------------------------------------------------------------------------------------------
+constexpr float kPadScore = -3.0e38f;  // score of the padding rows past C: finite, so that tagging its low bits keeps it a number
+constexpr int kResWaves = 8;
+template <int D>
+__global__ void __launch_bounds__(64 * kResWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) k_assign_res(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ chat, const float* __restrict__ nhc2,
+    int32_t* __restrict__ assign, int N, int C, int Cpad) {
+  constexpr int KS = D / 16, CPR = D / 8, PT = D == 64 ? 2 : 1, LDW = D + 8;
+  extern __shared__ __attribute__((aligned(16))) unsigned char res_lds[];
+  bf16_t* cs = reinterpret_cast<bf16_t*>(res_lds);                          // [Cpad][D + 8]
+  float* c2s = reinterpret_cast<float*>(res_lds + (size_t)Cpad * LDW * 2);  // [Cpad]
+  const int h = blockIdx.y;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  const bf16_t* Xh = X + (size_t)h * N * D;
+  const bf16_t* Ch = chat + (size_t)h * C * D;
+  for (int idx = threadIdx.x; idx < Cpad * CPR; idx += 64 * kResWaves) {
+    const int row = idx / CPR, cc = idx % CPR;
+    *reinterpret_cast<uint4*>(&cs[(size_t)row * LDW + cc * 8]) =
+        row < C ? *reinterpret_cast<const uint4*>(Ch + (size_t)row * D + cc * 8) : make_uint4(0u, 0u, 0u, 0u);
+  }
+  for (int row = threadIdx.x; row < Cpad; row += 64 * kResWaves) c2s[row] = row < C ? nhc2[(size_t)h * C + row] : kPadScore;
+  __syncthreads();
+
+  constexpr int BP = kResWaves * 32 * PT;  // points per batch
+  const int nbatch = (N + BP - 1) / BP;
+  auto load_x = [&](bf16x8_t (&xb)[PT][KS], int batch) {
+#pragma unroll
+    for (int t = 0; t < PT; ++t) {
+      int n = batch * BP + (wave * PT + t) * 32 + col;
+      n = n < N ? n : N - 1;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) xb[t][s] = *reinterpret_cast<const bf16x8_t*>(Xh + (size_t)n * D + 16 * s + 8 * half);
+    }
+  };
+  auto tag = [](float v, uint32_t code) { return __uint_as_float((__float_as_uint(v) & 0xfffffff0u) | code); };
+  bf16x8_t xn[PT][KS];
+  if ((int)blockIdx.x < nbatch) load_x(xn, blockIdx.x);
+  for (int batch = blockIdx.x; batch < nbatch; batch += gridDim.x) {
+    bf16x8_t xb[PT][KS];
+#pragma unroll
+    for (int t = 0; t < PT; ++t)
+#pragma unroll
+      for (int s = 0; s < KS; ++s) xb[t][s] = xn[t][s];
+    if (batch + (int)gridDim.x < nbatch) load_x(xn, batch + gridDim.x);
+    float sbest[PT][16], gbest[PT][16];
+    int grun[PT][16];
+#pragma unroll
+    for (int t = 0; t < PT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { sbest[t][e] = MUSE_NEG_INF; gbest[t][e] = MUSE_NEG_INF; grun[t][e] = 0; }
+    const int ntile = Cpad / 32;  // even
+    for (int ct = 0; ct < ntile; ct += 2) {
+      bf16x8_t ca[2][KS];
+#pragma unroll
+      for (int z = 0; z < 2; ++z)
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+          ca[z][s] = *reinterpret_cast<const bf16x8_t*>(&cs[(size_t)((ct + z) * 32 + col) * LDW + 16 * s + 8 * half]);
+      auto init = [&](int z) {  // -||c||^2 / 2 of the tile's rows: read again for every point tile (registers are scarcer than LDS reads)
+        f32x16_t v;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 c4 = *reinterpret_cast<const float4*>(&c2s[(ct + z) * 32 + 8 * g + 4 * half]);
+          v[4 * g] = c4.x; v[4 * g + 1] = c4.y; v[4 * g + 2] = c4.z; v[4 * g + 3] = c4.w;
+        }
+        return v;
+      };
+      uint32_t code0 = 15u - (uint32_t)(ct & 15), code1 = code0 - 1u;
+      // opaque to the optimiser, which otherwise rewrites "| code" as per-element additions of its terms
+      asm volatile("" : "+s"(code0), "+s"(code1));
+#pragma unroll
+      for (int t = 0; t < PT; ++t) {
+        asm volatile("" ::: "memory");  // keeps the two point tiles' reads of the bias rows apart
+        f32x16_t a0 = init(0), a1 = init(1);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[0][s], xb[t][s], a0, 0, 0, 0);
+          a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[1][s], xb[t][s], a1, 0, 0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sbest[t][e] = fmaxf(fmaxf(sbest[t][e], tag(a0[e], code0)), tag(a1[e], code1));
+      }
+      if ((ct & 15) == 14 || ct + 2 >= ntile) {  // a run of 16 tiles, or the last one, is complete
+        const int run = ct >> 4;
+#pragma unroll
+        for (int t = 0; t < PT; ++t)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const bool gt = sbest[t][e] > gbest[t][e];
+            gbest[t][e] = gt ? sbest[t][e] : gbest[t][e];
+            grun[t][e] = gt ? run : grun[t][e];
+            sbest[t][e] = MUSE_NEG_INF;
+          }
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < PT; ++t) {
+      float bv = MUSE_NEG_INF;
+      int bj = 0x7fffffff;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int tile = grun[t][e] * 16 + 15 - (int)(__float_as_uint(gbest[t][e]) & 15u);
+        const int j = tile * 32 + 8 * (e / 4) + 4 * half + (e % 4);
+        const bool take = gbest[t][e] > bv || (gbest[t][e] == bv && j < bj);
+        bv = take ? gbest[t][e] : bv;
+        bj = take ? j : bj;
+      }
+      const float ov = __shfl_xor(bv, 32, 64);
+      const int oj = __shfl_xor(bj, 32, 64);
+      if (ov > bv || (ov == bv && oj < bj)) { bv = ov; bj = oj; }
+      const int n = batch * BP + (wave * PT + t) * 32 + col;
+      if (half == 0 && n < N) assign[(size_t)h * N + n] = bj;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // stable bucketing by (block, cluster): grid (nb, heads), 1024 threads = 16 waves
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(1024) k_bucket(const int32_t* __restrict__ assign,
@@ -873,10 +999,29 @@ int cluster_impl(const MuseDims& d, const T* X, int H, int C, const int32_t* ini
       if (D == 64) { MuseProf prof_("k_assign_f32", st); hipLaunchKernelGGL(k_assign_f32<64>, g, dim3(256), 0, st, (const float*)X, (const float*)chat, nhc2, assign, N, C); }
       else { MuseProf prof_("k_assign_f32", st); hipLaunchKernelGGL(k_assign_f32<128>, g, dim3(256), 0, st, (const float*)X, (const float*)chat, nhc2, assign, N, C); }
     } else {
-      constexpr int PT = 2;
-      dim3 g((N + 4 * 32 * PT - 1) / (4 * 32 * PT), heads);
-      if (D == 64) { MuseProf prof_("k_assign_bf16", st); hipLaunchKernelGGL((k_assign_bf16<64, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C); }
-      else { MuseProf prof_("k_assign_bf16", st); hipLaunchKernelGGL((k_assign_bf16<128, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C); }
+      // all centroids resident in LDS when they fit (rows padded to a multiple of 64 for the tile pairs)
+      const int Cpad = (C + 63) / 64 * 64;
+      const size_t res_bytes = (size_t)Cpad * (D + 8) * 2 + (size_t)Cpad * 4;
+      if (res_bytes <= 160 * 1024) {
+        static bool attr_set = false;
+        if (!attr_set) {
+          MUSE_HIP_CHECK(hipFuncSetAttribute((const void*)k_assign_res<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+          MUSE_HIP_CHECK(hipFuncSetAttribute((const void*)k_assign_res<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+          attr_set = true;
+        }
+        const int bp = (D == 64 ? 64 : 32) * kResWaves;  // points per batch
+        const int nbatch = (N + bp - 1) / bp;
+        int gx = (256 + heads - 1) / heads;  // about one workgroup per CU over all heads
+        gx = gx > nbatch ? nbatch : gx;
+        dim3 g(gx, heads);
+        if (D == 64) { MuseProf prof_("k_assign_bf16", st); hipLaunchKernelGGL(k_assign_res<64>, g, dim3(64 * kResWaves), res_bytes, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C, Cpad); }
+        else { MuseProf prof_("k_assign_bf16", st); hipLaunchKernelGGL(k_assign_res<128>, g, dim3(64 * kResWaves), res_bytes, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C, Cpad); }
+      } else {
+        constexpr int PT = 2;
+        dim3 g((N + 4 * 32 * PT - 1) / (4 * 32 * PT), heads);
+        if (D == 64) { MuseProf prof_("k_assign_bf16", st); hipLaunchKernelGGL((k_assign_bf16<64, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C); }
+        else { MuseProf prof_("k_assign_bf16", st); hipLaunchKernelGGL((k_assign_bf16<128, PT>), g, dim3(256), 0, st, (const bf16_t*)X, (const bf16_t*)chat, nhc2, assign, N, C); }
+      }
     }
     MUSE_LAUNCH_CHECK();
     if (it == T_ && d.balanced) {
