@@ -354,6 +354,23 @@ __global__ void __launch_bounds__(256) k_chainmask(const int32_t* __restrict__ s
   if (j >= 0) atomicOr(&chainmask[((size_t)hl * Cq + aq[qn]) * W + (j >> 5)], 1u << (j & 31));
 }
 
+// the mask key-cluster-major: maskT[hl][j][i/32] bit i%32.  One wave per (32 query clusters, 32 key clusters): lane
+// i holds the word of its row, a ballot per bit gives the 32 rows' bits of one column.
+__global__ void __launch_bounds__(64) k_chainmask_t(const uint32_t* __restrict__ chainmask, uint32_t* __restrict__ maskT,
+                                                     int Cq, int Ck, int W, int WT) {
+  const int jt = blockIdx.x, itile = blockIdx.y, hl = blockIdx.z, lane = threadIdx.x;
+  const int i = itile * 32 + lane;
+  const uint32_t word = (lane < 32 && i < Cq) ? chainmask[((size_t)hl * Cq + i) * W + jt] : 0u;
+  uint32_t mine = 0u;
+#pragma unroll
+  for (int jl = 0; jl < 32; ++jl) {
+    const uint32_t colbits = (uint32_t)__ballot((word >> jl) & 1u);
+    if (lane == jl) mine = colbits;
+  }
+  const int j = jt * 32 + lane;
+  if (lane < 32 && j < Ck) maskT[((size_t)hl * Ck + j) * WT + itile] = mine;
+}
+
 // One wave per (query cluster i, tile of 32 key clusters).  A chain's blocks go to the wave's eight 8-lane
 // groups (block b to group b % 8), each lane holding D/8 adjacent head dims.  With mu-bar known, the normalised
 // weight of key p in cell (b, i, j) is exp(L[i][p] - mu-bar), so a row is one pass over the cell's keys.
@@ -409,6 +426,108 @@ __global__ void __launch_bounds__(64) k_block_summaries(const T* __restrict__ Ks
         st4(s_k, cell * D + DL * l8 + 4 * x, &ak[4 * x]);
         st4(s_v, cell * D + DL * l8 + 4 * x, &av[4 * x]);
       }
+    }
+  }
+}
+
+// The same rows on fp32 MFMA, key-cluster-major: one wave per (key cluster j, key block b), four blocks to a workgroup.  The query clusters
+// whose chain (i, j) is retrieved are listed from the mask's column (ballot ranks, ascending i) and taken 32 at a
+// time as the MFMA columns; the cell's keys are the contraction index, two per instruction, as in k_summaries:
+//   E^T[key, i] = exp(L[i, key] - mu-bar[b, i, j]),   s_k^T[d, i] = sum_key K^T[d, key] E^T[key, i]
+// A cell's keys are read once for all its chains instead of once per chain, and the sums leave through an LDS
+// transpose as whole rows.
+template <typename T, int D>
+__global__ void __launch_bounds__(256) k_block_summaries_mx(const T* __restrict__ Ks, const T* __restrict__ Vs,
+                                                            const float* __restrict__ L, const int32_t* __restrict__ off_k,
+                                                            const uint32_t* __restrict__ maskT,
+                                                            const float* __restrict__ s_mu, float* __restrict__ s_k,
+                                                            T* __restrict__ s_v, int h0, int N, int nb, int Cq, int Ck,
+                                                            int Hq, int Hkv) {
+  constexpr int DS = D / 64;
+  __shared__ float tr_all[4][32][68];
+  __shared__ uint16_t list[MUSE_MAX_CLUSTERS];
+  __shared__ int nflag_s;
+  const int j = (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8;  // an XCD takes a run of consecutive clusters
+  if (j >= Ck) return;
+  // the four waves of a workgroup take four key blocks of the same cluster and share its list of chains
+  const int wave = threadIdx.x / 64, b = 4 * blockIdx.y + wave, hl = blockIdx.z, hq = h0 + hl;
+  const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
+  const int lane = threadIdx.x % 64, col = lane % 32, half = lane / 32, NBm = nb - 1, WT = (Cq + 31) / 32;
+  float (*tr)[68] = tr_all[wave];
+  if (wave == 0) {
+    int nf = 0;
+    for (int i0 = 0; i0 < Cq; i0 += 64) {
+      const int i = i0 + lane;
+      const bool f = i < Cq && ((maskT[((size_t)hl * Ck + j) * WT + (i >> 5)] >> (i & 31)) & 1u);
+      const unsigned long long bal = __ballot(f);
+      if (f) list[nf + __popcll(bal & ((1ull << lane) - 1ull))] = (uint16_t)i;
+      nf += __popcll(bal);
+    }
+    if (lane == 0) nflag_s = nf;
+  }
+  __syncthreads();
+  const int nflag = nflag_s;
+  if (nflag == 0 || b >= NBm) return;
+  const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
+  const int lo = ok[b * Ck + j], hi = ok[b * Ck + j + 1];
+  const int lrow = lane / 16;
+  for (int it = 0; it * 32 < nflag; ++it) {
+    const int nrow = nflag - 32 * it < 32 ? nflag - 32 * it : 32;
+    const int il = list[32 * it + (col < nrow ? col : nrow - 1)];
+    const size_t cell = (((size_t)hl * NBm + b) * Cq + il) * Ck + j;
+    const float mu = s_mu[cell];
+    const float* Li = L + ((size_t)hl * Cq + il) * N;
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) {
+      const int d0 = 64 * ds;
+      // accumulator tile x, row m holds head dim d0 + 2 m + x: one paired load feeds both tiles
+      const T* Kh = Ks + (size_t)hk * N * D + d0 + 2 * col;
+      const T* Vh = Vs + (size_t)hk * N * D + d0 + 2 * col;
+      f32x16_t ak[2], av[2];
+      ak[0] = zero16(); ak[1] = zero16(); av[0] = zero16(); av[1] = zero16();
+      for (int c0 = lo; c0 < hi; c0 += 8) {
+        float lg[4];
+        typename Pair<T>::raw kk[4], vv[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int p = c0 + 4 * half + t;
+          const int pc = p < hi ? p : hi - 1;
+          lg[t] = Li[pc];
+          kk[t] = Pair<T>::ld(Kh, (size_t)pc * D);
+          vv[t] = Pair<T>::ld(Vh, (size_t)pc * D);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const float e = c0 + 4 * half + t < hi ? __expf(lg[t] - mu) : 0.f;
+          ak[0] = mfma32(Pair<T>::lo(kk[t]), e, ak[0]);
+          ak[1] = mfma32(Pair<T>::hi(kk[t]), e, ak[1]);
+          av[0] = mfma32(Pair<T>::lo(vv[t]), e, av[0]);
+          av[1] = mfma32(Pair<T>::hi(vv[t]), e, av[1]);
+        }
+      }
+      // rows out through the LDS transpose: 16 lanes write one row's 64 dims (an empty cell gives zero rows)
+      auto emit = [&](const f32x16_t(&a)[2], bool values) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int t = 0; t < 4; ++t)
+            *reinterpret_cast<float2*>(&tr[col][2 * (8 * g + 4 * half + t)]) = make_float2(a[0][4 * g + t], a[1][4 * g + t]);
+        wave_lds_fence();
+#pragma unroll
+        for (int ps = 0; ps < 8; ++ps) {
+          const int row = 4 * ps + lrow;
+          if (row < nrow) {
+            const float4 v = *reinterpret_cast<const float4*>(&tr[row][4 * (lane % 16)]);
+            const size_t o = ((((size_t)hl * NBm + b) * Cq + list[32 * it + row]) * Ck + j) * D + d0 + 4 * (lane % 16);
+            const float v4[4] = {v.x, v.y, v.z, v.w};
+            if (values) st4(s_v, o, v4);
+            else st4(s_k, o, v4);
+          }
+        }
+        wave_lds_fence();
+      };
+      emit(ak, false);
+      emit(av, true);
     }
   }
 }
@@ -970,6 +1089,7 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
   size_t cells = (size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * d.Ck;
   w->L = (float*)take(hc * d.Cq * N * 4);
   w->chainmask = (uint32_t*)take(hc * d.Cq * ((d.Ck + 31) / 32) * 4);
+  w->chainmaskT = (uint32_t*)take(hc * d.Ck * ((d.Cq + 31) / 32) * 4);
   w->s_mu = (float*)take(hc * cells * 4);
   w->A_mu = (float*)take(hc * cells * 4);
   w->s_k = (float*)take(hc * cells * D * 4);
@@ -1049,7 +1169,17 @@ int muse_ff_block_summaries(const MuseDims& d, const int32_t* selc, const int32_
   dim3 gm((unsigned)(((size_t)(d.N - d.Bs) * d.r + 255) / 256), hn);
   { MuseProf prof_("k_chainmask", st); hipLaunchKernelGGL(k_chainmask, gm, dim3(256), 0, st, selc, aq, w.chainmask, h0, d.N, d.Bs, d.r, d.Cq, W); }
   dim3 gs(W, d.Cq, hn);
-  if (d.D == 64)
+  if (sizeof(T) == 2) {  // bf16 inputs: key-cluster-major on fp32 MFMA
+    const int WT = (d.Cq + 31) / 32;
+    { MuseProf prof_("k_chainmask_t", st); hipLaunchKernelGGL(k_chainmask_t, dim3(W, WT, hn), dim3(64), 0, st, w.chainmask, w.chainmaskT, d.Cq, d.Ck, W, WT); }
+    dim3 gj((d.Ck + 7) / 8 * 8, (d.nb - 1 + 3) / 4, hn);
+    if (d.D == 64)
+      { MuseProf prof_("k_block_summaries", st); hipLaunchKernelGGL((k_block_summaries_mx<T, 64>), gj, dim3(256), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k,
+                         w.chainmaskT, w.s_mu, w.s_k, (T*)w.s_v, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
+    else
+      { MuseProf prof_("k_block_summaries", st); hipLaunchKernelGGL((k_block_summaries_mx<T, 128>), gj, dim3(256), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k,
+                         w.chainmaskT, w.s_mu, w.s_k, (T*)w.s_v, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
+  } else if (d.D == 64)
     { MuseProf prof_("k_block_summaries", st); hipLaunchKernelGGL((k_block_summaries<T, 64>), gs, dim3(64), 0, st, (const T*)w.Ks, (const T*)w.Vs, w.L, w.off_k,
                        w.chainmask, w.s_mu, w.s_k, (T*)w.s_v, h0, d.N, d.nb, d.Cq, d.Ck, d.Hq, d.Hkv); }
   else

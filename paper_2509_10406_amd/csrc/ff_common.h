@@ -222,6 +222,7 @@ struct FFWorkspace {
   // per chunk of `hc` query heads
   float* L;
   uint32_t* chainmask;  // [hc][Cq][ceil(Ck/32)]: key clusters retrieved by some query of the query cluster
+  uint32_t* chainmaskT;  // [hc][Ck][ceil(Cq/32)]: the same bits, key-cluster-major
   // Value summaries and every cell gradient are stored in the input type.  The accumulated k-bar decides
   // selections: fp32 inputs keep it in fp32 (A_k); bf16 inputs keep a bf16 plane A_kb (also the operand of the
   // gradient contractions), an fp16 plane A_km of the remainder and the scalar A_c = mu-bar - scale * qc_i . k-bar
@@ -281,7 +282,7 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
 static inline size_t ff_head_bytes(const MuseDims& d, bool bwd) {
   size_t cells = (size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * d.Ck, D = d.D;
   size_t es = d.dtype == MUSE_DTYPE_BF16 ? 2 : 4;
-  size_t b = ff_al((size_t)d.Cq * d.N * 4) + ff_al((size_t)d.Cq * ((d.Ck + 31) / 32) * 4) + 2 * ff_al(cells * 4) + ff_al(cells * D * 4) + 2 * ff_al(cells * D * es);
+  size_t b = ff_al((size_t)d.Cq * d.N * 4) + ff_al((size_t)d.Cq * ((d.Ck + 31) / 32) * 4) + ff_al((size_t)d.Ck * ((d.Cq + 31) / 32) * 4) + 2 * ff_al(cells * 4) + ff_al(cells * D * 4) + 2 * ff_al(cells * D * es);
   b += es == 2 ? 2 * ff_al(cells * D * 2) + ff_al(cells * 4) : ff_al(cells * D * 4);
   if (bwd) b += 2 * ff_al(cells * 4) + 4 * ff_al(cells * D * es);
   if (d.dipole) b += ff_al((size_t)(d.nb > 1 ? d.nb - 1 : 1) * d.Cq * D * D * 4);
