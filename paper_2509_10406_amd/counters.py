@@ -1,7 +1,7 @@
 """Per-kernel summary of rocprofv3 SQ counter runs of bench.py (matrix-core, vector-unit and LDS activity).
 
     rocprofv3 --pmc SQ_BUSY_CU_CYCLES SQ_WAVE_CYCLES SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_MFMA SQ_INSTS_VALU \
-              SQ_INSTS_LDS SQ_ACTIVE_INST_VALU SQ_ACTIVE_INST_LDS --kernel-include-regex 'k_flash|k_assign_bf16' \
+              SQ_INSTS_LDS SQ_ACTIVE_INST_VALU SQ_ACTIVE_INST_LDS --kernel-include-regex 'k_flash|k_assign' \
               --kernel-trace --output-format csv -d DIR_A -o a -- python3 bench.py --steps 1 --warmup 0 \
               --no-cpu-baseline --no-variants --serial-streams
     rocprofv3 --pmc SQ_WAIT_ANY SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS SQ_ACTIVE_INST_ANY SQ_INSTS_VALU_TRANS_F32 \
@@ -11,7 +11,7 @@
 
 One hardware pass holds at most 8 SQ counters, hence two runs.  bench.py launches the flash kernels twice over:
 for MuSe's block diagonal (block = N / 8: the short launches) and for the in-house exact attention (block = N: the
-long launches); k_assign_bf16 runs for the query side (Cq centroids: short) and the key side (Ck centroids: long).
+long launches); the assignment kernel (k_assign_res, or k_assign_bf16 for the largest C x D) runs for the query side (Cq centroids: short) and the key side (Ck centroids: long).
 The launches of one kernel are split into these two classes by their duration.
 
 Derived columns (per launch averages):
@@ -30,7 +30,7 @@ per-query and per-chain kernels), from
            SQ_ACTIVE_INST_VALU SQ_INSTS_VMEM_WR
     run B: SQ_WAIT_ANY SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS SQ_ACTIVE_INST_ANY SQ_INSTS_VMEM_RD SQ_INSTS_SALU
            SQ_ACTIVE_INST_VMEM SQ_WAVES
-    (--kernel-include-regex 'k_summaries|k_farfield_fwd|k_block_summaries|k_comp2|k_chain_grads|k_cell_grads|k_cells_to_keys_mx|k_ff_bwd')
+    (--kernel-include-regex 'k_summaries|k_farfield_fwd|k_block_summaries|k_comp2|k_chain_grads|k_cell_grads|k_cells_to_keys_mx|k_ff_bwd|k_hit_lists|k_merge_ret|k_ret_|k_c3_pairs|k_update')
     python -m paper_2509_10406_amd.counters DIR_A/a_counter_collection.csv DIR_B/b_counter_collection.csv \
         --mode vector --out profiles/vector_counters_cfg3.txt
 Columns of that mode (per launch averages):
