@@ -861,30 +861,33 @@ __global__ void __launch_bounds__(64) k_c3_reduce(const int32_t* __restrict__ of
 }
 
 // ------------------------------------------------------------------------------------------
-// Retrieval forward (Sec. 3.3 "Exact retrieval"): one wave per retrieved pair and hit slice; the queries
-// that retrieved it are the MFMA columns (32 at a time, rows read straight from Q), its keys the rows.
+// Retrieval forward (Sec. 3.3 "Exact retrieval"): one wave per work item, a run of up to kRunTiles hit tiles of one
+// retrieved pair (a heavy pair is many items, a light one a single item); the queries that retrieved the pair are
+// the MFMA columns (32 at a time, rows read straight from Q), its keys the rows.
 // A pair rarely has more than 32 keys: its key fragments and transposed value tile are then loaded once
 // and reused by every hit tile; the hit list of the next tile is fetched while this one is computed.
 // Writes, per (query, slot), the partial softmax state over the keys of the pair:
 //   part[(qn*R2 + su)][0..D) = sum_m exp(l_m - max) v_m,  [D] = max (natural log units),  [D+1] = sum.
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2, 4))) k_ret_fwd_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Ks,
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, 4))) k_ret_fwd_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Ks,
                                                        const bf16_t* __restrict__ Vs, const int32_t* __restrict__ off_k,
-                                                       const int32_t* __restrict__ pair_off, const uint2* __restrict__ hits,
-                                                       float* __restrict__ part, size_t hit_cap, int N, int nb, int Ck,
-                                                       int Hq, int Hkv, int R2, int S, float scale_log2e) {
+                                                       const int32_t* __restrict__ run_off, const int4* __restrict__ run_map,
+                                                       const uint2* __restrict__ hits, float* __restrict__ part,
+                                                       size_t run_cap, size_t hit_cap, int N, int nb, int Ck,
+                                                       int Hq, int Hkv, int R2, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32, CPR = D / 8, NIT = 32 * CPR / 64;
   __shared__ __attribute__((aligned(16))) bf16_t vt[D][32 + TPAD];
-  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z / S, sl = blockIdx.z % S, NBm = nb - 1;
+  const int hk = blockIdx.y, NBm = nb - 1;
+  if ((int)blockIdx.x >= run_off[(size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)NBm * Ck]) return;  // past the last work item
+  const int4 item = run_map[(size_t)hk * run_cap + blockIdx.x];  // (pair, first hit, end)
   const int G_ = Hq / Hkv;
   const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
   const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
   const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
-  const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
-  const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
-  const int hlo = po[0] + 32 * sl, hhi = po[1];
-  if (klo == khi || hlo >= hhi) return;
+  const int klo = ok[item.x], khi = ok[item.x + 1];  // pair = b' Ck + j indexes the segment table directly
+  const int hlo = item.y, hhi = item.z;
+  if (klo == khi) return;
   const uint2* hh = hits + (size_t)hk * hit_cap;
   const bool single = khi - klo <= 32;
   bf16x8_t kf[KS];
@@ -910,17 +913,37 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
     }
     wave_lds_fence();
   };
+  // the hits of all the item's tiles are requested at once, and the query rows of tile t + 1 while tile t is
+  // computed: one memory round trip per item after the first tile, not two per tile
+  uint2 hitv[kRunTiles];
+#pragma unroll
+  for (int t = 0; t < kRunTiles; ++t) {
+    const int h = hlo + 32 * t + col;
+    hitv[t] = hh[h < hhi ? h : hhi - 1];
+  }
   if (single) stage(klo);
-  uint2 hit = hh[hlo + col < hhi ? hlo + col : hhi - 1];
-  for (int h0 = hlo; h0 < hhi; h0 += 32 * S) {
+  auto qrow = [&](const uint2 h) { return (hqbase + (h.x >> 22)) * N + (h.x & 0x3fffffu); };
+  bf16x8_t qnext[KS];
+  {
+    const size_t q0 = qrow(hitv[0]);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qnext[s] = *reinterpret_cast<const bf16x8_t*>(Q + q0 * D + 16 * s + 8 * half);
+  }
+#pragma unroll
+  for (int ti = 0; ti < kRunTiles; ++ti) {
+    const int h0 = hlo + 32 * ti;
+    if (h0 >= hhi) break;
     const bool hvalid = h0 + col < hhi;
-    const uint2 hcur = hit;
-    const int hn = h0 + 32 * S;
-    if (hn < hhi) hit = hh[hn + col < hhi ? hn + col : hhi - 1];
-    const size_t qn = (hqbase + (hcur.x >> 22)) * N + (hcur.x & 0x3fffffu);
+    const uint2 hcur = hitv[ti];
+    const size_t qn = qrow(hcur);
     bf16x8_t qf[KS];
 #pragma unroll
-    for (int s = 0; s < KS; ++s) qf[s] = *reinterpret_cast<const bf16x8_t*>(Q + qn * D + 16 * s + 8 * half);
+    for (int s = 0; s < KS; ++s) qf[s] = qnext[s];
+    if (ti + 1 < kRunTiles && h0 + 32 < hhi) {
+      const size_t q1 = qrow(hitv[ti + 1 < kRunTiles ? ti + 1 : ti]);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) qnext[s] = *reinterpret_cast<const bf16x8_t*>(Q + q1 * D + 16 * s + 8 * half);
+    }
     f32x16_t o[DT];
 #pragma unroll
     for (int t = 0; t < DT; ++t)
@@ -986,25 +1009,27 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
 // dqpart[(qn*R2 + su)][0..D) = scale * sum_m dl_m k_m over the keys of the pair.
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 1, 3))) k_ret_bwd_dq_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, 3))) k_ret_bwd_dq_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
                                                           const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
                                                           const float* __restrict__ LSE, const float* __restrict__ delta,
                                                           const int32_t* __restrict__ off_k,
-                                                          const int32_t* __restrict__ pair_off,
+                                                          const int32_t* __restrict__ run_off,
+                                                          const int4* __restrict__ run_map,
                                                           const uint2* __restrict__ hits, float* __restrict__ dqpart,
-                                                          size_t hit_cap, int N, int nb, int Ck, int Hq, int Hkv, int R2,
-                                                          int S, float scale, float scale_log2e) {
+                                                          size_t run_cap, size_t hit_cap, int N, int nb, int Ck, int Hq,
+                                                          int Hkv, int R2, float scale, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32, CPR = D / 8, NIT = 32 * CPR / 64;
   __shared__ __attribute__((aligned(16))) bf16_t kt_[D][32 + TPAD];
-  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z / S, sl = blockIdx.z % S, NBm = nb - 1;
+  const int hk = blockIdx.y, NBm = nb - 1;
+  if ((int)blockIdx.x >= run_off[(size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)NBm * Ck]) return;  // past the last work item
+  const int4 item = run_map[(size_t)hk * run_cap + blockIdx.x];  // (pair, first hit, end)
   const int G_ = Hq / Hkv;
   const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
   const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
   const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
-  const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
-  const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
-  const int hlo = po[0] + 32 * sl, hhi = po[1];
-  if (klo == khi || hlo >= hhi) return;
+  const int klo = ok[item.x], khi = ok[item.x + 1];  // pair = b' Ck + j indexes the segment table directly
+  const int hlo = item.y, hhi = item.z;
+  if (klo == khi) return;
   const uint2* hh = hits + (size_t)hk * hit_cap;
   const bool single = khi - klo <= 32;
   bf16x8_t kf[KS], vf[KS];
@@ -1032,21 +1057,48 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
     }
     wave_lds_fence();
   };
+  // the hits of all the item's tiles are requested at once, and the rows of tile t + 1 while tile t is computed
+  uint2 hitv[kRunTiles];
+#pragma unroll
+  for (int t = 0; t < kRunTiles; ++t) {
+    const int h = hlo + 32 * t + col;
+    hitv[t] = hh[h < hhi ? h : hhi - 1];
+  }
   if (single) stage(klo);
-  uint2 hit = hh[hlo + col < hhi ? hlo + col : hhi - 1];
-  for (int h0 = hlo; h0 < hhi; h0 += 32 * S) {
-    const bool hvalid = h0 + col < hhi;
-    const uint2 hcur = hit;
-    const int hn = h0 + 32 * S;
-    if (hn < hhi) hit = hh[hn + col < hhi ? hn + col : hhi - 1];
-    const size_t qn = (hqbase + (hcur.x >> 22)) * N + (hcur.x & 0x3fffffu);
-    bf16x8_t qf[KS], gf[KS];
+  auto qrow = [&](const uint2 h) { return (hqbase + (h.x >> 22)) * N + (h.x & 0x3fffffu); };
+  bf16x8_t qnext[KS], gnext[KS];
+  float lnext, dnext;
+  {
+    const size_t q0 = qrow(hitv[0]);
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      qf[s] = *reinterpret_cast<const bf16x8_t*>(Q + qn * D + 16 * s + 8 * half);
-      gf[s] = *reinterpret_cast<const bf16x8_t*>(dO + qn * D + 16 * s + 8 * half);
+      qnext[s] = *reinterpret_cast<const bf16x8_t*>(Q + q0 * D + 16 * s + 8 * half);
+      gnext[s] = *reinterpret_cast<const bf16x8_t*>(dO + q0 * D + 16 * s + 8 * half);
     }
-    const float lse2 = LSE[qn] * 1.4426950408889634f, dl = delta[qn];
+    lnext = LSE[q0];
+    dnext = delta[q0];
+  }
+#pragma unroll
+  for (int ti = 0; ti < kRunTiles; ++ti) {
+    const int h0 = hlo + 32 * ti;
+    if (h0 >= hhi) break;
+    const bool hvalid = h0 + col < hhi;
+    const uint2 hcur = hitv[ti];
+    const size_t qn = qrow(hcur);
+    bf16x8_t qf[KS], gf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) { qf[s] = qnext[s]; gf[s] = gnext[s]; }
+    const float lse2 = lnext * 1.4426950408889634f, dl = dnext;
+    if (ti + 1 < kRunTiles && h0 + 32 < hhi) {
+      const size_t q1 = qrow(hitv[ti + 1 < kRunTiles ? ti + 1 : ti]);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        qnext[s] = *reinterpret_cast<const bf16x8_t*>(Q + q1 * D + 16 * s + 8 * half);
+        gnext[s] = *reinterpret_cast<const bf16x8_t*>(dO + q1 * D + 16 * s + 8 * half);
+      }
+      lnext = LSE[q1];
+      dnext = delta[q1];
+    }
     f32x16_t dq[DT];
 #pragma unroll
     for (int t = 0; t < DT; ++t)
@@ -1477,28 +1529,29 @@ int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO
 }
 
 int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, const void* Vs, const int32_t* off_k,
-                              const int32_t* pair_off, const uint2* hits, size_t hit_cap, float* part, hipStream_t st) {
-  const int S = 8;  // hit slices per pair: slice s takes the hit tiles s, s + S, ... (a few pairs hold thousands of hits)
-  dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv * S);
+                              const int32_t* run_off, const int4* run_map, size_t run_cap, const uint2* hits,
+                              size_t hit_cap, float* part, hipStream_t st) {
+  // one wave per work item (a run of hit tiles inside one pair); the grid covers the most there can be
+  dim3 g((unsigned)run_cap, d.B * d.Hkv);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64)
-    { MuseProf prof_("k_ret_fwd_pairs", st); hipLaunchKernelGGL(k_ret_fwd_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)Ks, (const bf16_t*)Vs, off_k, pair_off, hits, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, S, sl); }
+    { MuseProf prof_("k_ret_fwd_pairs", st); hipLaunchKernelGGL(k_ret_fwd_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)Ks, (const bf16_t*)Vs, off_k, run_off, run_map, hits, part, run_cap, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, sl); }
   else
-    { MuseProf prof_("k_ret_fwd_pairs", st); hipLaunchKernelGGL(k_ret_fwd_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)Ks, (const bf16_t*)Vs, off_k, pair_off, hits, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, S, sl); }
+    { MuseProf prof_("k_ret_fwd_pairs", st); hipLaunchKernelGGL(k_ret_fwd_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)Ks, (const bf16_t*)Vs, off_k, run_off, run_map, hits, part, run_cap, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, sl); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
 
 int muse_launch_ret_bwd_dq_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
-                                 const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
-                                 const uint2* hits, size_t hit_cap, float* dqpart, hipStream_t st) {
-  const int S = 8;  // hit slices per pair, as in the forward
-  dim3 g(d.Ck, d.nb - 1, d.B * d.Hkv * S);
+                                 const float* LSE, const float* delta, const int32_t* off_k, const int32_t* run_off,
+                                 const int4* run_map, size_t run_cap, const uint2* hits, size_t hit_cap, float* dqpart,
+                                 hipStream_t st) {
+  dim3 g((unsigned)run_cap, d.B * d.Hkv);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64)
-    { MuseProf prof_("k_ret_bwd_dq_pairs", st); hipLaunchKernelGGL(k_ret_bwd_dq_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks, (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dqpart, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, S, d.scale, sl); }
+    { MuseProf prof_("k_ret_bwd_dq_pairs", st); hipLaunchKernelGGL(k_ret_bwd_dq_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks, (const bf16_t*)Vs, LSE, delta, off_k, run_off, run_map, hits, dqpart, run_cap, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, d.scale, sl); }
   else
-    { MuseProf prof_("k_ret_bwd_dq_pairs", st); hipLaunchKernelGGL(k_ret_bwd_dq_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks, (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dqpart, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, S, d.scale, sl); }
+    { MuseProf prof_("k_ret_bwd_dq_pairs", st); hipLaunchKernelGGL(k_ret_bwd_dq_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks, (const bf16_t*)Vs, LSE, delta, off_k, run_off, run_map, hits, dqpart, run_cap, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, d.r * d.k2e, d.scale, sl); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }

@@ -1059,6 +1059,9 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
     w->pairmask = (uint32_t*)take(ff_pairmask_bytes(d));
     w->pair_off = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
     w->pair_cnt = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
+    w->run_off = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
+    w->run_cap = ff_run_cap(d);
+    w->run_map = (int4*)take(HK * w->run_cap * 16);
     w->seg_cnt = (int32_t*)take(ff_segcnt_bytes(d));
     w->seg_off = (int32_t*)take(ff_segcnt_bytes(d));
     w->hit_cap = (size_t)(d.Hq / d.Hkv) * N * R2;
@@ -1249,7 +1252,7 @@ int run_fwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const f
   if (d.nb > 1 && d.r > 0 && sizeof(T) == 2) {
     // exact retrieval (Sec. 3.3): inverse index pair -> queries, one dense MFMA block per retrieved pair
     if ((rc = muse_ff_build_inverse_index(d, selc, selb, w, true, st))) return rc;
-    if ((rc = muse_launch_ret_fwd_pairs(d, Q, w.Ks, w.Vs, w.off_k, w.pair_off, w.hits, w.hit_cap, w.ret_part, st))) return rc;
+    if ((rc = muse_launch_ret_fwd_pairs(d, Q, w.Ks, w.Vs, w.off_k, w.run_off, w.run_map, w.run_cap, w.hits, w.hit_cap, w.ret_part, st))) return rc;
     if ((rc = muse_launch_merge_ret(d, selb, w.ret_part, w.ff_acc, w.ff_ml, st))) return rc;
   }
   return muse_launch_attn_fwd(d, d.Bs, Q, K, V, w.ff_acc, O, LSE, st);

@@ -1308,8 +1308,8 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
           MUSE_HIP_CHECK(hipEventRecord(ax.mid, st));
           MUSE_HIP_CHECK(hipStreamWaitEvent(sb, ax.mid, 0));
         }
-        if ((rc = muse_launch_ret_bwd_dq_pairs(d, Q, dO, w.Ks, w.Vs, LSE, w.delta, w.off_k, w.pair_off, w.hits, w.hit_cap,
-                                               w.ret_part, split ? sb : st)))
+        if ((rc = muse_launch_ret_bwd_dq_pairs(d, Q, dO, w.Ks, w.Vs, LSE, w.delta, w.off_k, w.run_off, w.run_map, w.run_cap, w.hits,
+                                               w.hit_cap, w.ret_part, split ? sb : st)))
           return rc;
       } else {
         dim3 g((d.Ck + 31) / 32, d.nb - 1, HK);

@@ -195,6 +195,7 @@ __device__ __forceinline__ bf16x8_t cvt8(const float* __restrict__ p) {
 
 constexpr int kMaxCk = 2304;  // key clusters a kernel can index in LDS
 static_assert(kMaxCk >= MUSE_MAX_CLUSTERS, "the host accepts more clusters than the kernels index");
+constexpr int kRunTiles = 4;  // hit tiles (of 32) per work item of the retrieval forward / dq pair kernels
 constexpr int kC3Slices = 8;  // most waves that share the hits of one retrieved pair in the key/value gradients
 constexpr int kC3TilesPerSlice = 4;  // a pair gets one slice per so many tiles of 32 hits
 
@@ -209,7 +210,10 @@ struct FFWorkspace {
   int32_t* slotinfo;   // [HQ][N][r] by bucketed query position: cluster | retrieved-block mask << 16
   uint32_t* pairmask;  // [HQ][nb-1][W][N], fp32 inputs only
   int32_t* pair_off;             // inverse index of the retrieval: (kv head, key block, key cluster) -> hits
-  int32_t* pair_cnt;             // hits per pair, [HK][pairs + 1]
+  int32_t* pair_cnt;             // hits per pair (later: runs per pair), [HK][pairs + 1]
+  int32_t* run_off;              // [HK][pairs + 1]: first work item of every pair, [pairs] = their number
+  int4* run_map;                 // [HK][run_cap]: (pair, first hit, end) of a work item
+  size_t run_cap;                // work items per kv head the map can hold
   int32_t *seg_cnt, *seg_off;    // its construction: counts / list starts [HK][head of the group x query slice][pair]
   uint2* hits;                   // x = n | g << 22 (query position, head inside the KV group), y = slot*k2e + u
   size_t hit_cap;                // hits per kv head
@@ -252,6 +256,12 @@ static inline size_t ff_pairmask_bytes(const MuseDims& d) {
   size_t HQ = (size_t)d.B * d.Hq, W = (d.Ck + 31) / 32, NBm = d.nb > 1 ? d.nb - 1 : 1;
   return d.dtype == MUSE_DTYPE_BF16 ? 0 : HQ * d.N * W * 4 * NBm;
 }
+// most work items (runs of kRunTiles hit tiles inside one pair) a kv head can have
+static inline size_t ff_run_cap(const MuseDims& d) {
+  size_t NBm = d.nb > 1 ? d.nb - 1 : 1, R2 = (size_t)(d.r > 0 ? d.r : 1) * d.k2e;
+  size_t npair = NBm * d.Ck, hits = (size_t)(d.Hq / d.Hkv) * d.N * R2;
+  return (hits / 32 + npair) / kRunTiles + npair + 1;
+}
 static inline size_t ff_segcnt_bytes(const MuseDims& d) {
   size_t HK = (size_t)d.B * d.Hkv, NBm = d.nb > 1 ? d.nb - 1 : 1;
   return d.dtype == MUSE_DTYPE_BF16 ? HK * (d.Hq / d.Hkv) * ff_hit_segments(d) * NBm * d.Ck * 4 : 0;
@@ -266,7 +276,8 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
              ff_al(HQ * ((size_t)d.nb * d.Cq + 1) * 4) + ff_al(HQ * d.nb * ((size_t)d.Cq + 1) * 4) +
              2 * ff_al(HK * N * D * es) + ff_al(HQ * N * (D + 2) * 4);
   // inverse index of the retrieval and its per-(query, slot) partial results
-  b += ff_al(ff_pairmask_bytes(d)) + 2 * ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) + 2 * ff_al(ff_segcnt_bytes(d)) +
+  b += ff_al(ff_pairmask_bytes(d)) + 3 * ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) + 2 * ff_al(ff_segcnt_bytes(d)) +
+       ff_al(HK * ff_run_cap(d) * 16) +
        ff_al(HQ * N * R2 * 8) +
        ff_al(HQ * N * R2 * (D + 4) * 4);
   if (bwd) {
@@ -305,10 +316,12 @@ int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const
                          const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
                          const uint2* hits, size_t hit_cap, float* dKs, float* dVs, float* part, hipStream_t st);
 int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, const void* Vs, const int32_t* off_k,
-                              const int32_t* pair_off, const uint2* hits, size_t hit_cap, float* part, hipStream_t st);
+                              const int32_t* run_off, const int4* run_map, size_t run_cap, const uint2* hits,
+                              size_t hit_cap, float* part, hipStream_t st);
 int muse_launch_ret_bwd_dq_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
-                                 const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
-                                 const uint2* hits, size_t hit_cap, float* dqpart, hipStream_t st);
+                                 const float* LSE, const float* delta, const int32_t* off_k, const int32_t* run_off,
+                                 const int4* run_map, size_t run_cap, const uint2* hits, size_t hit_cap, float* dqpart,
+                                 hipStream_t st);
 int muse_launch_ff_bwd_cells_mx(const MuseDims& d, const void* Q, const void* dO, const float* qc, const float* A_mu,
                                 const void* A_kb, const void* A_v, const int32_t* perm_q, const int32_t* off_q,
                                 const float* LSE, const float* delta, const uint32_t* selmask, float* g_A_c,

@@ -60,7 +60,8 @@ __global__ void __launch_bounds__(64 * kHitWaves) k_hit_lists(const int32_t* __r
       const int j = valid ? selc[qn * r + t] : -1;
       for (int u = 0; u < k2e; ++u) {
         const int bp = j >= 0 ? selb[(qn * r + t) * k2e + u] : -1;
-        const int pair = bp >= 0 ? bp * Ck + j : -1;
+        // (selections are trusted inputs; one outside the table is dropped rather than indexed)
+        const int pair = (bp >= 0 && j < Ck && bp * Ck + j < npair) ? bp * Ck + j : -1;
         unsigned long long act = __ballot(pair >= 0 && pair % kHitWaves == wave);
         while (act) {
           const int src = __ffsll((long long)act) - 1;
@@ -104,6 +105,28 @@ __global__ void __launch_bounds__(256) k_seg_offsets(const int32_t* __restrict__
     seg_off[base + (size_t)gs * npair] = run;
     run += seg_cnt[base + (size_t)gs * npair];
   }
+}
+
+// Work items of the per-pair retrieval kernels: a pair's hit tiles (32 hits each) are cut into runs of kRunTiles, so
+// a heavy pair becomes many equal items and a light one a single item (no empty slices, no tails).
+//   run_cnt[hk][p] = runs of pair p;  run_map[hk][run_off[hk][p] + u] = (p, first hit of run u, end of the run)
+__global__ void __launch_bounds__(256) k_run_counts(const int32_t* __restrict__ pair_off, int32_t* __restrict__ run_cnt, int npair) {
+  const int hk = blockIdx.y, p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= npair) return;
+  const int32_t* po = pair_off + (size_t)hk * (npair + 1);
+  const int tiles = (po[p + 1] - po[p] + 31) / 32;
+  run_cnt[(size_t)hk * (npair + 1) + p] = (tiles + kRunTiles - 1) / kRunTiles;
+}
+__global__ void __launch_bounds__(256) k_run_fill(const int32_t* __restrict__ pair_off, const int32_t* __restrict__ run_off,
+                                                   int4* __restrict__ run_map, int npair, size_t run_cap) {
+  const int hk = blockIdx.y, p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= npair) return;
+  const int32_t* po = pair_off + (size_t)hk * (npair + 1);
+  const int32_t* ro = run_off + (size_t)hk * (npair + 1);
+  const int lo = po[p], hi = po[p + 1];
+  int4* out = run_map + (size_t)hk * run_cap + ro[p];
+  for (int u = 0, h = lo; h < hi; ++u, h += 32 * kRunTiles)
+    out[u] = make_int4(p, h, h + 32 * kRunTiles < hi ? h + 32 * kRunTiles : hi, 0);
 }
 
 // exclusive prefix of n counts per kv head, off[n] = total
@@ -195,6 +218,10 @@ int muse_ff_build_inverse_index(const MuseDims& d, const int32_t* selc, const in
   { MuseProf prof_("k_pair_scan", st); hipLaunchKernelGGL(k_pair_scan, dim3(HK), dim3(1024), 0, st, w.pair_cnt, w.pair_off, npair); }
   { MuseProf prof_("k_seg_offsets", st); hipLaunchKernelGGL(k_seg_offsets, gp, dim3(256), 0, st, w.seg_cnt, w.pair_off, w.seg_off, npair, SEGT); }
   { MuseProf prof_("k_hit_lists", st); hipLaunchKernelGGL(k_hit_lists<true>, g, dim3(64 * kHitWaves), lds, st, selc, selb, w.seg_cnt, w.seg_off, w.hits, w.hit_cap, N, d.Bs, d.Ck, d.r, d.k2e, d.Hq, d.Hkv, npair, SEG, cps); }
+  // the pair kernels' work items (pair_cnt is free again: it holds the runs per pair now)
+  { MuseProf prof_("k_run_counts", st); hipLaunchKernelGGL(k_run_counts, gp, dim3(256), 0, st, w.pair_off, w.pair_cnt, npair); }
+  { MuseProf prof_("k_pair_scan", st); hipLaunchKernelGGL(k_pair_scan, dim3(HK), dim3(1024), 0, st, w.pair_cnt, w.run_off, npair); }
+  { MuseProf prof_("k_run_fill", st); hipLaunchKernelGGL(k_run_fill, gp, dim3(256), 0, st, w.pair_off, w.run_off, w.run_map, npair, w.run_cap); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
