@@ -669,33 +669,33 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 // rows of the pair's keys, the others write partial rows, which k_c3_reduce adds in slice order (fixed order, no
 // atomics).  S depends on the pair's hit count only.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ int c3_slices(int nhits) {
-  const int nt = (nhits + 31) / 32;
-  const int s = nt / kC3TilesPerSlice;
-  return s < 1 ? 1 : (s > kC3Slices ? kC3Slices : s);
-}
 
 template <int D>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, D == 64 ? 2 : 1))) k_c3_pairs(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ dO,
                                                   const bf16_t* __restrict__ Ks, const bf16_t* __restrict__ Vs,
                                                   const float* __restrict__ LSE, const float* __restrict__ delta,
                                                   const int32_t* __restrict__ off_k, const int32_t* __restrict__ pair_off,
+                                                  const int32_t* __restrict__ c3_off, const int2* __restrict__ c3_map,
                                                   const uint2* __restrict__ hits, float* __restrict__ dKs,
-                                                  float* __restrict__ dVs, float* __restrict__ part, size_t hit_cap,
-                                                  int N, int nb, int Ck, int Hq, int Hkv, int HK, float scale,
-                                                  float scale_log2e) {
+                                                  float* __restrict__ dVs, float* __restrict__ part, size_t run_cap,
+                                                  size_t hit_cap, int N, int nb, int Ck, int Hq, int Hkv, int HK,
+                                                  float scale, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(16))) bf16_t qt_[D][32 + TPAD];
   __shared__ __attribute__((aligned(16))) bf16_t gt_[D][32 + TPAD];
   __shared__ __attribute__((aligned(16))) float lse_s[32];
   __shared__ __attribute__((aligned(16))) float dl_s[32];
-  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z % HK, sl = blockIdx.z / HK, NBm = nb - 1;
+  // one wave per work item (pair, hit slice): only the slices a pair has are launched
+  const int hk = blockIdx.y, NBm = nb - 1;
+  if ((int)blockIdx.x >= c3_off[(size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)NBm * Ck]) return;  // past the last item
+  const int2 item = c3_map[(size_t)hk * run_cap + blockIdx.x];  // (pair, slice)
+  const int sl = item.y;
   const int G_ = Hq / Hkv;
   const size_t hqbase = (size_t)(hk / Hkv) * Hq + (size_t)(hk % Hkv) * G_;
   const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
   const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
-  const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
-  const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
+  const int klo = ok[item.x], khi = ok[item.x + 1];  // pair = b' Ck + j indexes the segment table directly
+  const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + item.x;
   const int hlo = po[0], hhi = po[1];
   if (klo == khi || hlo == hhi) return;
   const int S = c3_slices(hhi - hlo);
@@ -1558,17 +1558,18 @@ int muse_launch_ret_bwd_dq_pairs(const MuseDims& d, const void* Q, const void* d
 
 int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
                          const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
-                         const uint2* hits, size_t hit_cap, float* dKs, float* dVs, float* part, hipStream_t st) {
+                         const int32_t* c3_off, const int2* c3_map, size_t run_cap, const uint2* hits, size_t hit_cap,
+                         float* dKs, float* dVs, float* part, hipStream_t st) {
   const int HK = d.B * d.Hkv;
-  dim3 g(d.Ck, d.nb - 1, HK * kC3Slices), gr(d.Ck, d.nb - 1, HK);
+  dim3 g((unsigned)run_cap, HK), gr(d.Ck, d.nb - 1, HK);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64) {
     { MuseProf prof_("k_c3_pairs", st); hipLaunchKernelGGL(k_c3_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks,
-                       (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dKs, dVs, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, HK, d.scale, sl); }
+                       (const bf16_t*)Vs, LSE, delta, off_k, pair_off, c3_off, c3_map, hits, dKs, dVs, part, run_cap, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, HK, d.scale, sl); }
     { MuseProf prof_("k_c3_reduce", st); hipLaunchKernelGGL(k_c3_reduce<64>, gr, dim3(64), 0, st, off_k, pair_off, part, dKs, dVs, d.N, d.nb, d.Ck, HK); }
   } else {
     { MuseProf prof_("k_c3_pairs", st); hipLaunchKernelGGL(k_c3_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks,
-                       (const bf16_t*)Vs, LSE, delta, off_k, pair_off, hits, dKs, dVs, part, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, HK, d.scale, sl); }
+                       (const bf16_t*)Vs, LSE, delta, off_k, pair_off, c3_off, c3_map, hits, dKs, dVs, part, run_cap, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, HK, d.scale, sl); }
     { MuseProf prof_("k_c3_reduce", st); hipLaunchKernelGGL(k_c3_reduce<128>, gr, dim3(64), 0, st, off_k, pair_off, part, dKs, dVs, d.N, d.nb, d.Ck, HK); }
   }
   MUSE_LAUNCH_CHECK();

@@ -1062,6 +1062,8 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
     w->run_off = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
     w->run_cap = ff_run_cap(d);
     w->run_map = (int4*)take(HK * w->run_cap * 16);
+    w->c3_off = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
+    w->c3_map = (int2*)take(HK * w->run_cap * 8);
     w->seg_cnt = (int32_t*)take(ff_segcnt_bytes(d));
     w->seg_off = (int32_t*)take(ff_segcnt_bytes(d));
     w->hit_cap = (size_t)(d.Hq / d.Hkv) * N * R2;

@@ -1301,8 +1301,8 @@ int run_bwd_typed(const MuseDims& d, const T* Q, const T* K, const T* V, const T
       if (!reuse || sizeof(T) == 4)
         if ((rc = muse_ff_build_inverse_index(d, selc, selb, w, sizeof(T) == 2, st))) return rc;
       if (sizeof(T) == 2) {
-        if ((rc = muse_launch_c3_pairs(d, Q, dO, w.Ks, w.Vs, LSE, w.delta, w.off_k, w.pair_off, w.hits, w.hit_cap, w.dKs,
-                                       w.dVs, w.c3_part, st)))
+        if ((rc = muse_launch_c3_pairs(d, Q, dO, w.Ks, w.Vs, LSE, w.delta, w.off_k, w.pair_off, w.c3_off, w.c3_map, w.run_cap, w.hits,
+                                       w.hit_cap, w.dKs, w.dVs, w.c3_part, st)))
           return rc;
         if (split) {
           MUSE_HIP_CHECK(hipEventRecord(ax.mid, st));

@@ -198,6 +198,12 @@ static_assert(kMaxCk >= MUSE_MAX_CLUSTERS, "the host accepts more clusters than 
 constexpr int kRunTiles = 4;  // hit tiles (of 32) per work item of the retrieval forward / dq pair kernels
 constexpr int kC3Slices = 8;  // most waves that share the hits of one retrieved pair in the key/value gradients
 constexpr int kC3TilesPerSlice = 4;  // a pair gets one slice per so many tiles of 32 hits
+// hit slices of a pair in the key/value gradient kernel of the retrieval (depends on its hit count only)
+__host__ __device__ inline int c3_slices(int nhits) {
+  const int nt = (nhits + 31) / 32;
+  const int s = nt / kC3TilesPerSlice;
+  return s < 1 ? 1 : (s > kC3Slices ? kC3Slices : s);
+}
 
 struct FFWorkspace {
   // all heads
@@ -213,6 +219,8 @@ struct FFWorkspace {
   int32_t* pair_cnt;             // hits per pair (later: runs per pair), [HK][pairs + 1]
   int32_t* run_off;              // [HK][pairs + 1]: first work item of every pair, [pairs] = their number
   int4* run_map;                 // [HK][run_cap]: (pair, first hit, end) of a work item
+  int32_t* c3_off;               // [HK][pairs + 1]: first (pair, hit slice) item of every pair, [pairs] = their number
+  int2* c3_map;                  // [HK][run_cap]: (pair, slice) items of the key/value gradient kernel
   size_t run_cap;                // work items per kv head the map can hold
   int32_t *seg_cnt, *seg_off;    // its construction: counts / list starts [HK][head of the group x query slice][pair]
   uint2* hits;                   // x = n | g << 22 (query position, head inside the KV group), y = slot*k2e + u
@@ -276,8 +284,8 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
              ff_al(HQ * ((size_t)d.nb * d.Cq + 1) * 4) + ff_al(HQ * d.nb * ((size_t)d.Cq + 1) * 4) +
              2 * ff_al(HK * N * D * es) + ff_al(HQ * N * (D + 2) * 4);
   // inverse index of the retrieval and its per-(query, slot) partial results
-  b += ff_al(ff_pairmask_bytes(d)) + 3 * ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) + 2 * ff_al(ff_segcnt_bytes(d)) +
-       ff_al(HK * ff_run_cap(d) * 16) +
+  b += ff_al(ff_pairmask_bytes(d)) + 4 * ff_al(HK * ((size_t)d.nb * d.Ck + 1) * 4) + 2 * ff_al(ff_segcnt_bytes(d)) +
+       ff_al(HK * ff_run_cap(d) * 16) + ff_al(HK * ff_run_cap(d) * 8) +
        ff_al(HQ * N * R2 * 8) +
        ff_al(HQ * N * R2 * (D + 4) * 4);
   if (bwd) {
@@ -314,7 +322,8 @@ int muse_ff_block_summaries(const MuseDims& d, const int32_t* selc, const int32_
 // attn_mfma.hip
 int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const void* Ks, const void* Vs,
                          const float* LSE, const float* delta, const int32_t* off_k, const int32_t* pair_off,
-                         const uint2* hits, size_t hit_cap, float* dKs, float* dVs, float* part, hipStream_t st);
+                         const int32_t* c3_off, const int2* c3_map, size_t run_cap, const uint2* hits, size_t hit_cap,
+                         float* dKs, float* dVs, float* part, hipStream_t st);
 int muse_launch_ret_fwd_pairs(const MuseDims& d, const void* Q, const void* Ks, const void* Vs, const int32_t* off_k,
                               const int32_t* run_off, const int4* run_map, size_t run_cap, const uint2* hits,
                               size_t hit_cap, float* part, hipStream_t st);

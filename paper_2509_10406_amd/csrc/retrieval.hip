@@ -129,6 +129,25 @@ __global__ void __launch_bounds__(256) k_run_fill(const int32_t* __restrict__ pa
     out[u] = make_int4(p, h, h + 32 * kRunTiles < hi ? h + 32 * kRunTiles : hi, 0);
 }
 
+// The same for the key/value gradient kernel: its items are (pair, hit slice), c3_slices of them per pair that has hits.
+__global__ void __launch_bounds__(256) k_c3_counts(const int32_t* __restrict__ pair_off, int32_t* __restrict__ cnt, int npair) {
+  const int hk = blockIdx.y, p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= npair) return;
+  const int32_t* po = pair_off + (size_t)hk * (npair + 1);
+  const int h = po[p + 1] - po[p];
+  cnt[(size_t)hk * (npair + 1) + p] = h > 0 ? c3_slices(h) : 0;
+}
+__global__ void __launch_bounds__(256) k_c3_fill(const int32_t* __restrict__ pair_off, const int32_t* __restrict__ c3_off,
+                                                  int2* __restrict__ c3_map, int npair, size_t run_cap) {
+  const int hk = blockIdx.y, p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= npair) return;
+  const int32_t* po = pair_off + (size_t)hk * (npair + 1);
+  const int h = po[p + 1] - po[p];
+  const int S = h > 0 ? c3_slices(h) : 0;
+  int2* out = c3_map + (size_t)hk * run_cap + c3_off[(size_t)hk * (npair + 1) + p];
+  for (int u = 0; u < S; ++u) out[u] = make_int2(p, u);
+}
+
 // exclusive prefix of n counts per kv head, off[n] = total
 __global__ void __launch_bounds__(1024) k_pair_scan(const int32_t* __restrict__ cnt, int32_t* __restrict__ off, int n) {
   __shared__ int wsum[16];
@@ -222,6 +241,9 @@ int muse_ff_build_inverse_index(const MuseDims& d, const int32_t* selc, const in
   { MuseProf prof_("k_run_counts", st); hipLaunchKernelGGL(k_run_counts, gp, dim3(256), 0, st, w.pair_off, w.pair_cnt, npair); }
   { MuseProf prof_("k_pair_scan", st); hipLaunchKernelGGL(k_pair_scan, dim3(HK), dim3(1024), 0, st, w.pair_cnt, w.run_off, npair); }
   { MuseProf prof_("k_run_fill", st); hipLaunchKernelGGL(k_run_fill, gp, dim3(256), 0, st, w.pair_off, w.run_off, w.run_map, npair, w.run_cap); }
+  { MuseProf prof_("k_c3_counts", st); hipLaunchKernelGGL(k_c3_counts, gp, dim3(256), 0, st, w.pair_off, w.pair_cnt, npair); }
+  { MuseProf prof_("k_pair_scan", st); hipLaunchKernelGGL(k_pair_scan, dim3(HK), dim3(1024), 0, st, w.pair_cnt, w.c3_off, npair); }
+  { MuseProf prof_("k_c3_fill", st); hipLaunchKernelGGL(k_c3_fill, gp, dim3(256), 0, st, w.pair_off, w.c3_off, w.c3_map, npair, w.run_cap); }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
