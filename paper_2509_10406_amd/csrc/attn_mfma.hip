@@ -837,14 +837,18 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
 // (key cluster, key block, kv head), 16 lanes per key row
 template <int D>
 __global__ void __launch_bounds__(64) k_c3_reduce(const int32_t* __restrict__ off_k, const int32_t* __restrict__ pair_off,
+                                                   const int32_t* __restrict__ c3_off, const int2* __restrict__ c3_map,
                                                    const float* __restrict__ part, float* __restrict__ dKs,
-                                                   float* __restrict__ dVs, int N, int nb, int Ck, int HK) {
-  const int j = blockIdx.x, bp = blockIdx.y, hk = blockIdx.z, NBm = nb - 1;
-  const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)bp * Ck + j;
+                                                   float* __restrict__ dVs, size_t run_cap, int N, int nb, int Ck, int HK) {
+  // walks the same item list as k_c3_pairs: the item (pair, slice 1) exists exactly for the pairs with partial rows
+  const int hk = blockIdx.y, NBm = nb - 1;
+  if ((int)blockIdx.x >= c3_off[(size_t)hk * ((size_t)NBm * Ck + 1) + (size_t)NBm * Ck]) return;
+  const int2 item = c3_map[(size_t)hk * run_cap + blockIdx.x];
+  if (item.y != 1) return;
+  const int32_t* po = pair_off + (size_t)hk * ((size_t)NBm * Ck + 1) + item.x;
   const int S = c3_slices(po[1] - po[0]);
-  if (po[1] == po[0] || S == 1) return;
   const int32_t* ok = off_k + (size_t)hk * ((size_t)nb * Ck + 1);
-  const int klo = ok[bp * Ck + j], khi = ok[bp * Ck + j + 1];
+  const int klo = ok[item.x], khi = ok[item.x + 1];
   const int lane = threadIdx.x, sub = lane / 16, l16 = lane % 16;
   for (int m = klo + sub; m < khi; m += 4)
     for (int d = 4 * l16; d < 2 * D; d += 64) {  // the row pair [dK | dV] as 2 D floats
@@ -1561,16 +1565,16 @@ int muse_launch_c3_pairs(const MuseDims& d, const void* Q, const void* dO, const
                          const int32_t* c3_off, const int2* c3_map, size_t run_cap, const uint2* hits, size_t hit_cap,
                          float* dKs, float* dVs, float* part, hipStream_t st) {
   const int HK = d.B * d.Hkv;
-  dim3 g((unsigned)run_cap, HK), gr(d.Ck, d.nb - 1, HK);
+  dim3 g((unsigned)run_cap, HK), gr((unsigned)run_cap, HK);
   float sl = d.scale * 1.4426950408889634f;
   if (d.D == 64) {
     { MuseProf prof_("k_c3_pairs", st); hipLaunchKernelGGL(k_c3_pairs<64>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks,
                        (const bf16_t*)Vs, LSE, delta, off_k, pair_off, c3_off, c3_map, hits, dKs, dVs, part, run_cap, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, HK, d.scale, sl); }
-    { MuseProf prof_("k_c3_reduce", st); hipLaunchKernelGGL(k_c3_reduce<64>, gr, dim3(64), 0, st, off_k, pair_off, part, dKs, dVs, d.N, d.nb, d.Ck, HK); }
+    { MuseProf prof_("k_c3_reduce", st); hipLaunchKernelGGL(k_c3_reduce<64>, gr, dim3(64), 0, st, off_k, pair_off, c3_off, c3_map, part, dKs, dVs, run_cap, d.N, d.nb, d.Ck, HK); }
   } else {
     { MuseProf prof_("k_c3_pairs", st); hipLaunchKernelGGL(k_c3_pairs<128>, g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)dO, (const bf16_t*)Ks,
                        (const bf16_t*)Vs, LSE, delta, off_k, pair_off, c3_off, c3_map, hits, dKs, dVs, part, run_cap, hit_cap, d.N, d.nb, d.Ck, d.Hq, d.Hkv, HK, d.scale, sl); }
-    { MuseProf prof_("k_c3_reduce", st); hipLaunchKernelGGL(k_c3_reduce<128>, gr, dim3(64), 0, st, off_k, pair_off, part, dKs, dVs, d.N, d.nb, d.Ck, HK); }
+    { MuseProf prof_("k_c3_reduce", st); hipLaunchKernelGGL(k_c3_reduce<128>, gr, dim3(64), 0, st, off_k, pair_off, c3_off, c3_map, part, dKs, dVs, run_cap, d.N, d.nb, d.Ck, HK); }
   }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
