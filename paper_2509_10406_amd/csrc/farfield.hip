@@ -879,10 +879,17 @@ __global__ void __launch_bounds__(256) k_comp2_fwd(
 #pragma unroll
       for (int t = 0; t < 4; ++t) o[x][t] = o[x][t] * a + p * v[x][t];
   };
+  // the query's first eight retrieved clusters are read up front: a cluster's rows then wait for one round trip
+  int sel8[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) sel8[t] = t < r ? selc[qn * r + t] : -1;
   auto run = [&](auto bw_c) {
   constexpr int bw = decltype(bw_c)::value;
   for (int t = 0; t < r; ++t) {
-    const int j = selc[qn * r + t];
+    int j = -1;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) j = t == u ? sel8[u] : j;
+    if (t >= 8) j = selc[qn * r + t];
     if (j < 0) continue;
     // scores of the preceding blocks, 8 at a time: every load of a chunk is in flight together (with at
     // most 8 preceding blocks the value rows ride along, one round trip per retrieved cluster)
