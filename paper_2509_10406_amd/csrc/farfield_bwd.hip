@@ -467,16 +467,35 @@ __global__ void __launch_bounds__(256) k_comp2_bwd_dq(
 #pragma unroll
     for (int t = 0; t < 4; ++t) dq[x][t] *= scale;
   // retrieval part, computed per retrieved pair (already scaled); a slot's pair u exists iff its block bit is set
-  for (int t = 0; t < r; ++t) {
-    const int info = si[t];
-    if (info < 0 || ((unsigned)info >> 16) == 0u) continue;
-    for (int u = 0; u < k2e; ++u) {
-      const float* pp = dqpart + (qn * r * k2e + t * k2e + u) * D;
-      if (u < __popc((unsigned)info >> 16)) {
+  if (k2e == 1 && r <= 8) {
+    // the usual shape: the partial rows of all slots are requested together and added in slot order
+    int inf[8];
 #pragma unroll
-        for (int x = 0; x < NG; ++x) {
-          const float4 v = *reinterpret_cast<const float4*>(pp + 64 * x + 4 * l16);
-          dq[x][0] += v.x; dq[x][1] += v.y; dq[x][2] += v.z; dq[x][3] += v.w;
+    for (int t = 0; t < 8; ++t) inf[t] = t < r ? si[t] : -1;
+    float4 v[8][NG];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const bool ok = inf[t] >= 0 && ((unsigned)inf[t] >> 16) != 0u;
+#pragma unroll
+      for (int x = 0; x < NG; ++x)
+        v[t][x] = ok ? *reinterpret_cast<const float4*>(dqpart + (qn * r + t) * D + 64 * x + 4 * l16) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+      for (int x = 0; x < NG; ++x) { dq[x][0] += v[t][x].x; dq[x][1] += v[t][x].y; dq[x][2] += v[t][x].z; dq[x][3] += v[t][x].w; }
+  } else {
+    for (int t = 0; t < r; ++t) {
+      const int info = si[t];
+      if (info < 0 || ((unsigned)info >> 16) == 0u) continue;
+      for (int u = 0; u < k2e; ++u) {
+        const float* pp = dqpart + (qn * r * k2e + t * k2e + u) * D;
+        if (u < __popc((unsigned)info >> 16)) {
+#pragma unroll
+          for (int x = 0; x < NG; ++x) {
+            const float4 v = *reinterpret_cast<const float4*>(pp + 64 * x + 4 * l16);
+            dq[x][0] += v.x; dq[x][1] += v.y; dq[x][2] += v.z; dq[x][3] += v.w;
+          }
         }
       }
     }
