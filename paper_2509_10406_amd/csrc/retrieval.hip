@@ -191,18 +191,36 @@ __global__ void __launch_bounds__(256) k_merge_ret(const int32_t* __restrict__ s
   float m = ff_ml[q * 2], l = ff_ml[q * 2 + 1];
   float4 a = *reinterpret_cast<float4*>(ff_acc + q * D + 4 * c);
   if (!(l > 0.f)) { m = MUSE_NEG_INF; l = 0.f; a = make_float4(0.f, 0.f, 0.f, 0.f); }
-  for (int su = 0; su < R2; ++su) {
-    if (selb[q * R2 + su] < 0) continue;
-    const float* pr = part + (q * R2 + su) * (size_t)(D + 4);
-    const float pm = pr[D], pl = pr[D + 1];
-    if (!(pl > 0.f)) continue;
-    const float4 pa = *reinterpret_cast<const float4*>(pr + 4 * c);
+  auto fold = [&](float pm, float pl, const float4 pa) {
     const float mn = fmaxf(m, pm);
     const float ca = __expf(m - mn), cb = __expf(pm - mn);
     l = l * ca + pl * cb;
     a.x = a.x * ca + pa.x * cb; a.y = a.y * ca + pa.y * cb;
     a.z = a.z * ca + pa.z * cb; a.w = a.w * ca + pa.w * cb;
     m = mn;
+  };
+  if (R2 <= 8) {
+    // the usual shape: all the query's partial states are requested together and folded in slot order
+    float2 ml[8];
+    float4 pa[8];
+#pragma unroll
+    for (int su = 0; su < 8; ++su) {
+      const bool ok = su < R2 && selb[q * R2 + (su < R2 ? su : 0)] >= 0;
+      const float* pr = part + (q * R2 + (su < R2 ? su : 0)) * (size_t)(D + 4);
+      ml[su] = ok ? *reinterpret_cast<const float2*>(pr + D) : make_float2(0.f, 0.f);
+      pa[su] = ok ? *reinterpret_cast<const float4*>(pr + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int su = 0; su < 8; ++su)
+      if (ml[su].y > 0.f) fold(ml[su].x, ml[su].y, pa[su]);
+  } else {
+    for (int su = 0; su < R2; ++su) {
+      if (selb[q * R2 + su] < 0) continue;
+      const float* pr = part + (q * R2 + su) * (size_t)(D + 4);
+      const float pm = pr[D], pl = pr[D + 1];
+      if (!(pl > 0.f)) continue;
+      fold(pm, pl, *reinterpret_cast<const float4*>(pr + 4 * c));
+    }
   }
   *reinterpret_cast<float4*>(ff_acc + q * D + 4 * c) = a;
   if (c == 0) { ff_ml[q * 2] = m; ff_ml[q * 2 + 1] = l; }
