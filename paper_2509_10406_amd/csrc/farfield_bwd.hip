@@ -33,21 +33,36 @@ __global__ void __launch_bounds__(256) k_selinfo(const int32_t* __restrict__ sel
   int info[8];
 #pragma unroll
   for (int t = 0; t < 8; ++t) info[t] = -1;
-  for (int t = 0; t < r; ++t) {
-    const int j = selc[q * r + t];
-    int v = -1;
-    if (j >= 0) {
-      uint32_t bm = 0;
-      for (int u = 0; u < k2e; ++u) {
-        const int bb = selb[(q * r + t) * k2e + u];
-        bm |= bb >= 0 ? 1u << bb : 0u;
-      }
-      v = (int)((uint32_t)j | (bm << 16));
-    }
-    si[t] = v;
+  if (r <= 8 && k2e == 1) {
+    // the usual shape: the query's selections are requested together
+    int jj[8], bb[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
-      if (k == t) info[k] = v;
+    for (int t = 0; t < 8; ++t) {
+      jj[t] = t < r ? selc[q * r + t] : -1;
+      bb[t] = t < r ? selb[q * r + t] : -1;
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      info[t] = jj[t] >= 0 ? (int)((uint32_t)jj[t] | ((bb[t] >= 0 ? 1u << bb[t] : 0u) << 16)) : -1;
+      if (t < r) si[t] = info[t];
+    }
+  } else {
+    for (int t = 0; t < r; ++t) {
+      const int j = selc[q * r + t];
+      int v = -1;
+      if (j >= 0) {
+        uint32_t bm = 0;
+        for (int u = 0; u < k2e; ++u) {
+          const int bb = selb[(q * r + t) * k2e + u];
+          bm |= bb >= 0 ? 1u << bb : 0u;
+        }
+        v = (int)((uint32_t)j | (bm << 16));
+      }
+      si[t] = v;
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (k == t) info[k] = v;
+    }
   }
   for (int w = 0; w < W; ++w) {
     uint32_t m = 0;
