@@ -397,6 +397,10 @@ __global__ void __launch_bounds__(256) k_comp2_bwd_dq(
     for (int t = 0; t < 4; ++t) dq[x][t] = 0.f;
   }
   const int32_t* si = slotinfo + ((size_t)hq * N + pos) * r;
+  // the row this kernel adds to is requested now and used at the end
+  float4 oldq[NG];
+#pragma unroll
+  for (int x = 0; x < NG; ++x) oldq[x] = *reinterpret_cast<const float4*>(dQ + qn * D + 64 * x + 4 * l16);
   // the four queries of a wave are neighbours in the block-major order: the largest b among them (wave-uniform)
   // bounds the block loops
   // (the bound is a template constant of the loop body below: one straight-line body per value, loads batched)
@@ -518,7 +522,7 @@ __global__ void __launch_bounds__(256) k_comp2_bwd_dq(
 #pragma unroll
   for (int x = 0; x < NG; ++x) {
     float4* out = reinterpret_cast<float4*>(dQ + qn * D + 64 * x + 4 * l16);
-    float4 o = *out;
+    float4 o = oldq[x];
     o.x += dq[x][0]; o.y += dq[x][1]; o.z += dq[x][2]; o.w += dq[x][3];
     *out = o;
   }
