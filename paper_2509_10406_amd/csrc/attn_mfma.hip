@@ -131,6 +131,22 @@ __device__ __forceinline__ void commit_tile(const TileRegs& r, bf16_t (*rm)[D + 
   if constexpr (NCH > 3) commit_chunk<D, ROWS, ROWM, TRANS>(r.d, 3, rm, tr);
 }
 
+// rows 2r and 2r+1 (chunk cc of each) into the row-major tile, and their 8 columns into the transposed tile as
+// 4-byte stores of two neighbouring queries: half the store instructions of the 2-byte form, and LDS instructions,
+// not bytes, are what the backward kernels run out of.
+template <int D, int ROWS>
+__device__ __forceinline__ void commit_pair(const uint4 a, const uint4 b, int r, int cc, bf16_t (*rm)[D + 8],
+                                            bf16_t (*tr)[ROWS + TPAD]) {
+  *reinterpret_cast<uint4*>(&rm[2 * r][cc * 8]) = a;
+  *reinterpret_cast<uint4*>(&rm[2 * r + 1][cc * 8]) = b;
+  const uint32_t wa[4] = {a.x, a.y, a.z, a.w}, wb[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    *reinterpret_cast<uint32_t*>(&tr[cc * 8 + 2 * i][2 * r]) = __builtin_amdgcn_perm(wb[i], wa[i], 0x05040100u);
+    *reinterpret_cast<uint32_t*>(&tr[cc * 8 + 2 * i + 1][2 * r]) = __builtin_amdgcn_perm(wb[i], wa[i], 0x07060302u);
+  }
+}
+
 template <int D>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2))) k_flash_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                     const bf16_t* __restrict__ V, const float* __restrict__ ff,
@@ -651,6 +667,179 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       // every key row belongs to exactly one tile (the query heads of the group are summed in registers)
+      size_t o = (kh + mk) * D + 32 * t + 8 * g + 4 * half;
+      *reinterpret_cast<float4*>(dK + o) =
+          make_float4(scale * dk[t][4 * g + 0], scale * dk[t][4 * g + 1], scale * dk[t][4 * g + 2], scale * dk[t][4 * g + 3]);
+      *reinterpret_cast<float4*>(dV + o) = make_float4(dv[t][4 * g + 0], dv[t][4 * g + 1], dv[t][4 * g + 2], dv[t][4 * g + 3]);
+    }
+}
+
+// dK/dV of the block diagonal for D = 64, arranged in phases so that a wave never waits for LDS right before a
+// matrix instruction, and with the fewest vector instructions per score.  For a tile of 32 queries:
+//   A  8 MFMAs   S = Q K^T and dP = dO V^T.  Their accumulators start at -LSE / scale and -delta (read from LDS
+//                straight into the accumulator registers), so the probability is exp2(c S) and dS = P dP with no
+//                further subtraction;
+//   B  vector    P, dS, conversion to bf16 operands; the causal mask only on the tiles the diagonal crosses;
+//   C  8 MFMAs   dV += P^T dO, dK += dS^T Q.
+// The transposed operands of C are requested before A, the row operands and accumulator seeds of the next tile
+// after B, so each is in flight across a whole phase.  A wave's own vector and matrix instructions do not overlap
+// on this machine (the issue of a wave stalls behind its MFMA), so the overlap comes from the second wave of the
+// SIMD being in another phase; what this arrangement removes are the stalls that kept both waves idle.
+template <int D>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) k_flash_bwd_dkv_p(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ delta,
+    float* __restrict__ dK, float* __restrict__ dV, int N, int Bs, int Hq, int Hkv, int nbatch, float scale,
+    float scale_log2e) {
+  constexpr int KS = D / 16, DT = D / 32;
+  constexpr int BQ = 64, NQT = BQ / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t qs[BQ][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gs[BQ][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][BQ + TPAD];
+  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][BQ + TPAD];
+  __shared__ __attribute__((aligned(16))) float lse_s[BQ];  // -LSE / scale
+  __shared__ __attribute__((aligned(16))) float dl_s[BQ];   // -delta
+  const FlashTile ft = flash_tile(N, Bs, Hkv, nbatch);
+  if (!ft.ok) return;
+  const int hk = ft.h, b = ft.b, G_ = Hq / Hkv;
+  const size_t kh = ((size_t)b * Hkv + hk) * N;
+  const int k0 = (ft.blk * ft.tpg + ft.t) * 128;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, col = lane % 32, half = lane / 32;
+  const int mk = k0 + 32 * wave + col;
+  const int mkc = mk < N ? mk : N - 1;
+  const int myend = min((mkc / Bs + 1) * Bs, N);
+  const int qend = min((min(k0 + 127, N - 1) / Bs + 1) * Bs, N);
+  // a tile of 128 keys inside one block with every row in range: only the diagonal needs a mask
+  const bool aligned = (Bs % 128) == 0 && k0 + 128 <= N;
+  const float seed = -1.4426950408889634f / scale_log2e;
+  static_assert(BQ / 2 * (D / 8) == 256, "one pair of rows and one 16-byte chunk per thread");
+  const int pr_ = threadIdx.x % (BQ / 2), pc_ = threadIdx.x / (BQ / 2);  // row pair and chunk this thread stages
+
+  bf16x8_t kf[KS], vf[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    kf[s] = *reinterpret_cast<const bf16x8_t*>(K + (kh + mkc) * D + 16 * s + 8 * half);
+    vf[s] = *reinterpret_cast<const bf16x8_t*>(V + (kh + mkc) * D + 16 * s + 8 * half);
+  }
+  f32x16_t dk[DT], dv[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { dk[t][e] = 0.f; dv[t][e] = 0.f; }
+
+  for (int g = 0; g < G_; ++g) {
+    const size_t qh = ((size_t)b * Hq + (size_t)hk * G_ + g) * N;
+    uint4 qa, qb, ga, gb;  // rows 2r and 2r+1 of the next tile, chunk cc, of Q and dO
+    float lreg = 0.f, dreg = 0.f;
+    auto fetch = [&](int q0) {
+      int r0 = q0 + 2 * pr_, r1 = r0 + 1;
+      r0 = r0 < N ? r0 : N - 1;
+      r1 = r1 < N ? r1 : N - 1;
+      qa = *reinterpret_cast<const uint4*>(Q + (qh + r0) * D + 8 * pc_);
+      qb = *reinterpret_cast<const uint4*>(Q + (qh + r1) * D + 8 * pc_);
+      ga = *reinterpret_cast<const uint4*>(dO + (qh + r0) * D + 8 * pc_);
+      gb = *reinterpret_cast<const uint4*>(dO + (qh + r1) * D + 8 * pc_);
+      if (threadIdx.x < BQ) {
+        int n = q0 + threadIdx.x;
+        n = n < N ? n : N - 1;
+        lreg = LSE[qh + n];
+        dreg = delta[qh + n];
+      }
+    };
+    if (k0 < qend) fetch(k0);
+    for (int q0 = k0; q0 < qend; q0 += BQ) {
+      __syncthreads();
+      commit_pair<D, BQ>(qa, qb, pr_, pc_, qs, qt_);
+      commit_pair<D, BQ>(ga, gb, pr_, pc_, gs, gt_);
+      if (threadIdx.x < BQ) {
+        lse_s[threadIdx.x] = lreg * seed;
+        dl_s[threadIdx.x] = -dreg;
+      }
+      __syncthreads();
+      if (q0 + BQ < qend) fetch(q0 + BQ);  // in flight while this tile is consumed
+      if (q0 + BQ - 1 < k0 + 32 * wave) continue;  // every query of the tile precedes this wave's keys
+      f32x16_t s, dp;
+      bf16x8_t aq[KS], ag[KS];
+      auto seed_acc = [&](int qt) {
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const float4 l4 = *reinterpret_cast<const float4*>(&lse_s[32 * qt + 8 * gq + 4 * half]);
+          const float4 d4 = *reinterpret_cast<const float4*>(&dl_s[32 * qt + 8 * gq + 4 * half]);
+          s[4 * gq + 0] = l4.x; s[4 * gq + 1] = l4.y; s[4 * gq + 2] = l4.z; s[4 * gq + 3] = l4.w;
+          dp[4 * gq + 0] = d4.x; dp[4 * gq + 1] = d4.y; dp[4 * gq + 2] = d4.z; dp[4 * gq + 3] = d4.w;
+        }
+      };
+      auto load_rows = [&](int qt, int part) {  // half of the row operands of a tile
+#pragma unroll
+        for (int x = part * (KS / 2); x < (part + 1) * (KS / 2); ++x) {
+          aq[x] = *reinterpret_cast<const bf16x8_t*>(&qs[32 * qt + col][16 * x + 8 * half]);
+          ag[x] = *reinterpret_cast<const bf16x8_t*>(&gs[32 * qt + col][16 * x + 8 * half]);
+        }
+      };
+      seed_acc(0);
+      load_rows(0, 0);
+      load_rows(0, 1);
+#pragma unroll
+      for (int qt = 0; qt < NQT; ++qt) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int x = 0; x < KS; ++x) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[x], kf[x], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag[x], vf[x], dp, 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8_t tq[2][DT], tg[2][DT];
+#pragma unroll
+        for (int G = 0; G < 2; ++G)
+#pragma unroll
+          for (int t = 0; t < DT; ++t) {
+            tg[G][t] = ld_tr8(&gt_[32 * t + col][0], 32 * qt + 16 * G, half);
+            tq[G][t] = ld_tr8(&qt_[32 * t + col][0], 32 * qt + 16 * G, half);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+        if (aligned && q0 + 32 * qt >= k0 + 32 * wave + 32) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const float p = fast_exp2(s[e] * scale_log2e);
+            s[e] = p;
+            dp[e] = p * dp[e];
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int n = q0 + 32 * qt + 8 * (e / 4) + 4 * half + e % 4;
+            float p = fast_exp2(s[e] * scale_log2e);
+            p = (n < mk || n >= myend) ? 0.f : p;
+            s[e] = p;
+            dp[e] = p * dp[e];
+          }
+        }
+        bf16x8_t pf[2], df[2];
+#pragma unroll
+        for (int G = 0; G < 2; ++G) {
+          pf[G] = pack8(s, 2 * G, 2 * G + 1);
+          df[G] = pack8(dp, 2 * G, 2 * G + 1);
+        }
+        if (qt + 1 < NQT) seed_acc(qt + 1);
+#pragma unroll
+        for (int G = 0; G < 2; ++G) {
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int t = 0; t < DT; ++t) {
+            dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tg[G][t], pf[G], dv[t], 0, 0, 0);
+            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[G][t], df[G], dk[t], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          if (qt + 1 < NQT) load_rows(qt + 1, G);  // the operands just consumed leave room for these
+        }
+      }
+    }
+  }
+  if (mk >= N) return;
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
       size_t o = (kh + mk) * D + 32 * t + 8 * g + 4 * half;
       *reinterpret_cast<float4*>(dK + o) =
           make_float4(scale * dk[t][4 * g + 0], scale * dk[t][4 * g + 1], scale * dk[t][4 * g + 2], scale * dk[t][4 * g + 3]);
@@ -1603,7 +1792,7 @@ int muse_launch_attn_bwd_mfma(const MuseDims& d, int Bs, const void* Q, const vo
   const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V, *g = (const bf16_t*)dO;
   if (d.D == 64) {
     { MuseProf prof_("k_flash_bwd_dq", st); hipLaunchKernelGGL(k_flash_bwd_dq<64>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.B, d.scale, sl); }
-    { MuseProf prof_("k_flash_bwd_dkv", st); hipLaunchKernelGGL(k_flash_bwd_dkv<64>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.B, d.scale, sl); }
+    { MuseProf prof_("k_flash_bwd_dkv", st); hipLaunchKernelGGL(k_flash_bwd_dkv_p<64>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.B, d.scale, sl); }
   } else {
     { MuseProf prof_("k_flash_bwd_dq", st); hipLaunchKernelGGL(k_flash_bwd_dq<128>, gq, dim3(256), 0, st, q, k, v, g, LSE, delta, dQacc, d.N, Bs, d.Hq, d.Hkv, d.B, d.scale, sl); }
     { MuseProf prof_("k_flash_bwd_dkv", st); hipLaunchKernelGGL(k_flash_bwd_dkv<128>, gk, dim3(256), 0, st, q, k, v, g, LSE, delta, dKacc, dVacc, d.N, Bs, d.Hq, d.Hkv, d.B, d.scale, sl); }

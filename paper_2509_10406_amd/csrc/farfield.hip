@@ -1062,7 +1062,7 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
   w->ff_acc = (float*)take(HQ * N * (D + 2) * 4);
   w->ff_ml = w->ff_acc + HQ * N * D;
   {
-    size_t W = (d.Ck + 31) / 32, NBm = d.nb > 1 ? d.nb - 1 : 1, R2 = (size_t)(d.r > 0 ? d.r : 1) * d.k2e;
+    size_t R2 = (size_t)(d.r > 0 ? d.r : 1) * d.k2e;
     w->pairmask = (uint32_t*)take(ff_pairmask_bytes(d));
     w->pair_off = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);
     w->pair_cnt = (int32_t*)take(HK * ((size_t)d.nb * d.Ck + 1) * 4);

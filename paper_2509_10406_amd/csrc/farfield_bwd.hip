@@ -509,7 +509,7 @@ __global__ void __launch_bounds__(256) k_comp2_bwd_dq(
       if (info < 0 || ((unsigned)info >> 16) == 0u) continue;
       for (int u = 0; u < k2e; ++u) {
         const float* pp = dqpart + (qn * r * k2e + t * k2e + u) * D;
-        if (u < __popc((unsigned)info >> 16)) {
+        if (u < (int)__popc((unsigned)info >> 16)) {
 #pragma unroll
           for (int x = 0; x < NG; ++x) {
             const float4 v = *reinterpret_cast<const float4*>(pp + 64 * x + 4 * l16);

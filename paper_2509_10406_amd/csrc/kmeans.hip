@@ -71,7 +71,7 @@ __global__ void __launch_bounds__(256) k_assign_f32(const float* __restrict__ X,
       int jj = t / D, d = t % D;
       cs[jj][d] = (j0 + jj < C) ? chat[((size_t)h * C + j0 + jj) * D + d] : 0.f;
     }
-    if (threadIdx.x < CT) c2s[threadIdx.x] = (j0 + threadIdx.x < C) ? nhc2[(size_t)h * C + j0 + threadIdx.x] : MUSE_NEG_INF;
+    if ((int)threadIdx.x < CT) c2s[threadIdx.x] = (j0 + (int)threadIdx.x < C) ? nhc2[(size_t)h * C + j0 + threadIdx.x] : MUSE_NEG_INF;
     __syncthreads();
     if (n < N) {
       for (int jj = 0; jj < CT && j0 + jj < C; ++jj) {
