@@ -131,20 +131,32 @@ __device__ __forceinline__ void commit_tile(const TileRegs& r, bf16_t (*rm)[D + 
   if constexpr (NCH > 3) commit_chunk<D, ROWS, ROWM, TRANS>(r.d, 3, rm, tr);
 }
 
+// Transposed tile in operand order.  The second contraction of the backward kernels takes, for lane half h and the
+// 16 rows r0 .. r0+15 of the staged tile, the rows r0 + {4h .. 4h+3} and r0 + {8+4h .. 8+4h+3} as its 8 k-slots.
+// Stored in that order (inside every group of 16 rows the bits 2 and 3 of the row index change places) an operand
+// is one 16-byte read instead of two 8-byte ones; an LDS instruction costs about the same whatever its width, and
+// LDS instructions, not bytes, are what these kernels run out of.  Rows are padded to a multiple of 16 bytes.
+constexpr int TPAD16 = 8;
+__device__ __forceinline__ int tr_pos(int row) { return (row & ~12) | ((row & 4) << 1) | ((row & 8) >> 1); }
 // rows 2r and 2r+1 (chunk cc of each) into the row-major tile, and their 8 columns into the transposed tile as
-// 4-byte stores of two neighbouring queries: half the store instructions of the 2-byte form, and LDS instructions,
-// not bytes, are what the backward kernels run out of.
+// 4-byte stores of two neighbouring rows (they stay neighbours in operand order)
 template <int D, int ROWS>
 __device__ __forceinline__ void commit_pair(const uint4 a, const uint4 b, int r, int cc, bf16_t (*rm)[D + 8],
-                                            bf16_t (*tr)[ROWS + TPAD]) {
+                                            bf16_t (*tr)[ROWS + TPAD16]) {
   *reinterpret_cast<uint4*>(&rm[2 * r][cc * 8]) = a;
   *reinterpret_cast<uint4*>(&rm[2 * r + 1][cc * 8]) = b;
   const uint32_t wa[4] = {a.x, a.y, a.z, a.w}, wb[4] = {b.x, b.y, b.z, b.w};
+  const int pos = tr_pos(2 * r);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    *reinterpret_cast<uint32_t*>(&tr[cc * 8 + 2 * i][2 * r]) = __builtin_amdgcn_perm(wb[i], wa[i], 0x05040100u);
-    *reinterpret_cast<uint32_t*>(&tr[cc * 8 + 2 * i + 1][2 * r]) = __builtin_amdgcn_perm(wb[i], wa[i], 0x07060302u);
+    *reinterpret_cast<uint32_t*>(&tr[cc * 8 + 2 * i][pos]) = __builtin_amdgcn_perm(wb[i], wa[i], 0x05040100u);
+    *reinterpret_cast<uint32_t*>(&tr[cc * 8 + 2 * i + 1][pos]) = __builtin_amdgcn_perm(wb[i], wa[i], 0x07060302u);
   }
+}
+// the operand of lane half `half` over the 16 rows starting at r0 (a multiple of 16)
+template <int W>
+__device__ __forceinline__ bf16x8_t ld_tr16(const bf16_t (*tr)[W], int d, int r0, int half) {
+  return *reinterpret_cast<const bf16x8_t*>(&tr[d][r0 + 8 * half]);
 }
 
 template <int D>
@@ -681,10 +693,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 //                further subtraction;
 //   B  vector    P, dS, conversion to bf16 operands; the causal mask only on the tiles the diagonal crosses;
 //   C  8 MFMAs   dV += P^T dO, dK += dS^T Q.
-// The transposed operands of C are requested before A, the row operands and accumulator seeds of the next tile
-// after B, so each is in flight across a whole phase.  A wave's own vector and matrix instructions do not overlap
-// on this machine (the issue of a wave stalls behind its MFMA), so the overlap comes from the second wave of the
-// SIMD being in another phase; what this arrangement removes are the stalls that kept both waves idle.
+// The transposed operands of C are requested before B, the accumulator seeds and row operands of the next tile
+// during C, so each request is in flight across a whole phase.  Two staged tiles of 64 queries: while one is
+// consumed the next is written into the other (in the middle of the tile, when its global loads have landed) and
+// the one after that is requested from memory, so a tile costs one barrier.  With two waves per SIMD the vector
+// phase of one wave runs beside the matrix phases of the other.
 template <int D>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) k_flash_bwd_dkv_p(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
@@ -693,12 +706,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32;
   constexpr int BQ = 64, NQT = BQ / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t qs[BQ][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t gs[BQ][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][BQ + TPAD];
-  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][BQ + TPAD];
-  __shared__ __attribute__((aligned(16))) float lse_s[BQ];  // -LSE / scale
-  __shared__ __attribute__((aligned(16))) float dl_s[BQ];   // -delta
+  __shared__ __attribute__((aligned(16))) bf16_t qs[2][BQ][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t gs[2][BQ][D + 8];
+  __shared__ __attribute__((aligned(16))) bf16_t qt_[2][D][BQ + TPAD16];
+  __shared__ __attribute__((aligned(16))) bf16_t gt_[2][D][BQ + TPAD16];
+  __shared__ __attribute__((aligned(16))) float lse_s[2][BQ];  // -LSE / scale
+  __shared__ __attribute__((aligned(16))) float dl_s[2][BQ];   // -delta
   const FlashTile ft = flash_tile(N, Bs, Hkv, nbatch);
   if (!ft.ok) return;
   const int hk = ft.h, b = ft.b, G_ = Hq / Hkv;
@@ -727,9 +740,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
     for (int e = 0; e < 16; ++e) { dk[t][e] = 0.f; dv[t][e] = 0.f; }
 
+  int cur = 0;  // the staged tile being consumed; the other one is written meanwhile: one barrier per tile
   for (int g = 0; g < G_; ++g) {
     const size_t qh = ((size_t)b * Hq + (size_t)hk * G_ + g) * N;
-    uint4 qa, qb, ga, gb;  // rows 2r and 2r+1 of the next tile, chunk cc, of Q and dO
+    uint4 qa, qb, ga, gb;  // rows 2r and 2r+1 of a coming tile, chunk cc, of Q and dO
     float lreg = 0.f, dreg = 0.f;
     auto fetch = [&](int q0) {
       int r0 = q0 + 2 * pr_, r1 = r0 + 1;
@@ -746,25 +760,35 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         dreg = delta[qh + n];
       }
     };
-    if (k0 < qend) fetch(k0);
-    for (int q0 = k0; q0 < qend; q0 += BQ) {
-      __syncthreads();
-      commit_pair<D, BQ>(qa, qb, pr_, pc_, qs, qt_);
-      commit_pair<D, BQ>(ga, gb, pr_, pc_, gs, gt_);
+    auto commit = [&](int buf) {
+      commit_pair<D, BQ>(qa, qb, pr_, pc_, qs[buf], qt_[buf]);
+      commit_pair<D, BQ>(ga, gb, pr_, pc_, gs[buf], gt_[buf]);
       if (threadIdx.x < BQ) {
-        lse_s[threadIdx.x] = lreg * seed;
-        dl_s[threadIdx.x] = -dreg;
+        lse_s[buf][threadIdx.x] = lreg * seed;
+        dl_s[buf][threadIdx.x] = -dreg;
       }
+    };
+    if (k0 < qend) {
+      fetch(k0);
+      commit(cur);  // every wave is past the barrier that ended the last tile of the previous head
       __syncthreads();
-      if (q0 + BQ < qend) fetch(q0 + BQ);  // in flight while this tile is consumed
-      if (q0 + BQ - 1 < k0 + 32 * wave) continue;  // every query of the tile precedes this wave's keys
+      if (k0 + BQ < qend) fetch(k0 + BQ);
+    }
+    for (int q0 = k0; q0 < qend; q0 += BQ) {
+      const bool skip = q0 + BQ - 1 < k0 + 32 * wave;  // every query of the tile precedes this wave's keys
+      bf16_t (*qsc)[D + 8] = qs[cur];
+      bf16_t (*gsc)[D + 8] = gs[cur];
+      bf16_t (*qtc)[BQ + TPAD16] = qt_[cur];
+      bf16_t (*gtc)[BQ + TPAD16] = gt_[cur];
+      const float* lsc = lse_s[cur];
+      const float* dlc = dl_s[cur];
       f32x16_t s, dp;
       bf16x8_t aq[KS], ag[KS];
       auto seed_acc = [&](int qt) {
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-          const float4 l4 = *reinterpret_cast<const float4*>(&lse_s[32 * qt + 8 * gq + 4 * half]);
-          const float4 d4 = *reinterpret_cast<const float4*>(&dl_s[32 * qt + 8 * gq + 4 * half]);
+          const float4 l4 = *reinterpret_cast<const float4*>(&lsc[32 * qt + 8 * gq + 4 * half]);
+          const float4 d4 = *reinterpret_cast<const float4*>(&dlc[32 * qt + 8 * gq + 4 * half]);
           s[4 * gq + 0] = l4.x; s[4 * gq + 1] = l4.y; s[4 * gq + 2] = l4.z; s[4 * gq + 3] = l4.w;
           dp[4 * gq + 0] = d4.x; dp[4 * gq + 1] = d4.y; dp[4 * gq + 2] = d4.z; dp[4 * gq + 3] = d4.w;
         }
@@ -772,15 +796,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
       auto load_rows = [&](int qt, int part) {  // half of the row operands of a tile
 #pragma unroll
         for (int x = part * (KS / 2); x < (part + 1) * (KS / 2); ++x) {
-          aq[x] = *reinterpret_cast<const bf16x8_t*>(&qs[32 * qt + col][16 * x + 8 * half]);
-          ag[x] = *reinterpret_cast<const bf16x8_t*>(&gs[32 * qt + col][16 * x + 8 * half]);
+          aq[x] = *reinterpret_cast<const bf16x8_t*>(&qsc[32 * qt + col][16 * x + 8 * half]);
+          ag[x] = *reinterpret_cast<const bf16x8_t*>(&gsc[32 * qt + col][16 * x + 8 * half]);
         }
       };
-      seed_acc(0);
-      load_rows(0, 0);
-      load_rows(0, 1);
-#pragma unroll
-      for (int qt = 0; qt < NQT; ++qt) {
+      auto tile = [&](int qt) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int x = 0; x < KS; ++x) {
@@ -793,8 +813,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         for (int G = 0; G < 2; ++G)
 #pragma unroll
           for (int t = 0; t < DT; ++t) {
-            tg[G][t] = ld_tr8(&gt_[32 * t + col][0], 32 * qt + 16 * G, half);
-            tq[G][t] = ld_tr8(&qt_[32 * t + col][0], 32 * qt + 16 * G, half);
+            tg[G][t] = ld_tr16(gtc, 32 * t + col, 32 * qt + 16 * G, half);
+            tq[G][t] = ld_tr16(qtc, 32 * t + col, 32 * qt + 16 * G, half);
           }
         __builtin_amdgcn_sched_barrier(0);
         if (aligned && q0 + 32 * qt >= k0 + 32 * wave + 32) {
@@ -832,7 +852,20 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
           __builtin_amdgcn_sched_barrier(0);
           if (qt + 1 < NQT) load_rows(qt + 1, G);  // the operands just consumed leave room for these
         }
+      };
+      if (!skip) {
+        seed_acc(0);
+        load_rows(0, 0);
+        load_rows(0, 1);
+        tile(0);
       }
+      if (q0 + BQ < qend) {  // the next tile into the other buffer, the one after it into the registers
+        commit(cur ^ 1);
+        if (q0 + 2 * BQ < qend) fetch(q0 + 2 * BQ);
+      }
+      if (!skip) tile(1);
+      __syncthreads();
+      cur ^= 1;
     }
   }
   if (mk >= N) return;
