@@ -159,6 +159,44 @@ __device__ __forceinline__ bf16x8_t ld_tr16(const bf16_t (*tr)[W], int d, int r0
   return *reinterpret_cast<const bf16x8_t*>(&tr[d][r0 + 8 * half]);
 }
 
+// a whole tile in row pairs: pair c % (ROWS / 2), chunk c / (ROWS / 2) for c = thread + 256 i.  Values, not
+// references into the register struct, go through the helpers (see TileRegs).
+template <int D, int ROWS>
+__device__ __forceinline__ uint4 fetch_pair_row(const bf16_t* __restrict__ src, int r0, int N, int i, int which) {
+  const int c = threadIdx.x + 256 * i, pr = c % (ROWS / 2), pc = c / (ROWS / 2);
+  int row = r0 + 2 * pr + which;
+  row = row < N ? row : N - 1;
+  return *reinterpret_cast<const uint4*>(src + (size_t)row * D + 8 * pc);
+}
+template <int D, int ROWS>
+__device__ __forceinline__ void fetch_pairs(const bf16_t* __restrict__ src, int r0, int N, TileRegs& r) {
+  constexpr int NP = ROWS / 2 * (D / 8) / 256;
+  static_assert(NP == 1 || NP == 2, "one or two row pairs per thread");
+  r.a = fetch_pair_row<D, ROWS>(src, r0, N, 0, 0);
+  r.b = fetch_pair_row<D, ROWS>(src, r0, N, 0, 1);
+  if constexpr (NP > 1) {
+    r.c = fetch_pair_row<D, ROWS>(src, r0, N, 1, 0);
+    r.d = fetch_pair_row<D, ROWS>(src, r0, N, 1, 1);
+  }
+}
+template <int D, int ROWS, bool TRANS>
+__device__ __forceinline__ void commit_pair_i(const uint4 lo, const uint4 hi, int i, bf16_t (*rm)[D + 8],
+                                              bf16_t (*tr)[ROWS + TPAD16]) {
+  const int c = threadIdx.x + 256 * i, pr = c % (ROWS / 2), pc = c / (ROWS / 2);
+  if constexpr (TRANS) {
+    commit_pair<D, ROWS>(lo, hi, pr, pc, rm, tr);
+  } else {
+    *reinterpret_cast<uint4*>(&rm[2 * pr][pc * 8]) = lo;
+    *reinterpret_cast<uint4*>(&rm[2 * pr + 1][pc * 8]) = hi;
+  }
+}
+template <int D, int ROWS, bool TRANS>
+__device__ __forceinline__ void commit_pairs(const TileRegs& r, bf16_t (*rm)[D + 8], bf16_t (*tr)[ROWS + TPAD16]) {
+  constexpr int NP = ROWS / 2 * (D / 8) / 256;
+  commit_pair_i<D, ROWS, TRANS>(r.a, r.b, 0, rm, tr);
+  if constexpr (NP > 1) commit_pair_i<D, ROWS, TRANS>(r.c, r.d, 1, rm, tr);
+}
+
 template <int D>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2, D == 64 ? 3 : 2))) k_flash_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                     const bf16_t* __restrict__ V, const float* __restrict__ ff,
@@ -479,7 +517,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   constexpr int KS = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(16))) bf16_t ks[BN][D + 8];
   __shared__ __attribute__((aligned(16))) bf16_t vs[BN][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t kt_[D][BN + TPAD];
+  __shared__ __attribute__((aligned(16))) bf16_t kt_[D][BN + TPAD16];
   const FlashTile ft = flash_tile(N, Bs, Hq, nbatch);
   if (!ft.ok) return;
   const int hq = ft.h, b = ft.b, hk = hq / (Hq / Hkv);
@@ -506,16 +544,16 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 
   const int kbeg = (q0 / Bs) * Bs, kend = min(q0 + 128, N);
   TileRegs kreg, vreg;
-  fetch_tile<D, BN>(K + kh * D, kbeg, N, kreg);
-  fetch_tile<D, BN>(V + kh * D, kbeg, N, vreg);
+  fetch_pairs<D, BN>(K + kh * D, kbeg, N, kreg);
+  fetch_pairs<D, BN>(V + kh * D, kbeg, N, vreg);
   for (int k0 = kbeg; k0 < kend; k0 += BN) {
     __syncthreads();
-    commit_tile<D, BN, true, true>(kreg, ks, kt_);
-    commit_tile<D, BN, true, false>(vreg, vs, nullptr);
+    commit_pairs<D, BN, true>(kreg, ks, kt_);
+    commit_pairs<D, BN, false>(vreg, vs, nullptr);
     __syncthreads();
     if (k0 + BN < kend) {  // in flight while this tile is consumed
-      fetch_tile<D, BN>(K + kh * D, k0 + BN, N, kreg);
-      fetch_tile<D, BN>(V + kh * D, k0 + BN, N, vreg);
+      fetch_pairs<D, BN>(K + kh * D, k0 + BN, N, kreg);
+      fetch_pairs<D, BN>(V + kh * D, k0 + BN, N, vreg);
     }
     if (k0 > q0 + 32 * wave + 31) continue;
     const bool edge = unaligned || k0 + BN - 1 > q0 + 32 * wave || k0 + BN > N;
@@ -548,7 +586,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
         bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
 #pragma unroll
         for (int t = 0; t < DT; ++t) {
-          bf16x8_t a = ld_tr8(&kt_[32 * t + col][0], 32 * kt + 16 * G, half);
+          bf16x8_t a = ld_tr16(kt_, 32 * t + col, 32 * kt + 16 * G, half);
           dq[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, df, dq[t], 0, 0, 0);
         }
       }
