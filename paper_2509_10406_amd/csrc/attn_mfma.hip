@@ -66,29 +66,7 @@ static dim3 flash_grid(int N, int Bs, int H, int nbatch, int TR = 128) {
   return dim3(8 * tpg, (nbatch * H * nblk + 7) / 8, 1);
 }
 
-// cooperative load of `rows` x D bf16 into a row-major tile (pad 8) and optionally a transposed one.
-// Consecutive lanes take consecutive rows (one 16-byte chunk each): the 2-byte stores into the transposed tile
-// then fall into consecutive LDS banks, and the row-major 16-byte stores are 36 dwords apart, which is
-// conflict-free for the 16 lanes served together.
-template <int D, int ROWS, bool ROWM, bool TRANS>
-__device__ __forceinline__ void load_tile(const bf16_t* __restrict__ src, int r0, int N,
-                                          bf16_t (*rm)[D + 8], bf16_t (*tr)[ROWS + TPAD]) {
-  constexpr int CPR = D / 8;
-  for (int c = threadIdx.x; c < ROWS * CPR; c += 256) {
-    int row = c % ROWS, cc = c / ROWS;
-    int gr = r0 + row;
-    gr = gr < N ? gr : N - 1;
-    uint4 v = *reinterpret_cast<const uint4*>(src + (size_t)gr * D + cc * 8);
-    if (ROWM) *reinterpret_cast<uint4*>(&rm[row][cc * 8]) = v;
-    if (TRANS) {
-      const bf16_t* pv = reinterpret_cast<const bf16_t*>(&v);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) tr[cc * 8 + e][row] = pv[e];
-    }
-  }
-}
-
-// the same in two halves, so that the global loads of the next tile are in flight while the current one is
+// Staging of a tile through registers, so that the global loads of the next tile are in flight while the current one is
 // consumed: fetch_tile into registers, commit_tile from registers into LDS.  The registers are named members,
 // not an array: an array that is passed around and read through pointer casts ends up in memory (the compiler
 // parks it in LDS), and the wait for its loads then comes right after they are issued.
@@ -140,11 +118,13 @@ constexpr int TPAD16 = 8;
 __device__ __forceinline__ int tr_pos(int row) { return (row & ~12) | ((row & 4) << 1) | ((row & 8) >> 1); }
 // rows 2r and 2r+1 (chunk cc of each) into the row-major tile, and their 8 columns into the transposed tile as
 // 4-byte stores of two neighbouring rows (they stay neighbours in operand order)
-template <int D, int ROWS>
+template <int D, int ROWS, bool ROWM = true>
 __device__ __forceinline__ void commit_pair(const uint4 a, const uint4 b, int r, int cc, bf16_t (*rm)[D + 8],
                                             bf16_t (*tr)[ROWS + TPAD16]) {
-  *reinterpret_cast<uint4*>(&rm[2 * r][cc * 8]) = a;
-  *reinterpret_cast<uint4*>(&rm[2 * r + 1][cc * 8]) = b;
+  if constexpr (ROWM) {
+    *reinterpret_cast<uint4*>(&rm[2 * r][cc * 8]) = a;
+    *reinterpret_cast<uint4*>(&rm[2 * r + 1][cc * 8]) = b;
+  }
   const uint32_t wa[4] = {a.x, a.y, a.z, a.w}, wb[4] = {b.x, b.y, b.z, b.w};
   const int pos = tr_pos(2 * r);
 #pragma unroll
@@ -179,22 +159,22 @@ __device__ __forceinline__ void fetch_pairs(const bf16_t* __restrict__ src, int 
     r.d = fetch_pair_row<D, ROWS>(src, r0, N, 1, 1);
   }
 }
-template <int D, int ROWS, bool TRANS>
+template <int D, int ROWS, bool TRANS, bool ROWM>
 __device__ __forceinline__ void commit_pair_i(const uint4 lo, const uint4 hi, int i, bf16_t (*rm)[D + 8],
                                               bf16_t (*tr)[ROWS + TPAD16]) {
   const int c = threadIdx.x + 256 * i, pr = c % (ROWS / 2), pc = c / (ROWS / 2);
   if constexpr (TRANS) {
-    commit_pair<D, ROWS>(lo, hi, pr, pc, rm, tr);
+    commit_pair<D, ROWS, ROWM>(lo, hi, pr, pc, rm, tr);
   } else {
     *reinterpret_cast<uint4*>(&rm[2 * pr][pc * 8]) = lo;
     *reinterpret_cast<uint4*>(&rm[2 * pr + 1][pc * 8]) = hi;
   }
 }
-template <int D, int ROWS, bool TRANS>
+template <int D, int ROWS, bool TRANS, bool ROWM = true>
 __device__ __forceinline__ void commit_pairs(const TileRegs& r, bf16_t (*rm)[D + 8], bf16_t (*tr)[ROWS + TPAD16]) {
   constexpr int NP = ROWS / 2 * (D / 8) / 256;
-  commit_pair_i<D, ROWS, TRANS>(r.a, r.b, 0, rm, tr);
-  if constexpr (NP > 1) commit_pair_i<D, ROWS, TRANS>(r.c, r.d, 1, rm, tr);
+  commit_pair_i<D, ROWS, TRANS, ROWM>(r.a, r.b, 0, rm, tr);
+  if constexpr (NP > 1) commit_pair_i<D, ROWS, TRANS, ROWM>(r.c, r.d, 1, rm, tr);
 }
 
 template <int D>
@@ -204,7 +184,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
                                                     int Hq, int Hkv, int nbatch, float scale_log2e) {
   constexpr int KS = D / 16, DT = D / 32;
   __shared__ __attribute__((aligned(16))) bf16_t ks[BN][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t vt[D][BN + TPAD];
+  __shared__ __attribute__((aligned(16))) bf16_t vt[D][BN + TPAD16];
   const FlashTile ft = flash_tile(N, Bs, Hq, nbatch);
   if (!ft.ok) return;
   const int hq = ft.h, b = ft.b, hk = hq / (Hq / Hkv);
@@ -230,15 +210,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   const int kbeg = (q0 / Bs) * Bs, kend = min(q0 + 128, N);
   TileRegs kreg, vreg;
   fetch_tile<D, BN>(K + kh * D, kbeg, N, kreg);
-  fetch_tile<D, BN>(V + kh * D, kbeg, N, vreg);
+  fetch_pairs<D, BN>(V + kh * D, kbeg, N, vreg);
   for (int k0 = kbeg; k0 < kend; k0 += BN) {
     __syncthreads();
     commit_tile<D, BN, true, false>(kreg, ks, nullptr);
-    commit_tile<D, BN, false, true>(vreg, nullptr, vt);
+    commit_pairs<D, BN, true, false>(vreg, nullptr, vt);
     __syncthreads();
     if (k0 + BN < kend) {  // in flight while this tile is consumed
       fetch_tile<D, BN>(K + kh * D, k0 + BN, N, kreg);
-      fetch_tile<D, BN>(V + kh * D, k0 + BN, N, vreg);
+      fetch_pairs<D, BN>(V + kh * D, k0 + BN, N, vreg);
     }
     if (k0 > q0 + 32 * wave + 31) continue;  // every key of the tile is in this wave's future
     f32x16_t s[2];
@@ -297,7 +277,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
         psum = sum8(pf, psum);  // the normaliser sums the probabilities as the matrix cores see them
 #pragma unroll
         for (int t = 0; t < DT; ++t) {
-          bf16x8_t a = ld_tr8(&vt[32 * t + col][0], 32 * kt + 16 * G, half);
+          bf16x8_t a = ld_tr16(vt, 32 * t + col, 32 * kt + 16 * G, half);
           o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, o[t], 0, 0, 0);
         }
       }
@@ -351,7 +331,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     bf16_t* __restrict__ O, float* __restrict__ LSE, int N, int Bs, int Hq, int Hkv, int nbatch, float scale_log2e) {
   constexpr int D = 64, KS = D / 16, DT = D / 32, TR = 256;
   __shared__ __attribute__((aligned(16))) bf16_t ks[BN][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t vt[D][BN + TPAD];
+  __shared__ __attribute__((aligned(16))) bf16_t vt[D][BN + TPAD16];
   const FlashTile ft = flash_tile<TR>(N, Bs, Hq, nbatch);
   if (!ft.ok) return;
   const int hq = ft.h, b = ft.b, hk = hq / (Hq / Hkv);
@@ -384,15 +364,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
   const int kbeg = (q0 / Bs) * Bs, kend = min(q0 + TR, N);
   TileRegs kreg, vreg;
   fetch_tile<D, BN>(K + kh * D, kbeg, N, kreg);
-  fetch_tile<D, BN>(V + kh * D, kbeg, N, vreg);
+  fetch_pairs<D, BN>(V + kh * D, kbeg, N, vreg);
   for (int k0 = kbeg; k0 < kend; k0 += BN) {
     __syncthreads();
     commit_tile<D, BN, true, false>(kreg, ks, nullptr);
-    commit_tile<D, BN, false, true>(vreg, nullptr, vt);
+    commit_pairs<D, BN, true, false>(vreg, nullptr, vt);
     __syncthreads();
     if (k0 + BN < kend) {  // in flight while this tile is consumed
       fetch_tile<D, BN>(K + kh * D, k0 + BN, N, kreg);
-      fetch_tile<D, BN>(V + kh * D, k0 + BN, N, vreg);
+      fetch_pairs<D, BN>(V + kh * D, k0 + BN, N, vreg);
     }
     if (k0 > w0 + 63) continue;  // every key of the tile is in this wave's future
     f32x16_t s[2][2];            // [query tile][key half]
@@ -461,7 +441,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
       for (int G = 0; G < 2; ++G)
 #pragma unroll
         for (int t = 0; t < DT; ++t) {
-          const bf16x8_t vf = ld_tr8(&vt[32 * t + col][0], 32 * kt + 16 * G, half);
+          const bf16x8_t vf = ld_tr16(vt, 32 * t + col, 32 * kt + 16 * G, half);
           o[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[0][kt][G], o[0][t], 0, 0, 0);
           o[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[1][kt][G], o[1][t], 0, 0, 0);
         }
@@ -613,8 +593,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
   constexpr int BQ = D == 64 ? 64 : 32;  // queries staged per step (LDS budget)
   __shared__ __attribute__((aligned(16))) bf16_t qs[BQ][D + 8];
   __shared__ __attribute__((aligned(16))) bf16_t gs[BQ][D + 8];
-  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][BQ + TPAD];
-  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][BQ + TPAD];
+  __shared__ __attribute__((aligned(16))) bf16_t qt_[D][BQ + TPAD16];
+  __shared__ __attribute__((aligned(16))) bf16_t gt_[D][BQ + TPAD16];
   __shared__ __attribute__((aligned(16))) float lse_s[BQ];
   __shared__ __attribute__((aligned(16))) float dl_s[BQ];
   const FlashTile ft = flash_tile(N, Bs, Hkv, nbatch);
@@ -645,8 +625,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     TileRegs qreg, greg;
     float lreg = 0.f, dreg = 0.f;
     auto fetch = [&](int q0) {
-      fetch_tile<D, BQ>(Q + qh * D, q0, N, qreg);
-      fetch_tile<D, BQ>(dO + qh * D, q0, N, greg);
+      fetch_pairs<D, BQ>(Q + qh * D, q0, N, qreg);
+      fetch_pairs<D, BQ>(dO + qh * D, q0, N, greg);
       if (threadIdx.x < BQ) {
         int n = q0 + threadIdx.x;
         n = n < N ? n : N - 1;
@@ -657,8 +637,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     if (k0 < qend) fetch(k0);
     for (int q0 = k0; q0 < qend; q0 += BQ) {
       __syncthreads();
-      commit_tile<D, BQ, true, true>(qreg, qs, qt_);
-      commit_tile<D, BQ, true, true>(greg, gs, gt_);
+      commit_pairs<D, BQ, true>(qreg, qs, qt_);
+      commit_pairs<D, BQ, true>(greg, gs, gt_);
       if (threadIdx.x < BQ) {
         lse_s[threadIdx.x] = lreg * 1.4426950408889634f;
         dl_s[threadIdx.x] = dreg;
@@ -702,9 +682,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
           bf16x8_t df = pack8(s, 2 * G, 2 * G + 1);
 #pragma unroll
           for (int t = 0; t < DT; ++t) {
-            bf16x8_t ag = ld_tr8(&gt_[32 * t + col][0], 32 * qt + 16 * G, half);
+            bf16x8_t ag = ld_tr16(gt_, 32 * t + col, 32 * qt + 16 * G, half);
             dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, pf, dv[t], 0, 0, 0);
-            bf16x8_t aq = ld_tr8(&qt_[32 * t + col][0], 32 * qt + 16 * G, half);
+            bf16x8_t aq = ld_tr16(qt_, 32 * t + col, 32 * qt + 16 * G, half);
             dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, df, dk[t], 0, 0, 0);
           }
         }
