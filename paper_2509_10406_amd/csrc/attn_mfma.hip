@@ -139,11 +139,21 @@ __device__ __forceinline__ bf16x8_t ld_tr16(const bf16_t (*tr)[W], int d, int r0
   return *reinterpret_cast<const bf16x8_t*>(&tr[d][r0 + 8 * half]);
 }
 
-// a whole tile in row pairs: pair c % (ROWS / 2), chunk c / (ROWS / 2) for c = thread + 256 i.  Values, not
+// Which row pair and which 16-byte chunk the c-th of a tile's (ROWS / 2) x (D / 8) staging units is: consecutive
+// lanes take consecutive pairs of one chunk.  The 4-byte transposed stores of 32 lanes then fall into 32 different
+// banks; the 16-byte row stores (lanes 288 bytes apart) pay a two-way conflict, 14 % of their time in a
+// microbenchmark, where a mapping that spares them doubles the time of the transposed stores.
+template <int D, int ROWS>
+__device__ __forceinline__ void pair_unit(int c, int& pr, int& pc) {
+  pr = c % (ROWS / 2);
+  pc = c / (ROWS / 2);
+}
+// a whole tile in row pairs, unit c = thread + 256 i, chunk c / (ROWS / 2) for c = thread + 256 i.  Values, not
 // references into the register struct, go through the helpers (see TileRegs).
 template <int D, int ROWS>
 __device__ __forceinline__ uint4 fetch_pair_row(const bf16_t* __restrict__ src, int r0, int N, int i, int which) {
-  const int c = threadIdx.x + 256 * i, pr = c % (ROWS / 2), pc = c / (ROWS / 2);
+  int pr, pc;
+  pair_unit<D, ROWS>(threadIdx.x + 256 * i, pr, pc);
   int row = r0 + 2 * pr + which;
   row = row < N ? row : N - 1;
   return *reinterpret_cast<const uint4*>(src + (size_t)row * D + 8 * pc);
@@ -162,7 +172,8 @@ __device__ __forceinline__ void fetch_pairs(const bf16_t* __restrict__ src, int 
 template <int D, int ROWS, bool TRANS, bool ROWM>
 __device__ __forceinline__ void commit_pair_i(const uint4 lo, const uint4 hi, int i, bf16_t (*rm)[D + 8],
                                               bf16_t (*tr)[ROWS + TPAD16]) {
-  const int c = threadIdx.x + 256 * i, pr = c % (ROWS / 2), pc = c / (ROWS / 2);
+  int pr, pc;
+  pair_unit<D, ROWS>(threadIdx.x + 256 * i, pr, pc);
   if constexpr (TRANS) {
     commit_pair<D, ROWS, ROWM>(lo, hi, pr, pc, rm, tr);
   } else {
@@ -744,7 +755,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
   const bool aligned = (Bs % 128) == 0 && k0 + 128 <= N;
   const float seed = -1.4426950408889634f / scale_log2e;
   static_assert(BQ / 2 * (D / 8) == 256, "one pair of rows and one 16-byte chunk per thread");
-  const int pr_ = threadIdx.x % (BQ / 2), pc_ = threadIdx.x / (BQ / 2);  // row pair and chunk this thread stages
+  int pr_, pc_;  // row pair and chunk this thread stages
+  pair_unit<D, BQ>(threadIdx.x, pr_, pc_);
 
   bf16x8_t kf[KS], vf[KS];
 #pragma unroll
