@@ -361,7 +361,7 @@ def cpu_baseline(w, d, p):
     op = orc.MuseParams(w.N, w.D, w.Bs, w.Cq, w.Ck, w.r, w.k2, 1.0 / math.sqrt(w.D))
     rm = 1 if w.dtype == "bf16" else 0
     G = w.Hq // w.Hkv
-    ncl = 8                                       # query clusters whose queries are evaluated
+    ncl = 16                                      # query clusters whose queries are evaluated
 
     def one(h):
         q, k, v, g = (d[x][0, hh].double().numpy() for x, hh in (("Q", h), ("K", h // G), ("V", h // G), ("dO", h)))
