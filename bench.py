@@ -49,9 +49,11 @@ def kernel_models(w, p):
     m["k_assign_bf16"] = ("mfma", PEAK["mfma_bf16"], 2 * N * Ck * D * Hk, "flop")
     # forward tile kernel: two passes over k-bar (scores for the selection, then scores again + monopole PV).
     # bf16 inputs: the scores run on 16-bit MFMA and the kernel streams each (block, query cluster) group's
-    # summaries once per pass; fp32 inputs: fp32 MFMA decides
+    # summaries once per pass: the bf16 plane of k-bar in the first (with r > 0; both planes with r = 0), both planes
+    # and v-bar in the second, the per-cell scalar in both; fp32 inputs: fp32 MFMA decides
     if es == 2:
-        m["k_farfield_fwd"] = ("hbm", PEAK["hbm"], (cells * (2 * 2 * D * 2 + D * es + 2 * 4) + 2 * Nff * D * 4) * H, "byte")
+        first = D * 2 if r > 0 else 2 * D * 2
+        m["k_farfield_fwd"] = ("hbm", PEAK["hbm"], (cells * (first + 2 * D * 2 + D * es + 2 * 4) + 2 * Nff * D * 4) * H, "byte")
     else:
         m["k_farfield_fwd"] = ("mfma", PEAK["mfma_fp32"], 2 * 2 * Nff * Ck * D * H, "flop")
     if es == 2:

@@ -543,8 +543,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
     const bf16_t* __restrict__ A_kb, const uint16_t* __restrict__ A_km, const float* __restrict__ A_c,
     const T* __restrict__ A_v, const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q,
     const int32_t* __restrict__ tile_off, float* __restrict__ ff_acc, float* __restrict__ ff_ml,
-    int32_t* __restrict__ selc, int h0, int N, int nb, int Cq, int Ck, int r, float scale) {
+    int32_t* __restrict__ selc, int h0, int N, int nb, int Cq, int Ck, int r, float scale,
+    const int32_t* __restrict__ only_flag) {
   constexpr int U = D / 8, DT = D / 32;
+  // as the second launch behind the one-plane kernel: only the tiles that kernel flagged
+  if (only_flag && only_flag[((size_t)blockIdx.z * (nb - 1) + blockIdx.y) * gridDim.x + blockIdx.x] == 0) return;
   // fp32 inputs: output tile x, row m holds head dim DT*m + x (a lane reads DT consecutive dims of a value row)
   using VF = Frag<T, DT>;
   constexpr bool kH = sizeof(T) == 2;  // bf16 inputs: P V on bf16 MFMA through a transposed value tile in LDS
@@ -816,6 +819,315 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64
 }
 
 // ------------------------------------------------------------------------------------------
+// largest Euclidean norm of a key row per kv head: every k-bar is a convex combination of key rows, so this bounds
+// |k-bar| for the error bound of the one-plane scores
+// ------------------------------------------------------------------------------------------
+constexpr int kNormParts = 64;  // workgroups per kv head in the first stage
+template <int D>
+__global__ void __launch_bounds__(256) k_key_norm_part(const bf16_t* __restrict__ K, float* __restrict__ part, int N) {
+  __shared__ float red[4];
+  const int hk = blockIdx.y;
+  float best = 0.f;
+  for (int n = blockIdx.x * 256 + threadIdx.x; n < N; n += 256 * kNormParts) {
+    const bf16_t* row = K + ((size_t)hk * N + n) * D;
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < D / 8; ++c) {
+      const bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(row + 8 * c);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s = fmaf((float)v[e], (float)v[e], s);
+    }
+    best = fmaxf(best, s);
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) best = fmaxf(best, __shfl_xor(best, o, 64));
+  if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = best;
+  __syncthreads();
+  if (threadIdx.x == 0) part[(size_t)hk * kNormParts + blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+__global__ void __launch_bounds__(64) k_key_norm_max(const float* __restrict__ part, float* __restrict__ knorm) {
+  float best = part[(size_t)blockIdx.x * kNormParts + threadIdx.x];
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) best = fmaxf(best, __shfl_xor(best, o, 64));
+  if (threadIdx.x == 0) knorm[blockIdx.x] = sqrtf(best);
+}
+
+// ------------------------------------------------------------------------------------------
+// The per-query-tile far-field kernel for bf16 inputs whose first pass streams the bf16 plane of k-bar only.
+// A score from the bf16 plane alone (Eq. 7 up to the plane's rounding) is off by at most
+//   eps = scale * 2^-8 * |q| * max_n |k_n|     (plus the rounding of the fp32 accumulation),
+// and r clusters reach the r-th largest approximate score, so the r-th largest exact score is at least that
+// minus eps: the cut.
+//   pass 1   approximate scores (bf16 plane and the per-cell scalar: 132 bytes per cell), the r largest per query;
+//   pass 2   exact scores from both planes, as in the two-plane kernel; a cluster at or above the cut is a
+//            candidate: listed and left out; the softmax over all others, and P V;
+//   then     the r best candidates by (score, index) are the selection; the other candidates (a few per query)
+//            re-enter the softmax state one by one.
+// Against the two-plane kernel pass 1 reads 132 instead of 260 bytes per cell.  A lane's candidate list holds CAP
+// entries; a tile where one overflows (many near-equal scores) is flagged and left to the two-plane kernel, which
+// runs as a second launch over the flagged tiles only.
+// ------------------------------------------------------------------------------------------
+template <int D, int RCAP>
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 2 : 1, 2))) k_farfield_fwd_b(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ A_kb, const uint16_t* __restrict__ A_km,
+    const float* __restrict__ A_c, const bf16_t* __restrict__ A_v, const float* __restrict__ knorm,
+    const int32_t* __restrict__ perm_q, const int32_t* __restrict__ off_q, const int32_t* __restrict__ tile_off,
+    float* __restrict__ ff_acc, float* __restrict__ ff_ml, int32_t* __restrict__ selc, int32_t* __restrict__ flag,
+    int h0, int N, int nb, int Cq, int Ck, int r, int Hq, int Hkv, float scale) {
+  constexpr int DT = D / 32, KS = D / 16, CPR = D / 8, NIT = 32 * CPR / 64;
+  constexpr int CAP = RCAP + 8;
+  __shared__ __attribute__((aligned(16))) bf16_t vt[D][32 + 4];
+  __shared__ float cs[64][CAP];   // scores of a lane's candidates
+  __shared__ int ci[64][CAP];     // their clusters
+  __shared__ int sel_s[32][RCAP];
+  const int hl = blockIdx.z, hq = h0 + hl;
+  const int hk = (hq / Hq) * Hkv + (hq % Hq) / (Hq / Hkv);
+  const int b = blockIdx.y + 1, NBm = nb - 1;
+  const int lane = threadIdx.x, col = lane % 32, half = lane / 32;
+
+  const int32_t* to = tile_off + ((size_t)hq * nb + b) * (Cq + 1);
+  const int ntl = to[Cq], run = (ntl + 7) / 8;
+  const int tile = (blockIdx.x % 8) * run + blockIdx.x / 8;
+  if ((int)blockIdx.x / 8 >= run || tile >= ntl) return;
+  int32_t* myflag = flag + ((size_t)hl * NBm + (b - 1)) * gridDim.x + blockIdx.x;
+  int lo_ = 0, hi_ = Cq;
+  while (hi_ - lo_ > 1) {
+    int mid = (lo_ + hi_) >> 1;
+    if (to[mid] <= tile) lo_ = mid; else hi_ = mid;
+  }
+  const int i = lo_, tt = tile - to[lo_];
+  const int32_t* oq = off_q + (size_t)hq * ((size_t)nb * Cq + 1);
+  const int qlo = oq[b * Cq + i], qhi = oq[b * Cq + i + 1];
+  int pos = qlo + 32 * tt + col;
+  const bool valid = pos < qhi;
+  pos = valid ? pos : qlo + 32 * tt;
+  const int n = perm_q[(size_t)hq * N + pos];
+
+  // the query itself as the bf16 operand (dims 16 ks + 8 half .. + 7), and its norm
+  bf16x8_t qb[KS];
+  f16x8_t qh[KS];
+  float q2 = 0.f;
+  {
+    const bf16_t* qrow = Q + ((size_t)hq * N + n) * D;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qb[ks] = *reinterpret_cast<const bf16x8_t*>(qrow + 16 * ks + 8 * half);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        qh[ks][e] = (_Float16)(float)qb[ks][e];
+        q2 = fmaf((float)qb[ks][e], (float)qb[ks][e], q2);
+      }
+    }
+    q2 += __shfl_xor(q2, 32, 64);
+  }
+  // 2^-8: half an ulp of bf16; 1.01 and 1e-4 cover the rounding of the fp32 accumulation
+  const float eps = 1.01f * scale * 0.00390625f * sqrtf(q2) * knorm[hk] + 1e-4f;
+  const size_t acell = (((size_t)hl * NBm + (b - 1)) * Cq + i) * Ck;
+  const bf16_t* Av = A_v + acell * D;
+  const int ntile = (Ck + 31) / 32;
+  using KT = KTileB<D>;
+  auto load_kt = [&](KT& kt, int j0) { load_ktile_b<D>(kt, A_c + acell, A_kb + acell * D, j0, Ck, col, half); };
+  auto score_kt = [&](const KT& kt, int j0) { return score_ktile_b<D>(kt, j0, Ck, qb, scale, half); };
+
+  // ---- pass 1: the r largest approximate scores seen by this lane half ----
+  float list[RCAP];
+#pragma unroll
+  for (int k = 0; k < RCAP; ++k) list[k] = MUSE_NEG_INF;
+  {
+    auto insert = [&](const f32x16_t& acc) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float x = acc[e];
+#pragma unroll
+        for (int k = RCAP - 1; k > 0; --k) list[k] = __builtin_amdgcn_fmed3f(x, list[k - 1], list[k]);
+        list[0] = fmaxf(list[0], x);
+      }
+    };
+    KT ka, kb;
+    load_kt(ka, 0);
+    for (int jt = 0; jt < ntile; jt += 2) {
+      if (jt + 1 < ntile) load_kt(kb, (jt + 1) * 32);
+      insert(score_kt(ka, jt * 32));
+      if (jt + 1 < ntile) {
+        if (jt + 2 < ntile) load_kt(ka, (jt + 2) * 32);
+        insert(score_kt(kb, (jt + 1) * 32));
+      }
+    }
+  }
+  // ---- the cut: the query's r-th largest approximate score, lowered by 2 eps ----
+  float cut;
+  {
+    int quota = 0;
+    float other[RCAP];
+#pragma unroll
+    for (int k = 0; k < RCAP; ++k) other[k] = __shfl_xor(list[k], 32, 64);
+#pragma unroll
+    for (int k = 0; k < RCAP; ++k) {
+      int ahead = 0;
+#pragma unroll
+      for (int y = 0; y < RCAP; ++y) ahead += half == 0 ? (other[y] > list[k]) : (other[y] >= list[k]);
+      quota += (k + ahead < r) && (list[k] > MUSE_NEG_INF);
+    }
+    float thr = __builtin_huge_valf();
+#pragma unroll
+    for (int k = 0; k < RCAP; ++k)
+      if (k == quota - 1) thr = list[k];
+    const int total = quota + __shfl_xor(quota, 32, 64);
+    const float thrq = fminf(thr, __shfl_xor(thr, 32, 64));
+    // fewer than r clusters with a finite score: every one of them is selected
+    // r clusters have an approximate score of thrq or more, so an exact one of thrq - eps or more: the r-th
+    // largest exact score is at least that
+    cut = total < r ? -3.0e38f : thrq - eps;
+  }
+
+  // ---- pass 2: candidates listed and left out, the softmax over the rest, P V ----
+  float m = MUSE_NEG_INF, l = 0.f;
+  f32x16_t o[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t) o[t] = zero16();
+  int ncand = 0;
+  bool over = false;
+  struct PTile {
+    KTileH<D> kt;
+    uint4 vch[NIT];
+  };
+  auto load_ptile = [&](PTile& pt, int j0) {
+    load_ktile_h<D>(pt.kt, A_c + acell, A_kb + acell * D, A_km + acell * D, j0, Ck, col, half);
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = lane + 64 * it, row = c % 32, cc = c / 32;
+      const int jr = j0 + row < Ck ? j0 + row : Ck - 1;
+      pt.vch[it] = *reinterpret_cast<const uint4*>(Av + (size_t)jr * D + cc * 8);
+    }
+  };
+  auto process = [&](const PTile& pt, int j0) {
+    f32x16_t acc = score_ktile_h<D>(pt.kt, j0, Ck, qb, qh, scale, half);
+    float tmax = MUSE_NEG_INF;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      if (acc[e] >= cut) {
+        if (ncand < CAP) {
+          cs[lane][ncand] = acc[e];
+          ci[lane][ncand] = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+          ++ncand;
+        } else {
+          over = true;
+        }
+        acc[e] = MUSE_NEG_INF;
+      }
+      tmax = fmaxf(tmax, acc[e]);
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    float mn = fmaxf(m, tmax);
+    float mref = mn == MUSE_NEG_INF ? 0.f : mn;
+    float alpha = __expf(m - mref);
+    float psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float p = __expf(acc[e] - mref);
+      acc[e] = p;
+      psum += p;
+    }
+    l = l * alpha + psum;
+    m = mn;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+    wave_lds_fence();
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = lane + 64 * it, row = c % 32, cc = c / 32;
+      const bf16_t* pv = reinterpret_cast<const bf16_t*>(&pt.vch[it]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vt[cc * 8 + e][row] = pv[e];
+    }
+    wave_lds_fence();
+#pragma unroll
+    for (int G = 0; G < 2; ++G) {
+      const bf16x8_t pf = pack8(acc, 2 * G, 2 * G + 1);
+#pragma unroll
+      for (int x = 0; x < DT; ++x)
+        o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_tr8(&vt[32 * x + col][0], 16 * G, half), pf, o[x], 0, 0, 0);
+    }
+  };
+  for (int jt = 0; jt < ntile; ++jt) {
+    PTile pt;
+    load_ptile(pt, jt * 32);
+    process(pt, jt * 32);
+  }
+  // a list overflowed somewhere in the tile: the two-plane kernel takes the whole tile
+  const bool tile_over = __ballot(over) != 0ull;
+  if (lane == 0) *myflag = tile_over ? 1 : 0;
+  if (tile_over) return;
+
+  for (int k = lane; k < 32 * RCAP; k += 64) (&sel_s[0][0])[k] = -1;
+  __syncthreads();
+  // ---- rank the query's candidates by (exact score desc, index asc); the r first are the selection ----
+  // (the ranks go where the transposed value tile was: pass 2 is over)
+  static_assert(sizeof(vt) >= 64 * CAP && 2 * CAP < 256, "the rank table (a byte per candidate) does not fit the value tile");
+  unsigned char (*rk)[CAP] = reinterpret_cast<unsigned char (*)[CAP]>(&vt[0][0]);
+  const int nother = __shfl_xor(ncand, 32, 64);
+  {
+    for (int k = 0; k < ncand; ++k) {
+      const float sv = cs[lane][k];
+      const int iv = ci[lane][k];
+      int rank = 0;
+      for (int y = 0; y < ncand; ++y) rank += (cs[lane][y] > sv) || (cs[lane][y] == sv && ci[lane][y] < iv);
+      for (int y = 0; y < nother; ++y)
+        rank += (cs[lane ^ 32][y] > sv) || (cs[lane ^ 32][y] == sv && ci[lane ^ 32][y] < iv);
+      rk[lane][k] = (unsigned char)rank;
+      if (rank < r) sel_s[col][rank] = iv;
+    }
+    __syncthreads();
+    if (valid && half == 0) {
+      const int total = ncand + nother;
+      int32_t* out = selc + ((size_t)hq * N + n) * r;
+      for (int k = 0; k < r; ++k) out[k] = k < total ? sel_s[col][k] : -1;
+    }
+  }
+  // ---- the candidates that are not selected re-enter the softmax state (both halves of the query take each of
+  //      them, in the same order: own list of the lower half first) ----
+#pragma unroll
+  for (int side = 0; side < 2; ++side) {
+    const int src = side == 0 ? col : col + 32;  // the list of the lower half, then of the upper half
+    const int cnt = src == lane ? ncand : nother;
+    for (int k = 0; k < cnt; ++k) {
+      if ((int)rk[src][k] < r) continue;
+      const float s = cs[src][k];
+      const int j = ci[src][k];
+      const float mn = fmaxf(m, s);
+      const float alpha = __expf(m - mn), pw = __expf(s - mn);
+      l = l * alpha + (src == lane ? pw : 0.f);
+      m = mn;
+      const bf16_t* vr = Av + (size_t)j * D;
+#pragma unroll
+      for (int x = 0; x < DT; ++x)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float v4[4];
+          ld4(vr, 32 * x + 8 * g + 4 * half, v4);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) o[x][4 * g + u] = fmaf(pw, v4[u], o[x][4 * g + u] * alpha);
+        }
+    }
+  }
+  l += __shfl_xor(l, 32, 64);
+  if (!valid) return;
+  float* fa = ff_acc + ((size_t)hq * N + n) * D;
+#pragma unroll
+  for (int g = 0; g < 4; ++g)
+#pragma unroll
+    for (int x = 0; x < DT; ++x)
+      *reinterpret_cast<float4*>(fa + 32 * x + 8 * g + 4 * half) =
+          make_float4(o[x][4 * g], o[x][4 * g + 1], o[x][4 * g + 2], o[x][4 * g + 3]);
+  if (half == 0) {
+    ff_ml[((size_t)hq * N + n) * 2] = m;
+    ff_ml[((size_t)hq * N + n) * 2 + 1] = l;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // Per query (blocks >= 1), over its r retrieved clusters: block selection on the per-block summaries
 // (scores q~.k-bar + mu-bar of the preceding blocks, the k2 largest are retrieved, ties to the earlier
 // block), then component 2 = monopole attention over the per-block summaries of the blocks NOT
@@ -1077,6 +1389,8 @@ int muse_ff_carve(const MuseDims& d, bool bwd, void* ws, size_t ws_bytes, FFWork
     w->hits = (uint2*)take(HQ * N * R2 * 8);
     w->ret_part = (float*)take(HQ * N * R2 * (D + 4) * 4);
   }
+  w->knorm = (float*)take(HK * 65 * 4);  // [HK] and the partial maxima [HK][64] behind them
+  w->ff_flag = (int32_t*)take(ff_flag_bytes(d));
   if (bwd) {
     size_t W = (d.Ck + 31) / 32;
     w->delta = (float*)take(HQ * N * 4);
@@ -1141,6 +1455,13 @@ int muse_ff_prepare(const MuseDims& d, const T* K, const T* V, const int32_t* aq
   { MuseProf prof_("k_gather_rows", st); hipLaunchKernelGGL(k_gather_rows<T>, g, dim3(256), 0, st, K, w.perm_k, (T*)w.Ks, N, D); }
   { MuseProf prof_("k_gather_rows", st); hipLaunchKernelGGL(k_gather_rows<T>, g, dim3(256), 0, st, V, w.perm_k, (T*)w.Vs, N, D); }
   { MuseProf prof_("k_tile_schedule", st); hipLaunchKernelGGL(k_tile_schedule, dim3((HQ * d.nb + 63) / 64), dim3(64), 0, st, w.off_q, w.tile_off, HQ, d.nb, d.Cq); }
+  if constexpr (sizeof(T) == 2) {
+    MuseProf prof_("k_key_norm_max", st);
+    float* part = w.knorm + HK;  // [HK][kNormParts]
+    if (D == 64) hipLaunchKernelGGL(k_key_norm_part<64>, dim3(kNormParts, HK), dim3(256), 0, st, (const bf16_t*)K, part, N);
+    else hipLaunchKernelGGL(k_key_norm_part<128>, dim3(kNormParts, HK), dim3(256), 0, st, (const bf16_t*)K, part, N);
+    hipLaunchKernelGGL(k_key_norm_max, dim3(HK), dim3(64), 0, st, (const float*)part, w.knorm);
+  }
   MUSE_LAUNCH_CHECK();
   return MUSE_OK;
 }
@@ -1213,9 +1534,19 @@ namespace {
 template <typename T, int D, int RCAP>
 void launch_ff_fwd(const MuseDims& d, const T* Q, const float* qc, FFWorkspace& w, int32_t* selc, int h0, int hn,
                    hipStream_t st) {
-  dim3 g((d.Bs / 32 + d.Cq + 1 + 7) / 8 * 8, d.nb - 1, hn);
-  { MuseProf prof_("k_farfield_fwd", st); hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, w.A_mu, w.A_k, (const bf16_t*)w.A_kb, (const uint16_t*)w.A_km, w.A_c,
-                     (const T*)w.A_v, w.perm_q, w.off_q, w.tile_off, w.ff_acc, w.ff_ml, selc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.scale); }
+  dim3 g((unsigned)ff_tile_grid_x(d), d.nb - 1, hn);
+  const int32_t* only_flag = nullptr;
+  if constexpr (sizeof(T) == 2) {
+    if (d.r > 0) {
+      // bf16 inputs: the one-plane kernel first; the two-plane kernel below then takes the tiles it flagged
+      { MuseProf prof_("k_farfield_fwd", st); hipLaunchKernelGGL((k_farfield_fwd_b<D, RCAP>), g, dim3(64), 0, st, (const bf16_t*)Q, (const bf16_t*)w.A_kb, (const uint16_t*)w.A_km,
+                         w.A_c, (const bf16_t*)w.A_v, w.knorm, w.perm_q, w.off_q, w.tile_off, w.ff_acc, w.ff_ml, selc, w.ff_flag, h0,
+                         d.N, d.nb, d.Cq, d.Ck, d.r, d.Hq, d.Hkv, d.scale); }
+      only_flag = w.ff_flag;
+    }
+  }
+  { MuseProf prof_(only_flag ? "k_farfield_fwd_rest" : "k_farfield_fwd", st); hipLaunchKernelGGL((k_farfield_fwd<T, D, RCAP>), g, dim3(64), 0, st, Q, qc, w.A_mu, w.A_k, (const bf16_t*)w.A_kb, (const uint16_t*)w.A_km, w.A_c,
+                     (const T*)w.A_v, w.perm_q, w.off_q, w.tile_off, w.ff_acc, w.ff_ml, selc, h0, d.N, d.nb, d.Cq, d.Ck, d.r, d.scale, only_flag); }
 }
 
 template <typename T, int D>

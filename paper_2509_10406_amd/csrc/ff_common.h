@@ -161,6 +161,54 @@ __device__ __forceinline__ f32x16_t score_ktile_h(const KTileH<D>& kt, int j0, i
   return acc;
 }
 
+// The bf16 plane alone: an approximate score, off by at most scale * 2^-8 * |q| . |k-bar| (the plane is k-bar rounded
+// to nearest), for the passes that only need to know which clusters can be among the r best.
+template <int D>
+struct KTileB {
+  uint4 h[D / 16];
+  float mu[16];
+};
+template <int D>
+__device__ __forceinline__ void load_ktile_b(KTileB<D>& kt, const float* __restrict__ Amuq,
+                                             const bf16_t* __restrict__ Akb, int j0, int Ck, int col, int half) {
+  int c = j0 + col;
+  c = c < Ck ? c : Ck - 1;
+  const bf16_t* rh = Akb + (size_t)c * D + 8 * half;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) kt.h[ks] = *reinterpret_cast<const uint4*>(rh + 16 * ks);
+  if ((Ck & 3) == 0) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      int base = j0 + 8 * g + 4 * half;
+      base = base < Ck ? base : Ck - 4;
+      const float4 m4 = *reinterpret_cast<const float4*>(Amuq + base);
+      kt.mu[4 * g] = m4.x; kt.mu[4 * g + 1] = m4.y; kt.mu[4 * g + 2] = m4.z; kt.mu[4 * g + 3] = m4.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+      kt.mu[e] = Amuq[jr < Ck ? jr : Ck - 1];
+    }
+  }
+}
+template <int D>
+__device__ __forceinline__ f32x16_t score_ktile_b(const KTileB<D>& kt, int j0, int Ck, const bf16x8_t (&qb)[D / 16],
+                                                  float scale, int half) {
+  f32x16_t acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks)
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kt.h[ks]), qb[ks], acc, 0, 0, 0);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const int jr = j0 + 8 * (e / 4) + 4 * half + (e % 4);
+    acc[e] = jr < Ck ? fmaf(scale, acc[e], kt.mu[e]) : MUSE_NEG_INF;
+  }
+  return acc;
+}
+
 // bf16 MFMA (v_mfma_f32_32x32x16_bf16) helpers.  pack8: accumulator rows 4*g0..+3 and 4*g1..+3 of a lane
 // become the 8 k-slots of a B (or A) operand; the matching other operand must use the same row order.
 __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& s, int g0, int g1) {
@@ -226,6 +274,8 @@ struct FFWorkspace {
   uint2* hits;                   // x = n | g << 22 (query position, head inside the KV group), y = slot*k2e + u
   size_t hit_cap;                // hits per kv head
   float* ret_part;               // per (query, slot, u): forward partial state [acc D | max | sum | pad2], or dq partial [D]
+  float* knorm;                  // [HK]: largest Euclidean norm of a key row of the kv head (bf16 inputs); then [HK][64] partial maxima
+  int32_t* ff_flag;              // [HQ][nb-1][ff_tile_grid_x]: tiles the one-plane forward kernel leaves to the two-plane one
   float *dKs, *dVs;            // fp32 gradients in bucketed key order
   float* c3_part;              // bf16 inputs, r > 0: [kC3Slices - 1][HK][N][2][D] partial dK | dV rows of the later hit slices of a pair
   float *dQacc, *dKacc, *dVacc;  // fp32 gradients in sequence order (alias the outputs when they are fp32)
@@ -276,6 +326,11 @@ static inline size_t ff_segcnt_bytes(const MuseDims& d) {
 }
 
 // bytes of the all-heads part / of one query head of the chunked part
+// x extent of the forward tile kernels' grid: the tiles of a (head, block) pair, rounded up to the 8 XCDs
+static inline size_t ff_tile_grid_x(const MuseDims& d) { return (size_t)(d.Bs / 32 + d.Cq + 1 + 7) / 8 * 8; }
+static inline size_t ff_flag_bytes(const MuseDims& d) {
+  return (size_t)d.B * d.Hq * (d.nb > 1 ? d.nb - 1 : 1) * ff_tile_grid_x(d) * 4;
+}
 static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
   size_t HQ = (size_t)d.B * d.Hq, HK = (size_t)d.B * d.Hkv, N = d.N, D = d.D;
   size_t es = d.dtype == MUSE_DTYPE_BF16 ? 2 : 4;
@@ -288,6 +343,7 @@ static inline size_t ff_fixed_bytes(const MuseDims& d, bool bwd) {
        ff_al(HK * ff_run_cap(d) * 16) + ff_al(HK * ff_run_cap(d) * 8) +
        ff_al(HQ * N * R2 * 8) +
        ff_al(HQ * N * R2 * (D + 4) * 4);
+  b += ff_al(HK * 65 * 4) + ff_al(ff_flag_bytes(d));
   if (bwd) {
     b += ff_al(HQ * N * 4) + ff_al(HQ * N * W * 4) + ff_al(HQ * N * (size_t)(d.r > 0 ? d.r : 1) * 4) + 2 * ff_al(HK * N * D * 4) +
          ff_al(HQ * N * D * 4) + ff_al(HQ * D * (size_t)((d.Cq + 31) / 32 * 32) * 2);
