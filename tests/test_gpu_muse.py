@@ -189,6 +189,37 @@ def test_forward_with_small_workspace_chunks_heads():
         mb.muse_fwd(*args, ws=torch.empty(mn - 256, dtype=torch.uint8, device="cuda"))
 
 
+def test_forward_tiles_with_many_tied_clusters():
+    """Every key is the same row and the key clusters are dealt round-robin (teacher-forced), so in every block all
+    64 accumulated cells of a query cluster are equal: every cluster scores the same, all of them are candidates
+    for the r best, and the candidate lists of the one-plane tile kernel (r + 8 entries per lane half, 32 clusters
+    per half here) overflow in every tile.  Those tiles are left to the two-plane kernel; the result must be a
+    valid selection (nothing chosen scores below something left out, by the oracle's scores) and O, LSE must be
+    the oracle's at that selection (Sec. 3.2, Eq. 7; Sec. 3.3)."""
+    w = small("cfg2", N=1024, Hq=2, Hkv=1, Cq=4, Ck=64, r=3, block=128, kmeans_iters=1)
+    d = generate(w)
+    p = mb.params_for(w)
+    d["K"][:] = d["K"][0, 0, 0]                                     # one key row everywhere
+    qc, aq, _ = oracle_clustering(w, d, p)
+    ak = np.tile((np.arange(w.N) % w.Ck).astype(np.int32), (w.B, w.Hkv, 1))   # 2 keys per (block, cluster)
+    Q, K, V = (dev(d[x], p) for x in ("Q", "K", "V"))
+    O, LSE, selc, selb = mb.muse_fwd(p, Q, K, V, torch.tensor(qc).cuda(), torch.tensor(aq).cuda(), torch.tensor(ak).cuda())
+    torch.cuda.synchronize()
+    op = orc.MuseParams(w.N, w.D, w.Bs, w.Cq, w.Ck, w.r, w.k2, p.eff_scale)
+    for h in range(w.Hq):
+        q, k, v = (f64(x) for x in (Q[0, h], K[0, 0], V[0, 0]))
+        sc = selc.cpu().numpy()[0, h][:, : w.r]
+        sb = selb.cpu().numpy()[0, h][:, : w.r].reshape(w.N, w.r, op.k2e)
+        res = oracle_head(orc, op, q, k, v, q, qc[0, h], aq[0, h], ak[0, 0], (sc, sb), threads=8, with_bwd=False)
+        free, forced = res["free"], res["forced"]
+        far = np.arange(w.N) >= w.Bs
+        assert (free["margin_c"][far] <= MARGIN).all(), "the clusters were meant to tie"
+        assert (forced["margin_c"] >= -MARGIN).all() and (forced["margin_b"] >= -MARGIN).all()
+        assert (sc[far] >= 0).all() and (np.sort(sc[far], 1)[:, 1:] != np.sort(sc[far], 1)[:, :-1]).all()
+        assert_close(f64(O[0, h]), forced["O"], p, f"tied clusters O head {h}")
+        np.testing.assert_allclose(LSE[0, h].cpu().numpy(), forced["LSE"], rtol=0, atol=2e-2 * max(1, np.abs(forced["LSE"]).max()))
+
+
 def test_gpu_own_clustering_reports_rse(oracle):
     """End to end on the GPU's own clustering (cfg1): approximation error against exact attention."""
     w = small("cfg1")
