@@ -297,7 +297,7 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 4)))
           const float4 v = *reinterpret_cast<const float4*>(&tr[4 * ps + lrow][4 * (lane % 16)]);
           const uint32_t o = loff + ps * pstr;
           if (dstf) *reinterpret_cast<float4*>(pf + o) = v;
-          if (dsth) *reinterpret_cast<uint2*>(ph + o) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+          if (dsth) { const unsigned long long pk = (unsigned long long)pack_bf16x2(v.x, v.y) | ((unsigned long long)pack_bf16x2(v.z, v.w) << 32); __builtin_nontemporal_store(pk, reinterpret_cast<unsigned long long*>(ph + o)); }
         }
       }
       wave_lds_fence();
@@ -319,11 +319,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 4)))
           const float4 v = *reinterpret_cast<const float4*>(&tr[4 * ps + lrow][4 * (lane % 16)]);
           const uint32_t o = loff + ps * pstr;
           const uint32_t h01 = pack_bf16x2(v.x, v.y), h23 = pack_bf16x2(v.z, v.w);
-          *reinterpret_cast<uint2*>(ph + o) = make_uint2(h01, h23);
+          __builtin_nontemporal_store((unsigned long long)h01 | ((unsigned long long)h23 << 32), reinterpret_cast<unsigned long long*>(ph + o));
           const float r0 = v.x - __uint_as_float(h01 << 16), r1 = v.y - __uint_as_float(h01 & 0xffff0000u);
           const float r2 = v.z - __uint_as_float(h23 << 16), r3 = v.w - __uint_as_float(h23 & 0xffff0000u);
           auto hb = [](float x) { return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)x); };
-          *reinterpret_cast<uint2*>(pm + o) = make_uint2(hb(r0) | hb(r1) << 16, hb(r2) | hb(r3) << 16);
+          __builtin_nontemporal_store((unsigned long long)(hb(r0) | hb(r1) << 16) | ((unsigned long long)(hb(r2) | hb(r3) << 16) << 32), reinterpret_cast<unsigned long long*>(pm + o));
         }
       }
       wave_lds_fence();
