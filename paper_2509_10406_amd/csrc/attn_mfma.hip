@@ -1579,7 +1579,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
                                     __uint_as_float(pn[u] & 0xffff0000u) + __uint_as_float(po[u] & 0xffff0000u));
               v = make_uint4(rr[0], rr[1], rr[2], rr[3]);
             }
-            *o = v;
+            typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+            const u4_t vs = {v.x, v.y, v.z, v.w};
+            __builtin_nontemporal_store(vs, reinterpret_cast<u4_t*>(o));  // written once, read by the next kernel much later
           }
         }
       }

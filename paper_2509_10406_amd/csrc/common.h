@@ -108,6 +108,18 @@ __device__ __forceinline__ void st4(bf16_t* p, size_t i, const float v[4]) {
   *reinterpret_cast<uint2*>(p + i) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
 }
 
+// the same as streaming stores: for rows that are written once and read much later (the summaries and the cell
+// gradients are several GB per head chunk; nothing of them is still in a cache when it is read)
+__device__ __forceinline__ void st4_stream(float* p, size_t i, const float v[4]) {
+  typedef float f4_t __attribute__((ext_vector_type(4)));
+  const f4_t x = {v[0], v[1], v[2], v[3]};
+  __builtin_nontemporal_store(x, reinterpret_cast<f4_t*>(p + i));
+}
+__device__ __forceinline__ void st4_stream(bf16_t* p, size_t i, const float v[4]) {
+  const unsigned long long x = (unsigned long long)pack_bf16x2(v[0], v[1]) | ((unsigned long long)pack_bf16x2(v[2], v[3]) << 32);
+  __builtin_nontemporal_store(x, reinterpret_cast<unsigned long long*>(p + i));
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
