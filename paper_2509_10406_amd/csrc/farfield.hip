@@ -520,8 +520,8 @@ __global__ void __launch_bounds__(256) k_block_summaries_mx(const T* __restrict_
             const float4 v = *reinterpret_cast<const float4*>(&tr[row][4 * (lane % 16)]);
             const size_t o = ((((size_t)hl * NBm + b) * Cq + list[32 * it + row]) * Ck + j) * D + d0 + 4 * (lane % 16);
             const float v4[4] = {v.x, v.y, v.z, v.w};
-            if (values) st4(s_v, o, v4);
-            else st4(s_k, o, v4);
+            if (values) st4_stream(s_v, o, v4);
+            else st4_stream(s_k, o, v4);
           }
         }
         wave_lds_fence();
